@@ -1,0 +1,296 @@
+// TreeKV CPU oracle: TEST INFRASTRUCTURE, NOT THE PRODUCT.
+//
+// A plain, slow, scalar fp64 implementation of the TreeKV cache step for ONE
+// (batch, kv-head) stream, written from the paper (Algorithm 1 "Compression by
+// TreeKV", Section 4.1; attention of Section 3.1).  Only tests, the smoke check
+// and the benchmark's cpu_baseline leg may build, load or call it.  It shares
+// no code, header, table or helper with the HIP library.
+//
+// What it follows, step by step (Algorithm 1, one loop iteration):
+//   K, V grow by the new row                                   (lines 4-5)
+//   a = SoftMax(q K^T * scale) over the whole cache, o = a V   (line 6, Sec. 3.1)
+//   C = (C u {0}) + 1,  S = (S u {0}) + a                      (lines 7-8)
+//   if length > c:  Sbar = S / C; compare Sbar[idx], Sbar[idx+1];
+//                   evict idx+1 if Sbar[idx] > Sbar[idx+1], else evict idx;
+//                   advance idx                                (lines 9-17)
+// Eviction is a std::vector erase on every per-token array; nothing is blocked,
+// fused or reordered.
+//
+// Readings of the paper taken here (each also listed in the design notes):
+//  * idx advance.  The printed update "(idx+1) mod c + 1" skips every other
+//    scope, contradicting Section 4.1 ("idx cycles through 1, 2, 3, and 4").
+//    Default: idx <- (idx mod m) + 1.  The printed form is kept behind
+//    TKO_IDX_LITERAL.
+//  * Layout.  Section 5.2 keeps 4 initial and 508 recent tokens next to 512
+//    method-selected ones.  The cache is [n_sink | m tree slots | n_recent]
+//    with m = c - n_sink - n_recent; Algorithm 1's scope indexes the tree
+//    region, i.e. logical slots (n_sink+idx, n_sink+idx+1), and its cycle
+//    length is m.  n_sink = n_recent = 0 is Algorithm 1 verbatim.
+//  * Grouped queries (paper silent).  The G query heads that share this KV
+//    head all attend; S adds the sum of their probabilities, C adds 1.
+//  * Ties.  The comparison is a strict ">", so equal scores evict idx.
+//  * Ablation of Section 5.4 (always keep the left token): TKO_KEEP_LEFT.
+//  * Chunked prefill (not in the paper, whose prefill works on blocks with an
+//    observation window; Section 4.2 only says scores and scopes are computed
+//    ahead of the selection).  A chunk of L tokens attends the cache as it
+//    was before the chunk plus the chunk's own tokens up to and including
+//    itself; S and C are updated with every row; Sbar is then frozen and
+//    Algorithm 1's append / compare / evict / advance is replayed for the L
+//    tokens in order.  L = 1 is exactly a decode step.
+//
+// Near-tie handling for parity runs: every decision reports its relative
+// margin |Sbar_l - Sbar_r| / max(Sbar_l, Sbar_r).  A caller may pass the
+// position another implementation evicted; the oracle adopts it only when
+// that position is the other member of the scope AND the margin is below the
+// caller's threshold; otherwise it keeps its own choice and reports the
+// disagreement.
+//
+// parity unpinned: model quality (perplexity, task scores) of the heuristic;
+// it needs datasets and weights that are not available.
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+enum : int { TKO_KEEP_LEFT = 1, TKO_IDX_LITERAL = 2 };
+
+struct Stream {
+  int c = 0, n_sink = 0, n_recent = 0, m = 0, G = 1, d = 0, flags = 0;
+  double scale = 1.0;
+  long long t = 0;  // tokens processed so far == position of the next token
+  int idx = 1;      // the paper's 1-based idx (Algorithm 1, line 1)
+  std::vector<std::vector<double>> K, V;  // one row per cached token
+  std::vector<double> S;                  // accumulated attention weight
+  std::vector<long long> C;               // number of queries that attended the token
+  std::vector<long long> pos;             // original 0-based stream position
+};
+
+struct Decision {
+  long long evicted_pos = -1;
+  double margin = -1.0;     // -1: no eviction at this step
+  int adopted = 0;          // 1: took the caller's choice at a near-tie
+  int disagreed = 0;        // 1: caller's choice differed and was NOT adopted
+};
+
+void softmax_row(const std::vector<double>& logits, size_t n, std::vector<double>& a) {
+  double mx = -INFINITY;
+  for (size_t j = 0; j < n; ++j) mx = logits[j] > mx ? logits[j] : mx;
+  double sum = 0.0;
+  for (size_t j = 0; j < n; ++j) { a[j] = std::exp(logits[j] - mx); sum += a[j]; }
+  for (size_t j = 0; j < n; ++j) a[j] /= sum;
+}
+
+// Lines 9-17 of Algorithm 1 on a list of token handles `order` whose scores are sbar[handle].
+// Returns the index (into `order`) that is to be erased, or -1 when length <= c.
+int choose_eviction(Stream& s, const std::vector<int>& order, const std::vector<double>& sbar,
+                    const std::vector<long long>& pos_of, long long forced_pos, double follow_thresh,
+                    Decision& dec) {
+  if ((long long)order.size() <= (long long)s.c) return -1;
+  const int l = s.n_sink + (s.idx - 1);  // 0-based logical slot of the paper's idx
+  const int r = l + 1;
+  const double sl = sbar[order[l]], sr = sbar[order[r]];
+  int victim;
+  if (s.flags & TKO_KEEP_LEFT) victim = r;
+  else victim = (sl > sr) ? r : l;
+  const double big = sl > sr ? sl : sr;
+  dec.margin = big > 0.0 ? std::fabs(sl - sr) / big : 0.0;
+  if (forced_pos >= 0 && forced_pos != pos_of[order[victim]]) {
+    const int other = victim == l ? r : l;
+    if (forced_pos == pos_of[order[other]] && dec.margin < follow_thresh && !(s.flags & TKO_KEEP_LEFT)) {
+      victim = other;
+      dec.adopted = 1;
+    } else {
+      dec.disagreed = 1;
+    }
+  }
+  dec.evicted_pos = pos_of[order[victim]];
+  if (s.flags & TKO_IDX_LITERAL) s.idx = (s.idx + 1) % s.m + 1;
+  else s.idx = s.idx % s.m + 1;
+  return victim;
+}
+
+}  // namespace
+
+extern "C" {
+
+void* tko_new(int budget, int n_sink, int n_recent, int G, int d, double scale, int flags) {
+  if (budget < 1 || n_sink < 0 || n_recent < 0 || G < 1 || d < 1) return nullptr;
+  if (budget - n_sink - n_recent < 1) return nullptr;
+  Stream* s = new Stream;
+  s->c = budget; s->n_sink = n_sink; s->n_recent = n_recent; s->m = budget - n_sink - n_recent;
+  s->G = G; s->d = d; s->scale = scale; s->flags = flags;
+  return s;
+}
+
+void tko_free(void* h) { delete static_cast<Stream*>(h); }
+
+int tko_len(void* h) { return (int)static_cast<Stream*>(h)->pos.size(); }
+long long tko_t(void* h) { return static_cast<Stream*>(h)->t; }
+int tko_idx(void* h) { return static_cast<Stream*>(h)->idx; }
+
+// Copies the per-token state in cache order; any pointer may be null.
+void tko_state(void* h, long long* pos, double* S, long long* C) {
+  Stream& s = *static_cast<Stream*>(h);
+  for (size_t j = 0; j < s.pos.size(); ++j) {
+    if (pos) pos[j] = s.pos[j];
+    if (S) S[j] = s.S[j];
+    if (C) C[j] = s.C[j];
+  }
+}
+
+// Copies the cached K and V rows (cache order), [len][d] each.
+void tko_kv(void* h, double* K, double* V) {
+  Stream& s = *static_cast<Stream*>(h);
+  for (size_t j = 0; j < s.K.size(); ++j)
+    for (int e = 0; e < s.d; ++e) { K[j * s.d + e] = s.K[j][e]; V[j * s.d + e] = s.V[j][e]; }
+}
+
+// One decode step (one iteration of Algorithm 1's loop without the projections).
+//   q [G][d], k [d], v [d]  ->  out [G][d]
+//   forced_pos: -1, or the position another implementation evicted at this step.
+//   result[0] = evicted position or -1, result[1] = adopted, result[2] = disagreed.
+//   commit == 0: report what the step would do (out, margin, result) and leave the
+//   state untouched.
+void tko_decode_step(void* h, const double* q, const double* k, const double* v, double* out,
+                     long long forced_pos, double follow_thresh, int commit,
+                     long long* result, double* margin) {
+  Stream& s = *static_cast<Stream*>(h);
+  const Stream backup = commit ? Stream() : s;
+  // lines 4-5, and the "u {0}" of lines 7-8
+  s.K.emplace_back(k, k + s.d);
+  s.V.emplace_back(v, v + s.d);
+  s.S.push_back(0.0);
+  s.C.push_back(0);
+  s.pos.push_back(s.t);
+  const size_t n = s.K.size();
+  // line 6 and o = a V, once per query head of the group
+  std::vector<double> logits(n), a(n), asum(n, 0.0);
+  for (int g = 0; g < s.G; ++g) {
+    for (size_t j = 0; j < n; ++j) {
+      double acc = 0.0;
+      for (int e = 0; e < s.d; ++e) acc += q[g * s.d + e] * s.K[j][e];
+      logits[j] = acc * s.scale;
+    }
+    softmax_row(logits, n, a);
+    for (int e = 0; e < s.d; ++e) {
+      double acc = 0.0;
+      for (size_t j = 0; j < n; ++j) acc += a[j] * s.V[j][e];
+      out[g * s.d + e] = acc;
+    }
+    for (size_t j = 0; j < n; ++j) asum[j] += a[j];
+  }
+  // lines 7-8
+  for (size_t j = 0; j < n; ++j) { s.C[j] += 1; s.S[j] += asum[j]; }
+  // lines 9-17
+  Decision dec;
+  std::vector<int> order(n);
+  std::vector<double> sbar(n);
+  for (size_t j = 0; j < n; ++j) { order[j] = (int)j; sbar[j] = s.S[j] / (double)s.C[j]; }
+  const int victim = choose_eviction(s, order, sbar, s.pos, forced_pos, follow_thresh, dec);
+  if (victim >= 0) {
+    s.K.erase(s.K.begin() + victim);
+    s.V.erase(s.V.begin() + victim);
+    s.S.erase(s.S.begin() + victim);
+    s.C.erase(s.C.begin() + victim);
+    s.pos.erase(s.pos.begin() + victim);
+  }
+  s.t += 1;
+  if (result) { result[0] = dec.evicted_pos; result[1] = dec.adopted; result[2] = dec.disagreed; }
+  if (margin) *margin = dec.margin;
+  if (!commit) s = backup;
+}
+
+// T decode steps in a row: the loop of Algorithm 1 over a whole stream.
+//   q [T][G][d], k [T][d], v [T][d]; out [T][G][d] or null; forced [T] or null;
+//   evicted [T], margins [T] or null; counts[0] += adopted, counts[1] += disagreed.
+void tko_decode_stream(void* h, const double* q, const double* k, const double* v, int T, double* out,
+                       const long long* forced, double follow_thresh, long long* evicted, double* margins,
+                       long long* counts) {
+  Stream& s = *static_cast<Stream*>(h);
+  std::vector<double> o((size_t)s.G * s.d);
+  for (int i = 0; i < T; ++i) {
+    long long res[3];
+    double mg;
+    tko_decode_step(h, q + (size_t)i * s.G * s.d, k + (size_t)i * s.d, v + (size_t)i * s.d,
+                    out ? out + (size_t)i * s.G * s.d : o.data(), forced ? forced[i] : -1, follow_thresh, 1,
+                    res, &mg);
+    if (evicted) evicted[i] = res[0];
+    if (margins) margins[i] = mg;
+    if (counts) { counts[0] += res[1]; counts[1] += res[2]; }
+  }
+}
+
+// One prefill chunk of L tokens (see the header for the definition).
+//   Q [L][G][d], K [L][d], V [L][d]  ->  out [L][G][d]
+//   forced_pos: null, or [L] positions another implementation evicted at each of the
+//   chunk's tokens (-1 where it evicted nothing).
+//   evicted [L], margins [L], adopted [L], disagreed [L]: per-token decision records
+//   (any may be null).
+void tko_prefill_chunk(void* h, const double* Q, const double* K, const double* V, int L, double* out,
+                       const long long* forced_pos, double follow_thresh,
+                       long long* evicted, double* margins, int* adopted, int* disagreed) {
+  Stream& s = *static_cast<Stream*>(h);
+  const size_t n0 = s.K.size();
+  for (int i = 0; i < L; ++i) {
+    s.K.emplace_back(K + (size_t)i * s.d, K + (size_t)(i + 1) * s.d);
+    s.V.emplace_back(V + (size_t)i * s.d, V + (size_t)(i + 1) * s.d);
+    s.S.push_back(0.0);
+    s.C.push_back(0);
+    s.pos.push_back(s.t + i);
+  }
+  const size_t n = s.K.size();
+  std::vector<double> logits(n), a(n), asum(n);
+  for (int i = 0; i < L; ++i) {
+    const size_t vis = n0 + (size_t)i + 1;  // the cache before the chunk, plus chunk tokens <= i
+    for (size_t j = 0; j < vis; ++j) asum[j] = 0.0;
+    for (int g = 0; g < s.G; ++g) {
+      const double* q = Q + ((size_t)i * s.G + g) * s.d;
+      for (size_t j = 0; j < vis; ++j) {
+        double acc = 0.0;
+        for (int e = 0; e < s.d; ++e) acc += q[e] * s.K[j][e];
+        logits[j] = acc * s.scale;
+      }
+      softmax_row(logits, vis, a);
+      double* o = out + ((size_t)i * s.G + g) * s.d;
+      for (int e = 0; e < s.d; ++e) {
+        double acc = 0.0;
+        for (size_t j = 0; j < vis; ++j) acc += a[j] * s.V[j][e];
+        o[e] = acc;
+      }
+      for (size_t j = 0; j < vis; ++j) asum[j] += a[j];
+    }
+    for (size_t j = 0; j < vis; ++j) { s.C[j] += 1; s.S[j] += asum[j]; }
+  }
+  // frozen scores, then the replay of lines 4-5 and 9-17 token by token
+  std::vector<double> sbar(n);
+  for (size_t j = 0; j < n; ++j) sbar[j] = s.S[j] / (double)s.C[j];
+  std::vector<int> order;
+  order.reserve(n);
+  for (size_t j = 0; j < n0; ++j) order.push_back((int)j);
+  for (int i = 0; i < L; ++i) {
+    order.push_back((int)(n0 + i));
+    Decision dec;
+    const int victim = choose_eviction(s, order, sbar, s.pos, forced_pos ? forced_pos[i] : -1,
+                                       follow_thresh, dec);
+    if (victim >= 0) order.erase(order.begin() + victim);
+    if (evicted) evicted[i] = dec.evicted_pos;
+    if (margins) margins[i] = dec.margin;
+    if (adopted) adopted[i] = dec.adopted;
+    if (disagreed) disagreed[i] = dec.disagreed;
+  }
+  // keep the survivors, in order
+  std::vector<std::vector<double>> K2, V2;
+  std::vector<double> S2;
+  std::vector<long long> C2, P2;
+  for (int hnd : order) {
+    K2.push_back(s.K[hnd]); V2.push_back(s.V[hnd]);
+    S2.push_back(s.S[hnd]); C2.push_back(s.C[hnd]); P2.push_back(s.pos[hnd]);
+  }
+  s.K.swap(K2); s.V.swap(V2); s.S.swap(S2); s.C.swap(C2); s.pos.swap(P2);
+  s.t += L;
+}
+
+}  // extern "C"

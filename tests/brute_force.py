@@ -1,0 +1,92 @@
+"""Independent re-simulation of TreeKV on tiny inputs, used only to pin the oracle.
+
+Pure Python: one list of dict records per stream, `list.pop` for eviction,
+`math.fsum` for every sum.  Written from Algorithm 1 of the paper (Section 4.1),
+separately from the C++ oracle: it shares nothing with it.
+"""
+import math
+
+
+def _softmax(xs):
+    mx = max(xs)
+    es = [math.exp(x - mx) for x in xs]
+    tot = math.fsum(es)
+    return [e / tot for e in es]
+
+
+def _dot(a, b):
+    return math.fsum(x * y for x, y in zip(a, b))
+
+
+class BruteTreeKV:
+    def __init__(self, c, G, d, n_sink=0, n_recent=0, scale=None, keep_left=False, literal_idx=False):
+        self.c, self.G, self.d = c, G, d
+        self.n_sink, self.m = n_sink, c - n_sink - n_recent
+        self.scale = 1.0 / math.sqrt(d) if scale is None else scale
+        self.keep_left, self.literal_idx = keep_left, literal_idx
+        self.cache = []   # records: pos, k, v, S, C
+        self.idx = 1      # 1-based, as printed in Algorithm 1
+        self.t = 0
+
+    def _attend(self, q, visible):
+        outs, probs = [], []
+        for g in range(self.G):
+            a = _softmax([self.scale * _dot(q[g], rec["k"]) for rec in visible])
+            outs.append([math.fsum(a[j] * visible[j]["v"][e] for j in range(len(visible)))
+                         for e in range(self.d)])
+            probs.append(a)
+        return outs, probs
+
+    def _maybe_evict(self, seq, sbar_of):
+        """seq: list of records in cache order; returns evicted position or -1."""
+        if len(seq) <= self.c:
+            return -1
+        i = self.n_sink + self.idx - 1
+        left, right = seq[i], seq[i + 1]
+        if self.keep_left or sbar_of(left) > sbar_of(right):
+            gone = seq.pop(i + 1)
+        else:
+            gone = seq.pop(i)
+        if self.literal_idx:
+            self.idx = (self.idx + 1) % self.m + 1
+        else:
+            self.idx = self.idx % self.m + 1
+        return gone["pos"]
+
+    def decode_step(self, q, k, v):
+        self.cache.append(dict(pos=self.t, k=list(k), v=list(v), S=0.0, C=0))
+        outs, probs = self._attend(q, self.cache)
+        for j, rec in enumerate(self.cache):
+            rec["C"] += 1
+            rec["S"] = math.fsum([rec["S"]] + [probs[g][j] for g in range(self.G)])
+        ev = self._maybe_evict(self.cache, lambda r: r["S"] / r["C"])
+        self.t += 1
+        return outs, ev
+
+    def prefill_chunk(self, Q, K, V):
+        L = len(K)
+        n0 = len(self.cache)
+        full = self.cache + [dict(pos=self.t + i, k=list(K[i]), v=list(V[i]), S=0.0, C=0) for i in range(L)]
+        outs = []
+        for i in range(L):
+            vis = full[: n0 + i + 1]
+            o, probs = self._attend(Q[i], vis)
+            outs.append(o)
+            for j, rec in enumerate(vis):
+                rec["C"] += 1
+                rec["S"] = math.fsum([rec["S"]] + [probs[g][j] for g in range(self.G)])
+        frozen = {id(rec): rec["S"] / rec["C"] for rec in full}
+        seq = full[:n0]
+        evs = []
+        for i in range(L):
+            seq.append(full[n0 + i])
+            evs.append(self._maybe_evict(seq, lambda r: frozen[id(r)]))
+        self.cache = seq
+        self.t += L
+        return outs, evs
+
+    def positions(self):
+        return [rec["pos"] for rec in self.cache]
+
+    def scores(self):
+        return [rec["S"] for rec in self.cache], [rec["C"] for rec in self.cache]

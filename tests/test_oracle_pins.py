@@ -1,0 +1,447 @@
+"""Pins for the CPU oracle: facts the paper prints, closed forms, invariants, a dense
+library reference, exact-tie inputs and brute force on tiny inputs.  No GPU needed."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from paper_2501_04987_amd import inputs
+from tests.brute_force import BruteTreeKV
+from tests.span_sim import SpanSim
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "fig3_worked_example.txt")
+
+
+def _cfg(c, G=1, d=4, n_sink=0, n_recent=0, scale=None, flags=0):
+    return dict(budget=c, G=G, d=d, n_sink=n_sink, n_recent=n_recent, scale=scale, flags=flags)
+
+
+def _rand_stream(seed, T, G, d):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((T, G, d)), rng.standard_normal((T, d)), rng.standard_normal((T, d)))
+
+
+# --------------------------------------------------------------------------- #
+# P1: the worked example of Figure 3 / Section 4.1
+# --------------------------------------------------------------------------- #
+def _read_golden():
+    facts = {}
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, *vals = line.split()
+        facts.setdefault(key, []).append(vals)
+    return facts
+
+
+def test_fig3_worked_example(oracle):
+    g = _read_golden()
+    c = int(g["cache_size"][0][0])
+    T = int(g["sequence_length"][0][0])
+    # rig the scores: paper token 2 (0-based position 1) draws nearly all attention at every step
+    d = 2
+    q = np.tile(np.array([1.0, 0.0]), (T, 1, 1))
+    k = np.zeros((T, d))
+    k[1, 0] = 8.0
+    v = np.arange(T * d, dtype=np.float64).reshape(T, d)
+    s = oracle.OracleStream(c, 1, d, scale=1.0)
+    idx_before, evicted, caches = {}, {}, {}
+    for t in range(T):
+        step = t + 1  # the paper counts steps and tokens from 1
+        idx_before[step] = s.idx
+        before = list(s.retained() + 1) + [step]
+        _, ev, _, _, _ = s.decode_step(q[t], k[t], v[t])
+        evicted[step] = ev + 1 if ev >= 0 else None
+        caches[step] = list(s.retained() + 1)
+        if ev >= 0:
+            i = idx_before[step] - 1
+            assert evicted[step] in before[i:i + 2], "evicted token must lie in scope {idx, idx+1}"
+    first = int(g["first_eviction_step"][0][0])
+    assert [st for st in range(1, T + 1) if evicted[st] is not None][0] == first
+    for st, val in g["idx_at_step"]:
+        assert idx_before[int(st)] == int(val)
+    st, a, b = map(int, g["scope_at_step"][0])
+    assert list(range(1, c + 1))[idx_before[st] - 1: idx_before[st] + 1] == [a, b]
+    st, tok = map(int, g["evicted_at_step"][0])
+    assert evicted[st] == tok
+    st, *toks = map(int, g["cache_after_step"][0])
+    assert caches[st] == toks
+    cyc = list(map(int, g["idx_cycle"][0]))
+    assert [idx_before[first + i] for i in range(2 * len(cyc))] == cyc + cyc
+    st, tok = map(int, g["scope_left_at_step"][0])
+    before17 = caches[st - 1] + [st]
+    assert before17[idx_before[st] - 1] == tok
+    assert g["evicted_side_at_step"][0] == [str(st), "right"]
+    assert evicted[st] == before17[idx_before[st]] and tok in caches[st]
+
+
+def test_fig3_scopes_in_spans(oracle):
+    """At every step the scope is the pair of spans the tree structure predicts (c=4, 17 tokens):
+    5:(1|2) 6:(3|4) 7:(5|6) 8:(7|8) 9:(1-2|3-4) ... 13:(1-4|5-8) ... 17:(1-8|9-12)."""
+    expect = {5: ((1, 1), (2, 2)), 6: ((3, 3), (4, 4)), 7: ((5, 5), (6, 6)), 8: ((7, 7), (8, 8)),
+              9: ((1, 2), (3, 4)), 10: ((5, 6), (7, 8)), 11: ((9, 9), (10, 10)), 12: ((11, 11), (12, 12)),
+              13: ((1, 4), (5, 8)), 14: ((9, 10), (11, 12)), 15: ((13, 13), (14, 14)),
+              16: ((15, 15), (16, 16)), 17: ((1, 8), (9, 12))}
+    for seed in range(20):
+        q, k, v = _rand_stream(seed, 17, 1, 3)
+        s = oracle.OracleStream(4, 1, 3)
+        sim = SpanSim(4)
+        for t in range(17):
+            before = list(s.retained()) + [t]
+            _, ev, _, _, _ = s.decode_step(q[t], k[t], v[t])
+            scope = sim.step()
+            if t + 1 < 5:
+                assert ev == -1 and scope is None
+                continue
+            (llo, lhi), (rlo, rhi) = scope
+            assert ((llo + 1, lhi + 1), (rlo + 1, rhi + 1)) == expect[t + 1]
+            assert llo <= ev <= rhi
+            i = before.index(ev)
+            partner = before[i + 1] if llo <= ev <= lhi else before[i - 1]
+            assert (rlo <= partner <= rhi) if llo <= ev <= lhi else (llo <= partner <= lhi)
+
+
+# --------------------------------------------------------------------------- #
+# P3: span structure (score independent) and P6: budget invariants
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("c,rounds,sizes", [
+    (4, 1, [2, 2, 2, 2]), (4, 2, [4, 4, 2, 2]), (4, 3, [8, 4, 2, 2]), (4, 4, [12, 4, 2, 2]),
+    (4, 5, [16, 4, 2, 2]), (8, 4, [16, 8, 4, 4, 2, 2, 2, 2]), (6, 3, [8, 6, 4, 2, 2, 2]),
+    (5, 3, [8, 5, 3, 2, 2]),
+])
+def test_span_closed_forms(c, rounds, sizes):
+    """s'_j = e_{2j-1} + e_{2j} with e = (spans at round start, then m ones)."""
+    sim = SpanSim(c)
+    for _ in range(c + rounds * c):
+        sim.step()
+    assert sim.sizes() == sizes
+    e = [1] * c
+    for _ in range(rounds):
+        e = e + [1] * c
+        e = [e[2 * j] + e[2 * j + 1] for j in range(c)]
+    assert e == sizes
+
+
+def test_span_fig1_setting():
+    """Cache 128 on a 512-token sequence (the setting of Figure 1): 32 slots of span 8, 32 of 4, 64 of 2."""
+    sim = SpanSim(128)
+    for _ in range(512):
+        sim.step()
+    assert sim.sizes() == [8] * 32 + [4] * 32 + [2] * 64
+
+
+@pytest.mark.parametrize("c,n_sink,n_recent,G", [(4, 0, 0, 1), (8, 0, 0, 2), (13, 0, 0, 1), (16, 2, 5, 1),
+                                                  (16, 4, 4, 4), (9, 0, 3, 1), (9, 3, 0, 1), (6, 2, 3, 1)])
+def test_retained_in_spans_and_budget(oracle, c, n_sink, n_recent, G):
+    T, d = 6 * c + 7, 5
+    for seed in range(5):
+        q, k, v = _rand_stream(100 + seed, T, G, d)
+        s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent)
+        sim = SpanSim(c, n_sink, n_recent)
+        for t in range(T):
+            _, ev, margin, _, _ = s.decode_step(q[t], k[t], v[t])
+            scope = sim.step()
+            pos, S, Cn = s.state()
+            # budget (the cache keeps a fixed size) and ordering
+            assert len(pos) == min(t + 1, c)
+            assert np.all(np.diff(pos) > 0)
+            assert (ev >= 0) == (t + 1 > c) == (scope is not None)
+            # every slot keeps exactly one position of its span; spans shrink towards the right
+            for p, (lo, hi) in zip(pos, sim.spans):
+                assert lo <= p <= hi
+            sizes = sim.sizes()[n_sink:n_sink + sim.m]
+            if scope is not None and sim.idx0 == 0:   # at a round boundary the tree region is sorted
+                assert all(a >= b for a, b in zip(sizes, sizes[1:]))
+            # sinks and the recent window are never evicted
+            assert list(pos[:min(n_sink, t + 1)]) == list(range(min(n_sink, t + 1)))
+            nr = min(n_recent, t + 1)
+            if nr:
+                assert list(pos[-nr:]) == list(range(t + 1 - nr, t + 1))
+            # C counts the queries since arrival
+            assert np.array_equal(Cn, t - pos + 1)
+            if ev >= 0:
+                assert scope[0][0] <= ev <= scope[1][1] and margin >= 0.0
+
+
+def test_newest_token_without_recent_window(oracle):
+    """Algorithm 1 verbatim (no protected window): token t is attended at step t and can be evicted
+    only when the scope has reached the end of the cache (idx = c)."""
+    c, T, d = 8, 100, 3
+    q, k, v = _rand_stream(7, T, 1, d)
+    s = oracle.OracleStream(c, 1, d)
+    for t in range(T):
+        idx = s.idx
+        _, ev, _, _, _ = s.decode_step(q[t], k[t], v[t])
+        if ev == t:
+            assert idx == c
+        else:
+            assert s.retained()[-1] == t
+
+
+# --------------------------------------------------------------------------- #
+# P2: the keep-left ablation (Section 5.4) has a closed form
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("c,n_sink,n_recent", [(4, 0, 0), (8, 0, 0), (7, 0, 0), (12, 2, 3)])
+def test_keep_left_closed_form(oracle, c, n_sink, n_recent):
+    T, d = 9 * c + 3, 3
+    q, k, v = _rand_stream(3, T, 1, d)
+    s = oracle.OracleStream(c, 1, d, n_sink=n_sink, n_recent=n_recent, flags=oracle.KEEP_LEFT)
+    sim = SpanSim(c, n_sink, n_recent)
+    for t in range(T):
+        s.decode_step(q[t], k[t], v[t])
+        sim.step()
+        assert list(s.retained()) == [lo for lo, _ in sim.spans]
+
+
+def test_literal_idx_schedule(oracle):
+    """The printed update idx = (idx+1) mod c + 1 visits only every other scope."""
+    c, d = 4, 2
+    q, k, v = _rand_stream(0, 12, 1, d)
+    s = oracle.OracleStream(c, 1, d, flags=oracle.IDX_LITERAL)
+    seen = []
+    for t in range(12):
+        seen.append(s.idx)
+        s.decode_step(q[t], k[t], v[t])
+    assert seen[c:] == [1, 3, 1, 3, 1, 3, 1, 3]
+
+
+# --------------------------------------------------------------------------- #
+# P4: with no eviction the step is textbook causal softmax attention (Section 3.1)
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("G", [1, 3])
+def test_no_eviction_equals_dense_causal_attention(oracle, G):
+    import torch
+
+    T, d = 40, 8
+    q, k, v = _rand_stream(11, T, G, d)
+    res = oracle.run_decode_stream(_cfg(T, G, d), q, k, v)
+    tq, tk, tv = (torch.from_numpy(x) for x in (q, k, v))
+    logits = torch.einsum("tgd,sd->gts", tq, tk) / math.sqrt(d)
+    mask = torch.tril(torch.ones(T, T, dtype=torch.bool))
+    A = torch.softmax(logits.masked_fill(~mask, float("-inf")), dim=-1)      # [G, T, T]
+    out = torch.einsum("gts,sd->tgd", A, tv)
+    np.testing.assert_allclose(res["out"], out.numpy(), rtol=0, atol=1e-12)
+    pos, S, Cn = res["stream"].state()
+    colsum = A.sum(dim=(0, 1)).numpy()
+    np.testing.assert_allclose(S, colsum, rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(Cn, T - np.arange(T))
+    assert np.all(res["evicted"] == -1)
+    # mass: every query row sums to one
+    assert abs(S.sum() - G * T) < 1e-10
+
+
+def test_prefill_without_eviction_equals_dense(oracle):
+    import torch
+
+    T, d, G = 48, 8, 2
+    q, k, v = _rand_stream(12, T, G, d)
+    s = oracle.OracleStream(T + 5, G, d)
+    outs = []
+    for lo, hi in [(0, 7), (7, 8), (8, 30), (30, 48)]:
+        outs.append(s.prefill_chunk(q[lo:hi], k[lo:hi], v[lo:hi])["out"])
+    out = np.concatenate(outs)
+    tq, tk, tv = (torch.from_numpy(x) for x in (q, k, v))
+    logits = torch.einsum("tgd,sd->gts", tq, tk) / math.sqrt(d)
+    mask = torch.tril(torch.ones(T, T, dtype=torch.bool))
+    A = torch.softmax(logits.masked_fill(~mask, float("-inf")), dim=-1)
+    np.testing.assert_allclose(out, torch.einsum("gts,sd->tgd", A, tv).numpy(), rtol=0, atol=1e-12)
+    pos, S, Cn = s.state()
+    np.testing.assert_allclose(S, A.sum(dim=(0, 1)).numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(Cn, T - np.arange(T))
+
+
+# --------------------------------------------------------------------------- #
+# P7: brute force on tiny inputs
+# --------------------------------------------------------------------------- #
+def _tiny_cases():
+    rng = np.random.default_rng(2025)
+    cases = []
+    for seed in range(150):
+        c = int(rng.integers(2, 9))
+        n_sink = int(rng.integers(0, max(1, c // 3)))
+        n_recent = int(rng.integers(0, max(1, c - n_sink - 1)))
+        if seed % 3 == 0:
+            n_sink = n_recent = 0
+        cases.append((seed, c, n_sink, n_recent, int(rng.integers(1, 4)), int(rng.integers(1, 5)),
+                      int(rng.integers(c + 1, 65))))
+    return cases
+
+
+def test_brute_force_decode(oracle):
+    for seed, c, n_sink, n_recent, G, d, T in _tiny_cases():
+        q, k, v = _rand_stream(seed, T, G, d)
+        flags = [0, oracle.KEEP_LEFT, oracle.IDX_LITERAL][seed % 11 % 3] if seed % 11 < 3 else 0
+        s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent, flags=flags)
+        b = BruteTreeKV(c, G, d, n_sink, n_recent, keep_left=flags == oracle.KEEP_LEFT,
+                        literal_idx=flags == oracle.IDX_LITERAL)
+        for t in range(T):
+            o, ev, _, _, _ = s.decode_step(q[t], k[t], v[t])
+            bo, bev = b.decode_step(q[t].tolist(), k[t].tolist(), v[t].tolist())
+            assert ev == bev, (seed, t)
+            np.testing.assert_allclose(o, np.array(bo), rtol=0, atol=1e-12)
+            assert list(s.retained()) == b.positions()
+        pos, S, Cn = s.state()
+        bS, bC = b.scores()
+        np.testing.assert_allclose(S, bS, rtol=0, atol=1e-12)
+        assert list(Cn) == bC
+
+
+def test_brute_force_prefill(oracle):
+    for seed, c, n_sink, n_recent, G, d, T in _tiny_cases()[:100]:
+        q, k, v = _rand_stream(1000 + seed, T, G, d)
+        rng = np.random.default_rng(seed)
+        s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent)
+        b = BruteTreeKV(c, G, d, n_sink, n_recent)
+        lo = 0
+        while lo < T:
+            L = int(rng.integers(1, 2 * c + 2))
+            hi = min(T, lo + L)
+            if rng.random() < 0.25 and hi - lo == 1:      # mix single decode steps in
+                o, ev, _, _, _ = s.decode_step(q[lo], k[lo], v[lo])
+                bo, bev = b.decode_step(q[lo].tolist(), k[lo].tolist(), v[lo].tolist())
+                assert ev == bev
+                np.testing.assert_allclose(o, np.array(bo), rtol=0, atol=1e-12)
+            else:
+                r = s.prefill_chunk(q[lo:hi], k[lo:hi], v[lo:hi])
+                bo, bev = b.prefill_chunk(q[lo:hi].tolist(), k[lo:hi].tolist(), v[lo:hi].tolist())
+                assert list(r["evicted"]) == bev, (seed, lo, hi)
+                np.testing.assert_allclose(r["out"], np.array(bo), rtol=0, atol=1e-12)
+            assert list(s.retained()) == b.positions()
+            lo = hi
+        pos, S, Cn = s.state()
+        bS, bC = b.scores()
+        np.testing.assert_allclose(S, bS, rtol=0, atol=1e-12)
+        assert list(Cn) == bC
+
+
+# --------------------------------------------------------------------------- #
+# P5: mass conservation with evictions
+# --------------------------------------------------------------------------- #
+def test_mass_conservation(oracle):
+    c, G, d, T = 8, 2, 4, 60
+    q, k, v = _rand_stream(5, T, G, d)
+    s = oracle.OracleStream(c, G, d)
+    lost = 0.0
+    for t in range(T):
+        pos0, S0, _ = s.state()
+        _, ev, _, _, _ = s.decode_step(q[t], k[t], v[t])
+        pos1, S1, _ = s.state()
+        if ev >= 0:
+            # the evicted token took its score with it: old score plus what it got at this step,
+            # which is G minus what the survivors got at this step
+            gained = {p: S1[i] - (S0[list(pos0).index(p)] if p in pos0 else 0.0) for i, p in enumerate(pos1)}
+            got = G - sum(gained.values())
+            old = S0[list(pos0).index(ev)] if ev in pos0 else 0.0
+            assert got > -1e-12
+            lost += old + got
+        assert abs(S1.sum() + lost - G * (t + 1)) < 1e-9
+
+
+# --------------------------------------------------------------------------- #
+# P8: exact ties resolve towards evicting the left slot (strict ">")
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("c", [3, 7, 15])
+def test_exact_ties(oracle, c):
+    """q = 0 gives uniform attention; with c+1 a power of two every token that arrives after the
+    cache filled has Sbar = 1/(c+1) exactly, older tokens have strictly larger Sbar."""
+    d, T = 2, 6 * c + 5
+    rng = np.random.default_rng(0)
+    k, v = rng.standard_normal((T, d)), rng.standard_normal((T, d))
+    q = np.zeros((T, 1, d))
+    s = oracle.OracleStream(c, 1, d)
+    cache = []      # reference: left wins iff it arrived while the cache was still filling
+    idx0 = 0
+    for t in range(T):
+        _, ev, margin, _, _ = s.decode_step(q[t], k[t], v[t])
+        cache.append(t)
+        if len(cache) > c:
+            left, right = cache[idx0], cache[idx0 + 1]
+            gone = right if left < c else left
+            cache.remove(gone)
+            idx0 = (idx0 + 1) % c
+            assert ev == gone
+            if left >= c:
+                assert margin == 0.0
+        assert list(s.retained()) == cache
+    pos, S, Cn = s.state()
+    late = pos >= c
+    assert np.all(S[late] / Cn[late] == 1.0 / (c + 1))
+
+
+# --------------------------------------------------------------------------- #
+# P9: consistency between the prefill chunk and the decode step
+# --------------------------------------------------------------------------- #
+def test_prefill_len1_is_decode(oracle):
+    c, G, d, T = 10, 2, 6, 50
+    q, k, v = _rand_stream(21, T, G, d)
+    a = oracle.OracleStream(c, G, d, n_sink=1, n_recent=3)
+    b = oracle.OracleStream(c, G, d, n_sink=1, n_recent=3)
+    for t in range(T):
+        o, ev, mg, _, _ = a.decode_step(q[t], k[t], v[t])
+        r = b.prefill_chunk(q[t:t + 1], k[t:t + 1], v[t:t + 1])
+        assert np.array_equal(o, r["out"][0]) and ev == r["evicted"][0] and mg == r["margins"][0]
+    for x, y in zip(a.state(), b.state()):
+        assert np.array_equal(x, y)
+
+
+def test_prefill_spans_match_decode(oracle):
+    """Chunked prefill keeps one position per span, the same spans as token-by-token decoding."""
+    c, d = 16, 4
+    for n_sink, n_recent in [(0, 0), (2, 4)]:
+        q, k, v = _rand_stream(33, 200, 1, d)
+        s = oracle.OracleStream(c, 1, d, n_sink=n_sink, n_recent=n_recent)
+        sim = SpanSim(c, n_sink, n_recent)
+        lo = 0
+        for L in [5, 11, 1, 40, 16, 17, 64, 46]:
+            s.prefill_chunk(q[lo:lo + L], k[lo:lo + L], v[lo:lo + L])
+            for _ in range(L):
+                sim.step()
+            lo += L
+            pos = s.retained()
+            assert len(pos) == min(lo, c)
+            for p, (a, b) in zip(pos, sim.spans):
+                assert a <= p <= b
+
+
+def test_dry_run_leaves_state(oracle):
+    c, d = 5, 3
+    q, k, v = _rand_stream(8, 20, 1, d)
+    s = oracle.OracleStream(c, 1, d)
+    for t in range(20):
+        before = [x.copy() for x in s.state()]
+        o1, ev1, m1, _, _ = s.decode_step(q[t], k[t], v[t], commit=False)
+        for x, y in zip(before, s.state()):
+            assert np.array_equal(x, y)
+        assert s.t == t
+        o2, ev2, m2, _, _ = s.decode_step(q[t], k[t], v[t])
+        assert np.array_equal(o1, o2) and ev1 == ev2 and m1 == m2
+
+
+def test_follow_mode(oracle):
+    """The oracle adopts another implementation's choice only inside the near-tie threshold."""
+    c, d = 4, 2
+    q, k, v = _rand_stream(9, 5, 1, d)
+    s = oracle.OracleStream(c, 1, d)
+    for t in range(4):
+        s.decode_step(q[t], k[t], v[t])
+    _, ev, margin, _, _ = s.decode_step(q[4], k[4], v[4], commit=False)
+    other = 1 - ev          # the scope at the first eviction is positions (0, 1)
+    assert ev in (0, 1) and margin > 1e-6
+    _, ev2, _, adopted, disagreed = s.decode_step(q[4], k[4], v[4], forced_pos=other, follow_thresh=1e-9,
+                                                  commit=False)
+    assert (ev2, adopted, disagreed) == (ev, 0, 1)
+    _, ev3, _, adopted, disagreed = s.decode_step(q[4], k[4], v[4], forced_pos=other, follow_thresh=2.0,
+                                                  commit=False)
+    assert (ev3, adopted, disagreed) == (other, 1, 0)
+    _, ev4, _, adopted, disagreed = s.decode_step(q[4], k[4], v[4], forced_pos=3, follow_thresh=2.0)
+    assert (ev4, adopted, disagreed) == (ev, 0, 1)
+
+
+def test_tiny_config_runs_in_seconds(oracle):
+    """The tiny decode configuration: 2 heads, d 64, fp32, budget 64, 512 tokens."""
+    for h in range(2):
+        q, k, v = inputs.stream_iid(0, 512, 1, 64, kv_head=h, k_scale=1.0 / 8.0, dtype="f32")
+        res = oracle.run_decode_stream(_cfg(64, 1, 64, 4, 28, scale=1.0), q, k, v)
+        assert len(res["stream"]) == 64 and np.count_nonzero(res["evicted"] >= 0) == 512 - 64
