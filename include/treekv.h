@@ -1,0 +1,156 @@
+/*
+ * treekv.h - C ABI of the TreeKV hot path for AMD MI355X (gfx950).
+ *
+ * One context holds the state of ONE attention layer: for every (batch element,
+ * KV head) an independent fixed-budget KV cache with per-slot importance
+ * scores, managed by the paper's Algorithm 1 ("Compression by TreeKV",
+ * Section 4.1).  A call attends the new query/queries over the cache
+ * (Section 3.1: a = SoftMax(q K^T / sqrt(d)), o = a V), adds the attention
+ * probabilities to the slots' scores (Algorithm 1, lines 7-8), evicts by the
+ * tree rule (lines 9-17) and reuses the freed slots for the next tokens.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library
+ *     never allocates or frees device memory.  Its own state lives in a
+ *     workspace the caller allocates and binds (treekv_workspace_bytes,
+ *     treekv_bind_workspace).  A snapshot of a context is a copy of that buffer.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; outputs are valid once the stream has been
+ *     synchronised.  Calls on one context must be ordered (one stream, or
+ *     events); calls on different contexts are independent.
+ *   - Tensors are contiguous, row-major, innermost dimension last.
+ *     B = batch, H = query heads, Hkv = KV heads, G = H / Hkv, d = head_dim,
+ *     c = budget.  Query head h reads KV head h / G.
+ *   - Positions are 0-based indices into the token stream of one sequence.
+ *   - Every function returning int returns TREEKV_OK (0) or a negative
+ *     treekv_status.  Argument errors are detected before any work is enqueued
+ *     and leave the context unchanged.
+ *   - Host-side mutable state: none.  Lengths, the eviction index and the free
+ *     slot live in the workspace, so identical calls can be captured in a HIP
+ *     graph and replayed.
+ */
+#ifndef TREEKV_H
+#define TREEKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum treekv_status {
+  TREEKV_OK = 0,
+  TREEKV_EINVAL = -1,       /* null pointer, bad size, inconsistent configuration */
+  TREEKV_ENOWS = -2,        /* workspace not bound, misaligned or too small        */
+  TREEKV_EHIP = -3,         /* a HIP call or kernel launch failed                  */
+  TREEKV_EUNSUPPORTED = -4  /* valid request this build has no kernel for          */
+} treekv_status;
+
+enum { TREEKV_BF16 = 0, TREEKV_F32 = 1 };      /* storage type of q, k, v and of the cache */
+enum { TREEKV_KEEP_LEFT = 1 };                 /* flags: ablation of Section 5.4 (always keep the
+                                                  left slot of the scope, ignore the scores)   */
+
+typedef struct treekv_ctx treekv_ctx;          /* opaque, host memory, owns no device memory */
+
+typedef struct treekv_config {
+  int32_t budget;        /* c: slots kept after every call (Algorithm 1, input "cache size c") */
+  int32_t q_heads;       /* H                                                                  */
+  int32_t kv_heads;      /* Hkv, must divide H; the scores of a KV head add up the attention
+                            probabilities of its G query heads                               */
+  int32_t head_dim;      /* d: 64 or 128                                                       */
+  int32_t batch;         /* B independent sequences, all advancing together                   */
+  int32_t dtype;         /* TREEKV_BF16 or TREEKV_F32                                          */
+  int32_t n_sink;        /* leading tokens never evicted  (Section 5.2: 4)                     */
+  int32_t n_recent;      /* trailing tokens never evicted (Section 5.2: 508 of 1024)           */
+  float softmax_scale;   /* multiplies q.k; 0 selects 1/sqrt(head_dim) (Section 3.1)           */
+  int32_t flags;         /* TREEKV_KEEP_LEFT or 0                                              */
+  int32_t max_chunk;     /* largest `len` treekv_prefill_chunk will be given; 0 selects 512    */
+  int32_t kv_splits;     /* decode: workgroups per (batch, KV head); 0 lets the library choose */
+} treekv_config;
+
+/*
+ * treekv_init - the three-argument form of the problem statement: one sequence
+ * (B = 1), Hkv = H = heads, bf16, scale 1/sqrt(head_dim), and the cache layout
+ * of Section 5.2 scaled to the budget: 4 sink tokens, budget/2 tree slots, the
+ * rest recent tokens (4 + 512 + 508 at budget 1024).  Needs budget >= 16.
+ * Allocates only host memory.  *out is set on success.
+ */
+int treekv_init(treekv_ctx** out, int budget, int heads, int head_dim);
+
+/* treekv_init_ex - full configuration.  Requires budget - n_sink - n_recent >= 1. */
+int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg);
+
+/* Frees the host-side context (not the workspace, which is the caller's). */
+void treekv_destroy(treekv_ctx* ctx);
+
+/* The effective configuration (defaults filled in). */
+int treekv_get_config(const treekv_ctx* ctx, treekv_config* out);
+
+/* Bytes of device memory the context needs (cache rows, scores, positions, order
+ * arrays, split-KV and prefill scratch).  0 for a null context. */
+size_t treekv_workspace_bytes(const treekv_ctx* ctx);
+
+/* Binds caller-allocated device memory (256-byte aligned, at least
+ * treekv_workspace_bytes).  Does not touch the memory; call treekv_reset next. */
+int treekv_bind_workspace(treekv_ctx* ctx, void* dev_ptr, size_t bytes);
+
+/* Algorithm 1, line 1: empty cache, idx at the first scope, position counter 0. */
+int treekv_reset(treekv_ctx* ctx, void* stream);
+
+/*
+ * treekv_decode_step - one iteration of Algorithm 1's loop (lines 4-17) for every
+ * (batch, KV head), without the projections of line 3.
+ *   q [B, H, d], k [B, Hkv, d], v [B, Hkv, d]   storage dtype, read only
+ *   out        [B, H, d] float32: o = SoftMax(q K^T * scale) V over the cache
+ *              including the new token, computed before the eviction
+ *   retained   [B, Hkv, c] int32: positions kept after the step, ascending,
+ *              padded with -1 while the cache is still filling
+ *   n_retained [B, Hkv] int32 (may be NULL)
+ *   evicted    [B, Hkv] int32 (may be NULL): position evicted at this step, or -1
+ */
+int treekv_decode_step(treekv_ctx* ctx, const void* q, const void* k, const void* v, void* out,
+                       int32_t* retained, int32_t* n_retained, int32_t* evicted, void* stream);
+
+/*
+ * treekv_prefill_chunk - `len` consecutive tokens at once (1 <= len <= max_chunk).
+ * Row i attends the cache as it was before the call plus the chunk's tokens
+ * 0..i (causal inside the chunk).  All rows' probabilities are added to the
+ * scores and counts; the averaged scores are then frozen and Algorithm 1's
+ * append / compare / evict / advance (lines 4-5, 9-17) is replayed for the
+ * chunk's tokens in order.  len = 1 is exactly treekv_decode_step.
+ *   Q [B, len, H, d], K [B, len, Hkv, d], V [B, len, Hkv, d]   storage dtype
+ *   out        [B, len, H, d] float32
+ *   retained   [B, Hkv, c] int32, n_retained [B, Hkv] (may be NULL): as above
+ *   evicted    [B, Hkv, len] int32 (may be NULL): position evicted when the
+ *              chunk's i-th token was appended, or -1
+ */
+int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const void* V, int len,
+                         void* out, int32_t* retained, int32_t* n_retained, int32_t* evicted,
+                         void* stream);
+
+/*
+ * treekv_scores - accumulated attention weights S (Algorithm 1, line 8) of the
+ * retained tokens, in the order of `retained`; the count C of line 7 is
+ * t - position + 1 with t the last processed position, so Sbar = S / C.
+ *   scores [B, Hkv, c] float32, padded with 0.
+ */
+int treekv_scores(treekv_ctx* ctx, float* scores, void* stream);
+
+/*
+ * treekv_gather_kv - the retained keys and values in the order of `retained`
+ * (the compacted cache), for callers that want it contiguous.
+ *   K_out, V_out [B, Hkv, c, d] storage dtype; rows past n_retained are zeroed.
+ */
+int treekv_gather_kv(treekv_ctx* ctx, void* K_out, void* V_out, void* stream);
+
+/* Static description of a status code. */
+const char* treekv_strerror(int status);
+
+/* Text of the last HIP error seen by this context ("" if none). */
+const char* treekv_last_hip_error(const treekv_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TREEKV_H */

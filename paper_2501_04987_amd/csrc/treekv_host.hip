@@ -1,0 +1,275 @@
+// Host side of the TreeKV C ABI: configuration checks, workspace carving, launches.
+// Also the three small utility kernels (reset, score read-out, K/V gather).
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "treekv_internal.h"
+
+struct treekv_ctx {
+  treekv_config cfg;
+  tkv::Params p;
+  size_t ws_bytes;
+  bool bound;
+  char hip_err[256];
+};
+
+namespace tkv {
+namespace {
+
+constexpr size_t ALIGN = 256;
+size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+// Walks the workspace layout; with base == nullptr it only measures.
+size_t carve(Params& p, char* base) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* ptr = base ? base + off : nullptr;
+    off += align_up(bytes);
+    return ptr;
+  };
+  const size_t esz = p.dtype == TREEKV_BF16 ? 2 : 4;
+  const size_t U = p.U, cap = p.cap, ext = (size_t)p.cap + p.max_chunk;
+  p.K = take(U * cap * p.D * esz);
+  p.V = take(U * cap * p.D * esz);
+  p.S = (float*)take(U * cap * 4);
+  p.pos = (int*)take(U * cap * 4);
+  p.E = (int*)take(U * 2 * p.m * 4);
+  p.R = (int*)take(U * (size_t)(p.n_recent > 0 ? p.n_recent : 1) * 4);
+  p.meta = (int*)take(U * META_STRIDE * 4);
+  p.logits = (float*)take(U * p.G * cap * 4);
+  p.partial = (float*)take(U * p.nsplit * p.G * (size_t)(p.D + 2) * 4);
+  p.counter = (unsigned*)take(U * 4);
+  p.pf_colsum = (float*)take(U * (size_t)p.pf_qtiles * ext * 4);
+  p.pf_rowstat = (float*)take(U * p.G * (size_t)p.max_chunk * 2 * 4);
+  p.pf_sbar = (float*)take(U * ext * 4);
+  p.pf_snew = (float*)take(U * (size_t)p.max_chunk * 4);
+  p.pf_flag = (int*)take(U * ext * 4);
+  return off;
+}
+
+__global__ void reset_kernel(Params p) {
+  const int unit = blockIdx.x;
+  int* meta = p.meta + (size_t)unit * META_STRIDE;
+  int* Eu = p.E + (size_t)unit * 2 * p.m;
+  int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
+  // While the cache fills, token i sits in slot i, so at the first eviction the tree region
+  // is slots n_sink .. n_sink+m-1 and the recent window the slots after it.
+  for (int i = threadIdx.x; i < 2 * p.m; i += blockDim.x) Eu[i] = i < p.m ? p.n_sink + i : 0;
+  for (int i = threadIdx.x; i < p.n_recent; i += blockDim.x) Ru[i] = p.n_sink + p.m + i;
+  for (int i = threadIdx.x; i < p.cap; i += blockDim.x) {
+    p.S[(size_t)unit * p.cap + i] = 0.f;
+    p.pos[(size_t)unit * p.cap + i] = -1;
+  }
+  if (threadIdx.x < META_STRIDE) meta[threadIdx.x] = 0;
+  if (threadIdx.x == 0) p.counter[unit] = 0;
+}
+
+__global__ void scores_kernel(Params p, float* __restrict__ scores) {
+  const int unit = blockIdx.x;
+  const int* meta = p.meta + (size_t)unit * META_STRIDE;
+  const int n = meta[META_N], j = meta[META_J], rhead = meta[META_RHEAD];
+  const int* Eu = p.E + (size_t)unit * 2 * p.m;
+  const int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
+  for (int i = threadIdx.x; i < p.budget; i += blockDim.x) {
+    float s = 0.f;
+    if (i < n) {
+      const int slot = n < p.budget ? i : logical_to_slot(p, Eu, Ru, rhead, j, i);
+      s = p.S[(size_t)unit * p.cap + slot];
+    }
+    scores[(size_t)unit * p.budget + i] = s;
+  }
+}
+
+__global__ void gather_kv_kernel(Params p, uint4* __restrict__ Kout, uint4* __restrict__ Vout, int row_vec) {
+  const int unit = blockIdx.y, i = blockIdx.x;   // one block per logical row
+  const int* meta = p.meta + (size_t)unit * META_STRIDE;
+  const int n = meta[META_N], j = meta[META_J], rhead = meta[META_RHEAD];
+  const int* Eu = p.E + (size_t)unit * 2 * p.m;
+  const int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
+  const size_t dst = ((size_t)unit * p.budget + i) * row_vec;
+  if (i >= n) {
+    for (int e = threadIdx.x; e < row_vec; e += blockDim.x) Kout[dst + e] = Vout[dst + e] = make_uint4(0, 0, 0, 0);
+    return;
+  }
+  const int slot = n < p.budget ? i : logical_to_slot(p, Eu, Ru, rhead, j, i);
+  const size_t src = ((size_t)unit * p.cap + slot) * row_vec;
+  for (int e = threadIdx.x; e < row_vec; e += blockDim.x) {
+    Kout[dst + e] = reinterpret_cast<const uint4*>(p.K)[src + e];
+    Vout[dst + e] = reinterpret_cast<const uint4*>(p.V)[src + e];
+  }
+}
+
+int check_launch() { return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP; }
+
+}  // namespace
+
+int launch_reset(const Params& p, hipStream_t s) {
+  hipLaunchKernelGGL(reset_kernel, dim3(p.U), dim3(256), 0, s, p);
+  return check_launch();
+}
+
+int launch_scores(const Params& p, float* scores, hipStream_t s) {
+  hipLaunchKernelGGL(scores_kernel, dim3(p.U), dim3(256), 0, s, p, scores);
+  return check_launch();
+}
+
+int launch_gather_kv(const Params& p, void* K_out, void* V_out, hipStream_t s) {
+  const int row_vec = p.D * (p.dtype == TREEKV_BF16 ? 2 : 4) / 16;
+  hipLaunchKernelGGL(gather_kv_kernel, dim3(p.budget, p.U), dim3(64), 0, s, p, (uint4*)K_out, (uint4*)V_out, row_vec);
+  return check_launch();
+}
+
+}  // namespace tkv
+
+// --------------------------------------------------------------------------------------
+// C ABI
+// --------------------------------------------------------------------------------------
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int record_hip(treekv_ctx* ctx, int rc) {
+  if (rc == TREEKV_EHIP) {
+    hipError_t e = hipPeekAtLastError();
+    snprintf(ctx->hip_err, sizeof(ctx->hip_err), "%s", hipGetErrorString(e));
+    (void)hipGetLastError();
+  }
+  return rc;
+}
+
+int pick_splits(const treekv_config& c) {
+  // Enough workgroups to cover 256 compute units a few times over, but no split shorter
+  // than 128 slots (below that the merge costs more than the streaming it spreads).
+  const int units = c.batch * c.kv_heads;
+  int splits = (1024 + units - 1) / units;
+  const int max_by_len = (c.budget + 1 + 127) / 128;
+  if (splits > max_by_len) splits = max_by_len;
+  if (splits > 32) splits = 32;
+  if (splits < 1) splits = 1;
+  return splits;
+}
+
+}  // namespace
+
+extern "C" {
+
+int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg_in) {
+  if (!out || !cfg_in) return TREEKV_EINVAL;
+  treekv_config c = *cfg_in;
+  if (c.budget < 1 || c.q_heads < 1 || c.kv_heads < 1 || c.batch < 1) return TREEKV_EINVAL;
+  if (c.q_heads % c.kv_heads != 0) return TREEKV_EINVAL;
+  if (c.n_sink < 0 || c.n_recent < 0 || c.budget - c.n_sink - c.n_recent < 1) return TREEKV_EINVAL;
+  if (c.dtype != TREEKV_BF16 && c.dtype != TREEKV_F32) return TREEKV_EINVAL;
+  if (c.flags & ~TREEKV_KEEP_LEFT) return TREEKV_EINVAL;
+  if (c.max_chunk < 0 || c.kv_splits < 0 || c.kv_splits > 64) return TREEKV_EINVAL;
+  if (!(c.softmax_scale >= 0.0f) || isinf(c.softmax_scale)) return TREEKV_EINVAL;
+  if (c.head_dim != 64 && c.head_dim != 128) return TREEKV_EUNSUPPORTED;
+  const int G = c.q_heads / c.kv_heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return TREEKV_EUNSUPPORTED;
+  if ((long long)c.budget > (1 << 24) || (long long)c.batch * c.kv_heads > 65535) return TREEKV_EUNSUPPORTED;
+  if (c.max_chunk == 0) c.max_chunk = 512;
+  if (c.max_chunk > 4096) return TREEKV_EUNSUPPORTED;
+  if (c.softmax_scale == 0.0f) c.softmax_scale = 1.0f / sqrtf((float)c.head_dim);
+  if (c.kv_splits == 0) c.kv_splits = pick_splits(c);
+
+  treekv_ctx* ctx = new (std::nothrow) treekv_ctx;
+  if (!ctx) return TREEKV_EINVAL;
+  memset(ctx, 0, sizeof(*ctx));
+  ctx->cfg = c;
+  tkv::Params& p = ctx->p;
+  p.budget = c.budget; p.cap = c.budget + 1; p.n_sink = c.n_sink; p.n_recent = c.n_recent;
+  p.m = c.budget - c.n_sink - c.n_recent;
+  p.B = c.batch; p.H = c.q_heads; p.Hkv = c.kv_heads; p.G = G; p.D = c.head_dim; p.U = c.batch * c.kv_heads;
+  p.dtype = c.dtype; p.flags = c.flags; p.nsplit = c.kv_splits; p.max_chunk = c.max_chunk;
+  p.scale_log2e = c.softmax_scale * 1.4426950408889634f;
+  p.pf_qtiles = (c.max_chunk + 63) / 64;
+  ctx->ws_bytes = tkv::carve(p, nullptr);
+  *out = ctx;
+  return TREEKV_OK;
+}
+
+int treekv_init(treekv_ctx** out, int budget, int heads, int head_dim) {
+  if (budget < 16) return TREEKV_EINVAL;
+  treekv_config c;
+  memset(&c, 0, sizeof(c));
+  c.budget = budget; c.q_heads = heads; c.kv_heads = heads; c.head_dim = head_dim; c.batch = 1;
+  c.dtype = TREEKV_BF16;
+  c.n_sink = 4;
+  c.n_recent = budget - budget / 2 - 4;   // tree region = budget / 2 slots
+  return treekv_init_ex(out, &c);
+}
+
+void treekv_destroy(treekv_ctx* ctx) { delete ctx; }
+
+int treekv_get_config(const treekv_ctx* ctx, treekv_config* out) {
+  if (!ctx || !out) return TREEKV_EINVAL;
+  *out = ctx->cfg;
+  return TREEKV_OK;
+}
+
+size_t treekv_workspace_bytes(const treekv_ctx* ctx) { return ctx ? ctx->ws_bytes : 0; }
+
+int treekv_bind_workspace(treekv_ctx* ctx, void* dev_ptr, size_t bytes) {
+  if (!ctx || !dev_ptr) return TREEKV_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(dev_ptr) & (tkv::ALIGN - 1)) != 0 || bytes < ctx->ws_bytes) return TREEKV_ENOWS;
+  tkv::carve(ctx->p, static_cast<char*>(dev_ptr));
+  ctx->bound = true;
+  return TREEKV_OK;
+}
+
+int treekv_reset(treekv_ctx* ctx, void* stream) {
+  if (!ctx) return TREEKV_EINVAL;
+  if (!ctx->bound) return TREEKV_ENOWS;
+  return record_hip(ctx, tkv::launch_reset(ctx->p, (hipStream_t)stream));
+}
+
+int treekv_decode_step(treekv_ctx* ctx, const void* q, const void* k, const void* v, void* out, int32_t* retained,
+                       int32_t* n_retained, int32_t* evicted, void* stream) {
+  if (!ctx || !q || !k || !v || !out || !retained) return TREEKV_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return TREEKV_EINVAL;
+  if (!ctx->bound) return TREEKV_ENOWS;
+  return record_hip(ctx, tkv::launch_decode(ctx->p, q, k, v, (float*)out, retained, n_retained, evicted,
+                                            (hipStream_t)stream));
+}
+
+int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const void* V, int len, void* out,
+                         int32_t* retained, int32_t* n_retained, int32_t* evicted, void* stream) {
+  if (!ctx || !Q || !K || !V || !out || !retained) return TREEKV_EINVAL;
+  if (len < 1 || len > ctx->cfg.max_chunk) return TREEKV_EINVAL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out)) return TREEKV_EINVAL;
+  if (!ctx->bound) return TREEKV_ENOWS;
+  return record_hip(ctx, tkv::launch_prefill(ctx->p, Q, K, V, len, (float*)out, retained, n_retained, evicted,
+                                             (hipStream_t)stream));
+}
+
+int treekv_scores(treekv_ctx* ctx, float* scores, void* stream) {
+  if (!ctx || !scores) return TREEKV_EINVAL;
+  if (!ctx->bound) return TREEKV_ENOWS;
+  return record_hip(ctx, tkv::launch_scores(ctx->p, scores, (hipStream_t)stream));
+}
+
+int treekv_gather_kv(treekv_ctx* ctx, void* K_out, void* V_out, void* stream) {
+  if (!ctx || !K_out || !V_out) return TREEKV_EINVAL;
+  if (!aligned16(K_out) || !aligned16(V_out)) return TREEKV_EINVAL;
+  if (!ctx->bound) return TREEKV_ENOWS;
+  return record_hip(ctx, tkv::launch_gather_kv(ctx->p, K_out, V_out, (hipStream_t)stream));
+}
+
+const char* treekv_strerror(int status) {
+  switch (status) {
+    case TREEKV_OK: return "ok";
+    case TREEKV_EINVAL: return "invalid argument";
+    case TREEKV_ENOWS: return "workspace not bound, misaligned or too small";
+    case TREEKV_EHIP: return "HIP call failed";
+    case TREEKV_EUNSUPPORTED: return "configuration not supported by this build";
+    default: return "unknown status";
+  }
+}
+
+const char* treekv_last_hip_error(const treekv_ctx* ctx) { return ctx ? ctx->hip_err : ""; }
+
+}  // extern "C"

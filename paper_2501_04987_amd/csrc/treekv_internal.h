@@ -1,0 +1,115 @@
+// Internal declarations shared by the host library and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "treekv.h"
+
+namespace tkv {
+
+// Per-unit bookkeeping words (unit = one (batch, KV head) stream).
+enum MetaField : int {
+  META_N = 0,      // tokens currently retained
+  META_FREE = 1,   // physical slot the next token is written to
+  META_J = 2,      // 0-based eviction index inside the tree region (the paper's idx - 1)
+  META_RHEAD = 3,  // oldest entry of the recent-window ring
+  META_T = 4,      // tokens processed so far == position of the next token
+  META_STRIDE = 8
+};
+
+// Everything a kernel needs to find its way through the workspace.
+//
+// Physical layout.  A unit owns cap = budget + 1 cache rows ("slots").  A token
+// stays in the slot it was written to until it is evicted; the evicted slot is
+// the next token's slot.  Attention ignores order, so rows never move.
+// Logical (position) order is kept in three small index arrays:
+//   sinks   : slots 0 .. n_sink-1 (the first tokens, written while filling)
+//   tree    : E[2m].  During a round of m evictions, E[0..m) is the tree region
+//             at the round's start and E[m+j] the token that entered the tree
+//             region at the round's j-th step.  Eviction j compares E[2j] and
+//             E[2j+1] and stores the survivor in E[j].  After eviction j the
+//             region reads E[0..j] then E[2j+2 .. m+j].
+//   recent  : ring R[n_recent] of slots, oldest at META_RHEAD.
+struct Params {
+  int budget, cap, n_sink, n_recent, m;
+  int B, H, Hkv, G, D, U;   // U = B * Hkv units
+  int dtype, flags, nsplit, max_chunk;
+  float scale_log2e;        // softmax_scale * log2(e): probabilities are exp2 of scaled logits
+  void* K;                  // [U][cap][D] storage dtype
+  void* V;                  // [U][cap][D]
+  float* S;                 // [U][cap] accumulated attention weight per slot
+  int* pos;                 // [U][cap] stream position held by the slot
+  int* E;                   // [U][2m]
+  int* R;                   // [U][max(n_recent,1)]
+  int* meta;                // [U][META_STRIDE]
+  float* logits;            // [U][G][cap]   decode scratch: scaled logits (log2 domain)
+  float* partial;           // [U][nsplit][G][D+2] decode scratch: split-KV partial (acc, max, sum)
+  unsigned* counter;        // [U] decode scratch: split arrival tickets
+  // prefill scratch
+  float* pf_colsum;         // [U][pf_qtiles][cap + max_chunk] per-query-tile column sums
+  float* pf_rowstat;        // [U][G][max_chunk][2] row max (log2 domain) and 1/row sum
+  float* pf_sbar;           // [U][cap + max_chunk] frozen averaged scores by token id
+  float* pf_snew;           // [U][max_chunk] accumulated S of the chunk's tokens
+  int* pf_flag;             // [U][cap + max_chunk] liveness / slot assignment scratch
+  int pf_qtiles;
+};
+
+int launch_reset(const Params& p, hipStream_t s);
+int launch_decode(const Params& p, const void* q, const void* k, const void* v, float* out,
+                  int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s);
+int launch_prefill(const Params& p, const void* Q, const void* K, const void* V, int len, float* out,
+                   int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s);
+int launch_scores(const Params& p, float* scores, hipStream_t s);
+int launch_gather_kv(const Params& p, void* K_out, void* V_out, hipStream_t s);
+
+// ---- device helpers shared by the kernels ---------------------------------
+#if defined(__HIPCC__)
+
+template <typename T> struct Storage;
+template <> struct Storage<uint16_t> {   // bfloat16 bit patterns
+  static constexpr int EPL = 8;          // elements in one 16-byte lane load
+  __device__ static inline void widen(const uint4& r, float (&f)[8]) {
+    const unsigned w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+template <> struct Storage<float> {
+  static constexpr int EPL = 4;
+  __device__ static inline void widen(const uint4& r, float (&f)[4]) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Loads and stores that stay coherent across the per-XCD L2 caches inside one kernel.
+__device__ inline float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Logical index i (0 <= i < n) -> physical slot, for a unit whose cache is full
+// (n == budget) and whose last eviction was the j_done-th of its round
+// (j_done = number of evictions already done in the round, 1..m; m means the round
+// just ended, which reads the same as 0 done in the next round).
+__device__ inline int logical_to_slot(const Params& p, const int* E, const int* R, int rhead, int j_done, int i) {
+  if (i < p.n_sink) return i;
+  int k = i - p.n_sink;
+  if (k < p.m) return (k < j_done) ? E[k] : E[k + j_done];
+  k -= p.m;
+  int r = rhead + k;
+  if (r >= p.n_recent) r -= p.n_recent;
+  return R[r];
+}
+
+#endif  // __HIPCC__
+
+}  // namespace tkv

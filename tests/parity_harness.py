@@ -1,0 +1,128 @@
+"""Drives the HIP path through the C ABI and the CPU oracle on the same inputs, and compares.
+
+Retained-index sets must match bit for bit.  The two sides accumulate scores in different
+precision (fp32 on the GPU, fp64 in the oracle), so a comparison whose relative margin is
+below FOLLOW_THRESH can legitimately fall either way: there the oracle adopts the GPU's
+choice, the event is counted, and everything after it is still compared exactly.  A
+disagreement at a larger margin is a failure.
+"""
+from __future__ import annotations
+
+import os
+
+import numpy as np
+
+FOLLOW_THRESH = 1e-4          # relative score margin below which a decision is "flagged"
+TOL = {"bf16": 2e-3, "f32": 1e-5}
+
+
+def to_device(x: np.ndarray, dtype: str):
+    import torch
+
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    return t.to(torch.bfloat16 if dtype == "bf16" else torch.float32).cuda()
+
+
+def gpu_decode_run(kv, Qd, Kd, Vd, sample_steps=()):
+    """Run T decode steps.  Qd [T,B,H,d], Kd/Vd [T,B,Hkv,d] device tensors in storage dtype.
+
+    Returns dict(out [T,B,H,d] f32 cpu, evicted [T,B,Hkv] cpu, n_retained [T,B,Hkv] cpu,
+    retained {step: [B,Hkv,c] cpu}).
+    """
+    import torch
+
+    T = Qd.shape[0]
+    c = kv.cfg
+    out = torch.empty(T, c.batch, c.q_heads, c.head_dim, dtype=torch.float32, device=kv.device)
+    ev = torch.empty(T, c.batch, c.kv_heads, dtype=torch.int32, device=kv.device)
+    nret = torch.empty(T, c.batch, c.kv_heads, dtype=torch.int32, device=kv.device)
+    sample_steps = sorted(set(int(s) for s in sample_steps))
+    ret_s = torch.empty(max(len(sample_steps), 1), c.batch, c.kv_heads, c.budget, dtype=torch.int32, device=kv.device)
+    scratch = torch.empty(c.batch, c.kv_heads, c.budget, dtype=torch.int32, device=kv.device)
+    where = {s: i for i, s in enumerate(sample_steps)}
+    for t in range(T):
+        r = ret_s[where[t]] if t in where else scratch
+        kv.decode_step(Qd[t], Kd[t], Vd[t], out[t], r, nret[t], ev[t])
+    torch.cuda.synchronize()
+    return dict(out=out.cpu().numpy(), evicted=ev.cpu().numpy(), n_retained=nret.cpu().numpy(),
+                retained={s: ret_s[i].cpu().numpy() for s, i in where.items()})
+
+
+def oracle_cfg(kv, **over):
+    c = kv.cfg
+    d = dict(budget=c.budget, G=c.q_heads // c.kv_heads, d=c.head_dim, n_sink=c.n_sink, n_recent=c.n_recent,
+             scale=float(c.softmax_scale), flags=int(c.flags))
+    d.update(over)
+    return d
+
+
+def retained_from_evictions(evicted: np.ndarray, upto: int) -> np.ndarray:
+    """Ascending positions alive after step `upto` given the per-step evicted positions."""
+    alive = np.ones(upto + 1, bool)
+    ev = evicted[: upto + 1]
+    alive[ev[ev >= 0]] = False
+    return np.flatnonzero(alive)
+
+
+def compare_decode(oracle, kv, Q, K, V, gpu, units=None, dtype="bf16", every_step_retained=False, workers=None):
+    """Q [T,B,H,d], K/V [T,B,Hkv,d] float arrays holding the values the GPU consumed.
+
+    Runs the oracle (follow mode) on the chosen units and checks outputs, evictions, retained
+    sets.  Returns dict(flagged, max_err, decisions).
+    """
+    c = kv.cfg
+    G = c.q_heads // c.kv_heads
+    T = Q.shape[0]
+    if units is None:
+        units = [(b, h) for b in range(c.batch) for h in range(c.kv_heads)]
+    cfg = oracle_cfg(kv)
+    tol = TOL[dtype]
+
+    def job(u):
+        b, h = u
+        return oracle.run_decode_stream(cfg, Q[:, b, h * G:(h + 1) * G, :], K[:, b, h, :], V[:, b, h, :],
+                                        forced=gpu["evicted"][:, b, h], follow_thresh=FOLLOW_THRESH)
+
+    results = oracle.run_many(job, units, workers=workers or min(len(units), os.cpu_count() or 1, 16))
+    flagged = 0
+    decisions = 0
+    max_err = 0.0
+    for (b, h), res in zip(units, results):
+        assert res["disagreed"] == 0, f"unit {(b, h)}: {res['disagreed']} eviction decisions differ outside the near-tie margin"
+        np.testing.assert_array_equal(res["evicted"], gpu["evicted"][:, b, h], err_msg=f"evicted positions, unit {(b, h)}")
+        flagged += res["adopted"]
+        decisions += int(np.count_nonzero(res["evicted"] >= 0))
+        err = np.abs(res["out"] - gpu["out"][:, b, h * G:(h + 1) * G, :]).max()
+        max_err = max(max_err, float(err))
+        assert err <= tol, f"unit {(b, h)}: attention output differs by {err} > {tol}"
+        want_n = np.minimum(np.arange(1, T + 1), c.budget)
+        np.testing.assert_array_equal(gpu["n_retained"][:, b, h], want_n)
+        steps = gpu["retained"].keys()
+        for s in steps:
+            want = retained_from_evictions(res["evicted"], s)
+            got = gpu["retained"][s][b, h]
+            assert np.array_equal(got[: len(want)], want), f"retained set, unit {(b, h)}, step {s}"
+            assert np.all(got[len(want):] == -1)
+        # the oracle's own final state agrees with the reconstruction
+        assert np.array_equal(res["stream"].retained(), retained_from_evictions(res["evicted"], T - 1))
+    return dict(flagged=flagged, max_err=max_err, decisions=decisions, results=dict(zip(units, results)))
+
+
+def compare_scores(kv, results, dtype="bf16"):
+    """Averaged scores Sbar = S / C of the retained tokens, GPU vs oracle, at the current step."""
+    import torch
+
+    S = kv.scores()
+    torch.cuda.synchronize()
+    S = S.cpu().numpy()
+    tol = TOL[dtype]
+    worst = 0.0
+    for (b, h), res in results.items():
+        pos, So, Co = res["stream"].state()
+        n = len(pos)
+        sbar_o = So / Co
+        sbar_g = S[b, h, :n].astype(np.float64) / Co
+        worst = max(worst, float(np.abs(sbar_o - sbar_g).max()))
+        assert np.all(S[b, h, n:] == 0)
+    assert worst <= tol, f"averaged scores differ by {worst} > {tol}"
+    return worst

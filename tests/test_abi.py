@@ -1,0 +1,94 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared
+symbol, validates configurations and sizes the workspace."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2501_04987_amd import binding as b
+    from paper_2501_04987_amd import build
+
+    if not os.path.exists(b.LIB_PATH):
+        build.build()
+    b.load()
+    return b
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "treekv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(treekv_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(binding):
+    lib = binding.load()
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in include/treekv.h but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def _init(binding, **kw):
+    base = dict(budget=64, q_heads=4, kv_heads=4, head_dim=128, batch=1, dtype=binding.TREEKV_BF16, n_sink=0,
+                n_recent=0, softmax_scale=0.0, flags=0, max_chunk=0, kv_splits=0)
+    base.update(kw)
+    cfg = binding.treekv_config(**base)
+    h = C.c_void_p()
+    rc = binding.load().treekv_init_ex(C.byref(h), C.byref(cfg))
+    return rc, h
+
+
+def test_config_validation(binding):
+    lib = binding.load()
+    bad = [dict(budget=0), dict(q_heads=6, kv_heads=4), dict(n_sink=40, n_recent=24), dict(dtype=7),
+           dict(flags=8), dict(n_sink=-1), dict(softmax_scale=float("nan")), dict(kv_splits=100)]
+    for kw in bad:
+        rc, h = _init(binding, **kw)
+        assert rc == binding.TREEKV_EINVAL and not h.value, kw
+    for kw in [dict(head_dim=96), dict(q_heads=12, kv_heads=4), dict(max_chunk=100000)]:
+        rc, h = _init(binding, **kw)
+        assert rc == binding.TREEKV_EUNSUPPORTED, kw
+    h = C.c_void_p()
+    assert lib.treekv_init(C.byref(h), 8, 4, 128) == binding.TREEKV_EINVAL     # default layout needs budget >= 16
+    assert lib.treekv_init(None, 64, 4, 128) == binding.TREEKV_EINVAL
+    assert lib.treekv_strerror(binding.TREEKV_ENOWS).decode().startswith("workspace")
+
+
+def test_defaults_and_workspace_size(binding):
+    lib = binding.load()
+    h = C.c_void_p()
+    assert lib.treekv_init(C.byref(h), 2048, 32, 128) == 0
+    cfg = binding.treekv_config()
+    assert lib.treekv_get_config(h, C.byref(cfg)) == 0
+    assert (cfg.n_sink, cfg.n_recent, cfg.batch, cfg.kv_heads, cfg.max_chunk) == (4, 1020, 1, 32, 512)
+    assert abs(cfg.softmax_scale - 128 ** -0.5) < 1e-7 and cfg.kv_splits >= 1
+    nbytes = lib.treekv_workspace_bytes(h)
+    kv_bytes = 2 * 32 * 2049 * 128 * 2
+    assert kv_bytes < nbytes < kv_bytes * 1.25       # the cache rows dominate the workspace
+    # unbound context: every call that needs the workspace refuses, nothing is launched
+    assert lib.treekv_reset(h, None) == binding.TREEKV_ENOWS
+    assert lib.treekv_bind_workspace(h, None, nbytes) == binding.TREEKV_EINVAL
+    assert lib.treekv_bind_workspace(h, C.c_void_p(0x1001), nbytes) == binding.TREEKV_ENOWS
+    assert lib.treekv_bind_workspace(h, C.c_void_p(0x1000), nbytes - 1) == binding.TREEKV_ENOWS
+    one = C.c_void_p(0x1000)
+    assert lib.treekv_decode_step(h, one, one, one, one, one, None, None, None) == binding.TREEKV_ENOWS
+    assert lib.treekv_decode_step(h, None, one, one, one, one, None, None, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_decode_step(h, C.c_void_p(0x1004), one, one, one, one, None, None, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_prefill_chunk(h, one, one, one, 0, one, one, None, None, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_prefill_chunk(h, one, one, one, 513, one, one, None, None, None) == binding.TREEKV_EINVAL
+    lib.treekv_destroy(h)
+    assert lib.treekv_workspace_bytes(None) == 0
+
+
+def test_missing_library_is_loud(binding, monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libtreekv.so")
+    with pytest.raises(RuntimeError):
+        binding.load()

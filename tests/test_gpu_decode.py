@@ -1,0 +1,138 @@
+"""GPU parity: the HIP decode step (through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+from paper_2501_04987_amd import inputs
+from tests import parity_harness as ph
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2501_04987_amd import binding as b
+
+    b.load()     # raises if the HIP library is not built: there is no fallback
+    return b
+
+
+def _run(binding, oracle, *, kind, T, B, H, Hkv, d, dtype, budget, n_sink, n_recent, seed=0, flags=0,
+         kv_splits=0, scale=0.0, k_scale=1.0, every_step=True, units=None, sample=None):
+    G = H // Hkv
+    kw = dict(k_scale=k_scale) if kind == "iid" else {}
+    Q, K, V = inputs.batch_streams(kind, seed, T, B, Hkv, G, d, dtype=dtype, **kw)
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype=dtype, n_sink=n_sink, n_recent=n_recent,
+                        softmax_scale=scale, flags=flags, kv_splits=kv_splits)
+    steps = range(T) if every_step else (sample or [T - 1])
+    gpu = ph.gpu_decode_run(kv, ph.to_device(Q, dtype), ph.to_device(K, dtype), ph.to_device(V, dtype), steps)
+    rep = ph.compare_decode(oracle, kv, Q, K, V, gpu, units=units, dtype=dtype)
+    rep["score_err"] = ph.compare_scores(kv, rep["results"], dtype)
+    # flagged near-ties are rare by construction of the inputs
+    assert rep["flagged"] <= max(2, rep["decisions"] // 500), rep["flagged"]
+    print(f"  flagged={rep['flagged']}/{rep['decisions']} max_err={rep['max_err']:.2e} score_err={rep['score_err']:.2e}")
+    return kv, gpu, rep
+
+
+@pytest.mark.parametrize("layout", [(4, 28), (0, 0)])
+def test_tiny_decode_config(binding, oracle, layout):
+    """2 heads, head_dim 64, fp32, budget 64, 512-token stream; K carries the 1/sqrt(64), scale 1."""
+    _run(binding, oracle, kind="iid", T=512, B=1, H=2, Hkv=2, d=64, dtype="f32", budget=64,
+         n_sink=layout[0], n_recent=layout[1], scale=1.0, k_scale=0.125)
+
+
+@pytest.mark.parametrize("splits", [1, 2, 3, 5])
+def test_bf16_ragged_budget_splits(binding, oracle, splits):
+    """Budget 203 (cap 204 is not a multiple of any tile), several split counts, incl. empty splits."""
+    _run(binding, oracle, kind="lowrank", T=650, B=1, H=3, Hkv=3, d=128, dtype="bf16", budget=203,
+         n_sink=4, n_recent=98, kv_splits=splits, seed=3)
+
+
+def test_bf16_pure_algorithm1(binding, oracle):
+    """No sinks, no recent window: Algorithm 1 verbatim; the new token itself can be in the scope."""
+    _run(binding, oracle, kind="lowrank", T=700, B=2, H=2, Hkv=2, d=128, dtype="bf16", budget=160,
+         n_sink=0, n_recent=0, kv_splits=4, seed=5)
+
+
+@pytest.mark.parametrize("G,d,dtype", [(4, 128, "bf16"), (2, 64, "bf16"), (8, 64, "f32"), (1, 128, "f32")])
+def test_grouped_queries_and_types(binding, oracle, G, d, dtype):
+    # the low-rank streams (values up to ~15) go with bf16; fp32 is checked to 1e-5 on unit-variance streams
+    _run(binding, oracle, kind="lowrank" if dtype == "bf16" else "iid", T=400, B=2, H=2 * G, Hkv=2, d=d, dtype=dtype, budget=96,
+         n_sink=2, n_recent=30, kv_splits=2, seed=7)
+
+
+@pytest.mark.parametrize("budget,n_sink,n_recent", [(1, 0, 0), (2, 0, 0), (3, 1, 1), (5, 0, 4), (5, 4, 0)])
+def test_degenerate_budgets(binding, oracle, budget, n_sink, n_recent):
+    _run(binding, oracle, kind="iid", T=40, B=1, H=1, Hkv=1, d=64, dtype="f32", budget=budget,
+         n_sink=n_sink, n_recent=n_recent)
+
+
+def test_keep_left_ablation(binding, oracle):
+    kv, gpu, rep = _run(binding, oracle, kind="lowrank", T=300, B=1, H=2, Hkv=2, d=128, dtype="bf16", budget=64,
+                        n_sink=0, n_recent=0, flags=binding.TREEKV_KEEP_LEFT, seed=9)
+    from tests.span_sim import SpanSim
+
+    sim = SpanSim(64)
+    for _ in range(300):
+        sim.step()
+    assert list(gpu["retained"][299][0, 0]) == [lo for lo, _ in sim.spans]
+
+
+def test_default_init_layout(binding):
+    """treekv_init(budget, heads, head_dim): 4 sinks + budget/2 tree slots + the rest recent."""
+    kv = binding.TreeKV(1024, 32, 128)
+    c = kv.cfg
+    assert (c.n_sink, c.n_recent, c.budget - c.n_sink - c.n_recent) == (4, 508, 512)
+    assert (c.batch, c.kv_heads, c.dtype) == (1, 32, binding.TREEKV_BF16)
+    assert abs(c.softmax_scale - 128 ** -0.5) < 1e-7
+
+
+def test_gather_kv_matches_retained(binding, oracle):
+    import torch
+
+    T, B, H, d, budget = 300, 1, 2, 128, 50
+    Q, K, V = inputs.batch_streams("lowrank", 11, T, B, H, 1, d, dtype="bf16")
+    kv = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=2, n_recent=10)
+    gpu = ph.gpu_decode_run(kv, ph.to_device(Q, "bf16"), ph.to_device(K, "bf16"), ph.to_device(V, "bf16"), [T - 1])
+    Kc, Vc = kv.gather_kv()
+    torch.cuda.synchronize()
+    ret = gpu["retained"][T - 1]
+    for h in range(H):
+        np.testing.assert_array_equal(Kc[0, h].float().cpu().numpy(), K[ret[0, h], 0, h])
+        np.testing.assert_array_equal(Vc[0, h].float().cpu().numpy(), V[ret[0, h], 0, h])
+
+
+def test_reset_restarts_the_stream(binding, oracle):
+    import torch
+
+    T, H, d, budget = 120, 2, 64, 32
+    Q, K, V = inputs.batch_streams("iid", 2, T, 1, H, 1, d, dtype="f32")
+    kv = binding.TreeKV(budget, H, d, kv_heads=H, dtype="f32", n_sink=0, n_recent=0)
+    Qd, Kd, Vd = (ph.to_device(x, "f32") for x in (Q, K, V))
+    a = ph.gpu_decode_run(kv, Qd, Kd, Vd, [T - 1])
+    kv.reset()
+    b = ph.gpu_decode_run(kv, Qd, Kd, Vd, [T - 1])
+    np.testing.assert_array_equal(a["out"], b["out"])          # same launches, same order: deterministic
+    np.testing.assert_array_equal(a["evicted"], b["evicted"])
+    np.testing.assert_array_equal(a["retained"][T - 1], b["retained"][T - 1])
+
+
+def test_llama7b_shaped_layer_sampled(binding, oracle):
+    """32 heads x 128, bf16, budget 1024 (4 + 512 + 508), batch 1: the GPU runs all 32 heads for
+    4096 steps; the oracle audits 6 heads over the full length."""
+    T = 4096
+    Q, K, V = inputs.batch_streams("lowrank", 0, T, 1, 32, 1, 128, dtype="bf16")
+    kv = binding.TreeKV(1024, 32, 128)
+    sample = [1023, 1024, 2047, 3000, T - 1]
+    gpu = ph.gpu_decode_run(kv, ph.to_device(Q, "bf16"), ph.to_device(K, "bf16"), ph.to_device(V, "bf16"), sample)
+    units = [(0, h) for h in (0, 5, 13, 21, 30, 31)]
+    rep = ph.compare_decode(oracle, kv, Q, K, V, gpu, units=units, dtype="bf16")
+    rep["score_err"] = ph.compare_scores(kv, rep["results"], "bf16")
+    print(f"  flagged={rep['flagged']}/{rep['decisions']} max_err={rep['max_err']:.2e} score_err={rep['score_err']:.2e}")
+    assert rep["flagged"] <= rep["decisions"] // 500 + 2
+    # properties that hold for every head at any size
+    ret = gpu["retained"][T - 1][0]
+    assert np.all(np.diff(ret, axis=-1) > 0)
+    assert np.all(ret[:, :4] == np.arange(4)) and np.all(ret[:, -508:] == np.arange(T - 508, T))
