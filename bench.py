@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the TreeKV decode hot path on one MI355X.
+
+Workload (the configuration the headline metric is quoted on): 32 layers x 32 heads x 128 dim,
+bf16, cache budget 2048 (4 sink + 1024 tree + 1020 recent slots), batch 8.  One "step" decodes
+one token for all 8 sequences through all 32 layers: 32 launches of the decode kernel, one per
+layer (a model runs its layers one after the other), each doing attend -> score update ->
+tree eviction -> slot reuse -> retained positions for 256 (batch, head) units.  The caches are
+full before the timed region starts (filled with chunked prefill when the library has it,
+else with decode steps); inputs are synthetic and already resident in HBM.
+
+Prints ONE JSON line.  `roofline` prices the decode kernel's algorithmic bytes per launch
+against the 8 TB/s HBM peak; `cpu_baseline` times the fp64 CPU oracle on a bounded sample of
+the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+LAYERS, BATCH, HEADS, KV_HEADS, HEAD_DIM, BUDGET = 32, 8, 32, 32, 128, 2048
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per decode launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/),
+# scaled by a copy kernel of known size.  None until measured for the current kernel.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def algorithmic_bytes_per_unit(c=BUDGET, d=HEAD_DIM, G=HEADS // KV_HEADS, esz=2):
+    """Bytes one (batch, KV head) unit must move in one decode step with a full cache."""
+    kv = 2 * (c + 1) * d * esz          # K and V rows, read once
+    s = 2 * (c + 1) * 4                 # scores read + written
+    pos = (c + 1) * 4                   # positions read for the retained list
+    ret = c * 4                         # retained positions written
+    qo = G * d * esz + G * d * 4        # q read, o written (fp32)
+    new = 2 * d * esz                   # the new k, v rows written into the cache
+    return kv + s + pos + ret + qo + new
+
+
+def cpu_baseline(seconds_budget=20.0):
+    """The oracle as it stands, on a bounded sample: S streams (one per thread), each filled to the
+    2048-slot budget (untimed) and then timed for a few hundred decode steps."""
+    import numpy as np
+
+    from oracle import treekv_oracle as orc
+    from paper_2501_04987_amd import inputs
+
+    orc.build()
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16") or 16), 16)
+    n_timed = 384
+    T = BUDGET + n_timed
+    cfg = dict(budget=BUDGET, G=1, d=HEAD_DIM, n_sink=4, n_recent=BUDGET - BUDGET // 2 - 4)
+
+    def job(i):
+        q, k, v = inputs.stream_lowrank(1 + i % 8, T, 1, HEAD_DIM, layer=i // 256, batch=i % 8, kv_head=i % 32)
+        q, k, v = (np.ascontiguousarray(x, np.float64) for x in (q, k, v))
+        s = orc.OracleStream(cfg["budget"], 1, HEAD_DIM, n_sink=cfg["n_sink"], n_recent=cfg["n_recent"])
+        lib, dp, lp = s._lib, orc._dptr, orc._lptr
+        ev = np.empty(T, np.int64)
+        lib.tko_decode_stream(s._h, dp(q), dp(k), dp(v), BUDGET, None, None, 0.0, lp(ev), None, None)
+        t0 = time.perf_counter()
+        lib.tko_decode_stream(s._h, dp(q[BUDGET:]), dp(k[BUDGET:]), dp(v[BUDGET:]), n_timed, None, None, 0.0,
+                              lp(ev[BUDGET:]), None, None)
+        return time.perf_counter() - t0
+
+    t0 = time.perf_counter()
+    times = orc.run_many(job, list(range(cores)), workers=cores)
+    wall = time.perf_counter() - t0
+    unit_steps_per_s = sum(n_timed / t for t in times)          # all cores busy, one stream each
+    per_step_units = LAYERS * BATCH * KV_HEADS
+    return {
+        "value": unit_steps_per_s / per_step_units, "unit": "steps/s", "cores": cores, "kind": "oracle",
+        "sample": (f"{cores} of the {per_step_units} (layer, batch, head) streams, one per thread, each filled to "
+                   f"{BUDGET} slots then timed for {n_timed} decode steps; scaled to {per_step_units} streams per step"),
+        "unit_steps_per_s": unit_steps_per_s, "wall_s": wall,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kv-splits", type=int, default=0)
+    ap.add_argument("--graph", type=int, default=1, help="replay the timed steps from HIP graphs (1) or launch them (0)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (every TreeKV stream is independent; there is no "
+              "multi-GPU path to time); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2501_04987_amd import binding, inputs
+
+    lib = binding.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K_steps, W = args.steps, args.warmup
+
+    layers = [binding.TreeKV(BUDGET, HEADS, HEAD_DIM, kv_heads=KV_HEADS, batch=BATCH, dtype="bf16",
+                             n_sink=4, n_recent=BUDGET - BUDGET // 2 - 4, kv_splits=args.kv_splits)
+              for _ in range(LAYERS)]
+    cfg = layers[0].cfg
+
+    def gen(seed, T):
+        """[T, LAYERS, B, H, d] inputs; every (layer, head) has its own low-rank basis."""
+        q, k, v = inputs.device_lowrank(seed, T, BATCH, LAYERS * KV_HEADS, HEADS // KV_HEADS, HEAD_DIM, device=dev)
+        f = lambda x, h: x.view(T, BATCH, LAYERS, h, HEAD_DIM).permute(0, 2, 1, 3, 4).contiguous()
+        return f(q, HEADS), f(k, KV_HEADS), f(v, KV_HEADS)
+
+    out = torch.empty(LAYERS, BATCH, HEADS, HEAD_DIM, dtype=torch.float32, device=dev)
+    ret = torch.empty(LAYERS, BATCH, KV_HEADS, BUDGET, dtype=torch.int32, device=dev)
+    nret = torch.empty(LAYERS, BATCH, KV_HEADS, dtype=torch.int32, device=dev)
+    ev = torch.empty(LAYERS, BATCH, KV_HEADS, dtype=torch.int32, device=dev)
+
+    def step(q, k, v):
+        for l, kv in enumerate(layers):
+            kv.decode_step(q[l], k[l], v[l], out[l], ret[l], nret[l], ev[l])
+
+    # ---- fill the caches to the budget (untimed) ----
+    filled = 0
+    seed = 100
+    has_prefill = True
+    chunk = 512
+    while filled < BUDGET:
+        if has_prefill:
+            q, k, v = gen(seed, chunk)                         # [chunk, L, B, H, d]
+            qc = q.permute(1, 2, 0, 3, 4).contiguous()         # [L, B, chunk, H, d]
+            kc = k.permute(1, 2, 0, 3, 4).contiguous()
+            vc = v.permute(1, 2, 0, 3, 4).contiguous()
+            o = torch.empty(BATCH, chunk, HEADS, HEAD_DIM, dtype=torch.float32, device=dev)
+            try:
+                for l, kv in enumerate(layers):
+                    kv.prefill_chunk(qc[l], kc[l], vc[l], chunk, o, ret[l], nret[l], None)
+                filled += chunk
+                seed += 1
+                del q, k, v, qc, kc, vc, o
+                continue
+            except binding.TreeKVError as e:
+                if e.status != binding.TREEKV_EUNSUPPORTED or filled:
+                    raise
+                has_prefill = False
+        blk = 32
+        q, k, v = gen(seed, blk)
+        for t in range(blk):
+            step(q[t], k[t], v[t])
+        filled += blk
+        seed += 1
+    torch.cuda.synchronize()
+    assert int(nret.min()) == BUDGET, "caches are not full"
+
+    # ---- timed region: W warmup steps, then exactly K steps ----
+    q, k, v = gen(7, W + K_steps)
+    for t in range(W):
+        step(q[t], k[t], v[t])
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    graphs = None
+    if args.graph:
+        # one graph per step (inputs differ per step); capture is outside the timed region
+        graphs = []
+        for t in range(W, W + K_steps):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(q[t], k[t], v[t])
+            graphs.append(g)
+        torch.cuda.synchronize()
+        stream = torch.cuda.current_stream()
+    torch.cuda.synchronize()
+    t_host0 = time.perf_counter()
+    e0.record(stream)
+    if graphs is not None:
+        for g in graphs:
+            g.replay()
+    else:
+        for t in range(W, W + K_steps):
+            step(q[t], k[t], v[t])
+    e1.record(stream)
+    torch.cuda.synchronize()
+    host_s = time.perf_counter() - t_host0
+    dev_ms = e0.elapsed_time(e1)
+    total_s = max(host_s, dev_ms * 1e-3)
+    assert int(nret.min()) == BUDGET and int(ev.min()) >= 0, "every unit must evict once per step"
+
+    ms_per_step = total_s * 1e3 / K_steps
+    steps_per_s = K_steps / total_s
+    launches = K_steps * LAYERS
+    launch_us = dev_ms * 1e3 / launches
+    bytes_per_launch = algorithmic_bytes_per_unit() * BATCH * KV_HEADS
+    achieved = bytes_per_launch / (launch_us * 1e-6) / 1e9
+    res = {
+        "metric": "decode steps/s (one token for 8 sequences through 32 layers; 32h x 128d, cache 2048, bf16)",
+        "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": K_steps, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 storage, fp32 arithmetic", "data": "synthetic",
+        "config": {"workload": "configs[2]: 32 layers x 32 heads x 128 dim, bf16, budget 2048 "
+                               "(4 sink + 1024 tree + 1020 recent), batch 8, caches full",
+                   "layers": LAYERS, "batch": BATCH, "heads": HEADS, "kv_heads": KV_HEADS, "head_dim": HEAD_DIM,
+                   "budget": BUDGET, "kv_splits": int(cfg.kv_splits), "launch": "hip graph" if graphs else "stream",
+                   "filled_by": "prefill chunks of 512" if has_prefill else "decode steps"},
+        "tokens_per_s": steps_per_s * BATCH,
+        "layer_steps_per_s": steps_per_s * LAYERS,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "kernel": "decode_kernel<bf16,128,1>", "bytes_per_launch": bytes_per_launch,
+                     "launch_us": launch_us,
+                     "note": "launch_us = HIP-event time of the timed region / number of decode launches "
+                             "(gaps between launches included)"},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
