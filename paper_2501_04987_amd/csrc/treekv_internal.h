@@ -23,24 +23,26 @@ enum MetaField : int {
 // Physical layout.  A unit owns cap = budget + 1 cache rows ("slots").  A token
 // stays in the slot it was written to until it is evicted; the evicted slot is
 // the next token's slot.  Attention ignores order, so rows never move.
-// Logical (position) order is kept in three small index arrays:
-//   sinks   : slots 0 .. n_sink-1 (the first tokens, written while filling)
-//   tree    : E[2m].  During a round of m evictions, E[0..m) is the tree region
-//             at the round's start and E[m+j] the token that entered the tree
-//             region at the round's j-th step.  Eviction j compares E[2j] and
-//             E[2j+1] and stores the survivor in E[j].  After eviction j the
-//             region reads E[0..j] then E[2j+2 .. m+j].
-//   recent  : ring R[n_recent] of slots, oldest at META_RHEAD.
+// Logical (position) order is kept in small index arrays:
+//   sinks   : slots 0 .. n_sink-1 hold positions 0 .. n_sink-1 (written while filling)
+//   tree    : E[2m] (slots) and PE[2m] (the positions they hold).  During a round of m
+//             evictions, E[0..m) is the tree region at the round's start and E[m+j] the
+//             token that entered the tree region at the round's j-th step.  Eviction j
+//             compares E[2j] and E[2j+1] and stores the survivor in E[j].  After
+//             eviction j the region reads E[0..j] then E[2j+2 .. m+j].
+//   recent  : ring R[n_recent] of slots, oldest at META_RHEAD; it always holds the last
+//             n_recent positions, so their positions need no array.
 struct Params {
   int budget, cap, n_sink, n_recent, m;
   int B, H, Hkv, G, D, U;   // U = B * Hkv units
   int dtype, flags, nsplit, max_chunk;
+  int rows_per_split;       // decode: slots one workgroup streams (a multiple of 64)
   float scale_log2e;        // softmax_scale * log2(e): probabilities are exp2 of scaled logits
   void* K;                  // [U][cap][D] storage dtype
   void* V;                  // [U][cap][D]
   float* S;                 // [U][cap] accumulated attention weight per slot
-  int* pos;                 // [U][cap] stream position held by the slot
-  int* E;                   // [U][2m]
+  int* E;                   // [U][2m] slots of the tree region
+  int* PE;                  // [U][2m] positions of the tree region
   int* R;                   // [U][max(n_recent,1)]
   int* meta;                // [U][META_STRIDE]
   float* logits;            // [U][G][cap]   decode scratch: scaled logits (log2 domain)
@@ -96,14 +98,15 @@ __device__ inline void st_agent(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Logical index i (0 <= i < n) -> physical slot, for a unit whose cache is full
-// (n == budget) and whose last eviction was the j_done-th of its round
-// (j_done = number of evictions already done in the round, 1..m; m means the round
-// just ended, which reads the same as 0 done in the next round).
+// Tree-region index k (0 <= k < m) -> index into E / PE, after j_done evictions of the
+// current round (0 <= j_done <= m; a round that just ended reads the same either way).
+__device__ inline int tree_index(int k, int j_done) { return k < j_done ? k : k + j_done; }
+
+// Logical index i (0 <= i < budget) -> physical slot, for a unit whose cache is full.
 __device__ inline int logical_to_slot(const Params& p, const int* E, const int* R, int rhead, int j_done, int i) {
   if (i < p.n_sink) return i;
   int k = i - p.n_sink;
-  if (k < p.m) return (k < j_done) ? E[k] : E[k + j_done];
+  if (k < p.m) return E[tree_index(k, j_done)];
   k -= p.m;
   int r = rhead + k;
   if (r >= p.n_recent) r -= p.n_recent;
