@@ -2,7 +2,7 @@
 // HBM-bound: per unit it must read every K and V row once (Section 3.1).
 //
 // Two launch shapes share the streaming code and the epilogue:
-//   FUSED  one kernel, grid = U workgroups.  One workgroup owns a unit end to end; logits stay
+//   FUSED  one kernel, grid = U workgroups of 512 threads (measured best of 256..1024).  One workgroup owns a unit end to end; logits stay
 //          in LDS, scores and tree positions are prefetched into registers before the streaming
 //          starts, so the epilogue (score update, eviction, retained list) waits for no global
 //          load.  Used when U alone fills the chip.
@@ -28,7 +28,7 @@ namespace {
 
 // Tuning constants (overridable at compile time for sweeps).
 #ifndef TKV_FUSED_THREADS
-#define TKV_FUSED_THREADS 1024
+#define TKV_FUSED_THREADS 512
 #endif
 #ifndef TKV_KU
 #define TKV_KU 2
@@ -115,7 +115,8 @@ struct Step {
   int scope_l, scope_r, pos_l, pos_r;   // the eviction scope {idx, idx+1}: slots and positions
 };
 
-__device__ inline Step load_step(const Params& p, const int* meta, const int* Eu, const int* PEu, const int* Ru) {
+// The five bookkeeping words: everything the streaming and the retained list need.
+__device__ inline Step load_meta(const Params& p, const int* meta) {
   Step s;
   s.n1 = meta[META_N] + 1;
   s.fslot = meta[META_FREE];
@@ -129,14 +130,18 @@ __device__ inline Step load_step(const Params& p, const int* meta, const int* Eu
   s.newcomer_pos = s.t - p.n_recent;     // the recent window holds the last n_recent positions
   s.scope_l = s.scope_r = -1;
   s.pos_l = s.pos_r = 0;
-  if (s.evict) {
-    if (p.n_recent > 0) s.newcomer = Ru[s.rhead];   // the window's oldest member moves into the tree region
-    s.scope_l = Eu[2 * s.j0];
-    s.pos_l = PEu[2 * s.j0];
-    if (2 * s.j0 + 1 == p.m + s.j0) { s.scope_r = s.newcomer; s.pos_r = s.newcomer_pos; }
-    else { s.scope_r = Eu[2 * s.j0 + 1]; s.pos_r = PEu[2 * s.j0 + 1]; }
-  }
   return s;
+}
+
+// The eviction scope: loads that depend on the bookkeeping words and are first needed in the
+// epilogue, so they are requested while the rows stream.
+__device__ inline void load_scope(const Params& p, Step& s, const int* Eu, const int* PEu, const int* Ru) {
+  if (!s.evict) return;
+  if (p.n_recent > 0) s.newcomer = Ru[s.rhead];     // the window's oldest member moves into the tree region
+  s.scope_l = Eu[2 * s.j0];
+  s.pos_l = PEu[2 * s.j0];
+  if (2 * s.j0 + 1 == p.m + s.j0) { s.scope_r = s.newcomer; s.pos_r = s.newcomer_pos; }
+  else { s.scope_r = Eu[2 * s.j0 + 1]; s.pos_r = PEu[2 * s.j0 + 1]; }
 }
 
 // Position of logical index i once the step is over.  The two tree entries the step itself
@@ -184,7 +189,7 @@ struct Stream {
     const T* Ku = (const T*)p.K + (size_t)unit * p.cap * D;
     const T* Vu = (const T*)p.V + (size_t)unit * p.cap * D;
 
-    // first tile, requested before the bookkeeping words are known (rows clamped to the allocation)
+    // first two tiles, requested before the bookkeeping words are known (rows clamped to the allocation)
     uint4 ka[KU], va[KU], kb[KU], vb[KU];
     int base = begin_spec + wave * TILE;
 #pragma unroll
@@ -193,13 +198,18 @@ struct Stream {
       ka[u] = *reinterpret_cast<const uint4*>(Ku + (size_t)row * D + li * EPL);
       va[u] = *reinterpret_cast<const uint4*>(Vu + (size_t)row * D + li * EPL);
     }
+#pragma unroll
+    for (int u = 0; u < KU; ++u) {
+      const int row = min(base + STEP + u * RPL + ri, p.cap - 1);
+      kb[u] = *reinterpret_cast<const uint4*>(Ku + (size_t)row * D + li * EPL);
+      vb[u] = *reinterpret_cast<const uint4*>(Vu + (size_t)row * D + li * EPL);
+    }
     uint4 qr[G];
 #pragma unroll
     for (int g = 0; g < G; ++g)
       qr[g] = *reinterpret_cast<const uint4*>(q_in + ((size_t)b * p.H + (size_t)kvh * G + g) * D + li * EPL);
 
-    st = load_step(p, meta, p.E + (size_t)unit * 2 * p.m, p.PE + (size_t)unit * 2 * p.m,
-                   p.R + (size_t)unit * max(p.n_recent, 1));
+    st = load_meta(p, meta);
     begin = begin_spec;
     end = fused ? st.n1 : min(st.n1, begin + p.rows_per_split);
     const int fslot = st.fslot;
@@ -217,16 +227,20 @@ struct Stream {
         vd[u] = *reinterpret_cast<const uint4*>(vs + li * EPL);
       }
     };
-    // the speculative tile read the free slot's stale row if it covers it: fetch the real one
-    if (fslot >= base && fslot < base + TILE) {
+    // a speculative tile read the free slot's stale row if it covers it: fetch the real one
+    auto patch_new = [&](uint4 (&kd)[KU], uint4 (&vd)[KU], int tb) {
+      if (fslot >= tb && fslot < tb + TILE) {
 #pragma unroll
-      for (int u = 0; u < KU; ++u) {
-        if (base + u * RPL + ri == fslot) {
-          ka[u] = *reinterpret_cast<const uint4*>(knew + li * EPL);
-          va[u] = *reinterpret_cast<const uint4*>(vnew + li * EPL);
+        for (int u = 0; u < KU; ++u) {
+          if (tb + u * RPL + ri == fslot) {
+            kd[u] = *reinterpret_cast<const uint4*>(knew + li * EPL);
+            vd[u] = *reinterpret_cast<const uint4*>(vnew + li * EPL);
+          }
         }
       }
-    }
+    };
+    patch_new(ka, va, base);
+    patch_new(kb, vb, base + STEP);
 
     float m_run[G], l_run[G], acc[G][EPL];
 #pragma unroll
@@ -281,7 +295,7 @@ struct Stream {
 
     int iter = 0;
     for (; base < end; base += 2 * STEP, ++iter) {
-      if (base + STEP < end) load_tile(kb, vb, base + STEP);
+      if (iter > 0 && base + STEP < end) load_tile(kb, vb, base + STEP);
       tile(ka, va, base);
       if (base + 2 * STEP < end) load_tile(ka, va, base + 2 * STEP);
       if (base + STEP < end) tile(kb, vb, base + STEP);
@@ -462,6 +476,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
             }
           },
           [&]() {
+            load_scope(p, st, p.E + (size_t)unit * 2 * p.m, PEu, p.R + (size_t)unit * max(p.n_recent, 1));
             int32_t* ret = retained + (size_t)unit * p.budget;
 #pragma unroll
             for (int x = 0; x < EP; ++x) {
@@ -538,7 +553,8 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, c
   const int unit = blockIdx.x, tid = threadIdx.x;
   int* meta = p.meta + (size_t)unit * META_STRIDE;
   const int* PEu = p.PE + (size_t)unit * 2 * p.m;
-  const Step st = load_step(p, meta, p.E + (size_t)unit * 2 * p.m, PEu, p.R + (size_t)unit * max(p.n_recent, 1));
+  Step st = load_meta(p, meta);
+  load_scope(p, st, p.E + (size_t)unit * 2 * p.m, PEu, p.R + (size_t)unit * max(p.n_recent, 1));
   const float* parts = p.partial + (size_t)unit * p.nsplit * G * (D + 2);
   float M[G], invL[G];
 #pragma unroll
