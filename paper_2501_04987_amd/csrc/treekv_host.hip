@@ -42,12 +42,10 @@ size_t carve(Params& p, char* base) {
   p.meta = (int*)take(U * META_STRIDE * 4);
   p.logits = (float*)take(U * p.G * cap * 4);
   p.partial = (float*)take(U * p.nsplit * p.G * (size_t)(p.D + 2) * 4);
-  p.counter = (unsigned*)take(U * 4);
-  p.pf_colsum = (float*)take(U * (size_t)p.pf_qtiles * ext * 4);
   p.pf_rowstat = (float*)take(U * p.G * (size_t)p.max_chunk * 2 * 4);
-  p.pf_sbar = (float*)take(U * ext * 4);
   p.pf_snew = (float*)take(U * (size_t)p.max_chunk * 4);
   p.pf_flag = (int*)take(U * ext * 4);
+  p.pf_list = (int*)take(U * ext * 4);
   return off;
 }
 
@@ -69,7 +67,6 @@ __global__ void reset_kernel(Params p) {
   uint4* Vz = reinterpret_cast<uint4*>(p.V) + (size_t)unit * vecs;
   for (size_t i = threadIdx.x; i < vecs; i += blockDim.x) Kz[i] = Vz[i] = make_uint4(0, 0, 0, 0);
   if (threadIdx.x < META_STRIDE) meta[threadIdx.x] = 0;
-  if (threadIdx.x == 0) p.counter[unit] = 0;
 }
 
 __global__ void scores_kernel(Params p, float* __restrict__ scores) {
@@ -194,7 +191,6 @@ int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg_in) {
   p.dtype = c.dtype; p.flags = c.flags; p.nsplit = c.kv_splits; p.max_chunk = c.max_chunk;
   p.scale_log2e = c.softmax_scale * 1.4426950408889634f;
   p.rows_per_split = ((p.cap + p.nsplit - 1) / p.nsplit + 63) / 64 * 64;
-  p.pf_qtiles = (c.max_chunk + 63) / 64;
   ctx->ws_bytes = tkv::carve(p, nullptr);
   *out = ctx;
   return TREEKV_OK;

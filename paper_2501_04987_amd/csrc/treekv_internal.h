@@ -47,14 +47,11 @@ struct Params {
   int* meta;                // [U][META_STRIDE]
   float* logits;            // [U][G][cap]   decode scratch: scaled logits (log2 domain)
   float* partial;           // [U][nsplit][G][D+2] decode scratch: split-KV partial (acc, max, sum)
-  unsigned* counter;        // [U] decode scratch: split arrival tickets
   // prefill scratch
-  float* pf_colsum;         // [U][pf_qtiles][cap + max_chunk] per-query-tile column sums
-  float* pf_rowstat;        // [U][G][max_chunk][2] row max (log2 domain) and 1/row sum
-  float* pf_sbar;           // [U][cap + max_chunk] frozen averaged scores by token id
+  float* pf_rowstat;        // [U][G][max_chunk][2] final row max (log2 domain) and 1 / row sum
   float* pf_snew;           // [U][max_chunk] accumulated S of the chunk's tokens
-  int* pf_flag;             // [U][cap + max_chunk] liveness / slot assignment scratch
-  int pf_qtiles;
+  int* pf_flag;             // [U][cap + max_chunk] freed slots / dead chunk tokens, then destinations
+  int* pf_list;             // [U][cap + max_chunk] free slots in ascending order
 };
 
 int launch_reset(const Params& p, hipStream_t s);
@@ -89,14 +86,6 @@ template <> struct Storage<float> {
 };
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// Loads and stores that stay coherent across the per-XCD L2 caches inside one kernel.
-__device__ inline float ld_agent(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline void st_agent(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // Tree-region index k (0 <= k < m) -> index into E / PE, after j_done evictions of the
 // current round (0 <= j_done <= m; a round that just ended reads the same either way).

@@ -1,9 +1,538 @@
-// Chunked prefill of TreeKV for gfx950 (placeholder until the MFMA kernels land).
+// Chunked prefill of TreeKV for gfx950.
+//
+// A chunk of L tokens attends the cache as it was before the chunk plus the chunk's own tokens
+// up to and including itself; every row's probabilities are added to the scores; the averaged
+// scores are then frozen and Algorithm 1's append / compare / evict / advance (lines 4-5, 9-17)
+// is replayed for the L tokens.  L = 1 gives the decode step.
+//
+// Four launches per chunk:
+//   attend   grid (row tiles, G, U).  Flash-style pass over all visible columns with MFMA:
+//            S^T = K Q^T (16x16x32 bf16), online softmax in registers, O^T += V^T P^T with P
+//            split into two bf16 halves (hi + lo) so that rounding P costs 2^-16, not 2^-9.
+//            Writes O and the final row statistics (max, 1/sum).
+//   colsum   grid (column tiles, U).  Recomputes S = Q K^T for one 64-column tile against every
+//            row that sees it, normalises with the final row statistics and sums down the rows:
+//            a workgroup owns its columns, so the sums need no atomics and have a fixed order.
+//            Cache columns add to S in place (Algorithm 1, line 8), chunk columns get their S.
+//   replay   grid U.  Algorithm 1's eviction for the chunk's tokens with frozen scores.  Inside one
+//            sweep of idx over the tree region the scopes are disjoint pairs, so a sweep is one
+//            parallel pass; sweeps run one after the other.  Then surviving chunk tokens are
+//            matched with freed slots (prefix sums), the order arrays are rewritten and the
+//            retained positions emitted.
+//   scatter  grid (L, U).  Copies the surviving chunk rows into their slots.
+//
+// Token ids during the replay: a slot number (< cap) for a cached token, cap + i for chunk
+// token i that has no slot yet.
+
 #include "treekv_internal.h"
 
 namespace tkv {
-int launch_prefill(const Params&, const void*, const void*, const void*, int, float*, int32_t*, int32_t*, int32_t*,
-                   hipStream_t) {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+constexpr int PF_THREADS = 256;
+constexpr int ROW_TILE = 64;     // query rows per attend workgroup (16 per wave)
+constexpr int COL_TILE = 64;     // columns per step
+constexpr float NEG_BIG = -1.0e30f;
+
+__device__ inline f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+// float -> bf16 bits, round to nearest even (finite inputs)
+__device__ inline unsigned bf16_rn(float x) {
+  unsigned u = __float_as_uint(x);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+struct ChunkInfo {
+  int n;        // tokens cached before the chunk
+  int fslot;    // the free slot (a hole among slots [0, n] once the cache is full)
+  int t0;       // position of the chunk's first token
+};
+
+__device__ inline ChunkInfo load_chunk_info(const int* meta) {
+  ChunkInfo c;
+  c.n = meta[META_N];
+  c.fslot = meta[META_FREE];
+  c.t0 = meta[META_T];
+  return c;
+}
+
+// ---------------------------------------------------------------------------------------------
+// attend
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(PF_THREADS) void prefill_attend_kernel(Params p, const uint16_t* __restrict__ Q,
+                                                                    const uint16_t* __restrict__ Kc,
+                                                                    const uint16_t* __restrict__ Vc, int L,
+                                                                    float* __restrict__ out) {
+  constexpr int KS = D / 32;          // k-steps of the q.k contraction
+  constexpr int DB = D / 16;          // 16-wide blocks of the head dimension
+  constexpr int KSTRIDE = D + 8;      // LDS row strides in bf16 elements (padded against bank conflicts)
+  constexpr int VSTRIDE = COL_TILE + 8;
+  __shared__ __attribute__((aligned(16))) uint16_t sK[COL_TILE * KSTRIDE];
+  __shared__ __attribute__((aligned(16))) uint16_t sVt[D * VSTRIDE];
+
+  const int row_tile = blockIdx.x, g = blockIdx.y, unit = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, q4 = lane >> 4;
+  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+  const int h = kvh * p.G + g;
+  const ChunkInfo ci = load_chunk_info(p.meta + (size_t)unit * META_STRIDE);
+
+  const int row0 = row_tile * ROW_TILE + wave * 16;        // first chunk row of this wave
+  const int my_row = row0 + lr;                            // the query row this lane's results belong to
+  const int ld_row = min(my_row, L - 1);
+  const uint16_t* qp = Q + (((size_t)b * L + ld_row) * p.H + h) * D;
+  uint4 qa[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) qa[ks] = *reinterpret_cast<const uint4*>(qp + ks * 32 + q4 * 8);
+
+  const uint16_t* Ku = (const uint16_t*)p.K + (size_t)unit * p.cap * D;
+  const uint16_t* Vu = (const uint16_t*)p.V + (size_t)unit * p.cap * D;
+
+  float m_run = NEG_BIG, l_part = 0.f;
+  f32x4_t oacc[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d) oacc[d] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const int n_cache_cols = ci.n + 1;                                   // slots [0, n], the free one masked
+  const int cache_tiles = (n_cache_cols + COL_TILE - 1) / COL_TILE;
+  const int last_row = min(row_tile * ROW_TILE + ROW_TILE, L) - 1;     // last chunk row of the workgroup
+  const int chunk_tiles = last_row / COL_TILE + 1;                     // causal: columns <= last_row
+
+  for (int tile = 0; tile < cache_tiles + chunk_tiles; ++tile) {
+    const bool is_cache = tile < cache_tiles;
+    const int col0 = is_cache ? tile * COL_TILE : (tile - cache_tiles) * COL_TILE;
+    __syncthreads();                                                   // previous tile fully consumed
+    // stage K (row major) and V (transposed) of the tile in LDS
+    constexpr int CHUNKS = COL_TILE * D / 8;                           // 16-byte pieces per tile
+#pragma unroll
+    for (int x = 0; x < CHUNKS / PF_THREADS; ++x) {
+      const int c = tid + x * PF_THREADS;
+      const int r = c / (D / 8), part = c % (D / 8);
+      const uint16_t *ks, *vs;
+      if (is_cache) {
+        const int slot = min(col0 + r, p.cap - 1);
+        ks = Ku + (size_t)slot * D; vs = Vu + (size_t)slot * D;
+      } else {
+        const int jc = min(col0 + r, L - 1);
+        ks = Kc + (((size_t)b * L + jc) * p.Hkv + kvh) * D; vs = Vc + (((size_t)b * L + jc) * p.Hkv + kvh) * D;
+      }
+      const uint4 kv = *reinterpret_cast<const uint4*>(ks + part * 8);
+      const uint4 vv = *reinterpret_cast<const uint4*>(vs + part * 8);
+      *reinterpret_cast<uint4*>(&sK[r * KSTRIDE + part * 8]) = kv;
+      const unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sVt[(part * 8 + 2 * e) * VSTRIDE + r] = (uint16_t)(w[e] & 0xffffu);
+        sVt[(part * 8 + 2 * e + 1) * VSTRIDE + r] = (uint16_t)(w[e] >> 16);
+      }
+    }
+    __syncthreads();
+
+    // S^T block bk: rows = columns col0 + bk*16 + q4*4 + i, column = this lane's query row
+    float s[4][4];
+#pragma unroll
+    for (int bk = 0; bk < 4; ++bk) {
+      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const uint4 a = *reinterpret_cast<const uint4*>(&sK[(bk * 16 + lr) * KSTRIDE + ks * 32 + q4 * 8]);
+        acc = mfma16(a, qa[ks], acc);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int col = col0 + bk * 16 + q4 * 4 + i;
+        const bool vis = is_cache ? (col <= ci.n && col != ci.fslot) : (col <= my_row);
+        s[bk][i] = vis ? acc[i] * p.scale_log2e : NEG_BIG;
+      }
+    }
+    float mx = m_run;
+#pragma unroll
+    for (int bk = 0; bk < 4; ++bk)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[bk][i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float corr = fast_exp2(m_run - mx);
+    m_run = mx;
+    l_part *= corr;
+#pragma unroll
+    for (int d = 0; d < DB; ++d) oacc[d] *= corr;
+    uint4 phi[2], plo[2];                     // P^T operands: k = the 8 columns {bk even: i} u {bk odd: i}
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      unsigned hi[8], lo[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float sv = s[2 * half + (e >> 2)][e & 3];
+        const float pr = sv > 0.5f * NEG_BIG ? fast_exp2(sv - mx) : 0.f;
+        l_part += pr;
+        hi[e] = bf16_rn(pr);
+        lo[e] = bf16_rn(pr - __uint_as_float(hi[e] << 16));
+      }
+      phi[half] = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+      plo[half] = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+    }
+    // O^T += V^T P^T : A = V^T[d][the same 8 columns], B = P^T
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+      for (int d = 0; d < DB; ++d) {
+        const uint16_t* vrow = &sVt[(d * 16 + lr) * VSTRIDE + half * 32 + q4 * 4];
+        const uint2 v0 = *reinterpret_cast<const uint2*>(vrow);
+        const uint2 v1 = *reinterpret_cast<const uint2*>(vrow + 16);
+        const uint4 a = make_uint4(v0.x, v0.y, v1.x, v1.y);
+        oacc[d] = mfma16(a, phi[half], oacc[d]);
+        oacc[d] = mfma16(a, plo[half], oacc[d]);
+      }
+    }
+  }
+
+  float l_row = l_part + __shfl_xor(l_part, 16, 64);
+  l_row += __shfl_xor(l_row, 32, 64);
+  const float inv = 1.0f / l_row;
+  if (my_row < L) {
+    float* op = out + (((size_t)b * L + my_row) * p.H + h) * D;
+#pragma unroll
+    for (int d = 0; d < DB; ++d) {
+      float4 o = make_float4(oacc[d][0] * inv, oacc[d][1] * inv, oacc[d][2] * inv, oacc[d][3] * inv);
+      *reinterpret_cast<float4*>(op + d * 16 + q4 * 4) = o;
+    }
+    if (q4 == 0) {
+      float* rs = p.pf_rowstat + (((size_t)unit * p.G + g) * p.max_chunk + my_row) * 2;
+      rs[0] = m_run; rs[1] = inv;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// colsum
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(PF_THREADS) void prefill_colsum_kernel(Params p, const uint16_t* __restrict__ Q,
+                                                                    const uint16_t* __restrict__ Kc, int L) {
+  constexpr int KS = D / 32;
+  __shared__ float sm_cs[PF_THREADS / 64][COL_TILE];
+
+  const int unit = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, q4 = lane >> 4;
+  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+  const ChunkInfo ci = load_chunk_info(p.meta + (size_t)unit * META_STRIDE);
+
+  const int max_cache_tiles = (p.cap + COL_TILE - 1) / COL_TILE;
+  const bool is_cache = (int)blockIdx.x < max_cache_tiles;
+  const int col0 = is_cache ? blockIdx.x * COL_TILE : ((int)blockIdx.x - max_cache_tiles) * COL_TILE;
+  if (is_cache ? col0 > ci.n : col0 >= L) return;          // nothing visible in this tile (uniform)
+
+  // the tile's K rows as B operands, held in registers for the whole kernel
+  uint4 kb[4][KS];
+#pragma unroll
+  for (int bk = 0; bk < 4; ++bk) {
+    const int col = col0 + bk * 16 + lr;
+    const uint16_t* ks = is_cache ? (const uint16_t*)p.K + ((size_t)unit * p.cap + min(col, p.cap - 1)) * D
+                                  : Kc + (((size_t)b * L + min(col, L - 1)) * p.Hkv + kvh) * D;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) kb[bk][kk] = *reinterpret_cast<const uint4*>(ks + kk * 32 + q4 * 8);
+  }
+  bool colvis[4];                                           // validity of this lane's column in each block
+#pragma unroll
+  for (int bk = 0; bk < 4; ++bk) {
+    const int col = col0 + bk * 16 + lr;
+    colvis[bk] = is_cache ? (col <= ci.n && col != ci.fslot) : (col < L);
+  }
+
+  float cs[4] = {0.f, 0.f, 0.f, 0.f};
+  const int first_rt = is_cache ? 0 : col0 / 16;            // causal: rows below the tile's first column see none of it
+  const int n_rt = (L + 15) / 16;
+  for (int g = 0; g < p.G; ++g) {
+    const int h = kvh * p.G + g;
+    const float* rs = p.pf_rowstat + ((size_t)unit * p.G + g) * p.max_chunk * 2;
+    for (int rt = first_rt + wave; rt < n_rt; rt += PF_THREADS / 64) {
+      const int arow = min(rt * 16 + lr, L - 1);            // A operand: this lane's query row
+      const uint16_t* qp = Q + (((size_t)b * L + arow) * p.H + h) * D;
+      uint4 qa[KS];
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) qa[kk] = *reinterpret_cast<const uint4*>(qp + kk * 32 + q4 * 8);
+      float mrow[4], irow[4];
+      int rowi[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {                         // results: rows rt*16 + q4*4 + i, column lr
+        rowi[i] = rt * 16 + q4 * 4 + i;
+        const int rr = min(rowi[i], L - 1);
+        mrow[i] = rs[rr * 2]; irow[i] = rs[rr * 2 + 1];
+      }
+#pragma unroll
+      for (int bk = 0; bk < 4; ++bk) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) acc = mfma16(qa[kk], kb[bk][kk], acc);
+        const int col = col0 + bk * 16 + lr;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool vis = colvis[bk] && rowi[i] < L && (is_cache || col <= rowi[i]);
+          cs[bk] += vis ? fast_exp2(acc[i] * p.scale_log2e - mrow[i]) * irow[i] : 0.f;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int bk = 0; bk < 4; ++bk) {
+    cs[bk] += __shfl_xor(cs[bk], 16, 64);
+    cs[bk] += __shfl_xor(cs[bk], 32, 64);
+    if (q4 == 0) sm_cs[wave][bk * 16 + lr] = cs[bk];
+  }
+  __syncthreads();
+  if (tid < COL_TILE) {
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < PF_THREADS / 64; ++w) tot += sm_cs[w][tid];
+    const int col = col0 + tid;
+    if (is_cache) {
+      if (col <= ci.n && col != ci.fslot) p.S[(size_t)unit * p.cap + col] += tot;
+    } else if (col < L) {
+      p.pf_snew[(size_t)unit * p.max_chunk + col] = tot;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// replay
+// ---------------------------------------------------------------------------------------------
+constexpr int RP_THREADS = 512;
+
+// Inclusive prefix sum of one int per thread over the workgroup (RP_THREADS threads).
+__device__ inline int block_scan_inclusive(int v, int* sm_wave) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(v, off, 64);
+    if (lane >= off) v += o;
+  }
+  __syncthreads();
+  if (lane == 63) sm_wave[wave] = v;
+  __syncthreads();
+  int add = 0;
+  for (int w = 0; w < wave; ++w) add += sm_wave[w];
+  return v + add;
+}
+
+__global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, int L, int32_t* __restrict__ retained,
+                                                                    int32_t* __restrict__ n_retained,
+                                                                    int32_t* __restrict__ evicted) {
+  __shared__ int sm_wave[RP_THREADS / 64];
+  __shared__ int sm_carry;
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  int* meta = p.meta + (size_t)unit * META_STRIDE;
+  float* Su = p.S + (size_t)unit * p.cap;
+  int* Eu = p.E + (size_t)unit * 2 * p.m;
+  int* PEu = p.PE + (size_t)unit * 2 * p.m;
+  int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
+  const float* snew = p.pf_snew + (size_t)unit * p.max_chunk;
+  int* flag = p.pf_flag + (size_t)unit * (p.cap + p.max_chunk);   // [0,cap): slot freed; [cap, cap+L): chunk token dead -> later its slot
+  int32_t* evu = evicted ? evicted + (size_t)unit * L : nullptr;
+
+  const int n0 = meta[META_N], f0 = meta[META_FREE], j0 = meta[META_J], rhead0 = meta[META_RHEAD], t0 = meta[META_T];
+  const int cap = p.cap, c = p.budget, m = p.m, r = p.n_recent;
+  const int F = min(L, c - n0);            // tokens that still fit without eviction (they take slots n0 ..)
+  const int Lev = L - F;                   // tokens that each trigger one eviction
+  const int t_end = t0 + L - 1;            // every count C is t_end - position + 1 once the chunk is in
+  const int tev = t0 + F;                  // position of the first evicting token
+
+  // ---- phase 0: flags, scores of the tokens that got slots while filling ----
+  for (int i = tid; i < cap + L; i += RP_THREADS) flag[i] = 0;
+  for (int i = tid; i < F; i += RP_THREADS) Su[n0 + i] = snew[i];
+  for (int i = tid; i < F; i += RP_THREADS) if (evu) evu[i] = -1;
+  __syncthreads();
+
+  int j_final = j0, rhead_final = rhead0, f_final = n0 + F, n_final = n0 + F;
+  if (Lev > 0) {
+    n_final = c;
+    const int fstart = F > 0 ? c : f0;     // the one free slot when the evictions start
+    auto score_of = [&](int id) -> float { return id < cap ? Su[id] : snew[id - cap]; };
+    auto chunk_id = [&](int i) -> int { return i < F ? n0 + i : cap + i; };   // id of chunk token i
+
+    // sweeps of idx over the tree region: eviction steps [e_a, e_b) share one sweep
+    int e_a = 0;
+    while (e_a < Lev) {
+      const int j_a = (j0 + e_a) % m;
+      const int e_b = min(Lev, e_a + (m - j_a));
+      const int cnt = e_b - e_a;
+      // (1) the tokens that enter the tree region at these steps
+      for (int x = tid; x < cnt; x += RP_THREADS) {
+        const int e = e_a + x;
+        const int pos_nc = tev + e - r;    // r == 0: the new token itself
+        int id;
+        if (pos_nc >= t0) id = chunk_id(pos_nc - t0);
+        else id = Ru[(rhead0 + e) % r];    // still the ring's entry from before the chunk (e < r here)
+        Eu[m + j_a + x] = id;
+        PEu[m + j_a + x] = pos_nc;
+      }
+      __syncthreads();
+      // (2) all scopes of the sweep are disjoint pairs: decide them in parallel, then write
+      for (int x0 = 0; x0 < cnt; x0 += RP_THREADS) {
+        const int x = x0 + tid;
+        int surv_id = 0, surv_pos = 0, lose_id = 0, lose_pos = 0;
+        if (x < cnt) {
+          const int j = j_a + x;
+          const int idl = Eu[2 * j], idr = Eu[2 * j + 1];
+          const int pl = PEu[2 * j], pr = PEu[2 * j + 1];
+          const float bl = score_of(idl) / (float)(t_end - pl + 1);
+          const float br = score_of(idr) / (float)(t_end - pr + 1);
+          const bool drop_right = (p.flags & TREEKV_KEEP_LEFT) || (bl > br);
+          surv_id = drop_right ? idl : idr; surv_pos = drop_right ? pl : pr;
+          lose_id = drop_right ? idr : idl; lose_pos = drop_right ? pr : pl;
+        }
+        __syncthreads();
+        if (x < cnt) {
+          const int j = j_a + x;
+          Eu[j] = surv_id; PEu[j] = surv_pos;
+          flag[lose_id] = 1;               // a slot that is free now, or a chunk token that is gone
+          if (evu) evu[F + e_a + x] = lose_pos;
+        }
+        __syncthreads();
+      }
+      e_a = e_b;
+    }
+    j_final = (j0 + Lev) % m;
+
+    // ---- the recent window: the last r chunk tokens (or fewer) take over ring entries ----
+    if (r > 0) {
+      for (int x = tid; x < r; x += RP_THREADS) {
+        // ring index (rhead0 + e) % r is written by steps e = x, x + r, ...; the last one below Lev stays
+        if (x < Lev) {
+          const int e_last = x + ((Lev - 1 - x) / r) * r;
+          Ru[(rhead0 + x) % r] = chunk_id(F + e_last);
+        }
+      }
+      rhead_final = (rhead0 + Lev) % r;
+    }
+    __syncthreads();
+
+    // ---- match surviving slot-less chunk tokens with free slots ----
+    if (tid == 0) flag[fstart] = 1;
+    __syncthreads();
+    // rank of every free slot among the free slots (ascending slot number)
+    int* free_list = p.pf_list + (size_t)unit * (p.cap + p.max_chunk);
+    int carry = 0;
+    for (int s0 = 0; s0 < cap; s0 += RP_THREADS) {
+      const int s = s0 + tid;
+      const int isf = s < cap ? flag[s] : 0;
+      const int inc = block_scan_inclusive(isf, sm_wave) + carry;
+      if (isf) free_list[inc - 1] = s;       // the free slots in ascending order
+      if (tid == RP_THREADS - 1) sm_carry = inc;
+      __syncthreads();
+      carry = sm_carry;
+      __syncthreads();
+    }
+    const int n_free = carry;
+    // rank of every surviving slot-less chunk token (ascending chunk index)
+    carry = 0;
+    for (int i0 = F; i0 < L; i0 += RP_THREADS) {
+      const int i = i0 + tid;
+      const int alive = (i < L) ? (flag[cap + i] == 0) : 0;
+      const int inc = block_scan_inclusive(alive, sm_wave) + carry;
+      if (i < L) flag[cap + i] = alive ? free_list[inc - 1] : -1;   // now: its slot, or -1
+      if (tid == RP_THREADS - 1) sm_carry = inc;
+      __syncthreads();
+      carry = sm_carry;
+      __syncthreads();
+    }
+    const int n_alive = carry;                       // n_free == n_alive + 1: one slot stays free
+    f_final = free_list[n_alive < n_free ? n_alive : n_free - 1];
+
+    // ---- rewrite ids that still name chunk tokens, hand their scores to their slots ----
+    for (int k = tid; k < m; k += RP_THREADS) {
+      const int x = tree_index(k, j_final);
+      const int id = Eu[x];
+      if (id >= cap) Eu[x] = flag[id];
+    }
+    for (int x = tid; x < r; x += RP_THREADS) {
+      const int id = Ru[x];
+      if (id >= cap) Ru[x] = flag[id];
+    }
+    for (int i = F + tid; i < L; i += RP_THREADS) {
+      const int slot = flag[cap + i];
+      if (slot >= 0) Su[slot] = snew[i];
+    }
+  }
+  // tokens that arrived while filling sit in slots n0 + i unless the chunk also evicted them;
+  // flag[cap + i] is now every chunk token's destination slot (or -1) for the scatter
+  for (int i = tid; i < F; i += RP_THREADS) flag[cap + i] = flag[n0 + i] ? -1 : n0 + i;
+  __syncthreads();
+
+  // ---- retained positions, bookkeeping words ----
+  int32_t* ret = retained + (size_t)unit * c;
+  for (int i = tid; i < c; i += RP_THREADS) {
+    int pv = -1;
+    if (i < n_final) {
+      pv = i;
+      if (n_final == c) {
+        const int k = i - p.n_sink;
+        if (k >= 0 && k < m) pv = PEu[tree_index(k, j_final)];
+        else if (k >= m) pv = t_end + 1 - r + (k - m);
+      }
+    }
+    ret[i] = pv;
+  }
+  if (tid == 0) {
+    meta[META_N] = n_final;
+    meta[META_FREE] = f_final;
+    meta[META_J] = j_final;
+    meta[META_RHEAD] = rhead_final;
+    meta[META_T] = t0 + L;
+    if (n_retained) n_retained[unit] = n_final;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// scatter: chunk rows that survived go to their slots
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void prefill_scatter_kernel(Params p, const uint4* __restrict__ Kc,
+                                                             const uint4* __restrict__ Vc, int L, int row_vec) {
+  const int i = blockIdx.x, unit = blockIdx.y;
+  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+  const int slot = p.pf_flag[(size_t)unit * (p.cap + p.max_chunk) + p.cap + i];
+  if (slot < 0) return;
+  const size_t src = (((size_t)b * L + i) * p.Hkv + kvh) * row_vec;
+  const size_t dst = ((size_t)unit * p.cap + slot) * row_vec;
+  for (int e = threadIdx.x; e < row_vec; e += 64) {
+    reinterpret_cast<uint4*>(p.K)[dst + e] = Kc[src + e];
+    reinterpret_cast<uint4*>(p.V)[dst + e] = Vc[src + e];
+  }
+}
+
+template <int D>
+int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* V, int L, float* out,
+                     int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s) {
+  const uint16_t* q = (const uint16_t*)Q;
+  const uint16_t* k = (const uint16_t*)K;
+  const uint16_t* v = (const uint16_t*)V;
+  const int row_tiles = (L + ROW_TILE - 1) / ROW_TILE;
+  hipLaunchKernelGGL((prefill_attend_kernel<D>), dim3(row_tiles, p.G, p.U), dim3(PF_THREADS), 0, s, p, q, k, v, L, out);
+  const int col_tiles = (p.cap + COL_TILE - 1) / COL_TILE + (L + COL_TILE - 1) / COL_TILE;
+  hipLaunchKernelGGL((prefill_colsum_kernel<D>), dim3(col_tiles, p.U), dim3(PF_THREADS), 0, s, p, q, k, L);
+  hipLaunchKernelGGL(prefill_replay_kernel, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, retained, n_retained, evicted);
+  hipLaunchKernelGGL(prefill_scatter_kernel, dim3(L, p.U), dim3(64), 0, s, p, (const uint4*)K, (const uint4*)V, L,
+                     D * 2 / 16);
+  return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
+}
+
+}  // namespace
+
+int launch_prefill(const Params& p, const void* Q, const void* K, const void* V, int len, float* out,
+                   int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s) {
+  if (p.dtype != TREEKV_BF16) return TREEKV_EUNSUPPORTED;      // the MFMA path is bf16
+  if (p.D == 128) return launch_prefill_d<128>(p, Q, K, V, len, out, retained, n_retained, evicted, s);
+  if (p.D == 64) return launch_prefill_d<64>(p, Q, K, V, len, out, retained, n_retained, evicted, s);
   return TREEKV_EUNSUPPORTED;
 }
+
 }  // namespace tkv

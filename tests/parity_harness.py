@@ -126,3 +126,87 @@ def compare_scores(kv, results, dtype="bf16"):
         assert np.all(S[b, h, n:] == 0)
     assert worst <= tol, f"averaged scores differ by {worst} > {tol}"
     return worst
+
+
+# --------------------------------------------------------------------------- #
+# mixed prefill / decode schedules
+# --------------------------------------------------------------------------- #
+def run_schedule(oracle, kv, Q, K, V, schedule, dtype="bf16", units=None, check_every_call=True):
+    """Drive GPU and oracle through `schedule`, a list of chunk lengths (0 = one decode step).
+
+    Q [T,B,H,d], K/V [T,B,Hkv,d]: float arrays of the values the GPU consumes, T = total tokens.
+    After every call compares outputs, evicted positions (follow mode) and the retained list.
+    """
+    import torch
+
+    c = kv.cfg
+    G = c.q_heads // c.kv_heads
+    if units is None:
+        units = [(b, h) for b in range(c.batch) for h in range(c.kv_heads)]
+    ocfg = oracle_cfg(kv)
+    streams = {u: oracle.OracleStream(ocfg["budget"], G, c.head_dim, n_sink=ocfg["n_sink"], n_recent=ocfg["n_recent"],
+                                      scale=ocfg["scale"], flags=ocfg["flags"]) for u in units}
+    tol = TOL[dtype]
+    Qd, Kd, Vd = to_device(Q, dtype), to_device(K, dtype), to_device(V, dtype)
+    t = 0
+    stats = dict(flagged=0, decisions=0, max_err=0.0, calls=0)
+    for L in schedule:
+        if L == 0:
+            out, ret, nret, ev = kv.new_outputs()
+            kv.decode_step(Qd[t], Kd[t], Vd[t], out, ret, nret, ev)
+            torch.cuda.synchronize()
+            o_g = out.cpu().numpy()[:, None]                      # [B,1,H,d]
+            ev_g = ev.cpu().numpy()[:, :, None]                   # [B,Hkv,1]
+            n_tok = 1
+        else:
+            qc = Qd[t:t + L].permute(1, 0, 2, 3).contiguous()     # [B,L,H,d]
+            kc = Kd[t:t + L].permute(1, 0, 2, 3).contiguous()
+            vc = Vd[t:t + L].permute(1, 0, 2, 3).contiguous()
+            out, ret, nret, ev = kv.new_outputs(L)
+            kv.prefill_chunk(qc, kc, vc, L, out, ret, nret, ev)
+            torch.cuda.synchronize()
+            o_g, ev_g = out.cpu().numpy(), ev.cpu().numpy()
+            n_tok = L
+        ret_g, nret_g = ret.cpu().numpy(), nret.cpu().numpy()
+
+        def job(u):
+            b, h = u
+            s = streams[u]
+            qs, ks, vs = Q[t:t + n_tok, b, h * G:(h + 1) * G, :], K[t:t + n_tok, b, h, :], V[t:t + n_tok, b, h, :]
+            if L == 0:
+                o, e, mg, ad, dis = s.decode_step(qs[0], ks[0], vs[0], forced_pos=int(ev_g[b, h, 0]),
+                                                  follow_thresh=FOLLOW_THRESH)
+                return dict(out=o[None], evicted=np.array([e]), adopted=np.array([ad]), disagreed=np.array([dis]))
+            return s.prefill_chunk(qs, ks, vs, forced_pos=ev_g[b, h], follow_thresh=FOLLOW_THRESH)
+
+        results = oracle.run_many(job, units, workers=min(len(units), os.cpu_count() or 1, 16))
+        for (b, h), res in zip(units, results):
+            where = f"call {stats['calls']} (len {L}, t={t}), unit {(b, h)}"
+            assert int(np.sum(res["disagreed"])) == 0, f"{where}: eviction decisions differ outside the near-tie margin"
+            np.testing.assert_array_equal(res["evicted"], ev_g[b, h], err_msg=where)
+            err = float(np.abs(res["out"] - o_g[b, :, h * G:(h + 1) * G, :]).max())
+            assert err <= tol, f"{where}: attention output differs by {err} > {tol}"
+            stats["max_err"] = max(stats["max_err"], err)
+            stats["flagged"] += int(np.sum(res["adopted"]))
+            stats["decisions"] += int(np.count_nonzero(res["evicted"] >= 0))
+            want = streams[(b, h)].retained()
+            assert nret_g[b, h] == len(want), where
+            assert np.array_equal(ret_g[b, h, :len(want)], want), f"{where}: retained set"
+            assert np.all(ret_g[b, h, len(want):] == -1)
+        t += n_tok
+        stats["calls"] += 1
+    stats["results"] = {u: dict(stream=streams[u]) for u in units}
+    return stats
+
+
+def smoke_prefill(oracle, binding):
+    """Two prefill chunks and two decode steps on a small GQA configuration, checked against the oracle."""
+    from paper_2501_04987_amd import inputs
+
+    T, B, H, Hkv, d, budget = 150, 1, 4, 2, 128, 40
+    Q, K, V = inputs.batch_streams("lowrank", 1, T, B, Hkv, H // Hkv, d, dtype="bf16")
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=2, n_recent=10, max_chunk=128)
+    st = run_schedule(oracle, kv, Q, K, V, [30, 100, 0, 18, 0], dtype="bf16")
+    err = compare_scores(kv, st["results"], "bf16")
+    print(f"smoke: prefill ok, {st['decisions']} evictions, {st['flagged']} near-ties, "
+          f"max |out err| {st['max_err']:.2e}, max |score err| {err:.2e}")

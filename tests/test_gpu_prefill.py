@@ -1,0 +1,112 @@
+"""GPU parity: chunked prefill (through the C ABI) against the CPU oracle, mixed with decode steps."""
+import numpy as np
+import pytest
+
+from paper_2501_04987_amd import inputs
+from tests import parity_harness as ph
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2501_04987_amd import binding as b
+
+    b.load()
+    return b
+
+
+def _run(binding, oracle, schedule, *, B, H, Hkv, d, budget, n_sink, n_recent, seed=0, max_chunk=0, flags=0,
+         units=None, kind="lowrank"):
+    T = sum(max(L, 1) for L in schedule)
+    Q, K, V = inputs.batch_streams(kind, seed, T, B, Hkv, H // Hkv, d, dtype="bf16")
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=n_sink, n_recent=n_recent,
+                        max_chunk=max_chunk, flags=flags)
+    st = ph.run_schedule(oracle, kv, Q, K, V, schedule, dtype="bf16", units=units)
+    st["score_err"] = ph.compare_scores(kv, st["results"], "bf16")
+    assert st["flagged"] <= max(2, st["decisions"] // 500), st["flagged"]
+    print(f"  flagged={st['flagged']}/{st['decisions']} max_err={st['max_err']:.2e} score_err={st['score_err']:.2e}")
+    return kv, st
+
+
+def test_prefill_fill_then_evict_with_layout(binding, oracle):
+    """Chunks that fill the cache, cross the budget, and span several sweeps of the scope index."""
+    _run(binding, oracle, [40, 17, 64, 1, 100, 33, 128, 7], B=1, H=2, Hkv=2, d=128, budget=96, n_sink=2, n_recent=30,
+         max_chunk=128)
+
+
+def test_prefill_pure_algorithm1_many_sweeps(binding, oracle):
+    """No protected tokens, tree region of 50 slots, chunks of up to 200 tokens: up to 5 sweeps per chunk."""
+    _run(binding, oracle, [30, 200, 3, 150, 200, 49, 51], B=1, H=2, Hkv=2, d=128, budget=50, n_sink=0, n_recent=0,
+         max_chunk=256, seed=4)
+
+
+def test_prefill_interleaved_with_decode(binding, oracle):
+    _run(binding, oracle, [0, 0, 20, 0, 64, 0, 0, 0, 70, 0, 5, 0], B=2, H=2, Hkv=2, d=128, budget=48, n_sink=1,
+         n_recent=15, max_chunk=128, seed=6)
+
+
+@pytest.mark.parametrize("G,d", [(4, 128), (2, 64), (8, 64)])
+def test_prefill_grouped_queries(binding, oracle, G, d):
+    _run(binding, oracle, [50, 90, 0, 128, 13], B=2, H=2 * G, Hkv=2, d=d, budget=72, n_sink=3, n_recent=20,
+         max_chunk=128, seed=8)
+
+
+@pytest.mark.parametrize("budget,n_sink,n_recent", [(1, 0, 0), (2, 0, 0), (3, 1, 1), (6, 0, 5), (6, 5, 0)])
+def test_prefill_degenerate_budgets(binding, oracle, budget, n_sink, n_recent):
+    _run(binding, oracle, [5, 1, 16, 0, 33], B=1, H=1, Hkv=1, d=64, budget=budget, n_sink=n_sink, n_recent=n_recent,
+         max_chunk=64, seed=9, kind="iid")
+
+
+def test_prefill_keep_left(binding, oracle):
+    _run(binding, oracle, [64, 64, 10, 64], B=1, H=2, Hkv=2, d=128, budget=40, n_sink=0, n_recent=8, max_chunk=64,
+         flags=binding.TREEKV_KEEP_LEFT, seed=10)
+
+
+def test_prefill_len1_equals_decode(binding, oracle):
+    """A one-token chunk is a decode step: same evictions, same retained list, outputs within tolerance."""
+    import torch
+
+    T, B, H, d, budget = 150, 1, 4, 128, 32
+    Q, K, V = inputs.batch_streams("lowrank", 12, T, B, H, 1, d, dtype="bf16")
+    a = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=2, n_recent=6, max_chunk=16)
+    b = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=2, n_recent=6, max_chunk=16)
+    Qd, Kd, Vd = (ph.to_device(x, "bf16") for x in (Q, K, V))
+    oa, ra, na, ea = a.new_outputs()
+    ob, rb, nb, eb = b.new_outputs(1)
+    for t in range(T):
+        a.decode_step(Qd[t], Kd[t], Vd[t], oa, ra, na, ea)
+        b.prefill_chunk(Qd[t:t + 1].permute(1, 0, 2, 3).contiguous(), Kd[t:t + 1].permute(1, 0, 2, 3).contiguous(),
+                        Vd[t:t + 1].permute(1, 0, 2, 3).contiguous(), 1, ob, rb, nb, eb)
+        torch.cuda.synchronize()
+        assert torch.equal(ea.flatten(), eb.flatten()) and torch.equal(ra, rb) and torch.equal(na, nb), t
+        assert (oa - ob[:, 0]).abs().max().item() < 1e-4
+    assert (a.scores() - b.scores()).abs().max().item() < 1e-3
+
+
+def test_prefill_argument_errors(binding):
+    import torch
+
+    kv = binding.TreeKV(32, 2, 128, max_chunk=64)
+    out, ret, nret, ev = kv.new_outputs(8)
+    x = torch.zeros(1, 80, 2, 128, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.TreeKVError):
+        kv.prefill_chunk(x, x, x, 65, out, ret, nret, ev)          # longer than max_chunk
+    with pytest.raises(binding.TreeKVError):
+        kv.prefill_chunk(x, x, x, 0, out, ret, nret, ev)
+    kv32 = binding.TreeKV(32, 2, 64, kv_heads=2, dtype="f32", n_sink=0, n_recent=0)
+    with pytest.raises(binding.TreeKVError) as e:
+        kv32.prefill_chunk(x, x, x, 8, out, ret, nret, ev)         # the MFMA prefill is bf16 only
+    assert e.value.status == binding.TREEKV_EUNSUPPORTED
+
+
+def test_prefill_llama_shaped_prompt_sampled(binding, oracle):
+    """32 heads x 128, bf16, budget 2048 (4 + 1024 + 1020), prompt of 8192 tokens in chunks of 512, then
+    32 decode steps; the GPU runs all heads, the oracle audits 4 of them call by call."""
+    sched = [512] * 16 + [0] * 32
+    kv, st = _run(binding, oracle, sched, B=1, H=32, Hkv=32, d=128, budget=2048, n_sink=4, n_recent=1020,
+                  units=[(0, 0), (0, 11), (0, 22), (0, 31)], seed=0)
+    assert st["decisions"] == 4 * (8192 + 32 - 2048)
