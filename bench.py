@@ -11,7 +11,9 @@ else with decode steps); inputs are synthetic and already resident in HBM.
 
 Prints ONE JSON line.  `roofline` prices the decode kernel's algorithmic bytes per launch
 against the 8 TB/s HBM peak; `cpu_baseline` times the fp64 CPU oracle on a bounded sample of
-the same workload on this machine's host cores.
+the same workload on this machine's host cores.  `prefill` reports the other half of the hot
+path, the 512-token prefill chunk over a full 2048-slot cache (32 heads x 128, bf16), against
+the dense bf16 MFMA peak; it is measured after the headline figure and is not part of `value`.
 """
 from __future__ import annotations
 
@@ -28,6 +30,8 @@ if ROOT not in sys.path:
 
 LAYERS, BATCH, HEADS, KV_HEADS, HEAD_DIM, BUDGET = 32, 8, 32, 32, 128, 2048
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+PREFILL_CHUNK = 512
 
 # HBM bytes per decode launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/),
 # scaled by a copy kernel of known size.  None until measured for the current kernel.
@@ -55,7 +59,7 @@ def cpu_baseline(seconds_budget=20.0):
 
     orc.build()
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16") or 16), 16)
-    n_timed = 384
+    n_timed = 1536
     T = BUDGET + n_timed
     cfg = dict(budget=BUDGET, G=1, d=HEAD_DIM, n_sink=4, n_recent=BUDGET - BUDGET // 2 - 4)
 
@@ -84,12 +88,60 @@ def cpu_baseline(seconds_budget=20.0):
     }
 
 
+def prefill_flops_per_chunk(c=BUDGET, L=PREFILL_CHUNK, d=HEAD_DIM, heads=HEADS):
+    """Algorithmic flops of one chunk over a full cache: Q.K^T and P.V over c cache columns plus the
+    causal half of the chunk's own L x L block, for every head."""
+    return 2 * 2 * L * (c + (L + 1) / 2) * d * heads
+
+
+def bench_prefill(torch, binding, inputs, dev, chunks=24, warm=6, layers=4):
+    """Chunks of 512 tokens into full 2048-slot caches, 32 heads x 128, batch 1, cycling over a few layers."""
+    kvs = [binding.TreeKV(BUDGET, HEADS, HEAD_DIM, kv_heads=KV_HEADS, batch=1, dtype="bf16", n_sink=4,
+                          n_recent=BUDGET - BUDGET // 2 - 4, max_chunk=PREFILL_CHUNK) for _ in range(layers)]
+    n_in = 8
+    q, k, v = inputs.device_lowrank(11, n_in * PREFILL_CHUNK, 1, KV_HEADS, HEADS // KV_HEADS, HEAD_DIM, device=dev)
+    mk = lambda x, h: x.view(n_in, PREFILL_CHUNK, 1, h, HEAD_DIM).permute(0, 2, 1, 3, 4).contiguous()   # [n,B,L,H,d]
+    q, k, v = mk(q, HEADS), mk(k, KV_HEADS), mk(v, KV_HEADS)
+    out = torch.empty(1, PREFILL_CHUNK, HEADS, HEAD_DIM, dtype=torch.float32, device=dev)
+    ret = torch.empty(layers, 1, KV_HEADS, BUDGET, dtype=torch.int32, device=dev)
+    nret = torch.empty(layers, 1, KV_HEADS, dtype=torch.int32, device=dev)
+    ev = torch.empty(1, KV_HEADS, PREFILL_CHUNK, dtype=torch.int32, device=dev)
+
+    def run(i):
+        l = i % layers
+        kvs[l].prefill_chunk(q[i % n_in], k[i % n_in], v[i % n_in], PREFILL_CHUNK, out, ret[l], nret[l], ev)
+
+    for i in range(layers * (BUDGET // PREFILL_CHUNK)):          # fill every layer's cache
+        run(i)
+    for i in range(warm):
+        run(i)
+    torch.cuda.synchronize()
+    assert int(nret.min()) == BUDGET
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(chunks):
+        run(i)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / chunks
+    assert int(ev.min()) >= 0, "every token of a chunk into a full cache evicts one"
+    flops = prefill_flops_per_chunk()
+    tf = flops / (us * 1e-6) / 1e12
+    return {"workload": "configs[3] shape: 512-token chunk into a full 2048-slot cache, 32 heads x 128 dim, bf16, batch 1",
+            "chunks": chunks, "us_per_chunk": us, "prompt_tokens_per_s": PREFILL_CHUNK / (us * 1e-6),
+            "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "flops_per_chunk": flops,
+                         "note": "algorithmic flops (Q.K^T and P.V once each) over the whole chunk call: attend, "
+                                 "column sums, replay and scatter kernels"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-chunk measurement")
     ap.add_argument("--kv-splits", type=int, default=0)
     ap.add_argument("--graph", type=int, default=0, help="replay the timed steps from HIP graphs (1) or launch them (0)")
     args = ap.parse_args()
@@ -214,11 +266,15 @@ def main():
         "layer_steps_per_s": steps_per_s * LAYERS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": "decode_kernel<bf16,128,1>", "bytes_per_launch": bytes_per_launch,
+                     "kernel": "decode_fused_kernel<bf16,128,1>", "bytes_per_launch": bytes_per_launch,
                      "launch_us": launch_us,
                      "note": "launch_us = HIP-event time of the timed region / number of decode launches "
                              "(gaps between launches included)"},
     }
+    if not args.no_prefill:
+        del q, k, v, layers
+        torch.cuda.empty_cache()
+        res["prefill"] = bench_prefill(torch, binding, inputs, dev)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline()
     print(json.dumps(res))

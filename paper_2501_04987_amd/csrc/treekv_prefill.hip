@@ -42,13 +42,6 @@ __device__ inline f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
-// float -> bf16 bits, round to nearest even (finite inputs)
-__device__ inline unsigned bf16_rn(float x) {
-  unsigned u = __float_as_uint(x);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
-
 struct ChunkInfo {
   int n;        // tokens cached before the chunk
   int fslot;    // the free slot (a hole among slots [0, n] once the cache is full)
@@ -66,26 +59,63 @@ __device__ inline ChunkInfo load_chunk_info(const int* meta) {
 // ---------------------------------------------------------------------------------------------
 // attend
 // ---------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+
+// two floats -> two bf16 (round to nearest even) packed in one dword, first value in the low half
+__device__ inline unsigned pack_bf16(float a, float b) {
+  f32x2_t v = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
+
+constexpr int AT_THREADS = 512;   // 8 waves: waves 0-3 take columns 0-31 of every 64-column tile, waves 4-7 columns 32-63
+
 template <int D>
-__global__ __launch_bounds__(PF_THREADS) void prefill_attend_kernel(Params p, const uint16_t* __restrict__ Q,
+struct AttendLds {
+  static constexpr int KSTRIDE = D + 8;          // bf16 elements per staged K row (padded: conflict-free b128 reads)
+  static constexpr int VSTRIDE = COL_TILE + 8;   // bf16 elements per staged V^T row
+  static constexpr int K_ELEMS = COL_TILE * KSTRIDE;
+  static constexpr int V_ELEMS = D * VSTRIDE;
+  static constexpr size_t BYTES = 2 * (size_t)(K_ELEMS + V_ELEMS) * sizeof(uint16_t);   // two stages
+};
+
+// Staged V^T layout.  Row d holds the tile's 64 columns in the order the P^T operand uses them:
+// column j sits at position (j/32)*32 + ((j%16)/4)*8 + ((j%32)/16)*4 + j%4, so that the 8 k-slots of
+// lane group q4 in half h (columns h*32 + q4*4 + {0..3} and h*32 + 16 + q4*4 + {0..3}) are the 16
+// contiguous bytes of "pair" h*4 + q4.  Pairs are XOR-swizzled with (d/16)%8: the 16 lanes of an operand
+// read share d/16, so reads stay conflict free, while the transposing 8-byte writes of 16 lanes (same
+// columns, rows 8 apart) spread over all banks.
+//
+// Work split.  A workgroup owns 64 query rows of one head.  Wave w and wave w+4 both own rows
+// 16*(w%4)..+15 and split every tile's columns in halves, each with its own online-softmax state; two
+// waves per SIMD let one wave's exp/convert work overlap the other's MFMAs.  The halves are merged
+// through LDS at the end.  Threads 0-255 stage V (transposing), threads 256-511 stage K.
+template <int D>
+__global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, const uint16_t* __restrict__ Q,
                                                                     const uint16_t* __restrict__ Kc,
                                                                     const uint16_t* __restrict__ Vc, int L,
                                                                     float* __restrict__ out) {
+  using Lds = AttendLds<D>;
   constexpr int KS = D / 32;          // k-steps of the q.k contraction
   constexpr int DB = D / 16;          // 16-wide blocks of the head dimension
-  constexpr int KSTRIDE = D + 8;      // LDS row strides in bf16 elements (padded against bank conflicts)
-  constexpr int VSTRIDE = COL_TILE + 8;
-  __shared__ __attribute__((aligned(16))) uint16_t sK[COL_TILE * KSTRIDE];
-  __shared__ __attribute__((aligned(16))) uint16_t sVt[D * VSTRIDE];
+  constexpr int PARTS = D / 8;        // 16-byte pieces per row
+  constexpr int KCH = COL_TILE * PARTS / 256;          // K pieces per K-staging thread (2 or 4)
+  static_assert(KCH == 2 || KCH == 4, "staging is written for head_dim 64 and 128");
+  constexpr int NVBLK = (COL_TILE / 4) * PARTS;        // 4-column x 8-dim V blocks per tile (128 or 256)
+  constexpr int KROWS_PER_X = 256 / PARTS;             // rows between a K thread's consecutive pieces
+  extern __shared__ __attribute__((aligned(16))) uint16_t pf_smem[];
+  uint16_t* sK = pf_smem;                               // [2][K_ELEMS]
+  uint16_t* sVt = pf_smem + 2 * Lds::K_ELEMS;           // [2][V_ELEMS]
 
   const int row_tile = blockIdx.x, g = blockIdx.y, unit = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, q4 = lane >> 4;
+  const int half = wave >> 2;                              // which 32 columns of every tile
   const int kvh = unit % p.Hkv, b = unit / p.Hkv;
   const int h = kvh * p.G + g;
   const ChunkInfo ci = load_chunk_info(p.meta + (size_t)unit * META_STRIDE);
 
-  const int row0 = row_tile * ROW_TILE + wave * 16;        // first chunk row of this wave
+  const int row0 = row_tile * ROW_TILE + (wave & 3) * 16;  // first chunk row of this wave
   const int my_row = row0 + lr;                            // the query row this lane's results belong to
   const int ld_row = min(my_row, L - 1);
   const uint16_t* qp = Q + (((size_t)b * L + ld_row) * p.H + h) * D;
@@ -95,106 +125,196 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_attend_kernel(Params p, co
 
   const uint16_t* Ku = (const uint16_t*)p.K + (size_t)unit * p.cap * D;
   const uint16_t* Vu = (const uint16_t*)p.V + (size_t)unit * p.cap * D;
+  const int chunk_row_stride = p.Hkv * D;
+  const uint16_t* Kcu = Kc + ((size_t)b * L * p.Hkv + kvh) * D;
+  const uint16_t* Vcu = Vc + ((size_t)b * L * p.Hkv + kvh) * D;
 
-  float m_run = NEG_BIG, l_part = 0.f;
+  const int cache_tiles = (ci.n + 1 + COL_TILE - 1) / COL_TILE;        // slots [0, n], the free one masked
+  const int last_row = min(row_tile * ROW_TILE + ROW_TILE, L) - 1;     // last chunk row of the workgroup
+  const int chunk_tiles = last_row / COL_TILE + 1;                     // causal: columns <= last_row
+  const int ntiles = cache_tiles + chunk_tiles;
+
+  // ---- staging: global -> registers -> LDS (named registers: arrays here end up in scratch memory) ----
+  uint4 g0, g1, g2, g3;
+  g0 = g1 = g2 = g3 = make_uint4(0, 0, 0, 0);
+  const bool v_role = tid < 256;
+  const int st = tid & 255;
+  // V role: block of columns v_jg*4..+3, dims v_part*8..+7.  K role: pieces st + x*256.
+  const int v_part = st % PARTS, v_jg = st / PARTS;
+  const bool v_active = v_role && (NVBLK >= 256 || st < NVBLK);
+  const int k_r0 = st / PARTS, k_part = st % PARTS;
+  const int first_row = v_role ? v_jg * 4 : k_r0;                       // first tile row this thread loads
+  const int row_step = v_role ? 1 : KROWS_PER_X;                        // rows between its loads
+  const int col_off = (v_role ? v_part : k_part) * 8;
+  const uint16_t* cache_base = (v_role ? Vu : Ku) + col_off;
+  const uint16_t* chunk_base = (v_role ? Vcu : Kcu) + col_off;
+  const int cache_lim = p.cap - 1, chunk_lim = L - 1;                   // last row that exists
+  const bool do_load = !v_role || v_active;
+  const bool four_loads = v_role || KCH > 2;
+  auto load_regs = [&](int tile) {
+    const bool is_cache = tile < cache_tiles;
+    const int col0 = is_cache ? tile * COL_TILE : (tile - cache_tiles) * COL_TILE;
+    const uint16_t* base = is_cache ? cache_base : chunk_base;
+    const int rstride = is_cache ? D : chunk_row_stride;
+    const int lim = is_cache ? cache_lim : chunk_lim;
+    const int r = col0 + first_row;
+    if (do_load) {
+      g0 = *reinterpret_cast<const uint4*>(base + (size_t)min(r, lim) * rstride);
+      g1 = *reinterpret_cast<const uint4*>(base + (size_t)min(r + row_step, lim) * rstride);
+      if (four_loads) {
+        g2 = *reinterpret_cast<const uint4*>(base + (size_t)min(r + 2 * row_step, lim) * rstride);
+        g3 = *reinterpret_cast<const uint4*>(base + (size_t)min(r + 3 * row_step, lim) * rstride);
+      }
+    }
+  };
+  // LDS destinations do not depend on the tile: byte offsets inside one stage
+  const int k_dst = (k_r0 * Lds::KSTRIDE + k_part * 8) * 2;
+  const int v_pair = ((v_jg / 8) * 4 + (v_jg % 4)) ^ ((v_part >> 1) & 7);   // (d/16)%8 == v_part/2 for all 8 dims
+  const int v_dst = ((v_part * 8) * Lds::VSTRIDE + v_pair * 8 + ((v_jg % 8) / 4) * 4) * 2;
+  auto store_lds = [&](int buf) {
+    if (!v_role) {
+      char* k = reinterpret_cast<char*>(sK + buf * Lds::K_ELEMS) + k_dst;
+      *reinterpret_cast<uint4*>(k) = g0;
+      *reinterpret_cast<uint4*>(k + KROWS_PER_X * Lds::KSTRIDE * 2) = g1;
+      if constexpr (KCH > 2) {
+        *reinterpret_cast<uint4*>(k + 2 * KROWS_PER_X * Lds::KSTRIDE * 2) = g2;
+        *reinterpret_cast<uint4*>(k + 3 * KROWS_PER_X * Lds::KSTRIDE * 2) = g3;
+      }
+    } else if (v_active) {
+      char* v = reinterpret_cast<char*>(sVt + buf * Lds::V_ELEMS) + v_dst;
+      // dword w of the four rows holds dims 2w, 2w+1 of columns +0..+3: regroup into one 8-byte word per dim
+      auto emit = [&](unsigned a0, unsigned a1, unsigned a2, unsigned a3, int e_even) {
+#pragma unroll
+        for (int odd = 0; odd < 2; ++odd) {
+          const unsigned sel = odd ? 0x07060302u : 0x05040100u;       // the odd / even bf16 of both dwords
+          uint2 o;
+          o.x = __builtin_amdgcn_perm(a1, a0, sel);                   // columns +0, +1
+          o.y = __builtin_amdgcn_perm(a3, a2, sel);                   // columns +2, +3
+          *reinterpret_cast<uint2*>(v + (e_even + odd) * Lds::VSTRIDE * 2) = o;
+        }
+      };
+      emit(g0.x, g1.x, g2.x, g3.x, 0);
+      emit(g0.y, g1.y, g2.y, g3.y, 2);
+      emit(g0.z, g1.z, g2.z, g3.z, 4);
+      emit(g0.w, g1.w, g2.w, g3.w, 6);
+    }
+  };
+
+  // operand read offsets (bytes inside one stage), tile independent
+  const int ka_off = ((2 * half * 16 + lr) * Lds::KSTRIDE + q4 * 8) * 2;               // + bk*16 rows, + ks*64 bytes
+  const int va_row = (lr * Lds::VSTRIDE) * 2;
+  const int va0 = va_row + ((q4 ^ 0) * 16), va1 = va_row + ((q4 ^ 1) * 16);            // by d & 3
+  const int va2 = va_row + ((q4 ^ 2) * 16), va3 = va_row + ((q4 ^ 3) * 16);
+
+  float m_run = NEG_BIG;               // running row max of the raw (unscaled) logits over this wave's columns
+  float l_part = 0.f;
   f32x4_t oacc[DB];
 #pragma unroll
   for (int d = 0; d < DB; ++d) oacc[d] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  const float sc = p.scale_log2e;
+  const int n_cached = ci.n, fslot = ci.fslot;
 
-  const int n_cache_cols = ci.n + 1;                                   // slots [0, n], the free one masked
-  const int cache_tiles = (n_cache_cols + COL_TILE - 1) / COL_TILE;
-  const int last_row = min(row_tile * ROW_TILE + ROW_TILE, L) - 1;     // last chunk row of the workgroup
-  const int chunk_tiles = last_row / COL_TILE + 1;                     // causal: columns <= last_row
-
-  for (int tile = 0; tile < cache_tiles + chunk_tiles; ++tile) {
+  load_regs(0);
+  store_lds(0);
+  __syncthreads();
+  for (int tile = 0; tile < ntiles; ++tile) {
+    if (tile + 1 < ntiles) load_regs(tile + 1);            // in flight while this tile is computed
     const bool is_cache = tile < cache_tiles;
     const int col0 = is_cache ? tile * COL_TILE : (tile - cache_tiles) * COL_TILE;
-    __syncthreads();                                                   // previous tile fully consumed
-    // stage K (row major) and V (transposed) of the tile in LDS
-    constexpr int CHUNKS = COL_TILE * D / 8;                           // 16-byte pieces per tile
-#pragma unroll
-    for (int x = 0; x < CHUNKS / PF_THREADS; ++x) {
-      const int c = tid + x * PF_THREADS;
-      const int r = c / (D / 8), part = c % (D / 8);
-      const uint16_t *ks, *vs;
-      if (is_cache) {
-        const int slot = min(col0 + r, p.cap - 1);
-        ks = Ku + (size_t)slot * D; vs = Vu + (size_t)slot * D;
-      } else {
-        const int jc = min(col0 + r, L - 1);
-        ks = Kc + (((size_t)b * L + jc) * p.Hkv + kvh) * D; vs = Vc + (((size_t)b * L + jc) * p.Hkv + kvh) * D;
-      }
-      const uint4 kv = *reinterpret_cast<const uint4*>(ks + part * 8);
-      const uint4 vv = *reinterpret_cast<const uint4*>(vs + part * 8);
-      *reinterpret_cast<uint4*>(&sK[r * KSTRIDE + part * 8]) = kv;
-      const unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        sVt[(part * 8 + 2 * e) * VSTRIDE + r] = (uint16_t)(w[e] & 0xffffu);
-        sVt[(part * 8 + 2 * e + 1) * VSTRIDE + r] = (uint16_t)(w[e] >> 16);
-      }
-    }
-    __syncthreads();
+    const char* k = reinterpret_cast<const char*>(sK + (tile & 1) * Lds::K_ELEMS) + ka_off;
+    const char* v = reinterpret_cast<const char*>(sVt + (tile & 1) * Lds::V_ELEMS);
 
-    // S^T block bk: rows = columns col0 + bk*16 + q4*4 + i, column = this lane's query row
-    float s[4][4];
+    // S^T block bk of this wave's half: rows = columns col0 + half*32 + bk*16 + q4*4 + i, column = the lane's query row
+    f32x4_t s[2];
 #pragma unroll
-    for (int bk = 0; bk < 4; ++bk) {
-      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int bk = 0; bk < 2; ++bk) {
+      s[bk] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const uint4 a = *reinterpret_cast<const uint4*>(&sK[(bk * 16 + lr) * KSTRIDE + ks * 32 + q4 * 8]);
-        acc = mfma16(a, qa[ks], acc);
+        const uint4 a = *reinterpret_cast<const uint4*>(k + bk * 16 * Lds::KSTRIDE * 2 + ks * 64);
+        s[bk] = mfma16(a, qa[ks], s[bk]);
       }
+    }
+    // only tiles that touch the end of the cache, the free slot or the causal diagonal need a mask (wave uniform)
+    const bool need_mask = is_cache ? (col0 + COL_TILE - 1 > ci.n || (ci.fslot >= col0 && ci.fslot < col0 + COL_TILE))
+                                    : (col0 + COL_TILE - 1 > row0);
+    if (need_mask) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int col = col0 + bk * 16 + q4 * 4 + i;
-        const bool vis = is_cache ? (col <= ci.n && col != ci.fslot) : (col <= my_row);
-        s[bk][i] = vis ? acc[i] * p.scale_log2e : NEG_BIG;
-      }
+      for (int bk = 0; bk < 2; ++bk)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int col = col0 + half * 32 + bk * 16 + q4 * 4 + i;
+          const bool vis = is_cache ? (col <= ci.n && col != ci.fslot) : (col <= my_row);
+          s[bk][i] = vis ? s[bk][i] : NEG_BIG;
+        }
     }
     float mx = m_run;
 #pragma unroll
-    for (int bk = 0; bk < 4; ++bk)
+    for (int bk = 0; bk < 2; ++bk)
 #pragma unroll
       for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[bk][i]);
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float corr = fast_exp2(m_run - mx);
-    m_run = mx;
-    l_part *= corr;
+    if (__any(mx != m_run)) {                 // the running max moved for some row of the wave: rescale
+      const float corr = fast_exp2((m_run - mx) * sc);
+      l_part *= corr;
 #pragma unroll
-    for (int d = 0; d < DB; ++d) oacc[d] *= corr;
-    uint4 phi[2], plo[2];                     // P^T operands: k = the 8 columns {bk even: i} u {bk odd: i}
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      unsigned hi[8], lo[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float sv = s[2 * half + (e >> 2)][e & 3];
-        const float pr = sv > 0.5f * NEG_BIG ? fast_exp2(sv - mx) : 0.f;
-        l_part += pr;
-        hi[e] = bf16_rn(pr);
-        lo[e] = bf16_rn(pr - __uint_as_float(hi[e] << 16));
-      }
-      phi[half] = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
-      plo[half] = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+      for (int d = 0; d < DB; ++d) oacc[d] *= corr;
+      m_run = mx;
     }
-    // O^T += V^T P^T : A = V^T[d][the same 8 columns], B = P^T
+    const float neg_ms = -mx * sc;
+    unsigned hi[4], lo[4];                    // P^T operand: k-slots 0-3 = block 0, i = 0..3; k-slots 4-7 = block 1
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-#pragma unroll
-      for (int d = 0; d < DB; ++d) {
-        const uint16_t* vrow = &sVt[(d * 16 + lr) * VSTRIDE + half * 32 + q4 * 4];
-        const uint2 v0 = *reinterpret_cast<const uint2*>(vrow);
-        const uint2 v1 = *reinterpret_cast<const uint2*>(vrow + 16);
-        const uint4 a = make_uint4(v0.x, v0.y, v1.x, v1.y);
-        oacc[d] = mfma16(a, phi[half], oacc[d]);
-        oacc[d] = mfma16(a, plo[half], oacc[d]);
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const float s0 = s[e2 >> 1][(e2 & 1) * 2], s1 = s[e2 >> 1][(e2 & 1) * 2 + 1];
+      float p0 = fast_exp2(fmaf(s0, sc, neg_ms)), p1 = fast_exp2(fmaf(s1, sc, neg_ms));
+      if (need_mask) {                        // a row with nothing visible yet has max == NEG_BIG: exp2(0) must not count
+        p0 = s0 > 0.5f * NEG_BIG ? p0 : 0.f;
+        p1 = s1 > 0.5f * NEG_BIG ? p1 : 0.f;
       }
+      l_part += p0 + p1;
+      hi[e2] = pack_bf16(p0, p1);
+      lo[e2] = pack_bf16(p0 - __uint_as_float(hi[e2] << 16), p1 - __uint_as_float(hi[e2] & 0xffff0000u));
     }
+    const uint4 phi = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    const uint4 plo = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    // O^T += V^T P^T : A = V^T[d][the same 8 columns], B = P^T (hi and lo parts)
+#pragma unroll
+    for (int d = 0; d < DB; ++d) {
+      const int vo = (d & 3) == 0 ? va0 : (d & 3) == 1 ? va1 : (d & 3) == 2 ? va2 : va3;
+      const uint4 a = *reinterpret_cast<const uint4*>(v + vo + d * 16 * Lds::VSTRIDE * 2 + (((half * 4) ^ (d & 4)) * 16));
+      oacc[d] = mfma16(a, phi, oacc[d]);
+      oacc[d] = mfma16(a, plo, oacc[d]);
+    }
+    if (tile + 1 < ntiles) store_lds((tile + 1) & 1);      // the other stage: last read one barrier ago
+    __syncthreads();
   }
 
+  // ---- merge the two column halves of every row (waves w and w+4) through LDS ----
+  float* xch = reinterpret_cast<float*>(pf_smem);           // [4 waves][2 + DB*4][64 lanes]
+  constexpr int XN = 2 + DB * 4;
+  if (half == 1) {
+    float* dst = xch + ((wave & 3) * XN) * 64 + lane;
+    dst[0] = m_run; dst[64] = l_part;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) dst[(2 + d * 4 + i) * 64] = oacc[d][i];
+  }
+  __syncthreads();
+  if (half == 1) return;
+  {
+    const float* src = xch + ((wave & 3) * XN) * 64 + lane;
+    const float mo = src[0], lo2 = src[64];
+    const float mx = fmaxf(m_run, mo);
+    const float ca = fast_exp2((m_run - mx) * sc), cb = fast_exp2((mo - mx) * sc);
+    l_part = l_part * ca + lo2 * cb;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) oacc[d][i] = oacc[d][i] * ca + src[(2 + d * 4 + i) * 64] * cb;
+    m_run = mx;
+  }
   float l_row = l_part + __shfl_xor(l_part, 16, 64);
   l_row += __shfl_xor(l_row, 32, 64);
   const float inv = 1.0f / l_row;
@@ -207,7 +327,8 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_attend_kernel(Params p, co
     }
     if (q4 == 0) {
       float* rs = p.pf_rowstat + (((size_t)unit * p.G + g) * p.max_chunk + my_row) * 2;
-      rs[0] = m_run; rs[1] = inv;
+      rs[0] = m_run * sc;                   // row max in the scaled log2 domain
+      rs[1] = inv;
     }
   }
 }
@@ -219,7 +340,8 @@ template <int D>
 __global__ __launch_bounds__(PF_THREADS) void prefill_colsum_kernel(Params p, const uint16_t* __restrict__ Q,
                                                                     const uint16_t* __restrict__ Kc, int L) {
   constexpr int KS = D / 32;
-  __shared__ float sm_cs[PF_THREADS / 64][COL_TILE];
+  constexpr int WAVES = PF_THREADS / 64;
+  __shared__ float sm_cs[WAVES][COL_TILE];
 
   const int unit = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -234,6 +356,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_colsum_kernel(Params p, co
 
   // the tile's K rows as B operands, held in registers for the whole kernel
   uint4 kb[4][KS];
+  bool colvis[4];                                           // validity of this lane's column in each block
 #pragma unroll
   for (int bk = 0; bk < 4; ++bk) {
     const int col = col0 + bk * 16 + lr;
@@ -241,46 +364,59 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_colsum_kernel(Params p, co
                                   : Kc + (((size_t)b * L + min(col, L - 1)) * p.Hkv + kvh) * D;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) kb[bk][kk] = *reinterpret_cast<const uint4*>(ks + kk * 32 + q4 * 8);
-  }
-  bool colvis[4];                                           // validity of this lane's column in each block
-#pragma unroll
-  for (int bk = 0; bk < 4; ++bk) {
-    const int col = col0 + bk * 16 + lr;
     colvis[bk] = is_cache ? (col <= ci.n && col != ci.fslot) : (col < L);
   }
 
   float cs[4] = {0.f, 0.f, 0.f, 0.f};
   const int first_rt = is_cache ? 0 : col0 / 16;            // causal: rows below the tile's first column see none of it
   const int n_rt = (L + 15) / 16;
-  for (int g = 0; g < p.G; ++g) {
-    const int h = kvh * p.G + g;
-    const float* rs = p.pf_rowstat + ((size_t)unit * p.G + g) * p.max_chunk * 2;
-    for (int rt = first_rt + wave; rt < n_rt; rt += PF_THREADS / 64) {
-      const int arow = min(rt * 16 + lr, L - 1);            // A operand: this lane's query row
-      const uint16_t* qp = Q + (((size_t)b * L + arow) * p.H + h) * D;
-      uint4 qa[KS];
+  const int n_items = (n_rt - first_rt) * p.G;              // (g, row tile) pairs, dealt round robin to the waves
+  const float sc = p.scale_log2e;
+
+  // software pipeline: the next item's Q rows and row statistics are requested before this item's MFMAs
+  uint4 qa[KS], qn[KS];
+  float2 st[4], stn[4];
+  auto fetch = [&](int item, uint4 (&q)[KS], float2 (&stat)[4]) {
+    const int g = item / (n_rt - first_rt), rt = first_rt + item % (n_rt - first_rt);
+    const int arow = min(rt * 16 + lr, L - 1);              // A operand: this lane's query row
+    const uint16_t* qp = Q + (((size_t)b * L + arow) * p.H + kvh * p.G + g) * D;
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) qa[kk] = *reinterpret_cast<const uint4*>(qp + kk * 32 + q4 * 8);
-      float mrow[4], irow[4];
-      int rowi[4];
+    for (int kk = 0; kk < KS; ++kk) q[kk] = *reinterpret_cast<const uint4*>(qp + kk * 32 + q4 * 8);
+    const float2* rs = reinterpret_cast<const float2*>(p.pf_rowstat) + ((size_t)unit * p.G + g) * p.max_chunk;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {                         // results: rows rt*16 + q4*4 + i, column lr
-        rowi[i] = rt * 16 + q4 * 4 + i;
-        const int rr = min(rowi[i], L - 1);
-        mrow[i] = rs[rr * 2]; irow[i] = rs[rr * 2 + 1];
-      }
+    for (int i = 0; i < 4; ++i) stat[i] = rs[min(rt * 16 + q4 * 4 + i, L - 1)];   // results: rows rt*16 + q4*4 + i
+  };
+  int item = wave;
+  if (item < n_items) fetch(item, qa, st);
+  for (; item < n_items; item += WAVES) {
+    const bool more = item + WAVES < n_items;
+    if (more) fetch(item + WAVES, qn, stn);
+    const int rt = first_rt + item % (n_rt - first_rt);
+    const bool need_mask = !is_cache ? (col0 + COL_TILE - 1 > rt * 16) : false;   // causal diagonal inside the tile
+    const bool tail_rows = rt * 16 + 15 >= L;
 #pragma unroll
-      for (int bk = 0; bk < 4; ++bk) {
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int bk = 0; bk < 4; ++bk) {
+      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) acc = mfma16(qa[kk], kb[bk][kk], acc);
-        const int col = col0 + bk * 16 + lr;
+      for (int kk = 0; kk < KS; ++kk) acc = mfma16(qa[kk], kb[bk][kk], acc);
+      const int col = col0 + bk * 16 + lr;
+      float add = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const bool vis = colvis[bk] && rowi[i] < L && (is_cache || col <= rowi[i]);
-          cs[bk] += vis ? fast_exp2(acc[i] * p.scale_log2e - mrow[i]) * irow[i] : 0.f;
+      for (int i = 0; i < 4; ++i) {
+        float pr = fast_exp2(fmaf(acc[i], sc, -st[i].x)) * st[i].y;
+        if (need_mask || tail_rows) {
+          const int row = rt * 16 + q4 * 4 + i;
+          pr = (row < L && (is_cache || col <= row)) ? pr : 0.f;
         }
+        add += pr;
       }
+      cs[bk] += colvis[bk] ? add : 0.f;
+    }
+    if (more) {
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) qa[kk] = qn[kk];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) st[i] = stn[i];
     }
   }
 #pragma unroll
@@ -293,7 +429,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_colsum_kernel(Params p, co
   if (tid < COL_TILE) {
     float tot = 0.f;
 #pragma unroll
-    for (int w = 0; w < PF_THREADS / 64; ++w) tot += sm_cs[w][tid];
+    for (int w = 0; w < WAVES; ++w) tot += sm_cs[w][tid];
     const int col = col0 + tid;
     if (is_cache) {
       if (col <= ci.n && col != ci.fslot) p.S[(size_t)unit * p.cap + col] += tot;
@@ -516,7 +652,12 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
   const uint16_t* k = (const uint16_t*)K;
   const uint16_t* v = (const uint16_t*)V;
   const int row_tiles = (L + ROW_TILE - 1) / ROW_TILE;
-  hipLaunchKernelGGL((prefill_attend_kernel<D>), dim3(row_tiles, p.G, p.U), dim3(PF_THREADS), 0, s, p, q, k, v, L, out);
+  auto attend = prefill_attend_kernel<D>;
+  const size_t lds = AttendLds<D>::BYTES;
+  if (lds > 48 * 1024 &&
+      hipFuncSetAttribute((const void*)attend, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    return TREEKV_EHIP;
+  hipLaunchKernelGGL(attend, dim3(row_tiles, p.G, p.U), dim3(AT_THREADS), lds, s, p, q, k, v, L, out);
   const int col_tiles = (p.cap + COL_TILE - 1) / COL_TILE + (L + COL_TILE - 1) / COL_TILE;
   hipLaunchKernelGGL((prefill_colsum_kernel<D>), dim3(col_tiles, p.U), dim3(PF_THREADS), 0, s, p, q, k, L);
   hipLaunchKernelGGL(prefill_replay_kernel, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, retained, n_retained, evicted);
