@@ -341,7 +341,11 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_colsum_kernel(Params p, co
                                                                     const uint16_t* __restrict__ Kc, int L) {
   constexpr int KS = D / 32;
   constexpr int WAVES = PF_THREADS / 64;
+  constexpr int QSTRIDE = D + 8;                    // bf16 elements per staged Q row (padded: conflict-free b128 reads)
+  constexpr int LPR = D / 8;                        // lanes that cover one Q row with 16-byte loads
+  constexpr int QLOADS = 16 * LPR / 64;             // loads per lane for a 16-row tile (4 at d=128, 2 at d=64)
   __shared__ float sm_cs[WAVES][COL_TILE];
+  __shared__ __attribute__((aligned(16))) uint16_t sm_q[WAVES][16 * QSTRIDE];   // one 16-row Q tile per wave
 
   const int unit = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -367,58 +371,96 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_colsum_kernel(Params p, co
     colvis[bk] = is_cache ? (col <= ci.n && col != ci.fslot) : (col < L);
   }
 
-  float cs[4] = {0.f, 0.f, 0.f, 0.f};
+  float cs0 = 0.f, cs1 = 0.f, cs2 = 0.f, cs3 = 0.f;
   const int first_rt = is_cache ? 0 : col0 / 16;            // causal: rows below the tile's first column see none of it
   const int n_rt = (L + 15) / 16;
-  const int n_items = (n_rt - first_rt) * p.G;              // (g, row tile) pairs, dealt round robin to the waves
   const float sc = p.scale_log2e;
+  const int Lm1 = L - 1;
+  const size_t q_row_stride = (size_t)p.H * D;
 
-  // software pipeline: the next item's Q rows and row statistics are requested before this item's MFMAs
-  uint4 qa[KS], qn[KS];
-  float2 st[4], stn[4];
-  auto fetch = [&](int item, uint4 (&q)[KS], float2 (&stat)[4]) {
-    const int g = item / (n_rt - first_rt), rt = first_rt + item % (n_rt - first_rt);
-    const int arow = min(rt * 16 + lr, L - 1);              // A operand: this lane's query row
-    const uint16_t* qp = Q + (((size_t)b * L + arow) * p.H + kvh * p.G + g) * D;
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) q[kk] = *reinterpret_cast<const uint4*>(qp + kk * 32 + q4 * 8);
-    const float2* rs = reinterpret_cast<const float2*>(p.pf_rowstat) + ((size_t)unit * p.G + g) * p.max_chunk;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) stat[i] = rs[min(rt * 16 + q4 * 4 + i, L - 1)];   // results: rows rt*16 + q4*4 + i
-  };
-  int item = wave;
-  if (item < n_items) fetch(item, qa, st);
-  for (; item < n_items; item += WAVES) {
-    const bool more = item + WAVES < n_items;
-    if (more) fetch(item + WAVES, qn, stn);
-    const int rt = first_rt + item % (n_rt - first_rt);
-    const bool need_mask = !is_cache ? (col0 + COL_TILE - 1 > rt * 16) : false;   // causal diagonal inside the tile
-    const bool tail_rows = rt * 16 + 15 >= L;
-#pragma unroll
-    for (int bk = 0; bk < 4; ++bk) {
-      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < KS; ++kk) acc = mfma16(qa[kk], kb[bk][kk], acc);
-      const int col = col0 + bk * 16 + lr;
-      float add = 0.f;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float pr = fast_exp2(fmaf(acc[i], sc, -st[i].x)) * st[i].y;
-        if (need_mask || tail_rows) {
-          const int row = rt * 16 + q4 * 4 + i;
-          pr = (row < L && (is_cache || col <= row)) ? pr : 0.f;
-        }
-        add += pr;
-      }
-      cs[bk] += colvis[bk] ? add : 0.f;
+  // One item = one 16-row tile of one query head against the 64 columns.  Items are dealt round robin
+  // to the waves.  Q rows are 8 KB apart in the caller's [B, L, H, d] layout, so they are fetched as whole
+  // rows (16 lanes per row), parked in a wave-private LDS tile and read back in MFMA operand order.  The
+  // next item's rows and row statistics are requested before this item's MFMAs (two named register sets).
+  const int q_lrow = lane / LPR, q_lpart = lane % LPR;      // this lane's row (of each group of 64/LPR rows) and piece
+  uint16_t* myq = sm_q[wave];
+  auto fetch = [&](uint4& iq0, uint4& iq1, uint4& iq2, uint4& iq3, float4& is01, float4& is23, int g, int rt) {
+    const uint16_t* qp = Q + ((size_t)b * L) * q_row_stride + (size_t)(kvh * p.G + g) * D + q_lpart * 8;
+    auto row = [&](int x) { return qp + (size_t)min(rt * 16 + q_lrow + x * (64 / LPR), Lm1) * q_row_stride; };
+    iq0 = *reinterpret_cast<const uint4*>(row(0));
+    iq1 = *reinterpret_cast<const uint4*>(row(1));
+    if constexpr (QLOADS > 2) {
+      iq2 = *reinterpret_cast<const uint4*>(row(2));
+      iq3 = *reinterpret_cast<const uint4*>(row(3));
     }
-    if (more) {
-#pragma unroll
-      for (int kk = 0; kk < KS; ++kk) qa[kk] = qn[kk];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) st[i] = stn[i];
+    // results land on rows rt*16 + q4*4 + {0..3}: their (max, 1/sum) pairs are 32 contiguous bytes
+    // (rows past L hold stale values; the array is padded and those rows are masked out below)
+    const float* rs = p.pf_rowstat + (((size_t)unit * p.G + g) * p.max_chunk + rt * 16 + q4 * 4) * 2;
+    is01 = *reinterpret_cast<const float4*>(rs);
+    is23 = *reinterpret_cast<const float4*>(rs + 4);
+  };
+  auto compute = [&](const uint4& iq0, const uint4& iq1, const uint4& iq2, const uint4& iq3, const float4& is01,
+                     const float4& is23, int rt) {
+    // rows of the tile past L, or the causal diagonal
+    const bool special = (rt * 16 + 15 > Lm1) || (!is_cache && col0 + COL_TILE - 1 > rt * 16);
+    const float m0 = is01.x, i0 = is01.y, m1 = is01.z, i1 = is01.w;
+    const float m2 = is23.x, i2 = is23.y, m3 = is23.z, i3 = is23.w;
+    // rows -> LDS -> A operands (row lr, k = ks*32 + q4*8 ..)
+    uint16_t* wq = myq + q_lrow * QSTRIDE + q_lpart * 8;
+    *reinterpret_cast<uint4*>(wq) = iq0;
+    *reinterpret_cast<uint4*>(wq + (64 / LPR) * QSTRIDE) = iq1;
+    if constexpr (QLOADS > 2) {
+      *reinterpret_cast<uint4*>(wq + 2 * (64 / LPR) * QSTRIDE) = iq2;
+      *reinterpret_cast<uint4*>(wq + 3 * (64 / LPR) * QSTRIDE) = iq3;
+    }
+    __builtin_amdgcn_wave_barrier();
+    const uint16_t* rq = myq + lr * QSTRIDE + q4 * 8;
+    const uint4 a0 = *reinterpret_cast<const uint4*>(rq);
+    const uint4 a1 = *reinterpret_cast<const uint4*>(rq + 32);
+    uint4 a2 = a0, a3 = a1;
+    if constexpr (KS > 2) {
+      a2 = *reinterpret_cast<const uint4*>(rq + 64);
+      a3 = *reinterpret_cast<const uint4*>(rq + 96);
+    }
+    __builtin_amdgcn_wave_barrier();
+    auto block = [&](int bk, float& cs) {
+      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+      acc = mfma16(a0, kb[bk][0], acc);
+      acc = mfma16(a1, kb[bk][1], acc);
+      if constexpr (KS > 2) {
+        acc = mfma16(a2, kb[bk][2], acc);
+        acc = mfma16(a3, kb[bk][3], acc);
+      }
+      float p0 = fast_exp2(fmaf(acc[0], sc, -m0)) * i0;
+      float p1 = fast_exp2(fmaf(acc[1], sc, -m1)) * i1;
+      float p2 = fast_exp2(fmaf(acc[2], sc, -m2)) * i2;
+      float p3 = fast_exp2(fmaf(acc[3], sc, -m3)) * i3;
+      if (special) {
+        const int col = col0 + bk * 16 + lr, row = rt * 16 + q4 * 4;
+        p0 = (row + 0 <= Lm1 && (is_cache || col <= row + 0)) ? p0 : 0.f;
+        p1 = (row + 1 <= Lm1 && (is_cache || col <= row + 1)) ? p1 : 0.f;
+        p2 = (row + 2 <= Lm1 && (is_cache || col <= row + 2)) ? p2 : 0.f;
+        p3 = (row + 3 <= Lm1 && (is_cache || col <= row + 3)) ? p3 : 0.f;
+      }
+      cs += (p0 + p1) + (p2 + p3);
+    };
+    block(0, cs0); block(1, cs1); block(2, cs2); block(3, cs3);
+  };
+  const uint4 z4 = make_uint4(0, 0, 0, 0);
+  const float4 zf = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int g = 0; g < p.G; ++g) {
+    uint4 aq0 = z4, aq1 = z4, aq2 = z4, aq3 = z4, bq0 = z4, bq1 = z4, bq2 = z4, bq3 = z4;
+    float4 as01 = zf, as23 = zf, bs01 = zf, bs23 = zf;
+    int rt = first_rt + wave;
+    if (rt < n_rt) fetch(aq0, aq1, aq2, aq3, as01, as23, g, rt);
+    for (; rt < n_rt; rt += 2 * WAVES) {
+      if (rt + WAVES < n_rt) fetch(bq0, bq1, bq2, bq3, bs01, bs23, g, rt + WAVES);
+      compute(aq0, aq1, aq2, aq3, as01, as23, rt);
+      if (rt + 2 * WAVES < n_rt) fetch(aq0, aq1, aq2, aq3, as01, as23, g, rt + 2 * WAVES);
+      if (rt + WAVES < n_rt) compute(bq0, bq1, bq2, bq3, bs01, bs23, rt + WAVES);
     }
   }
+  float cs[4] = {colvis[0] ? cs0 : 0.f, colvis[1] ? cs1 : 0.f, colvis[2] ? cs2 : 0.f, colvis[3] ? cs3 : 0.f};
 #pragma unroll
   for (int bk = 0; bk < 4; ++bk) {
     cs[bk] += __shfl_xor(cs[bk], 16, 64);
