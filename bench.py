@@ -33,9 +33,11 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 PREFILL_CHUNK = 512
 
-# HBM bytes per decode launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/),
-# scaled by a copy kernel of known size.  None until measured for the current kernel.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per decode launch measured with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per
+# dispatch), each scaled by what the same counter reads for a 1 GiB device copy (`--calibrate-copy`):
+# FETCH_SIZE reads 0.5 KiB per KiB copied (factor 2.0), WRITE_SIZE 1.0 (factor 1.0).
+# 132,966 KiB x 2.0 read + 4,655 KiB written (profiles/decode_fused_kernel_hbm_traffic.txt).
+MEASURED_TRAFFIC_BYTES = (132966 * 2 + 4655) * 1024
 
 
 def algorithmic_bytes_per_unit(c=BUDGET, d=HEAD_DIM, G=HEADS // KV_HEADS, esz=2):
@@ -142,6 +144,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-chunk measurement")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of 1 GiB a few times (a kernel of known traffic, for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
     ap.add_argument("--kv-splits", type=int, default=0)
     ap.add_argument("--graph", type=int, default=0, help="replay the timed steps from HIP graphs (1) or launch them (0)")
     args = ap.parse_args()
@@ -154,9 +159,18 @@ def main():
 
     from paper_2501_04987_amd import binding, inputs
 
-    lib = binding.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.full((n,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)                     # reads n bytes, writes n bytes
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "device copy", "bytes_read": n, "bytes_written": n, "launches": 5}))
+        return
+    lib = binding.load()
     K_steps, W = args.steps, args.warmup
 
     layers = [binding.TreeKV(BUDGET, HEADS, HEAD_DIM, kv_heads=KV_HEADS, batch=BATCH, dtype="bf16",

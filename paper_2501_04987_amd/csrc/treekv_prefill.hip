@@ -6,7 +6,7 @@
 // is replayed for the L tokens.  L = 1 gives the decode step.
 //
 // Four launches per chunk:
-//   attend   grid (row tiles, G, U).  Flash-style pass over all visible columns with MFMA:
+//   attend   grid row tiles x G x U (ids remapped so that a unit's row tiles share an XCD's L2).  Flash-style pass over all visible columns with MFMA:
 //            S^T = K Q^T (16x16x32 bf16), online softmax in registers, O^T += V^T P^T with P
 //            split into two bf16 halves (hi + lo) so that rounding P costs 2^-16, not 2^-9.
 //            Writes O and the final row statistics (max, 1/sum).
@@ -94,7 +94,7 @@ template <int D>
 __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, const uint16_t* __restrict__ Q,
                                                                     const uint16_t* __restrict__ Kc,
                                                                     const uint16_t* __restrict__ Vc, int L,
-                                                                    float* __restrict__ out) {
+                                                                    int row_tiles, float* __restrict__ out) {
   using Lds = AttendLds<D>;
   constexpr int KS = D / 32;          // k-steps of the q.k contraction
   constexpr int DB = D / 16;          // 16-wide blocks of the head dimension
@@ -107,7 +107,13 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   uint16_t* sK = pf_smem;                               // [2][K_ELEMS]
   uint16_t* sVt = pf_smem + 2 * Lds::K_ELEMS;           // [2][V_ELEMS]
 
-  const int row_tile = blockIdx.x, g = blockIdx.y, unit = blockIdx.z;
+  // Workgroups are dealt to the 8 XCDs round robin by their linear id, and each XCD has its own L2.
+  // The row tiles of one unit read the same K and V, so give them ids that land on one XCD:
+  // workgroup w works on item (w % 8) * (n/8) + w / 8 of the (row tile fastest) item list.
+  const int n_items = row_tiles * p.G * p.U, per_xcd = (n_items + 7) / 8;
+  const int item = ((int)blockIdx.x % 8) * per_xcd + (int)blockIdx.x / 8;
+  if (item >= n_items) return;
+  const int row_tile = item % row_tiles, g = (item / row_tiles) % p.G, unit = item / (row_tiles * p.G);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, q4 = lane >> 4;
   const int half = wave >> 2;                              // which 32 columns of every tile
@@ -699,7 +705,8 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
   if (lds > 48 * 1024 &&
       hipFuncSetAttribute((const void*)attend, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
     return TREEKV_EHIP;
-  hipLaunchKernelGGL(attend, dim3(row_tiles, p.G, p.U), dim3(AT_THREADS), lds, s, p, q, k, v, L, out);
+  const int n_items = row_tiles * p.G * p.U;
+  hipLaunchKernelGGL(attend, dim3((n_items + 7) / 8 * 8), dim3(AT_THREADS), lds, s, p, q, k, v, L, row_tiles, out);
   const int col_tiles = (p.cap + COL_TILE - 1) / COL_TILE + (L + COL_TILE - 1) / COL_TILE;
   hipLaunchKernelGGL((prefill_colsum_kernel<D>), dim3(col_tiles, p.U), dim3(PF_THREADS), 0, s, p, q, k, L);
   hipLaunchKernelGGL(prefill_replay_kernel, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, retained, n_retained, evicted);
