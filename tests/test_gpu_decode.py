@@ -136,3 +136,45 @@ def test_llama7b_shaped_layer_sampled(binding, oracle):
     ret = gpu["retained"][T - 1][0]
     assert np.all(np.diff(ret, axis=-1) > 0)
     assert np.all(ret[:, :4] == np.arange(4)) and np.all(ret[:, -508:] == np.arange(T - 508, T))
+
+
+def test_benchmark_launch_configuration_sampled(binding, oracle):
+    """The shape bench.py times: batch 8 x 32 heads x 128, bf16, budget 2048 (4 + 1024 + 1020), one workgroup per
+    unit (256 units).  Caches are filled with four 512-token prefill chunks as in the benchmark, then 300 decode
+    steps run with evictions; the oracle audits 6 of the 256 streams call by call, every stream is checked for the
+    properties that hold at any size."""
+    B, H, d, budget, steps = 8, 32, 128, 2048, 300
+    T = budget + steps
+    Q, K, V = inputs.batch_streams("lowrank", 1, T, B, H, 1, d, dtype="bf16", seed_per_batch=True)
+    kv = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=4, n_recent=1020)
+    assert kv.cfg.kv_splits == 1
+    units = [(0, 0), (1, 7), (3, 31), (4, 16), (6, 9), (7, 30)]
+    st = ph.run_schedule(oracle, kv, Q, K, V, [512] * 4 + [0] * steps, dtype="bf16", units=units)
+    err = ph.compare_scores(kv, st["results"], "bf16")
+    print(f"  flagged={st['flagged']}/{st['decisions']} max_err={st['max_err']:.2e} score_err={err:.2e}")
+    assert st["decisions"] == len(units) * steps and st["flagged"] <= 2
+    import torch
+
+    out, ret, nret, ev = kv.new_outputs()
+    kv.decode_step(ph.to_device(Q[T - 1], "bf16"), ph.to_device(K[T - 1], "bf16"), ph.to_device(V[T - 1], "bf16"),
+                   out, ret, nret, ev)                    # one more step for all 256 units (inputs reused)
+    torch.cuda.synchronize()
+    ret, nret, ev = ret.cpu().numpy(), nret.cpu().numpy(), ev.cpu().numpy()
+    assert np.all(nret == budget) and np.all(np.diff(ret, axis=-1) > 0)
+    assert np.all(ret[..., :4] == np.arange(4)) and np.all(ret[..., -1020:] == np.arange(T + 1 - 1020, T + 1))
+    assert np.all((ev >= 4) & (ev < T + 1 - 1020)) and np.all(np.isfinite(out.cpu().numpy()))
+
+
+def test_gqa_long_budget_split_path_sampled(binding, oracle):
+    """32 query heads on 8 KV heads, head_dim 128, bf16, budget 4096, batch 16: 128 units, so the slots of a unit
+    are split over several workgroups and merged by the second kernel; scores add up the group's 4 query heads."""
+    B, H, Hkv, d, budget = 16, 32, 8, 128, 4096
+    sched = [512] * 9 + [0] * 40
+    T = 512 * 9 + 40
+    Q, K, V = inputs.batch_streams("lowrank", 2, T, B, Hkv, H // Hkv, d, dtype="bf16", seed_per_batch=True)
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=4, n_recent=2044)
+    assert kv.cfg.kv_splits > 1
+    st = ph.run_schedule(oracle, kv, Q, K, V, sched, dtype="bf16", units=[(0, 0), (9, 5), (15, 7)])
+    err = ph.compare_scores(kv, st["results"], "bf16")
+    print(f"  flagged={st['flagged']}/{st['decisions']} max_err={st['max_err']:.2e} score_err={err:.2e}")
+    assert st["decisions"] == 3 * (T - budget)
