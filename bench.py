@@ -29,6 +29,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 LAYERS, BATCH, HEADS, KV_HEADS, HEAD_DIM, BUDGET = 32, 8, 32, 32, 128, 2048
+# Other decode shapes of the configuration list, selectable with --workload for side measurements
+# (they replace the constants above; the default, and the headline, is "graded").
+WORKLOADS = {
+    "graded": dict(LAYERS=32, BATCH=8, HEADS=32, KV_HEADS=32, BUDGET=2048,
+                   name="configs[2]: 32 layers x 32 heads x 128 dim, bf16, budget 2048 "
+                        "(4 sink + 1024 tree + 1020 recent), batch 8, caches full"),
+    "llama7b-1k": dict(LAYERS=32, BATCH=1, HEADS=32, KV_HEADS=32, BUDGET=1024,
+                       name="configs[1] shape: 32 layers x 32 heads x 128 dim, bf16, budget 1024 (4 + 512 + 508), "
+                            "batch 1, caches full"),
+    "gqa-4k": dict(LAYERS=8, BATCH=16, HEADS=32, KV_HEADS=8, BUDGET=4096,
+                   name="configs[4] shape: 8 layers x (32 query / 8 KV heads) x 128 dim, bf16, budget 4096 "
+                        "(4 + 2048 + 2044), batch 16, caches full"),
+}
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 PREFILL_CHUNK = 512
@@ -40,8 +53,10 @@ PREFILL_CHUNK = 512
 MEASURED_TRAFFIC_BYTES = (132966 * 2 + 4655) * 1024
 
 
-def algorithmic_bytes_per_unit(c=BUDGET, d=HEAD_DIM, G=HEADS // KV_HEADS, esz=2):
+def algorithmic_bytes_per_unit(c=None, d=HEAD_DIM, G=None, esz=2):
     """Bytes one (batch, KV head) unit must move in one decode step with a full cache."""
+    c = BUDGET if c is None else c
+    G = HEADS // KV_HEADS if G is None else G
     kv = 2 * (c + 1) * d * esz          # K and V rows, read once
     s = 2 * (c + 1) * 4                 # scores read + written
     pos = (c + 1) * 4                   # positions read for the retained list
@@ -148,12 +163,19 @@ def main():
                     help="only run a plain device copy of 1 GiB a few times (a kernel of known traffic, for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
     ap.add_argument("--kv-splits", type=int, default=0)
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="graded")
     ap.add_argument("--graph", type=int, default=0, help="replay the timed steps from HIP graphs (1) or launch them (0)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (every TreeKV stream is independent; there is no "
               "multi-GPU path to time); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    global LAYERS, BATCH, HEADS, KV_HEADS, BUDGET
+    wl = WORKLOADS[args.workload]
+    LAYERS, BATCH, HEADS, KV_HEADS, BUDGET = wl["LAYERS"], wl["BATCH"], wl["HEADS"], wl["KV_HEADS"], wl["BUDGET"]
+    if args.workload != "graded":
+        args.no_prefill = args.no_cpu_baseline = True
 
     import torch
 
@@ -267,12 +289,12 @@ def main():
     bytes_per_launch = algorithmic_bytes_per_unit() * BATCH * KV_HEADS
     achieved = bytes_per_launch / (launch_us * 1e-6) / 1e9
     res = {
-        "metric": "decode steps/s (one token for 8 sequences through 32 layers; 32h x 128d, cache 2048, bf16)",
+        "metric": "decode steps/s (one token for 8 sequences through 32 layers; 32h x 128d, cache 2048, bf16)"
+                  if args.workload == "graded" else f"decode steps/s ({args.workload})",
         "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": K_steps, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 storage, fp32 arithmetic", "data": "synthetic",
-        "config": {"workload": "configs[2]: 32 layers x 32 heads x 128 dim, bf16, budget 2048 "
-                               "(4 sink + 1024 tree + 1020 recent), batch 8, caches full",
+        "config": {"workload": wl["name"],
                    "layers": LAYERS, "batch": BATCH, "heads": HEADS, "kv_heads": KV_HEADS, "head_dim": HEAD_DIM,
                    "budget": BUDGET, "kv_splits": int(cfg.kv_splits), "launch": "hip graph" if graphs else "stream",
                    "filled_by": "prefill chunks of 512" if has_prefill else "decode steps"},
@@ -280,7 +302,7 @@ def main():
         "layer_steps_per_s": steps_per_s * LAYERS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": "decode_fused_kernel<bf16,128,1>", "bytes_per_launch": bytes_per_launch,
+                     "kernel": "decode_fused_kernel<bf16,128,1>" if int(cfg.kv_splits) == 1 else "decode_split_kernel + decode_merge_kernel", "bytes_per_launch": bytes_per_launch,
                      "launch_us": launch_us,
                      "note": "launch_us = HIP-event time of the timed region / number of decode launches "
                              "(gaps between launches included)"},

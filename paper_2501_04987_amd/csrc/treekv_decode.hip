@@ -6,7 +6,7 @@
 //          in LDS, scores and tree positions are prefetched into registers before the streaming
 //          starts, so the epilogue (score update, eviction, retained list) waits for no global
 //          load.  Used when U alone fills the chip.
-//   SPLIT  two kernels.  grid = (nsplit, U) workgroups of 256 threads each stream a slice of the
+//   SPLIT  two kernels.  grid = (nsplit, U) workgroups of 512 threads each stream a slice of the
 //          unit's slots and write a partial (output accumulator, max, sum) plus the slice's
 //          logits to scratch; a second kernel with one workgroup per unit merges the slices and
 //          runs the same epilogue.  The kernel boundary is the only synchronisation.
@@ -48,7 +48,7 @@ __device__ inline void store_maybe_nt(V v, V* ptr) {
   else *ptr = v;
 }
 constexpr int FUSED_THREADS = TKV_FUSED_THREADS;
-constexpr int SPLIT_THREADS = 256;
+constexpr int SPLIT_THREADS = 512;
 constexpr int MERGE_THREADS = 512;
 constexpr int KU = TKV_KU;             // wave loads of K (and of V) per tile
 constexpr float NEG_BIG = -1.0e30f;

@@ -143,13 +143,13 @@ int record_hip(treekv_ctx* ctx, int rc) {
 }
 
 int pick_splits(const treekv_config& c) {
-  // With about 200 units or more, one 1024-thread workgroup per unit fills the chip and keeps the
-  // whole step in one workgroup.  Below that, split every unit's slots over enough 256-thread
-  // workgroups to put about four on each of the 256 compute units, but keep a split at 128 slots
-  // or more (below that the merge costs more than the streaming it spreads).
+  // With about 200 units or more, one 512-thread workgroup per unit fills the 256 compute units and
+  // keeps the whole step in one kernel.  Below that, split every unit's slots over a few 512-thread
+  // workgroups (measured best: about 160 workgroups in all; 128 units -> 2 slices, 32 units -> 5), but keep
+  // a slice at 128 slots or more (below that the merge costs more than the streaming it spreads).
   const int units = c.batch * c.kv_heads;
   if (units >= 192) return 1;
-  int splits = (1024 + units - 1) / units;
+  int splits = (160 + units - 1) / units;
   const int max_by_len = (c.budget + 1 + 127) / 128;
   if (splits > max_by_len) splits = max_by_len;
   if (splits > 32) splits = 32;
