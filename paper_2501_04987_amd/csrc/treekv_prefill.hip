@@ -68,28 +68,31 @@ __device__ inline unsigned pack_bf16(float a, float b) {
   return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
 }
 
-constexpr int AT_THREADS = 512;   // 8 waves: waves 0-3 take columns 0-31 of every 64-column tile, waves 4-7 columns 32-63
+constexpr int AT_THREADS = 512;   // 8 waves
+constexpr int AT_COLS = 128;      // columns per staged tile of the attend kernel
 
 template <int D>
 struct AttendLds {
   static constexpr int KSTRIDE = D + 8;          // bf16 elements per staged K row (padded: conflict-free b128 reads)
-  static constexpr int VSTRIDE = COL_TILE + 8;   // bf16 elements per staged V^T row
-  static constexpr int K_ELEMS = COL_TILE * KSTRIDE;
+  static constexpr int VSTRIDE = AT_COLS + 8;    // bf16 elements per staged V^T row
+  static constexpr int K_ELEMS = AT_COLS * KSTRIDE;
   static constexpr int V_ELEMS = D * VSTRIDE;
   static constexpr size_t BYTES = 2 * (size_t)(K_ELEMS + V_ELEMS) * sizeof(uint16_t);   // two stages
 };
 
-// Staged V^T layout.  Row d holds the tile's 64 columns in the order the P^T operand uses them:
-// column j sits at position (j/32)*32 + ((j%16)/4)*8 + ((j%32)/16)*4 + j%4, so that the 8 k-slots of
-// lane group q4 in half h (columns h*32 + q4*4 + {0..3} and h*32 + 16 + q4*4 + {0..3}) are the 16
-// contiguous bytes of "pair" h*4 + q4.  Pairs are XOR-swizzled with (d/16)%8: the 16 lanes of an operand
-// read share d/16, so reads stay conflict free, while the transposing 8-byte writes of 16 lanes (same
-// columns, rows 8 apart) spread over all banks.
+// Work split.  A workgroup owns 64 query rows of one head and walks over the visible columns in
+// tiles of 128.  Its 8 waves are 2 row groups (32 rows = two 16-row MFMA blocks) x 4 column quarters
+// (32 columns of every tile): each K / V^T operand read from LDS feeds the MFMAs of two row blocks,
+// and two waves share a SIMD so that one's exp / convert work overlaps the other's MFMAs.  Every wave
+// keeps its own online-softmax state per row block; the four quarters of a row group are merged through
+// LDS at the end.  Threads 0-255 stage V (transposing), threads 256-511 stage K.
 //
-// Work split.  A workgroup owns 64 query rows of one head.  Wave w and wave w+4 both own rows
-// 16*(w%4)..+15 and split every tile's columns in halves, each with its own online-softmax state; two
-// waves per SIMD let one wave's exp/convert work overlap the other's MFMAs.  The halves are merged
-// through LDS at the end.  Threads 0-255 stage V (transposing), threads 256-511 stage K.
+// Staged V^T layout.  Row d holds the tile's columns in the order the P^T operand uses them: inside
+// quarter c, column j sits at position c*32 + ((j%16)/4)*8 + ((j%32)/16)*4 + j%4, so that the 8 k-slots of
+// lane group q4 (columns c*32 + q4*4 + {0..3} and c*32 + 16 + q4*4 + {0..3}) are the 16 contiguous
+// bytes of "pair" c*4 + q4.  Pairs are XOR-swizzled with (d/16)%8: the 16 lanes of an operand read share
+// d/16, so reads stay conflict free, while the transposing 8-byte writes of 16 lanes (same columns, rows 8
+// apart) spread over the banks.
 template <int D>
 __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, const uint16_t* __restrict__ Q,
                                                                     const uint16_t* __restrict__ Kc,
@@ -99,10 +102,11 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   constexpr int KS = D / 32;          // k-steps of the q.k contraction
   constexpr int DB = D / 16;          // 16-wide blocks of the head dimension
   constexpr int PARTS = D / 8;        // 16-byte pieces per row
-  constexpr int KCH = COL_TILE * PARTS / 256;          // K pieces per K-staging thread (2 or 4)
-  static_assert(KCH == 2 || KCH == 4, "staging is written for head_dim 64 and 128");
-  constexpr int NVBLK = (COL_TILE / 4) * PARTS;        // 4-column x 8-dim V blocks per tile (128 or 256)
+  constexpr int KCH = AT_COLS * PARTS / 256;           // K pieces per K-staging thread (4 or 8)
+  constexpr int VBL = (AT_COLS / 4) * PARTS / 256;     // 4-column x 8-dim V blocks per V-staging thread (1 or 2)
+  static_assert((KCH == 4 || KCH == 8) && (VBL == 1 || VBL == 2), "staging is written for head_dim 64 and 128");
   constexpr int KROWS_PER_X = 256 / PARTS;             // rows between a K thread's consecutive pieces
+  constexpr int VJG_PER_X = 256 / PARTS;               // column groups between a V thread's two blocks
   extern __shared__ __attribute__((aligned(16))) uint16_t pf_smem[];
   uint16_t* sK = pf_smem;                               // [2][K_ELEMS]
   uint16_t* sVt = pf_smem + 2 * Lds::K_ELEMS;           // [2][V_ELEMS]
@@ -116,18 +120,24 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const int row_tile = item % row_tiles, g = (item / row_tiles) % p.G, unit = item / (row_tiles * p.G);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, q4 = lane >> 4;
-  const int half = wave >> 2;                              // which 32 columns of every tile
+  const int rg = wave & 1;                                 // row group: rows 32*rg .. +31 of the workgroup's 64
+  const int cq = wave >> 1;                                // column quarter of every tile
   const int kvh = unit % p.Hkv, b = unit / p.Hkv;
   const int h = kvh * p.G + g;
   const ChunkInfo ci = load_chunk_info(p.meta + (size_t)unit * META_STRIDE);
 
-  const int row0 = row_tile * ROW_TILE + (wave & 3) * 16;  // first chunk row of this wave
-  const int my_row = row0 + lr;                            // the query row this lane's results belong to
-  const int ld_row = min(my_row, L - 1);
-  const uint16_t* qp = Q + (((size_t)b * L + ld_row) * p.H + h) * D;
-  uint4 qa[KS];
+  const int row0 = row_tile * ROW_TILE + rg * 32;          // first chunk row of this wave
+  const int my_row0 = row0 + lr, my_row1 = row0 + 16 + lr; // the query rows this lane's results belong to
+  uint4 qa0[KS], qa1[KS];                                  // B operands: Q rows of the two row blocks
+  {
+    const uint16_t* q0p = Q + (((size_t)b * L + min(my_row0, L - 1)) * p.H + h) * D + q4 * 8;
+    const uint16_t* q1p = Q + (((size_t)b * L + min(my_row1, L - 1)) * p.H + h) * D + q4 * 8;
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) qa[ks] = *reinterpret_cast<const uint4*>(qp + ks * 32 + q4 * 8);
+    for (int ks = 0; ks < KS; ++ks) {
+      qa0[ks] = *reinterpret_cast<const uint4*>(q0p + ks * 32);
+      qa1[ks] = *reinterpret_cast<const uint4*>(q1p + ks * 32);
+    }
+  }
 
   const uint16_t* Ku = (const uint16_t*)p.K + (size_t)unit * p.cap * D;
   const uint16_t* Vu = (const uint16_t*)p.V + (size_t)unit * p.cap * D;
@@ -135,61 +145,70 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const uint16_t* Kcu = Kc + ((size_t)b * L * p.Hkv + kvh) * D;
   const uint16_t* Vcu = Vc + ((size_t)b * L * p.Hkv + kvh) * D;
 
-  const int cache_tiles = (ci.n + 1 + COL_TILE - 1) / COL_TILE;        // slots [0, n], the free one masked
+  const int cache_tiles = (ci.n + 1 + AT_COLS - 1) / AT_COLS;          // slots [0, n], the free one masked
   const int last_row = min(row_tile * ROW_TILE + ROW_TILE, L) - 1;     // last chunk row of the workgroup
-  const int chunk_tiles = last_row / COL_TILE + 1;                     // causal: columns <= last_row
+  const int chunk_tiles = last_row / AT_COLS + 1;                      // causal: columns <= last_row
   const int ntiles = cache_tiles + chunk_tiles;
 
   // ---- staging: global -> registers -> LDS (named registers: arrays here end up in scratch memory) ----
-  uint4 g0, g1, g2, g3;
-  g0 = g1 = g2 = g3 = make_uint4(0, 0, 0, 0);
+  uint4 g0, g1, g2, g3, g4, g5, g6, g7;
+  g0 = g1 = g2 = g3 = g4 = g5 = g6 = g7 = make_uint4(0, 0, 0, 0);
   const bool v_role = tid < 256;
   const int st = tid & 255;
-  // V role: block of columns v_jg*4..+3, dims v_part*8..+7.  K role: pieces st + x*256.
+  // V role: blocks of columns (v_jg + x*VJG_PER_X)*4..+3, dims v_part*8..+7.  K role: pieces st + x*256.
   const int v_part = st % PARTS, v_jg = st / PARTS;
-  const bool v_active = v_role && (NVBLK >= 256 || st < NVBLK);
   const int k_r0 = st / PARTS, k_part = st % PARTS;
-  const int first_row = v_role ? v_jg * 4 : k_r0;                       // first tile row this thread loads
-  const int row_step = v_role ? 1 : KROWS_PER_X;                        // rows between its loads
-  const int col_off = (v_role ? v_part : k_part) * 8;
-  const uint16_t* cache_base = (v_role ? Vu : Ku) + col_off;
-  const uint16_t* chunk_base = (v_role ? Vcu : Kcu) + col_off;
+  const uint16_t* cache_base = (v_role ? Vu : Ku) + (v_role ? v_part : k_part) * 8;
+  const uint16_t* chunk_base = (v_role ? Vcu : Kcu) + (v_role ? v_part : k_part) * 8;
   const int cache_lim = p.cap - 1, chunk_lim = L - 1;                   // last row that exists
-  const bool do_load = !v_role || v_active;
-  const bool four_loads = v_role || KCH > 2;
   auto load_regs = [&](int tile) {
     const bool is_cache = tile < cache_tiles;
-    const int col0 = is_cache ? tile * COL_TILE : (tile - cache_tiles) * COL_TILE;
+    const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
     const uint16_t* base = is_cache ? cache_base : chunk_base;
     const int rstride = is_cache ? D : chunk_row_stride;
     const int lim = is_cache ? cache_lim : chunk_lim;
-    const int r = col0 + first_row;
-    if (do_load) {
-      g0 = *reinterpret_cast<const uint4*>(base + (size_t)min(r, lim) * rstride);
-      g1 = *reinterpret_cast<const uint4*>(base + (size_t)min(r + row_step, lim) * rstride);
-      if (four_loads) {
-        g2 = *reinterpret_cast<const uint4*>(base + (size_t)min(r + 2 * row_step, lim) * rstride);
-        g3 = *reinterpret_cast<const uint4*>(base + (size_t)min(r + 3 * row_step, lim) * rstride);
+    auto ld = [&](int r) { return *reinterpret_cast<const uint4*>(base + (size_t)min(col0 + r, lim) * rstride); };
+    if (v_role) {
+      const int r = v_jg * 4;
+      g0 = ld(r); g1 = ld(r + 1); g2 = ld(r + 2); g3 = ld(r + 3);
+      if constexpr (VBL > 1) {
+        const int r2 = r + VJG_PER_X * 4;
+        g4 = ld(r2); g5 = ld(r2 + 1); g6 = ld(r2 + 2); g7 = ld(r2 + 3);
+      }
+    } else {
+      g0 = ld(k_r0); g1 = ld(k_r0 + KROWS_PER_X); g2 = ld(k_r0 + 2 * KROWS_PER_X); g3 = ld(k_r0 + 3 * KROWS_PER_X);
+      if constexpr (KCH > 4) {
+        g4 = ld(k_r0 + 4 * KROWS_PER_X); g5 = ld(k_r0 + 5 * KROWS_PER_X);
+        g6 = ld(k_r0 + 6 * KROWS_PER_X); g7 = ld(k_r0 + 7 * KROWS_PER_X);
       }
     }
   };
   // LDS destinations do not depend on the tile: byte offsets inside one stage
   const int k_dst = (k_r0 * Lds::KSTRIDE + k_part * 8) * 2;
-  const int v_pair = ((v_jg / 8) * 4 + (v_jg % 4)) ^ ((v_part >> 1) & 7);   // (d/16)%8 == v_part/2 for all 8 dims
-  const int v_dst = ((v_part * 8) * Lds::VSTRIDE + v_pair * 8 + ((v_jg % 8) / 4) * 4) * 2;
+  auto v_dst_of = [&](int jg) {        // column group jg (4 columns) of the tile, this thread's 8 dims
+    const int c = jg / 8, jq = jg % 8;                                  // quarter, group inside the quarter
+    const int pair = (c * 4 + (jq % 4)) ^ ((v_part >> 1) & 7);          // (d/16)%8 == v_part/2 for all 8 dims
+    return ((v_part * 8) * Lds::VSTRIDE + pair * 8 + (jq / 4) * 4) * 2;
+  };
+  const int v_dst0 = v_dst_of(v_jg), v_dst1 = v_dst_of(v_jg + VJG_PER_X);
   auto store_lds = [&](int buf) {
     if (!v_role) {
       char* k = reinterpret_cast<char*>(sK + buf * Lds::K_ELEMS) + k_dst;
+      constexpr int step = KROWS_PER_X * Lds::KSTRIDE * 2;
       *reinterpret_cast<uint4*>(k) = g0;
-      *reinterpret_cast<uint4*>(k + KROWS_PER_X * Lds::KSTRIDE * 2) = g1;
-      if constexpr (KCH > 2) {
-        *reinterpret_cast<uint4*>(k + 2 * KROWS_PER_X * Lds::KSTRIDE * 2) = g2;
-        *reinterpret_cast<uint4*>(k + 3 * KROWS_PER_X * Lds::KSTRIDE * 2) = g3;
+      *reinterpret_cast<uint4*>(k + step) = g1;
+      *reinterpret_cast<uint4*>(k + 2 * step) = g2;
+      *reinterpret_cast<uint4*>(k + 3 * step) = g3;
+      if constexpr (KCH > 4) {
+        *reinterpret_cast<uint4*>(k + 4 * step) = g4;
+        *reinterpret_cast<uint4*>(k + 5 * step) = g5;
+        *reinterpret_cast<uint4*>(k + 6 * step) = g6;
+        *reinterpret_cast<uint4*>(k + 7 * step) = g7;
       }
-    } else if (v_active) {
-      char* v = reinterpret_cast<char*>(sVt + buf * Lds::V_ELEMS) + v_dst;
+    } else {
+      char* vb = reinterpret_cast<char*>(sVt + buf * Lds::V_ELEMS);
       // dword w of the four rows holds dims 2w, 2w+1 of columns +0..+3: regroup into one 8-byte word per dim
-      auto emit = [&](unsigned a0, unsigned a1, unsigned a2, unsigned a3, int e_even) {
+      auto emit = [&](char* v, unsigned a0, unsigned a1, unsigned a2, unsigned a3, int e_even) {
 #pragma unroll
         for (int odd = 0; odd < 2; ++odd) {
           const unsigned sel = odd ? 0x07060302u : 0x05040100u;       // the odd / even bf16 of both dwords
@@ -199,61 +218,32 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
           *reinterpret_cast<uint2*>(v + (e_even + odd) * Lds::VSTRIDE * 2) = o;
         }
       };
-      emit(g0.x, g1.x, g2.x, g3.x, 0);
-      emit(g0.y, g1.y, g2.y, g3.y, 2);
-      emit(g0.z, g1.z, g2.z, g3.z, 4);
-      emit(g0.w, g1.w, g2.w, g3.w, 6);
+      char* v0 = vb + v_dst0;
+      emit(v0, g0.x, g1.x, g2.x, g3.x, 0); emit(v0, g0.y, g1.y, g2.y, g3.y, 2);
+      emit(v0, g0.z, g1.z, g2.z, g3.z, 4); emit(v0, g0.w, g1.w, g2.w, g3.w, 6);
+      if constexpr (VBL > 1) {
+        char* v1 = vb + v_dst1;
+        emit(v1, g4.x, g5.x, g6.x, g7.x, 0); emit(v1, g4.y, g5.y, g6.y, g7.y, 2);
+        emit(v1, g4.z, g5.z, g6.z, g7.z, 4); emit(v1, g4.w, g5.w, g6.w, g7.w, 6);
+      }
     }
   };
 
   // operand read offsets (bytes inside one stage), tile independent
-  const int ka_off = ((2 * half * 16 + lr) * Lds::KSTRIDE + q4 * 8) * 2;               // + bk*16 rows, + ks*64 bytes
+  const int ka_off = ((cq * 32 + lr) * Lds::KSTRIDE + q4 * 8) * 2;                     // + bk*16 rows, + ks*64 bytes
   const int va_row = (lr * Lds::VSTRIDE) * 2;
-  const int va0 = va_row + ((q4 ^ 0) * 16), va1 = va_row + ((q4 ^ 1) * 16);            // by d & 3
-  const int va2 = va_row + ((q4 ^ 2) * 16), va3 = va_row + ((q4 ^ 3) * 16);
+  const int va_pair = cq * 4 + q4;                                                     // swizzled with d & 7 per read
 
-  float m_run = NEG_BIG;               // running row max of the raw (unscaled) logits over this wave's columns
-  float l_part = 0.f;
-  f32x4_t oacc[DB];
+  float m0 = NEG_BIG, m1 = NEG_BIG;    // running row max of the raw logits over this wave's columns, per row block
+  float l0 = 0.f, l1 = 0.f;
+  f32x4_t o0[DB], o1[DB];
 #pragma unroll
-  for (int d = 0; d < DB; ++d) oacc[d] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int d = 0; d < DB; ++d) { o0[d] = f32x4_t{0.f, 0.f, 0.f, 0.f}; o1[d] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
   const float sc = p.scale_log2e;
   const int n_cached = ci.n, fslot = ci.fslot;
 
-  load_regs(0);
-  store_lds(0);
-  __syncthreads();
-  for (int tile = 0; tile < ntiles; ++tile) {
-    if (tile + 1 < ntiles) load_regs(tile + 1);            // in flight while this tile is computed
-    const bool is_cache = tile < cache_tiles;
-    const int col0 = is_cache ? tile * COL_TILE : (tile - cache_tiles) * COL_TILE;
-    const char* k = reinterpret_cast<const char*>(sK + (tile & 1) * Lds::K_ELEMS) + ka_off;
-    const char* v = reinterpret_cast<const char*>(sVt + (tile & 1) * Lds::V_ELEMS);
-
-    // S^T block bk of this wave's half: rows = columns col0 + half*32 + bk*16 + q4*4 + i, column = the lane's query row
-    f32x4_t s[2];
-#pragma unroll
-    for (int bk = 0; bk < 2; ++bk) {
-      s[bk] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const uint4 a = *reinterpret_cast<const uint4*>(k + bk * 16 * Lds::KSTRIDE * 2 + ks * 64);
-        s[bk] = mfma16(a, qa[ks], s[bk]);
-      }
-    }
-    // only tiles that touch the end of the cache, the free slot or the causal diagonal need a mask (wave uniform)
-    const bool need_mask = is_cache ? (col0 + COL_TILE - 1 > ci.n || (ci.fslot >= col0 && ci.fslot < col0 + COL_TILE))
-                                    : (col0 + COL_TILE - 1 > row0);
-    if (need_mask) {
-#pragma unroll
-      for (int bk = 0; bk < 2; ++bk)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int col = col0 + half * 32 + bk * 16 + q4 * 4 + i;
-          const bool vis = is_cache ? (col <= ci.n && col != ci.fslot) : (col <= my_row);
-          s[bk][i] = vis ? s[bk][i] : NEG_BIG;
-        }
-    }
+  // softmax of one row block's 8 logits against its running state; returns the packed hi / lo P^T operands
+  auto soft = [&](f32x4_t (&s)[2], float& m_run, float& l_part, f32x4_t (&oacc)[DB], bool need_mask, uint4& phi, uint4& plo) {
     float mx = m_run;
 #pragma unroll
     for (int bk = 0; bk < 2; ++bk)
@@ -261,7 +251,7 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[bk][i]);
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    if (__any(mx != m_run)) {                 // the running max moved for some row of the wave: rescale
+    if (__any(mx != m_run)) {                 // the running max moved for some row of the block: rescale
       const float corr = fast_exp2((m_run - mx) * sc);
       l_part *= corr;
 #pragma unroll
@@ -269,7 +259,7 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       m_run = mx;
     }
     const float neg_ms = -mx * sc;
-    unsigned hi[4], lo[4];                    // P^T operand: k-slots 0-3 = block 0, i = 0..3; k-slots 4-7 = block 1
+    unsigned hi[4], lo[4];                    // k-slots 0-3 = block 0, i = 0..3; k-slots 4-7 = block 1
 #pragma unroll
     for (int e2 = 0; e2 < 4; ++e2) {
       const float s0 = s[e2 >> 1][(e2 & 1) * 2], s1 = s[e2 >> 1][(e2 & 1) * 2 + 1];
@@ -282,35 +272,83 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       hi[e2] = pack_bf16(p0, p1);
       lo[e2] = pack_bf16(p0 - __uint_as_float(hi[e2] << 16), p1 - __uint_as_float(hi[e2] & 0xffff0000u));
     }
-    const uint4 phi = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-    const uint4 plo = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-    // O^T += V^T P^T : A = V^T[d][the same 8 columns], B = P^T (hi and lo parts)
+    phi = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    plo = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+  };
+
+  load_regs(0);
+  store_lds(0);
+  __syncthreads();
+  for (int tile = 0; tile < ntiles; ++tile) {
+    if (tile + 1 < ntiles) load_regs(tile + 1);            // in flight while this tile is computed
+    const bool is_cache = tile < cache_tiles;
+    const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
+    const char* k = reinterpret_cast<const char*>(sK + (tile & 1) * Lds::K_ELEMS) + ka_off;
+    const char* v = reinterpret_cast<const char*>(sVt + (tile & 1) * Lds::V_ELEMS);
+
+    // S^T blocks: rows = columns col0 + cq*32 + bk*16 + q4*4 + i, column = the lane's query row of block 0 / 1
+    f32x4_t s0[2], s1[2];
+#pragma unroll
+    for (int bk = 0; bk < 2; ++bk) {
+      s0[bk] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      s1[bk] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const uint4 a = *reinterpret_cast<const uint4*>(k + bk * 16 * Lds::KSTRIDE * 2 + ks * 64);
+        s0[bk] = mfma16(a, qa0[ks], s0[bk]);
+        s1[bk] = mfma16(a, qa1[ks], s1[bk]);
+      }
+    }
+    // only tiles that touch the end of the cache, the free slot or the causal diagonal need a mask (wave uniform)
+    const bool need_mask = is_cache ? (col0 + AT_COLS - 1 > n_cached || (fslot >= col0 && fslot < col0 + AT_COLS))
+                                    : (col0 + AT_COLS - 1 > row0);
+    if (need_mask) {
+#pragma unroll
+      for (int bk = 0; bk < 2; ++bk)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int col = col0 + cq * 32 + bk * 16 + q4 * 4 + i;
+          const bool cvis = is_cache ? (col <= n_cached && col != fslot) : true;
+          s0[bk][i] = (cvis && (is_cache || col <= my_row0)) ? s0[bk][i] : NEG_BIG;
+          s1[bk][i] = (cvis && (is_cache || col <= my_row1)) ? s1[bk][i] : NEG_BIG;
+        }
+    }
+    uint4 phi0, plo0, phi1, plo1;
+    soft(s0, m0, l0, o0, need_mask, phi0, plo0);
+    soft(s1, m1, l1, o1, need_mask, phi1, plo1);
+    // O^T += V^T P^T : A = V^T[d][the quarter's 8 k-slot columns of this lane group], B = P^T (hi and lo parts)
 #pragma unroll
     for (int d = 0; d < DB; ++d) {
-      const int vo = (d & 3) == 0 ? va0 : (d & 3) == 1 ? va1 : (d & 3) == 2 ? va2 : va3;
-      const uint4 a = *reinterpret_cast<const uint4*>(v + vo + d * 16 * Lds::VSTRIDE * 2 + (((half * 4) ^ (d & 4)) * 16));
-      oacc[d] = mfma16(a, phi, oacc[d]);
-      oacc[d] = mfma16(a, plo, oacc[d]);
+      const uint4 a = *reinterpret_cast<const uint4*>(v + va_row + ((va_pair ^ (d & 7)) * 16) + d * 16 * Lds::VSTRIDE * 2);
+      o0[d] = mfma16(a, phi0, o0[d]);
+      o1[d] = mfma16(a, phi1, o1[d]);
+      o0[d] = mfma16(a, plo0, o0[d]);
+      o1[d] = mfma16(a, plo1, o1[d]);
     }
     if (tile + 1 < ntiles) store_lds((tile + 1) & 1);      // the other stage: last read one barrier ago
     __syncthreads();
   }
 
-  // ---- merge the two column halves of every row (waves w and w+4) through LDS ----
-  float* xch = reinterpret_cast<float*>(pf_smem);           // [4 waves][2 + DB*4][64 lanes]
+  // ---- merge the four column quarters of every row group through LDS ----
+  float* xch = reinterpret_cast<float*>(pf_smem);           // [6 waves][2 blocks][2 + DB*4][64 lanes]
   constexpr int XN = 2 + DB * 4;
-  if (half == 1) {
-    float* dst = xch + ((wave & 3) * XN) * 64 + lane;
-    dst[0] = m_run; dst[64] = l_part;
+  if (cq > 0) {
+    float* dst = xch + (((cq - 1) * 2 + rg) * 2 * XN) * 64 + lane;
+    dst[0] = m0; dst[64] = l0;
 #pragma unroll
     for (int d = 0; d < DB; ++d)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) dst[(2 + d * 4 + i) * 64] = oacc[d][i];
+      for (int i = 0; i < 4; ++i) dst[(2 + d * 4 + i) * 64] = o0[d][i];
+    dst += XN * 64;
+    dst[0] = m1; dst[64] = l1;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) dst[(2 + d * 4 + i) * 64] = o1[d][i];
   }
   __syncthreads();
-  if (half == 1) return;
-  {
-    const float* src = xch + ((wave & 3) * XN) * 64 + lane;
+  if (cq > 0) return;
+  auto merge_in = [&](const float* src, float& m_run, float& l_part, f32x4_t (&oacc)[DB]) {
     const float mo = src[0], lo2 = src[64];
     const float mx = fmaxf(m_run, mo);
     const float ca = fast_exp2((m_run - mx) * sc), cb = fast_exp2((mo - mx) * sc);
@@ -320,23 +358,32 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
 #pragma unroll
       for (int i = 0; i < 4; ++i) oacc[d][i] = oacc[d][i] * ca + src[(2 + d * 4 + i) * 64] * cb;
     m_run = mx;
+  };
+  for (int c = 0; c < 3; ++c) {
+    const float* src = xch + ((c * 2 + rg) * 2 * XN) * 64 + lane;
+    merge_in(src, m0, l0, o0);
+    merge_in(src + XN * 64, m1, l1, o1);
   }
-  float l_row = l_part + __shfl_xor(l_part, 16, 64);
-  l_row += __shfl_xor(l_row, 32, 64);
-  const float inv = 1.0f / l_row;
-  if (my_row < L) {
-    float* op = out + (((size_t)b * L + my_row) * p.H + h) * D;
+  auto finish = [&](int my_row, float m_run, float l_part, const f32x4_t (&oacc)[DB]) {
+    float l_row = l_part + __shfl_xor(l_part, 16, 64);
+    l_row += __shfl_xor(l_row, 32, 64);
+    const float inv = 1.0f / l_row;
+    if (my_row < L) {
+      float* op = out + (((size_t)b * L + my_row) * p.H + h) * D;
 #pragma unroll
-    for (int d = 0; d < DB; ++d) {
-      float4 o = make_float4(oacc[d][0] * inv, oacc[d][1] * inv, oacc[d][2] * inv, oacc[d][3] * inv);
-      *reinterpret_cast<float4*>(op + d * 16 + q4 * 4) = o;
+      for (int d = 0; d < DB; ++d) {
+        float4 o = make_float4(oacc[d][0] * inv, oacc[d][1] * inv, oacc[d][2] * inv, oacc[d][3] * inv);
+        *reinterpret_cast<float4*>(op + d * 16 + q4 * 4) = o;
+      }
+      if (q4 == 0) {
+        float* rs = p.pf_rowstat + (((size_t)unit * p.G + g) * p.max_chunk + my_row) * 2;
+        rs[0] = m_run * sc;                   // row max in the scaled log2 domain
+        rs[1] = inv;
+      }
     }
-    if (q4 == 0) {
-      float* rs = p.pf_rowstat + (((size_t)unit * p.G + g) * p.max_chunk + my_row) * 2;
-      rs[0] = m_run * sc;                   // row max in the scaled log2 domain
-      rs[1] = inv;
-    }
-  }
+  };
+  finish(my_row0, m0, l0, o0);
+  finish(my_row1, m1, l1, o1);
 }
 
 // ---------------------------------------------------------------------------------------------
