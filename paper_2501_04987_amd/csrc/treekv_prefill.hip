@@ -555,20 +555,52 @@ __device__ inline int block_scan_inclusive(int v, int* sm_wave) {
   return v + add;
 }
 
+// Words of LDS the replay needs to keep a unit's order arrays, scores and flags on chip.
+__host__ __device__ inline size_t replay_lds_words(int m, int cap, int r, int L) {
+  return (size_t)4 * m + cap + L + (cap + L) + (L + 2) + (r > 0 ? r : 1);
+}
+
+// IN_LDS: the unit's E, PE, R, S, the chunk's S, the flags and the free list are copied into LDS up
+// front, the replay runs on those copies (generic pointers, so the code below is the same either way) and
+// the live parts are written back at the end.  Without it (budgets too large for LDS) it runs in place.
+template <bool IN_LDS>
 __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, int L, int32_t* __restrict__ retained,
                                                                     int32_t* __restrict__ n_retained,
                                                                     int32_t* __restrict__ evicted) {
   __shared__ int sm_wave[RP_THREADS / 64];
   __shared__ int sm_carry;
+  extern __shared__ __attribute__((aligned(16))) int rp_smem[];
   const int unit = blockIdx.x, tid = threadIdx.x;
   int* meta = p.meta + (size_t)unit * META_STRIDE;
-  float* Su = p.S + (size_t)unit * p.cap;
-  int* Eu = p.E + (size_t)unit * 2 * p.m;
-  int* PEu = p.PE + (size_t)unit * 2 * p.m;
-  int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
-  const float* snew = p.pf_snew + (size_t)unit * p.max_chunk;
-  int* flag = p.pf_flag + (size_t)unit * (p.cap + p.max_chunk);   // [0,cap): slot freed; [cap, cap+L): chunk token dead -> later its slot
+  float* Sg = p.S + (size_t)unit * p.cap;
+  int* Eg = p.E + (size_t)unit * 2 * p.m;
+  int* PEg = p.PE + (size_t)unit * 2 * p.m;
+  int* Rg = p.R + (size_t)unit * max(p.n_recent, 1);
+  const float* snew_g = p.pf_snew + (size_t)unit * p.max_chunk;
+  int* flag_g = p.pf_flag + (size_t)unit * (p.cap + p.max_chunk);
   int32_t* evu = evicted ? evicted + (size_t)unit * L : nullptr;
+
+  float* Su = Sg;
+  int *Eu = Eg, *PEu = PEg, *Ru = Rg;
+  const float* snew = snew_g;
+  int* flag = flag_g;              // [0,cap): slot freed; [cap, cap+L): chunk token dead -> later its destination slot
+  int* free_list = p.pf_list + (size_t)unit * (p.cap + p.max_chunk);
+  if constexpr (IN_LDS) {
+    int* w = rp_smem;
+    Eu = w; w += 2 * p.m;
+    PEu = w; w += 2 * p.m;
+    Su = reinterpret_cast<float*>(w); w += p.cap;
+    float* sn = reinterpret_cast<float*>(w); w += L;
+    flag = w; w += p.cap + L;
+    free_list = w; w += L + 2;
+    Ru = w;
+    for (int i = tid; i < 2 * p.m; i += RP_THREADS) { Eu[i] = Eg[i]; PEu[i] = PEg[i]; }
+    for (int i = tid; i < p.cap; i += RP_THREADS) Su[i] = Sg[i];
+    for (int i = tid; i < L; i += RP_THREADS) sn[i] = snew_g[i];
+    for (int i = tid; i < p.n_recent; i += RP_THREADS) Ru[i] = Rg[i];
+    snew = sn;
+    __syncthreads();
+  }
 
   const int n0 = meta[META_N], f0 = meta[META_FREE], j0 = meta[META_J], rhead0 = meta[META_RHEAD], t0 = meta[META_T];
   const int cap = p.cap, c = p.budget, m = p.m, r = p.n_recent;
@@ -579,7 +611,10 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
 
   // ---- phase 0: flags, scores of the tokens that got slots while filling ----
   for (int i = tid; i < cap + L; i += RP_THREADS) flag[i] = 0;
-  for (int i = tid; i < F; i += RP_THREADS) Su[n0 + i] = snew[i];
+  for (int i = tid; i < F; i += RP_THREADS) {
+    Su[n0 + i] = snew[i];
+    if constexpr (IN_LDS) Sg[n0 + i] = snew[i];
+  }
   for (int i = tid; i < F; i += RP_THREADS) if (evu) evu[i] = -1;
   __syncthreads();
 
@@ -651,7 +686,6 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
     if (tid == 0) flag[fstart] = 1;
     __syncthreads();
     // rank of every free slot among the free slots (ascending slot number)
-    int* free_list = p.pf_list + (size_t)unit * (p.cap + p.max_chunk);
     int carry = 0;
     for (int s0 = 0; s0 < cap; s0 += RP_THREADS) {
       const int s = s0 + tid;
@@ -691,13 +725,20 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
     }
     for (int i = F + tid; i < L; i += RP_THREADS) {
       const int slot = flag[cap + i];
-      if (slot >= 0) Su[slot] = snew[i];
+      if (slot >= 0) Sg[slot] = snew[i];
     }
   }
   // tokens that arrived while filling sit in slots n0 + i unless the chunk also evicted them;
   // flag[cap + i] is now every chunk token's destination slot (or -1) for the scatter
   for (int i = tid; i < F; i += RP_THREADS) flag[cap + i] = flag[n0 + i] ? -1 : n0 + i;
   __syncthreads();
+  if constexpr (IN_LDS) {          // write back what later kernels and later calls read
+    for (int i = tid; i < L; i += RP_THREADS) flag_g[cap + i] = flag[cap + i];
+    if (Lev > 0) {
+      for (int i = tid; i < 2 * m; i += RP_THREADS) { Eg[i] = Eu[i]; PEg[i] = PEu[i]; }
+      for (int i = tid; i < r; i += RP_THREADS) Rg[i] = Ru[i];
+    }
+  }
 
   // ---- retained positions, bookkeeping words ----
   int32_t* ret = retained + (size_t)unit * c;
@@ -756,7 +797,17 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
   hipLaunchKernelGGL(attend, dim3((n_items + 7) / 8 * 8), dim3(AT_THREADS), lds, s, p, q, k, v, L, row_tiles, out);
   const int col_tiles = (p.cap + COL_TILE - 1) / COL_TILE + (L + COL_TILE - 1) / COL_TILE;
   hipLaunchKernelGGL((prefill_colsum_kernel<D>), dim3(col_tiles, p.U), dim3(PF_THREADS), 0, s, p, q, k, L);
-  hipLaunchKernelGGL(prefill_replay_kernel, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, retained, n_retained, evicted);
+  const size_t rp_lds = replay_lds_words(p.m, p.cap, p.n_recent, L) * sizeof(int);
+  if (rp_lds <= 140 * 1024) {
+    auto replay = prefill_replay_kernel<true>;
+    if (rp_lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)replay, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rp_lds) != hipSuccess)
+      return TREEKV_EHIP;
+    hipLaunchKernelGGL(replay, dim3(p.U), dim3(RP_THREADS), rp_lds, s, p, L, retained, n_retained, evicted);
+  } else {
+    hipLaunchKernelGGL(prefill_replay_kernel<false>, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, retained, n_retained,
+                       evicted);
+  }
   hipLaunchKernelGGL(prefill_scatter_kernel, dim3(L, p.U), dim3(64), 0, s, p, (const uint4*)K, (const uint4*)V, L,
                      D * 2 / 16);
   return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;

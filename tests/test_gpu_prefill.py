@@ -66,6 +66,12 @@ def test_prefill_keep_left(binding, oracle):
          flags=binding.TREEKV_KEEP_LEFT, seed=10)
 
 
+def test_prefill_large_budget_runs_in_place(binding, oracle):
+    """A budget whose order arrays do not fit in LDS takes the replay kernel's in-place variant."""
+    _run(binding, oracle, [1024] * 9 + [700, 0, 0], B=1, H=1, Hkv=1, d=64, budget=9000, n_sink=0, n_recent=0,
+         max_chunk=1024, seed=13)
+
+
 def test_prefill_len1_equals_decode(binding, oracle):
     """A one-token chunk is a decode step: same evictions, same retained list, outputs within tolerance."""
     import torch
