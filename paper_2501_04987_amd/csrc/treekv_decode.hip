@@ -30,6 +30,9 @@ namespace {
 #ifndef TKV_FUSED_THREADS
 #define TKV_FUSED_THREADS 512
 #endif
+#ifndef TKV_SPLIT_THREADS
+#define TKV_SPLIT_THREADS 512
+#endif
 #ifndef TKV_KU
 #define TKV_KU 2
 #endif
@@ -48,7 +51,7 @@ __device__ inline void store_maybe_nt(V v, V* ptr) {
   else *ptr = v;
 }
 constexpr int FUSED_THREADS = TKV_FUSED_THREADS;
-constexpr int SPLIT_THREADS = 512;
+constexpr int SPLIT_THREADS = TKV_SPLIT_THREADS;
 constexpr int MERGE_THREADS = 512;
 constexpr int KU = TKV_KU;             // wave loads of K (and of V) per tile
 constexpr float NEG_BIG = -1.0e30f;

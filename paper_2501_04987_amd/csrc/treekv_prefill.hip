@@ -433,8 +433,7 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_colsum_kernel(Params p, co
 
   // One item = one 16-row tile of one query head against the 64 columns.  Items are dealt round robin
   // to the waves.  Q rows are 8 KB apart in the caller's [B, L, H, d] layout, so they are fetched as whole
-  // rows (16 lanes per row), parked in a wave-private LDS tile and read back in MFMA operand order.  The
-  // next item's rows and row statistics are requested before this item's MFMAs (two named register sets).
+  // rows (16 lanes per row), parked in a wave-private LDS tile and read back in MFMA operand order.
   const int q_lrow = lane / LPR, q_lpart = lane % LPR;      // this lane's row (of each group of 64/LPR rows) and piece
   uint16_t* myq = sm_q[wave];
   auto fetch = [&](uint4& iq0, uint4& iq1, uint4& iq2, uint4& iq3, float4& is01, float4& is23, int g, int rt) {
@@ -501,16 +500,14 @@ __global__ __launch_bounds__(PF_THREADS) void prefill_colsum_kernel(Params p, co
   };
   const uint4 z4 = make_uint4(0, 0, 0, 0);
   const float4 zf = make_float4(0.f, 0.f, 0.f, 0.f);
+  // One Q tile in flight per wave: with the K tile held in registers, a second buffered tile costs more in
+  // occupancy than it hides in latency (measured).
   for (int g = 0; g < p.G; ++g) {
-    uint4 aq0 = z4, aq1 = z4, aq2 = z4, aq3 = z4, bq0 = z4, bq1 = z4, bq2 = z4, bq3 = z4;
-    float4 as01 = zf, as23 = zf, bs01 = zf, bs23 = zf;
-    int rt = first_rt + wave;
-    if (rt < n_rt) fetch(aq0, aq1, aq2, aq3, as01, as23, g, rt);
-    for (; rt < n_rt; rt += 2 * WAVES) {
-      if (rt + WAVES < n_rt) fetch(bq0, bq1, bq2, bq3, bs01, bs23, g, rt + WAVES);
+    uint4 aq0 = z4, aq1 = z4, aq2 = z4, aq3 = z4;
+    float4 as01 = zf, as23 = zf;
+    for (int rt = first_rt + wave; rt < n_rt; rt += WAVES) {
+      fetch(aq0, aq1, aq2, aq3, as01, as23, g, rt);
       compute(aq0, aq1, aq2, aq3, as01, as23, rt);
-      if (rt + 2 * WAVES < n_rt) fetch(aq0, aq1, aq2, aq3, as01, as23, g, rt + 2 * WAVES);
-      if (rt + WAVES < n_rt) compute(bq0, bq1, bq2, bq3, bs01, bs23, rt + WAVES);
     }
   }
   float cs[4] = {colvis[0] ? cs0 : 0.f, colvis[1] ? cs1 : 0.f, colvis[2] ? cs2 : 0.f, colvis[3] ? cs3 : 0.f};
