@@ -52,9 +52,10 @@ __device__ inline void store_maybe_nt(V v, V* ptr) {
 }
 constexpr int FUSED_THREADS = TKV_FUSED_THREADS;
 constexpr int SPLIT_THREADS = TKV_SPLIT_THREADS;
-constexpr int MERGE_THREADS = 512;
+constexpr int MERGE_THREADS = 1024;
 constexpr int KU = TKV_KU;             // wave loads of K (and of V) per tile
 constexpr float NEG_BIG = -1.0e30f;
+constexpr size_t LDS_LIMIT = 150 * 1024;   // of the 160 KB a workgroup can have
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 
@@ -335,6 +336,231 @@ struct Stream {
   }
 };
 
+// ---------------------------------------------------------------------------------------------
+// Streaming for grouped queries (bf16, G >= 2).  With G query heads per KV head the per-row work
+// is a small contraction, [G x d] . [d x rows] and [G x rows] . [rows x d], and doing it on the
+// vector ALU costs G times the instructions of the G = 1 stream: the kernel turns ALU bound.  Here the two
+// contractions go to the matrix pipe (16x16x32 bf16 MFMA with the G heads in 16 columns), which is
+// otherwise idle; the stream itself (every K and V row read once, 16-byte lane loads) is unchanged.
+//   S^T = K Q^T   A = 16 K rows read straight from global in operand order, B = Q (columns >= G are padding)
+//   O^T += V^T P^T  A = V^T: the wave's 32 V rows are transposed in registers (v_perm) into a wave-private
+//                   LDS tile; B = P^T, which is exactly the accumulator layout of S^T (no lane movement).
+// P is split into two bf16 parts (hi + lo) so that rounding it costs 2^-16, not 2^-9.
+// Same outputs as Stream::run: per-wave (max, sum, accumulator) in LDS, scaled logits in sm_s.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+
+__device__ inline f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+__device__ inline unsigned pack_bf16(float a, float b) {
+  f32x2_t v = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
+
+template <int D, int G, int THREADS>
+struct StreamMfma {
+  using T = uint16_t;
+  static constexpr int WAVES = THREADS / 64;
+  static constexpr int TILE = 32;                 // rows per wave iteration (one k-step of the P.V contraction)
+  static constexpr int STEP = WAVES * TILE;
+  static constexpr int KS = D / 32, DB = D / 16, PARTS = D / 8;
+  static constexpr int VSTRIDE = TILE + 8;        // bf16 elements per staged V^T row (80 bytes: conflict-free b128 reads)
+  static constexpr int VT_FLOATS = D * VSTRIDE / 2;
+  static constexpr int LDS_FLOATS_FIXED = WAVES * G * (D + 2) + WAVES * VT_FLOATS;
+  static constexpr int VLOADS = TILE * PARTS / 64;        // 16-byte V pieces per lane and tile (8 at d=128, 4 at d=64)
+  static_assert(G >= 2 && G <= 16 && (VLOADS == 8 || VLOADS == 4), "written for head_dim 64 / 128");
+
+  template <class AfterMeta, class MidStream>
+  __device__ static inline void run(const Params& p, int unit, int begin_spec, const T* __restrict__ q_in,
+                                    const T* __restrict__ knew, const T* __restrict__ vnew, const int* meta,
+                                    float* sm_s, int lds_rows, float* sm_acc, float* sm_wm, float* sm_wl,
+                                    Step& st, int& begin, int& end, bool fused, AfterMeta after_meta,
+                                    MidStream mid_stream) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lr = lane & 15, q4 = lane >> 4;
+    const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+    const T* Ku = (const T*)p.K + (size_t)unit * p.cap * D;
+    const T* Vu = (const T*)p.V + (size_t)unit * p.cap * D;
+    uint16_t* vt = reinterpret_cast<uint16_t*>(sm_acc + WAVES * G * (D + 2)) + (size_t)wave * (VT_FLOATS * 2);
+
+    // B operand of S^T = K Q^T: column lr is query head lr of the group (zero beyond G)
+    uint4 qa[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qa[ks] = make_uint4(0, 0, 0, 0);
+      if (lr < G) qa[ks] = *reinterpret_cast<const uint4*>(q_in + ((size_t)b * p.H + (size_t)kvh * G + lr) * D + ks * 32 + q4 * 8);
+    }
+
+    st = load_meta(p, meta);
+    begin = begin_spec;
+    end = fused ? st.n1 : min(st.n1, begin + p.rows_per_split);
+    const int fslot = st.fslot;
+    after_meta(st);
+
+    // K rows arrive in operand order: lane (lr, q4) holds K[row + lr][ks*32 + q4*8 ..] of two 16-row blocks.
+    // V rows arrive as whole rows: 16 lanes per row, lane group q4 takes rows q4*4 + {0..3} of each block.
+    uint4 k00, k01, k02, k03, k10, k11, k12, k13;            // [block][k-step]
+    uint4 v00, v01, v02, v03, v10, v11, v12, v13;            // [block][row q4*4 + x], this lane's 8 dims
+    k00 = k01 = k02 = k03 = k10 = k11 = k12 = k13 = make_uint4(0, 0, 0, 0);
+    v00 = v01 = v02 = v03 = v10 = v11 = v12 = v13 = make_uint4(0, 0, 0, 0);
+    auto row_ptr = [&](const T* cache, const T* fresh, int row) -> const T* {
+      const int r = min(row, end - 1);
+      return r == fslot ? fresh : cache + (size_t)r * D;
+    };
+    auto load_k = [&](int tb) {
+      const T* r0 = row_ptr(Ku, knew, tb + lr) + q4 * 8;
+      const T* r1 = row_ptr(Ku, knew, tb + 16 + lr) + q4 * 8;
+      k00 = *reinterpret_cast<const uint4*>(r0); k01 = *reinterpret_cast<const uint4*>(r0 + 32);
+      k10 = *reinterpret_cast<const uint4*>(r1); k11 = *reinterpret_cast<const uint4*>(r1 + 32);
+      if constexpr (KS > 2) {
+        k02 = *reinterpret_cast<const uint4*>(r0 + 64); k03 = *reinterpret_cast<const uint4*>(r0 + 96);
+        k12 = *reinterpret_cast<const uint4*>(r1 + 64); k13 = *reinterpret_cast<const uint4*>(r1 + 96);
+      }
+    };
+    // V pieces: piece index = lane + 64*x; row = piece / PARTS, part = piece % PARTS.  With PARTS = 16 a lane keeps
+    // part = lr and rows q4 + 4x; the transposition below wants rows q4*4 + {0..3}, so rows are dealt that way.
+    const int v_part = lane % PARTS, v_rg = lane / PARTS;    // v_rg: 0..3 (d=128) or 0..7 (d=64)
+    auto load_v = [&](int tb) {
+      if constexpr (PARTS == 16) {
+        const int r = tb + v_rg * 4;
+        v00 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r) + v_part * 8);
+        v01 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 1) + v_part * 8);
+        v02 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 2) + v_part * 8);
+        v03 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 3) + v_part * 8);
+        v10 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 16) + v_part * 8);
+        v11 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 17) + v_part * 8);
+        v12 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 18) + v_part * 8);
+        v13 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 19) + v_part * 8);
+      } else {                                               // d = 64: 8 row groups of 4 rows cover the 32 rows
+        const int r = tb + v_rg * 4;
+        v00 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r) + v_part * 8);
+        v01 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 1) + v_part * 8);
+        v02 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 2) + v_part * 8);
+        v03 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 3) + v_part * 8);
+      }
+    };
+    // staged V^T: row d, the tile's rows in k-slot order: row (blk*16 + q*4 + i) at position q*8 + blk*4 + i;
+    // the 16-byte pair q is XOR-swizzled with (d/16)%4 (reads of an operand share d/16; writes spread out)
+    auto put_v = [&](const uint4& a, const uint4& b2, const uint4& c, const uint4& d4, int blk, int q) {
+      auto emit = [&](unsigned a0, unsigned a1, unsigned a2, unsigned a3, int e_even) {
+#pragma unroll
+        for (int odd = 0; odd < 2; ++odd) {
+          const unsigned sel = odd ? 0x07060302u : 0x05040100u;
+          uint2 o;
+          o.x = __builtin_amdgcn_perm(a1, a0, sel);
+          o.y = __builtin_amdgcn_perm(a3, a2, sel);
+          const int dd = v_part * 8 + e_even + odd;
+          *reinterpret_cast<uint2*>(&vt[dd * VSTRIDE + ((q ^ ((dd >> 4) & 3)) * 8) + blk * 4]) = o;
+        }
+      };
+      emit(a.x, b2.x, c.x, d4.x, 0); emit(a.y, b2.y, c.y, d4.y, 2);
+      emit(a.z, b2.z, c.z, d4.z, 4); emit(a.w, b2.w, c.w, d4.w, 6);
+    };
+
+    float m_run = NEG_BIG, l_part = 0.f;           // this lane's query head (lr): running max, partial sum
+    f32x4_t oacc[DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d) oacc[d] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const float sc = p.scale_log2e;
+
+    int base = begin + wave * TILE;
+    if (base < end) { load_k(base); load_v(base); }
+    int iter = 0;
+    for (; base < end; base += STEP, ++iter) {
+      const int nb = base + STEP;
+      // ---- S^T: two 16-row blocks ----
+      f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+      s0 = mfma16(k00, qa[0], s0); s1 = mfma16(k10, qa[0], s1);
+      s0 = mfma16(k01, qa[1], s0); s1 = mfma16(k11, qa[1], s1);
+      if constexpr (KS > 2) {
+        s0 = mfma16(k02, qa[2], s0); s1 = mfma16(k12, qa[2], s1);
+        s0 = mfma16(k03, qa[3], s0); s1 = mfma16(k13, qa[3], s1);
+      }
+      if (nb < end) load_k(nb);                                       // next tile's K behind this tile's softmax
+      // ---- V rows -> V^T tile (wave private) ----
+      if constexpr (PARTS == 16) {
+        put_v(v00, v01, v02, v03, 0, v_rg);
+        put_v(v10, v11, v12, v13, 1, v_rg);
+      } else {
+        put_v(v00, v01, v02, v03, v_rg >> 2, v_rg & 3);
+      }
+      if (nb < end) load_v(nb);
+      // ---- logits of rows base + blk*16 + q4*4 + i for head lr ----
+      float sv[8];
+      const bool tail = base + TILE > end;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { sv[i] = s0[i] * sc; sv[4 + i] = s1[i] * sc; }
+      if (tail) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sv[e] = (base + (e >> 2) * 16 + q4 * 4 + (e & 3) < end) ? sv[e] : NEG_BIG;
+      }
+      if (lr < G) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int row = base + (e >> 2) * 16 + q4 * 4 + (e & 3);
+          if (!tail || row < end) sm_s[(size_t)lr * lds_rows + (row - begin)] = sv[e];
+        }
+      }
+      float mx = m_run;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      if (__any(mx != m_run)) {
+        const float corr = fast_exp2(m_run - mx);
+        l_part *= corr;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) oacc[d] *= corr;
+        m_run = mx;
+      }
+      unsigned hi[4], lo[4];
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        float p0 = fast_exp2(sv[2 * e2] - mx), p1 = fast_exp2(sv[2 * e2 + 1] - mx);
+        if (tail) {
+          p0 = sv[2 * e2] > 0.5f * NEG_BIG ? p0 : 0.f;
+          p1 = sv[2 * e2 + 1] > 0.5f * NEG_BIG ? p1 : 0.f;
+        }
+        l_part += p0 + p1;
+        hi[e2] = pack_bf16(p0, p1);
+        lo[e2] = pack_bf16(p0 - __uint_as_float(hi[e2] << 16), p1 - __uint_as_float(hi[e2] & 0xffff0000u));
+      }
+      const uint4 phi = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+      const uint4 plo = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+      // ---- O^T += V^T P^T ----
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int d = 0; d < DB; ++d) {
+        const uint4 a = *reinterpret_cast<const uint4*>(&vt[(d * 16 + lr) * VSTRIDE + ((q4 ^ (d & 3)) * 8)]);
+        oacc[d] = mfma16(a, phi, oacc[d]);
+        oacc[d] = mfma16(a, plo, oacc[d]);
+      }
+      __builtin_amdgcn_wave_barrier();
+      if (iter == TKV_MID_ITER) mid_stream();
+    }
+    if (iter <= TKV_MID_ITER) mid_stream();
+
+    float l_row = l_part + __shfl_xor(l_part, 16, 64);
+    l_row += __shfl_xor(l_row, 32, 64);
+    if (lr < G) {
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sm_acc[(wave * G + lr) * D + d * 16 + q4 * 4 + i] = oacc[d][i];
+      if (q4 == 0) { sm_wm[wave * G + lr] = m_run; sm_wl[wave * G + lr] = l_row; }
+    }
+  }
+};
+
+// The stream to use for a storage type and group size.
+template <typename T, int D, int G, int THREADS> struct PickStream { using type = Stream<T, D, G, THREADS>; };
+template <int D, int THREADS> struct PickStream<uint16_t, D, 2, THREADS> { using type = StreamMfma<D, 2, THREADS>; };
+template <int D, int THREADS> struct PickStream<uint16_t, D, 4, THREADS> { using type = StreamMfma<D, 4, THREADS>; };
+template <int D, int THREADS> struct PickStream<uint16_t, D, 8, THREADS> { using type = StreamMfma<D, 8, THREADS>; };
+
 // Global (max, sum) over the parts' (max, sum) pairs, identical in every thread that calls it.
 __device__ inline void merge_stats(const float* pm, const float* pl, int nparts, int stride, float& M, float& L) {
   float mx = NEG_BIG;
@@ -440,14 +666,14 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
                                                                      int32_t* __restrict__ n_retained,
                                                                      int32_t* __restrict__ evicted) {
   constexpr int THREADS = FUSED_THREADS;
-  using St = Stream<T, D, G, THREADS>;
+  using St = typename PickStream<T, D, G, THREADS>::type;
   constexpr int WAVES = St::WAVES;
   constexpr int EP = 5 * 1024 / THREADS;       // covers budgets up to 5119 from registers
   extern __shared__ float smem[];
   float* sm_acc = smem;
   float* sm_wm = sm_acc + WAVES * G * D;
   float* sm_wl = sm_wm + WAVES * G;
-  float* sm_s = sm_wl + WAVES * G;             // [G][cap]
+  float* sm_s = smem + St::LDS_FLOATS_FIXED;   // [G][cap]
   __shared__ float sm_sc[2];
 
   const int unit = blockIdx.x, tid = threadIdx.x;
@@ -467,7 +693,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
   int begin, end;
   St::run(p, unit, 0, q_in, knew, vnew, meta, sm_s, p.cap, sm_acc, sm_wm, sm_wl, st, begin, end, true,
           [&](const Step& s0) {
-            if (tid < St::LPR) {
+            if (tid < D / Storage<T>::EPL) {
               knew_r = reinterpret_cast<const uint4*>(knew)[tid];
               vnew_r = reinterpret_cast<const uint4*>(vnew)[tid];
             }
@@ -514,13 +740,13 @@ __global__ __launch_bounds__(SPLIT_THREADS) void decode_split_kernel(Params p, c
                                                                      const T* __restrict__ k_in,
                                                                      const T* __restrict__ v_in) {
   constexpr int THREADS = SPLIT_THREADS;
-  using St = Stream<T, D, G, THREADS>;
+  using St = typename PickStream<T, D, G, THREADS>::type;
   constexpr int WAVES = St::WAVES;
   extern __shared__ float smem[];
   float* sm_acc = smem;
   float* sm_wm = sm_acc + WAVES * G * D;
   float* sm_wl = sm_wm + WAVES * G;
-  float* sm_s = sm_wl + WAVES * G;             // [G][rows_per_split]
+  float* sm_s = smem + St::LDS_FLOATS_FIXED;   // [G][rows_per_split]
 
   const int split = blockIdx.x, unit = blockIdx.y, tid = threadIdx.x;
   const int* meta = p.meta + (size_t)unit * META_STRIDE;
@@ -544,7 +770,11 @@ __global__ __launch_bounds__(SPLIT_THREADS) void decode_split_kernel(Params p, c
     for (int r = tid; r < end - begin; r += THREADS) lg[(size_t)g * p.cap + begin + r] = sm_s[(size_t)g * p.rows_per_split + r];
 }
 
-template <typename T, int D, int G>
+// Second kernel of the SPLIT shape: one workgroup per unit.  Latency is all that matters here, so
+// everything the epilogue needs (the slices' logits, the old scores, the tree positions) is requested in one
+// go right after the bookkeeping words, the logits are parked in LDS, and from there on the kernel is the
+// tail of the fused one.
+template <typename T, int D, int G, bool LOGITS_IN_LDS>
 __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, const T* __restrict__ k_in,
                                                                      const T* __restrict__ v_in,
                                                                      float* __restrict__ out,
@@ -552,12 +782,36 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, c
                                                                      int32_t* __restrict__ n_retained,
                                                                      int32_t* __restrict__ evicted) {
   constexpr int THREADS = MERGE_THREADS;
+  // slots / list entries per thread served from registers (none when the logits do not fit in LDS: huge budgets)
+  constexpr int EP = LOGITS_IN_LDS ? 5 * 1024 / THREADS : 0;
+  constexpr int LPR = D / Storage<T>::EPL;
+  extern __shared__ float smem[];              // [G][cap] logits
   __shared__ float sm_sc[2];
   const int unit = blockIdx.x, tid = threadIdx.x;
   int* meta = p.meta + (size_t)unit * META_STRIDE;
   const int* PEu = p.PE + (size_t)unit * 2 * p.m;
+  const float* Su = p.S + (size_t)unit * p.cap;
+  const float* lg = p.logits + (size_t)unit * G * p.cap;
   Step st = load_meta(p, meta);
+
+  float s_old[EP > 0 ? EP : 1], lreg[EP > 0 ? EP : 1][G];
+  int pe_pre[EP > 0 ? EP : 1];
+#pragma unroll
+  for (int x = 0; x < EP; ++x) {
+    const int slot = tid + x * THREADS;
+    const bool live = slot < st.n1;
+    s_old[x] = (live && slot != st.fslot) ? Su[slot] : 0.f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) lreg[x][g] = live ? lg[(size_t)g * p.cap + slot] : 0.f;
+    pe_pre[x] = position_of(p, st, PEu, slot, -1, true);
+  }
+  uint4 knew_r = make_uint4(0, 0, 0, 0), vnew_r = knew_r;
+  if (tid < LPR) {
+    knew_r = reinterpret_cast<const uint4*>(k_in + (size_t)unit * D)[tid];
+    vnew_r = reinterpret_cast<const uint4*>(v_in + (size_t)unit * D)[tid];
+  }
   load_scope(p, st, p.E + (size_t)unit * 2 * p.m, PEu, p.R + (size_t)unit * max(p.n_recent, 1));
+
   const float* parts = p.partial + (size_t)unit * p.nsplit * G * (D + 2);
   float M[G], invL[G];
 #pragma unroll
@@ -576,15 +830,29 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, c
     }
     out[((size_t)b * p.H + (size_t)kvh * G + g) * D + col] = a * invL[g];
   }
-  const float* lg = p.logits + (size_t)unit * G * p.cap;
-  constexpr int LPR = D / Storage<T>::EPL;
-  uint4 knew_r = make_uint4(0, 0, 0, 0), vnew_r = knew_r;
-  if (tid < LPR) {
-    knew_r = reinterpret_cast<const uint4*>(k_in + (size_t)unit * D)[tid];
-    vnew_r = reinterpret_cast<const uint4*>(v_in + (size_t)unit * D)[tid];
+  // logits -> LDS, retained list (all but the entry the decision fills)
+  int32_t* ret = retained + (size_t)unit * p.budget;
+#pragma unroll
+  for (int x = 0; x < EP; ++x) {
+    const int slot = tid + x * THREADS;
+    if (slot < p.cap) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) smem[(size_t)g * p.cap + slot] = lreg[x][g];
+    }
+    if (slot < p.budget) ret[slot] = pe_pre[x];
   }
-  epilogue<T, D, G, THREADS, 0>(p, unit, st, M, invL, [&](int g, int slot) { return lg[(size_t)g * p.cap + slot]; },
-                                nullptr, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta);
+  if constexpr (LOGITS_IN_LDS) {
+    for (int slot = tid + EP * THREADS; slot < st.n1; slot += THREADS)
+      for (int g = 0; g < G; ++g) smem[(size_t)g * p.cap + slot] = lg[(size_t)g * p.cap + slot];
+    for (int i = tid + EP * THREADS; i < p.budget; i += THREADS) ret[i] = position_of(p, st, PEu, i, -1, true);
+    __syncthreads();
+    epilogue<T, D, G, THREADS, EP>(p, unit, st, M, invL, [&](int g, int slot) { return smem[(size_t)g * p.cap + slot]; },
+                                   s_old, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta);
+  } else {
+    (void)ret;
+    epilogue<T, D, G, THREADS, 0>(p, unit, st, M, invL, [&](int g, int slot) { return lg[(size_t)g * p.cap + slot]; },
+                                  nullptr, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta);
+  }
 }
 
 template <typename T, int D, int G>
@@ -594,23 +862,32 @@ int launch_decode_g(const Params& p, const void* q, const void* k, const void* v
   const T* kt = (const T*)k;
   const T* vt = (const T*)v;
   if (p.nsplit == 1) {
-    const size_t lds = (Stream<T, D, G, FUSED_THREADS>::LDS_FLOATS_FIXED + (size_t)G * p.cap) * sizeof(float);
-    if (lds > 150 * 1024) return TREEKV_EUNSUPPORTED;
+    const size_t lds = (PickStream<T, D, G, FUSED_THREADS>::type::LDS_FLOATS_FIXED + (size_t)G * p.cap) * sizeof(float);
+    if (lds > LDS_LIMIT) return TREEKV_EUNSUPPORTED;
     auto kern = decode_fused_kernel<T, D, G>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return TREEKV_EHIP;
     hipLaunchKernelGGL(kern, dim3(p.U), dim3(FUSED_THREADS), lds, s, p, qt, kt, vt, out, retained, n_retained, evicted);
   } else {
-    const size_t lds = (Stream<T, D, G, SPLIT_THREADS>::LDS_FLOATS_FIXED + (size_t)G * p.rows_per_split) * sizeof(float);
-    if (lds > 150 * 1024) return TREEKV_EUNSUPPORTED;
+    const size_t lds = (PickStream<T, D, G, SPLIT_THREADS>::type::LDS_FLOATS_FIXED + (size_t)G * p.rows_per_split) * sizeof(float);
+    if (lds > LDS_LIMIT) return TREEKV_EUNSUPPORTED;
     auto kern = decode_split_kernel<T, D, G>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return TREEKV_EHIP;
     hipLaunchKernelGGL(kern, dim3(p.nsplit, p.U), dim3(SPLIT_THREADS), lds, s, p, qt, kt, vt);
-    hipLaunchKernelGGL((decode_merge_kernel<T, D, G>), dim3(p.U), dim3(MERGE_THREADS), 0, s, p, kt, vt, out, retained,
-                       n_retained, evicted);
+    const size_t mlds = (size_t)G * p.cap * sizeof(float);
+    if (mlds <= LDS_LIMIT) {
+      auto merge = decode_merge_kernel<T, D, G, true>;
+      if (mlds > 48 * 1024 &&
+          hipFuncSetAttribute((const void*)merge, hipFuncAttributeMaxDynamicSharedMemorySize, (int)mlds) != hipSuccess)
+        return TREEKV_EHIP;
+      hipLaunchKernelGGL(merge, dim3(p.U), dim3(MERGE_THREADS), mlds, s, p, kt, vt, out, retained, n_retained, evicted);
+    } else {
+      hipLaunchKernelGGL((decode_merge_kernel<T, D, G, false>), dim3(p.U), dim3(MERGE_THREADS), 0, s, p, kt, vt, out,
+                         retained, n_retained, evicted);
+    }
   }
   return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
 }
@@ -627,7 +904,29 @@ int launch_decode_d(const Params& p, const void* q, const void* k, const void* v
   }
 }
 
+// LDS bytes the streaming kernel of the current shape (fused when nsplit == 1) asks for; 0 if no kernel exists.
+template <typename T, int D>
+size_t stream_lds_d(const Params& p) {
+  auto bytes = [&](size_t fixed_fused, size_t fixed_split) {
+    return (p.nsplit == 1 ? fixed_fused + (size_t)p.G * p.cap : fixed_split + (size_t)p.G * p.rows_per_split) * sizeof(float);
+  };
+  switch (p.G) {
+    case 1: return bytes(PickStream<T, D, 1, FUSED_THREADS>::type::LDS_FLOATS_FIXED, PickStream<T, D, 1, SPLIT_THREADS>::type::LDS_FLOATS_FIXED);
+    case 2: return bytes(PickStream<T, D, 2, FUSED_THREADS>::type::LDS_FLOATS_FIXED, PickStream<T, D, 2, SPLIT_THREADS>::type::LDS_FLOATS_FIXED);
+    case 4: return bytes(PickStream<T, D, 4, FUSED_THREADS>::type::LDS_FLOATS_FIXED, PickStream<T, D, 4, SPLIT_THREADS>::type::LDS_FLOATS_FIXED);
+    case 8: return bytes(PickStream<T, D, 8, FUSED_THREADS>::type::LDS_FLOATS_FIXED, PickStream<T, D, 8, SPLIT_THREADS>::type::LDS_FLOATS_FIXED);
+    default: return 0;
+  }
+}
+
 }  // namespace
+
+bool decode_shape_fits(const Params& p) {
+  size_t b = 0;
+  if (p.dtype == TREEKV_BF16) b = p.D == 128 ? stream_lds_d<uint16_t, 128>(p) : p.D == 64 ? stream_lds_d<uint16_t, 64>(p) : 0;
+  else if (p.dtype == TREEKV_F32) b = p.D == 128 ? stream_lds_d<float, 128>(p) : p.D == 64 ? stream_lds_d<float, 64>(p) : 0;
+  return b != 0 && b <= LDS_LIMIT;
+}
 
 int launch_decode(const Params& p, const void* q, const void* k, const void* v, float* out, int32_t* retained,
                   int32_t* n_retained, int32_t* evicted, hipStream_t s) {

@@ -190,7 +190,15 @@ int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg_in) {
   p.B = c.batch; p.H = c.q_heads; p.Hkv = c.kv_heads; p.G = G; p.D = c.head_dim; p.U = c.batch * c.kv_heads;
   p.dtype = c.dtype; p.flags = c.flags; p.nsplit = c.kv_splits; p.max_chunk = c.max_chunk;
   p.scale_log2e = c.softmax_scale * 1.4426950408889634f;
-  p.rows_per_split = ((p.cap + p.nsplit - 1) / p.nsplit + 63) / 64 * 64;
+  // a unit whose logits do not fit one workgroup's LDS is split further
+  for (;;) {
+    p.rows_per_split = ((p.cap + p.nsplit - 1) / p.nsplit + 63) / 64 * 64;
+    if (tkv::decode_shape_fits(p) || p.nsplit >= 64) break;
+    p.nsplit = p.nsplit < 2 ? 2 : p.nsplit + (p.nsplit + 1) / 2;
+    if (p.nsplit > 64) p.nsplit = 64;
+  }
+  if (!tkv::decode_shape_fits(p)) { delete ctx; return TREEKV_EUNSUPPORTED; }
+  ctx->cfg.kv_splits = p.nsplit;
   ctx->ws_bytes = tkv::carve(p, nullptr);
   *out = ctx;
   return TREEKV_OK;

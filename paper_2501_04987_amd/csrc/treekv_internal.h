@@ -54,6 +54,8 @@ struct Params {
   int* pf_list;             // [U][cap + max_chunk] free slots in ascending order
 };
 
+// true if the decode kernels of the current shape (p.nsplit, p.rows_per_split) fit in LDS
+bool decode_shape_fits(const Params& p);
 int launch_reset(const Params& p, hipStream_t s);
 int launch_decode(const Params& p, const void* q, const void* k, const void* v, float* out,
                   int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s);

@@ -92,3 +92,17 @@ def test_missing_library_is_loud(binding, monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libtreekv.so")
     with pytest.raises(RuntimeError):
         binding.load()
+
+
+def test_splits_follow_lds_capacity(binding):
+    """A configuration whose per-unit logits do not fit one workgroup's LDS is split over more workgroups at init."""
+    rc, h = _init(binding, budget=16384, q_heads=32, kv_heads=8, head_dim=128, batch=64, kv_splits=0)
+    assert rc == 0
+    cfg = binding.treekv_config()
+    binding.load().treekv_get_config(h, C.byref(cfg))
+    assert cfg.kv_splits >= 2          # 512 units would run fused, but 4 x 16385 logits are 262 KB
+    binding.load().treekv_destroy(h)
+    rc, h = _init(binding, budget=2048, q_heads=32, kv_heads=32, head_dim=128, batch=8)
+    binding.load().treekv_get_config(h, C.byref(cfg))
+    assert rc == 0 and cfg.kv_splits == 1
+    binding.load().treekv_destroy(h)
