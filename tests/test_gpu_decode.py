@@ -178,3 +178,31 @@ def test_gqa_long_budget_split_path_sampled(binding, oracle):
     err = ph.compare_scores(kv, st["results"], "bf16")
     print(f"  flagged={st['flagged']}/{st['decisions']} max_err={st['max_err']:.2e} score_err={err:.2e}")
     assert st["decisions"] == 3 * (T - budget)
+
+
+def test_decode_steps_replay_from_a_hip_graph(binding):
+    """No host-side state changes between steps, so a captured step can be replayed: replays with fresh inputs
+    (and eager work in between) must give exactly what eager launches give."""
+    import torch
+
+    T, B, H, d, budget = 80, 2, 4, 128, 24
+    Q, K, V = inputs.batch_streams("lowrank", 21, T, B, H, 1, d, dtype="bf16")
+    Qd, Kd, Vd = (ph.to_device(x, "bf16") for x in (Q, K, V))
+    eager = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=2, n_recent=6, kv_splits=1)
+    graph = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=2, n_recent=6, kv_splits=1)
+    want = ph.gpu_decode_run(eager, Qd, Kd, Vd, range(T))
+    q_s, k_s, v_s = Qd[0].clone(), Kd[0].clone(), Vd[0].clone()          # static input buffers of the graph
+    out, ret, nret, ev = graph.new_outputs()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graph.decode_step(q_s, k_s, v_s, out, ret, nret, ev)
+    graph.reset()                                                        # capture does not execute; start clean
+    torch.cuda.synchronize()
+    for t in range(T):
+        q_s.copy_(Qd[t]); k_s.copy_(Kd[t]); v_s.copy_(Vd[t])
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want["out"][t]), t
+        assert np.array_equal(ev.cpu().numpy(), want["evicted"][t]), t
+        assert np.array_equal(ret.cpu().numpy(), want["retained"][t]), t
+        _ = (Qd[t].float() * 2).sum().item()                             # unrelated eager work between replays

@@ -116,3 +116,22 @@ def test_prefill_llama_shaped_prompt_sampled(binding, oracle):
     kv, st = _run(binding, oracle, sched, B=1, H=32, Hkv=32, d=128, budget=2048, n_sink=4, n_recent=1020,
                   units=[(0, 0), (0, 11), (0, 22), (0, 31)], seed=0)
     assert st["decisions"] == 4 * (8192 + 32 - 2048)
+
+
+def test_prefill_gather_kv_matches_retained(binding, oracle):
+    """After chunks and decode steps the compacted cache (treekv_gather_kv) holds exactly the rows of the retained
+    positions: surviving chunk rows were scattered into the right freed slots."""
+    import torch
+
+    sched = [40, 100, 0, 64, 0, 0, 90]
+    T = sum(max(L, 1) for L in sched)
+    B, H, d, budget = 2, 2, 128, 56
+    Q, K, V = inputs.batch_streams("lowrank", 31, T, B, H, 1, d, dtype="bf16")
+    kv = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=3, n_recent=13, max_chunk=128)
+    st = ph.run_schedule(oracle, kv, Q, K, V, sched, dtype="bf16")     # retained lists compared call by call
+    Kc, Vc = kv.gather_kv()
+    torch.cuda.synchronize()
+    for (b, h), res in st["results"].items():
+        pos = res["stream"].retained()
+        np.testing.assert_array_equal(Kc[b, h, :len(pos)].float().cpu().numpy(), K[pos, b, h])
+        np.testing.assert_array_equal(Vc[b, h, :len(pos)].float().cpu().numpy(), V[pos, b, h])
