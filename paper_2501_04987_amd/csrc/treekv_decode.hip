@@ -45,6 +45,19 @@ namespace {
 #ifndef TKV_NT_S
 #define TKV_NT_S 1
 #endif
+#ifndef TKV_NT_LOAD
+#define TKV_NT_LOAD 1
+#endif
+// 16-byte row piece; optionally with the non-temporal hint (rows are read once per step)
+__device__ inline uint4 ld_row16(const void* ptr) {
+#if TKV_NT_LOAD
+  typedef unsigned v4u __attribute__((ext_vector_type(4)));
+  const v4u r = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(ptr));
+  return make_uint4(r.x, r.y, r.z, r.w);
+#else
+  return *reinterpret_cast<const uint4*>(ptr);
+#endif
+}
 template <bool NT, typename V>
 __device__ inline void store_maybe_nt(V v, V* ptr) {
   if constexpr (NT) __builtin_nontemporal_store(v, ptr);
@@ -199,14 +212,14 @@ struct Stream {
 #pragma unroll
     for (int u = 0; u < KU; ++u) {
       const int row = min(base + u * RPL + ri, p.cap - 1);
-      ka[u] = *reinterpret_cast<const uint4*>(Ku + (size_t)row * D + li * EPL);
-      va[u] = *reinterpret_cast<const uint4*>(Vu + (size_t)row * D + li * EPL);
+      ka[u] = ld_row16(Ku + (size_t)row * D + li * EPL);
+      va[u] = ld_row16(Vu + (size_t)row * D + li * EPL);
     }
 #pragma unroll
     for (int u = 0; u < KU; ++u) {
       const int row = min(base + STEP + u * RPL + ri, p.cap - 1);
-      kb[u] = *reinterpret_cast<const uint4*>(Ku + (size_t)row * D + li * EPL);
-      vb[u] = *reinterpret_cast<const uint4*>(Vu + (size_t)row * D + li * EPL);
+      kb[u] = ld_row16(Ku + (size_t)row * D + li * EPL);
+      vb[u] = ld_row16(Vu + (size_t)row * D + li * EPL);
     }
     uint4 qr[G];
 #pragma unroll
@@ -227,8 +240,8 @@ struct Stream {
         const T* ks = Ku + (size_t)row * D;
         const T* vs = Vu + (size_t)row * D;
         if (has_new && row == fslot) { ks = knew; vs = vnew; }
-        kd[u] = *reinterpret_cast<const uint4*>(ks + li * EPL);
-        vd[u] = *reinterpret_cast<const uint4*>(vs + li * EPL);
+        kd[u] = ld_row16(ks + li * EPL);
+        vd[u] = ld_row16(vs + li * EPL);
       }
     };
     // a speculative tile read the free slot's stale row if it covers it: fetch the real one
@@ -413,11 +426,11 @@ struct StreamMfma {
     auto load_k = [&](int tb) {
       const T* r0 = row_ptr(Ku, knew, tb + lr) + q4 * 8;
       const T* r1 = row_ptr(Ku, knew, tb + 16 + lr) + q4 * 8;
-      k00 = *reinterpret_cast<const uint4*>(r0); k01 = *reinterpret_cast<const uint4*>(r0 + 32);
-      k10 = *reinterpret_cast<const uint4*>(r1); k11 = *reinterpret_cast<const uint4*>(r1 + 32);
+      k00 = ld_row16(r0); k01 = ld_row16(r0 + 32);
+      k10 = ld_row16(r1); k11 = ld_row16(r1 + 32);
       if constexpr (KS > 2) {
-        k02 = *reinterpret_cast<const uint4*>(r0 + 64); k03 = *reinterpret_cast<const uint4*>(r0 + 96);
-        k12 = *reinterpret_cast<const uint4*>(r1 + 64); k13 = *reinterpret_cast<const uint4*>(r1 + 96);
+        k02 = ld_row16(r0 + 64); k03 = ld_row16(r0 + 96);
+        k12 = ld_row16(r1 + 64); k13 = ld_row16(r1 + 96);
       }
     };
     // V pieces: piece index = lane + 64*x; row = piece / PARTS, part = piece % PARTS.  With PARTS = 16 a lane keeps
@@ -426,20 +439,20 @@ struct StreamMfma {
     auto load_v = [&](int tb) {
       if constexpr (PARTS == 16) {
         const int r = tb + v_rg * 4;
-        v00 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r) + v_part * 8);
-        v01 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 1) + v_part * 8);
-        v02 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 2) + v_part * 8);
-        v03 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 3) + v_part * 8);
-        v10 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 16) + v_part * 8);
-        v11 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 17) + v_part * 8);
-        v12 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 18) + v_part * 8);
-        v13 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 19) + v_part * 8);
+        v00 = ld_row16(row_ptr(Vu, vnew, r) + v_part * 8);
+        v01 = ld_row16(row_ptr(Vu, vnew, r + 1) + v_part * 8);
+        v02 = ld_row16(row_ptr(Vu, vnew, r + 2) + v_part * 8);
+        v03 = ld_row16(row_ptr(Vu, vnew, r + 3) + v_part * 8);
+        v10 = ld_row16(row_ptr(Vu, vnew, r + 16) + v_part * 8);
+        v11 = ld_row16(row_ptr(Vu, vnew, r + 17) + v_part * 8);
+        v12 = ld_row16(row_ptr(Vu, vnew, r + 18) + v_part * 8);
+        v13 = ld_row16(row_ptr(Vu, vnew, r + 19) + v_part * 8);
       } else {                                               // d = 64: 8 row groups of 4 rows cover the 32 rows
         const int r = tb + v_rg * 4;
-        v00 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r) + v_part * 8);
-        v01 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 1) + v_part * 8);
-        v02 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 2) + v_part * 8);
-        v03 = *reinterpret_cast<const uint4*>(row_ptr(Vu, vnew, r + 3) + v_part * 8);
+        v00 = ld_row16(row_ptr(Vu, vnew, r) + v_part * 8);
+        v01 = ld_row16(row_ptr(Vu, vnew, r + 1) + v_part * 8);
+        v02 = ld_row16(row_ptr(Vu, vnew, r + 2) + v_part * 8);
+        v03 = ld_row16(row_ptr(Vu, vnew, r + 3) + v_part * 8);
       }
     };
     // staged V^T: row d, the tile's rows in k-slot order: row (blk*16 + q*4 + i) at position q*8 + blk*4 + i;
