@@ -49,8 +49,8 @@ PREFILL_CHUNK = 512
 # HBM bytes per decode launch measured with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per
 # dispatch), each scaled by what the same counter reads for a 1 GiB device copy (`--calibrate-copy`):
 # FETCH_SIZE reads 0.5 KiB per KiB copied (factor 2.0), WRITE_SIZE 1.0 (factor 1.0).
-# 132,966 KiB x 2.0 read + 4,655 KiB written (profiles/decode_fused_kernel_hbm_traffic.txt).
-MEASURED_TRAFFIC_BYTES = (132966 * 2 + 4655) * 1024
+# 132,954 KiB x 2.0 read + 4,432 KiB written (profiles/decode_fused_kernel_hbm_traffic.txt).
+MEASURED_TRAFFIC_BYTES = (132954 * 2 + 4432) * 1024
 
 
 def algorithmic_bytes_per_unit(c=None, d=HEAD_DIM, G=None, esz=2):
