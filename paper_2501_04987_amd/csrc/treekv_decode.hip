@@ -592,7 +592,7 @@ __device__ inline void merge_stats(const float* pm, const float* pl, int nparts,
 template <typename T, int D, int G, int THREADS, int EP, class LogitFn>
 __device__ inline void epilogue(const Params& p, int unit, const Step& st, const float (&M)[G], const float (&invL)[G],
                                 LogitFn logit, const float* s_old, uint4 knew_r, uint4 vnew_r, float* sm_sc, int32_t* __restrict__ retained, int32_t* __restrict__ n_retained,
-                                int32_t* __restrict__ evicted, int* meta) {
+                                int32_t* __restrict__ evicted, int* meta, int ret_patch_tid) {
   constexpr int LPR = D / Storage<T>::EPL;
   const int tid = threadIdx.x;
   float* Su = p.S + (size_t)unit * p.cap;
@@ -663,7 +663,7 @@ __device__ inline void epilogue(const Params& p, int unit, const Step& st, const
   int32_t* ret = retained + (size_t)unit * p.budget;
   if constexpr (EP > 0) {
     // the rest was written up front; the same thread that wrote this entry's old value patches it
-    if (st.evict && tid == (p.n_sink + st.j0) % THREADS) ret[p.n_sink + st.j0] = surv_pos;
+    if (st.evict && tid == ret_patch_tid) ret[p.n_sink + st.j0] = surv_pos;
   } else {
     for (int i = tid; i < p.budget; i += THREADS) ret[i] = position_of(p, st, PEu, i, surv_pos, true);
   }
@@ -700,7 +700,8 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
   // the new row, and the retained list, which is known up front except for the one entry the
   // eviction decides (patched in the epilogue).
   float s_old[EP];
-  int pe_pre[EP];
+  constexpr int EP4 = (EP + 3) / 4;            // each thread writes runs of four retained entries
+  int4 pe_pre[EP4];
   uint4 knew_r = make_uint4(0, 0, 0, 0), vnew_r = knew_r;
   Step st;
   int begin, end;
@@ -714,19 +715,32 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
             for (int x = 0; x < EP; ++x) {
               const int slot = tid + x * THREADS;
               s_old[x] = (slot < s0.n1 && slot != s0.fslot) ? Su[slot] : 0.f;
-              pe_pre[x] = position_of(p, s0, PEu, slot, -1, true);
+            }
+#pragma unroll
+            for (int x = 0; x < EP4; ++x) {
+              const int i = 4 * (tid + x * THREADS);
+              pe_pre[x] = make_int4(position_of(p, s0, PEu, i, -1, true), position_of(p, s0, PEu, i + 1, -1, true),
+                                    position_of(p, s0, PEu, i + 2, -1, true), position_of(p, s0, PEu, i + 3, -1, true));
             }
           },
           [&]() {
             load_scope(p, st, p.E + (size_t)unit * 2 * p.m, PEu, p.R + (size_t)unit * max(p.n_recent, 1));
             int32_t* ret = retained + (size_t)unit * p.budget;
+            const bool quads = (p.budget & 3) == 0 && (reinterpret_cast<uintptr_t>(retained) & 15) == 0;
 #pragma unroll
-            for (int x = 0; x < EP; ++x) {
-              const int slot = tid + x * THREADS;
-              if (slot < p.budget) store_maybe_nt<TKV_NT_RET>(pe_pre[x], ret + slot);
+            for (int x = 0; x < EP4; ++x) {
+              const int i = 4 * (tid + x * THREADS);
+              if (quads) {
+                if (i < p.budget) *reinterpret_cast<int4*>(ret + i) = pe_pre[x];
+              } else {
+                if (i < p.budget) ret[i] = pe_pre[x].x;
+                if (i + 1 < p.budget) ret[i + 1] = pe_pre[x].y;
+                if (i + 2 < p.budget) ret[i + 2] = pe_pre[x].z;
+                if (i + 3 < p.budget) ret[i + 3] = pe_pre[x].w;
+              }
             }
-            for (int i = tid + EP * THREADS; i < p.budget; i += THREADS)
-              store_maybe_nt<TKV_NT_RET>(position_of(p, st, PEu, i, -1, true), ret + i);
+            for (int i = tid + 4 * EP4 * THREADS; i < p.budget; i += THREADS)
+              ret[i] = position_of(p, st, PEu, i, -1, true);
           });
   __syncthreads();
 
@@ -744,8 +758,11 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
     for (int w = 0; w < WAVES; ++w) a += sm_acc[(w * G + g) * D + col] * fast_exp2(sm_wm[w * G + g] - M[g]);
     out[((size_t)b * p.H + (size_t)kvh * G + g) * D + col] = a * invL[g];
   }
+  // the thread that wrote the retained entry the decision fills in
+  const int ret_i = p.n_sink + st.j0;
+  const int ret_owner = (ret_i < 4 * EP4 * THREADS ? ret_i / 4 : ret_i) % THREADS;
   epilogue<T, D, G, THREADS, EP>(p, unit, st, M, invL, [&](int g, int slot) { return sm_s[(size_t)g * p.cap + slot]; },
-                                 s_old, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta);
+                                 s_old, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta, ret_owner);
 }
 
 template <typename T, int D, int G>
@@ -860,11 +877,12 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, c
     for (int i = tid + EP * THREADS; i < p.budget; i += THREADS) ret[i] = position_of(p, st, PEu, i, -1, true);
     __syncthreads();
     epilogue<T, D, G, THREADS, EP>(p, unit, st, M, invL, [&](int g, int slot) { return smem[(size_t)g * p.cap + slot]; },
-                                   s_old, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta);
+                                   s_old, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta,
+                                   (p.n_sink + st.j0) % THREADS);
   } else {
     (void)ret;
     epilogue<T, D, G, THREADS, 0>(p, unit, st, M, invL, [&](int g, int slot) { return lg[(size_t)g * p.cap + slot]; },
-                                  nullptr, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta);
+                                  nullptr, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta, -1);
   }
 }
 
