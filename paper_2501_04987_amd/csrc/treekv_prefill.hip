@@ -5,16 +5,14 @@
 // scores are then frozen and Algorithm 1's append / compare / evict / advance (lines 4-5, 9-17)
 // is replayed for the L tokens.  L = 1 gives the decode step.
 //
-// Four launches per chunk:
-//   attend   grid row tiles x G x U (ids remapped so that a unit's row tiles share an XCD's L2).  Flash-style pass over all visible columns with MFMA:
-//            S^T = K Q^T (16x16x32 bf16), online softmax in registers, O^T += V^T P^T with P
-//            split into two bf16 halves (hi + lo) so that rounding P costs 2^-16, not 2^-9.
-//            Writes O and the final row statistics (max, 1/sum).
-//   colsum   grid (column tiles, U).  Recomputes S = Q K^T for one 64-column tile against every
-//            row that sees it, normalises with the final row statistics and sums down the rows:
-//            a workgroup owns its columns, so the sums need no atomics and have a fixed order.
-//            Cache columns add to S in place (Algorithm 1, line 8), chunk columns get their S.
-//   replay   grid U.  Algorithm 1's eviction for the chunk's tokens with frozen scores.  Inside one
+// Three launches per chunk:
+//   attend   grid row tiles x G x U (ids remapped so that a unit's row tiles share an XCD's L2).  Two passes
+//            over all visible columns with MFMA (16x16x32 bf16): the first finds the row statistics, the
+//            second forms the final probabilities, O^T += V^T P^T with P split into two bf16 halves
+//            (hi + lo) so that rounding P costs 2^-16, not 2^-9, and the probabilities' sums down the
+//            workgroup's rows, one part per row group.  Writes O and the column-sum parts.
+//   replay   grid U.  Adds the column-sum parts to the scores (Algorithm 1, line 8; fixed order, no
+//            atomics), then Algorithm 1's eviction for the chunk's tokens with frozen scores.  Inside one
 //            sweep of idx over the tree region the scopes are disjoint pairs, so a sweep is one
 //            parallel pass; sweeps run one after the other.  Then surviving chunk tokens are
 //            matched with freed slots (prefix sums), the order arrays are rewritten and the
@@ -33,9 +31,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-constexpr int PF_THREADS = 256;
-constexpr int ROW_TILE = 64;     // query rows per attend workgroup (16 per wave)
-constexpr int COL_TILE = 64;     // columns per step
+constexpr int ROW_TILE = 64;     // query rows per attend workgroup
 constexpr float NEG_BIG = -1.0e30f;
 
 __device__ inline f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
@@ -80,12 +76,26 @@ struct AttendLds {
   static constexpr size_t BYTES = 2 * (size_t)(K_ELEMS + V_ELEMS) * sizeof(uint16_t);   // two stages
 };
 
-// Work split.  A workgroup owns 64 query rows of one head and walks over the visible columns in
-// tiles of 128.  Its 8 waves are 2 row groups (32 rows = two 16-row MFMA blocks) x 4 column quarters
-// (32 columns of every tile): each K / V^T operand read from LDS feeds the MFMAs of two row blocks,
-// and two waves share a SIMD so that one's exp / convert work overlaps the other's MFMAs.  Every wave
-// keeps its own online-softmax state per row block; the four quarters of a row group are merged through
-// LDS at the end.  Threads 0-255 stage V (transposing), threads 256-511 stage K.
+// One workgroup owns 64 query rows of one head and passes over the visible columns twice.
+//
+// Sweep 1 finds every row's softmax statistics (max, sum).  No LDS and no barriers: wave w takes the
+// 16-column block w of every 128-column tile against all 64 rows, its K rows loaded straight from
+// global memory in MFMA operand order (every K row is read once per workgroup).  Each lane keeps a
+// running (max, sum) for its own columns of its four rows; lanes and waves are merged once, at the end.
+//
+// Sweep 2 recomputes the logits and, knowing the statistics, forms the normalised probabilities
+// directly: p = exp2(s*scale - max - log2(sum)), no running maximum and nothing to rescale.  They feed
+// O^T += V^T P^T and, summed down the rows, the per-column score increments (Algorithm 1, line 8).
+// Here K and V^T tiles are staged through LDS, double buffered, and the 8 waves are 2 row groups (32 rows
+// = two 16-row MFMA blocks) x 4 column quarters (32 columns of every tile): each K / V^T operand read
+// from LDS feeds the MFMAs of two row blocks, and two waves share a SIMD so that one's exp / convert
+// work overlaps the other's MFMAs.  The four quarters of a row group add their O through LDS at the end.
+// Threads 0-255 stage V (transposing), threads 256-511 stage K.
+//
+// Column sums: a wave adds its two row blocks, reduces over the 16 lanes that hold the 16 rows and
+// writes the 32 sums of its columns to part row_tile*2 + row_group of the head's partial array;
+// the replay kernel adds the parts in a fixed order.  A workgroup writes every column of every tile it
+// visits (masked entries as zeros) and nothing else.
 //
 // Staged V^T layout.  Row d holds the tile's columns in the order the P^T operand uses them: inside
 // quarter c, column j sits at position c*32 + ((j%16)/4)*8 + ((j%32)/16)*4 + j%4, so that the 8 k-slots of
@@ -93,6 +103,25 @@ struct AttendLds {
 // bytes of "pair" c*4 + q4.  Pairs are XOR-swizzled with (d/16)%8: the 16 lanes of an operand read share
 // d/16, so reads stay conflict free, while the transposing 8-byte writes of 16 lanes (same columns, rows 8
 // apart) spread over the banks.
+template <int CTRL>
+__device__ inline float dpp_add(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+  return v + __int_as_float(moved);
+}
+// max of three.  This file is compiled with -fno-honor-nans: otherwise every fmaxf operand that comes out of
+// an MFMA costs an extra instruction that quiets signalling NaNs, and the pair is not fused into v_max3_f32.
+__device__ inline float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+template <bool B> struct BoolTag { static constexpr bool value = B; };
+
+// Sum over the 16 lanes of a DPP row; every lane gets the total.
+__device__ inline float row16_sum(float v) {
+  v = dpp_add<0x128>(v);           // row_ror:8
+  v = dpp_add<0x124>(v);           // row_ror:4
+  v = dpp_add<0x122>(v);           // row_ror:2
+  v = dpp_add<0x121>(v);           // row_ror:1
+  return v;
+}
+
 template <int D>
 __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, const uint16_t* __restrict__ Q,
                                                                     const uint16_t* __restrict__ Kc,
@@ -120,23 +149,20 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const int row_tile = item % row_tiles, g = (item / row_tiles) % p.G, unit = item / (row_tiles * p.G);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, q4 = lane >> 4;
-  const int rg = wave & 1;                                 // row group: rows 32*rg .. +31 of the workgroup's 64
-  const int cq = wave >> 1;                                // column quarter of every tile
+  const int rg = wave & 1;                                 // sweep 2: rows 32*rg .. +31 of the workgroup's 64
+  const int cq = wave >> 1;                                // sweep 2: column quarter of every tile
   const int kvh = unit % p.Hkv, b = unit / p.Hkv;
   const int h = kvh * p.G + g;
   const ChunkInfo ci = load_chunk_info(p.meta + (size_t)unit * META_STRIDE);
+  const int rbase = row_tile * ROW_TILE;                   // first chunk row of the workgroup
 
-  const int row0 = row_tile * ROW_TILE + rg * 32;          // first chunk row of this wave
-  const int my_row0 = row0 + lr, my_row1 = row0 + 16 + lr; // the query rows this lane's results belong to
-  uint4 qa0[KS], qa1[KS];                                  // B operands: Q rows of the two row blocks
-  {
-    const uint16_t* q0p = Q + (((size_t)b * L + min(my_row0, L - 1)) * p.H + h) * D + q4 * 8;
-    const uint16_t* q1p = Q + (((size_t)b * L + min(my_row1, L - 1)) * p.H + h) * D + q4 * 8;
+  // B operands: the Q rows of the four 16-row blocks (rows past the chunk repeat its last row)
+  uint4 qa[4][KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      qa0[ks] = *reinterpret_cast<const uint4*>(q0p + ks * 32);
-      qa1[ks] = *reinterpret_cast<const uint4*>(q1p + ks * 32);
-    }
+  for (int rb = 0; rb < 4; ++rb) {
+    const uint16_t* qp = Q + (((size_t)b * L + min(rbase + rb * 16 + lr, L - 1)) * p.H + h) * D + q4 * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qa[rb][ks] = *reinterpret_cast<const uint4*>(qp + ks * 32);
   }
 
   const uint16_t* Ku = (const uint16_t*)p.K + (size_t)unit * p.cap * D;
@@ -146,9 +172,154 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const uint16_t* Vcu = Vc + ((size_t)b * L * p.Hkv + kvh) * D;
 
   const int cache_tiles = (ci.n + 1 + AT_COLS - 1) / AT_COLS;          // slots [0, n], the free one masked
-  const int last_row = min(row_tile * ROW_TILE + ROW_TILE, L) - 1;     // last chunk row of the workgroup
+  const int last_row = min(rbase + ROW_TILE, L) - 1;                   // last chunk row of the workgroup
   const int chunk_tiles = last_row / AT_COLS + 1;                      // causal: columns <= last_row
   const int ntiles = cache_tiles + chunk_tiles;
+  const float sc = p.scale_log2e;
+  const int n_cached = ci.n, fslot = ci.fslot;
+  const int cache_lim = p.cap - 1, chunk_lim = L - 1;                   // last row that exists
+
+  // ------------------------------------------------------------------------------------------
+  // sweep 1: row statistics
+  // ------------------------------------------------------------------------------------------
+  float neg_ml0, neg_ml1;              // -(max + log2(sum)) in the scaled log2 domain, rows of the two sweep-2 blocks
+  {
+    float m_run[4], l_run[4];          // this lane's columns of row rb*16 + lr: max of the scaled logits, sum of exp2
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) { m_run[rb] = NEG_BIG; l_run[rb] = 0.f; }
+    // K tiles go through LDS here too (two stages): 16 lanes fetch one row with 16-byte loads, which the memory
+    // pipeline coalesces; MFMA operand order (consecutive lanes = consecutive rows) straight from global does not.
+    constexpr int RPP = AT_THREADS / PARTS;          // rows per pass of the 512 threads
+    constexpr int NPASS = AT_COLS / RPP;             // passes per tile (4 at d=128, 2 at d=64)
+    const int s_row = tid / PARTS, s_part = tid % PARTS;
+    uint4 kr0, kr1, kr2, kr3;
+    kr0 = kr1 = kr2 = kr3 = make_uint4(0, 0, 0, 0);
+    auto load_k = [&](int tile) {
+      const bool is_cache = tile < cache_tiles;
+      const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
+      const uint16_t* base = (is_cache ? Ku : Kcu) + s_part * 8;
+      const int rstride = is_cache ? D : chunk_row_stride;
+      const int lim = is_cache ? cache_lim : chunk_lim;
+      auto ld = [&](int x) { return *reinterpret_cast<const uint4*>(base + (size_t)min(col0 + s_row + x * RPP, lim) * rstride); };
+      kr0 = ld(0); kr1 = ld(1);
+      if constexpr (NPASS > 2) { kr2 = ld(2); kr3 = ld(3); }
+    };
+    auto store_k = [&](int buf) {
+      uint16_t* dst = sK + buf * Lds::K_ELEMS + s_row * Lds::KSTRIDE + s_part * 8;
+      *reinterpret_cast<uint4*>(dst) = kr0;
+      *reinterpret_cast<uint4*>(dst + RPP * Lds::KSTRIDE) = kr1;
+      if constexpr (NPASS > 2) {
+        *reinterpret_cast<uint4*>(dst + 2 * RPP * Lds::KSTRIDE) = kr2;
+        *reinterpret_cast<uint4*>(dst + 3 * RPP * Lds::KSTRIDE) = kr3;
+      }
+    };
+    // S^T of this wave's 16 columns of a staged tile against the 64 rows
+    const int k1_off = (wave * 16 + lr) * Lds::KSTRIDE + q4 * 8;
+    auto qk = [&](f32x4_t (&s)[4], int buf) {
+      const uint16_t* kp = sK + buf * Lds::K_ELEMS + k1_off;
+      uint4 k[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) k[ks] = *reinterpret_cast<const uint4*>(kp + ks * 32);
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) s[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) s[rb] = mfma16(k[ks], qa[rb][ks], s[rb]);
+    };
+    // Masked logits become -inf: their exp2 is 0 against any finite running max, and a lane that has seen
+    // nothing yet keeps its (finite) initial max, so no probability needs a guard.
+    auto stats = [&](f32x4_t (&s)[4], int tile) {
+      const bool is_cache = tile < cache_tiles;
+      const int c0 = (is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS) + wave * 16;   // this wave's 16 columns
+      // only tiles that touch the end of the cache, the free slot or the causal diagonal need a mask (wave uniform)
+      const bool need_mask = is_cache ? (c0 + 15 > n_cached || (fslot >= c0 && fslot < c0 + 16)) : (c0 + 15 > rbase);
+      if (need_mask) {
+        const int excl = is_cache ? fslot : -1;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+          const int lim = is_cache ? n_cached : rbase + rb * 16 + lr;      // last visible column of this lane's row
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int col = c0 + q4 * 4 + i;
+            s[rb][i] = (col <= lim && col != excl) ? s[rb][i] : -INFINITY;
+          }
+        }
+      }
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        // The running max lives in the scaled domain: exp2(m_run - m_new) is then exactly 1 when the max stays.
+        const float m_new = fmaxf(m_run[rb], max3(s[rb][0], s[rb][1], fmaxf(s[rb][2], s[rb][3])) * sc);
+        const float e0 = fast_exp2(fmaf(s[rb][0], sc, -m_new)), e1 = fast_exp2(fmaf(s[rb][1], sc, -m_new));
+        const float e2 = fast_exp2(fmaf(s[rb][2], sc, -m_new)), e3 = fast_exp2(fmaf(s[rb][3], sc, -m_new));
+        l_run[rb] = fmaf(l_run[rb], fast_exp2(m_run[rb] - m_new), (e0 + e1) + (e2 + e3));
+        m_run[rb] = m_new;
+      }
+    };
+    // Software pipeline: while the statistics of tile t are updated (vector ALU), the logits of tile t+1 are
+    // formed (matrix pipe) and tile t+2 is on its way from global memory.  One barrier per tile.
+    f32x4_t sa[4], sb[4];
+    load_k(0);
+    store_k(0);
+    if (ntiles > 1) { load_k(1); store_k(1); }
+    __syncthreads();
+    qk(sa, 0);
+    __syncthreads();                    // stage 0 is overwritten below
+    auto step = [&](f32x4_t (&cur)[4], f32x4_t (&nxt)[4], int t) {
+      if (t + 2 < ntiles) load_k(t + 2);
+      if (t + 1 < ntiles) qk(nxt, (t + 1) & 1);
+      stats(cur, t);
+      if (t + 2 < ntiles) store_k(t & 1);        // tile t's stage: last read one barrier ago
+      __syncthreads();
+    };
+    for (int t = 0; t < ntiles; t += 2) {
+      step(sa, sb, t);
+      if (t + 1 < ntiles) step(sb, sa, t + 1);
+    }
+    // merge the four lanes that share a row, then the eight waves through LDS
+    float* st = reinterpret_cast<float*>(pf_smem);       // [8 waves][64 rows][2]
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+#pragma unroll
+      for (int off = 16; off <= 32; off <<= 1) {
+        const float mo = __shfl_xor(m_run[rb], off, 64), lo = __shfl_xor(l_run[rb], off, 64);
+        const float mn = fmaxf(m_run[rb], mo);
+        l_run[rb] = l_run[rb] * fast_exp2(m_run[rb] - mn) + lo * fast_exp2(mo - mn);
+        m_run[rb] = mn;
+      }
+      if (q4 == 0) {
+        st[(wave * 64 + rb * 16 + lr) * 2] = m_run[rb];
+        st[(wave * 64 + rb * 16 + lr) * 2 + 1] = l_run[rb];
+      }
+    }
+    __syncthreads();
+    auto final_of = [&](int r) {       // r: row inside the workgroup's 64
+      float mx = NEG_BIG;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) mx = fmaxf(mx, st[(w * 64 + r) * 2]);
+      float l = 0.f;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) l += st[(w * 64 + r) * 2 + 1] * fast_exp2(st[(w * 64 + r) * 2] - mx);
+      // rows past the chunk get probabilities of zero: they must not reach the column sums
+      return rbase + r < L ? -(mx + __log2f(l)) : NEG_BIG;
+    };
+    neg_ml0 = final_of(rg * 32 + lr);
+    neg_ml1 = final_of(rg * 32 + 16 + lr);
+    __syncthreads();                   // the staging below reuses this LDS
+  }
+
+  // ------------------------------------------------------------------------------------------
+  // sweep 2: outputs and column sums
+  // ------------------------------------------------------------------------------------------
+  const int row0 = rbase + rg * 32;                        // first chunk row of this wave
+  const int my_row0 = row0 + lr, my_row1 = row0 + 16 + lr; // the query rows this lane's results belong to
+  uint4 qa0[KS], qa1[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    const uint4 a0 = qa[0][ks], a1 = qa[1][ks], a2 = qa[2][ks], a3 = qa[3][ks];   // values, not addresses, into the select
+    qa0[ks] = rg ? a2 : a0;
+    qa1[ks] = rg ? a3 : a1;
+  }
 
   // ---- staging: global -> registers -> LDS (named registers: arrays here end up in scratch memory) ----
   uint4 g0, g1, g2, g3, g4, g5, g6, g7;
@@ -160,7 +331,6 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const int k_r0 = st / PARTS, k_part = st % PARTS;
   const uint16_t* cache_base = (v_role ? Vu : Ku) + (v_role ? v_part : k_part) * 8;
   const uint16_t* chunk_base = (v_role ? Vcu : Kcu) + (v_role ? v_part : k_part) * 8;
-  const int cache_lim = p.cap - 1, chunk_lim = L - 1;                   // last row that exists
   auto load_regs = [&](int tile) {
     const bool is_cache = tile < cache_tiles;
     const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
@@ -234,41 +404,25 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const int va_row = (lr * Lds::VSTRIDE) * 2;
   const int va_pair = cq * 4 + q4;                                                     // swizzled with d & 7 per read
 
-  float m0 = NEG_BIG, m1 = NEG_BIG;    // running row max of the raw logits over this wave's columns, per row block
-  float l0 = 0.f, l1 = 0.f;
   f32x4_t o0[DB], o1[DB];
 #pragma unroll
   for (int d = 0; d < DB; ++d) { o0[d] = f32x4_t{0.f, 0.f, 0.f, 0.f}; o1[d] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
-  const float sc = p.scale_log2e;
-  const int n_cached = ci.n, fslot = ci.fslot;
 
-  // softmax of one row block's 8 logits against its running state; returns the packed hi / lo P^T operands
-  auto soft = [&](f32x4_t (&s)[2], float& m_run, float& l_part, f32x4_t (&oacc)[DB], bool need_mask, uint4& phi, uint4& plo) {
-    float mx = m_run;
-#pragma unroll
-    for (int bk = 0; bk < 2; ++bk)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[bk][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    if (__any(mx != m_run)) {                 // the running max moved for some row of the block: rescale
-      const float corr = fast_exp2((m_run - mx) * sc);
-      l_part *= corr;
-#pragma unroll
-      for (int d = 0; d < DB; ++d) oacc[d] *= corr;
-      m_run = mx;
-    }
-    const float neg_ms = -mx * sc;
+  // the part of the head's column-sum array this wave writes: [cache columns rounded up to a tile | chunk columns]
+  const int cap_cols = (p.cap + AT_COLS - 1) / AT_COLS * AT_COLS;
+  const int cs_stride = cap_cols + (p.max_chunk + AT_COLS - 1) / AT_COLS * AT_COLS;
+  const int n_parts = 2 * ((p.max_chunk + ROW_TILE - 1) / ROW_TILE);
+  float* cs_part = p.pf_colpart + (((size_t)unit * p.G + g) * n_parts + row_tile * 2 + rg) * cs_stride + cq * 32 + q4 * 4;
+
+  // probabilities of one row block's 8 logits: the packed hi / lo P^T operands; the values themselves in place of s
+  auto soft = [&](f32x4_t (&s)[2], float neg_ml, uint4& phi, uint4& plo) {
     unsigned hi[4], lo[4];                    // k-slots 0-3 = block 0, i = 0..3; k-slots 4-7 = block 1
 #pragma unroll
     for (int e2 = 0; e2 < 4; ++e2) {
-      const float s0 = s[e2 >> 1][(e2 & 1) * 2], s1 = s[e2 >> 1][(e2 & 1) * 2 + 1];
-      float p0 = fast_exp2(fmaf(s0, sc, neg_ms)), p1 = fast_exp2(fmaf(s1, sc, neg_ms));
-      if (need_mask) {                        // a row with nothing visible yet has max == NEG_BIG: exp2(0) must not count
-        p0 = s0 > 0.5f * NEG_BIG ? p0 : 0.f;
-        p1 = s1 > 0.5f * NEG_BIG ? p1 : 0.f;
-      }
-      l_part += p0 + p1;
+      const float p0 = fast_exp2(fmaf(s[e2 >> 1][(e2 & 1) * 2], sc, neg_ml));
+      const float p1 = fast_exp2(fmaf(s[e2 >> 1][(e2 & 1) * 2 + 1], sc, neg_ml));
+      s[e2 >> 1][(e2 & 1) * 2] = p0;
+      s[e2 >> 1][(e2 & 1) * 2 + 1] = p1;
       hi[e2] = pack_bf16(p0, p1);
       lo[e2] = pack_bf16(p0 - __uint_as_float(hi[e2] << 16), p1 - __uint_as_float(hi[e2] & 0xffff0000u));
     }
@@ -303,19 +457,21 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     const bool need_mask = is_cache ? (col0 + AT_COLS - 1 > n_cached || (fslot >= col0 && fslot < col0 + AT_COLS))
                                     : (col0 + AT_COLS - 1 > row0);
     if (need_mask) {
+      const int cbase = col0 + cq * 32 + q4 * 4;
+      const int excl = is_cache ? fslot : -1;
+      const int lim0 = is_cache ? n_cached : my_row0, lim1 = is_cache ? n_cached : my_row1;   // last visible column
 #pragma unroll
       for (int bk = 0; bk < 2; ++bk)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int col = col0 + cq * 32 + bk * 16 + q4 * 4 + i;
-          const bool cvis = is_cache ? (col <= n_cached && col != fslot) : true;
-          s0[bk][i] = (cvis && (is_cache || col <= my_row0)) ? s0[bk][i] : NEG_BIG;
-          s1[bk][i] = (cvis && (is_cache || col <= my_row1)) ? s1[bk][i] : NEG_BIG;
+          const int col = cbase + bk * 16 + i;
+          s0[bk][i] = (col <= lim0 && col != excl) ? s0[bk][i] : -INFINITY;   // exp2 gives exactly 0
+          s1[bk][i] = (col <= lim1 && col != excl) ? s1[bk][i] : -INFINITY;
         }
     }
     uint4 phi0, plo0, phi1, plo1;
-    soft(s0, m0, l0, o0, need_mask, phi0, plo0);
-    soft(s1, m1, l1, o1, need_mask, phi1, plo1);
+    soft(s0, neg_ml0, phi0, plo0);
+    soft(s1, neg_ml1, phi1, plo1);
     // O^T += V^T P^T : A = V^T[d][the quarter's 8 k-slot columns of this lane group], B = P^T (hi and lo parts)
 #pragma unroll
     for (int d = 0; d < DB; ++d) {
@@ -325,210 +481,53 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       o0[d] = mfma16(a, plo0, o0[d]);
       o1[d] = mfma16(a, plo1, o1[d]);
     }
+    // column sums over this wave's 32 rows
+    {
+      float* dst = cs_part + (is_cache ? col0 : cap_cols + col0);
+#pragma unroll
+      for (int bk = 0; bk < 2; ++bk) {
+        float4 c;
+        c.x = row16_sum(s0[bk][0] + s1[bk][0]);
+        c.y = row16_sum(s0[bk][1] + s1[bk][1]);
+        c.z = row16_sum(s0[bk][2] + s1[bk][2]);
+        c.w = row16_sum(s0[bk][3] + s1[bk][3]);
+        if (lr == 0) *reinterpret_cast<float4*>(dst + bk * 16) = c;
+      }
+    }
     if (tile + 1 < ntiles) store_lds((tile + 1) & 1);      // the other stage: last read one barrier ago
     __syncthreads();
   }
 
-  // ---- merge the four column quarters of every row group through LDS ----
-  float* xch = reinterpret_cast<float*>(pf_smem);           // [6 waves][2 blocks][2 + DB*4][64 lanes]
-  constexpr int XN = 2 + DB * 4;
+  // ---- add the four column quarters of every row group through LDS ----
+  float* xch = reinterpret_cast<float*>(pf_smem);           // [6 waves][2 blocks][DB*4][64 lanes]
+  constexpr int XN = DB * 4;
   if (cq > 0) {
     float* dst = xch + (((cq - 1) * 2 + rg) * 2 * XN) * 64 + lane;
-    dst[0] = m0; dst[64] = l0;
 #pragma unroll
     for (int d = 0; d < DB; ++d)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) dst[(2 + d * 4 + i) * 64] = o0[d][i];
-    dst += XN * 64;
-    dst[0] = m1; dst[64] = l1;
-#pragma unroll
-    for (int d = 0; d < DB; ++d)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) dst[(2 + d * 4 + i) * 64] = o1[d][i];
+      for (int i = 0; i < 4; ++i) { dst[(d * 4 + i) * 64] = o0[d][i]; dst[(XN + d * 4 + i) * 64] = o1[d][i]; }
   }
   __syncthreads();
   if (cq > 0) return;
-  auto merge_in = [&](const float* src, float& m_run, float& l_part, f32x4_t (&oacc)[DB]) {
-    const float mo = src[0], lo2 = src[64];
-    const float mx = fmaxf(m_run, mo);
-    const float ca = fast_exp2((m_run - mx) * sc), cb = fast_exp2((mo - mx) * sc);
-    l_part = l_part * ca + lo2 * cb;
+#pragma unroll
+  for (int c = 0; c < 3; ++c) {
+    const float* src = xch + ((c * 2 + rg) * 2 * XN) * 64 + lane;
 #pragma unroll
     for (int d = 0; d < DB; ++d)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) oacc[d][i] = oacc[d][i] * ca + src[(2 + d * 4 + i) * 64] * cb;
-    m_run = mx;
-  };
-  for (int c = 0; c < 3; ++c) {
-    const float* src = xch + ((c * 2 + rg) * 2 * XN) * 64 + lane;
-    merge_in(src, m0, l0, o0);
-    merge_in(src + XN * 64, m1, l1, o1);
+      for (int i = 0; i < 4; ++i) { o0[d][i] += src[(d * 4 + i) * 64]; o1[d][i] += src[(XN + d * 4 + i) * 64]; }
   }
-  auto finish = [&](int my_row, float m_run, float l_part, const f32x4_t (&oacc)[DB]) {
-    float l_row = l_part + __shfl_xor(l_part, 16, 64);
-    l_row += __shfl_xor(l_row, 32, 64);
-    const float inv = 1.0f / l_row;
+  auto finish = [&](int my_row, const f32x4_t (&oacc)[DB]) {
     if (my_row < L) {
       float* op = out + (((size_t)b * L + my_row) * p.H + h) * D;
 #pragma unroll
-      for (int d = 0; d < DB; ++d) {
-        float4 o = make_float4(oacc[d][0] * inv, oacc[d][1] * inv, oacc[d][2] * inv, oacc[d][3] * inv);
-        *reinterpret_cast<float4*>(op + d * 16 + q4 * 4) = o;
-      }
-      if (q4 == 0) {
-        float* rs = p.pf_rowstat + (((size_t)unit * p.G + g) * p.max_chunk + my_row) * 2;
-        rs[0] = m_run * sc;                   // row max in the scaled log2 domain
-        rs[1] = inv;
-      }
+      for (int d = 0; d < DB; ++d)
+        *reinterpret_cast<float4*>(op + d * 16 + q4 * 4) = make_float4(oacc[d][0], oacc[d][1], oacc[d][2], oacc[d][3]);
     }
   };
-  finish(my_row0, m0, l0, o0);
-  finish(my_row1, m1, l1, o1);
-}
-
-// ---------------------------------------------------------------------------------------------
-// colsum
-// ---------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(PF_THREADS) void prefill_colsum_kernel(Params p, const uint16_t* __restrict__ Q,
-                                                                    const uint16_t* __restrict__ Kc, int L) {
-  constexpr int KS = D / 32;
-  constexpr int WAVES = PF_THREADS / 64;
-  constexpr int QSTRIDE = D + 8;                    // bf16 elements per staged Q row (padded: conflict-free b128 reads)
-  constexpr int LPR = D / 8;                        // lanes that cover one Q row with 16-byte loads
-  constexpr int QLOADS = 16 * LPR / 64;             // loads per lane for a 16-row tile (4 at d=128, 2 at d=64)
-  __shared__ float sm_cs[WAVES][COL_TILE];
-  __shared__ __attribute__((aligned(16))) uint16_t sm_q[WAVES][16 * QSTRIDE];   // one 16-row Q tile per wave
-
-  const int unit = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lr = lane & 15, q4 = lane >> 4;
-  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
-  const ChunkInfo ci = load_chunk_info(p.meta + (size_t)unit * META_STRIDE);
-
-  const int max_cache_tiles = (p.cap + COL_TILE - 1) / COL_TILE;
-  const bool is_cache = (int)blockIdx.x < max_cache_tiles;
-  const int col0 = is_cache ? blockIdx.x * COL_TILE : ((int)blockIdx.x - max_cache_tiles) * COL_TILE;
-  if (is_cache ? col0 > ci.n : col0 >= L) return;          // nothing visible in this tile (uniform)
-
-  // the tile's K rows as B operands, held in registers for the whole kernel
-  uint4 kb[4][KS];
-  bool colvis[4];                                           // validity of this lane's column in each block
-#pragma unroll
-  for (int bk = 0; bk < 4; ++bk) {
-    const int col = col0 + bk * 16 + lr;
-    const uint16_t* ks = is_cache ? (const uint16_t*)p.K + ((size_t)unit * p.cap + min(col, p.cap - 1)) * D
-                                  : Kc + (((size_t)b * L + min(col, L - 1)) * p.Hkv + kvh) * D;
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) kb[bk][kk] = *reinterpret_cast<const uint4*>(ks + kk * 32 + q4 * 8);
-    colvis[bk] = is_cache ? (col <= ci.n && col != ci.fslot) : (col < L);
-  }
-
-  float cs0 = 0.f, cs1 = 0.f, cs2 = 0.f, cs3 = 0.f;
-  const int first_rt = is_cache ? 0 : col0 / 16;            // causal: rows below the tile's first column see none of it
-  const int n_rt = (L + 15) / 16;
-  const float sc = p.scale_log2e;
-  const int Lm1 = L - 1;
-  const size_t q_row_stride = (size_t)p.H * D;
-
-  // One item = one 16-row tile of one query head against the 64 columns.  Items are dealt round robin
-  // to the waves.  Q rows are 8 KB apart in the caller's [B, L, H, d] layout, so they are fetched as whole
-  // rows (16 lanes per row), parked in a wave-private LDS tile and read back in MFMA operand order.
-  const int q_lrow = lane / LPR, q_lpart = lane % LPR;      // this lane's row (of each group of 64/LPR rows) and piece
-  uint16_t* myq = sm_q[wave];
-  auto fetch = [&](uint4& iq0, uint4& iq1, uint4& iq2, uint4& iq3, float4& is01, float4& is23, int g, int rt) {
-    const uint16_t* qp = Q + ((size_t)b * L) * q_row_stride + (size_t)(kvh * p.G + g) * D + q_lpart * 8;
-    auto row = [&](int x) { return qp + (size_t)min(rt * 16 + q_lrow + x * (64 / LPR), Lm1) * q_row_stride; };
-    iq0 = *reinterpret_cast<const uint4*>(row(0));
-    iq1 = *reinterpret_cast<const uint4*>(row(1));
-    if constexpr (QLOADS > 2) {
-      iq2 = *reinterpret_cast<const uint4*>(row(2));
-      iq3 = *reinterpret_cast<const uint4*>(row(3));
-    }
-    // results land on rows rt*16 + q4*4 + {0..3}: their (max, 1/sum) pairs are 32 contiguous bytes
-    // (rows past L hold stale values; the array is padded and those rows are masked out below)
-    const float* rs = p.pf_rowstat + (((size_t)unit * p.G + g) * p.max_chunk + rt * 16 + q4 * 4) * 2;
-    is01 = *reinterpret_cast<const float4*>(rs);
-    is23 = *reinterpret_cast<const float4*>(rs + 4);
-  };
-  auto compute = [&](const uint4& iq0, const uint4& iq1, const uint4& iq2, const uint4& iq3, const float4& is01,
-                     const float4& is23, int rt) {
-    // rows of the tile past L, or the causal diagonal
-    const bool special = (rt * 16 + 15 > Lm1) || (!is_cache && col0 + COL_TILE - 1 > rt * 16);
-    const float m0 = is01.x, i0 = is01.y, m1 = is01.z, i1 = is01.w;
-    const float m2 = is23.x, i2 = is23.y, m3 = is23.z, i3 = is23.w;
-    // rows -> LDS -> A operands (row lr, k = ks*32 + q4*8 ..)
-    uint16_t* wq = myq + q_lrow * QSTRIDE + q_lpart * 8;
-    *reinterpret_cast<uint4*>(wq) = iq0;
-    *reinterpret_cast<uint4*>(wq + (64 / LPR) * QSTRIDE) = iq1;
-    if constexpr (QLOADS > 2) {
-      *reinterpret_cast<uint4*>(wq + 2 * (64 / LPR) * QSTRIDE) = iq2;
-      *reinterpret_cast<uint4*>(wq + 3 * (64 / LPR) * QSTRIDE) = iq3;
-    }
-    __builtin_amdgcn_wave_barrier();
-    const uint16_t* rq = myq + lr * QSTRIDE + q4 * 8;
-    const uint4 a0 = *reinterpret_cast<const uint4*>(rq);
-    const uint4 a1 = *reinterpret_cast<const uint4*>(rq + 32);
-    uint4 a2 = a0, a3 = a1;
-    if constexpr (KS > 2) {
-      a2 = *reinterpret_cast<const uint4*>(rq + 64);
-      a3 = *reinterpret_cast<const uint4*>(rq + 96);
-    }
-    __builtin_amdgcn_wave_barrier();
-    auto block = [&](int bk, float& cs) {
-      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-      acc = mfma16(a0, kb[bk][0], acc);
-      acc = mfma16(a1, kb[bk][1], acc);
-      if constexpr (KS > 2) {
-        acc = mfma16(a2, kb[bk][2], acc);
-        acc = mfma16(a3, kb[bk][3], acc);
-      }
-      float p0 = fast_exp2(fmaf(acc[0], sc, -m0)) * i0;
-      float p1 = fast_exp2(fmaf(acc[1], sc, -m1)) * i1;
-      float p2 = fast_exp2(fmaf(acc[2], sc, -m2)) * i2;
-      float p3 = fast_exp2(fmaf(acc[3], sc, -m3)) * i3;
-      if (special) {
-        const int col = col0 + bk * 16 + lr, row = rt * 16 + q4 * 4;
-        p0 = (row + 0 <= Lm1 && (is_cache || col <= row + 0)) ? p0 : 0.f;
-        p1 = (row + 1 <= Lm1 && (is_cache || col <= row + 1)) ? p1 : 0.f;
-        p2 = (row + 2 <= Lm1 && (is_cache || col <= row + 2)) ? p2 : 0.f;
-        p3 = (row + 3 <= Lm1 && (is_cache || col <= row + 3)) ? p3 : 0.f;
-      }
-      cs += (p0 + p1) + (p2 + p3);
-    };
-    block(0, cs0); block(1, cs1); block(2, cs2); block(3, cs3);
-  };
-  const uint4 z4 = make_uint4(0, 0, 0, 0);
-  const float4 zf = make_float4(0.f, 0.f, 0.f, 0.f);
-  // One Q tile in flight per wave: with the K tile held in registers, a second buffered tile costs more in
-  // occupancy than it hides in latency (measured).
-  for (int g = 0; g < p.G; ++g) {
-    uint4 aq0 = z4, aq1 = z4, aq2 = z4, aq3 = z4;
-    float4 as01 = zf, as23 = zf;
-    for (int rt = first_rt + wave; rt < n_rt; rt += WAVES) {
-      fetch(aq0, aq1, aq2, aq3, as01, as23, g, rt);
-      compute(aq0, aq1, aq2, aq3, as01, as23, rt);
-    }
-  }
-  float cs[4] = {colvis[0] ? cs0 : 0.f, colvis[1] ? cs1 : 0.f, colvis[2] ? cs2 : 0.f, colvis[3] ? cs3 : 0.f};
-#pragma unroll
-  for (int bk = 0; bk < 4; ++bk) {
-    cs[bk] += __shfl_xor(cs[bk], 16, 64);
-    cs[bk] += __shfl_xor(cs[bk], 32, 64);
-    if (q4 == 0) sm_cs[wave][bk * 16 + lr] = cs[bk];
-  }
-  __syncthreads();
-  if (tid < COL_TILE) {
-    float tot = 0.f;
-#pragma unroll
-    for (int w = 0; w < WAVES; ++w) tot += sm_cs[w][tid];
-    const int col = col0 + tid;
-    if (is_cache) {
-      if (col <= ci.n && col != ci.fslot) p.S[(size_t)unit * p.cap + col] += tot;
-    } else if (col < L) {
-      p.pf_snew[(size_t)unit * p.max_chunk + col] = tot;
-    }
-  }
+  finish(my_row0, o0);
+  finish(my_row1, o1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -573,13 +572,12 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
   int* Eg = p.E + (size_t)unit * 2 * p.m;
   int* PEg = p.PE + (size_t)unit * 2 * p.m;
   int* Rg = p.R + (size_t)unit * max(p.n_recent, 1);
-  const float* snew_g = p.pf_snew + (size_t)unit * p.max_chunk;
+  float* snew_w = p.pf_snew + (size_t)unit * p.max_chunk;    // the chunk tokens' scores (moved into LDS below)
   int* flag_g = p.pf_flag + (size_t)unit * (p.cap + p.max_chunk);
   int32_t* evu = evicted ? evicted + (size_t)unit * L : nullptr;
 
   float* Su = Sg;
   int *Eu = Eg, *PEu = PEg, *Ru = Rg;
-  const float* snew = snew_g;
   int* flag = flag_g;              // [0,cap): slot freed; [cap, cap+L): chunk token dead -> later its destination slot
   int* free_list = p.pf_list + (size_t)unit * (p.cap + p.max_chunk);
   if constexpr (IN_LDS) {
@@ -592,14 +590,57 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
     free_list = w; w += L + 2;
     Ru = w;
     for (int i = tid; i < 2 * p.m; i += RP_THREADS) { Eu[i] = Eg[i]; PEu[i] = PEg[i]; }
-    for (int i = tid; i < p.cap; i += RP_THREADS) Su[i] = Sg[i];
-    for (int i = tid; i < L; i += RP_THREADS) sn[i] = snew_g[i];
     for (int i = tid; i < p.n_recent; i += RP_THREADS) Ru[i] = Rg[i];
-    snew = sn;
-    __syncthreads();
+    snew_w = sn;
   }
 
   const int n0 = meta[META_N], f0 = meta[META_FREE], j0 = meta[META_J], rhead0 = meta[META_RHEAD], t0 = meta[META_T];
+
+  // ---- Algorithm 1, line 8 for the whole chunk: add the attend kernel's column-sum parts, in a fixed order ----
+  {
+    const int cap_cols = (p.cap + AT_COLS - 1) / AT_COLS * AT_COLS;
+    const int cs_stride = cap_cols + (p.max_chunk + AT_COLS - 1) / AT_COLS * AT_COLS;
+    const int n_parts = 2 * ((p.max_chunk + ROW_TILE - 1) / ROW_TILE);
+    const int used = 2 * ((L + ROW_TILE - 1) / ROW_TILE);          // parts the attend kernel wrote
+    const float* cp = p.pf_colpart + (size_t)unit * p.G * n_parts * cs_stride;
+    // four columns per thread and step, so that all the parts' loads are in flight together
+    for (int i4 = tid * 4; i4 < p.cap; i4 += RP_THREADS * 4) {
+      float4 add = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int g = 0; g < p.G; ++g)
+        for (int part = 0; part < used; ++part) {
+          const float4 x = *reinterpret_cast<const float4*>(cp + ((size_t)g * n_parts + part) * cs_stride + i4);
+          add.x += x.x; add.y += x.y; add.z += x.z; add.w += x.w;
+        }
+      const float a[4] = {add.x, add.y, add.z, add.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = i4 + e;
+        if (i < p.cap) {
+          float v = Sg[i];
+          if (i <= n0 && i != f0) {                                  // the columns every row tile visited
+            v += a[e];
+            Sg[i] = v;
+          }
+          if constexpr (IN_LDS) Su[i] = v;
+        }
+      }
+    }
+    for (int i4 = tid * 4; i4 < L; i4 += RP_THREADS * 4) {
+      // chunk columns of column tile i4 / 128 are visited by row tiles 2 * (i4 / 128) and up (causal)
+      float4 add = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int g = 0; g < p.G; ++g)
+        for (int part = 4 * (i4 / AT_COLS); part < used; ++part) {
+          const float4 x = *reinterpret_cast<const float4*>(cp + ((size_t)g * n_parts + part) * cs_stride + cap_cols + i4);
+          add.x += x.x; add.y += x.y; add.z += x.z; add.w += x.w;
+        }
+      const float a[4] = {add.x, add.y, add.z, add.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (i4 + e < L) snew_w[i4 + e] = a[e];
+    }
+    __syncthreads();
+  }
+  const float* snew = snew_w;
   const int cap = p.cap, c = p.budget, m = p.m, r = p.n_recent;
   const int F = min(L, c - n0);            // tokens that still fit without eviction (they take slots n0 ..)
   const int Lev = L - F;                   // tokens that each trigger one eviction
@@ -792,8 +833,6 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
     return TREEKV_EHIP;
   const int n_items = row_tiles * p.G * p.U;
   hipLaunchKernelGGL(attend, dim3((n_items + 7) / 8 * 8), dim3(AT_THREADS), lds, s, p, q, k, v, L, row_tiles, out);
-  const int col_tiles = (p.cap + COL_TILE - 1) / COL_TILE + (L + COL_TILE - 1) / COL_TILE;
-  hipLaunchKernelGGL((prefill_colsum_kernel<D>), dim3(col_tiles, p.U), dim3(PF_THREADS), 0, s, p, q, k, L);
   const size_t rp_lds = replay_lds_words(p.m, p.cap, p.n_recent, L) * sizeof(int);
   if (rp_lds <= 140 * 1024) {
     auto replay = prefill_replay_kernel<true>;
