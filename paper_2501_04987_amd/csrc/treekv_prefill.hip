@@ -67,52 +67,23 @@ __device__ inline unsigned pack_bf16(float a, float b) {
 constexpr int AT_THREADS = 512;   // 8 waves
 constexpr int AT_COLS = 128;      // columns per staged tile of the attend kernel
 
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(3))) short4_t lds_short4_t;
+
+// LDS of the attend kernel: K and V tiles exactly as they lie in memory (row-major, 128 rows each),
+// two stages of each; the 16-byte pieces of a row are XOR-swizzled (see the kernel).
 template <int D>
 struct AttendLds {
-  static constexpr int KSTRIDE = D + 8;          // bf16 elements per staged K row (padded: conflict-free b128 reads)
-  static constexpr int VSTRIDE = AT_COLS + 8;    // bf16 elements per staged V^T row
-  static constexpr int K_ELEMS = AT_COLS * KSTRIDE;
-  static constexpr int V_ELEMS = D * VSTRIDE;
-  static constexpr size_t BYTES = 2 * (size_t)(K_ELEMS + V_ELEMS) * sizeof(uint16_t);   // two stages
+  static constexpr int TILE_ELEMS = AT_COLS * D;                 // bf16 elements of one staged tile
+  static constexpr size_t BYTES = 4 * (size_t)TILE_ELEMS * sizeof(uint16_t);
 };
 
-// One workgroup owns 64 query rows of one head and passes over the visible columns twice.
-//
-// Sweep 1 finds every row's softmax statistics (max, sum).  No LDS and no barriers: wave w takes the
-// 16-column block w of every 128-column tile against all 64 rows, its K rows loaded straight from
-// global memory in MFMA operand order (every K row is read once per workgroup).  Each lane keeps a
-// running (max, sum) for its own columns of its four rows; lanes and waves are merged once, at the end.
-//
-// Sweep 2 recomputes the logits and, knowing the statistics, forms the normalised probabilities
-// directly: p = exp2(s*scale - max - log2(sum)), no running maximum and nothing to rescale.  They feed
-// O^T += V^T P^T and, summed down the rows, the per-column score increments (Algorithm 1, line 8).
-// Here K and V^T tiles are staged through LDS, double buffered, and the 8 waves are 2 row groups (32 rows
-// = two 16-row MFMA blocks) x 4 column quarters (32 columns of every tile): each K / V^T operand read
-// from LDS feeds the MFMAs of two row blocks, and two waves share a SIMD so that one's exp / convert
-// work overlaps the other's MFMAs.  The four quarters of a row group add their O through LDS at the end.
-// Threads 0-255 stage V (transposing), threads 256-511 stage K.
-//
-// Column sums: a wave adds its two row blocks, reduces over the 16 lanes that hold the 16 rows and
-// writes the 32 sums of its columns to part row_tile*2 + row_group of the head's partial array;
-// the replay kernel adds the parts in a fixed order.  A workgroup writes every column of every tile it
-// visits (masked entries as zeros) and nothing else.
-//
-// Staged V^T layout.  Row d holds the tile's columns in the order the P^T operand uses them: inside
-// quarter c, column j sits at position c*32 + ((j%16)/4)*8 + ((j%32)/16)*4 + j%4, so that the 8 k-slots of
-// lane group q4 (columns c*32 + q4*4 + {0..3} and c*32 + 16 + q4*4 + {0..3}) are the 16 contiguous
-// bytes of "pair" c*4 + q4.  Pairs are XOR-swizzled with (d/16)%8: the 16 lanes of an operand read share
-// d/16, so reads stay conflict free, while the transposing 8-byte writes of 16 lanes (same columns, rows 8
-// apart) spread over the banks.
 template <int CTRL>
 __device__ inline float dpp_add(float v) {
   const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
   return v + __int_as_float(moved);
 }
-// max of three.  This file is compiled with -fno-honor-nans: otherwise every fmaxf operand that comes out of
-// an MFMA costs an extra instruction that quiets signalling NaNs, and the pair is not fused into v_max3_f32.
-__device__ inline float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
-template <bool B> struct BoolTag { static constexpr bool value = B; };
-
 // Sum over the 16 lanes of a DPP row; every lane gets the total.
 __device__ inline float row16_sum(float v) {
   v = dpp_add<0x128>(v);           // row_ror:8
@@ -121,7 +92,58 @@ __device__ inline float row16_sum(float v) {
   v = dpp_add<0x121>(v);           // row_ror:1
   return v;
 }
+// max of three.  This file is compiled with -fno-honor-nans: otherwise every fmaxf operand that comes out of
+// an MFMA costs an extra instruction that quiets signalling NaNs, and the pair is not fused into v_max3_f32.
+__device__ inline float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
+// s_waitcnt vmcnt(N) alone (the other counters at their maxima, i.e. not waited for), N < 16
+template <int N>
+__device__ inline void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | N); }
+
+// Asynchronous copy of 16 bytes per lane from global memory into LDS: lane i's bytes land at
+// lds_base + 16 * i (lds_base: wave-uniform LDS byte address, taken from M0).  Written as assembly on
+// purpose: issued through the compiler's builtin, every later LDS read is preceded by a wait for all
+// outstanding copies (it cannot tell which LDS bytes they fill), which would undo the prefetching.
+// Completion is tracked by vmcnt like any load; the callers wait explicitly (wait_vmcnt) before the
+// barrier that publishes a tile.
+__device__ inline void async_copy16(const void* src, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(src), "s"(lds_base) : "memory");   // M0 is reserved: the compiler keeps nothing in it across statements
+}
+__device__ inline unsigned lds_address(const void* shared_ptr) {
+  return (unsigned)(uintptr_t)(lds_void_t*)shared_ptr;
+}
+
+// One workgroup owns 64 query rows of one head and passes over the visible columns twice, in tiles of 128.
+//
+// Staging.  Tiles go from global memory into LDS with asynchronous 16-byte loads (global_load_lds): no
+// registers, no LDS store instructions, and the next tiles are in flight while the current one is used.
+// One such instruction fills 1 KB of LDS in lane order, so a staged tile is row-major like the source; what
+// a lane is free to choose is which 16-byte piece of its row it fetches, and that gives the swizzle: slot s
+// of row r holds piece s ^ KSWZ(r) (K tiles) or s ^ VSWZ(r) (V tiles), chosen so that the operand reads
+// below touch every LDS bank once.
+//
+// Sweep 1 finds every row's softmax statistics (max, sum).  Wave w takes the 16-column block w of every
+// tile against all 64 rows (four 16-row MFMA blocks): S^T = K Q^T, K rows from LDS as A operands.  Each
+// lane keeps a running (max, sum) for its own columns of its four rows; lanes and waves are merged once,
+// at the end.  Four K stages, so tiles are requested three iterations before they are used.
+//
+// Sweep 2 recomputes the logits and, knowing the statistics, forms the normalised probabilities
+// directly: p = exp2(s*scale - max - log2(sum)), no running maximum and nothing to rescale.  They feed
+// O^T += V^T P^T and, summed down the rows, the per-column score increments (Algorithm 1, line 8).
+// The 8 waves are 2 row groups (32 rows = two 16-row MFMA blocks) x 4 column quarters (32 columns of
+// every tile).  S^T comes out of the MFMA with a lane holding 8 columns of one row, which is the B
+// operand layout of P^T, so P never leaves the registers; it is split into two bf16 halves (hi + lo) so that
+// rounding P costs 2^-16, not 2^-9.  The A operand V^T[d][8 columns] is read from the row-major V tile with
+// the transposing LDS read (ds_read_b64_tr_b16: 16 lanes fetch a 4 x 16 block and each gets one column).
+// Both sweeps are software pipelined: the logits of tile t+1 are formed (matrix pipe) while the
+// probabilities of tile t are worked out (vector ALU).  The four quarters of a row group add their O through
+// LDS at the end.
+//
+// Column sums: a wave adds its two row blocks, reduces over the 16 lanes that hold the 16 rows and
+// writes the 32 sums of its columns to part row_tile*2 + row_group of the head's partial array;
+// the replay kernel adds the parts in a fixed order.  A workgroup writes every column of every tile it
+// visits (masked entries as zeros) and nothing else.
 template <int D>
 __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, const uint16_t* __restrict__ Q,
                                                                     const uint16_t* __restrict__ Kc,
@@ -131,14 +153,17 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   constexpr int KS = D / 32;          // k-steps of the q.k contraction
   constexpr int DB = D / 16;          // 16-wide blocks of the head dimension
   constexpr int PARTS = D / 8;        // 16-byte pieces per row
-  constexpr int KCH = AT_COLS * PARTS / 256;           // K pieces per K-staging thread (4 or 8)
-  constexpr int VBL = (AT_COLS / 4) * PARTS / 256;     // 4-column x 8-dim V blocks per V-staging thread (1 or 2)
-  static_assert((KCH == 4 || KCH == 8) && (VBL == 1 || VBL == 2), "staging is written for head_dim 64 and 128");
-  constexpr int KROWS_PER_X = 256 / PARTS;             // rows between a K thread's consecutive pieces
-  constexpr int VJG_PER_X = 256 / PARTS;               // column groups between a V thread's two blocks
-  extern __shared__ __attribute__((aligned(16))) uint16_t pf_smem[];
-  uint16_t* sK = pf_smem;                               // [2][K_ELEMS]
-  uint16_t* sVt = pf_smem + 2 * Lds::K_ELEMS;           // [2][V_ELEMS]
+  constexpr int ROWB = D * 2;         // bytes per row
+  constexpr int RPC = 1024 / ROWB;    // rows per 1 KB async-load instruction (4 at d=128, 8 at d=64)
+  constexpr int CPW = AT_COLS / RPC / 8;               // such instructions per wave and tile (4 or 2)
+  static_assert(D == 64 || D == 128, "swizzles are written for head_dim 64 and 128");
+  extern __shared__ __attribute__((aligned(1024))) uint16_t pf_smem[];
+  uint16_t* sK = pf_smem;                               // sweep 2: [2][TILE_ELEMS]; sweep 1: all four stages
+  uint16_t* sV = pf_smem + 2 * Lds::TILE_ELEMS;         // [2][TILE_ELEMS]
+
+  // swizzles of the 16-byte slots of tile row r
+  auto kswz = [](int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); };
+  auto vswz = [](int r) { return D == 128 ? ((r & 7) << 1) : (((r >> 1) & 3) << 1); };
 
   // Workgroups are dealt to the 8 XCDs round robin by their linear id, and each XCD has its own L2.
   // The row tiles of one unit read the same K and V, so give them ids that land on one XCD:
@@ -147,7 +172,8 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const int item = ((int)blockIdx.x % 8) * per_xcd + (int)blockIdx.x / 8;
   if (item >= n_items) return;
   const int row_tile = item % row_tiles, g = (item / row_tiles) % p.G, unit = item / (row_tiles * p.G);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, q4 = lane >> 4;
   const int rg = wave & 1;                                 // sweep 2: rows 32*rg .. +31 of the workgroup's 64
   const int cq = wave >> 1;                                // sweep 2: column quarter of every tile
@@ -179,6 +205,23 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const int n_cached = ci.n, fslot = ci.fslot;
   const int cache_lim = p.cap - 1, chunk_lim = L - 1;                   // last row that exists
 
+  // ---- asynchronous tile loads: this wave's CPW instructions of 1 KB each ----
+  const int a_lrow = lane / PARTS, a_slot = lane % PARTS;
+  auto issue_tile = [&](const uint16_t* cache_src, const uint16_t* chunk_src, int tile, uint16_t* stage, auto swz) {
+    const bool is_cache = tile < cache_tiles;
+    const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
+    const uint16_t* base = is_cache ? cache_src : chunk_src;
+    const int rstride = is_cache ? D : chunk_row_stride;
+    const int lim = is_cache ? cache_lim : chunk_lim;
+#pragma unroll
+    for (int x = 0; x < CPW; ++x) {
+      const int c = wave * CPW + x;                       // 1 KB block of the stage (wave uniform)
+      const int r = c * RPC + a_lrow;                     // tile row this lane fetches from
+      const uint16_t* src = base + (size_t)min(col0 + r, lim) * rstride + (a_slot ^ swz(r)) * 8;
+      async_copy16(src, __builtin_amdgcn_readfirstlane(lds_address(stage + c * 512)));
+    }
+  };
+
   // ------------------------------------------------------------------------------------------
   // sweep 1: row statistics
   // ------------------------------------------------------------------------------------------
@@ -187,39 +230,15 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     float m_run[4], l_run[4];          // this lane's columns of row rb*16 + lr: max of the scaled logits, sum of exp2
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) { m_run[rb] = NEG_BIG; l_run[rb] = 0.f; }
-    // K tiles go through LDS here too (two stages): 16 lanes fetch one row with 16-byte loads, which the memory
-    // pipeline coalesces; MFMA operand order (consecutive lanes = consecutive rows) straight from global does not.
-    constexpr int RPP = AT_THREADS / PARTS;          // rows per pass of the 512 threads
-    constexpr int NPASS = AT_COLS / RPP;             // passes per tile (4 at d=128, 2 at d=64)
-    const int s_row = tid / PARTS, s_part = tid % PARTS;
-    uint4 kr0, kr1, kr2, kr3;
-    kr0 = kr1 = kr2 = kr3 = make_uint4(0, 0, 0, 0);
-    auto load_k = [&](int tile) {
-      const bool is_cache = tile < cache_tiles;
-      const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
-      const uint16_t* base = (is_cache ? Ku : Kcu) + s_part * 8;
-      const int rstride = is_cache ? D : chunk_row_stride;
-      const int lim = is_cache ? cache_lim : chunk_lim;
-      auto ld = [&](int x) { return *reinterpret_cast<const uint4*>(base + (size_t)min(col0 + s_row + x * RPP, lim) * rstride); };
-      kr0 = ld(0); kr1 = ld(1);
-      if constexpr (NPASS > 2) { kr2 = ld(2); kr3 = ld(3); }
-    };
-    auto store_k = [&](int buf) {
-      uint16_t* dst = sK + buf * Lds::K_ELEMS + s_row * Lds::KSTRIDE + s_part * 8;
-      *reinterpret_cast<uint4*>(dst) = kr0;
-      *reinterpret_cast<uint4*>(dst + RPP * Lds::KSTRIDE) = kr1;
-      if constexpr (NPASS > 2) {
-        *reinterpret_cast<uint4*>(dst + 2 * RPP * Lds::KSTRIDE) = kr2;
-        *reinterpret_cast<uint4*>(dst + 3 * RPP * Lds::KSTRIDE) = kr3;
-      }
-    };
     // S^T of this wave's 16 columns of a staged tile against the 64 rows
-    const int k1_off = (wave * 16 + lr) * Lds::KSTRIDE + q4 * 8;
-    auto qk = [&](f32x4_t (&s)[4], int buf) {
-      const uint16_t* kp = sK + buf * Lds::K_ELEMS + k1_off;
+    const int k1_row = wave * 16 + lr;
+    const int k1_off = k1_row * D;
+    const int k1_swz = kswz(k1_row);
+    auto qk = [&](f32x4_t (&s)[4], int stage) {
+      const uint16_t* kp = sK + stage * Lds::TILE_ELEMS + k1_off;
       uint4 k[KS];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) k[ks] = *reinterpret_cast<const uint4*>(kp + ks * 32);
+      for (int ks = 0; ks < KS; ++ks) k[ks] = *reinterpret_cast<const uint4*>(kp + ((ks * 4 + q4) ^ k1_swz) * 8);
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb) s[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -256,20 +275,22 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
         m_run[rb] = m_new;
       }
     };
-    // Software pipeline: while the statistics of tile t are updated (vector ALU), the logits of tile t+1 are
-    // formed (matrix pipe) and tile t+2 is on its way from global memory.  One barrier per tile.
+    // Iteration t: request tile t+3, form the logits of tile t+1 while the statistics of tile t are updated.
+    // Stage (t+3)&3 held tile t-1, last read in iteration t-2.  One barrier per tile.
     f32x4_t sa[4], sb[4];
-    load_k(0);
-    store_k(0);
-    if (ntiles > 1) { load_k(1); store_k(1); }
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+      if (t < ntiles) issue_tile(Ku, Kcu, t, sK + t * Lds::TILE_ELEMS, kswz);
+    wait_vmcnt<0>();
     __syncthreads();
     qk(sa, 0);
-    __syncthreads();                    // stage 0 is overwritten below
     auto step = [&](f32x4_t (&cur)[4], f32x4_t (&nxt)[4], int t) {
-      if (t + 2 < ntiles) load_k(t + 2);
-      if (t + 1 < ntiles) qk(nxt, (t + 1) & 1);
+      const bool more = t + 3 < ntiles;
+      if (more) issue_tile(Ku, Kcu, t + 3, sK + ((t + 3) & 3) * Lds::TILE_ELEMS, kswz);
+      if (t + 1 < ntiles) qk(nxt, (t + 1) & 3);
       stats(cur, t);
-      if (t + 2 < ntiles) store_k(t & 1);        // tile t's stage: last read one barrier ago
+      // tile t+2 must have landed before the next iteration reads it; only this iteration's requests may stay out
+      if (more) wait_vmcnt<CPW>(); else wait_vmcnt<0>();
       __syncthreads();
     };
     for (int t = 0; t < ntiles; t += 2) {
@@ -321,88 +342,15 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     qa1[ks] = rg ? a3 : a1;
   }
 
-  // ---- staging: global -> registers -> LDS (named registers: arrays here end up in scratch memory) ----
-  uint4 g0, g1, g2, g3, g4, g5, g6, g7;
-  g0 = g1 = g2 = g3 = g4 = g5 = g6 = g7 = make_uint4(0, 0, 0, 0);
-  const bool v_role = tid < 256;
-  const int st = tid & 255;
-  // V role: blocks of columns (v_jg + x*VJG_PER_X)*4..+3, dims v_part*8..+7.  K role: pieces st + x*256.
-  const int v_part = st % PARTS, v_jg = st / PARTS;
-  const int k_r0 = st / PARTS, k_part = st % PARTS;
-  const uint16_t* cache_base = (v_role ? Vu : Ku) + (v_role ? v_part : k_part) * 8;
-  const uint16_t* chunk_base = (v_role ? Vcu : Kcu) + (v_role ? v_part : k_part) * 8;
-  auto load_regs = [&](int tile) {
-    const bool is_cache = tile < cache_tiles;
-    const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
-    const uint16_t* base = is_cache ? cache_base : chunk_base;
-    const int rstride = is_cache ? D : chunk_row_stride;
-    const int lim = is_cache ? cache_lim : chunk_lim;
-    auto ld = [&](int r) { return *reinterpret_cast<const uint4*>(base + (size_t)min(col0 + r, lim) * rstride); };
-    if (v_role) {
-      const int r = v_jg * 4;
-      g0 = ld(r); g1 = ld(r + 1); g2 = ld(r + 2); g3 = ld(r + 3);
-      if constexpr (VBL > 1) {
-        const int r2 = r + VJG_PER_X * 4;
-        g4 = ld(r2); g5 = ld(r2 + 1); g6 = ld(r2 + 2); g7 = ld(r2 + 3);
-      }
-    } else {
-      g0 = ld(k_r0); g1 = ld(k_r0 + KROWS_PER_X); g2 = ld(k_r0 + 2 * KROWS_PER_X); g3 = ld(k_r0 + 3 * KROWS_PER_X);
-      if constexpr (KCH > 4) {
-        g4 = ld(k_r0 + 4 * KROWS_PER_X); g5 = ld(k_r0 + 5 * KROWS_PER_X);
-        g6 = ld(k_r0 + 6 * KROWS_PER_X); g7 = ld(k_r0 + 7 * KROWS_PER_X);
-      }
-    }
-  };
-  // LDS destinations do not depend on the tile: byte offsets inside one stage
-  const int k_dst = (k_r0 * Lds::KSTRIDE + k_part * 8) * 2;
-  auto v_dst_of = [&](int jg) {        // column group jg (4 columns) of the tile, this thread's 8 dims
-    const int c = jg / 8, jq = jg % 8;                                  // quarter, group inside the quarter
-    const int pair = (c * 4 + (jq % 4)) ^ ((v_part >> 1) & 7);          // (d/16)%8 == v_part/2 for all 8 dims
-    return ((v_part * 8) * Lds::VSTRIDE + pair * 8 + (jq / 4) * 4) * 2;
-  };
-  const int v_dst0 = v_dst_of(v_jg), v_dst1 = v_dst_of(v_jg + VJG_PER_X);
-  auto store_lds = [&](int buf) {
-    if (!v_role) {
-      char* k = reinterpret_cast<char*>(sK + buf * Lds::K_ELEMS) + k_dst;
-      constexpr int step = KROWS_PER_X * Lds::KSTRIDE * 2;
-      *reinterpret_cast<uint4*>(k) = g0;
-      *reinterpret_cast<uint4*>(k + step) = g1;
-      *reinterpret_cast<uint4*>(k + 2 * step) = g2;
-      *reinterpret_cast<uint4*>(k + 3 * step) = g3;
-      if constexpr (KCH > 4) {
-        *reinterpret_cast<uint4*>(k + 4 * step) = g4;
-        *reinterpret_cast<uint4*>(k + 5 * step) = g5;
-        *reinterpret_cast<uint4*>(k + 6 * step) = g6;
-        *reinterpret_cast<uint4*>(k + 7 * step) = g7;
-      }
-    } else {
-      char* vb = reinterpret_cast<char*>(sVt + buf * Lds::V_ELEMS);
-      // dword w of the four rows holds dims 2w, 2w+1 of columns +0..+3: regroup into one 8-byte word per dim
-      auto emit = [&](char* v, unsigned a0, unsigned a1, unsigned a2, unsigned a3, int e_even) {
-#pragma unroll
-        for (int odd = 0; odd < 2; ++odd) {
-          const unsigned sel = odd ? 0x07060302u : 0x05040100u;       // the odd / even bf16 of both dwords
-          uint2 o;
-          o.x = __builtin_amdgcn_perm(a1, a0, sel);                   // columns +0, +1
-          o.y = __builtin_amdgcn_perm(a3, a2, sel);                   // columns +2, +3
-          *reinterpret_cast<uint2*>(v + (e_even + odd) * Lds::VSTRIDE * 2) = o;
-        }
-      };
-      char* v0 = vb + v_dst0;
-      emit(v0, g0.x, g1.x, g2.x, g3.x, 0); emit(v0, g0.y, g1.y, g2.y, g3.y, 2);
-      emit(v0, g0.z, g1.z, g2.z, g3.z, 4); emit(v0, g0.w, g1.w, g2.w, g3.w, 6);
-      if constexpr (VBL > 1) {
-        char* v1 = vb + v_dst1;
-        emit(v1, g4.x, g5.x, g6.x, g7.x, 0); emit(v1, g4.y, g5.y, g6.y, g7.y, 2);
-        emit(v1, g4.z, g5.z, g6.z, g7.z, 4); emit(v1, g4.w, g5.w, g6.w, g7.w, 6);
-      }
-    }
-  };
-
-  // operand read offsets (bytes inside one stage), tile independent
-  const int ka_off = ((cq * 32 + lr) * Lds::KSTRIDE + q4 * 8) * 2;                     // + bk*16 rows, + ks*64 bytes
-  const int va_row = (lr * Lds::VSTRIDE) * 2;
-  const int va_pair = cq * 4 + q4;                                                     // swizzled with d & 7 per read
+  // operand read offsets inside one stage (bf16 elements), tile independent
+  // K: row cq*32 + bk*16 + lr, piece ks*4 + q4
+  const int k2_off = (cq * 32 + lr) * D;                                 // + bk*16 rows
+  const int k2_swz0 = kswz(cq * 32 + lr), k2_swz1 = kswz(cq * 32 + 16 + lr);
+  // V: the lane hands the transposing read the address of 4 dims of one row: row cq*32 + hh*16 + q4*4 + lr/4,
+  // dims db*16 + (lr%4)*4 .. +3, i.e. half (lr%4)%2 of piece db*2 + (lr%4)/2
+  const int v_row0 = cq * 32 + q4 * 4 + (lr >> 2), v_row1 = v_row0 + 16;
+  const int v_off0 = v_row0 * D + (lr & 1) * 4, v_off1 = v_row1 * D + (lr & 1) * 4;
+  const int v_swz0 = vswz(v_row0) ^ ((lr >> 1) & 1), v_swz1 = vswz(v_row1) ^ ((lr >> 1) & 1);   // piece db*2 ^ this
 
   f32x4_t o0[DB], o1[DB];
 #pragma unroll
@@ -414,6 +362,29 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const int n_parts = 2 * ((p.max_chunk + ROW_TILE - 1) / ROW_TILE);
   float* cs_part = p.pf_colpart + (((size_t)unit * p.G + g) * n_parts + row_tile * 2 + rg) * cs_stride + cq * 32 + q4 * 4;
 
+  // S^T blocks of a staged K tile: rows = columns cq*32 + bk*16 + q4*4 + i, column = the lane's query row of block 0 / 1
+  auto qk2 = [&](f32x4_t (&s0)[2], f32x4_t (&s1)[2], int stage) {
+    const uint16_t* kp = sK + stage * Lds::TILE_ELEMS + k2_off;
+    uint4 ka[2][KS];
+#pragma unroll
+    for (int bk = 0; bk < 2; ++bk)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        ka[bk][ks] = *reinterpret_cast<const uint4*>(kp + bk * 16 * D + ((ks * 4 + q4) ^ (bk ? k2_swz1 : k2_swz0)) * 8);
+#pragma unroll
+    for (int bk = 0; bk < 2; ++bk) { s0[bk] = f32x4_t{0.f, 0.f, 0.f, 0.f}; s1[bk] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int bk = 0; bk < 2; ++bk) {
+        s0[bk] = mfma16(ka[bk][ks], qa0[ks], s0[bk]);
+        s1[bk] = mfma16(ka[bk][ks], qa1[ks], s1[bk]);
+      }
+  };
+  // bf16 pairs (-1, 0) and (0, -1).  Kept opaque in scalar registers: as immediates, the second has the bit
+  // pattern of the fp32 inline constant -1.0, which a packed 16-bit operand does not read as these two halves.
+  unsigned minus_one_lo = 0x0000BF80u, minus_one_hi = 0xBF800000u;
+  asm volatile("" : "+s"(minus_one_lo), "+s"(minus_one_hi));
   // probabilities of one row block's 8 logits: the packed hi / lo P^T operands; the values themselves in place of s
   auto soft = [&](f32x4_t (&s)[2], float neg_ml, uint4& phi, uint4& plo) {
     unsigned hi[4], lo[4];                    // k-slots 0-3 = block 0, i = 0..3; k-slots 4-7 = block 1
@@ -424,35 +395,19 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       s[e2 >> 1][(e2 & 1) * 2] = p0;
       s[e2 >> 1][(e2 & 1) * 2 + 1] = p1;
       hi[e2] = pack_bf16(p0, p1);
-      lo[e2] = pack_bf16(p0 - __uint_as_float(hi[e2] << 16), p1 - __uint_as_float(hi[e2] & 0xffff0000u));
+      // p - hi in one instruction each: a bf16 dot product against (-1, 0) / (0, -1) added to p
+      const bf16x2_t hv = __builtin_bit_cast(bf16x2_t, hi[e2]);
+      const float l0 = __builtin_amdgcn_fdot2_f32_bf16(hv, __builtin_bit_cast(bf16x2_t, minus_one_lo), p0, false);
+      const float l1 = __builtin_amdgcn_fdot2_f32_bf16(hv, __builtin_bit_cast(bf16x2_t, minus_one_hi), p1, false);
+      lo[e2] = pack_bf16(l0, l1);
     }
     phi = make_uint4(hi[0], hi[1], hi[2], hi[3]);
     plo = make_uint4(lo[0], lo[1], lo[2], lo[3]);
   };
-
-  load_regs(0);
-  store_lds(0);
-  __syncthreads();
-  for (int tile = 0; tile < ntiles; ++tile) {
-    if (tile + 1 < ntiles) load_regs(tile + 1);            // in flight while this tile is computed
+  // everything that follows the logits of tile t: mask, probabilities, O^T += V^T P^T, column sums
+  auto finish_tile = [&](f32x4_t (&s0)[2], f32x4_t (&s1)[2], int tile) {
     const bool is_cache = tile < cache_tiles;
     const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
-    const char* k = reinterpret_cast<const char*>(sK + (tile & 1) * Lds::K_ELEMS) + ka_off;
-    const char* v = reinterpret_cast<const char*>(sVt + (tile & 1) * Lds::V_ELEMS);
-
-    // S^T blocks: rows = columns col0 + cq*32 + bk*16 + q4*4 + i, column = the lane's query row of block 0 / 1
-    f32x4_t s0[2], s1[2];
-#pragma unroll
-    for (int bk = 0; bk < 2; ++bk) {
-      s0[bk] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-      s1[bk] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const uint4 a = *reinterpret_cast<const uint4*>(k + bk * 16 * Lds::KSTRIDE * 2 + ks * 64);
-        s0[bk] = mfma16(a, qa0[ks], s0[bk]);
-        s1[bk] = mfma16(a, qa1[ks], s1[bk]);
-      }
-    }
     // only tiles that touch the end of the cache, the free slot or the causal diagonal need a mask (wave uniform)
     const bool need_mask = is_cache ? (col0 + AT_COLS - 1 > n_cached || (fslot >= col0 && fslot < col0 + AT_COLS))
                                     : (col0 + AT_COLS - 1 > row0);
@@ -473,29 +428,54 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     soft(s0, neg_ml0, phi0, plo0);
     soft(s1, neg_ml1, phi1, plo1);
     // O^T += V^T P^T : A = V^T[d][the quarter's 8 k-slot columns of this lane group], B = P^T (hi and lo parts)
+    const uint16_t* vp = sV + (tile & 1) * Lds::TILE_ELEMS;
 #pragma unroll
     for (int d = 0; d < DB; ++d) {
-      const uint4 a = *reinterpret_cast<const uint4*>(v + va_row + ((va_pair ^ (d & 7)) * 16) + d * 16 * Lds::VSTRIDE * 2);
+      const short4_t t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(vp + v_off0 + ((d * 2) ^ v_swz0) * 8));
+      const short4_t t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(vp + v_off1 + ((d * 2) ^ v_swz1) * 8));
+      const uint2 a0 = __builtin_bit_cast(uint2, t0), a1 = __builtin_bit_cast(uint2, t1);
+      const uint4 a = make_uint4(a0.x, a0.y, a1.x, a1.y);
       o0[d] = mfma16(a, phi0, o0[d]);
       o1[d] = mfma16(a, phi1, o1[d]);
       o0[d] = mfma16(a, plo0, o0[d]);
       o1[d] = mfma16(a, plo1, o1[d]);
     }
     // column sums over this wave's 32 rows
-    {
-      float* dst = cs_part + (is_cache ? col0 : cap_cols + col0);
+    float* dst = cs_part + (is_cache ? col0 : cap_cols + col0);
 #pragma unroll
-      for (int bk = 0; bk < 2; ++bk) {
-        float4 c;
-        c.x = row16_sum(s0[bk][0] + s1[bk][0]);
-        c.y = row16_sum(s0[bk][1] + s1[bk][1]);
-        c.z = row16_sum(s0[bk][2] + s1[bk][2]);
-        c.w = row16_sum(s0[bk][3] + s1[bk][3]);
-        if (lr == 0) *reinterpret_cast<float4*>(dst + bk * 16) = c;
-      }
+    for (int bk = 0; bk < 2; ++bk) {
+      float4 c;
+      c.x = row16_sum(s0[bk][0] + s1[bk][0]);
+      c.y = row16_sum(s0[bk][1] + s1[bk][1]);
+      c.z = row16_sum(s0[bk][2] + s1[bk][2]);
+      c.w = row16_sum(s0[bk][3] + s1[bk][3]);
+      if (lr == 0) *reinterpret_cast<float4*>(dst + bk * 16) = c;
     }
-    if (tile + 1 < ntiles) store_lds((tile + 1) & 1);      // the other stage: last read one barrier ago
+  };
+
+  // Iteration t: request K of tile t+2 and V of tile t+1, form the logits of tile t+1, finish tile t.
+  // K stage t&1 held tile t, whose logits were formed in iteration t-1; V stage (t+1)&1 held tile t-1.
+  issue_tile(Ku, Kcu, 0, sK, kswz);
+  issue_tile(Vu, Vcu, 0, sV, vswz);
+  if (ntiles > 1) issue_tile(Ku, Kcu, 1, sK + Lds::TILE_ELEMS, kswz);
+  wait_vmcnt<0>();
+  __syncthreads();
+  f32x4_t sa0[2], sa1[2], sb0[2], sb1[2];
+  qk2(sa0, sa1, 0);
+  __syncthreads();                     // K stage 0 is requested again right below
+  auto step2 = [&](f32x4_t (&c0)[2], f32x4_t (&c1)[2], f32x4_t (&n0)[2], f32x4_t (&n1)[2], int t) {
+    if (t + 2 < ntiles) issue_tile(Ku, Kcu, t + 2, sK + (t & 1) * Lds::TILE_ELEMS, kswz);
+    if (t + 1 < ntiles) {
+      issue_tile(Vu, Vcu, t + 1, sV + ((t + 1) & 1) * Lds::TILE_ELEMS, vswz);
+      qk2(n0, n1, (t + 1) & 1);
+    }
+    finish_tile(c0, c1, t);
+    wait_vmcnt<0>();                   // this iteration's requests are the next one's operands
     __syncthreads();
+  };
+  for (int t = 0; t < ntiles; t += 2) {
+    step2(sa0, sa1, sb0, sb1, t);
+    if (t + 1 < ntiles) step2(sb0, sb1, sa0, sa1, t + 1);
   }
 
   // ---- add the four column quarters of every row group through LDS ----
