@@ -43,7 +43,7 @@ size_t carve(Params& p, char* base) {
   p.logits = (float*)take(U * p.G * cap * 4);
   p.partial = (float*)take(U * p.nsplit * p.G * (size_t)(p.D + 2) * 4);
   const size_t cs_cols = (cap + 127) / 128 * 128 + ((size_t)p.max_chunk + 127) / 128 * 128;
-  p.pf_colpart = (float*)take(U * p.G * (2 * (((size_t)p.max_chunk + 63) / 64)) * cs_cols * 4);
+  p.pf_colpart = (float*)take(U * p.G * (((size_t)p.max_chunk + 63) / 64) * cs_cols * 4);
   p.pf_snew = (float*)take(U * (size_t)p.max_chunk * 4);
   p.pf_flag = (int*)take(U * ext * 4);
   p.pf_list = (int*)take(U * ext * 4);

@@ -17,7 +17,7 @@
 //            parallel pass; sweeps run one after the other.  Then surviving chunk tokens are
 //            matched with freed slots (prefix sums), the order arrays are rewritten and the
 //            retained positions emitted.
-//   scatter  grid (L, U).  Copies the surviving chunk rows into their slots.
+//   scatter  grid (L/4, U), one wave per token.  Copies the surviving chunk rows into their slots.
 //
 // Token ids during the replay: a slot number (< cap) for a cached token, cap + i for chunk
 // token i that has no slot yet.
@@ -76,7 +76,8 @@ typedef __attribute__((address_space(3))) short4_t lds_short4_t;
 template <int D>
 struct AttendLds {
   static constexpr int TILE_ELEMS = AT_COLS * D;                 // bf16 elements of one staged tile
-  static constexpr size_t BYTES = 4 * (size_t)TILE_ELEMS * sizeof(uint16_t);
+  static constexpr int COLBUF_FLOATS = 2 * 2 * AT_COLS;          // column sums on their way out: [2 tiles][2 row groups][128]
+  static constexpr size_t BYTES = 4 * (size_t)TILE_ELEMS * sizeof(uint16_t) + COLBUF_FLOATS * sizeof(float);
 };
 
 template <int CTRL>
@@ -110,6 +111,11 @@ __device__ inline void async_copy16(const void* src, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :: "v"(src), "s"(lds_base) : "memory");   // M0 is reserved: the compiler keeps nothing in it across statements
 }
+// The same with the source given as a wave-uniform base and a per-lane byte offset.
+__device__ inline void async_copy16_offset(const void* uniform_base, unsigned lane_offset, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(lane_offset), "s"(uniform_base), "s"(lds_base) : "memory");
+}
 __device__ inline unsigned lds_address(const void* shared_ptr) {
   return (unsigned)(uintptr_t)(lds_void_t*)shared_ptr;
 }
@@ -141,9 +147,11 @@ __device__ inline unsigned lds_address(const void* shared_ptr) {
 // LDS at the end.
 //
 // Column sums: a wave adds its two row blocks, reduces over the 16 lanes that hold the 16 rows and
-// writes the 32 sums of its columns to part row_tile*2 + row_group of the head's partial array;
-// the replay kernel adds the parts in a fixed order.  A workgroup writes every column of every tile it
-// visits (masked entries as zeros) and nothing else.
+// leaves the 32 sums of its columns in LDS.  During the next tile two of the waves add the two row groups
+// and write the tile's 128 sums to the head's partial array, one part per row tile (the stores then have a
+// whole iteration to complete before anything waits on the memory counter); the replay kernel adds the parts
+// in a fixed order.  A workgroup writes every column of every tile it visits (masked entries as zeros) and
+// nothing else.
 template <int D>
 __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, const uint16_t* __restrict__ Q,
                                                                     const uint16_t* __restrict__ Kc,
@@ -160,6 +168,7 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   extern __shared__ __attribute__((aligned(1024))) uint16_t pf_smem[];
   uint16_t* sK = pf_smem;                               // sweep 2: [2][TILE_ELEMS]; sweep 1: all four stages
   uint16_t* sV = pf_smem + 2 * Lds::TILE_ELEMS;         // [2][TILE_ELEMS]
+  float* sC = reinterpret_cast<float*>(pf_smem + 4 * Lds::TILE_ELEMS);   // [2][2][128]
 
   // swizzles of the 16-byte slots of tile row r
   auto kswz = [](int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); };
@@ -206,6 +215,9 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const int cache_lim = p.cap - 1, chunk_lim = L - 1;                   // last row that exists
 
   // ---- asynchronous tile loads: this wave's CPW instructions of 1 KB each ----
+  // Instruction x of wave w fills LDS block c = w*CPW + x, i.e. tile rows c*RPC + a_lrow.  w*CPW*RPC is a
+  // multiple of 16 rows, so the swizzle of a lane's row depends on x and a_lrow only.
+  static_assert(CPW * RPC == 16, "a wave covers 16 rows of every tile");
   const int a_lrow = lane / PARTS, a_slot = lane % PARTS;
   auto issue_tile = [&](const uint16_t* cache_src, const uint16_t* chunk_src, int tile, uint16_t* stage, auto swz) {
     const bool is_cache = tile < cache_tiles;
@@ -213,12 +225,24 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     const uint16_t* base = is_cache ? cache_src : chunk_src;
     const int rstride = is_cache ? D : chunk_row_stride;
     const int lim = is_cache ? cache_lim : chunk_lim;
+    const int row_w = col0 + wave * 16;                   // first source row of this wave's 16 (wave uniform)
+    if (row_w + 15 <= lim) {
+      // every row exists: a scalar base per instruction plus a per-lane byte offset
+      const unsigned lane_row = (unsigned)(a_lrow * rstride) * 2;
 #pragma unroll
-    for (int x = 0; x < CPW; ++x) {
-      const int c = wave * CPW + x;                       // 1 KB block of the stage (wave uniform)
-      const int r = c * RPC + a_lrow;                     // tile row this lane fetches from
-      const uint16_t* src = base + (size_t)min(col0 + r, lim) * rstride + (a_slot ^ swz(r)) * 8;
-      async_copy16(src, __builtin_amdgcn_readfirstlane(lds_address(stage + c * 512)));
+      for (int x = 0; x < CPW; ++x) {
+        const unsigned voff = lane_row + ((a_slot ^ swz(x * RPC + a_lrow)) * 16);
+        const uint16_t* sbase = base + (size_t)(row_w + x * RPC) * rstride;
+        async_copy16_offset(sbase, voff, __builtin_amdgcn_readfirstlane(lds_address(stage + (wave * CPW + x) * 512)));
+      }
+    } else {
+      // rows past the last one repeat it (they are masked later; what they must not be is unreadable)
+#pragma unroll
+      for (int x = 0; x < CPW; ++x) {
+        const int r = x * RPC + a_lrow;
+        const uint16_t* src = base + (size_t)min(row_w + r, lim) * rstride + (a_slot ^ swz(r)) * 8;
+        async_copy16(src, __builtin_amdgcn_readfirstlane(lds_address(stage + (wave * CPW + x) * 512)));
+      }
     }
   };
 
@@ -359,8 +383,16 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   // the part of the head's column-sum array this wave writes: [cache columns rounded up to a tile | chunk columns]
   const int cap_cols = (p.cap + AT_COLS - 1) / AT_COLS * AT_COLS;
   const int cs_stride = cap_cols + (p.max_chunk + AT_COLS - 1) / AT_COLS * AT_COLS;
-  const int n_parts = 2 * ((p.max_chunk + ROW_TILE - 1) / ROW_TILE);
-  float* cs_part = p.pf_colpart + (((size_t)unit * p.G + g) * n_parts + row_tile * 2 + rg) * cs_stride + cq * 32 + q4 * 4;
+  const int n_parts = (p.max_chunk + ROW_TILE - 1) / ROW_TILE;
+  float* cs_part = p.pf_colpart + (((size_t)unit * p.G + g) * n_parts + row_tile) * cs_stride;
+  float* cs_lds = sC + rg * AT_COLS + cq * 32 + q4 * 4;                  // + (tile & 1) * 2 * AT_COLS, + bk * 16
+  // the waves of column quarter t & 3 pass tile t's sums on (during tile t+1): thread j of the pair owns column j
+  auto drain = [&](int tile) {
+    const bool is_cache = tile < cache_tiles;
+    const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
+    const float* src = sC + (tile & 1) * 2 * AT_COLS + (tid & 127);
+    cs_part[(is_cache ? col0 : cap_cols + col0) + (tid & 127)] = src[0] + src[AT_COLS];
+  };
 
   // S^T blocks of a staged K tile: rows = columns cq*32 + bk*16 + q4*4 + i, column = the lane's query row of block 0 / 1
   auto qk2 = [&](f32x4_t (&s0)[2], f32x4_t (&s1)[2], int stage) {
@@ -441,7 +473,7 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       o1[d] = mfma16(a, plo1, o1[d]);
     }
     // column sums over this wave's 32 rows
-    float* dst = cs_part + (is_cache ? col0 : cap_cols + col0);
+    float* dst = cs_lds + (tile & 1) * 2 * AT_COLS;
 #pragma unroll
     for (int bk = 0; bk < 2; ++bk) {
       float4 c;
@@ -464,6 +496,7 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   qk2(sa0, sa1, 0);
   __syncthreads();                     // K stage 0 is requested again right below
   auto step2 = [&](f32x4_t (&c0)[2], f32x4_t (&c1)[2], f32x4_t (&n0)[2], f32x4_t (&n1)[2], int t) {
+    if (t > 0 && cq == ((t - 1) & 3)) drain(t - 1);
     if (t + 2 < ntiles) issue_tile(Ku, Kcu, t + 2, sK + (t & 1) * Lds::TILE_ELEMS, kswz);
     if (t + 1 < ntiles) {
       issue_tile(Vu, Vcu, t + 1, sV + ((t + 1) & 1) * Lds::TILE_ELEMS, vswz);
@@ -477,6 +510,7 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     step2(sa0, sa1, sb0, sb1, t);
     if (t + 1 < ntiles) step2(sb0, sb1, sa0, sa1, t + 1);
   }
+  if (cq == ((ntiles - 1) & 3)) drain(ntiles - 1);     // the last tile's sums (its barrier has passed)
 
   // ---- add the four column quarters of every row group through LDS ----
   float* xch = reinterpret_cast<float*>(pf_smem);           // [6 waves][2 blocks][DB*4][64 lanes]
@@ -580,17 +614,27 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
   {
     const int cap_cols = (p.cap + AT_COLS - 1) / AT_COLS * AT_COLS;
     const int cs_stride = cap_cols + (p.max_chunk + AT_COLS - 1) / AT_COLS * AT_COLS;
-    const int n_parts = 2 * ((p.max_chunk + ROW_TILE - 1) / ROW_TILE);
-    const int used = 2 * ((L + ROW_TILE - 1) / ROW_TILE);          // parts the attend kernel wrote
+    const int n_parts = (p.max_chunk + ROW_TILE - 1) / ROW_TILE;
+    const int used = (L + ROW_TILE - 1) / ROW_TILE;                // parts the attend kernel wrote: one per row tile
     const float* cp = p.pf_colpart + (size_t)unit * p.G * n_parts * cs_stride;
-    // four columns per thread and step, so that all the parts' loads are in flight together
-    for (int i4 = tid * 4; i4 < p.cap; i4 += RP_THREADS * 4) {
-      float4 add = make_float4(0.f, 0.f, 0.f, 0.f);
+    // Four columns per thread and step; the parts are fetched eight at a time (independent loads in
+    // flight together) and added in part order.
+    auto sum_parts = [&](const float* col, int first) {
+      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
       for (int g = 0; g < p.G; ++g)
-        for (int part = 0; part < used; ++part) {
-          const float4 x = *reinterpret_cast<const float4*>(cp + ((size_t)g * n_parts + part) * cs_stride + i4);
-          add.x += x.x; add.y += x.y; add.z += x.z; add.w += x.w;
+        for (int part = first; part < used; part += 8) {
+          float4 x[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            x[u] = *reinterpret_cast<const float4*>(col + ((size_t)g * n_parts + min(part + u, used - 1)) * cs_stride);
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (part + u < used) { acc.x += x[u].x; acc.y += x[u].y; acc.z += x[u].z; acc.w += x[u].w; }
         }
+      return acc;
+    };
+    for (int i4 = tid * 4; i4 < p.cap; i4 += RP_THREADS * 4) {
+      const float4 add = sum_parts(cp + i4, 0);
       const float a[4] = {add.x, add.y, add.z, add.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -607,12 +651,7 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
     }
     for (int i4 = tid * 4; i4 < L; i4 += RP_THREADS * 4) {
       // chunk columns of column tile i4 / 128 are visited by row tiles 2 * (i4 / 128) and up (causal)
-      float4 add = make_float4(0.f, 0.f, 0.f, 0.f);
-      for (int g = 0; g < p.G; ++g)
-        for (int part = 4 * (i4 / AT_COLS); part < used; ++part) {
-          const float4 x = *reinterpret_cast<const float4*>(cp + ((size_t)g * n_parts + part) * cs_stride + cap_cols + i4);
-          add.x += x.x; add.y += x.y; add.z += x.z; add.w += x.w;
-        }
+      const float4 add = sum_parts(cp + cap_cols + i4, 2 * (i4 / AT_COLS));
       const float a[4] = {add.x, add.y, add.z, add.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e)
@@ -785,15 +824,16 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
 // ---------------------------------------------------------------------------------------------
 // scatter: chunk rows that survived go to their slots
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void prefill_scatter_kernel(Params p, const uint4* __restrict__ Kc,
-                                                             const uint4* __restrict__ Vc, int L, int row_vec) {
-  const int i = blockIdx.x, unit = blockIdx.y;
+__global__ __launch_bounds__(256) void prefill_scatter_kernel(Params p, const uint4* __restrict__ Kc,
+                                                              const uint4* __restrict__ Vc, int L, int row_vec) {
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), unit = blockIdx.y;     // one wave per token
+  if (i >= L) return;
   const int kvh = unit % p.Hkv, b = unit / p.Hkv;
   const int slot = p.pf_flag[(size_t)unit * (p.cap + p.max_chunk) + p.cap + i];
   if (slot < 0) return;
   const size_t src = (((size_t)b * L + i) * p.Hkv + kvh) * row_vec;
   const size_t dst = ((size_t)unit * p.cap + slot) * row_vec;
-  for (int e = threadIdx.x; e < row_vec; e += 64) {
+  for (int e = threadIdx.x & 63; e < row_vec; e += 64) {
     reinterpret_cast<uint4*>(p.K)[dst + e] = Kc[src + e];
     reinterpret_cast<uint4*>(p.V)[dst + e] = Vc[src + e];
   }
@@ -824,7 +864,7 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
     hipLaunchKernelGGL(prefill_replay_kernel<false>, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, retained, n_retained,
                        evicted);
   }
-  hipLaunchKernelGGL(prefill_scatter_kernel, dim3(L, p.U), dim3(64), 0, s, p, (const uint4*)K, (const uint4*)V, L,
+  hipLaunchKernelGGL(prefill_scatter_kernel, dim3((L + 3) / 4, p.U), dim3(256), 0, s, p, (const uint4*)K, (const uint4*)V, L,
                      D * 2 / 16);
   return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
 }
