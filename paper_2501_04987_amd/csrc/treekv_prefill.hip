@@ -97,6 +97,8 @@ __device__ inline float row16_sum(float v) {
 // an MFMA costs an extra instruction that quiets signalling NaNs, and the pair is not fused into v_max3_f32.
 __device__ inline float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
+template <bool B> struct BoolTag { static constexpr bool value = B; };
+
 // s_waitcnt vmcnt(N) alone (the other counters at their maxima, i.e. not waited for), N < 16
 template <int N>
 __device__ inline void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | N); }
@@ -115,6 +117,12 @@ __device__ inline void async_copy16(const void* src, unsigned lds_base) {
 __device__ inline void async_copy16_offset(const void* uniform_base, unsigned lane_offset, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :: "v"(lane_offset), "s"(uniform_base), "s"(lds_base) : "memory");
+}
+// A further copy right behind async_copy16_offset, with the same M0: the instruction offset (bytes) is added to
+// the global and to the LDS address alike, which suits a source that is contiguous like its LDS image.
+template <int OFFSET>
+__device__ inline void async_copy16_next(const void* uniform_base, unsigned lane_offset) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" :: "v"(lane_offset), "s"(uniform_base), "n"(OFFSET) : "memory");
 }
 __device__ inline unsigned lds_address(const void* shared_ptr) {
   return (unsigned)(uintptr_t)(lds_void_t*)shared_ptr;
@@ -219,18 +227,38 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   // multiple of 16 rows, so the swizzle of a lane's row depends on x and a_lrow only.
   static_assert(CPW * RPC == 16, "a wave covers 16 rows of every tile");
   const int a_lrow = lane / PARTS, a_slot = lane % PARTS;
-  auto issue_tile = [&](const uint16_t* cache_src, const uint16_t* chunk_src, int tile, uint16_t* stage, auto swz) {
+  // q0, q1: the quarters [q0, q1) of the wave's instructions for this tile (all of them: 0, 4).
+  auto issue_tile = [&](const uint16_t* cache_src, const uint16_t* chunk_src, int tile, uint16_t* stage, auto swz,
+                        int q0, int q1) {
+    const int x0 = q0 * CPW / 4, x1 = q1 * CPW / 4;
     const bool is_cache = tile < cache_tiles;
     const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
     const uint16_t* base = is_cache ? cache_src : chunk_src;
     const int rstride = is_cache ? D : chunk_row_stride;
     const int lim = is_cache ? cache_lim : chunk_lim;
     const int row_w = col0 + wave * 16;                   // first source row of this wave's 16 (wave uniform)
-    if (row_w + 15 <= lim) {
+    if (row_w + 15 <= lim && is_cache) {
+      // Cache rows are contiguous, like their LDS image: one scalar base and one M0 for the run of requests, the
+      // instruction offset stepping both sides by 1 KB; the per-lane offset differs only in the swizzled piece.
+      const unsigned lane_row = (unsigned)(a_lrow * D) * 2;
+      const uint16_t* sbase = base + (size_t)(row_w + x0 * RPC) * D;
+      const unsigned m0 = __builtin_amdgcn_readfirstlane(lds_address(stage + (wave * CPW + x0) * 512));
+#pragma unroll
+      for (int x = 0; x < CPW; ++x) {
+        if (x < x0 || x >= x1) continue;
+        const unsigned voff = lane_row + ((a_slot ^ swz(x * RPC + a_lrow)) * 16);
+        const int k = x - x0;
+        if (k == 0) async_copy16_offset(sbase, voff, m0);
+        else if (k == 1) async_copy16_next<1024>(sbase, voff);
+        else if (k == 2) async_copy16_next<2048>(sbase, voff);
+        else async_copy16_next<3072>(sbase, voff);
+      }
+    } else if (row_w + 15 <= lim) {
       // every row exists: a scalar base per instruction plus a per-lane byte offset
       const unsigned lane_row = (unsigned)(a_lrow * rstride) * 2;
 #pragma unroll
       for (int x = 0; x < CPW; ++x) {
+        if (x < x0 || x >= x1) continue;
         const unsigned voff = lane_row + ((a_slot ^ swz(x * RPC + a_lrow)) * 16);
         const uint16_t* sbase = base + (size_t)(row_w + x * RPC) * rstride;
         async_copy16_offset(sbase, voff, __builtin_amdgcn_readfirstlane(lds_address(stage + (wave * CPW + x) * 512)));
@@ -239,6 +267,7 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       // rows past the last one repeat it (they are masked later; what they must not be is unreadable)
 #pragma unroll
       for (int x = 0; x < CPW; ++x) {
+        if (x < x0 || x >= x1) continue;
         const int r = x * RPC + a_lrow;
         const uint16_t* src = base + (size_t)min(row_w + r, lim) * rstride + (a_slot ^ swz(r)) * 8;
         async_copy16(src, __builtin_amdgcn_readfirstlane(lds_address(stage + (wave * CPW + x) * 512)));
@@ -289,14 +318,29 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
           }
         }
       }
+      // The reference m_run of a lane's sums only has to keep exp2 in range, so it is raised lazily: when some
+      // lane of the wave meets a logit more than 16 (log2 units) above its reference.  After the first tiles that
+      // is rare, and the common path has no rescaling and one exp2 per logit.
+      float tmax[4];
+      bool grow = false;
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb) {
-        // The running max lives in the scaled domain: exp2(m_run - m_new) is then exactly 1 when the max stays.
-        const float m_new = fmaxf(m_run[rb], max3(s[rb][0], s[rb][1], fmaxf(s[rb][2], s[rb][3])) * sc);
-        const float e0 = fast_exp2(fmaf(s[rb][0], sc, -m_new)), e1 = fast_exp2(fmaf(s[rb][1], sc, -m_new));
-        const float e2 = fast_exp2(fmaf(s[rb][2], sc, -m_new)), e3 = fast_exp2(fmaf(s[rb][3], sc, -m_new));
-        l_run[rb] = fmaf(l_run[rb], fast_exp2(m_run[rb] - m_new), (e0 + e1) + (e2 + e3));
-        m_run[rb] = m_new;
+        tmax[rb] = max3(s[rb][0], s[rb][1], fmaxf(s[rb][2], s[rb][3])) * sc;
+        grow |= tmax[rb] - 16.0f > m_run[rb];
+      }
+      if (__any(grow)) {
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+          const float m_new = fmaxf(m_run[rb], tmax[rb]);     // scaled domain: exp2(0) is exactly 1 where nothing changes
+          l_run[rb] *= fast_exp2(m_run[rb] - m_new);
+          m_run[rb] = m_new;
+        }
+      }
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        const float e0 = fast_exp2(fmaf(s[rb][0], sc, -m_run[rb])), e1 = fast_exp2(fmaf(s[rb][1], sc, -m_run[rb]));
+        const float e2 = fast_exp2(fmaf(s[rb][2], sc, -m_run[rb])), e3 = fast_exp2(fmaf(s[rb][3], sc, -m_run[rb]));
+        l_run[rb] += (e0 + e1) + (e2 + e3);
       }
     };
     // Iteration t: request tile t+3, form the logits of tile t+1 while the statistics of tile t are updated.
@@ -304,13 +348,13 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     f32x4_t sa[4], sb[4];
 #pragma unroll
     for (int t = 0; t < 3; ++t)
-      if (t < ntiles) issue_tile(Ku, Kcu, t, sK + t * Lds::TILE_ELEMS, kswz);
+      if (t < ntiles) issue_tile(Ku, Kcu, t, sK + t * Lds::TILE_ELEMS, kswz, 0, 4);
     wait_vmcnt<0>();
     __syncthreads();
     qk(sa, 0);
     auto step = [&](f32x4_t (&cur)[4], f32x4_t (&nxt)[4], int t) {
       const bool more = t + 3 < ntiles;
-      if (more) issue_tile(Ku, Kcu, t + 3, sK + ((t + 3) & 3) * Lds::TILE_ELEMS, kswz);
+      if (more) issue_tile(Ku, Kcu, t + 3, sK + ((t + 3) & 3) * Lds::TILE_ELEMS, kswz, 0, 4);
       if (t + 1 < ntiles) qk(nxt, (t + 1) & 3);
       stats(cur, t);
       // tile t+2 must have landed before the next iteration reads it; only this iteration's requests may stay out
@@ -436,8 +480,8 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     phi = make_uint4(hi[0], hi[1], hi[2], hi[3]);
     plo = make_uint4(lo[0], lo[1], lo[2], lo[3]);
   };
-  // everything that follows the logits of tile t: mask, probabilities, O^T += V^T P^T, column sums
-  auto finish_tile = [&](f32x4_t (&s0)[2], f32x4_t (&s1)[2], int tile) {
+  // what follows the logits of tile t, in three pieces: mask + probabilities, O^T += V^T P^T, column sums
+  auto mask_tile = [&](f32x4_t (&s0)[2], f32x4_t (&s1)[2], int tile) {
     const bool is_cache = tile < cache_tiles;
     const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
     // only tiles that touch the end of the cache, the free slot or the causal diagonal need a mask (wave uniform)
@@ -456,10 +500,9 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
           s1[bk][i] = (col <= lim1 && col != excl) ? s1[bk][i] : -INFINITY;
         }
     }
-    uint4 phi0, plo0, phi1, plo1;
-    soft(s0, neg_ml0, phi0, plo0);
-    soft(s1, neg_ml1, phi1, plo1);
-    // O^T += V^T P^T : A = V^T[d][the quarter's 8 k-slot columns of this lane group], B = P^T (hi and lo parts)
+  };
+  // O^T += V^T P^T : A = V^T[d][the quarter's 8 k-slot columns of this lane group], B = P^T (hi and lo parts)
+  auto pv = [&](int tile, const uint4& phi0, const uint4& plo0, const uint4& phi1, const uint4& plo1) {
     const uint16_t* vp = sV + (tile & 1) * Lds::TILE_ELEMS;
 #pragma unroll
     for (int d = 0; d < DB; ++d) {
@@ -472,7 +515,9 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       o0[d] = mfma16(a, plo0, o0[d]);
       o1[d] = mfma16(a, plo1, o1[d]);
     }
-    // column sums over this wave's 32 rows
+  };
+  // column sums over this wave's 32 rows (s0 / s1 hold the probabilities by now)
+  auto colsums = [&](const f32x4_t (&s0)[2], const f32x4_t (&s1)[2], int tile) {
     float* dst = cs_lds + (tile & 1) * 2 * AT_COLS;
 #pragma unroll
     for (int bk = 0; bk < 2; ++bk) {
@@ -487,28 +532,57 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
 
   // Iteration t: request K of tile t+2 and V of tile t+1, form the logits of tile t+1, finish tile t.
   // K stage t&1 held tile t, whose logits were formed in iteration t-1; V stage (t+1)&1 held tile t-1.
-  issue_tile(Ku, Kcu, 0, sK, kswz);
-  issue_tile(Vu, Vcu, 0, sV, vswz);
-  if (ntiles > 1) issue_tile(Ku, Kcu, 1, sK + Lds::TILE_ELEMS, kswz);
+  issue_tile(Ku, Kcu, 0, sK, kswz, 0, 4);
+  issue_tile(Vu, Vcu, 0, sV, vswz, 0, 4);
+  if (ntiles > 1) issue_tile(Ku, Kcu, 1, sK + Lds::TILE_ELEMS, kswz, 0, 4);
   wait_vmcnt<0>();
   __syncthreads();
   f32x4_t sa0[2], sa1[2], sb0[2], sb1[2];
   qk2(sa0, sa1, 0);
   __syncthreads();                     // K stage 0 is requested again right below
-  auto step2 = [&](f32x4_t (&c0)[2], f32x4_t (&c1)[2], f32x4_t (&n0)[2], f32x4_t (&n1)[2], int t) {
+  auto step2 = [&](f32x4_t (&c0)[2], f32x4_t (&c1)[2], f32x4_t (&n0)[2], f32x4_t (&n1)[2], int t, auto matrix_first) {
     if (t > 0 && cq == ((t - 1) & 3)) drain(t - 1);
-    if (t + 2 < ntiles) issue_tile(Ku, Kcu, t + 2, sK + (t & 1) * Lds::TILE_ELEMS, kswz);
-    if (t + 1 < ntiles) {
-      issue_tile(Vu, Vcu, t + 1, sV + ((t + 1) & 1) * Lds::TILE_ELEMS, vswz);
-      qk2(n0, n1, (t + 1) & 1);
+    // Requests of this iteration: K of tile t+2 into K stage t&1, V of tile t+1 into V stage (t+1)&1.
+    const bool more_k = t + 2 < ntiles, more_v = t + 1 < ntiles;
+    uint16_t* k_stage = sK + (t & 1) * Lds::TILE_ELEMS;
+    uint16_t* v_stage = sV + ((t + 1) & 1) * Lds::TILE_ELEMS;
+    auto ask_k = [&](int q0, int q1) { if (more_k) issue_tile(Ku, Kcu, t + 2, k_stage, kswz, q0, q1); };
+    auto ask_v = [&](int q0, int q1) { if (more_v) issue_tile(Vu, Vcu, t + 1, v_stage, vswz, q0, q1); };
+    // The two waves that share a SIMD take the four pieces in different orders, so that one is on the matrix pipe
+    // while the other is on the vector ALU instead of both wanting the same unit at the same time:
+    //   waves 0-3: logits(t+1)  probabilities(t)  PV(t)  column sums(t)
+    //   waves 4-7: probabilities(t)  column sums(t)  logits(t+1)  PV(t)
+    uint4 phi0, plo0, phi1, plo1;
+    ask_k(0, 4);
+    ask_v(0, 4);
+    if constexpr (decltype(matrix_first)::value) {
+      if (t + 1 < ntiles) qk2(n0, n1, (t + 1) & 1);
+      mask_tile(c0, c1, t);
+      soft(c0, neg_ml0, phi0, plo0);
+      soft(c1, neg_ml1, phi1, plo1);
+      pv(t, phi0, plo0, phi1, plo1);
+      colsums(c0, c1, t);
+    } else {
+      mask_tile(c0, c1, t);
+      soft(c0, neg_ml0, phi0, plo0);
+      soft(c1, neg_ml1, phi1, plo1);
+      colsums(c0, c1, t);
+      if (t + 1 < ntiles) qk2(n0, n1, (t + 1) & 1);
+      pv(t, phi0, plo0, phi1, plo1);
     }
-    finish_tile(c0, c1, t);
     wait_vmcnt<0>();                   // this iteration's requests are the next one's operands
     __syncthreads();
   };
-  for (int t = 0; t < ntiles; t += 2) {
-    step2(sa0, sa1, sb0, sb1, t);
-    if (t + 1 < ntiles) step2(sb0, sb1, sa0, sa1, t + 1);
+  if (wave < 4) {                      // (the choice is made outside the loop: inside, the two bodies would share registers badly)
+    for (int t = 0; t < ntiles; t += 2) {
+      step2(sa0, sa1, sb0, sb1, t, BoolTag<true>{});
+      if (t + 1 < ntiles) step2(sb0, sb1, sa0, sa1, t + 1, BoolTag<true>{});
+    }
+  } else {
+    for (int t = 0; t < ntiles; t += 2) {
+      step2(sa0, sa1, sb0, sb1, t, BoolTag<false>{});
+      if (t + 1 < ntiles) step2(sb0, sb1, sa0, sa1, t + 1, BoolTag<false>{});
+    }
   }
   if (cq == ((ntiles - 1) & 3)) drain(ntiles - 1);     // the last tile's sums (its barrier has passed)
 
