@@ -43,7 +43,7 @@ size_t carve(Params& p, char* base) {
   p.logits = (float*)take(U * p.G * cap * 4);
   p.partial = (float*)take(U * p.nsplit * p.G * (size_t)(p.D + 2) * 4);
   const size_t cs_cols = (cap + 127) / 128 * 128 + ((size_t)p.max_chunk + 127) / 128 * 128;
-  p.pf_colpart = (float*)take(U * p.G * (((size_t)p.max_chunk + 63) / 64) * cs_cols * 4);
+  p.pf_colacc = (unsigned long long*)take(U * cs_cols * 8);
   p.pf_snew = (float*)take(U * (size_t)p.max_chunk * 4);
   p.pf_flag = (int*)take(U * ext * 4);
   p.pf_list = (int*)take(U * ext * 4);
@@ -61,6 +61,8 @@ __global__ void reset_kernel(Params p) {
   for (int i = threadIdx.x; i < 2 * p.m; i += blockDim.x) Eu[i] = PEu[i] = i < p.m ? p.n_sink + i : 0;
   for (int i = threadIdx.x; i < p.n_recent; i += blockDim.x) Ru[i] = p.n_sink + p.m + i;
   for (int i = threadIdx.x; i < p.cap; i += blockDim.x) p.S[(size_t)unit * p.cap + i] = 0.f;
+  const size_t cs_cols = (size_t)(p.cap + 127) / 128 * 128 + (size_t)(p.max_chunk + 127) / 128 * 128;
+  for (size_t i = threadIdx.x; i < cs_cols; i += blockDim.x) p.pf_colacc[(size_t)unit * cs_cols + i] = 0;
   // Cache rows are always initialised memory: the decode kernel requests its first rows before it
   // knows how many are live, and multiplies what it did not need by zero.
   const size_t vecs = (size_t)p.cap * p.D * (p.dtype == TREEKV_BF16 ? 2 : 4) / 16;

@@ -48,7 +48,7 @@ struct Params {
   float* logits;            // [U][G][cap]   decode scratch: scaled logits (log2 domain)
   float* partial;           // [U][nsplit][G][D+2] decode scratch: split-KV partial (acc, max, sum)
   // prefill scratch
-  float* pf_colpart;        // [U][G][row tiles][cache columns | chunk columns, each rounded up to 128] column-sum parts
+  unsigned long long* pf_colacc;   // [U][cache columns | chunk columns, each rounded up to 128] column sums of the chunk in flight, fixed point
   float* pf_snew;           // [U][max_chunk] accumulated S of the chunk's tokens
   int* pf_flag;             // [U][cap + max_chunk] freed slots / dead chunk tokens, then destinations
   int* pf_list;             // [U][cap + max_chunk] free slots in ascending order

@@ -33,6 +33,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 constexpr int ROW_TILE = 64;     // query rows per attend workgroup
 constexpr float NEG_BIG = -1.0e30f;
+constexpr float COLSUM_FIX = 1099511627776.0f;      // 2^40: column sums cross kernels as 64-bit fixed point
 
 __device__ inline f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
@@ -427,15 +428,18 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   // the part of the head's column-sum array this wave writes: [cache columns rounded up to a tile | chunk columns]
   const int cap_cols = (p.cap + AT_COLS - 1) / AT_COLS * AT_COLS;
   const int cs_stride = cap_cols + (p.max_chunk + AT_COLS - 1) / AT_COLS * AT_COLS;
-  const int n_parts = (p.max_chunk + ROW_TILE - 1) / ROW_TILE;
-  float* cs_part = p.pf_colpart + (((size_t)unit * p.G + g) * n_parts + row_tile) * cs_stride;
+  unsigned long long* cs_acc = p.pf_colacc + (size_t)unit * cs_stride;
   float* cs_lds = sC + rg * AT_COLS + cq * 32 + q4 * 4;                  // + (tile & 1) * 2 * AT_COLS, + bk * 16
   // the waves of column quarter t & 3 pass tile t's sums on (during tile t+1): thread j of the pair owns column j
   auto drain = [&](int tile) {
     const bool is_cache = tile < cache_tiles;
     const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
     const float* src = sC + (tile & 1) * 2 * AT_COLS + (tid & 127);
-    cs_part[(is_cache ? col0 : cap_cols + col0) + (tid & 127)] = src[0] + src[AT_COLS];
+    // Integer adds commute exactly, so the row tiles (and query heads) of a unit can meet in one accumulator per
+    // column in any order and the result is still the same to the bit.  A tile's sum is below 64; 2^-40 resolves it
+    // far finer than fp32 does.
+    const long long fix = (long long)((src[0] + src[AT_COLS]) * COLSUM_FIX + 0.5f);
+    atomicAdd(cs_acc + (is_cache ? col0 : cap_cols + col0) + (tid & 127), (unsigned long long)fix);
   };
 
   // S^T blocks of a staged K tile: rows = columns cq*32 + bk*16 + q4*4 + i, column = the lane's query row of block 0 / 1
@@ -677,60 +681,60 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
     flag = w; w += p.cap + L;
     free_list = w; w += L + 2;
     Ru = w;
-    for (int i = tid; i < 2 * p.m; i += RP_THREADS) { Eu[i] = Eg[i]; PEu[i] = PEg[i]; }
-    for (int i = tid; i < p.n_recent; i += RP_THREADS) Ru[i] = Rg[i];
     snew_w = sn;
   }
 
+  // Everything the kernel reads from global memory is requested here in one go (what a unit's replay costs is
+  // memory round trips: its data was last touched a whole chunk ago): the bookkeeping words, the old scores and
+  // the chunk's column sums of the first PRE * 512 columns, and, for the LDS variant, the order arrays.
+  const int cap_cols = (p.cap + AT_COLS - 1) / AT_COLS * AT_COLS;
+  const int cs_stride = cap_cols + (p.max_chunk + AT_COLS - 1) / AT_COLS * AT_COLS;
+  unsigned long long* acc = p.pf_colacc + (size_t)unit * cs_stride;
+  constexpr int PRE = 8;
   const int n0 = meta[META_N], f0 = meta[META_FREE], j0 = meta[META_J], rhead0 = meta[META_RHEAD], t0 = meta[META_T];
+  float s_pre[PRE];
+  unsigned long long a_pre[PRE], n_pre[PRE];
+#pragma unroll
+  for (int u = 0; u < PRE; ++u) {
+    const int c = u * RP_THREADS + tid;
+    s_pre[u] = Sg[min(c, p.cap - 1)];
+    a_pre[u] = acc[min(c, p.cap - 1)];
+    n_pre[u] = acc[cap_cols + min(c, L - 1)];
+  }
+  if constexpr (IN_LDS) {
+    for (int i0 = 0; i0 < 2 * p.m; i0 += 4 * RP_THREADS) {
+      int e[4], pe[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { const int i = min(i0 + u * RP_THREADS + tid, 2 * p.m - 1); e[u] = Eg[i]; pe[u] = PEg[i]; }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { const int i = i0 + u * RP_THREADS + tid; if (i < 2 * p.m) { Eu[i] = e[u]; PEu[i] = pe[u]; } }
+    }
+    for (int i = tid; i < p.n_recent; i += RP_THREADS) Ru[i] = Rg[i];
+  }
 
-  // ---- Algorithm 1, line 8 for the whole chunk: add the attend kernel's column-sum parts, in a fixed order ----
+  // ---- Algorithm 1, line 8 for the whole chunk: add the column sums the attend kernel left in the accumulators ----
   {
-    const int cap_cols = (p.cap + AT_COLS - 1) / AT_COLS * AT_COLS;
-    const int cs_stride = cap_cols + (p.max_chunk + AT_COLS - 1) / AT_COLS * AT_COLS;
-    const int n_parts = (p.max_chunk + ROW_TILE - 1) / ROW_TILE;
-    const int used = (L + ROW_TILE - 1) / ROW_TILE;                // parts the attend kernel wrote: one per row tile
-    const float* cp = p.pf_colpart + (size_t)unit * p.G * n_parts * cs_stride;
-    // Four columns per thread and step; the parts are fetched eight at a time (independent loads in
-    // flight together) and added in part order.
-    auto sum_parts = [&](const float* col, int first) {
-      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-      for (int g = 0; g < p.G; ++g)
-        for (int part = first; part < used; part += 8) {
-          float4 x[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u)
-            x[u] = *reinterpret_cast<const float4*>(col + ((size_t)g * n_parts + min(part + u, used - 1)) * cs_stride);
-#pragma unroll
-          for (int u = 0; u < 8; ++u)
-            if (part + u < used) { acc.x += x[u].x; acc.y += x[u].y; acc.z += x[u].z; acc.w += x[u].w; }
-        }
-      return acc;
-    };
-    for (int i4 = tid * 4; i4 < p.cap; i4 += RP_THREADS * 4) {
-      const float4 add = sum_parts(cp + i4, 0);
-      const float a[4] = {add.x, add.y, add.z, add.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int i = i4 + e;
-        if (i < p.cap) {
-          float v = Sg[i];
-          if (i <= n0 && i != f0) {                                  // the columns every row tile visited
-            v += a[e];
-            Sg[i] = v;
-          }
-          if constexpr (IN_LDS) Su[i] = v;
-        }
+    // every accumulator that is read is also cleared for the next chunk (the others only ever received zeros)
+    auto cache_col = [&](int c, float v, unsigned long long a) {
+      if (c <= n0 && c != f0) {                                      // the columns every row tile visited
+        v += (float)(long long)a * (1.0f / COLSUM_FIX);
+        Sg[c] = v;
+        acc[c] = 0;
       }
-    }
-    for (int i4 = tid * 4; i4 < L; i4 += RP_THREADS * 4) {
-      // chunk columns of column tile i4 / 128 are visited by row tiles 2 * (i4 / 128) and up (causal)
-      const float4 add = sum_parts(cp + cap_cols + i4, 2 * (i4 / AT_COLS));
-      const float a[4] = {add.x, add.y, add.z, add.w};
+      if constexpr (IN_LDS) Su[c] = v;
+    };
+    auto chunk_col = [&](int c, unsigned long long a) {
+      snew_w[c] = (float)(long long)a * (1.0f / COLSUM_FIX);
+      acc[cap_cols + c] = 0;
+    };
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (i4 + e < L) snew_w[i4 + e] = a[e];
+    for (int u = 0; u < PRE; ++u) {
+      const int c = u * RP_THREADS + tid;
+      if (c < p.cap) cache_col(c, s_pre[u], a_pre[u]);
+      if (c < L) chunk_col(c, n_pre[u]);
     }
+    for (int c = PRE * RP_THREADS + tid; c < p.cap; c += RP_THREADS) cache_col(c, Sg[c], acc[c]);
+    for (int c = PRE * RP_THREADS + tid; c < L; c += RP_THREADS) chunk_col(c, acc[cap_cols + c]);
     __syncthreads();
   }
   const float* snew = snew_w;
