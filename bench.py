@@ -148,8 +148,8 @@ def bench_prefill(torch, binding, inputs, dev, chunks=24, warm=6, layers=4):
             "chunks": chunks, "us_per_chunk": us, "prompt_tokens_per_s": PREFILL_CHUNK / (us * 1e-6),
             "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "flops_per_chunk": flops,
-                         "note": "algorithmic flops (Q.K^T and P.V once each) over the whole chunk call: attend, "
-                                 "column sums, replay and scatter kernels"}}
+                         "note": "algorithmic flops (Q.K^T and P.V once each) over the whole chunk call: attend "
+                                 "(two passes, column sums included), replay and scatter kernels"}}
 
 
 def main():

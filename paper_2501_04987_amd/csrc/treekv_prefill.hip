@@ -10,9 +10,11 @@
 //            over all visible columns with MFMA (16x16x32 bf16): the first finds the row statistics, the
 //            second forms the final probabilities, O^T += V^T P^T with P split into two bf16 halves
 //            (hi + lo) so that rounding P costs 2^-16, not 2^-9, and the probabilities' sums down the
-//            workgroup's rows, one part per row group.  Writes O and the column-sum parts.
-//   replay   grid U.  Adds the column-sum parts to the scores (Algorithm 1, line 8; fixed order, no
-//            atomics), then Algorithm 1's eviction for the chunk's tokens with frozen scores.  Inside one
+//            workgroup's rows.  Writes O; the column sums go, as 64-bit fixed point, into one accumulator
+//            per column of the unit with integer atomic adds (which commute exactly: whatever order the
+//            workgroups arrive in, the sum is the same to the bit).
+//   replay   grid U.  Adds the accumulated column sums to the scores (Algorithm 1, line 8) and clears the
+//            accumulators, then Algorithm 1's eviction for the chunk's tokens with frozen scores.  Inside one
 //            sweep of idx over the tree region the scopes are disjoint pairs, so a sweep is one
 //            parallel pass; sweeps run one after the other.  Then surviving chunk tokens are
 //            matched with freed slots (prefix sums), the order arrays are rewritten and the
@@ -157,10 +159,9 @@ __device__ inline unsigned lds_address(const void* shared_ptr) {
 //
 // Column sums: a wave adds its two row blocks, reduces over the 16 lanes that hold the 16 rows and
 // leaves the 32 sums of its columns in LDS.  During the next tile two of the waves add the two row groups
-// and write the tile's 128 sums to the head's partial array, one part per row tile (the stores then have a
-// whole iteration to complete before anything waits on the memory counter); the replay kernel adds the parts
-// in a fixed order.  A workgroup writes every column of every tile it visits (masked entries as zeros) and
-// nothing else.
+// and add the tile's 128 sums to the unit's accumulators (the atomics then have a whole iteration to
+// complete before anything waits on the memory counter).  A workgroup touches every column of every tile
+// it visits (masked entries add zero) and nothing else.
 template <int D>
 __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, const uint16_t* __restrict__ Q,
                                                                     const uint16_t* __restrict__ Kc,
@@ -425,7 +426,7 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
 #pragma unroll
   for (int d = 0; d < DB; ++d) { o0[d] = f32x4_t{0.f, 0.f, 0.f, 0.f}; o1[d] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
 
-  // the part of the head's column-sum array this wave writes: [cache columns rounded up to a tile | chunk columns]
+  // the unit's column-sum accumulators: [cache columns rounded up to a tile | chunk columns]
   const int cap_cols = (p.cap + AT_COLS - 1) / AT_COLS * AT_COLS;
   const int cs_stride = cap_cols + (p.max_chunk + AT_COLS - 1) / AT_COLS * AT_COLS;
   unsigned long long* cs_acc = p.pf_colacc + (size_t)unit * cs_stride;
