@@ -19,7 +19,7 @@
 //            parallel pass; sweeps run one after the other.  Then surviving chunk tokens are
 //            matched with freed slots (prefix sums), the order arrays are rewritten and the
 //            retained positions emitted.
-//   scatter  grid (L/4, U), one wave per token.  Copies the surviving chunk rows into their slots.
+//   scatter  grid (L/16, U), 16 lanes per token.  Copies the surviving chunk rows into their slots.
 //
 // Token ids during the replay: a slot number (< cap) for a cached token, cap + i for chunk
 // token i that has no slot yet.
@@ -905,17 +905,17 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prefill_scatter_kernel(Params p, const uint4* __restrict__ Kc,
                                                               const uint4* __restrict__ Vc, int L, int row_vec) {
-  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), unit = blockIdx.y;     // one wave per token
+  // row_vec lanes (16-byte pieces of a row: 16 at d=128, 8 at d=64) per token, 256 / row_vec tokens per workgroup
+  const int per_wg = 256 / row_vec;
+  const int i = blockIdx.x * per_wg + threadIdx.x / row_vec, e = threadIdx.x % row_vec, unit = blockIdx.y;
   if (i >= L) return;
   const int kvh = unit % p.Hkv, b = unit / p.Hkv;
   const int slot = p.pf_flag[(size_t)unit * (p.cap + p.max_chunk) + p.cap + i];
   if (slot < 0) return;
-  const size_t src = (((size_t)b * L + i) * p.Hkv + kvh) * row_vec;
-  const size_t dst = ((size_t)unit * p.cap + slot) * row_vec;
-  for (int e = threadIdx.x & 63; e < row_vec; e += 64) {
-    reinterpret_cast<uint4*>(p.K)[dst + e] = Kc[src + e];
-    reinterpret_cast<uint4*>(p.V)[dst + e] = Vc[src + e];
-  }
+  const size_t src = (((size_t)b * L + i) * p.Hkv + kvh) * row_vec + e;
+  const size_t dst = ((size_t)unit * p.cap + slot) * row_vec + e;
+  reinterpret_cast<uint4*>(p.K)[dst] = Kc[src];
+  reinterpret_cast<uint4*>(p.V)[dst] = Vc[src];
 }
 
 template <int D>
@@ -943,7 +943,7 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
     hipLaunchKernelGGL(prefill_replay_kernel<false>, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, retained, n_retained,
                        evicted);
   }
-  hipLaunchKernelGGL(prefill_scatter_kernel, dim3((L + 3) / 4, p.U), dim3(256), 0, s, p, (const uint4*)K, (const uint4*)V, L,
+  hipLaunchKernelGGL(prefill_scatter_kernel, dim3((L + 256 / (D / 8) - 1) / (256 / (D / 8)), p.U), dim3(256), 0, s, p, (const uint4*)K, (const uint4*)V, L,
                      D * 2 / 16);
   return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
 }
