@@ -121,11 +121,23 @@ __device__ inline void async_copy16_offset(const void* uniform_base, unsigned la
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :: "v"(lane_offset), "s"(uniform_base), "s"(lds_base) : "memory");
 }
-// A further copy right behind async_copy16_offset, with the same M0: the instruction offset (bytes) is added to
-// the global and to the LDS address alike, which suits a source that is contiguous like its LDS image.
-template <int OFFSET>
-__device__ inline void async_copy16_next(const void* uniform_base, unsigned lane_offset) {
-  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" :: "v"(lane_offset), "s"(uniform_base), "n"(OFFSET) : "memory");
+// A run of copies whose sources and LDS images are both contiguous, 1 KB apart: one M0 write, and the instruction
+// offset (which is added to the global and to the LDS address alike) steps both sides.  One statement, so that
+// nothing can come between the M0 write and its readers.
+__device__ inline void async_copy16_run(const void* uniform_base, unsigned lds_base, unsigned off0, unsigned off1) {
+  asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\t"
+               "global_load_lds_dwordx4 %0, %2\n\t"
+               "global_load_lds_dwordx4 %1, %2 offset:1024"
+               :: "v"(off0), "v"(off1), "s"(uniform_base), "s"(lds_base) : "memory");
+}
+__device__ inline void async_copy16_run(const void* uniform_base, unsigned lds_base, unsigned off0, unsigned off1,
+                                        unsigned off2, unsigned off3) {
+  asm volatile("s_mov_b32 m0, %5\n\ts_nop 0\n\t"
+               "global_load_lds_dwordx4 %0, %4\n\t"
+               "global_load_lds_dwordx4 %1, %4 offset:1024\n\t"
+               "global_load_lds_dwordx4 %2, %4 offset:2048\n\t"
+               "global_load_lds_dwordx4 %3, %4 offset:3072"
+               :: "v"(off0), "v"(off1), "v"(off2), "v"(off3), "s"(uniform_base), "s"(lds_base) : "memory");
 }
 __device__ inline unsigned lds_address(const void* shared_ptr) {
   return (unsigned)(uintptr_t)(lds_void_t*)shared_ptr;
@@ -229,10 +241,7 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   // multiple of 16 rows, so the swizzle of a lane's row depends on x and a_lrow only.
   static_assert(CPW * RPC == 16, "a wave covers 16 rows of every tile");
   const int a_lrow = lane / PARTS, a_slot = lane % PARTS;
-  // q0, q1: the quarters [q0, q1) of the wave's instructions for this tile (all of them: 0, 4).
-  auto issue_tile = [&](const uint16_t* cache_src, const uint16_t* chunk_src, int tile, uint16_t* stage, auto swz,
-                        int q0, int q1) {
-    const int x0 = q0 * CPW / 4, x1 = q1 * CPW / 4;
+  auto issue_tile = [&](const uint16_t* cache_src, const uint16_t* chunk_src, int tile, uint16_t* stage, auto swz) {
     const bool is_cache = tile < cache_tiles;
     const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
     const uint16_t* base = is_cache ? cache_src : chunk_src;
@@ -240,27 +249,19 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     const int lim = is_cache ? cache_lim : chunk_lim;
     const int row_w = col0 + wave * 16;                   // first source row of this wave's 16 (wave uniform)
     if (row_w + 15 <= lim && is_cache) {
-      // Cache rows are contiguous, like their LDS image: one scalar base and one M0 for the run of requests, the
-      // instruction offset stepping both sides by 1 KB; the per-lane offset differs only in the swizzled piece.
+      // Cache rows are contiguous, like their LDS image: one scalar base and one M0 for the run of requests;
+      // the per-lane offsets differ only in the swizzled piece.
       const unsigned lane_row = (unsigned)(a_lrow * D) * 2;
-      const uint16_t* sbase = base + (size_t)(row_w + x0 * RPC) * D;
-      const unsigned m0 = __builtin_amdgcn_readfirstlane(lds_address(stage + (wave * CPW + x0) * 512));
-#pragma unroll
-      for (int x = 0; x < CPW; ++x) {
-        if (x < x0 || x >= x1) continue;
-        const unsigned voff = lane_row + ((a_slot ^ swz(x * RPC + a_lrow)) * 16);
-        const int k = x - x0;
-        if (k == 0) async_copy16_offset(sbase, voff, m0);
-        else if (k == 1) async_copy16_next<1024>(sbase, voff);
-        else if (k == 2) async_copy16_next<2048>(sbase, voff);
-        else async_copy16_next<3072>(sbase, voff);
-      }
+      const uint16_t* sbase = base + (size_t)row_w * D;
+      const unsigned m0 = __builtin_amdgcn_readfirstlane(lds_address(stage + wave * CPW * 512));
+      auto voff = [&](int x) { return lane_row + ((a_slot ^ swz(x * RPC + a_lrow)) * 16); };
+      if constexpr (CPW == 4) async_copy16_run(sbase, m0, voff(0), voff(1), voff(2), voff(3));
+      else async_copy16_run(sbase, m0, voff(0), voff(1));
     } else if (row_w + 15 <= lim) {
       // every row exists: a scalar base per instruction plus a per-lane byte offset
       const unsigned lane_row = (unsigned)(a_lrow * rstride) * 2;
 #pragma unroll
       for (int x = 0; x < CPW; ++x) {
-        if (x < x0 || x >= x1) continue;
         const unsigned voff = lane_row + ((a_slot ^ swz(x * RPC + a_lrow)) * 16);
         const uint16_t* sbase = base + (size_t)(row_w + x * RPC) * rstride;
         async_copy16_offset(sbase, voff, __builtin_amdgcn_readfirstlane(lds_address(stage + (wave * CPW + x) * 512)));
@@ -269,7 +270,6 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       // rows past the last one repeat it (they are masked later; what they must not be is unreadable)
 #pragma unroll
       for (int x = 0; x < CPW; ++x) {
-        if (x < x0 || x >= x1) continue;
         const int r = x * RPC + a_lrow;
         const uint16_t* src = base + (size_t)min(row_w + r, lim) * rstride + (a_slot ^ swz(r)) * 8;
         async_copy16(src, __builtin_amdgcn_readfirstlane(lds_address(stage + (wave * CPW + x) * 512)));
@@ -350,13 +350,13 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     f32x4_t sa[4], sb[4];
 #pragma unroll
     for (int t = 0; t < 3; ++t)
-      if (t < ntiles) issue_tile(Ku, Kcu, t, sK + t * Lds::TILE_ELEMS, kswz, 0, 4);
+      if (t < ntiles) issue_tile(Ku, Kcu, t, sK + t * Lds::TILE_ELEMS, kswz);
     wait_vmcnt<0>();
     __syncthreads();
     qk(sa, 0);
     auto step = [&](f32x4_t (&cur)[4], f32x4_t (&nxt)[4], int t) {
       const bool more = t + 3 < ntiles;
-      if (more) issue_tile(Ku, Kcu, t + 3, sK + ((t + 3) & 3) * Lds::TILE_ELEMS, kswz, 0, 4);
+      if (more) issue_tile(Ku, Kcu, t + 3, sK + ((t + 3) & 3) * Lds::TILE_ELEMS, kswz);
       if (t + 1 < ntiles) qk(nxt, (t + 1) & 3);
       stats(cur, t);
       // tile t+2 must have landed before the next iteration reads it; only this iteration's requests may stay out
@@ -537,9 +537,9 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
 
   // Iteration t: request K of tile t+2 and V of tile t+1, form the logits of tile t+1, finish tile t.
   // K stage t&1 held tile t, whose logits were formed in iteration t-1; V stage (t+1)&1 held tile t-1.
-  issue_tile(Ku, Kcu, 0, sK, kswz, 0, 4);
-  issue_tile(Vu, Vcu, 0, sV, vswz, 0, 4);
-  if (ntiles > 1) issue_tile(Ku, Kcu, 1, sK + Lds::TILE_ELEMS, kswz, 0, 4);
+  issue_tile(Ku, Kcu, 0, sK, kswz);
+  issue_tile(Vu, Vcu, 0, sV, vswz);
+  if (ntiles > 1) issue_tile(Ku, Kcu, 1, sK + Lds::TILE_ELEMS, kswz);
   wait_vmcnt<0>();
   __syncthreads();
   f32x4_t sa0[2], sa1[2], sb0[2], sb1[2];
@@ -551,15 +551,13 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     const bool more_k = t + 2 < ntiles, more_v = t + 1 < ntiles;
     uint16_t* k_stage = sK + (t & 1) * Lds::TILE_ELEMS;
     uint16_t* v_stage = sV + ((t + 1) & 1) * Lds::TILE_ELEMS;
-    auto ask_k = [&](int q0, int q1) { if (more_k) issue_tile(Ku, Kcu, t + 2, k_stage, kswz, q0, q1); };
-    auto ask_v = [&](int q0, int q1) { if (more_v) issue_tile(Vu, Vcu, t + 1, v_stage, vswz, q0, q1); };
+    if (more_k) issue_tile(Ku, Kcu, t + 2, k_stage, kswz);
+    if (more_v) issue_tile(Vu, Vcu, t + 1, v_stage, vswz);
     // The two waves that share a SIMD take the four pieces in different orders, so that one is on the matrix pipe
     // while the other is on the vector ALU instead of both wanting the same unit at the same time:
     //   waves 0-3: logits(t+1)  probabilities(t)  PV(t)  column sums(t)
     //   waves 4-7: probabilities(t)  column sums(t)  logits(t+1)  PV(t)
     uint4 phi0, plo0, phi1, plo1;
-    ask_k(0, 4);
-    ask_v(0, 4);
     if constexpr (decltype(matrix_first)::value) {
       if (t + 1 < ntiles) qk2(n0, n1, (t + 1) & 1);
       mask_tile(c0, c1, t);
