@@ -36,8 +36,8 @@ namespace {
 #ifndef TKV_KU
 #define TKV_KU 2
 #endif
-#ifndef TKV_MID_ITER
-#define TKV_MID_ITER 2
+#ifndef TKV_MID_NUM
+#define TKV_MID_NUM 3
 #endif
 #ifndef TKV_NT_RET
 #define TKV_NT_RET 1
@@ -68,6 +68,9 @@ constexpr int SPLIT_THREADS = TKV_SPLIT_THREADS;
 constexpr int MERGE_THREADS = 1024;
 constexpr int KU = TKV_KU;             // wave loads of K (and of V) per tile
 constexpr float NEG_BIG = -1.0e30f;
+// Iteration (of n) of the streaming loop at which a workgroup issues its mid-stream stores.  Measured: the
+// later they go the better, as long as they are out before the epilogue; early ones interrupt the reads.
+__device__ inline int mid_point(int n) { return n * TKV_MID_NUM / 4; }
 constexpr size_t LDS_LIMIT = 150 * 1024;   // of the 160 KB a workgroup can have
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
@@ -192,8 +195,8 @@ struct Stream {
 
   // sm_acc [WAVES][G][D], sm_wm [WAVES][G], sm_wl [WAVES][G].  `after_meta(st)` runs once the
   // bookkeeping words are known, after the first tile has been requested.
-  // `mid_stream()` runs once, a few tiles into the loop (or after it if the loop is short): the place
-  // for stores that should drain while the reads are still streaming.
+  // `mid_stream()` runs once, three quarters of the way through the loop: the place for stores that should
+  // be out of the way before the epilogue.
   template <class AfterMeta, class MidStream>
   __device__ static inline void run(const Params& p, int unit, int begin_spec, const T* __restrict__ q_in,
                                     const T* __restrict__ knew, const T* __restrict__ vnew, const int* meta,
@@ -310,15 +313,16 @@ struct Stream {
       }
     };
 
+    const int mid_iter = mid_point((end - begin + 2 * STEP - 1) / (2 * STEP));
     int iter = 0;
     for (; base < end; base += 2 * STEP, ++iter) {
       if (iter > 0 && base + STEP < end) load_tile(kb, vb, base + STEP);
       tile(ka, va, base);
       if (base + 2 * STEP < end) load_tile(ka, va, base + 2 * STEP);
       if (base + STEP < end) tile(kb, vb, base + STEP);
-      if (iter == TKV_MID_ITER) mid_stream();
+      if (iter == mid_iter) mid_stream();
     }
-    if (iter <= TKV_MID_ITER) mid_stream();
+    if (iter <= mid_iter) mid_stream();
 
     // merge the RPL lane groups of the wave
 #pragma unroll
@@ -481,6 +485,7 @@ struct StreamMfma {
 
     int base = begin + wave * TILE;
     if (base < end) { load_k(base); load_v(base); }
+    const int mid_iter = mid_point((end - begin + STEP - 1) / STEP);
     int iter = 0;
     for (; base < end; base += STEP, ++iter) {
       const int nb = base + STEP;
@@ -552,9 +557,9 @@ struct StreamMfma {
         oacc[d] = mfma16(a, plo, oacc[d]);
       }
       __builtin_amdgcn_wave_barrier();
-      if (iter == TKV_MID_ITER) mid_stream();
+      if (iter == mid_iter) mid_stream();
     }
-    if (iter <= TKV_MID_ITER) mid_stream();
+    if (iter <= mid_iter) mid_stream();
 
     float l_row = l_part + __shfl_xor(l_part, 16, 64);
     l_row += __shfl_xor(l_row, 32, 64);
@@ -588,12 +593,19 @@ __device__ inline void merge_stats(const float* pm, const float* pl, int nparts,
 // list, and the append of the new row.  `logit(g, slot)` returns the scaled logit; M, invL per g.
 // EP > 0: the first EP old scores per thread come in registers, and the caller has already written
 // the retained list except for the one entry this step's decision fills in.
+// With EP > 0, `park` (LDS, may alias the logits of head 0) receives every new score and the decision reads
+// its two operands from there; with EP == 0 the two owners leave them in sm_sc.
+// A wave issues an instruction every five cycles or so and nothing else runs at this point, so this code is
+// laid out for a short instruction stream per wave: uniform exits from the unrolled loops, and the dozen
+// bookkeeping stores dealt to lane 0 of different waves.  The k, v rows are held by the last LPR threads.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int D, int G, int THREADS, int EP, class LogitFn>
 __device__ inline void epilogue(const Params& p, int unit, const Step& st, const float (&M)[G], const float (&invL)[G],
-                                LogitFn logit, const float* s_old, uint4 knew_r, uint4 vnew_r, float* sm_sc, int32_t* __restrict__ retained, int32_t* __restrict__ n_retained,
+                                LogitFn logit, const float* s_old, uint4 knew_r, uint4 vnew_r, float* sm_sc, float* park,
+                                int32_t* __restrict__ retained, int32_t* __restrict__ n_retained,
                                 int32_t* __restrict__ evicted, int* meta, int ret_patch_tid) {
   constexpr int LPR = D / Storage<T>::EPL;
+  static_assert(THREADS >= 256 && LPR <= 64, "the bookkeeping stores are dealt to four waves");
   const int tid = threadIdx.x;
   float* Su = p.S + (size_t)unit * p.cap;
   int* Eu = p.E + (size_t)unit * 2 * p.m;
@@ -608,45 +620,49 @@ __device__ inline void epilogue(const Params& p, int unit, const Step& st, const
   };
   auto put_score = [&](int slot, float sn) {
     store_maybe_nt<TKV_NT_S>(sn, Su + slot);
-    if (slot == st.scope_l) sm_sc[0] = sn;
-    if (slot == st.scope_r) sm_sc[1] = sn;
+    if constexpr (EP > 0) park[slot] = sn;
+    else {
+      if (slot == st.scope_l) sm_sc[0] = sn;
+      if (slot == st.scope_r) sm_sc[1] = sn;
+    }
   };
 #pragma unroll
   for (int x = 0; x < EP; ++x) {
+    if (x * THREADS >= st.n1) break;                 // uniform
     const int slot = tid + x * THREADS;
     if (slot < st.n1) put_score(slot, s_old[x] + prob(slot));
   }
   for (int slot = tid + EP * THREADS; slot < st.n1; slot += THREADS)
     put_score(slot, (slot == st.fslot ? 0.f : Su[slot]) + prob(slot));
   // the new token's k, v become cache rows
-  if (tid < LPR) {
+  if (tid >= THREADS - LPR) {
     T* Kw = (T*)p.K + ((size_t)unit * p.cap + st.fslot) * D;
     T* Vw = (T*)p.V + ((size_t)unit * p.cap + st.fslot) * D;
-    reinterpret_cast<uint4*>(Kw)[tid] = knew_r;
-    reinterpret_cast<uint4*>(Vw)[tid] = vnew_r;
+    reinterpret_cast<uint4*>(Kw)[tid - (THREADS - LPR)] = knew_r;
+    reinterpret_cast<uint4*>(Vw)[tid - (THREADS - LPR)] = vnew_r;
   }
   __syncthreads();
 
-  // every thread takes the same decision from the same two numbers; thread 0 records it
+  // lane 0 of the first four waves and the owner of the open retained entry take the same decision from the
+  // same two numbers; everyone else is done
+  if (EP > 0 && !((tid & 63) == 0 && tid < 256) && tid != ret_patch_tid) return;
   bool drop_right = false;
   if (st.evict) {
-    const float bl = sm_sc[0] / (float)(st.t - st.pos_l + 1);
-    const float br = sm_sc[1] / (float)(st.t - st.pos_r + 1);
+    const float sl = EP > 0 ? park[st.scope_l] : sm_sc[0], sr = EP > 0 ? park[st.scope_r] : sm_sc[1];
+    const float bl = sl / (float)(st.t - st.pos_l + 1);
+    const float br = sr / (float)(st.t - st.pos_r + 1);
     drop_right = (p.flags & TREEKV_KEEP_LEFT) || (bl > br);     // strict: a tie evicts the left slot
   }
   const int surv_pos = drop_right ? st.pos_l : st.pos_r;
-  if (tid == 0) {
-    int f_new = st.n1, ev_pos = -1, j = st.j0, rhead = st.rhead;
+  if (tid == 0) {                                    // the tree entry the survivor moves up to
     if (st.evict) {
-      if (p.n_recent > 0) {                  // the new token takes the ring entry of the one that left
-        Ru[rhead] = st.fslot;
-        rhead = rhead + 1 == p.n_recent ? 0 : rhead + 1;
-      }
-      Eu[p.m + st.j0] = st.newcomer;
-      PEu[p.m + st.j0] = st.newcomer_pos;
       Eu[st.j0] = drop_right ? st.scope_l : st.scope_r;
       PEu[st.j0] = surv_pos;
-      ev_pos = drop_right ? st.pos_r : st.pos_l;
+    }
+  } else if (tid == 64) {                            // the five bookkeeping words
+    int f_new = st.n1, j = st.j0, rhead = st.rhead;
+    if (st.evict) {
+      if (p.n_recent > 0) rhead = rhead + 1 == p.n_recent ? 0 : rhead + 1;
       f_new = drop_right ? st.scope_r : st.scope_l;
       j = st.j0 + 1 == p.m ? 0 : st.j0 + 1;
     }
@@ -655,8 +671,15 @@ __device__ inline void epilogue(const Params& p, int unit, const Step& st, const
     meta[META_J] = j;
     meta[META_RHEAD] = rhead;
     meta[META_T] = st.t + 1;
-    if (evicted) evicted[unit] = ev_pos;
+  } else if (tid == 128) {                           // what the caller asked to be told
+    if (evicted) evicted[unit] = st.evict ? (drop_right ? st.pos_r : st.pos_l) : -1;
     if (n_retained) n_retained[unit] = st.n_new;
+  } else if (tid == 192) {                           // the newcomer's tree entry and the ring
+    if (st.evict) {
+      if (p.n_recent > 0) Ru[st.rhead] = st.fslot;   // the new token takes the ring entry of the one that left
+      Eu[p.m + st.j0] = st.newcomer;
+      PEu[p.m + st.j0] = st.newcomer_pos;
+    }
   }
 
   // retained positions in ascending order
@@ -707,9 +730,10 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
   int begin, end;
   St::run(p, unit, 0, q_in, knew, vnew, meta, sm_s, p.cap, sm_acc, sm_wm, sm_wl, st, begin, end, true,
           [&](const Step& s0) {
-            if (tid < D / Storage<T>::EPL) {
-              knew_r = reinterpret_cast<const uint4*>(knew)[tid];
-              vnew_r = reinterpret_cast<const uint4*>(vnew)[tid];
+            constexpr int LPR = D / Storage<T>::EPL;
+            if (tid >= THREADS - LPR) {
+              knew_r = reinterpret_cast<const uint4*>(knew)[tid - (THREADS - LPR)];
+              vnew_r = reinterpret_cast<const uint4*>(vnew)[tid - (THREADS - LPR)];
             }
 #pragma unroll
             for (int x = 0; x < EP; ++x) {
@@ -751,18 +775,20 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
     merge_stats(sm_wm + g, sm_wl + g, WAVES, G, M[g], L);
     invL[g] = 1.0f / L;
   }
-  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
-  for (int i = tid; i < G * D; i += THREADS) {
-    const int g = i / D, col = i % D;
-    float a = 0.f;
-    for (int w = 0; w < WAVES; ++w) a += sm_acc[(w * G + g) * D + col] * fast_exp2(sm_wm[w * G + g] - M[g]);
-    out[((size_t)b * p.H + (size_t)kvh * G + g) * D + col] = a * invL[g];
-  }
   // the thread that wrote the retained entry the decision fills in
   const int ret_i = p.n_sink + st.j0;
   const int ret_owner = (ret_i < 4 * EP4 * THREADS ? ret_i / 4 : ret_i) % THREADS;
   epilogue<T, D, G, THREADS, EP>(p, unit, st, M, invL, [&](int g, int slot) { return sm_s[(size_t)g * p.cap + slot]; },
-                                 s_old, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta, ret_owner);
+                                 s_old, knew_r, vnew_r, sm_sc, sm_s, retained, n_retained, evicted, meta, ret_owner);
+  // the attention output: last, and by the highest threads, whose waves have no bookkeeping stores to issue
+  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+  for (int i = THREADS - 1 - tid; i < G * D; i += THREADS) {
+    const int g = i / D, col = i % D;
+    float a = 0.f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) a += sm_acc[(w * G + g) * D + col] * fast_exp2(sm_wm[w * G + g] - M[g]);
+    out[((size_t)b * p.H + (size_t)kvh * G + g) * D + col] = a * invL[g];
+  }
 }
 
 template <typename T, int D, int G>
@@ -836,9 +862,9 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, c
     pe_pre[x] = position_of(p, st, PEu, slot, -1, true);
   }
   uint4 knew_r = make_uint4(0, 0, 0, 0), vnew_r = knew_r;
-  if (tid < LPR) {
-    knew_r = reinterpret_cast<const uint4*>(k_in + (size_t)unit * D)[tid];
-    vnew_r = reinterpret_cast<const uint4*>(v_in + (size_t)unit * D)[tid];
+  if (tid >= THREADS - LPR) {
+    knew_r = reinterpret_cast<const uint4*>(k_in + (size_t)unit * D)[tid - (THREADS - LPR)];
+    vnew_r = reinterpret_cast<const uint4*>(v_in + (size_t)unit * D)[tid - (THREADS - LPR)];
   }
   load_scope(p, st, p.E + (size_t)unit * 2 * p.m, PEu, p.R + (size_t)unit * max(p.n_recent, 1));
 
@@ -877,12 +903,12 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, c
     for (int i = tid + EP * THREADS; i < p.budget; i += THREADS) ret[i] = position_of(p, st, PEu, i, -1, true);
     __syncthreads();
     epilogue<T, D, G, THREADS, EP>(p, unit, st, M, invL, [&](int g, int slot) { return smem[(size_t)g * p.cap + slot]; },
-                                   s_old, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta,
+                                   s_old, knew_r, vnew_r, sm_sc, smem, retained, n_retained, evicted, meta,
                                    (p.n_sink + st.j0) % THREADS);
   } else {
     (void)ret;
     epilogue<T, D, G, THREADS, 0>(p, unit, st, M, invL, [&](int g, int slot) { return lg[(size_t)g * p.cap + slot]; },
-                                  nullptr, knew_r, vnew_r, sm_sc, retained, n_retained, evicted, meta, -1);
+                                  nullptr, knew_r, vnew_r, sm_sc, nullptr, retained, n_retained, evicted, meta, -1);
   }
 }
 
