@@ -38,6 +38,17 @@
 //    Algorithm 1's append / compare / evict / advance is replayed for the L
 //    tokens in order.  L = 1 is exactly a decode step.
 //
+//  * One-shot prompt compression (Section 4.2, "Prefilling Stage").  The prompt is cut into
+//    blocks of b tokens; the queries of the last block (the observation window) attend the
+//    whole prompt causally; a token's importance is its attention averaged over the window
+//    queries that see it (S / C of Algorithm 1 restricted to those queries, summed over the
+//    group's heads); a block's importance is the mean over its b tokens; Algorithm 1
+//    (lines 4-5, 9-17) then runs with blocks in the place of tokens, the block scores frozen,
+//    a capacity of c / b blocks and ceil(n_sink / b) sink and ceil(n_recent / b) recent
+//    blocks.  The paper does not say how decoding takes over; here the kept tokens keep their
+//    window average as Sbar: C becomes the number of prompt queries since the token arrived
+//    (T - position) and S = Sbar * C, and token-level eviction starts at idx = 1.
+//
 // Near-tie handling for parity runs: every decision reports its relative
 // margin |Sbar_l - Sbar_r| / max(Sbar_l, Sbar_r).  A caller may pass the
 // position another implementation evicted; the oracle adopts it only when
@@ -291,6 +302,84 @@ void tko_prefill_chunk(void* h, const double* Q, const double* K, const double* 
   }
   s.K.swap(K2); s.V.swap(V2); s.S.swap(S2); s.C.swap(C2); s.pos.swap(P2);
   s.t += L;
+}
+
+// One-shot block-level compression of a whole prompt (Section 4.2).  The stream must be empty.
+//   Qw [b][G][d]: queries of the prompt's last b tokens; K, V [T][d]: the whole prompt.
+//   forced_block: null, or [T/b] the block another implementation evicted when block i was
+//   appended (-1 where it evicted none); adopted only at near-ties, as in tko_decode_step.
+//   evicted_block, margins [T/b]; counts[0] += adopted, counts[1] += disagreed;
+//   token_sbar [T], block_score [T/b] (any may be null).
+// Returns 0, or -1 if the arguments do not fit (non-empty stream, T or c not a multiple of b,
+// no tree block left).
+int tko_prefill_prompt(void* h, const double* Qw, const double* K, const double* V, int T, int b,
+                       const long long* forced_block, double follow_thresh, long long* evicted_block,
+                       double* margins, long long* counts, double* token_sbar, double* block_score) {
+  Stream& s = *static_cast<Stream*>(h);
+  if (!s.pos.empty() || s.t != 0 || b < 1 || T < b || T % b != 0 || s.c % b != 0) return -1;
+  const int N = T / b, W = b;
+  Stream blk;                                     // Algorithm 1's scalars, counted in blocks
+  blk.c = s.c / b;
+  blk.n_sink = (s.n_sink + b - 1) / b;
+  blk.n_recent = (s.n_recent + b - 1) / b;
+  blk.m = blk.c - blk.n_sink - blk.n_recent;
+  blk.flags = s.flags;
+  if (blk.m < 1) return -1;
+  // the observation window queries the entire sequence (causally); lines 6-8 for those queries only
+  std::vector<double> Ssum((size_t)T, 0.0), logits((size_t)T), a((size_t)T);
+  std::vector<long long> Cnt((size_t)T, 0);
+  for (int i = 0; i < W; ++i) {
+    const size_t vis = (size_t)(T - W + i) + 1;
+    for (int g = 0; g < s.G; ++g) {
+      const double* q = Qw + ((size_t)i * s.G + g) * s.d;
+      for (size_t j = 0; j < vis; ++j) {
+        double acc = 0.0;
+        for (int e = 0; e < s.d; ++e) acc += q[e] * K[j * s.d + e];
+        logits[j] = acc * s.scale;
+      }
+      softmax_row(logits, vis, a);
+      for (size_t j = 0; j < vis; ++j) Ssum[j] += a[j];
+    }
+    for (size_t j = 0; j < vis; ++j) Cnt[j] += 1;
+  }
+  // line 10 per token, then the block's score: the average over its b tokens
+  std::vector<double> sbar((size_t)T), beta((size_t)N);
+  for (int j = 0; j < T; ++j) sbar[j] = Ssum[j] / (double)Cnt[j];
+  for (int k = 0; k < N; ++k) {
+    double acc = 0.0;
+    for (int x = 0; x < b; ++x) acc += sbar[(size_t)k * b + x];
+    beta[k] = acc / (double)b;
+  }
+  if (token_sbar) for (int j = 0; j < T; ++j) token_sbar[j] = sbar[j];
+  if (block_score) for (int k = 0; k < N; ++k) block_score[k] = beta[k];
+  // Algorithm 1, lines 4-5 and 9-17, one block at a time
+  std::vector<long long> block_id((size_t)N);
+  for (int k = 0; k < N; ++k) block_id[k] = k;
+  std::vector<int> order;
+  for (int k = 0; k < N; ++k) {
+    order.push_back(k);
+    Decision dec;
+    const int victim = choose_eviction(blk, order, beta, block_id, forced_block ? forced_block[k] : -1,
+                                       follow_thresh, dec);
+    if (victim >= 0) order.erase(order.begin() + victim);
+    if (evicted_block) evicted_block[k] = dec.evicted_pos;
+    if (margins) margins[k] = dec.margin;
+    if (counts) { counts[0] += dec.adopted; counts[1] += dec.disagreed; }
+  }
+  // the kept blocks' tokens are the cache that decoding starts from
+  for (int kb : order) {
+    for (int x = 0; x < b; ++x) {
+      const long long j = (long long)kb * b + x;
+      s.K.emplace_back(K + (size_t)j * s.d, K + (size_t)(j + 1) * s.d);
+      s.V.emplace_back(V + (size_t)j * s.d, V + (size_t)(j + 1) * s.d);
+      s.C.push_back((long long)T - j);
+      s.S.push_back(sbar[(size_t)j] * (double)((long long)T - j));
+      s.pos.push_back(j);
+    }
+  }
+  s.t = T;
+  s.idx = 1;
+  return 0;
 }
 
 }  // extern "C"

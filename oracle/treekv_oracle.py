@@ -56,6 +56,8 @@ def _load():
         lib.tko_decode_step.argtypes = [C.c_void_p, dp, dp, dp, dp, C.c_longlong, C.c_double, C.c_int, lp, dp]
         lib.tko_decode_stream.argtypes = [C.c_void_p, dp, dp, dp, C.c_int, dp, lp, C.c_double, lp, dp, lp]
         lib.tko_prefill_chunk.argtypes = [C.c_void_p, dp, dp, dp, C.c_int, dp, lp, C.c_double, lp, dp, ip, ip]
+        lib.tko_prefill_prompt.restype = C.c_int
+        lib.tko_prefill_prompt.argtypes = [C.c_void_p, dp, dp, dp, C.c_int, C.c_int, lp, C.c_double, lp, dp, lp, dp, dp]
         _lib = lib
     return _lib
 
@@ -153,6 +155,32 @@ class OracleStream:
                                     _lptr(fp) if fp is not None else None, float(follow_thresh),
                                     _lptr(ev), _dptr(mg), _iptr(ad), _iptr(dis))
         return dict(out=out, evicted=ev, margins=mg, adopted=ad, disagreed=dis)
+
+    def prefill_prompt(self, Qw, K, V, block: int, *, forced_blocks=None, follow_thresh: float = 0.0):
+        """One-shot block-level compression of a whole prompt (Section 4.2); the stream must be empty.
+
+        Qw [block, G, d] (queries of the last block), K/V [T, d] -> dict(evicted_blocks [T/block],
+        margins, adopted, disagreed, token_scores [T], block_scores [T/block]).
+        """
+        K = np.ascontiguousarray(K, np.float64)
+        T = K.shape[0]
+        K = K.reshape(T, self.d)
+        V = np.ascontiguousarray(V, np.float64).reshape(T, self.d)
+        Qw = np.ascontiguousarray(Qw, np.float64).reshape(block, self.G, self.d)
+        N = T // block if block > 0 else 0
+        ev = np.full(max(N, 1), -1, np.int64)
+        mg = np.full(max(N, 1), -1.0, np.float64)
+        counts = np.zeros(2, np.int64)
+        tok = np.empty(T, np.float64)
+        blk = np.empty(max(N, 1), np.float64)
+        fb = None if forced_blocks is None else np.ascontiguousarray(forced_blocks, np.int64).reshape(N)
+        rc = self._lib.tko_prefill_prompt(self._h, _dptr(Qw), _dptr(K), _dptr(V), T, int(block),
+                                          _lptr(fb) if fb is not None else None, float(follow_thresh),
+                                          _lptr(ev), _dptr(mg), _lptr(counts), _dptr(tok), _dptr(blk))
+        if rc != 0:
+            raise ValueError("prefill_prompt: arguments do not fit this stream")
+        return dict(evicted_blocks=ev[:N], margins=mg[:N], adopted=int(counts[0]), disagreed=int(counts[1]),
+                    token_scores=tok, block_scores=blk[:N])
 
 
 def run_decode_stream(cfg: dict, q, k, v, *, forced=None, follow_thresh: float = 0.0,

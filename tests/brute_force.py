@@ -85,6 +85,42 @@ class BruteTreeKV:
         self.t += L
         return outs, evs
 
+    def prefill_prompt(self, Qw, K, V, b):
+        """Section 4.2 on an empty cache: blocks of b tokens, the last block's queries score the prompt."""
+        T = len(K)
+        N = T // b
+        toks = [dict(pos=j, k=list(K[j]), v=list(V[j]), parts=[], C=0) for j in range(T)]
+        for i in range(b):
+            vis = toks[: T - b + i + 1]
+            _, probs = self._attend(Qw[i], vis)
+            for j, rec in enumerate(vis):
+                rec["C"] += 1
+                rec["parts"] += [probs[g][j] for g in range(self.G)]
+        sbar = [math.fsum(rec["parts"]) / rec["C"] for rec in toks]
+        beta = [math.fsum(sbar[k * b:(k + 1) * b]) / b for k in range(N)]
+        # Algorithm 1 with blocks for tokens
+        cb, sink_b = self.c // b, -(-self.n_sink // b)
+        recent_b = -(-(self.c - self.n_sink - self.m) // b)
+        m_b = cb - sink_b - recent_b
+        idx, seq, gone = 1, [], []
+        for k in range(N):
+            seq.append(k)
+            if len(seq) <= cb:
+                gone.append(-1)
+                continue
+            i = sink_b + idx - 1
+            if self.keep_left or beta[seq[i]] > beta[seq[i + 1]]:
+                gone.append(seq.pop(i + 1))
+            else:
+                gone.append(seq.pop(i))
+            idx = idx % m_b + 1
+        self.cache = []
+        for k in seq:
+            for j in range(k * b, (k + 1) * b):
+                self.cache.append(dict(pos=j, k=toks[j]["k"], v=toks[j]["v"], S=sbar[j] * (T - j), C=T - j))
+        self.t, self.idx = T, 1
+        return gone, sbar, beta
+
     def positions(self):
         return [rec["pos"] for rec in self.cache]
 

@@ -445,3 +445,183 @@ def test_tiny_config_runs_in_seconds(oracle):
         q, k, v = inputs.stream_iid(0, 512, 1, 64, kv_head=h, k_scale=1.0 / 8.0, dtype="f32")
         res = oracle.run_decode_stream(_cfg(64, 1, 64, 4, 28, scale=1.0), q, k, v)
         assert len(res["stream"]) == 64 and np.count_nonzero(res["evicted"] >= 0) == 512 - 64
+
+
+# --------------------------------------------------------------------------- #
+# One-shot block-level prompt compression (Section 4.2)
+# --------------------------------------------------------------------------- #
+def _prompt(seed, T, G, d, b):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((b, G, d)), rng.standard_normal((T, d)), rng.standard_normal((T, d))
+
+
+def _block_layout(c, b, n_sink, n_recent):
+    cb, sb, rb = c // b, -(-n_sink // b), -(-n_recent // b)
+    return cb, sb, rb, cb - sb - rb
+
+
+def _final_block_spans(N, c, b, n_sink, n_recent):
+    cb, sb, rb, _ = _block_layout(c, b, n_sink, n_recent)
+    sim = SpanSim(cb, sb, rb)
+    for _ in range(N):
+        sim.step()
+    return sim.spans
+
+
+@pytest.mark.parametrize("G", [1, 3])
+def test_prompt_scores_equal_dense_window_attention(oracle, G):
+    """Token scores are the column means of the window's causal attention matrix (library softmax, fp64);
+    block scores are the means of their tokens; each window row carries mass 1."""
+    import torch
+    T, d, b, c = 96, 8, 8, 32
+    Qw, K, V = _prompt(5, T, G, d, b)
+    s = oracle.OracleStream(c, G, d, n_sink=2, n_recent=8)
+    r = s.prefill_prompt(Qw, K, V, b)
+    logits = torch.einsum("igd,jd->gij", torch.tensor(Qw), torch.tensor(K)) / math.sqrt(d)
+    rows = torch.arange(b)[:, None] + (T - b)
+    mask = torch.arange(T)[None, :] > rows
+    A = torch.softmax(logits.masked_fill(mask[None], float("-inf")), dim=-1)     # [G, b, T]
+    seen = (~mask).sum(0).double()                                               # window queries that see j
+    want = (A.sum((0, 1)) / seen).numpy()
+    np.testing.assert_allclose(r["token_scores"], want, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(r["block_scores"], want.reshape(-1, b).mean(1), rtol=1e-12, atol=1e-15)
+    assert abs(float((r["token_scores"] * seen.numpy()).sum()) - G * b) < 1e-9
+
+
+@pytest.mark.parametrize("c,b,T,n_sink,n_recent", [(16, 4, 64, 0, 0), (16, 4, 100, 0, 4), (32, 4, 256, 4, 8),
+                                                   (24, 2, 90, 3, 5), (8, 1, 40, 0, 0), (64, 8, 1024, 4, 28)])
+def test_prompt_survivor_is_rightmost_maximum_of_its_span(oracle, c, b, T, n_sink, n_recent):
+    """With frozen scores the block a slot keeps is the best block of the slot's span, the rightmost one
+    among equals (strict '>' keeps the right member of a tied scope); the spans do not depend on scores."""
+    G, d = 1, 4
+    Qw, K, V = _prompt(c + T, T, G, d, b)
+    s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent)
+    r = s.prefill_prompt(Qw, K, V, b)
+    beta = r["block_scores"]
+    kept = []
+    for lo, hi in _final_block_spans(T // b, c, b, n_sink, n_recent):
+        seg = beta[lo:hi + 1]
+        kept.append(lo + int(np.flatnonzero(seg == seg.max())[-1]))
+    want = np.concatenate([np.arange(k * b, (k + 1) * b) for k in kept])
+    np.testing.assert_array_equal(s.retained(), want)
+    assert len(s) == min(T, c) and s.t == T and s.idx == 1
+
+
+def test_prompt_keep_left_keeps_first_block_of_every_span(oracle):
+    c, b, T, n_sink, n_recent = 32, 4, 200, 4, 8
+    Qw, K, V = _prompt(1, T, 1, 4, b)
+    s = oracle.OracleStream(c, 1, 4, n_sink=n_sink, n_recent=n_recent, flags=oracle.KEEP_LEFT)
+    s.prefill_prompt(Qw, K, V, b)
+    want = np.concatenate([np.arange(lo * b, (lo + 1) * b) for lo, _ in _final_block_spans(T // b, c, b, n_sink, n_recent)])
+    np.testing.assert_array_equal(s.retained(), want)
+
+
+def test_prompt_uniform_attention_ties_keep_the_right_block(oracle):
+    """q = 0: every token before the window gets bit-identical scores, so every scope before the window is an
+    exact tie and the strict comparison evicts its left member: each span keeps its last block."""
+    c, b, T = 16, 4, 128
+    _, K, V = _prompt(2, T, 1, 4, b)
+    s = oracle.OracleStream(c, 1, 4, n_sink=0, n_recent=4)
+    r = s.prefill_prompt(np.zeros((b, 1, 4)), K, V, b)
+    assert len(set(r["token_scores"][: T - b].tolist())) == 1
+    spans = _final_block_spans(T // b, c, b, 0, 4)
+    want = np.concatenate([np.arange(hi * b, (hi + 1) * b) for _, hi in spans])
+    np.testing.assert_array_equal(s.retained(), want)
+
+
+def test_prompt_that_fits_is_kept_whole(oracle):
+    c, b, T = 32, 4, 24
+    Qw, K, V = _prompt(3, T, 2, 4, b)
+    s = oracle.OracleStream(c, 2, 4, n_sink=4, n_recent=8)
+    r = s.prefill_prompt(Qw, K, V, b)
+    np.testing.assert_array_equal(s.retained(), np.arange(T))
+    assert (r["evicted_blocks"] == -1).all()
+    Kc, Vc = s.kv()
+    np.testing.assert_array_equal(Kc, K)
+    np.testing.assert_array_equal(Vc, V)
+
+
+def test_prompt_hands_over_to_decoding(oracle):
+    """After the prompt: C = T - position, S / C = the window average, idx = 1; decoding then keeps the budget
+    and evicts inside the token-level scope, starting at the first one."""
+    c, b, T, n_sink, n_recent, d = 16, 4, 64, 2, 4, 4
+    Qw, K, V = _prompt(4, T, 1, d, b)
+    s = oracle.OracleStream(c, 1, d, n_sink=n_sink, n_recent=n_recent)
+    r = s.prefill_prompt(Qw, K, V, b)
+    pos, S, C = s.state()
+    np.testing.assert_array_equal(C, T - pos)
+    np.testing.assert_allclose(S / C, r["token_scores"][pos], rtol=1e-15)
+    Kc, Vc = s.kv()
+    np.testing.assert_array_equal(Kc, K[pos])
+    np.testing.assert_array_equal(Vc, V[pos])
+    q, k, v = _rand_stream(9, 12, 1, d)
+    m = c - n_sink - n_recent
+    for t in range(12):
+        before = list(s.retained()) + [T + t]
+        i = n_sink + (t % m)
+        _, ev, _, _, _ = s.decode_step(q[t], k[t], v[t])
+        assert ev in before[i:i + 2] and len(s) == c
+    assert (s.retained()[-n_recent:] == np.arange(T + 12 - n_recent, T + 12)).all()
+
+
+def test_prompt_brute_force(oracle):
+    for seed in range(60):
+        rng = np.random.default_rng(seed)
+        b = int(rng.integers(1, 4))
+        cb = int(rng.integers(3, 7))
+        c = cb * b
+        n_sink = int(rng.integers(0, b + 1))
+        n_recent = int(rng.integers(0, b + 1))
+        if cb - (-(-n_sink // b)) - (-(-n_recent // b)) < 1:
+            continue
+        G, d = int(rng.integers(1, 3)), 3
+        T = b * int(rng.integers(1, 14))
+        Qw, K, V = _prompt(1000 + seed, T, G, d, b)
+        keep_left = seed % 7 == 0
+        s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent, flags=oracle.KEEP_LEFT if keep_left else 0)
+        r = s.prefill_prompt(Qw, K, V, b)
+        bf = BruteTreeKV(c, G, d, n_sink=n_sink, n_recent=n_recent, keep_left=keep_left)
+        gone, sbar, beta = bf.prefill_prompt(Qw.tolist(), K.tolist(), V.tolist(), b)
+        assert list(r["evicted_blocks"]) == gone, seed
+        assert list(s.retained()) == bf.positions(), seed
+        np.testing.assert_allclose(r["token_scores"], sbar, rtol=1e-12)
+        np.testing.assert_allclose(r["block_scores"], beta, rtol=1e-12)
+        S_b, C_b = bf.scores()
+        _, S, C = s.state()
+        np.testing.assert_allclose(S, S_b, rtol=1e-12)
+        assert list(C) == C_b
+        # and decoding goes on identically
+        q, k, v = _rand_stream(seed, 6, G, d)
+        for t in range(6):
+            o1, e1, _, _, _ = s.decode_step(q[t], k[t], v[t])
+            o2, e2 = bf.decode_step(q[t].tolist(), k[t].tolist(), v[t].tolist())
+            assert e1 == e2, (seed, t)
+            np.testing.assert_allclose(o1, np.array(o2), rtol=1e-10, atol=1e-12)
+
+
+def test_prompt_rejects_what_does_not_fit(oracle):
+    s = oracle.OracleStream(16, 1, 4)
+    Qw, K, V = _prompt(0, 30, 1, 4, 4)
+    with pytest.raises(ValueError):
+        s.prefill_prompt(Qw, K, V, 4)            # 30 is not a multiple of 4
+    with pytest.raises(ValueError):
+        s.prefill_prompt(Qw[:3], K[:27], V[:27], 3)  # nor is the budget of 3
+    s.prefill_prompt(Qw, K[:28], V[:28], 4)
+    with pytest.raises(ValueError):
+        s.prefill_prompt(Qw, K[:28], V[:28], 4)  # not empty any more
+
+
+def test_prompt_follow_mode(oracle):
+    """A forced block is adopted only when it is the other member of the scope and the margin is small."""
+    c, b, T = 16, 4, 64
+    Qw, K, V = _prompt(6, T, 1, 4, b)
+    ref = oracle.OracleStream(c, 1, 4).prefill_prompt(Qw, K, V, b)
+    first = int(np.flatnonzero(ref["evicted_blocks"] >= 0)[0])
+    forced = ref["evicted_blocks"].copy()
+    forced[first] = 1 - forced[first]            # the first scope is blocks (0, 1)
+    s = oracle.OracleStream(c, 1, 4)
+    r = s.prefill_prompt(Qw, K, V, b, forced_blocks=forced, follow_thresh=0.0)
+    assert r["disagreed"] == 1 and r["adopted"] == 0 and r["evicted_blocks"][first] == ref["evicted_blocks"][first]
+    s = oracle.OracleStream(c, 1, 4)
+    r = s.prefill_prompt(Qw, K, V, b, forced_blocks=forced, follow_thresh=2.0)
+    assert r["adopted"] == 1 and r["evicted_blocks"][first] == forced[first]
