@@ -67,6 +67,8 @@ typedef struct treekv_config {
   int32_t flags;         /* TREEKV_KEEP_LEFT or 0                                              */
   int32_t max_chunk;     /* largest `len` treekv_prefill_chunk will be given; 0 selects 512    */
   int32_t kv_splits;     /* decode: workgroups per (batch, KV head); 0 lets the library choose */
+  int32_t max_prompt;    /* longest `len` treekv_prefill_prompt will be given; 0: that call is not used
+                            (its scratch, 4 bytes per token and (batch, KV head), is then left out)    */
 } treekv_config;
 
 /*
@@ -128,6 +130,34 @@ int treekv_decode_step(treekv_ctx* ctx, const void* q, const void* k, const void
 int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const void* V, int len,
                          void* out, int32_t* retained, int32_t* n_retained, int32_t* evicted,
                          void* stream);
+
+/*
+ * treekv_prefill_prompt - the paper's own prefilling stage (Section 4.2): a whole prompt of `len` tokens is
+ * compressed in one shot, block by block.  The prompt is cut into blocks of `block` tokens; the queries of
+ * its last block (the observation window) attend the entire prompt causally; a token's importance is its
+ * attention weight averaged over the window queries that see it (S / C of Algorithm 1, lines 7-8 and 10,
+ * for those queries; the G query heads of a KV head add up); a block's importance is the mean over its
+ * tokens; Algorithm 1's append / compare / evict / advance (lines 4-5, 9-17) then runs with blocks in the
+ * place of tokens and these scores frozen: budget / block blocks are kept, ceil(n_sink / block) leading
+ * and ceil(n_recent / block) trailing blocks are never evicted.  The call REPLACES the context's state
+ * (the context must have been reset once since its workspace was bound).  Afterwards the cache holds
+ * the kept blocks' tokens and decoding can go on: the paper does not say how; here a kept token's
+ * averaged score stays its window average (its count becomes len - position, its accumulated weight
+ * that count times the average) and token-level eviction starts at the first scope.
+ *   Qw [B, block, H, d]: queries of the prompt's last `block` tokens; K, V [B, len, Hkv, d]: the whole
+ *   prompt; storage dtype (bf16 only), read only
+ *   retained   [B, Hkv, c] int32: positions kept, ascending, padded with -1 (len < c keeps everything)
+ *   n_retained [B, Hkv] int32 (may be NULL)
+ *   evicted_blocks [B, Hkv, len / block] int32 (may be NULL): the block evicted when block i was
+ *              appended, or -1
+ *   token_scores [B, Hkv, len] float32 (may be NULL): the tokens' averaged window attention
+ * Errors: TREEKV_EINVAL unless 1 <= block <= len <= max_prompt, block divides len and budget, and
+ * budget / block - ceil(n_sink / block) - ceil(n_recent / block) >= 1; TREEKV_EUNSUPPORTED if
+ * block * G > 128 or the dtype is not bf16.
+ */
+int treekv_prefill_prompt(treekv_ctx* ctx, const void* Qw, const void* K, const void* V, int len, int block,
+                          int32_t* retained, int32_t* n_retained, int32_t* evicted_blocks,
+                          float* token_scores, void* stream);
 
 /*
  * treekv_scores - accumulated attention weights S (Algorithm 1, line 8) of the

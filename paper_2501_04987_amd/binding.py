@@ -23,7 +23,8 @@ TREEKV_KEEP_LEFT = 1
 
 EXPORTS = [
     "treekv_init", "treekv_init_ex", "treekv_destroy", "treekv_get_config", "treekv_workspace_bytes",
-    "treekv_bind_workspace", "treekv_reset", "treekv_decode_step", "treekv_prefill_chunk", "treekv_scores",
+    "treekv_bind_workspace", "treekv_reset", "treekv_decode_step", "treekv_prefill_chunk", "treekv_prefill_prompt",
+    "treekv_scores",
     "treekv_gather_kv", "treekv_strerror", "treekv_last_hip_error",
 ]
 
@@ -33,6 +34,7 @@ class treekv_config(C.Structure):
         ("budget", C.c_int32), ("q_heads", C.c_int32), ("kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("batch", C.c_int32), ("dtype", C.c_int32), ("n_sink", C.c_int32), ("n_recent", C.c_int32),
         ("softmax_scale", C.c_float), ("flags", C.c_int32), ("max_chunk", C.c_int32), ("kv_splits", C.c_int32),
+        ("max_prompt", C.c_int32),
     ]
 
 
@@ -60,6 +62,7 @@ def load() -> C.CDLL:
     lib.treekv_reset.argtypes = [vp, vp]
     lib.treekv_decode_step.argtypes = [vp, vp, vp, vp, vp, i32p, i32p, i32p, vp]
     lib.treekv_prefill_chunk.argtypes = [vp, vp, vp, vp, C.c_int, vp, i32p, i32p, i32p, vp]
+    lib.treekv_prefill_prompt.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, i32p, i32p, i32p, vp, vp]
     lib.treekv_scores.argtypes = [vp, vp, vp]
     lib.treekv_gather_kv.argtypes = [vp, vp, vp, vp]
     lib.treekv_strerror.argtypes = [C.c_int]
@@ -87,7 +90,7 @@ class TreeKV:
     def __init__(self, budget: int, heads: int, head_dim: int, *, kv_heads: int | None = None, batch: int = 1,
                  dtype: str = "bf16", n_sink: int | None = None, n_recent: int | None = None,
                  softmax_scale: float = 0.0, flags: int = 0, max_chunk: int = 0, kv_splits: int = 0,
-                 device="cuda", workspace=None):
+                 max_prompt: int = 0, device="cuda", workspace=None):
         import torch
 
         self._torch = torch
@@ -95,14 +98,14 @@ class TreeKV:
         self._h = C.c_void_p()
         self.device = torch.device(device)
         if kv_heads is None and batch == 1 and dtype == "bf16" and n_sink is None and n_recent is None \
-                and softmax_scale == 0.0 and flags == 0 and max_chunk == 0 and kv_splits == 0:
+                and softmax_scale == 0.0 and flags == 0 and max_chunk == 0 and kv_splits == 0 and max_prompt == 0:
             rc = self._lib.treekv_init(C.byref(self._h), budget, heads, head_dim)
         else:
             if n_sink is None and n_recent is None:      # same default layout as treekv_init
                 n_sink, n_recent = 4, budget - budget // 2 - 4
             cfg = treekv_config(budget, heads, kv_heads or heads, head_dim, batch,
                                 {"bf16": TREEKV_BF16, "f32": TREEKV_F32}[dtype], n_sink or 0, n_recent or 0,
-                                softmax_scale, flags, max_chunk, kv_splits)
+                                softmax_scale, flags, max_chunk, kv_splits, max_prompt)
             rc = self._lib.treekv_init_ex(C.byref(self._h), C.byref(cfg))
         if rc != TREEKV_OK:
             self._h = C.c_void_p()
@@ -166,6 +169,13 @@ class TreeKV:
         self._check(self._lib.treekv_prefill_chunk(self._h, _ptr(Q), _ptr(K), _ptr(V), int(length), _ptr(out),
                                                    _ptr(retained), _ptr(n_retained), _ptr(evicted), self._stream()),
                     "treekv_prefill_chunk")
+
+    def prefill_prompt(self, Qw, K, V, length, block, retained, n_retained=None, evicted_blocks=None,
+                       token_scores=None):
+        self._check(self._lib.treekv_prefill_prompt(self._h, _ptr(Qw), _ptr(K), _ptr(V), int(length), int(block),
+                                                    _ptr(retained), _ptr(n_retained), _ptr(evicted_blocks),
+                                                    _ptr(token_scores), self._stream()),
+                    "treekv_prefill_prompt")
 
     def scores(self, scores=None):
         c = self.cfg

@@ -47,6 +47,11 @@ size_t carve(Params& p, char* base) {
   p.pf_snew = (float*)take(U * (size_t)p.max_chunk * 4);
   p.pf_flag = (int*)take(U * ext * 4);
   p.pf_list = (int*)take(U * ext * 4);
+  if (p.max_prompt > 0) {
+    p.pp_tok = (float*)take(U * (size_t)p.max_prompt * 4);
+    p.pp_stat = (float*)take(U * (size_t)PROMPT_MAX_SPLITS * 128 * 2 * 4);
+    p.pp_kept = (int*)take(U * (size_t)p.budget * 4);
+  }
   return off;
 }
 
@@ -180,6 +185,8 @@ int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg_in) {
   if ((long long)c.budget > (1 << 24) || (long long)c.batch * c.kv_heads > 65535) return TREEKV_EUNSUPPORTED;
   if (c.max_chunk == 0) c.max_chunk = 512;
   if (c.max_chunk > 4096) return TREEKV_EUNSUPPORTED;
+  if (c.max_prompt < 0) return TREEKV_EINVAL;
+  if (c.max_prompt > (1 << 24)) return TREEKV_EUNSUPPORTED;
   if (c.softmax_scale == 0.0f) c.softmax_scale = 1.0f / sqrtf((float)c.head_dim);
   if (c.kv_splits == 0) c.kv_splits = pick_splits(c);
 
@@ -192,6 +199,7 @@ int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg_in) {
   p.m = c.budget - c.n_sink - c.n_recent;
   p.B = c.batch; p.H = c.q_heads; p.Hkv = c.kv_heads; p.G = G; p.D = c.head_dim; p.U = c.batch * c.kv_heads;
   p.dtype = c.dtype; p.flags = c.flags; p.nsplit = c.kv_splits; p.max_chunk = c.max_chunk;
+  p.max_prompt = c.max_prompt;
   p.scale_log2e = c.softmax_scale * 1.4426950408889634f;
   // a unit whose logits do not fit one workgroup's LDS is split further
   for (;;) {
@@ -259,6 +267,23 @@ int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const vo
   if (!ctx->bound) return TREEKV_ENOWS;
   return record_hip(ctx, tkv::launch_prefill(ctx->p, Q, K, V, len, (float*)out, retained, n_retained, evicted,
                                              (hipStream_t)stream));
+}
+
+int treekv_prefill_prompt(treekv_ctx* ctx, const void* Qw, const void* K, const void* V, int len, int block,
+                          int32_t* retained, int32_t* n_retained, int32_t* evicted_blocks, float* token_scores,
+                          void* stream) {
+  if (!ctx || !Qw || !K || !V || !retained) return TREEKV_EINVAL;
+  const treekv_config& c = ctx->cfg;
+  if (block < 1 || len < block || len > c.max_prompt || len % block != 0 || c.budget % block != 0) return TREEKV_EINVAL;
+  const int cb = c.budget / block, sink_b = (c.n_sink + block - 1) / block, recent_b = (c.n_recent + block - 1) / block;
+  if (cb - sink_b - recent_b < 1) return TREEKV_EINVAL;
+  if (!aligned16(Qw) || !aligned16(K) || !aligned16(V)) return TREEKV_EINVAL;
+  if (!ctx->bound) return TREEKV_ENOWS;
+  // the window's queries of one KV head's group are the rows of one matrix operand set
+  if (block * (c.q_heads / c.kv_heads) > 128) return TREEKV_EUNSUPPORTED;
+  if (tkv::prompt_blocks_lds(len, block, cb, sink_b, recent_b) > 150 * 1024) return TREEKV_EUNSUPPORTED;
+  return record_hip(ctx, tkv::launch_prompt(ctx->p, Qw, K, V, len, block, retained, n_retained, evicted_blocks,
+                                            token_scores, (hipStream_t)stream));
 }
 
 int treekv_scores(treekv_ctx* ctx, float* scores, void* stream) {

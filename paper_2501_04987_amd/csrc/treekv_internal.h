@@ -52,7 +52,13 @@ struct Params {
   float* pf_snew;           // [U][max_chunk] accumulated S of the chunk's tokens
   int* pf_flag;             // [U][cap + max_chunk] freed slots / dead chunk tokens, then destinations
   int* pf_list;             // [U][cap + max_chunk] free slots in ascending order
+  // one-shot prompt compression scratch
+  int max_prompt;           // longest prompt treekv_prefill_prompt accepts (0: none)
+  float* pp_tok;            // [U][T] token scores of the prompt in flight (dense, stride T <= max_prompt)
+  float* pp_stat;           // [U][PROMPT_MAX_SPLITS][128][2] per slice and window query row: max, sum
+  int* pp_kept;             // [U][budget] kept blocks, ascending
 };
+constexpr int PROMPT_MAX_SPLITS = 64;
 
 // true if the decode kernels of the current shape (p.nsplit, p.rows_per_split) fit in LDS
 bool decode_shape_fits(const Params& p);
@@ -61,6 +67,9 @@ int launch_decode(const Params& p, const void* q, const void* k, const void* v, 
                   int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s);
 int launch_prefill(const Params& p, const void* Q, const void* K, const void* V, int len, float* out,
                    int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s);
+int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V, int T, int b, int32_t* retained,
+                  int32_t* n_retained, int32_t* evicted_blocks, float* token_scores, hipStream_t s);
+size_t prompt_blocks_lds(int T, int b, int cb, int sink_b, int recent_b);
 int launch_scores(const Params& p, float* scores, hipStream_t s);
 int launch_gather_kv(const Params& p, void* K_out, void* V_out, hipStream_t s);
 

@@ -1,0 +1,427 @@
+// TreeKV one-shot prompt compression on gfx950 (Section 4.2, "Prefilling Stage").
+//
+// The prompt is cut into blocks of b tokens.  The queries of the last block (the observation window)
+// attend the whole prompt causally; a token's importance is its attention weight averaged over the
+// window queries that see it (Algorithm 1's S / C restricted to those queries, summed over the query
+// heads of the group); a block's importance is the mean over its b tokens; Algorithm 1 (lines 4-5,
+// 9-17) then runs with blocks in the place of tokens and the block scores frozen.  The kept blocks'
+// rows become the cache and decoding takes over from there.
+//
+// Four launches:
+//   stats    grid (splits, units): every workgroup streams its slice of the prompt's keys once and
+//            leaves, per window query, the (max, sum) of the scaled logits it saw.
+//   scores   same grid: merges the slices' (max, sum), streams the same keys again, turns logits into
+//            probabilities and adds them up per key over the window queries: the token scores.
+//   blocks   grid (units): block means, then Algorithm 1 over blocks.  With frozen scores the scopes of
+//            one pass of idx over the tree region are disjoint pairs of the sequence at the pass's
+//            start followed by the blocks that enter during the pass, so a pass is one parallel step.
+//   handoff  grid (row groups, units): copies the kept rows into slots 0.., and writes the scores, the
+//            order arrays, the bookkeeping words and the retained list that decoding starts from.
+//
+// Both streaming kernels are bound by the read of K (twice 2*T*d bytes per unit): the logits of b queries
+// against T keys are [b x d].[d x T], a contraction with b*G <= 128 rows, done on the matrix pipe with
+// the keys read straight from global memory in operand order (S^T = K Q^T, 16 keys x 32 dims per
+// instruction; the window queries sit in registers as the other operand), so the vector ALU is left with
+// one exponential per logit.
+
+#include "treekv_internal.h"
+
+namespace tkv {
+
+namespace {
+
+constexpr int PP_THREADS = 512;
+constexpr int PP_WAVES = PP_THREADS / 64;
+constexpr int PP_TILE = 32;                      // keys per wave iteration (two operand blocks of 16)
+constexpr int PP_STEP = PP_WAVES * PP_TILE;
+constexpr float NEG_BIG = -1.0e30f;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+__device__ inline f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+template <int CTRL>
+__device__ inline float dpp_add(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+  return v + __int_as_float(moved);
+}
+// Sum over the 16 lanes of a DPP row; every lane gets the total.
+__device__ inline float row16_sum(float v) {
+  v = dpp_add<0x128>(v);
+  v = dpp_add<0x124>(v);
+  v = dpp_add<0x122>(v);
+  v = dpp_add<0x121>(v);
+  return v;
+}
+
+// What the two streaming kernels share: the window queries as MFMA operands, the slice of keys a
+// workgroup owns, and the loop that turns 32 keys into NB x 2 accumulators of scaled logits.
+//   query row qr = i * G + g (window query i, head g of the group), padded with zero rows to NB * 16;
+//   row qr sees the keys below T - W + i + 1.
+template <int D, int NB>
+struct PromptStream {
+  static constexpr int KS = D / 32;
+  uint4 qa[NB][KS];
+  int lim[NB];                 // first key this lane's query of block nb does not see, capped at the slice's end
+  const uint16_t* Ku;          // key 0 of the unit
+  size_t row_stride;           // elements between consecutive keys of the unit
+  int begin, end, T;
+  int lane, wave, lr, q4;
+
+  __device__ inline void init(const Params& p, const uint16_t* Qw, const uint16_t* K, int T_, int W, int unit,
+                              int split, int rows_per_split) {
+    const int tid = threadIdx.x;
+    lane = tid & 63; wave = tid >> 6; lr = lane & 15; q4 = lane >> 4;
+    T = T_;
+    const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+    Ku = K + ((size_t)b * T * p.Hkv + kvh) * D;
+    row_stride = (size_t)p.Hkv * D;
+    begin = split * rows_per_split;
+    end = min(T, begin + rows_per_split);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int qr = nb * 16 + lr;
+      const bool live = qr < W * p.G;
+      const int i = qr / p.G, g = qr % p.G;
+      lim[nb] = live ? min(end, T - W + i + 1) : 0;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        qa[nb][ks] = make_uint4(0, 0, 0, 0);
+        if (live)
+          qa[nb][ks] = *reinterpret_cast<const uint4*>(Qw + (((size_t)b * W + i) * p.H + (size_t)kvh * p.G + g) * D + ks * 32 + q4 * 8);
+      }
+    }
+  }
+  // one operand block: keys base + lr (clamped into the prompt), this lane's 8 dims of every k-step
+  __device__ inline void load_block(uint4 (&k)[KS], int base) const {
+    const uint16_t* r = Ku + (size_t)min(base + lr, T - 1) * row_stride + q4 * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) k[ks] = *reinterpret_cast<const uint4*>(r + ks * 32);
+  }
+  // scaled-logit accumulators of one operand block: acc[nb][i] = <key base + q4*4 + i, query nb*16 + lr>
+  __device__ inline void logits(const uint4 (&k)[KS], f32x4_t (&acc)[NB]) const {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) acc[nb] = mfma16(k[ks], qa[nb][ks], acc[nb]);
+    }
+  }
+};
+
+// ---------------------------------------------------------------------------------------------
+// stats: per (unit, slice, query row) the maximum and the sum of exp2(logit - maximum) over the slice
+// ---------------------------------------------------------------------------------------------
+template <int D, int NB>
+__global__ __launch_bounds__(PP_THREADS) void prompt_stats_kernel(Params p, const uint16_t* __restrict__ Qw,
+                                                                  const uint16_t* __restrict__ K, int T, int W,
+                                                                  int rows_per_split, int nsplit) {
+  constexpr int KS = D / 32;
+  __shared__ float sm_m[PP_WAVES][NB * 16], sm_l[PP_WAVES][NB * 16];
+  PromptStream<D, NB> st;
+  const int split = blockIdx.x, unit = blockIdx.y;
+  st.init(p, Qw, K, T, W, unit, split, rows_per_split);
+  const float sc = p.scale_log2e;
+  const int lim_all = min(st.end, T - W + 1);      // every query sees the keys below this
+
+  float m_run[NB], l_run[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) { m_run[nb] = NEG_BIG; l_run[nb] = 0.f; }
+
+  uint4 k0[KS], k1[KS];
+  int base = st.begin + st.wave * PP_TILE;
+  if (base < st.end) { st.load_block(k0, base); st.load_block(k1, base + 16); }
+  for (; base < st.end; base += PP_STEP) {
+    const int nb_base = base + PP_STEP;
+    const bool ragged = base + PP_TILE > lim_all;   // wave uniform: some query does not see some key of the tile
+    // one operand block of 16 keys at a time: its accumulators are consumed before the next block's exist
+    auto block = [&](uint4 (&k)[KS], int h) {
+      f32x4_t a[NB];
+      st.logits(k, a);
+      if (nb_base < st.end) st.load_block(k, nb_base + h * 16);     // the next tile's keys behind this block's softmax
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        float s[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          s[i] = a[nb][i] * sc;
+          if (ragged) s[i] = (base + h * 16 + st.q4 * 4 + i < st.lim[nb]) ? s[i] : NEG_BIG;
+        }
+        const float mx = fmaxf(fmaxf(m_run[nb], fmaxf(s[0], s[1])), fmaxf(s[2], s[3]));
+        float add = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float pe = fast_exp2(s[i] - mx);
+          if (ragged) pe = s[i] > 0.5f * NEG_BIG ? pe : 0.f;
+          add += pe;
+        }
+        l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - mx) + add;
+        m_run[nb] = mx;
+      }
+    };
+    block(k0, 0);
+    block(k1, 1);
+  }
+  // the four lane groups of a wave hold different keys of the same query; then the waves
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+    for (int off = 16; off < 64; off <<= 1) {
+      const float mo = __shfl_xor(m_run[nb], off, 64), lo = __shfl_xor(l_run[nb], off, 64);
+      const float mx = fmaxf(m_run[nb], mo);
+      l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - mx) + lo * fast_exp2(mo - mx);
+      m_run[nb] = mx;
+    }
+    if (st.q4 == 0) { sm_m[st.wave][nb * 16 + st.lr] = m_run[nb]; sm_l[st.wave][nb * 16 + st.lr] = l_run[nb]; }
+  }
+  __syncthreads();
+  const int tid = threadIdx.x;
+  if (tid < NB * 16) {
+    float mx = NEG_BIG, l = 0.f;
+#pragma unroll
+    for (int w = 0; w < PP_WAVES; ++w) mx = fmaxf(mx, sm_m[w][tid]);
+#pragma unroll
+    for (int w = 0; w < PP_WAVES; ++w) l += sm_l[w][tid] * fast_exp2(sm_m[w][tid] - mx);
+    float* dst = p.pp_stat + (((size_t)unit * nsplit + split) * 128 + tid) * 2;
+    dst[0] = mx; dst[1] = l;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// scores: token score = (sum over the window queries that see the key of its probability) / (their number)
+// ---------------------------------------------------------------------------------------------
+template <int D, int NB>
+__global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, const uint16_t* __restrict__ Qw,
+                                                                   const uint16_t* __restrict__ K, int T, int W,
+                                                                   int rows_per_split, int nsplit) {
+  constexpr int KS = D / 32;
+  __shared__ float sm_M[NB * 16], sm_iL[NB * 16];
+  PromptStream<D, NB> st;
+  const int split = blockIdx.x, unit = blockIdx.y, tid = threadIdx.x;
+  st.init(p, Qw, K, T, W, unit, split, rows_per_split);
+  const float sc = p.scale_log2e;
+  const int lim_all = min(st.end, T - W + 1);
+
+  uint4 k0[KS], k1[KS];
+  int base = st.begin + st.wave * PP_TILE;
+  if (base < st.end) { st.load_block(k0, base); st.load_block(k1, base + 16); }
+
+  if (tid < NB * 16) {                 // the slices' (max, sum) of this query row -> the row's max and 1 / sum
+    const float* src = p.pp_stat + ((size_t)unit * nsplit * 128 + tid) * 2;
+    float mx = NEG_BIG, l = 0.f;
+    for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, src[(size_t)s * 256]);
+    for (int s = 0; s < nsplit; ++s) l += src[(size_t)s * 256 + 1] * fast_exp2(src[(size_t)s * 256] - mx);
+    sm_M[tid] = mx;
+    sm_iL[tid] = (tid < W * p.G && l > 0.f) ? 1.0f / l : 0.f;      // padding rows add nothing
+  }
+  __syncthreads();
+  float Mq[NB], iLq[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) { Mq[nb] = sm_M[nb * 16 + st.lr]; iLq[nb] = sm_iL[nb * 16 + st.lr]; }
+
+  float* tok = p.pp_tok + (size_t)unit * T;
+  for (; base < st.end; base += PP_STEP) {
+    const int nb_base = base + PP_STEP;
+    const bool ragged = base + PP_TILE > lim_all;
+    auto block = [&](uint4 (&k)[KS], int h) {
+      f32x4_t a[NB];
+      st.logits(k, a);
+      if (nb_base < st.end) st.load_block(k, nb_base + h * 16);
+      float col[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float pe = fast_exp2(a[nb][i] * sc - Mq[nb]) * iLq[nb];
+          if (ragged) pe = (base + h * 16 + st.q4 * 4 + i < st.lim[nb]) ? pe : 0.f;
+          col[i] += pe;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) col[i] = row16_sum(col[i]);
+      if (st.lr == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int j = base + h * 16 + st.q4 * 4 + i;
+          if (j < st.end) tok[j] = col[i] / (float)min(W, T - j);
+        }
+      }
+    };
+    block(k0, 0);
+    block(k1, 1);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// blocks: block means, Algorithm 1 over blocks with frozen scores, the kept blocks in ascending order
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prompt_blocks_kernel(Params p, int T, int b, int cb, int sink_b, int recent_b,
+                                                            int32_t* __restrict__ evicted_blocks) {
+  extern __shared__ __attribute__((aligned(16))) float pb_smem[];
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  const int N = T / b, m_b = cb - sink_b - recent_b;
+  float* beta = pb_smem;                                  // [N]
+  int* seq_a = reinterpret_cast<int*>(pb_smem + N);       // [2 * m_b] the tree region, then the pass's newcomers
+  int* seq_b = seq_a + 2 * m_b;
+  const float* tok = p.pp_tok + (size_t)unit * T;
+  int* kept = p.pp_kept + (size_t)unit * p.budget;
+  int32_t* evu = evicted_blocks ? evicted_blocks + (size_t)unit * N : nullptr;
+
+  for (int k = tid; k < N; k += 256) {
+    float acc = 0.f;
+    for (int x = 0; x < b; ++x) acc += tok[(size_t)k * b + x];
+    beta[k] = acc / (float)b;
+    if (evu && k < cb) evu[k] = -1;                       // blocks that arrive while the cache still has room
+  }
+  if (N <= cb) {                                          // nothing to evict
+    for (int k = tid; k < N; k += 256) kept[k] = k;
+    return;
+  }
+  for (int k = tid; k < m_b; k += 256) seq_a[k] = sink_b + k;
+  __syncthreads();
+  // the block that enters the tree region at eviction step e is block sink_b + m_b + e (the one that just
+  // left the recent window, or the arriving block itself without one); the block arriving then is cb + e
+  const int n_ev = N - cb;
+  int* cur = seq_a;
+  int* nxt = seq_b;
+  for (int e0 = 0; e0 < n_ev; e0 += m_b) {
+    const int cnt = min(m_b, n_ev - e0);
+    for (int x = tid; x < cnt; x += 256) cur[m_b + x] = sink_b + m_b + e0 + x;
+    __syncthreads();
+    for (int k = tid; k < m_b; k += 256) {
+      int v;
+      if (k < cnt) {
+        const int l = cur[2 * k], r = cur[2 * k + 1];
+        const bool drop_right = (p.flags & TREEKV_KEEP_LEFT) || (beta[l] > beta[r]);   // a tie evicts the left block
+        v = drop_right ? l : r;
+        if (evu) evu[cb + e0 + k] = drop_right ? r : l;
+      } else {
+        v = cur[k + cnt];
+      }
+      nxt[k] = v;
+    }
+    __syncthreads();
+    int* t = cur; cur = nxt; nxt = t;
+  }
+  for (int i = tid; i < cb; i += 256) {
+    int v;
+    if (i < sink_b) v = i;
+    else if (i < sink_b + m_b) v = cur[i - sink_b];
+    else v = N - recent_b + (i - sink_b - m_b);
+    kept[i] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// handoff: the kept rows become slots 0 .. n-1 (logical order = slot order), and decoding's state is set
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prompt_handoff_kernel(Params p, const uint4* __restrict__ Kp,
+                                                             const uint4* __restrict__ Vp, int T, int b, int n,
+                                                             int row_vec, int32_t* __restrict__ retained,
+                                                             int32_t* __restrict__ n_retained) {
+  const int per_wg = 256 / row_vec;
+  const int unit = blockIdx.y, tid = threadIdx.x;
+  const int i = blockIdx.x * per_wg + tid / row_vec, e = tid % row_vec;
+  const int kvh = unit % p.Hkv, bq = unit / p.Hkv;
+  if (blockIdx.x == 0) {
+    int* meta = p.meta + (size_t)unit * META_STRIDE;
+    if (tid == 0) {
+      meta[META_N] = n;
+      meta[META_FREE] = n;             // n < budget: the next slot; n == budget: the spare slot
+      meta[META_J] = 0;                // token-level eviction starts at the first scope
+      meta[META_RHEAD] = 0;
+      meta[META_T] = T;
+      if (n_retained) n_retained[unit] = n;
+    }
+    int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
+    for (int x = tid; x < p.n_recent; x += 256) Ru[x] = p.n_sink + p.m + x;
+    int* Eu = p.E + (size_t)unit * 2 * p.m;
+    int* PEu = p.PE + (size_t)unit * 2 * p.m;
+    for (int k = p.m + tid; k < 2 * p.m; k += 256) Eu[k] = PEu[k] = 0;
+  }
+  if (i >= p.budget) return;
+  int pos = -1;
+  if (i < n) {
+    const int kb = p.pp_kept[(size_t)unit * p.budget + i / b];
+    pos = kb * b + i % b;
+    const size_t src = (((size_t)bq * T + pos) * p.Hkv + kvh) * row_vec + e;
+    const size_t dst = ((size_t)unit * p.cap + i) * row_vec + e;
+    reinterpret_cast<uint4*>(p.K)[dst] = Kp[src];
+    reinterpret_cast<uint4*>(p.V)[dst] = Vp[src];
+  }
+  if (e != 0) return;
+  retained[(size_t)unit * p.budget + i] = pos;
+  // Sbar stays the window average: C = T - pos queries of the prompt could attend the token, S = Sbar * C
+  if (i < n) p.S[(size_t)unit * p.cap + i] = p.pp_tok[(size_t)unit * T + pos] * (float)(T - pos);
+  const int k = i - p.n_sink;
+  if (k >= 0 && k < p.m) {
+    p.E[(size_t)unit * 2 * p.m + k] = i;
+    p.PE[(size_t)unit * 2 * p.m + k] = i < n ? pos : i;
+  }
+}
+
+template <int D, int NB>
+void launch_streams(const Params& p, const uint16_t* Qw, const uint16_t* K, int T, int W, int rows_per_split,
+                    int nsplit, hipStream_t s) {
+  hipLaunchKernelGGL((prompt_stats_kernel<D, NB>), dim3(nsplit, p.U), dim3(PP_THREADS), 0, s, p, Qw, K, T, W,
+                     rows_per_split, nsplit);
+  hipLaunchKernelGGL((prompt_scores_kernel<D, NB>), dim3(nsplit, p.U), dim3(PP_THREADS), 0, s, p, Qw, K, T, W,
+                     rows_per_split, nsplit);
+}
+
+template <int D>
+void launch_streams_d(const Params& p, const uint16_t* Qw, const uint16_t* K, int T, int W, int rows_per_split,
+                      int nsplit, hipStream_t s) {
+  const int nb = (W * p.G + 15) / 16;
+  if (nb <= 2) launch_streams<D, 2>(p, Qw, K, T, W, rows_per_split, nsplit, s);
+  else if (nb <= 4) launch_streams<D, 4>(p, Qw, K, T, W, rows_per_split, nsplit, s);
+  else launch_streams<D, 8>(p, Qw, K, T, W, rows_per_split, nsplit, s);
+}
+
+}  // namespace
+
+// Slices per unit: enough workgroups to fill the chip twice over, a slice a multiple of what a workgroup
+// takes per iteration, at most PROMPT_MAX_SPLITS of them.
+int prompt_splits(const Params& p, int T, int* rows_per_split) {
+  int ns = (512 + p.U - 1) / p.U;
+  const int by_len = (T + PP_STEP - 1) / PP_STEP;
+  if (ns > by_len) ns = by_len;
+  if (ns > PROMPT_MAX_SPLITS) ns = PROMPT_MAX_SPLITS;
+  if (ns < 1) ns = 1;
+  int rows = ((T + ns - 1) / ns + PP_STEP - 1) / PP_STEP * PP_STEP;
+  ns = (T + rows - 1) / rows;
+  *rows_per_split = rows;
+  return ns;
+}
+
+size_t prompt_blocks_lds(int T, int b, int cb, int sink_b, int recent_b) {
+  return ((size_t)(T / b) + 4 * (size_t)(cb - sink_b - recent_b)) * 4;
+}
+
+int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V, int T, int b, int32_t* retained,
+                  int32_t* n_retained, int32_t* evicted_blocks, float* token_scores, hipStream_t s) {
+  if (p.dtype != TREEKV_BF16) return TREEKV_EUNSUPPORTED;      // the MFMA path is bf16
+  const int cb = p.budget / b, sink_b = (p.n_sink + b - 1) / b, recent_b = (p.n_recent + b - 1) / b;
+  int rows_per_split = 0;
+  const int nsplit = prompt_splits(p, T, &rows_per_split);
+  if (p.D == 128) launch_streams_d<128>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, s);
+  else launch_streams_d<64>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, s);
+  const size_t lds = prompt_blocks_lds(T, b, cb, sink_b, recent_b);
+  if (lds > 48 * 1024 &&
+      hipFuncSetAttribute((const void*)prompt_blocks_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    return TREEKV_EHIP;
+  hipLaunchKernelGGL(prompt_blocks_kernel, dim3(p.U), dim3(256), lds, s, p, T, b, cb, sink_b, recent_b, evicted_blocks);
+  const int row_vec = p.D * 2 / 16, per_wg = 256 / row_vec;
+  const int n = T < p.budget ? T : p.budget;
+  hipLaunchKernelGGL(prompt_handoff_kernel, dim3((p.budget + per_wg - 1) / per_wg, p.U), dim3(256), 0, s, p,
+                     (const uint4*)K, (const uint4*)V, T, b, n, row_vec, retained, n_retained);
+  if (token_scores &&
+      hipMemcpyAsync(token_scores, p.pp_tok, (size_t)p.U * T * sizeof(float), hipMemcpyDeviceToDevice, s) != hipSuccess)
+    return TREEKV_EHIP;
+  return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
+}
+
+}  // namespace tkv

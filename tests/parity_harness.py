@@ -131,11 +131,13 @@ def compare_scores(kv, results, dtype="bf16"):
 # --------------------------------------------------------------------------- #
 # mixed prefill / decode schedules
 # --------------------------------------------------------------------------- #
-def run_schedule(oracle, kv, Q, K, V, schedule, dtype="bf16", units=None, check_every_call=True):
+def run_schedule(oracle, kv, Q, K, V, schedule, dtype="bf16", units=None, check_every_call=True, streams=None,
+                 t_start=0):
     """Drive GPU and oracle through `schedule`, a list of chunk lengths (0 = one decode step).
 
     Q [T,B,H,d], K/V [T,B,Hkv,d]: float arrays of the values the GPU consumes, T = total tokens.
     After every call compares outputs, evicted positions (follow mode) and the retained list.
+    `streams` / `t_start`: continue from oracle streams (and a token offset) an earlier call left.
     """
     import torch
 
@@ -144,11 +146,13 @@ def run_schedule(oracle, kv, Q, K, V, schedule, dtype="bf16", units=None, check_
     if units is None:
         units = [(b, h) for b in range(c.batch) for h in range(c.kv_heads)]
     ocfg = oracle_cfg(kv)
-    streams = {u: oracle.OracleStream(ocfg["budget"], G, c.head_dim, n_sink=ocfg["n_sink"], n_recent=ocfg["n_recent"],
-                                      scale=ocfg["scale"], flags=ocfg["flags"]) for u in units}
+    if streams is None:
+        streams = {u: oracle.OracleStream(ocfg["budget"], G, c.head_dim, n_sink=ocfg["n_sink"],
+                                          n_recent=ocfg["n_recent"], scale=ocfg["scale"], flags=ocfg["flags"])
+                   for u in units}
     tol = TOL[dtype]
     Qd, Kd, Vd = to_device(Q, dtype), to_device(K, dtype), to_device(V, dtype)
-    t = 0
+    t = t_start
     stats = dict(flagged=0, decisions=0, max_err=0.0, calls=0)
     for L in schedule:
         if L == 0:
@@ -196,6 +200,72 @@ def run_schedule(oracle, kv, Q, K, V, schedule, dtype="bf16", units=None, check_
         t += n_tok
         stats["calls"] += 1
     stats["results"] = {u: dict(stream=streams[u]) for u in units}
+    return stats
+
+
+# --------------------------------------------------------------------------- #
+# one-shot prompt compression, then decoding
+# --------------------------------------------------------------------------- #
+def run_prompt(oracle, kv, Q, K, V, T, block, decode_steps, units=None, dtype="bf16"):
+    """Compress the first T tokens in one shot on both sides, compare, then decode `decode_steps` more tokens.
+
+    Q [T + decode_steps, B, H, d], K/V [.., B, Hkv, d]: float arrays of the values the GPU consumes.
+    Compared: the block evicted at every step (follow mode), every token's score, the retained list, the
+    averaged scores and the cache rows of the retained tokens, then every decode step as in run_schedule.
+    """
+    import torch
+
+    c = kv.cfg
+    G = c.q_heads // c.kv_heads
+    if units is None:
+        units = [(b, h) for b in range(c.batch) for h in range(c.kv_heads)]
+    ocfg = oracle_cfg(kv)
+    streams = {u: oracle.OracleStream(ocfg["budget"], G, c.head_dim, n_sink=ocfg["n_sink"], n_recent=ocfg["n_recent"],
+                                      scale=ocfg["scale"], flags=ocfg["flags"]) for u in units}
+    N = T // block
+    Qd, Kd, Vd = to_device(Q[:T], dtype), to_device(K[:T], dtype), to_device(V[:T], dtype)
+    qw = Qd[T - block:T].permute(1, 0, 2, 3).contiguous()          # [B, block, H, d]
+    kp = Kd.permute(1, 0, 2, 3).contiguous()                       # [B, T, Hkv, d]
+    vp = Vd.permute(1, 0, 2, 3).contiguous()
+    _, ret, nret, _ = kv.new_outputs()
+    evb = torch.empty(c.batch, c.kv_heads, N, dtype=torch.int32, device=kv.device)
+    tok = torch.empty(c.batch, c.kv_heads, T, dtype=torch.float32, device=kv.device)
+    kv.prefill_prompt(qw, kp, vp, T, block, ret, nret, evb, tok)
+    torch.cuda.synchronize()
+    ret_g, nret_g, evb_g, tok_g = ret.cpu().numpy(), nret.cpu().numpy(), evb.cpu().numpy(), tok.cpu().numpy()
+
+    def job(u):
+        b, h = u
+        return streams[u].prefill_prompt(Q[T - block:T, b, h * G:(h + 1) * G, :], K[:T, b, h, :], V[:T, b, h, :], block,
+                                         forced_blocks=evb_g[b, h], follow_thresh=FOLLOW_THRESH)
+
+    results = oracle.run_many(job, units, workers=min(len(units), os.cpu_count() or 1, 16))
+    stats = dict(flagged=0, decisions=0, tok_err=0.0)
+    for (b, h), res in zip(units, results):
+        where = f"prompt of {T} in blocks of {block}, unit {(b, h)}"
+        assert res["disagreed"] == 0, f"{where}: block evictions differ outside the near-tie margin"
+        np.testing.assert_array_equal(res["evicted_blocks"], evb_g[b, h], err_msg=where)
+        # both sides consume the same bf16 values; the scores differ by fp32 accumulation only
+        np.testing.assert_allclose(tok_g[b, h], res["token_scores"], rtol=2e-4, atol=1e-9, err_msg=where)
+        stats["tok_err"] = max(stats["tok_err"], float(np.abs(tok_g[b, h] / res["token_scores"] - 1).max()))
+        stats["flagged"] += res["adopted"]
+        stats["decisions"] += int(np.count_nonzero(res["evicted_blocks"] >= 0))
+        want = streams[(b, h)].retained()
+        assert nret_g[b, h] == len(want), where
+        assert np.array_equal(ret_g[b, h, :len(want)], want), f"{where}: retained set"
+        assert np.all(ret_g[b, h, len(want):] == -1)
+    res_map = {u: dict(stream=streams[u]) for u in units}
+    stats["score_err"] = compare_scores(kv, res_map, dtype)
+    Kc, Vc = kv.gather_kv()
+    torch.cuda.synchronize()
+    for (b, h) in units:
+        pos = streams[(b, h)].retained()
+        np.testing.assert_array_equal(Kc[b, h, :len(pos)].float().cpu().numpy(), K[pos, b, h])
+        np.testing.assert_array_equal(Vc[b, h, :len(pos)].float().cpu().numpy(), V[pos, b, h])
+    if decode_steps:
+        st = run_schedule(oracle, kv, Q, K, V, [0] * decode_steps, dtype=dtype, units=units, streams=streams, t_start=T)
+        stats["decode"] = st
+        stats["score_err_after"] = compare_scores(kv, st["results"], dtype)
     return stats
 
 

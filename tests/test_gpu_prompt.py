@@ -1,0 +1,115 @@
+"""GPU parity: one-shot block-level prompt compression (Section 4.2) through the C ABI against the CPU oracle,
+followed by decode steps that start from the state the call leaves."""
+import numpy as np
+import pytest
+
+from paper_2501_04987_amd import inputs
+from tests import parity_harness as ph
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2501_04987_amd import binding as b
+
+    b.load()
+    return b
+
+
+def _run(binding, oracle, *, T, block, steps, B, H, Hkv, d, budget, n_sink, n_recent, seed=0, flags=0, units=None,
+         kind="lowrank"):
+    Q, K, V = inputs.batch_streams(kind, seed, T + steps, B, Hkv, H // Hkv, d, dtype="bf16")
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=n_sink, n_recent=n_recent,
+                        flags=flags, max_prompt=T)
+    st = ph.run_prompt(oracle, kv, Q, K, V, T, block, steps, units=units)
+    assert st["flagged"] <= max(1, st["decisions"] // 200), st["flagged"]
+    print(f"  blocks evicted={st['decisions']} flagged={st['flagged']} token score rel err={st['tok_err']:.2e} "
+          f"score_err={st['score_err']:.2e}")
+    return kv, st
+
+
+def test_prompt_layout_ragged_slices(binding, oracle):
+    """37 blocks of 16 into 8 block slots (1 sink, 5 tree, 2 recent blocks); the prompt's 592 keys end inside a
+    workgroup iteration and inside a wave's tile; 40 decode steps wrap the recent ring."""
+    _run(binding, oracle, T=592, block=16, steps=40, B=1, H=2, Hkv=2, d=128, budget=128, n_sink=4, n_recent=20)
+
+
+def test_prompt_several_slices_and_batches(binding, oracle):
+    _run(binding, oracle, T=4096 + 64, block=32, steps=12, B=2, H=2, Hkv=2, d=128, budget=512, n_sink=4, n_recent=100,
+         seed=3)
+
+
+@pytest.mark.parametrize("G,d,block", [(4, 64, 8), (2, 128, 16), (8, 64, 16)])
+def test_prompt_grouped_queries(binding, oracle, G, d, block):
+    _run(binding, oracle, T=block * 61, block=block, steps=10, B=1, H=2 * G, Hkv=2, d=d, budget=block * 12, n_sink=3,
+         n_recent=block + 5, seed=5)
+
+
+def test_prompt_window_of_128(binding, oracle):
+    """block = 128: the window's 128 queries fill all eight operand blocks."""
+    _run(binding, oracle, T=128 * 21, block=128, steps=6, B=1, H=2, Hkv=2, d=128, budget=1024, n_sink=4, n_recent=200,
+         seed=6)
+
+
+def test_prompt_pure_algorithm1_single_token_blocks(binding, oracle):
+    """block = 1: Algorithm 1 over tokens with the last token's attention as frozen scores."""
+    _run(binding, oracle, T=301, block=1, steps=25, B=1, H=2, Hkv=2, d=64, budget=20, n_sink=0, n_recent=0, seed=7)
+
+
+def test_prompt_that_fits_keeps_everything(binding, oracle):
+    kv, st = _run(binding, oracle, T=160, block=32, steps=120, B=1, H=2, Hkv=2, d=128, budget=256, n_sink=4,
+                  n_recent=60, seed=8)
+    assert st["decisions"] == 0 and st["decode"]["decisions"] == 2 * (160 + 120 - 256)
+
+
+def test_prompt_keep_left(binding, oracle):
+    _run(binding, oracle, T=16 * 50, block=16, steps=8, B=1, H=2, Hkv=2, d=128, budget=160, n_sink=0, n_recent=16,
+         flags=binding.TREEKV_KEEP_LEFT, seed=9)
+
+
+def test_prompt_replaces_earlier_state(binding, oracle):
+    """The call starts from scratch whatever the context held before."""
+    import torch
+
+    T, block, B, H, d, budget = 640, 32, 1, 2, 128, 192
+    Q, K, V = inputs.batch_streams("lowrank", 11, T + 4, B, H, 1, d, dtype="bf16")
+    kv = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=4, n_recent=40, max_prompt=T)
+    out, ret, nret, ev = kv.new_outputs()
+    junk = torch.randn(B, H, d, device="cuda").to(torch.bfloat16)
+    for _ in range(budget + 30):
+        kv.decode_step(junk, junk, junk, out, ret, nret, ev)
+    st = ph.run_prompt(oracle, kv, Q, K, V, T, block, 4)
+    assert st["decisions"] == H * (T // block - budget // block)
+
+
+def test_prompt_argument_errors(binding):
+    import torch
+
+    kv = binding.TreeKV(64, 2, 128, kv_heads=2, n_sink=4, n_recent=20, max_prompt=256)
+    _, ret, nret, _ = kv.new_outputs()
+    x = torch.zeros(1, 512, 2, 128, dtype=torch.bfloat16, device="cuda")
+    for T, block in [(250, 16), (512, 16), (256, 24), (256, 0), (8, 16), (256, 32)]:   # last: no tree block left
+        with pytest.raises(binding.TreeKVError) as e:
+            kv.prefill_prompt(x, x, x, T, block, ret, nret)
+        assert e.value.status == binding.TREEKV_EINVAL, (T, block)
+    none = binding.TreeKV(64, 2, 128, kv_heads=2, n_sink=4, n_recent=20)
+    with pytest.raises(binding.TreeKVError):
+        none.prefill_prompt(x, x, x, 256, 16, ret, nret)                              # max_prompt = 0
+    wide = binding.TreeKV(256, 8, 64, kv_heads=2, n_sink=0, n_recent=0, max_prompt=512)
+    _, ret, nret, _ = wide.new_outputs()
+    x = torch.zeros(1, 512, 8, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.TreeKVError) as e:
+        wide.prefill_prompt(x, x, x, 512, 64, ret, nret)                              # 64 queries x 4 heads > 128 rows
+    assert e.value.status == binding.TREEKV_EUNSUPPORTED
+
+
+def test_prompt_llama_shaped_sampled(binding, oracle):
+    """32 heads x 128, bf16, budget 2048 (4 + 1024 + 1020), a prompt of 16384 tokens in blocks of 64, then 16 decode
+    steps; the GPU runs all heads, the oracle audits 4 of them."""
+    kv, st = _run(binding, oracle, T=16384, block=64, steps=16, B=1, H=32, Hkv=32, d=128, budget=2048, n_sink=4,
+                  n_recent=1020, units=[(0, 0), (0, 9), (0, 20), (0, 31)], seed=0)
+    assert st["decisions"] == 4 * (16384 // 64 - 2048 // 64)
