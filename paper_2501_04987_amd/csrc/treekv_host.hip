@@ -49,6 +49,7 @@ size_t carve(Params& p, char* base) {
   p.pf_list = (int*)take(U * ext * 4);
   if (p.max_prompt > 0) {
     p.pp_tok = (float*)take(U * (size_t)p.max_prompt * 4);
+    p.pp_beta = (float*)take(U * (size_t)p.max_prompt * 4);
     p.pp_stat = (float*)take(U * (size_t)PROMPT_MAX_SPLITS * 128 * 2 * 4);
     p.pp_kept = (int*)take(U * (size_t)p.budget * 4);
   }

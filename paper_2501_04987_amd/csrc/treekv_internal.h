@@ -55,6 +55,7 @@ struct Params {
   // one-shot prompt compression scratch
   int max_prompt;           // longest prompt treekv_prefill_prompt accepts (0: none)
   float* pp_tok;            // [U][T] token scores of the prompt in flight (dense, stride T <= max_prompt)
+  float* pp_beta;           // [U][T / block] block scores of the prompt in flight
   float* pp_stat;           // [U][PROMPT_MAX_SPLITS][128][2] per slice and window query row: max, sum
   int* pp_kept;             // [U][budget] kept blocks, ascending
 };

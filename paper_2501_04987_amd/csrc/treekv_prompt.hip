@@ -36,6 +36,8 @@ constexpr int PP_TILE = 32;                      // keys per wave iteration (two
 constexpr int PP_STEP = PP_WAVES * PP_TILE;
 constexpr float NEG_BIG = -1.0e30f;
 
+template <bool B> struct BoolTag { static constexpr bool value = B; };
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
@@ -131,39 +133,48 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_stats_kernel(Params p, cons
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) { m_run[nb] = NEG_BIG; l_run[nb] = 0.f; }
 
-  uint4 k0[KS], k1[KS];
+  // two tiles of 32 keys in flight per wave: (k0, k1) and (k2, k3); a block is requested again, two tiles on,
+  // as soon as its logits are out
+  // (one tile with all eight operand blocks of queries: the registers do not hold more)
+  constexpr int AHEAD = NB < 8 ? 2 : 1;
+  uint4 k0[KS], k1[KS], k2[KS], k3[KS];
   int base = st.begin + st.wave * PP_TILE;
   if (base < st.end) { st.load_block(k0, base); st.load_block(k1, base + 16); }
-  for (; base < st.end; base += PP_STEP) {
-    const int nb_base = base + PP_STEP;
-    const bool ragged = base + PP_TILE > lim_all;   // wave uniform: some query does not see some key of the tile
-    // one operand block of 16 keys at a time: its accumulators are consumed before the next block's exist
-    auto block = [&](uint4 (&k)[KS], int h) {
-      f32x4_t a[NB];
-      st.logits(k, a);
-      if (nb_base < st.end) st.load_block(k, nb_base + h * 16);     // the next tile's keys behind this block's softmax
+  if (AHEAD == 2 && base + PP_STEP < st.end) { st.load_block(k2, base + PP_STEP); st.load_block(k3, base + PP_STEP + 16); }
+  // One operand block of 16 keys at a time: its accumulators are consumed before the next block's exist.
+  // `ragged` (a type, so that the common case carries no masking code): some query does not see some key.
+  auto block = [&](auto ragged, uint4 (&k)[KS], int tile, int h) {
+    constexpr bool RAGGED = decltype(ragged)::value;
+    f32x4_t a[NB];
+    st.logits(k, a);
+    if (tile + AHEAD * PP_STEP < st.end) st.load_block(k, tile + AHEAD * PP_STEP + h * 16);
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        float s[4];
+    for (int nb = 0; nb < NB; ++nb) {
+      float r[4];                                    // raw logits; the scale is positive, so max commutes with it
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          s[i] = a[nb][i] * sc;
-          if (ragged) s[i] = (base + h * 16 + st.q4 * 4 + i < st.lim[nb]) ? s[i] : NEG_BIG;
-        }
-        const float mx = fmaxf(fmaxf(m_run[nb], fmaxf(s[0], s[1])), fmaxf(s[2], s[3]));
-        float add = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float pe = fast_exp2(s[i] - mx);
-          if (ragged) pe = s[i] > 0.5f * NEG_BIG ? pe : 0.f;
-          add += pe;
-        }
-        l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - mx) + add;
-        m_run[nb] = mx;
+      for (int i = 0; i < 4; ++i) {
+        r[i] = a[nb][i];
+        if (RAGGED) r[i] = (tile + h * 16 + st.q4 * 4 + i < st.lim[nb]) ? r[i] : NEG_BIG;
       }
-    };
-    block(k0, 0);
-    block(k1, 1);
+      const float mx = fmaxf(m_run[nb], fmaxf(fmaxf(r[0], r[1]), fmaxf(r[2], r[3])) * sc);
+      float add = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float pe = fast_exp2(fmaf(r[i], sc, -mx));
+        if (RAGGED) pe = r[i] > 0.5f * NEG_BIG ? pe : 0.f;
+        add += pe;
+      }
+      l_run[nb] = fmaf(l_run[nb], fast_exp2(m_run[nb] - mx), add);
+      m_run[nb] = mx;
+    }
+  };
+  auto tile = [&](uint4 (&ka)[KS], uint4 (&kb)[KS], int t) {
+    if (t + PP_TILE > lim_all) { block(BoolTag<true>{}, ka, t, 0); block(BoolTag<true>{}, kb, t, 1); }
+    else { block(BoolTag<false>{}, ka, t, 0); block(BoolTag<false>{}, kb, t, 1); }
+  };
+  for (; base < st.end; base += AHEAD * PP_STEP) {
+    tile(k0, k1, base);
+    if (AHEAD == 2 && base + PP_STEP < st.end) tile(k2, k3, base + PP_STEP);
   }
   // the four lane groups of a wave hold different keys of the same query; then the waves
 #pragma unroll
@@ -196,62 +207,82 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_stats_kernel(Params p, cons
 template <int D, int NB>
 __global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, const uint16_t* __restrict__ Qw,
                                                                    const uint16_t* __restrict__ K, int T, int W,
-                                                                   int rows_per_split, int nsplit) {
+                                                                   int rows_per_split, int nsplit, int block_means) {
   constexpr int KS = D / 32;
-  __shared__ float sm_M[NB * 16], sm_iL[NB * 16];
+  __shared__ float sm_ML[NB * 16];
+  extern __shared__ __attribute__((aligned(16))) float sm_tok[];     // [rows_per_split] when block_means
   PromptStream<D, NB> st;
   const int split = blockIdx.x, unit = blockIdx.y, tid = threadIdx.x;
   st.init(p, Qw, K, T, W, unit, split, rows_per_split);
   const float sc = p.scale_log2e;
   const int lim_all = min(st.end, T - W + 1);
 
+  // This pass walks its slice from the end to the start: what the first pass read last is what the
+  // memory-side cache still holds, so most of a prompt that is not much larger than that cache is not
+  // fetched from HBM a second time.
   uint4 k0[KS], k1[KS];
-  int base = st.begin + st.wave * PP_TILE;
-  if (base < st.end) { st.load_block(k0, base); st.load_block(k1, base + 16); }
+  const int first = st.begin + st.wave * PP_TILE;
+  int base = first < st.end ? first + (st.end - 1 - first) / PP_STEP * PP_STEP : first - PP_STEP;
+  if (base >= first) { st.load_block(k0, base); st.load_block(k1, base + 16); }
 
   if (tid < NB * 16) {                 // the slices' (max, sum) of this query row -> the row's max and 1 / sum
     const float* src = p.pp_stat + ((size_t)unit * nsplit * 128 + tid) * 2;
     float mx = NEG_BIG, l = 0.f;
     for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, src[(size_t)s * 256]);
     for (int s = 0; s < nsplit; ++s) l += src[(size_t)s * 256 + 1] * fast_exp2(src[(size_t)s * 256] - mx);
-    sm_M[tid] = mx;
-    sm_iL[tid] = (tid < W * p.G && l > 0.f) ? 1.0f / l : 0.f;      // padding rows add nothing
+    // probability = exp2(logit * scale - (max + log2 sum)); padding rows add nothing
+    sm_ML[tid] = (tid < W * p.G && l > 0.f) ? -(mx + __builtin_amdgcn_logf(l)) : -INFINITY;
   }
   __syncthreads();
-  float Mq[NB], iLq[NB];
+  float negML[NB];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) { Mq[nb] = sm_M[nb * 16 + st.lr]; iLq[nb] = sm_iL[nb * 16 + st.lr]; }
+  for (int nb = 0; nb < NB; ++nb) negML[nb] = sm_ML[nb * 16 + st.lr];
+  const float inv_w = 1.0f / (float)W;
 
   float* tok = p.pp_tok + (size_t)unit * T;
-  for (; base < st.end; base += PP_STEP) {
-    const int nb_base = base + PP_STEP;
-    const bool ragged = base + PP_TILE > lim_all;
-    auto block = [&](uint4 (&k)[KS], int h) {
-      f32x4_t a[NB];
-      st.logits(k, a);
-      if (nb_base < st.end) st.load_block(k, nb_base + h * 16);
-      float col[4] = {0.f, 0.f, 0.f, 0.f};
+  auto block = [&](auto ragged, uint4 (&k)[KS], int tile, int h) {
+    constexpr bool RAGGED = decltype(ragged)::value;
+    f32x4_t a[NB];
+    st.logits(k, a);
+    if (tile - PP_STEP >= first) st.load_block(k, tile - PP_STEP + h * 16);
+    float col[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
+    for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float pe = fast_exp2(a[nb][i] * sc - Mq[nb]) * iLq[nb];
-          if (ragged) pe = (base + h * 16 + st.q4 * 4 + i < st.lim[nb]) ? pe : 0.f;
-          col[i] += pe;
+      for (int i = 0; i < 4; ++i) {
+        float pe = fast_exp2(fmaf(a[nb][i], sc, negML[nb]));
+        if (RAGGED) pe = (tile + h * 16 + st.q4 * 4 + i < st.lim[nb]) ? pe : 0.f;
+        col[i] += pe;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) col[i] = row16_sum(col[i]);
+    if (st.lr == 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = tile + h * 16 + st.q4 * 4 + i;
+        if (!RAGGED || j < st.end) {
+          // every window query sees a key before the window; the key T - x is seen by x of them
+          const float sj = RAGGED ? col[i] / (float)min(W, T - j) : col[i] * inv_w;
+          tok[j] = sj;
+          if (block_means) sm_tok[j - st.begin] = sj;
         }
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) col[i] = row16_sum(col[i]);
-      if (st.lr == 0) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int j = base + h * 16 + st.q4 * 4 + i;
-          if (j < st.end) tok[j] = col[i] / (float)min(W, T - j);
-        }
-      }
-    };
-    block(k0, 0);
-    block(k1, 1);
+    }
+  };
+  for (; base >= first; base -= PP_STEP) {
+    if (base + PP_TILE > lim_all) { block(BoolTag<true>{}, k0, base, 0); block(BoolTag<true>{}, k1, base, 1); }
+    else { block(BoolTag<false>{}, k0, base, 0); block(BoolTag<false>{}, k1, base, 1); }
+  }
+  // a block's score is the mean over its W tokens (the blocks of this slice lie wholly inside it)
+  if (block_means) {
+    __syncthreads();
+    float* beta = p.pp_beta + (size_t)unit * (T / W);
+    for (int k = tid; k < (st.end - st.begin) / W; k += PP_THREADS) {
+      float acc = 0.f;
+      for (int x = 0; x < W; ++x) acc += sm_tok[k * W + x];
+      beta[st.begin / W + k] = acc / (float)W;
+    }
   }
 }
 
@@ -259,54 +290,56 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, con
 // blocks: block means, Algorithm 1 over blocks with frozen scores, the kept blocks in ascending order
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prompt_blocks_kernel(Params p, int T, int b, int cb, int sink_b, int recent_b,
-                                                            int32_t* __restrict__ evicted_blocks) {
+                                                            int have_means, int32_t* __restrict__ evicted_blocks) {
   extern __shared__ __attribute__((aligned(16))) float pb_smem[];
-  const int unit = blockIdx.x, tid = threadIdx.x;
+  const int unit = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
   const int N = T / b, m_b = cb - sink_b - recent_b;
   float* beta = pb_smem;                                  // [N]
-  int* seq_a = reinterpret_cast<int*>(pb_smem + N);       // [2 * m_b] the tree region, then the pass's newcomers
-  int* seq_b = seq_a + 2 * m_b;
+  int* cur = reinterpret_cast<int*>(pb_smem + N);         // [m_b] the tree region
+  int* nxt = cur + m_b;
   const float* tok = p.pp_tok + (size_t)unit * T;
   int* kept = p.pp_kept + (size_t)unit * p.budget;
   int32_t* evu = evicted_blocks ? evicted_blocks + (size_t)unit * N : nullptr;
 
-  for (int k = tid; k < N; k += 256) {
-    float acc = 0.f;
-    for (int x = 0; x < b; ++x) acc += tok[(size_t)k * b + x];
-    beta[k] = acc / (float)b;
+  for (int k = tid; k < N; k += nt) {
+    if (have_means) {
+      beta[k] = p.pp_beta[(size_t)unit * N + k];
+    } else {
+      float acc = 0.f;
+      for (int x = 0; x < b; ++x) acc += tok[(size_t)k * b + x];
+      beta[k] = acc / (float)b;
+    }
     if (evu && k < cb) evu[k] = -1;                       // blocks that arrive while the cache still has room
   }
   if (N <= cb) {                                          // nothing to evict
-    for (int k = tid; k < N; k += 256) kept[k] = k;
+    for (int k = tid; k < N; k += nt) kept[k] = k;
     return;
   }
-  for (int k = tid; k < m_b; k += 256) seq_a[k] = sink_b + k;
+  for (int k = tid; k < m_b; k += nt) cur[k] = sink_b + k;
   __syncthreads();
-  // the block that enters the tree region at eviction step e is block sink_b + m_b + e (the one that just
-  // left the recent window, or the arriving block itself without one); the block arriving then is cb + e
+  // One pass of idx over the tree region: the sequence is the region at the pass's start followed by the blocks
+  // that enter during the pass; the block entering at eviction step e is block sink_b + m_b + e (the one that
+  // just left the recent window, or the arriving block itself without one), the block arriving then is cb + e.
   const int n_ev = N - cb;
-  int* cur = seq_a;
-  int* nxt = seq_b;
   for (int e0 = 0; e0 < n_ev; e0 += m_b) {
     const int cnt = min(m_b, n_ev - e0);
-    for (int x = tid; x < cnt; x += 256) cur[m_b + x] = sink_b + m_b + e0 + x;
-    __syncthreads();
-    for (int k = tid; k < m_b; k += 256) {
+    auto seq = [&](int k) { return k < m_b ? cur[k] : sink_b + e0 + k; };
+    for (int k = tid; k < m_b; k += nt) {
       int v;
       if (k < cnt) {
-        const int l = cur[2 * k], r = cur[2 * k + 1];
+        const int l = seq(2 * k), r = seq(2 * k + 1);
         const bool drop_right = (p.flags & TREEKV_KEEP_LEFT) || (beta[l] > beta[r]);   // a tie evicts the left block
         v = drop_right ? l : r;
         if (evu) evu[cb + e0 + k] = drop_right ? r : l;
       } else {
-        v = cur[k + cnt];
+        v = seq(k + cnt);
       }
       nxt[k] = v;
     }
     __syncthreads();
     int* t = cur; cur = nxt; nxt = t;
   }
-  for (int i = tid; i < cb; i += 256) {
+  for (int i = tid; i < cb; i += nt) {
     int v;
     if (i < sink_b) v = i;
     else if (i < sink_b + m_b) v = cur[i - sink_b];
@@ -365,28 +398,33 @@ __global__ __launch_bounds__(256) void prompt_handoff_kernel(Params p, const uin
 
 template <int D, int NB>
 void launch_streams(const Params& p, const uint16_t* Qw, const uint16_t* K, int T, int W, int rows_per_split,
-                    int nsplit, hipStream_t s) {
+                    int nsplit, int block_means, hipStream_t s) {
   hipLaunchKernelGGL((prompt_stats_kernel<D, NB>), dim3(nsplit, p.U), dim3(PP_THREADS), 0, s, p, Qw, K, T, W,
                      rows_per_split, nsplit);
-  hipLaunchKernelGGL((prompt_scores_kernel<D, NB>), dim3(nsplit, p.U), dim3(PP_THREADS), 0, s, p, Qw, K, T, W,
-                     rows_per_split, nsplit);
+  const size_t lds = block_means ? (size_t)rows_per_split * 4 : 0;
+  hipLaunchKernelGGL((prompt_scores_kernel<D, NB>), dim3(nsplit, p.U), dim3(PP_THREADS), lds, s, p, Qw, K, T, W,
+                     rows_per_split, nsplit, block_means);
 }
 
 template <int D>
 void launch_streams_d(const Params& p, const uint16_t* Qw, const uint16_t* K, int T, int W, int rows_per_split,
-                      int nsplit, hipStream_t s) {
+                      int nsplit, int block_means, hipStream_t s) {
   const int nb = (W * p.G + 15) / 16;
-  if (nb <= 2) launch_streams<D, 2>(p, Qw, K, T, W, rows_per_split, nsplit, s);
-  else if (nb <= 4) launch_streams<D, 4>(p, Qw, K, T, W, rows_per_split, nsplit, s);
-  else launch_streams<D, 8>(p, Qw, K, T, W, rows_per_split, nsplit, s);
+  if (nb <= 2) launch_streams<D, 2>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
+  else if (nb <= 4) launch_streams<D, 4>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
+  else launch_streams<D, 8>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
 }
 
 }  // namespace
 
-// Slices per unit: enough workgroups to fill the chip twice over, a slice a multiple of what a workgroup
+// Slices per unit: one workgroup per compute unit (measured: 256 workgroups 51 us, 512: 60, 1024: 73 for the
+// statistics pass over a 32k prompt of 32 heads), a slice a multiple of what a workgroup
 // takes per iteration, at most PROMPT_MAX_SPLITS of them.
 int prompt_splits(const Params& p, int T, int* rows_per_split) {
-  int ns = (512 + p.U - 1) / p.U;
+#ifndef TKV_PP_WGS
+#define TKV_PP_WGS 256
+#endif
+  int ns = (TKV_PP_WGS + p.U - 1) / p.U;
   const int by_len = (T + PP_STEP - 1) / PP_STEP;
   if (ns > by_len) ns = by_len;
   if (ns > PROMPT_MAX_SPLITS) ns = PROMPT_MAX_SPLITS;
@@ -398,7 +436,7 @@ int prompt_splits(const Params& p, int T, int* rows_per_split) {
 }
 
 size_t prompt_blocks_lds(int T, int b, int cb, int sink_b, int recent_b) {
-  return ((size_t)(T / b) + 4 * (size_t)(cb - sink_b - recent_b)) * 4;
+  return ((size_t)(T / b) + 2 * (size_t)(cb - sink_b - recent_b)) * 4;
 }
 
 int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V, int T, int b, int32_t* retained,
@@ -407,13 +445,19 @@ int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V,
   const int cb = p.budget / b, sink_b = (p.n_sink + b - 1) / b, recent_b = (p.n_recent + b - 1) / b;
   int rows_per_split = 0;
   const int nsplit = prompt_splits(p, T, &rows_per_split);
-  if (p.D == 128) launch_streams_d<128>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, s);
-  else launch_streams_d<64>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, s);
+  // the scores kernel also takes the block means when no block straddles two slices and a slice's scores fit
+  // in 40 KB of LDS (slices start at multiples of what a workgroup takes per iteration)
+  const int block_means = (PP_STEP % b == 0 && (size_t)rows_per_split * 4 <= 40 * 1024) ? 1 : 0;
+  if (p.D == 128) launch_streams_d<128>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, block_means, s);
+  else launch_streams_d<64>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, block_means, s);
   const size_t lds = prompt_blocks_lds(T, b, cb, sink_b, recent_b);
   if (lds > 48 * 1024 &&
       hipFuncSetAttribute((const void*)prompt_blocks_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
     return TREEKV_EHIP;
-  hipLaunchKernelGGL(prompt_blocks_kernel, dim3(p.U), dim3(256), lds, s, p, T, b, cb, sink_b, recent_b, evicted_blocks);
+  // a small tree region is one wave's work: its passes then cost no workgroup barrier to speak of
+  const int blocks_threads = (cb - sink_b - recent_b <= 64 && T / b <= 4096) ? 64 : 256;
+  hipLaunchKernelGGL(prompt_blocks_kernel, dim3(p.U), dim3(blocks_threads), lds, s, p, T, b, cb, sink_b, recent_b,
+                     block_means, evicted_blocks);
   const int row_vec = p.D * 2 / 16, per_wg = 256 / row_vec;
   const int n = T < p.budget ? T : p.budget;
   hipLaunchKernelGGL(prompt_handoff_kernel, dim3((p.budget + per_wg - 1) / per_wg, p.U), dim3(256), 0, s, p,

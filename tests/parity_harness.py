@@ -280,3 +280,15 @@ def smoke_prefill(oracle, binding):
     err = compare_scores(kv, st["results"], "bf16")
     print(f"smoke: prefill ok, {st['decisions']} evictions, {st['flagged']} near-ties, "
           f"max |out err| {st['max_err']:.2e}, max |score err| {err:.2e}")
+
+
+def smoke_prompt(oracle, binding):
+    """A one-shot prompt compression followed by decode steps, on a small configuration, against the oracle."""
+    from paper_2501_04987_amd import inputs
+
+    T, block, steps, B, H, Hkv, d, budget = 16 * 23, 16, 6, 1, 4, 2, 128, 96
+    Q, K, V = inputs.batch_streams("lowrank", 2, T + steps, B, Hkv, H // Hkv, d, dtype="bf16")
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=2, n_recent=20, max_prompt=T)
+    st = run_prompt(oracle, kv, Q, K, V, T, block, steps)
+    print(f"smoke: prompt ok, {st['decisions']} block evictions, {st['flagged']} near-ties, "
+          f"max token score rel err {st['tok_err']:.2e}, then {st['decode']['decisions']} decode evictions")
