@@ -49,6 +49,8 @@ def load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2501_04987_amd.build` "
                            "(or __graft_entry__.build()) first")
+    import torch  # noqa: F401  (first, so that this process has one HIP runtime: the one torch brings)
+
     lib = C.CDLL(LIB_PATH)
     vp, i32p = C.c_void_p, C.c_void_p
     lib.treekv_init.argtypes = [C.POINTER(vp), C.c_int, C.c_int, C.c_int]
