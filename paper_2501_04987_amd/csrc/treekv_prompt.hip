@@ -295,8 +295,9 @@ __global__ __launch_bounds__(256) void prompt_blocks_kernel(Params p, int T, int
   const int unit = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
   const int N = T / b, m_b = cb - sink_b - recent_b;
   float* beta = pb_smem;                                  // [N]
-  int* cur = reinterpret_cast<int*>(pb_smem + N);         // [m_b] the tree region
-  int* nxt = cur + m_b;
+  // the tree region as (block, score bits) pairs, so that a pass reads a scope's two entries and nothing else
+  int2* cur = reinterpret_cast<int2*>(pb_smem + ((N + 1) & ~1));   // [m_b]
+  int2* nxt = cur + m_b;
   const float* tok = p.pp_tok + (size_t)unit * T;
   int* kept = p.pp_kept + (size_t)unit * p.budget;
   int32_t* evu = evicted_blocks ? evicted_blocks + (size_t)unit * N : nullptr;
@@ -315,7 +316,8 @@ __global__ __launch_bounds__(256) void prompt_blocks_kernel(Params p, int T, int
     for (int k = tid; k < N; k += nt) kept[k] = k;
     return;
   }
-  for (int k = tid; k < m_b; k += nt) cur[k] = sink_b + k;
+  __syncthreads();
+  for (int k = tid; k < m_b; k += nt) cur[k] = make_int2(sink_b + k, __float_as_int(beta[sink_b + k]));
   __syncthreads();
   // One pass of idx over the tree region: the sequence is the region at the pass's start followed by the blocks
   // that enter during the pass; the block entering at eviction step e is block sink_b + m_b + e (the one that
@@ -323,26 +325,26 @@ __global__ __launch_bounds__(256) void prompt_blocks_kernel(Params p, int T, int
   const int n_ev = N - cb;
   for (int e0 = 0; e0 < n_ev; e0 += m_b) {
     const int cnt = min(m_b, n_ev - e0);
-    auto seq = [&](int k) { return k < m_b ? cur[k] : sink_b + e0 + k; };
+    auto seq = [&](int k) { return k < m_b ? cur[k] : make_int2(sink_b + e0 + k, __float_as_int(beta[sink_b + e0 + k])); };
     for (int k = tid; k < m_b; k += nt) {
-      int v;
+      int2 v;
       if (k < cnt) {
-        const int l = seq(2 * k), r = seq(2 * k + 1);
-        const bool drop_right = (p.flags & TREEKV_KEEP_LEFT) || (beta[l] > beta[r]);   // a tie evicts the left block
+        const int2 l = seq(2 * k), r = seq(2 * k + 1);
+        const bool drop_right = (p.flags & TREEKV_KEEP_LEFT) || (__int_as_float(l.y) > __int_as_float(r.y));   // a tie evicts the left block
         v = drop_right ? l : r;
-        if (evu) evu[cb + e0 + k] = drop_right ? r : l;
+        if (evu) evu[cb + e0 + k] = drop_right ? r.x : l.x;
       } else {
         v = seq(k + cnt);
       }
       nxt[k] = v;
     }
     __syncthreads();
-    int* t = cur; cur = nxt; nxt = t;
+    int2* t = cur; cur = nxt; nxt = t;
   }
   for (int i = tid; i < cb; i += nt) {
     int v;
     if (i < sink_b) v = i;
-    else if (i < sink_b + m_b) v = cur[i - sink_b];
+    else if (i < sink_b + m_b) v = cur[i - sink_b].x;
     else v = N - recent_b + (i - sink_b - m_b);
     kept[i] = v;
   }
@@ -436,7 +438,7 @@ int prompt_splits(const Params& p, int T, int* rows_per_split) {
 }
 
 size_t prompt_blocks_lds(int T, int b, int cb, int sink_b, int recent_b) {
-  return ((size_t)(T / b) + 2 * (size_t)(cb - sink_b - recent_b)) * 4;
+  return ((size_t)(T / b) + 1 + 4 * (size_t)(cb - sink_b - recent_b)) * 4;
 }
 
 int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V, int T, int b, int32_t* retained,
@@ -454,8 +456,7 @@ int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V,
   if (lds > 48 * 1024 &&
       hipFuncSetAttribute((const void*)prompt_blocks_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
     return TREEKV_EHIP;
-  // a small tree region is one wave's work: its passes then cost no workgroup barrier to speak of
-  const int blocks_threads = (cb - sink_b - recent_b <= 64 && T / b <= 4096) ? 64 : 256;
+  const int blocks_threads = 256;
   hipLaunchKernelGGL(prompt_blocks_kernel, dim3(p.U), dim3(blocks_threads), lds, s, p, T, b, cb, sink_b, recent_b,
                      block_means, evicted_blocks);
   const int row_vec = p.D * 2 / 16, per_wg = 256 / row_vec;
