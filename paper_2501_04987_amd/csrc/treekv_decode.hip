@@ -39,9 +39,6 @@ namespace {
 #ifndef TKV_MID_NUM
 #define TKV_MID_NUM 3
 #endif
-#ifndef TKV_NT_RET
-#define TKV_NT_RET 1
-#endif
 #ifndef TKV_NT_S
 #define TKV_NT_S 1
 #endif
