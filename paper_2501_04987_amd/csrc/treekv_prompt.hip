@@ -97,9 +97,11 @@ struct PromptStream {
       }
     }
   }
-  // one operand block: keys base + lr (clamped into the prompt), this lane's 8 dims of every k-step
+  // One operand block: keys base + lr (clamped into the prompt), this lane's 8 dims of every k-step.
+  // The callers request blocks past their slice rather than branch around the request: with every load on
+  // every path the compiler's count of outstanding loads is exact and a wait covers the block it needs only.
   __device__ inline void load_block(uint4 (&k)[KS], int base) const {
-    const uint16_t* r = Ku + (size_t)min(base + lr, T - 1) * row_stride + q4 * 8;
+    const uint16_t* r = Ku + (size_t)max(0, min(base + lr, T - 1)) * row_stride + q4 * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) k[ks] = *reinterpret_cast<const uint4*>(r + ks * 32);
   }
@@ -139,15 +141,15 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_stats_kernel(Params p, cons
   constexpr int AHEAD = NB < 8 ? 2 : 1;
   uint4 k0[KS], k1[KS], k2[KS], k3[KS];
   int base = st.begin + st.wave * PP_TILE;
-  if (base < st.end) { st.load_block(k0, base); st.load_block(k1, base + 16); }
-  if (AHEAD == 2 && base + PP_STEP < st.end) { st.load_block(k2, base + PP_STEP); st.load_block(k3, base + PP_STEP + 16); }
+  st.load_block(k0, base); st.load_block(k1, base + 16);
+  if (AHEAD == 2) { st.load_block(k2, base + PP_STEP); st.load_block(k3, base + PP_STEP + 16); }
   // One operand block of 16 keys at a time: its accumulators are consumed before the next block's exist.
   // `ragged` (a type, so that the common case carries no masking code): some query does not see some key.
   auto block = [&](auto ragged, uint4 (&k)[KS], int tile, int h) {
     constexpr bool RAGGED = decltype(ragged)::value;
     f32x4_t a[NB];
     st.logits(k, a);
-    if (tile + AHEAD * PP_STEP < st.end) st.load_block(k, tile + AHEAD * PP_STEP + h * 16);
+    st.load_block(k, tile + AHEAD * PP_STEP + h * 16);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       float r[4];                                    // raw logits; the scale is positive, so max commutes with it
@@ -174,7 +176,7 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_stats_kernel(Params p, cons
   };
   for (; base < st.end; base += AHEAD * PP_STEP) {
     tile(k0, k1, base);
-    if (AHEAD == 2 && base + PP_STEP < st.end) tile(k2, k3, base + PP_STEP);
+    if (AHEAD == 2) tile(k2, k3, base + PP_STEP);     // past the slice's end every key is masked
   }
   // the four lane groups of a wave hold different keys of the same query; then the waves
 #pragma unroll
@@ -223,7 +225,7 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, con
   uint4 k0[KS], k1[KS];
   const int first = st.begin + st.wave * PP_TILE;
   int base = first < st.end ? first + (st.end - 1 - first) / PP_STEP * PP_STEP : first - PP_STEP;
-  if (base >= first) { st.load_block(k0, base); st.load_block(k1, base + 16); }
+  st.load_block(k0, base); st.load_block(k1, base + 16);
 
   if (tid < NB * 16) {                 // the slices' (max, sum) of this query row -> the row's max and 1 / sum
     const float* src = p.pp_stat + ((size_t)unit * nsplit * 128 + tid) * 2;
@@ -244,7 +246,7 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, con
     constexpr bool RAGGED = decltype(ragged)::value;
     f32x4_t a[NB];
     st.logits(k, a);
-    if (tile - PP_STEP >= first) st.load_block(k, tile - PP_STEP + h * 16);
+    st.load_block(k, tile - PP_STEP + h * 16);
     float col[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
