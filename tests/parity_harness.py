@@ -262,6 +262,7 @@ def run_prompt(oracle, kv, Q, K, V, T, block, decode_steps, units=None, dtype="b
         pos = streams[(b, h)].retained()
         np.testing.assert_array_equal(Kc[b, h, :len(pos)].float().cpu().numpy(), K[pos, b, h])
         np.testing.assert_array_equal(Vc[b, h, :len(pos)].float().cpu().numpy(), V[pos, b, h])
+    stats["streams"] = streams
     if decode_steps:
         st = run_schedule(oracle, kv, Q, K, V, [0] * decode_steps, dtype=dtype, units=units, streams=streams, t_start=T)
         stats["decode"] = st
