@@ -154,6 +154,9 @@ def bench_prefill(torch, binding, inputs, dev, chunks=24, warm=6, layers=4):
 
 PROMPT_LEN = 32768
 PROMPT_BLOCK = 64
+# HBM bytes per prompt-compression call, measured like MEASURED_TRAFFIC_BYTES (same file under profiles/): the four
+# kernels' FETCH_SIZE x 2.0 (140438 + 140852 + 48 + 16679 KiB) plus WRITE_SIZE (128 + 4163 + 4 + 34165 KiB).
+PROMPT_MEASURED_TRAFFIC_BYTES = ((140438 + 140852 + 48 + 16679) * 2 + (128 + 4163 + 4 + 34165)) * 1024
 
 
 def prompt_bytes_per_call(T=PROMPT_LEN, c=BUDGET, d=HEAD_DIM, heads=HEADS, block=PROMPT_BLOCK):
@@ -199,7 +202,7 @@ def bench_prompt(torch, binding, inputs, dev, calls=20, warm=3, layers=3):
                         f"{BUDGET} slots, blocks of {b}, 32 heads x 128 dim, bf16, batch 1",
             "calls": calls, "us_per_call": us, "prompt_tokens_per_s": T / (us * 1e-6),
             "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_call": nbytes,
+                         "frac": gbs / HBM_PEAK_GBS, "traffic": PROMPT_MEASURED_TRAFFIC_BYTES, "bytes_per_call": nbytes,
                          "note": "algorithmic bytes (every key once) over the whole call: statistics and scores "
                                  "kernels (each streams the keys, so the keys are read twice), blocks and handoff "
                                  "kernels"}}
