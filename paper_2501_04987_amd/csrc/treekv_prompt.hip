@@ -61,7 +61,7 @@ __device__ inline float row16_sum(float v) {
 
 // What the two streaming kernels share: the window queries as MFMA operands, the slice of keys a
 // workgroup owns, and the loop that turns 32 keys into NB x 2 accumulators of scaled logits.
-//   query row qr = i * G + g (window query i, head g of the group), padded with zero rows to NB * 16;
+//   query row qr = i * G + g (window query i, head g of the group), padded with rows that see nothing to NB * 16;
 //   row qr sees the keys below T - W + i + 1.
 template <int D, int NB>
 struct PromptStream {
@@ -89,12 +89,12 @@ struct PromptStream {
       const bool live = qr < W * p.G;
       const int i = qr / p.G, g = qr % p.G;
       lim[nb] = live ? min(end, T - W + i + 1) : 0;
+      // (a padding row repeats the window's last query: it sees no key, lim = 0, so what it holds does not matter,
+      // and a load on every path lets the key requests go out without waiting for these)
+      const int iq = live ? i : W - 1, gq = live ? g : 0;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        qa[nb][ks] = make_uint4(0, 0, 0, 0);
-        if (live)
-          qa[nb][ks] = *reinterpret_cast<const uint4*>(Qw + (((size_t)b * W + i) * p.H + (size_t)kvh * p.G + g) * D + ks * 32 + q4 * 8);
-      }
+      for (int ks = 0; ks < KS; ++ks)
+        qa[nb][ks] = *reinterpret_cast<const uint4*>(Qw + (((size_t)b * W + iq) * p.H + (size_t)kvh * p.G + gq) * D + ks * 32 + q4 * 8);
     }
   }
   // One operand block: keys base + lr (clamped into the prompt), this lane's 8 dims of every k-step.
