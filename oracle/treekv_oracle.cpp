@@ -30,6 +30,11 @@
 //    head all attend; S adds the sum of their probabilities, C adds 1.
 //  * Ties.  The comparison is a strict ">", so equal scores evict idx.
 //  * Ablation of Section 5.4 (always keep the left token): TKO_KEEP_LEFT.
+//  * Importance criterion.  Section 4.1 names the averaged attention weight Sbar = S / C as the
+//    criterion of choice and mentions that accumulated weights were tried too: with
+//    TKO_SCORE_ACCUMULATED line 10 is skipped and lines 11-15 compare S itself.  (In the
+//    one-shot prompt compression a token's importance is then its summed, not averaged, window
+//    attention, and S is handed over as it is.)
 //  * Chunked prefill (not in the paper, whose prefill works on blocks with an
 //    observation window; Section 4.2 only says scores and scopes are computed
 //    ahead of the selection).  A chunk of L tokens attends the cache as it
@@ -66,7 +71,7 @@
 
 namespace {
 
-enum : int { TKO_KEEP_LEFT = 1, TKO_IDX_LITERAL = 2 };
+enum : int { TKO_KEEP_LEFT = 1, TKO_IDX_LITERAL = 2, TKO_SCORE_ACCUMULATED = 4 };
 
 struct Stream {
   int c = 0, n_sink = 0, n_recent = 0, m = 0, G = 1, d = 0, flags = 0;
@@ -199,7 +204,8 @@ void tko_decode_step(void* h, const double* q, const double* k, const double* v,
   Decision dec;
   std::vector<int> order(n);
   std::vector<double> sbar(n);
-  for (size_t j = 0; j < n; ++j) { order[j] = (int)j; sbar[j] = s.S[j] / (double)s.C[j]; }
+  const bool accumulated = (s.flags & TKO_SCORE_ACCUMULATED) != 0;
+  for (size_t j = 0; j < n; ++j) { order[j] = (int)j; sbar[j] = accumulated ? s.S[j] : s.S[j] / (double)s.C[j]; }
   const int victim = choose_eviction(s, order, sbar, s.pos, forced_pos, follow_thresh, dec);
   if (victim >= 0) {
     s.K.erase(s.K.begin() + victim);
@@ -276,8 +282,9 @@ void tko_prefill_chunk(void* h, const double* Q, const double* K, const double* 
     for (size_t j = 0; j < vis; ++j) { s.C[j] += 1; s.S[j] += asum[j]; }
   }
   // frozen scores, then the replay of lines 4-5 and 9-17 token by token
+  const bool accumulated = (s.flags & TKO_SCORE_ACCUMULATED) != 0;
   std::vector<double> sbar(n);
-  for (size_t j = 0; j < n; ++j) sbar[j] = s.S[j] / (double)s.C[j];
+  for (size_t j = 0; j < n; ++j) sbar[j] = accumulated ? s.S[j] : s.S[j] / (double)s.C[j];
   std::vector<int> order;
   order.reserve(n);
   for (size_t j = 0; j < n0; ++j) order.push_back((int)j);
@@ -344,7 +351,8 @@ int tko_prefill_prompt(void* h, const double* Qw, const double* K, const double*
   }
   // line 10 per token, then the block's score: the average over its b tokens
   std::vector<double> sbar((size_t)T), beta((size_t)N);
-  for (int j = 0; j < T; ++j) sbar[j] = Ssum[j] / (double)Cnt[j];
+  const bool accumulated = (s.flags & TKO_SCORE_ACCUMULATED) != 0;
+  for (int j = 0; j < T; ++j) sbar[j] = accumulated ? Ssum[j] : Ssum[j] / (double)Cnt[j];
   for (int k = 0; k < N; ++k) {
     double acc = 0.0;
     for (int x = 0; x < b; ++x) acc += sbar[(size_t)k * b + x];
@@ -373,7 +381,7 @@ int tko_prefill_prompt(void* h, const double* Qw, const double* K, const double*
       s.K.emplace_back(K + (size_t)j * s.d, K + (size_t)(j + 1) * s.d);
       s.V.emplace_back(V + (size_t)j * s.d, V + (size_t)(j + 1) * s.d);
       s.C.push_back((long long)T - j);
-      s.S.push_back(sbar[(size_t)j] * (double)((long long)T - j));
+      s.S.push_back(accumulated ? sbar[(size_t)j] : sbar[(size_t)j] * (double)((long long)T - j));
       s.pos.push_back(j);
     }
   }

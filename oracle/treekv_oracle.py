@@ -22,6 +22,7 @@ _lib = None
 
 KEEP_LEFT = 1
 IDX_LITERAL = 2
+SCORE_ACCUMULATED = 4
 
 
 def build(force: bool = False) -> str:

@@ -19,11 +19,12 @@ def _dot(a, b):
 
 
 class BruteTreeKV:
-    def __init__(self, c, G, d, n_sink=0, n_recent=0, scale=None, keep_left=False, literal_idx=False):
+    def __init__(self, c, G, d, n_sink=0, n_recent=0, scale=None, keep_left=False, literal_idx=False,
+                 accumulated=False):
         self.c, self.G, self.d = c, G, d
         self.n_sink, self.m = n_sink, c - n_sink - n_recent
         self.scale = 1.0 / math.sqrt(d) if scale is None else scale
-        self.keep_left, self.literal_idx = keep_left, literal_idx
+        self.keep_left, self.literal_idx, self.accumulated = keep_left, literal_idx, accumulated
         self.cache = []   # records: pos, k, v, S, C
         self.idx = 1      # 1-based, as printed in Algorithm 1
         self.t = 0
@@ -59,7 +60,7 @@ class BruteTreeKV:
         for j, rec in enumerate(self.cache):
             rec["C"] += 1
             rec["S"] = math.fsum([rec["S"]] + [probs[g][j] for g in range(self.G)])
-        ev = self._maybe_evict(self.cache, lambda r: r["S"] / r["C"])
+        ev = self._maybe_evict(self.cache, (lambda r: r["S"]) if self.accumulated else (lambda r: r["S"] / r["C"]))
         self.t += 1
         return outs, ev
 
@@ -75,7 +76,7 @@ class BruteTreeKV:
             for j, rec in enumerate(vis):
                 rec["C"] += 1
                 rec["S"] = math.fsum([rec["S"]] + [probs[g][j] for g in range(self.G)])
-        frozen = {id(rec): rec["S"] / rec["C"] for rec in full}
+        frozen = {id(rec): rec["S"] if self.accumulated else rec["S"] / rec["C"] for rec in full}
         seq = full[:n0]
         evs = []
         for i in range(L):
@@ -96,7 +97,7 @@ class BruteTreeKV:
             for j, rec in enumerate(vis):
                 rec["C"] += 1
                 rec["parts"] += [probs[g][j] for g in range(self.G)]
-        sbar = [math.fsum(rec["parts"]) / rec["C"] for rec in toks]
+        sbar = [math.fsum(rec["parts"]) / (1 if self.accumulated else rec["C"]) for rec in toks]
         beta = [math.fsum(sbar[k * b:(k + 1) * b]) / b for k in range(N)]
         # Algorithm 1 with blocks for tokens
         cb, sink_b = self.c // b, -(-self.n_sink // b)
@@ -117,7 +118,7 @@ class BruteTreeKV:
         self.cache = []
         for k in seq:
             for j in range(k * b, (k + 1) * b):
-                self.cache.append(dict(pos=j, k=toks[j]["k"], v=toks[j]["v"], S=sbar[j] * (T - j), C=T - j))
+                self.cache.append(dict(pos=j, k=toks[j]["k"], v=toks[j]["v"], S=sbar[j] * (1 if self.accumulated else T - j), C=T - j))
         self.t, self.idx = T, 1
         return gone, sbar, beta
 

@@ -625,3 +625,99 @@ def test_prompt_follow_mode(oracle):
     s = oracle.OracleStream(c, 1, 4)
     r = s.prefill_prompt(Qw, K, V, b, forced_blocks=forced, follow_thresh=2.0)
     assert r["adopted"] == 1 and r["evicted_blocks"][first] == forced[first]
+
+
+# --------------------------------------------------------------------------- #
+# The accumulated-weight criterion (Section 4.1, "Importance Score": the variant that was tried next to the average)
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("c,n_sink,n_recent", [(8, 0, 0), (16, 2, 5), (13, 0, 4)])
+def test_accumulated_uniform_attention_evicts_the_newer_token(oracle, c, n_sink, n_recent):
+    """q = 0: every step adds 1 / len to every cached token, so the older token of a scope has strictly more
+    accumulated weight and the right one is always evicted: the retained set is the keep-left closed form."""
+    T, d = 6 * c, 3
+    _, k, v = _rand_stream(3, T, 1, d)
+    s = oracle.OracleStream(c, 1, d, n_sink=n_sink, n_recent=n_recent, flags=oracle.SCORE_ACCUMULATED)
+    sim = SpanSim(c, n_sink, n_recent)
+    for t in range(T):
+        s.decode_step(np.zeros((1, d)), k[t], v[t])
+        sim.step()
+        assert list(s.retained()) == [lo for lo, _ in sim.spans]
+
+
+def test_accumulated_differs_from_averaged_only_through_the_counts(oracle):
+    """Same stream, both criteria: S and C evolve identically until the first decision that differs; that
+    decision is one where S_l > S_r but S_l / C_l <= S_r / C_r (the left token is the older one)."""
+    c, G, d, T = 12, 2, 4, 200
+    q, k, v = _rand_stream(11, T, G, d)
+    a = oracle.OracleStream(c, G, d, flags=oracle.SCORE_ACCUMULATED)
+    b = oracle.OracleStream(c, G, d)
+    differed = False
+    for t in range(T):
+        pos_b, S_b, C_b = b.state()
+        idx = b.idx
+        _, ea, _, _, _ = a.decode_step(q[t], k[t], v[t])
+        _, eb, _, _, _ = b.decode_step(q[t], k[t], v[t], commit=False)
+        if ea != eb:
+            # replay b's step to read the two scope members' S and C after the update
+            probe = oracle.OracleStream(c, G, d)
+            for u in range(t):
+                probe.decode_step(q[u], k[u], v[u])
+            before = list(probe.retained()) + [t]
+            _, _, _, _, _ = probe.decode_step(q[t], k[t], v[t], commit=True)
+            l_pos, r_pos = before[idx - 1], before[idx]
+            assert {ea, eb} == {l_pos, r_pos}
+            assert ea == r_pos and eb == l_pos          # accumulated keeps the older (left) token here
+            differed = True
+            break
+        b.decode_step(q[t], k[t], v[t])
+    assert differed, "the two criteria should part ways within 200 steps of a budget-12 cache"
+
+
+def test_accumulated_brute_force(oracle):
+    for seed in range(40):
+        rng = np.random.default_rng(500 + seed)
+        c = int(rng.integers(2, 9))
+        n_sink = int(rng.integers(0, 2))
+        n_recent = int(rng.integers(0, max(1, c - n_sink - 1)))
+        G, d = int(rng.integers(1, 3)), 3
+        s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent, flags=oracle.SCORE_ACCUMULATED)
+        bf = BruteTreeKV(c, G, d, n_sink=n_sink, n_recent=n_recent, accumulated=True)
+        T = 40
+        q, k, v = _rand_stream(seed, T, G, d)
+        t = 0
+        while t < T:
+            L = int(rng.integers(0, 6))
+            if L == 0 or t + L > T:
+                o1, e1, _, _, _ = s.decode_step(q[t], k[t], v[t])
+                o2, e2 = bf.decode_step(q[t].tolist(), k[t].tolist(), v[t].tolist())
+                assert e1 == e2, (seed, t)
+                t += 1
+            else:
+                r = s.prefill_chunk(q[t:t + L], k[t:t + L], v[t:t + L])
+                _, evs = bf.prefill_chunk(q[t:t + L].tolist(), k[t:t + L].tolist(), v[t:t + L].tolist())
+                assert list(r["evicted"]) == evs, (seed, t)
+                t += L
+        assert list(s.retained()) == bf.positions()
+
+
+def test_accumulated_prompt_brute_force(oracle):
+    for seed in range(30):
+        rng = np.random.default_rng(700 + seed)
+        b = int(rng.integers(1, 4))
+        cb = int(rng.integers(3, 7))
+        c = cb * b
+        G, d = int(rng.integers(1, 3)), 3
+        T = b * int(rng.integers(1, 14))
+        Qw, K, V = _prompt(2000 + seed, T, G, d, b)
+        s = oracle.OracleStream(c, G, d, flags=oracle.SCORE_ACCUMULATED)
+        r = s.prefill_prompt(Qw, K, V, b)
+        bf = BruteTreeKV(c, G, d, accumulated=True)
+        gone, sbar, beta = bf.prefill_prompt(Qw.tolist(), K.tolist(), V.tolist(), b)
+        assert list(r["evicted_blocks"]) == gone, seed
+        np.testing.assert_allclose(r["token_scores"], sbar, rtol=1e-12)
+        S_b, C_b = bf.scores()
+        _, S, C = s.state()
+        np.testing.assert_allclose(S, S_b, rtol=1e-12)
+        assert list(C) == C_b
+        # the token scores are plain column sums of the window's attention
+        assert abs(float(r["token_scores"].sum()) - G * b) < 1e-9
