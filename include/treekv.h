@@ -48,8 +48,13 @@ typedef enum treekv_status {
 } treekv_status;
 
 enum { TREEKV_BF16 = 0, TREEKV_F32 = 1 };      /* storage type of q, k, v and of the cache */
-enum { TREEKV_KEEP_LEFT = 1 };                 /* flags: ablation of Section 5.4 (always keep the
-                                                  left slot of the scope, ignore the scores)   */
+enum {
+  TREEKV_KEEP_LEFT = 1,          /* flags: ablation of Section 5.4 (always keep the left slot of the scope,
+                                    ignore the scores)                                                   */
+  TREEKV_SCORE_ACCUMULATED = 4   /* importance = accumulated weight S instead of the average S / C
+                                    (Section 4.1, "Importance Score": the criterion tried next to the
+                                    average); Algorithm 1 line 10 is skipped, lines 11-15 compare S     */
+};
 
 typedef struct treekv_ctx treekv_ctx;          /* opaque, host memory, owns no device memory */
 
@@ -64,7 +69,7 @@ typedef struct treekv_config {
   int32_t n_sink;        /* leading tokens never evicted  (Section 5.2: 4)                     */
   int32_t n_recent;      /* trailing tokens never evicted (Section 5.2: 508 of 1024)           */
   float softmax_scale;   /* multiplies q.k; 0 selects 1/sqrt(head_dim) (Section 3.1)           */
-  int32_t flags;         /* TREEKV_KEEP_LEFT or 0                                              */
+  int32_t flags;         /* 0, or an OR of TREEKV_KEEP_LEFT, TREEKV_SCORE_ACCUMULATED             */
   int32_t max_chunk;     /* largest `len` treekv_prefill_chunk will be given; 0 selects 512    */
   int32_t kv_splits;     /* decode: workgroups per (batch, KV head); 0 lets the library choose */
   int32_t max_prompt;    /* longest `len` treekv_prefill_prompt will be given; 0: that call is not used

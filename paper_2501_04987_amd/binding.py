@@ -20,6 +20,7 @@ TREEKV_EUNSUPPORTED = -4
 TREEKV_BF16 = 0
 TREEKV_F32 = 1
 TREEKV_KEEP_LEFT = 1
+TREEKV_SCORE_ACCUMULATED = 4
 
 EXPORTS = [
     "treekv_init", "treekv_init_ex", "treekv_destroy", "treekv_get_config", "treekv_workspace_bytes",

@@ -646,8 +646,9 @@ __device__ inline void epilogue(const Params& p, int unit, const Step& st, const
   bool drop_right = false;
   if (st.evict) {
     const float sl = EP > 0 ? park[st.scope_l] : sm_sc[0], sr = EP > 0 ? park[st.scope_r] : sm_sc[1];
-    const float bl = sl / (float)(st.t - st.pos_l + 1);
-    const float br = sr / (float)(st.t - st.pos_r + 1);
+    const bool averaged = !(p.flags & TREEKV_SCORE_ACCUMULATED);
+    const float bl = averaged ? sl / (float)(st.t - st.pos_l + 1) : sl;
+    const float br = averaged ? sr / (float)(st.t - st.pos_r + 1) : sr;
     drop_right = (p.flags & TREEKV_KEEP_LEFT) || (bl > br);     // strict: a tie evicts the left slot
   }
   const int surv_pos = drop_right ? st.pos_l : st.pos_r;

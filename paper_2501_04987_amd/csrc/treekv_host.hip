@@ -177,7 +177,7 @@ int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg_in) {
   if (c.q_heads % c.kv_heads != 0) return TREEKV_EINVAL;
   if (c.n_sink < 0 || c.n_recent < 0 || c.budget - c.n_sink - c.n_recent < 1) return TREEKV_EINVAL;
   if (c.dtype != TREEKV_BF16 && c.dtype != TREEKV_F32) return TREEKV_EINVAL;
-  if (c.flags & ~TREEKV_KEEP_LEFT) return TREEKV_EINVAL;
+  if (c.flags & ~(TREEKV_KEEP_LEFT | TREEKV_SCORE_ACCUMULATED)) return TREEKV_EINVAL;
   if (c.max_chunk < 0 || c.kv_splits < 0 || c.kv_splits > 64) return TREEKV_EINVAL;
   if (!(c.softmax_scale >= 0.0f) || isinf(c.softmax_scale)) return TREEKV_EINVAL;
   if (c.head_dim != 64 && c.head_dim != 128) return TREEKV_EUNSUPPORTED;

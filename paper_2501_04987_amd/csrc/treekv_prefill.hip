@@ -784,8 +784,9 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
           const int j = j_a + x;
           const int idl = Eu[2 * j], idr = Eu[2 * j + 1];
           const int pl = PEu[2 * j], pr = PEu[2 * j + 1];
-          const float bl = score_of(idl) / (float)(t_end - pl + 1);
-          const float br = score_of(idr) / (float)(t_end - pr + 1);
+          const bool averaged = !(p.flags & TREEKV_SCORE_ACCUMULATED);
+          const float bl = averaged ? score_of(idl) / (float)(t_end - pl + 1) : score_of(idl);
+          const float br = averaged ? score_of(idr) / (float)(t_end - pr + 1) : score_of(idr);
           const bool drop_right = (p.flags & TREEKV_KEEP_LEFT) || (bl > br);
           surv_id = drop_right ? idl : idr; surv_pos = drop_right ? pl : pr;
           lose_id = drop_right ? idr : idl; lose_pos = drop_right ? pr : pl;

@@ -240,6 +240,7 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, con
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) negML[nb] = sm_ML[nb * 16 + st.lr];
   const float inv_w = 1.0f / (float)W;
+  const bool averaged = !(p.flags & TREEKV_SCORE_ACCUMULATED);
 
   float* tok = p.pp_tok + (size_t)unit * T;
   auto block = [&](auto ragged, uint4 (&k)[KS], int tile, int h) {
@@ -265,7 +266,8 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, con
         const int j = tile + h * 16 + st.q4 * 4 + i;
         if (!RAGGED || j < st.end) {
           // every window query sees a key before the window; the key T - x is seen by x of them
-          const float sj = RAGGED ? col[i] / (float)min(W, T - j) : col[i] * inv_w;
+          // (with accumulated weights as the criterion the sum itself is the score)
+          const float sj = !averaged ? col[i] : RAGGED ? col[i] / (float)min(W, T - j) : col[i] * inv_w;
           tok[j] = sj;
           if (block_means) sm_tok[j - st.begin] = sj;
         }
@@ -392,7 +394,11 @@ __global__ __launch_bounds__(256) void prompt_handoff_kernel(Params p, const uin
   if (e != 0) return;
   retained[(size_t)unit * p.budget + i] = pos;
   // Sbar stays the window average: C = T - pos queries of the prompt could attend the token, S = Sbar * C
-  if (i < n) p.S[(size_t)unit * p.cap + i] = p.pp_tok[(size_t)unit * T + pos] * (float)(T - pos);
+  // (with accumulated weights as the criterion, S is the window's sum as it is)
+  if (i < n) {
+    const float sj = p.pp_tok[(size_t)unit * T + pos];
+    p.S[(size_t)unit * p.cap + i] = (p.flags & TREEKV_SCORE_ACCUMULATED) ? sj : sj * (float)(T - pos);
+  }
   const int k = i - p.n_sink;
   if (k >= 0 && k < p.m) {
     p.E[(size_t)unit * 2 * p.m + k] = i;

@@ -206,3 +206,12 @@ def test_decode_steps_replay_from_a_hip_graph(binding):
         assert np.array_equal(ev.cpu().numpy(), want["evicted"][t]), t
         assert np.array_equal(ret.cpu().numpy(), want["retained"][t]), t
         _ = (Qd[t].float() * 2).sum().item()                             # unrelated eager work between replays
+
+
+def test_accumulated_weight_criterion(binding, oracle):
+    """TREEKV_SCORE_ACCUMULATED: the scope compares S, not S / C (Section 4.1's other criterion); fused and split shapes."""
+    for splits, G in [(1, 1), (3, 4)]:
+        _run(binding, oracle, kind="lowrank", T=500, B=2, H=2 * G, Hkv=2, d=128, dtype="bf16", budget=96,
+             n_sink=3, n_recent=30, flags=binding.TREEKV_SCORE_ACCUMULATED, kv_splits=splits, seed=21)
+    _run(binding, oracle, kind="iid", T=300, B=1, H=2, Hkv=2, d=64, dtype="f32", budget=40, n_sink=0, n_recent=0,
+         flags=binding.TREEKV_SCORE_ACCUMULATED, seed=22)

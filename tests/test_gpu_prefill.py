@@ -135,3 +135,8 @@ def test_prefill_gather_kv_matches_retained(binding, oracle):
         pos = res["stream"].retained()
         np.testing.assert_array_equal(Kc[b, h, :len(pos)].float().cpu().numpy(), K[pos, b, h])
         np.testing.assert_array_equal(Vc[b, h, :len(pos)].float().cpu().numpy(), V[pos, b, h])
+
+
+def test_prefill_accumulated_weight_criterion(binding, oracle):
+    _run(binding, oracle, [40, 64, 0, 128, 0, 0, 77, 5], B=1, H=4, Hkv=2, d=128, budget=72, n_sink=2, n_recent=20,
+         max_chunk=128, flags=binding.TREEKV_SCORE_ACCUMULATED, seed=23)

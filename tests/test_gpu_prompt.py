@@ -71,6 +71,13 @@ def test_prompt_keep_left(binding, oracle):
          flags=binding.TREEKV_KEEP_LEFT, seed=9)
 
 
+def test_prompt_accumulated_weight_criterion(binding, oracle):
+    """With TREEKV_SCORE_ACCUMULATED a token's importance is its summed window attention; the window block's own
+    tokens, seen by fewer queries, then weigh less."""
+    _run(binding, oracle, T=16 * 45, block=16, steps=30, B=1, H=4, Hkv=2, d=128, budget=160, n_sink=4, n_recent=0,
+         flags=binding.TREEKV_SCORE_ACCUMULATED, seed=12)
+
+
 def test_prompt_replaces_earlier_state(binding, oracle):
     """The call starts from scratch whatever the context held before."""
     import torch
