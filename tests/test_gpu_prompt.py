@@ -120,3 +120,55 @@ def test_prompt_llama_shaped_sampled(binding, oracle):
     kv, st = _run(binding, oracle, T=16384, block=64, steps=16, B=1, H=32, Hkv=32, d=128, budget=2048, n_sink=4,
                   n_recent=1020, units=[(0, 0), (0, 9), (0, 20), (0, 31)], seed=0)
     assert st["decisions"] == 4 * (16384 // 64 - 2048 // 64)
+
+
+def test_prompt_chunk_and_step_replay_from_a_hip_graph(binding):
+    """A prompt compression, a prefill chunk and a decode step captured in one HIP graph: no host-side state changes
+    between calls, so replays with fresh inputs (and eager work in between) give exactly what eager launches give."""
+    import torch
+
+    T, block, L, B, H, d, budget, rounds = 512, 16, 48, 1, 4, 128, 96, 4
+    n_tok = rounds * (T + L + 1)
+    Q, K, V = inputs.batch_streams("lowrank", 33, n_tok, B, H, 1, d, dtype="bf16")
+    Qd, Kd, Vd = (ph.to_device(x, "bf16") for x in (Q, K, V))
+    mk = lambda x, a, n: x[a:a + n].permute(1, 0, 2, 3).contiguous()
+
+    def make():
+        return binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=2, n_recent=20, max_chunk=64,
+                              max_prompt=T)
+
+    eager, graph = make(), make()
+    # static buffers of the graph
+    qw, kp, vp = mk(Qd, T - block, block).clone(), mk(Kd, 0, T).clone(), mk(Vd, 0, T).clone()
+    qc, kc, vc = mk(Qd, T, L).clone(), mk(Kd, T, L).clone(), mk(Vd, T, L).clone()
+    qs, ks, vs = Qd[T + L].clone(), Kd[T + L].clone(), Vd[T + L].clone()
+    tok = torch.empty(B, H, T, dtype=torch.float32, device="cuda")
+    oc, rc, nc, ec = graph.new_outputs(L)
+    os_, rs, ns, es = graph.new_outputs()
+    rp = torch.empty_like(rs)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graph.prefill_prompt(qw, kp, vp, T, block, rp, None, None, tok)
+        graph.prefill_chunk(qc, kc, vc, L, oc, rc, nc, ec)
+        graph.decode_step(qs, ks, vs, os_, rs, ns, es)
+    torch.cuda.synchronize()
+    for r in range(rounds):
+        a = r * (T + L + 1)
+        qw.copy_(mk(Qd, a + T - block, block)); kp.copy_(mk(Kd, a, T)); vp.copy_(mk(Vd, a, T))
+        qc.copy_(mk(Qd, a + T, L)); kc.copy_(mk(Kd, a + T, L)); vc.copy_(mk(Vd, a + T, L))
+        qs.copy_(Qd[a + T + L]); ks.copy_(Kd[a + T + L]); vs.copy_(Vd[a + T + L])
+        g.replay()
+        torch.cuda.synchronize()
+        # the same three calls, eagerly, on the other context
+        tok_e = torch.empty_like(tok)
+        oc_e, rc_e, nc_e, ec_e = eager.new_outputs(L)
+        os_e, rs_e, ns_e, es_e = eager.new_outputs()
+        rp_e = torch.empty_like(rs_e)
+        eager.prefill_prompt(mk(Qd, a + T - block, block), mk(Kd, a, T), mk(Vd, a, T), T, block, rp_e, None, None, tok_e)
+        eager.prefill_chunk(mk(Qd, a + T, L), mk(Kd, a + T, L), mk(Vd, a + T, L), L, oc_e, rc_e, nc_e, ec_e)
+        eager.decode_step(Qd[a + T + L], Kd[a + T + L], Vd[a + T + L], os_e, rs_e, ns_e, es_e)
+        torch.cuda.synchronize()
+        for got, want in [(rp, rp_e), (tok, tok_e), (oc, oc_e), (rc, rc_e), (ec, ec_e), (os_, os_e), (rs, rs_e), (es, es_e)]:
+            assert torch.equal(got, want), r
+        assert torch.equal(graph.scores(), eager.scores()), r
+        _ = (Qd[a].float() * 2).sum().item()                             # unrelated eager work between replays
