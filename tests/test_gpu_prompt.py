@@ -71,6 +71,21 @@ def test_prompt_keep_left(binding, oracle):
          flags=binding.TREEKV_KEEP_LEFT, seed=9)
 
 
+def test_prompt_block_size_that_straddles_slices(binding, oracle):
+    """Blocks of 12 do not divide what a workgroup takes per iteration: the block means are then taken by the
+    blocks kernel from the token scores."""
+    _run(binding, oracle, T=12 * 130, block=12, steps=10, B=1, H=2, Hkv=2, d=128, budget=12 * 9, n_sink=5, n_recent=13,
+         seed=14)
+
+
+def test_prompt_of_700k_tokens_one_head(binding, oracle):
+    """One head, 704000 tokens in blocks of 32: 64 slices of 11008 keys (too long for the in-kernel block means),
+    22000 blocks through a tree region of 5 blocks."""
+    kv, st = _run(binding, oracle, T=32 * 22000, block=32, steps=4, B=1, H=1, Hkv=1, d=64, budget=256, n_sink=4,
+                  n_recent=40, seed=15, kind="iid")
+    assert st["decisions"] == 22000 - 8
+
+
 def test_prompt_accumulated_weight_criterion(binding, oracle):
     """With TREEKV_SCORE_ACCUMULATED a token's importance is its summed window attention; the window block's own
     tokens, seen by fewer queries, then weigh less."""
