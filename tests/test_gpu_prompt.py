@@ -130,11 +130,12 @@ def test_prompt_argument_errors(binding):
 
 
 def test_prompt_llama_shaped_sampled(binding, oracle):
-    """32 heads x 128, bf16, budget 2048 (4 + 1024 + 1020), a prompt of 16384 tokens in blocks of 64, then 16 decode
-    steps; the GPU runs all heads, the oracle audits 4 of them."""
-    kv, st = _run(binding, oracle, T=16384, block=64, steps=16, B=1, H=32, Hkv=32, d=128, budget=2048, n_sink=4,
+    """The benchmark's launch configuration: 32 heads x 128, bf16, budget 2048 (4 + 1024 + 1020), a prompt of 32768
+    tokens in blocks of 64, then 16 decode steps; the GPU runs all heads, the oracle audits 4 of them (one of the
+    heads whose keys sit at byte offset 256 mod 1024 of a token's row among them)."""
+    kv, st = _run(binding, oracle, T=32768, block=64, steps=16, B=1, H=32, Hkv=32, d=128, budget=2048, n_sink=4,
                   n_recent=1020, units=[(0, 0), (0, 9), (0, 20), (0, 31)], seed=0)
-    assert st["decisions"] == 4 * (16384 // 64 - 2048 // 64)
+    assert st["decisions"] == 4 * (32768 // 64 - 2048 // 64)
 
 
 def test_prompt_chunk_and_step_replay_from_a_hip_graph(binding):
