@@ -106,3 +106,28 @@ def test_splits_follow_lds_capacity(binding):
     binding.load().treekv_get_config(h, C.byref(cfg))
     assert rc == 0 and cfg.kv_splits == 1
     binding.load().treekv_destroy(h)
+
+
+def test_prompt_compression_host_checks(binding):
+    """treekv_prefill_prompt refuses what does not fit before anything is enqueued, and its scratch is part of the
+    workspace only when max_prompt asks for it."""
+    lib = binding.load()
+    rc, h0 = _init(binding, budget=256, n_sink=4, n_recent=60)
+    rc1, h1 = _init(binding, budget=256, n_sink=4, n_recent=60, max_prompt=4096)
+    assert rc == 0 and rc1 == 0
+    extra = lib.treekv_workspace_bytes(h1) - lib.treekv_workspace_bytes(h0)
+    assert 2 * 4 * 4096 * 4 <= extra <= 2 * 4 * 4096 * 4 + 4 * (64 * 128 * 2 * 4 + 256 * 4) + 4096
+    one = C.c_void_p(0x1000)
+    call = lambda h, T, b: lib.treekv_prefill_prompt(h, one, one, one, T, b, one, None, None, None, None)
+    assert call(h0, 1024, 32) == binding.TREEKV_EINVAL            # max_prompt = 0: the call is not available
+    for T, b in [(1000, 32), (8192, 32), (1024, 48), (1024, 0), (16, 32), (1024, 128)]:
+        assert call(h1, T, b) == binding.TREEKV_EINVAL, (T, b)    # (the last: 2 blocks, 1 sink, 1 recent, no tree block)
+    assert lib.treekv_prefill_prompt(h1, None, one, one, 1024, 32, one, None, None, None, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_prefill_prompt(h1, C.c_void_p(0x1008), one, one, 1024, 32, one, None, None, None, None) == binding.TREEKV_EINVAL
+    assert call(h1, 1024, 32) == binding.TREEKV_ENOWS             # valid arguments, but no workspace bound
+    for bad_flags in (2, 8, 16):
+        assert _init(binding, flags=bad_flags)[0] == binding.TREEKV_EINVAL
+    rc, h2 = _init(binding, flags=binding.TREEKV_KEEP_LEFT | binding.TREEKV_SCORE_ACCUMULATED)
+    assert rc == 0
+    for h in (h0, h1, h2):
+        lib.treekv_destroy(h)
