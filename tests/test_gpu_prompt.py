@@ -188,3 +188,34 @@ def test_prompt_chunk_and_step_replay_from_a_hip_graph(binding):
             assert torch.equal(got, want), r
         assert torch.equal(graph.scores(), eager.scores()), r
         _ = (Qd[a].float() * 2).sum().item()                             # unrelated eager work between replays
+
+
+def test_prompt_and_chunked_prefill_share_the_span_structure(binding):
+    """The scopes of Algorithm 1 do not depend on the scores, so the one-shot compression with single-token blocks
+    and the chunked prefill of the same prompt keep one token of every span each, whatever they score it by (the
+    last query's attention / all queries' averaged attention): in position order, the i-th token one of them keeps
+    lies before the (i+1)-th token the other keeps.  Sinks and the recent window are the same tokens."""
+    import torch
+
+    T, B, H, d, budget, n_sink, n_recent, L = 6000, 1, 4, 128, 256, 4, 60, 250
+    Q, K, V = inputs.batch_streams("lowrank", 21, T, B, H, 1, d, dtype="bf16")
+    Qd, Kd, Vd = (ph.to_device(x, "bf16").permute(1, 0, 2, 3).contiguous() for x in (Q, K, V))   # [B,T,H,d]
+    one = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=n_sink, n_recent=n_recent, max_prompt=T)
+    chk = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=n_sink, n_recent=n_recent, max_chunk=L)
+    _, ret_one, n_one, _ = one.new_outputs()
+    one.prefill_prompt(Qd[:, T - 1:T].contiguous(), Kd, Vd, T, 1, ret_one, n_one)
+    for t in range(0, T, L):
+        out, ret_chk, n_chk, ev = chk.new_outputs(L)
+        chk.prefill_chunk(Qd[:, t:t + L].contiguous(), Kd[:, t:t + L].contiguous(), Vd[:, t:t + L].contiguous(), L, out,
+                          ret_chk, n_chk, ev)
+    torch.cuda.synchronize()
+    a, b = ret_one.cpu().numpy()[0], ret_chk.cpu().numpy()[0]
+    assert np.all(n_one.cpu().numpy() == budget) and np.all(n_chk.cpu().numpy() == budget)
+    same = 0
+    for h in range(H):
+        assert np.array_equal(a[h, :n_sink], b[h, :n_sink]) and np.array_equal(a[h, -n_recent:], b[h, -n_recent:])
+        assert np.all(a[h, :-1] < b[h, 1:]) and np.all(b[h, :-1] < a[h, 1:]), h
+        same += int(np.sum(a[h] == b[h]))
+    # different criteria: the two must not simply coincide on the tree region
+    assert same < H * budget, same
+    print(f"  same token kept in {same - H * (n_sink + n_recent)} of {H * (budget - n_sink - n_recent)} spans")
