@@ -53,6 +53,15 @@
 //    blocks.  The paper does not say how decoding takes over; here the kept tokens keep their
 //    window average as Sbar: C becomes the number of prompt queries since the token arrived
 //    (T - position) and S = Sbar * C, and token-level eviction starts at idx = 1.
+//  * Position re-assignment (Section 4.1, "Position Encoding").  With TKO_POSITION_RERANK the
+//    stream holds keys WITHOUT positional encoding; at every step the cached tokens, in cache
+//    order and including the new one, are given the positions 0, 1, .., n-1 (the paper's
+//    example: tokens {0,1,2,3,7,8,9} and the 10th get {0,..,7}), and the rotary encoding of
+//    those positions is applied to the keys and (position n-1) to the query before line 6.
+//    The rotary encoding is the one of its defining paper (RoFormer, eq. 15/34): dimensions
+//    (2i, 2i+1) form a plane rotated by position * base^(-2i/d), base 10000 unless set.  The
+//    paper does not say which flavour its models use; a model that pairs (i, i + d/2) instead
+//    permutes the head dimension of q and k accordingly.  Decode steps only.
 //
 // Near-tie handling for parity runs: every decision reports its relative
 // margin |Sbar_l - Sbar_r| / max(Sbar_l, Sbar_r).  A caller may pass the
@@ -71,11 +80,12 @@
 
 namespace {
 
-enum : int { TKO_KEEP_LEFT = 1, TKO_IDX_LITERAL = 2, TKO_SCORE_ACCUMULATED = 4 };
+enum : int { TKO_KEEP_LEFT = 1, TKO_IDX_LITERAL = 2, TKO_SCORE_ACCUMULATED = 4, TKO_POSITION_RERANK = 8 };
 
 struct Stream {
   int c = 0, n_sink = 0, n_recent = 0, m = 0, G = 1, d = 0, flags = 0;
   double scale = 1.0;
+  double rope_base = 10000.0;
   long long t = 0;  // tokens processed so far == position of the next token
   int idx = 1;      // the paper's 1-based idx (Algorithm 1, line 1)
   std::vector<std::vector<double>> K, V;  // one row per cached token
@@ -97,6 +107,19 @@ void softmax_row(const std::vector<double>& logits, size_t n, std::vector<double
   double sum = 0.0;
   for (size_t j = 0; j < n; ++j) { a[j] = std::exp(logits[j] - mx); sum += a[j]; }
   for (size_t j = 0; j < n; ++j) a[j] /= sum;
+}
+
+// Rotary position encoding of one row x [d] at position p: every plane (2i, 2i+1) is turned by
+// the angle p * base^(-2i/d).
+std::vector<double> rotary(const double* x, int d, long long p, double base) {
+  std::vector<double> y(x, x + d);
+  for (int i = 0; 2 * i + 1 < d; ++i) {
+    const double angle = (double)p * std::pow(base, -2.0 * (double)i / (double)d);
+    const double co = std::cos(angle), si = std::sin(angle);
+    y[2 * i] = x[2 * i] * co - x[2 * i + 1] * si;
+    y[2 * i + 1] = x[2 * i] * si + x[2 * i + 1] * co;
+  }
+  return y;
 }
 
 // Lines 9-17 of Algorithm 1 on a list of token handles `order` whose scores are sbar[handle].
@@ -143,6 +166,8 @@ void* tko_new(int budget, int n_sink, int n_recent, int G, int d, double scale, 
 
 void tko_free(void* h) { delete static_cast<Stream*>(h); }
 
+void tko_set_rope_base(void* h, double base) { static_cast<Stream*>(h)->rope_base = base; }
+
 int tko_len(void* h) { return (int)static_cast<Stream*>(h)->pos.size(); }
 long long tko_t(void* h) { return static_cast<Stream*>(h)->t; }
 int tko_idx(void* h) { return static_cast<Stream*>(h)->idx; }
@@ -183,11 +208,19 @@ void tko_decode_step(void* h, const double* q, const double* k, const double* v,
   s.pos.push_back(s.t);
   const size_t n = s.K.size();
   // line 6 and o = a V, once per query head of the group
+  // with position re-assignment: the token at cache index j is at position j, the query at n - 1
+  const bool rerank = (s.flags & TKO_POSITION_RERANK) != 0;
+  std::vector<std::vector<double>> Kpos;
+  if (rerank)
+    for (size_t j = 0; j < n; ++j) Kpos.push_back(rotary(s.K[j].data(), s.d, (long long)j, s.rope_base));
+  const std::vector<std::vector<double>>& Katt = rerank ? Kpos : s.K;
   std::vector<double> logits(n), a(n), asum(n, 0.0);
   for (int g = 0; g < s.G; ++g) {
+    std::vector<double> qg(q + g * s.d, q + (g + 1) * s.d);
+    if (rerank) qg = rotary(qg.data(), s.d, (long long)n - 1, s.rope_base);
     for (size_t j = 0; j < n; ++j) {
       double acc = 0.0;
-      for (int e = 0; e < s.d; ++e) acc += q[g * s.d + e] * s.K[j][e];
+      for (int e = 0; e < s.d; ++e) acc += qg[e] * Katt[j][e];
       logits[j] = acc * s.scale;
     }
     softmax_row(logits, n, a);
@@ -246,10 +279,12 @@ void tko_decode_stream(void* h, const double* q, const double* k, const double* 
 //   chunk's tokens (-1 where it evicted nothing).
 //   evicted [L], margins [L], adopted [L], disagreed [L]: per-token decision records
 //   (any may be null).
-void tko_prefill_chunk(void* h, const double* Q, const double* K, const double* V, int L, double* out,
+// Returns 0, or -1 (nothing done) for a stream with position re-assignment.
+int tko_prefill_chunk(void* h, const double* Q, const double* K, const double* V, int L, double* out,
                        const long long* forced_pos, double follow_thresh,
                        long long* evicted, double* margins, int* adopted, int* disagreed) {
   Stream& s = *static_cast<Stream*>(h);
+  if (s.flags & TKO_POSITION_RERANK) return -1;
   const size_t n0 = s.K.size();
   for (int i = 0; i < L; ++i) {
     s.K.emplace_back(K + (size_t)i * s.d, K + (size_t)(i + 1) * s.d);
@@ -309,6 +344,7 @@ void tko_prefill_chunk(void* h, const double* Q, const double* K, const double* 
   }
   s.K.swap(K2); s.V.swap(V2); s.S.swap(S2); s.C.swap(C2); s.pos.swap(P2);
   s.t += L;
+  return 0;
 }
 
 // One-shot block-level compression of a whole prompt (Section 4.2).  The stream must be empty.
@@ -318,12 +354,13 @@ void tko_prefill_chunk(void* h, const double* Q, const double* K, const double* 
 //   evicted_block, margins [T/b]; counts[0] += adopted, counts[1] += disagreed;
 //   token_sbar [T], block_score [T/b] (any may be null).
 // Returns 0, or -1 if the arguments do not fit (non-empty stream, T or c not a multiple of b,
-// no tree block left).
+// no tree block left, a stream with position re-assignment).
 int tko_prefill_prompt(void* h, const double* Qw, const double* K, const double* V, int T, int b,
                        const long long* forced_block, double follow_thresh, long long* evicted_block,
                        double* margins, long long* counts, double* token_sbar, double* block_score) {
   Stream& s = *static_cast<Stream*>(h);
   if (!s.pos.empty() || s.t != 0 || b < 1 || T < b || T % b != 0 || s.c % b != 0) return -1;
+  if (s.flags & TKO_POSITION_RERANK) return -1;
   const int N = T / b, W = b;
   Stream blk;                                     // Algorithm 1's scalars, counted in blocks
   blk.c = s.c / b;

@@ -23,6 +23,7 @@ _lib = None
 KEEP_LEFT = 1
 IDX_LITERAL = 2
 SCORE_ACCUMULATED = 4
+POSITION_RERANK = 8
 
 
 def build(force: bool = False) -> str:
@@ -56,6 +57,8 @@ def _load():
         lib.tko_kv.argtypes = [C.c_void_p, dp, dp]
         lib.tko_decode_step.argtypes = [C.c_void_p, dp, dp, dp, dp, C.c_longlong, C.c_double, C.c_int, lp, dp]
         lib.tko_decode_stream.argtypes = [C.c_void_p, dp, dp, dp, C.c_int, dp, lp, C.c_double, lp, dp, lp]
+        lib.tko_set_rope_base.argtypes = [C.c_void_p, C.c_double]
+        lib.tko_prefill_chunk.restype = C.c_int
         lib.tko_prefill_chunk.argtypes = [C.c_void_p, dp, dp, dp, C.c_int, dp, lp, C.c_double, lp, dp, ip, ip]
         lib.tko_prefill_prompt.restype = C.c_int
         lib.tko_prefill_prompt.argtypes = [C.c_void_p, dp, dp, dp, C.c_int, C.c_int, lp, C.c_double, lp, dp, lp, dp, dp]
@@ -79,7 +82,7 @@ class OracleStream:
     """TreeKV state of one (batch, kv-head) stream, fp64 (Algorithm 1 with the layout reading)."""
 
     def __init__(self, budget: int, G: int, d: int, *, n_sink: int = 0, n_recent: int = 0,
-                 scale: float | None = None, flags: int = 0):
+                 scale: float | None = None, flags: int = 0, rope_base: float = 10000.0):
         self._lib = _load()
         self.budget, self.G, self.d = budget, G, d
         self.n_sink, self.n_recent = n_sink, n_recent
@@ -87,6 +90,8 @@ class OracleStream:
         self._h = self._lib.tko_new(budget, n_sink, n_recent, G, d, self.scale, flags)
         if not self._h:
             raise ValueError("invalid oracle configuration")
+        self.rope_base = float(rope_base)
+        self._lib.tko_set_rope_base(self._h, self.rope_base)
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
@@ -152,9 +157,11 @@ class OracleStream:
         fp = None
         if forced_pos is not None:
             fp = np.ascontiguousarray(forced_pos, np.int64).reshape(L)
-        self._lib.tko_prefill_chunk(self._h, _dptr(Q), _dptr(K), _dptr(V), L, _dptr(out),
-                                    _lptr(fp) if fp is not None else None, float(follow_thresh),
-                                    _lptr(ev), _dptr(mg), _iptr(ad), _iptr(dis))
+        rc = self._lib.tko_prefill_chunk(self._h, _dptr(Q), _dptr(K), _dptr(V), L, _dptr(out),
+                                         _lptr(fp) if fp is not None else None, float(follow_thresh),
+                                         _lptr(ev), _dptr(mg), _iptr(ad), _iptr(dis))
+        if rc != 0:
+            raise ValueError("prefill_chunk: not defined for a stream with position re-assignment")
         return dict(out=out, evicted=ev, margins=mg, adopted=ad, disagreed=dis)
 
     def prefill_prompt(self, Qw, K, V, block: int, *, forced_blocks=None, follow_thresh: float = 0.0):
@@ -194,7 +201,8 @@ def run_decode_stream(cfg: dict, q, k, v, *, forced=None, follow_thresh: float =
     """
     T = q.shape[0]
     s = OracleStream(cfg["budget"], cfg["G"], cfg["d"], n_sink=cfg.get("n_sink", 0),
-                     n_recent=cfg.get("n_recent", 0), scale=cfg.get("scale"), flags=cfg.get("flags", 0))
+                     n_recent=cfg.get("n_recent", 0), scale=cfg.get("scale"), flags=cfg.get("flags", 0),
+                     rope_base=cfg.get("rope_base", 10000.0))
     q = np.ascontiguousarray(q, np.float64).reshape(T, s.G, s.d)
     k = np.ascontiguousarray(k, np.float64).reshape(T, s.d)
     v = np.ascontiguousarray(v, np.float64).reshape(T, s.d)

@@ -4,6 +4,7 @@ Pure Python: one list of dict records per stream, `list.pop` for eviction,
 `math.fsum` for every sum.  Written from Algorithm 1 of the paper (Section 4.1),
 separately from the C++ oracle: it shares nothing with it.
 """
+import cmath
 import math
 
 
@@ -20,19 +21,32 @@ def _dot(a, b):
 
 class BruteTreeKV:
     def __init__(self, c, G, d, n_sink=0, n_recent=0, scale=None, keep_left=False, literal_idx=False,
-                 accumulated=False):
+                 accumulated=False, rerank_base=None):
         self.c, self.G, self.d = c, G, d
         self.n_sink, self.m = n_sink, c - n_sink - n_recent
         self.scale = 1.0 / math.sqrt(d) if scale is None else scale
         self.keep_left, self.literal_idx, self.accumulated = keep_left, literal_idx, accumulated
+        self.rerank_base = rerank_base   # not None: positions re-assigned to cache ranks, rotary encoding
         self.cache = []   # records: pos, k, v, S, C
         self.idx = 1      # 1-based, as printed in Algorithm 1
         self.t = 0
 
+    def _logit(self, q, k, distance):
+        if self.rerank_base is None:
+            return _dot(q, k)
+        # rotary encoding in its relative form: plane i contributes Re(q_i conj(k_i) e^{1j distance theta_i})
+        total = []
+        for i in range(self.d // 2):
+            theta = self.rerank_base ** (-2.0 * i / self.d)
+            total.append((complex(q[2 * i], q[2 * i + 1]) * complex(k[2 * i], -k[2 * i + 1])
+                          * cmath.exp(1j * distance * theta)).real)
+        return math.fsum(total)
+
     def _attend(self, q, visible):
         outs, probs = [], []
+        n = len(visible)
         for g in range(self.G):
-            a = _softmax([self.scale * _dot(q[g], rec["k"]) for rec in visible])
+            a = _softmax([self.scale * self._logit(q[g], rec["k"], n - 1 - j) for j, rec in enumerate(visible)])
             outs.append([math.fsum(a[j] * visible[j]["v"][e] for j in range(len(visible)))
                          for e in range(self.d)])
             probs.append(a)

@@ -721,3 +721,123 @@ def test_accumulated_prompt_brute_force(oracle):
         assert list(C) == C_b
         # the token scores are plain column sums of the window's attention
         assert abs(float(r["token_scores"].sum()) - G * b) < 1e-9
+
+
+# --------------------------------------------------------------------------- #
+# Position re-assignment (Section 4.1, "Position Encoding")
+# --------------------------------------------------------------------------- #
+def _rotary_attention(q, K, V, q_pos, k_pos, scale, base=10000.0):
+    """Textbook rotary attention with complex arithmetic: plane i of a row is the complex number
+    x[2i] + 1j*x[2i+1], multiplied by exp(1j * position * base**(-2i/d)); logit = Re <q', conj k'>."""
+    d = K.shape[1]
+    theta = base ** (-2.0 * np.arange(d // 2) / d)
+    kc = (K[:, 0::2] + 1j * K[:, 1::2]) * np.exp(1j * np.outer(k_pos, theta))
+    out = []
+    for qg in q:
+        qc = (qg[0::2] + 1j * qg[1::2]) * np.exp(1j * q_pos * theta)
+        logits = np.real(kc.conj() @ qc) * scale
+        a = np.exp(logits - logits.max())
+        a /= a.sum()
+        out.append(a @ V)
+    return np.array(out)
+
+
+def test_rerank_paper_example(oracle):
+    """The cache of the paper's example ({0,1,2,3,7,8,9}, then token 10) comes out of 3 sinks + 1 tree slot + 3
+    recent tokens with the keep-left policy; the step that decodes token 10 must see positions 0..7."""
+    facts = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "position_reassignment_example.txt")):
+        if line.strip() and not line.startswith("#"):
+            key, *vals = line.split()
+            facts[key] = [int(x) for x in vals]
+    G, d = 2, 8
+    q, k, v = _rand_stream(31, 11, G, d)
+    s = oracle.OracleStream(7, G, d, n_sink=3, n_recent=3, flags=oracle.KEEP_LEFT | oracle.POSITION_RERANK)
+    for t in range(10):
+        s.decode_step(q[t], k[t], v[t])
+    assert list(s.retained()) == facts["cached_tokens"]
+    out = s.decode_step(q[10], k[10], v[10], commit=False)[0]
+    toks = facts["cached_tokens"] + facts["new_token"]
+    want = _rotary_attention(q[10], k[toks], v[toks], facts["assigned_positions"][-1], facts["assigned_positions"],
+                             s.scale)
+    np.testing.assert_allclose(out, want, rtol=1e-10, atol=1e-12)
+    wrong = _rotary_attention(q[10], k[toks], v[toks], facts["original_positions"][-1], facts["original_positions"],
+                              s.scale)
+    assert np.abs(out - wrong).max() > 1e-3
+
+
+@pytest.mark.parametrize("c,n_sink,n_recent,G,d", [(12, 0, 0, 1, 4), (16, 2, 5, 2, 6), (9, 1, 0, 3, 8)])
+def test_rerank_equals_rotary_attention_over_cache_ranks(oracle, c, n_sink, n_recent, G, d):
+    """At every step: outputs equal rotary attention over the retained tokens at positions 0..n-1 (while the cache
+    fills these are the original positions: plain causal rotary attention)."""
+    T = 5 * c
+    q, k, v = _rand_stream(c * 7 + d, T, G, d)
+    s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent, flags=oracle.POSITION_RERANK, rope_base=50.0)
+    kept = []
+    S = {}
+    for t in range(T):
+        toks = kept + [t]
+        n = len(toks)
+        out, ev, *_ = s.decode_step(q[t], k[t], v[t])
+        want = _rotary_attention(q[t], k[toks], v[toks], n - 1, np.arange(n), s.scale, base=50.0)
+        np.testing.assert_allclose(out, want, rtol=1e-9, atol=1e-12)
+        # relative only: any common shift of the positions gives the same output
+        np.testing.assert_allclose(out, _rotary_attention(q[t], k[toks], v[toks], n + 2, np.arange(n) + 3, s.scale, 50.0),
+                                   rtol=1e-8, atol=1e-11)
+        assert (ev >= 0) == (n > c)
+        kept = [x for x in toks if x != ev]
+        assert list(s.retained()) == kept
+
+
+def test_rerank_closed_form_single_plane(oracle):
+    """d = 2, every key and query (1, 0): the plane's angle is the position itself (base^0 = 1), so the logit of
+    the key at cache index j is cos(n - 1 - j) whatever the base."""
+    c = 6
+    s = oracle.OracleStream(c, 1, 2, scale=1.0, flags=oracle.POSITION_RERANK | oracle.KEEP_LEFT, rope_base=123.0)
+    x = np.array([1.0, 0.0])
+    for t in range(15):
+        out, ev, *_ = s.decode_step(x[None], x, np.array([float(t), 1.0]), commit=False)
+        pos = list(s.retained()) + [t]
+        w = np.exp(np.cos(len(pos) - 1 - np.arange(len(pos))))
+        w /= w.sum()
+        np.testing.assert_allclose(out[0], [float(w @ np.array(pos, dtype=np.float64)), 1.0], rtol=1e-12)
+        s.decode_step(x[None], x, np.array([float(t), 1.0]))
+
+
+def test_rerank_off_is_untouched_and_prefill_refuses(oracle):
+    q, k, v = _rand_stream(5, 30, 1, 4)
+    a = oracle.run_decode_stream(_cfg(8), q, k, v)
+    b = oracle.run_decode_stream(dict(_cfg(8), rope_base=3.0), q, k, v)       # base without the flag: no effect
+    np.testing.assert_array_equal(a["out"], b["out"])
+    r = oracle.run_decode_stream(_cfg(8, flags=oracle.POSITION_RERANK), q, k, v)
+    assert np.abs(r["out"] - a["out"]).max() > 1e-3
+    s = oracle.OracleStream(8, 1, 4, flags=oracle.POSITION_RERANK)
+    with pytest.raises(ValueError):
+        s.prefill_chunk(q[:4], k[:4], v[:4])
+    with pytest.raises(ValueError):
+        s.prefill_prompt(q[:2], k[:8], v[:8], 2)
+
+
+def test_rerank_brute_force(oracle):
+    """Evictions, outputs and scores under position re-assignment against the independent re-simulation (which
+    uses the relative form of the rotary encoding)."""
+    for seed in range(25):
+        rng = np.random.default_rng(900 + seed)
+        c = int(rng.integers(3, 9))
+        n_sink = int(rng.integers(0, 2))
+        n_recent = int(rng.integers(0, 2))
+        G, d = int(rng.integers(1, 3)), 2 * int(rng.integers(1, 4))
+        base = float(rng.choice([10000.0, 7.0]))
+        T = 4 * c
+        q, k, v = _rand_stream(3000 + seed, T, G, d)
+        s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent, flags=oracle.POSITION_RERANK, rope_base=base)
+        bf = BruteTreeKV(c, G, d, n_sink=n_sink, n_recent=n_recent, rerank_base=base)
+        for t in range(T):
+            out, ev, *_ = s.decode_step(q[t], k[t], v[t])
+            o_b, ev_b = bf.decode_step(q[t].tolist(), k[t].tolist(), v[t].tolist())
+            assert ev == ev_b, (seed, t)
+            np.testing.assert_allclose(out, np.array(o_b), rtol=1e-9, atol=1e-12)
+        S_b, C_b = bf.scores()
+        _, S, C = s.state()
+        np.testing.assert_allclose(S, S_b, rtol=1e-10)
+        assert list(C) == C_b
