@@ -51,9 +51,19 @@ enum { TREEKV_BF16 = 0, TREEKV_F32 = 1 };      /* storage type of q, k, v and of
 enum {
   TREEKV_KEEP_LEFT = 1,          /* flags: ablation of Section 5.4 (always keep the left slot of the scope,
                                     ignore the scores)                                                   */
-  TREEKV_SCORE_ACCUMULATED = 4   /* importance = accumulated weight S instead of the average S / C
+  TREEKV_SCORE_ACCUMULATED = 4,  /* importance = accumulated weight S instead of the average S / C
                                     (Section 4.1, "Importance Score": the criterion tried next to the
                                     average); Algorithm 1 line 10 is skipped, lines 11-15 compare S     */
+  TREEKV_POSITION_RERANK = 8     /* positions re-assigned after eviction (Section 4.1, "Position Encoding"):
+                                    q and k are given WITHOUT positional encoding and the cache keeps them so;
+                                    at every decode step the cached tokens and the new one, in position order,
+                                    take the positions 0 .. n-1 (the paper's example: {0,1,2,3,7,8,9} and token
+                                    10 get 0..7) and the rotary encoding of those positions is applied to the
+                                    keys and the query inside the step.  Rotary encoding as defined by its
+                                    authors: dimensions (2i, 2i+1) form a plane turned by
+                                    position * rope_base^(-2i/d); a model that pairs (i, i + d/2) permutes the
+                                    head dimension of q and k accordingly.  Decode steps only: the two prefill
+                                    calls return TREEKV_EUNSUPPORTED for such a context.                  */
 };
 
 typedef struct treekv_ctx treekv_ctx;          /* opaque, host memory, owns no device memory */
@@ -69,11 +79,13 @@ typedef struct treekv_config {
   int32_t n_sink;        /* leading tokens never evicted  (Section 5.2: 4)                     */
   int32_t n_recent;      /* trailing tokens never evicted (Section 5.2: 508 of 1024)           */
   float softmax_scale;   /* multiplies q.k; 0 selects 1/sqrt(head_dim) (Section 3.1)           */
-  int32_t flags;         /* 0, or an OR of TREEKV_KEEP_LEFT, TREEKV_SCORE_ACCUMULATED             */
+  int32_t flags;         /* 0, or an OR of TREEKV_KEEP_LEFT, TREEKV_SCORE_ACCUMULATED,
+                            TREEKV_POSITION_RERANK                                             */
   int32_t max_chunk;     /* largest `len` treekv_prefill_chunk will be given; 0 selects 512    */
   int32_t kv_splits;     /* decode: workgroups per (batch, KV head); 0 lets the library choose */
   int32_t max_prompt;    /* longest `len` treekv_prefill_prompt will be given; 0: that call is not used
                             (its scratch, 4 bytes per token and (batch, KV head), is then left out)    */
+  float rope_base;       /* TREEKV_POSITION_RERANK: base of the rotary angles; 0 selects 10000            */
 } treekv_config;
 
 /*

@@ -21,6 +21,7 @@ TREEKV_BF16 = 0
 TREEKV_F32 = 1
 TREEKV_KEEP_LEFT = 1
 TREEKV_SCORE_ACCUMULATED = 4
+TREEKV_POSITION_RERANK = 8
 
 EXPORTS = [
     "treekv_init", "treekv_init_ex", "treekv_destroy", "treekv_get_config", "treekv_workspace_bytes",
@@ -35,7 +36,7 @@ class treekv_config(C.Structure):
         ("budget", C.c_int32), ("q_heads", C.c_int32), ("kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("batch", C.c_int32), ("dtype", C.c_int32), ("n_sink", C.c_int32), ("n_recent", C.c_int32),
         ("softmax_scale", C.c_float), ("flags", C.c_int32), ("max_chunk", C.c_int32), ("kv_splits", C.c_int32),
-        ("max_prompt", C.c_int32),
+        ("max_prompt", C.c_int32), ("rope_base", C.c_float),
     ]
 
 
@@ -93,7 +94,7 @@ class TreeKV:
     def __init__(self, budget: int, heads: int, head_dim: int, *, kv_heads: int | None = None, batch: int = 1,
                  dtype: str = "bf16", n_sink: int | None = None, n_recent: int | None = None,
                  softmax_scale: float = 0.0, flags: int = 0, max_chunk: int = 0, kv_splits: int = 0,
-                 max_prompt: int = 0, device="cuda", workspace=None):
+                 max_prompt: int = 0, rope_base: float = 0.0, device="cuda", workspace=None):
         import torch
 
         self._torch = torch
@@ -101,14 +102,15 @@ class TreeKV:
         self._h = C.c_void_p()
         self.device = torch.device(device)
         if kv_heads is None and batch == 1 and dtype == "bf16" and n_sink is None and n_recent is None \
-                and softmax_scale == 0.0 and flags == 0 and max_chunk == 0 and kv_splits == 0 and max_prompt == 0:
+                and softmax_scale == 0.0 and flags == 0 and max_chunk == 0 and kv_splits == 0 and max_prompt == 0 \
+                and rope_base == 0.0:
             rc = self._lib.treekv_init(C.byref(self._h), budget, heads, head_dim)
         else:
             if n_sink is None and n_recent is None:      # same default layout as treekv_init
                 n_sink, n_recent = 4, budget - budget // 2 - 4
             cfg = treekv_config(budget, heads, kv_heads or heads, head_dim, batch,
                                 {"bf16": TREEKV_BF16, "f32": TREEKV_F32}[dtype], n_sink or 0, n_recent or 0,
-                                softmax_scale, flags, max_chunk, kv_splits, max_prompt)
+                                softmax_scale, flags, max_chunk, kv_splits, max_prompt, rope_base)
             rc = self._lib.treekv_init_ex(C.byref(self._h), C.byref(cfg))
         if rc != TREEKV_OK:
             self._h = C.c_void_p()

@@ -180,7 +180,13 @@ __device__ inline int position_of(const Params& p, const Step& s, const int* PEu
 // Streaming: online softmax over slots [begin, end) of one unit by one workgroup.
 // Leaves per-wave (max, sum, accumulator) in LDS and the scaled logits in sm_s[g][row - begin].
 // ---------------------------------------------------------------------------------------------
-template <typename T, int D, int G, int THREADS>
+// ROPE (position re-assignment, Section 4.1 "Position Encoding"): the cache holds keys without positional
+// encoding; a key's position is its rank in the cache's logical order, the query's the rank of the new token, and
+// the rotary encoding enters the logit in its relative form: with (c, s) = (cos, sin) of distance * theta_i from a
+// table, plane i of the key is turned back by that angle and then multiplied with the query's plane.  The ranks of
+// the slots a workgroup streams are laid out in LDS (behind the logits) from the order arrays before the first
+// tile is consumed; table rows are requested together with the K/V rows they belong to.
+template <typename T, int D, int G, int THREADS, bool ROPE = false>
 struct Stream {
   static constexpr int WAVES = THREADS / 64;
   static constexpr int EPL = Storage<T>::EPL;   // elements per 16-byte lane load
@@ -189,6 +195,8 @@ struct Stream {
   static constexpr int TILE = RPL * KU;         // rows per wave iteration
   static constexpr int STEP = WAVES * TILE;     // rows per workgroup iteration
   static constexpr int LDS_FLOATS_FIXED = WAVES * G * (D + 2);
+  static constexpr int LDS_WORDS_PER_ROW = G + (ROPE ? 1 : 0);     // logits, and the slot's rank
+  static constexpr int TV = EPL / 4;            // 16-byte pieces of a lane's (cos, sin) pairs
 
   // sm_acc [WAVES][G][D], sm_wm [WAVES][G], sm_wl [WAVES][G].  `after_meta(st)` runs once the
   // bookkeeping words are known, after the first tile has been requested.
@@ -232,6 +240,39 @@ struct Stream {
     const int fslot = st.fslot;
     after_meta(st);
 
+    // position re-assignment: rank of every streamed slot, then the table rows of the two tiles in flight
+    int* sm_rank = reinterpret_cast<int*>(sm_s + (size_t)G * lds_rows);
+    uint4 ta[ROPE ? KU : 1][ROPE ? TV : 1], tb2[ROPE ? KU : 1][ROPE ? TV : 1];
+    auto load_tab = [&](uint4 (&td)[ROPE ? KU : 1][ROPE ? TV : 1], int tb) {
+      if constexpr (ROPE) {
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+          const int row = max(min(tb + u * RPL + ri, end - 1), begin);
+          const int dist = min(max(st.n1 - 1 - sm_rank[row - begin], 0), p.cap - 1);
+          const uint4* src = reinterpret_cast<const uint4*>(p.rope_tab + (size_t)dist * (D / 2) + li * (EPL / 2));
+#pragma unroll
+          for (int x = 0; x < TV; ++x) td[u][x] = src[x];
+        }
+      }
+    };
+    if constexpr (ROPE) {
+      const int n = st.n1 - 1;                  // cached tokens; the new one takes rank n
+      if (n < p.budget) {                       // still filling: token i sits in slot i
+        for (int r = begin + tid; r < end; r += THREADS) sm_rank[r - begin] = r;
+      } else {
+        const int* Eu = p.E + (size_t)unit * 2 * p.m;
+        const int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
+        for (int i = tid; i < n; i += THREADS) {
+          const int slot = logical_to_slot(p, Eu, Ru, st.rhead, st.j0, i);
+          if (slot >= begin && slot < end) sm_rank[slot - begin] = i;
+        }
+        if (tid == 0 && fslot >= begin && fslot < end) sm_rank[fslot - begin] = n;
+      }
+      __syncthreads();
+      if (base < end) load_tab(ta, base);
+      if (base + STEP < end) load_tab(tb2, base + STEP);
+    }
+
     auto load_tile = [&](uint4 (&kd)[KU], uint4 (&vd)[KU], int tb) {
       const bool has_new = fslot >= tb && fslot < tb + TILE;       // wave uniform
 #pragma unroll
@@ -267,16 +308,53 @@ struct Stream {
       for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     }
 
-    auto tile = [&](const uint4 (&kr)[KU], const uint4 (&vr)[KU], int tb) {
+    // the query as floats, up front unless that would not fit the registers
+    constexpr bool Q_WIDE = ROPE && G * EPL <= 32;
+    float qf[Q_WIDE ? G : 1][EPL];
+    if constexpr (Q_WIDE) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) Storage<T>::widen(qr[g], qf[g]);
+    }
+    auto tile = [&](const uint4 (&kr)[KU], const uint4 (&vr)[KU], const uint4 (&tr)[ROPE ? KU : 1][ROPE ? TV : 1], int tb) {
       float s[KU][G];
       bool ok[KU];
 #pragma unroll
       for (int u = 0; u < KU; ++u) {
         const int row = tb + u * RPL + ri;
         ok[u] = row < end;
+        float kt[EPL];                          // ROPE: the key's planes turned back by distance * theta
+        if constexpr (ROPE) {
+          float kf[EPL], cs[EPL];
+          Storage<T>::widen(kr[u], kf);
+#pragma unroll
+          for (int x = 0; x < TV; ++x) {
+            cs[4 * x] = __uint_as_float(tr[u][x].x); cs[4 * x + 1] = __uint_as_float(tr[u][x].y);
+            cs[4 * x + 2] = __uint_as_float(tr[u][x].z); cs[4 * x + 3] = __uint_as_float(tr[u][x].w);
+          }
+#pragma unroll
+          for (int e = 0; e < EPL; e += 2) {
+            kt[e] = fmaf(kf[e], cs[e], kf[e + 1] * cs[e + 1]);
+            kt[e + 1] = fmaf(kf[e + 1], cs[e], -(kf[e] * cs[e + 1]));
+          }
+        }
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-          float d = group_sum<LPR>(Dot<T>::run(kr[u], qr[g])) * p.scale_log2e;
+          float part;
+          if constexpr (ROPE) {
+            part = 0.f;
+            if constexpr (Q_WIDE) {
+#pragma unroll
+              for (int e = 0; e < EPL; ++e) part = fmaf(qf[g][e], kt[e], part);
+            } else {
+              float qg[EPL];
+              Storage<T>::widen(qr[g], qg);
+#pragma unroll
+              for (int e = 0; e < EPL; ++e) part = fmaf(qg[e], kt[e], part);
+            }
+          } else {
+            part = Dot<T>::run(kr[u], qr[g]);
+          }
+          float d = group_sum<LPR>(part) * p.scale_log2e;
           d = ok[u] ? d : NEG_BIG;
           s[u][g] = d;
           if (li == 0 && ok[u]) sm_s[(size_t)g * lds_rows + (row - begin)] = d;
@@ -313,10 +391,10 @@ struct Stream {
     const int mid_iter = mid_point((end - begin + 2 * STEP - 1) / (2 * STEP));
     int iter = 0;
     for (; base < end; base += 2 * STEP, ++iter) {
-      if (iter > 0 && base + STEP < end) load_tile(kb, vb, base + STEP);
-      tile(ka, va, base);
-      if (base + 2 * STEP < end) load_tile(ka, va, base + 2 * STEP);
-      if (base + STEP < end) tile(kb, vb, base + STEP);
+      if (iter > 0 && base + STEP < end) { load_tile(kb, vb, base + STEP); load_tab(tb2, base + STEP); }
+      tile(ka, va, ta, base);
+      if (base + 2 * STEP < end) { load_tile(ka, va, base + 2 * STEP); load_tab(ta, base + 2 * STEP); }
+      if (base + STEP < end) tile(kb, vb, tb2, base + STEP);
       if (iter == mid_iter) mid_stream();
     }
     if (iter <= mid_iter) mid_stream();
@@ -384,6 +462,7 @@ struct StreamMfma {
   static constexpr int VSTRIDE = TILE + 8;        // bf16 elements per staged V^T row (80 bytes: conflict-free b128 reads)
   static constexpr int VT_FLOATS = D * VSTRIDE / 2;
   static constexpr int LDS_FLOATS_FIXED = WAVES * G * (D + 2) + WAVES * VT_FLOATS;
+  static constexpr int LDS_WORDS_PER_ROW = G;
   static constexpr int VLOADS = TILE * PARTS / 64;        // 16-byte V pieces per lane and tile (8 at d=128, 4 at d=64)
   static_assert(G >= 2 && G <= 16 && (VLOADS == 8 || VLOADS == 4), "written for head_dim 64 / 128");
 
@@ -571,10 +650,10 @@ struct StreamMfma {
 };
 
 // The stream to use for a storage type and group size.
-template <typename T, int D, int G, int THREADS> struct PickStream { using type = Stream<T, D, G, THREADS>; };
-template <int D, int THREADS> struct PickStream<uint16_t, D, 2, THREADS> { using type = StreamMfma<D, 2, THREADS>; };
-template <int D, int THREADS> struct PickStream<uint16_t, D, 4, THREADS> { using type = StreamMfma<D, 4, THREADS>; };
-template <int D, int THREADS> struct PickStream<uint16_t, D, 8, THREADS> { using type = StreamMfma<D, 8, THREADS>; };
+template <typename T, int D, int G, int THREADS, bool ROPE> struct PickStream { using type = Stream<T, D, G, THREADS, ROPE>; };
+template <int D, int THREADS> struct PickStream<uint16_t, D, 2, THREADS, false> { using type = StreamMfma<D, 2, THREADS>; };
+template <int D, int THREADS> struct PickStream<uint16_t, D, 4, THREADS, false> { using type = StreamMfma<D, 4, THREADS>; };
+template <int D, int THREADS> struct PickStream<uint16_t, D, 8, THREADS, false> { using type = StreamMfma<D, 8, THREADS>; };
 
 // Global (max, sum) over the parts' (max, sum) pairs, identical in every thread that calls it.
 __device__ inline void merge_stats(const float* pm, const float* pl, int nparts, int stride, float& M, float& L) {
@@ -691,7 +770,7 @@ __device__ inline void epilogue(const Params& p, int unit, const Step& st, const
 }
 
 // ---------------------------------------------------------------------------------------------
-template <typename T, int D, int G>
+template <typename T, int D, int G, bool ROPE>
 __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, const T* __restrict__ q_in,
                                                                      const T* __restrict__ k_in,
                                                                      const T* __restrict__ v_in,
@@ -700,7 +779,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
                                                                      int32_t* __restrict__ n_retained,
                                                                      int32_t* __restrict__ evicted) {
   constexpr int THREADS = FUSED_THREADS;
-  using St = typename PickStream<T, D, G, THREADS>::type;
+  using St = typename PickStream<T, D, G, THREADS, ROPE>::type;
   constexpr int WAVES = St::WAVES;
   constexpr int EP = 5 * 1024 / THREADS;       // covers budgets up to 5119 from registers
   extern __shared__ float smem[];
@@ -789,12 +868,12 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
   }
 }
 
-template <typename T, int D, int G>
+template <typename T, int D, int G, bool ROPE>
 __global__ __launch_bounds__(SPLIT_THREADS) void decode_split_kernel(Params p, const T* __restrict__ q_in,
                                                                      const T* __restrict__ k_in,
                                                                      const T* __restrict__ v_in) {
   constexpr int THREADS = SPLIT_THREADS;
-  using St = typename PickStream<T, D, G, THREADS>::type;
+  using St = typename PickStream<T, D, G, THREADS, ROPE>::type;
   constexpr int WAVES = St::WAVES;
   extern __shared__ float smem[];
   float* sm_acc = smem;
@@ -910,24 +989,26 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, c
   }
 }
 
-template <typename T, int D, int G>
+template <typename T, int D, int G, bool ROPE>
 int launch_decode_g(const Params& p, const void* q, const void* k, const void* v, float* out, int32_t* retained,
                     int32_t* n_retained, int32_t* evicted, hipStream_t s) {
   const T* qt = (const T*)q;
   const T* kt = (const T*)k;
   const T* vt = (const T*)v;
   if (p.nsplit == 1) {
-    const size_t lds = (PickStream<T, D, G, FUSED_THREADS>::type::LDS_FLOATS_FIXED + (size_t)G * p.cap) * sizeof(float);
+    using St = typename PickStream<T, D, G, FUSED_THREADS, ROPE>::type;
+    const size_t lds = (St::LDS_FLOATS_FIXED + (size_t)St::LDS_WORDS_PER_ROW * p.cap) * sizeof(float);
     if (lds > LDS_LIMIT) return TREEKV_EUNSUPPORTED;
-    auto kern = decode_fused_kernel<T, D, G>;
+    auto kern = decode_fused_kernel<T, D, G, ROPE>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return TREEKV_EHIP;
     hipLaunchKernelGGL(kern, dim3(p.U), dim3(FUSED_THREADS), lds, s, p, qt, kt, vt, out, retained, n_retained, evicted);
   } else {
-    const size_t lds = (PickStream<T, D, G, SPLIT_THREADS>::type::LDS_FLOATS_FIXED + (size_t)G * p.rows_per_split) * sizeof(float);
+    using St = typename PickStream<T, D, G, SPLIT_THREADS, ROPE>::type;
+    const size_t lds = (St::LDS_FLOATS_FIXED + (size_t)St::LDS_WORDS_PER_ROW * p.rows_per_split) * sizeof(float);
     if (lds > LDS_LIMIT) return TREEKV_EUNSUPPORTED;
-    auto kern = decode_split_kernel<T, D, G>;
+    auto kern = decode_split_kernel<T, D, G, ROPE>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return TREEKV_EHIP;
@@ -950,26 +1031,40 @@ int launch_decode_g(const Params& p, const void* q, const void* k, const void* v
 template <typename T, int D>
 int launch_decode_d(const Params& p, const void* q, const void* k, const void* v, float* out, int32_t* retained,
                     int32_t* n_retained, int32_t* evicted, hipStream_t s) {
+  if (p.flags & TREEKV_POSITION_RERANK) {
+    switch (p.G) {
+      case 1: return launch_decode_g<T, D, 1, true>(p, q, k, v, out, retained, n_retained, evicted, s);
+      case 2: return launch_decode_g<T, D, 2, true>(p, q, k, v, out, retained, n_retained, evicted, s);
+      case 4: return launch_decode_g<T, D, 4, true>(p, q, k, v, out, retained, n_retained, evicted, s);
+      case 8: return launch_decode_g<T, D, 8, true>(p, q, k, v, out, retained, n_retained, evicted, s);
+      default: return TREEKV_EUNSUPPORTED;
+    }
+  }
   switch (p.G) {
-    case 1: return launch_decode_g<T, D, 1>(p, q, k, v, out, retained, n_retained, evicted, s);
-    case 2: return launch_decode_g<T, D, 2>(p, q, k, v, out, retained, n_retained, evicted, s);
-    case 4: return launch_decode_g<T, D, 4>(p, q, k, v, out, retained, n_retained, evicted, s);
-    case 8: return launch_decode_g<T, D, 8>(p, q, k, v, out, retained, n_retained, evicted, s);
+    case 1: return launch_decode_g<T, D, 1, false>(p, q, k, v, out, retained, n_retained, evicted, s);
+    case 2: return launch_decode_g<T, D, 2, false>(p, q, k, v, out, retained, n_retained, evicted, s);
+    case 4: return launch_decode_g<T, D, 4, false>(p, q, k, v, out, retained, n_retained, evicted, s);
+    case 8: return launch_decode_g<T, D, 8, false>(p, q, k, v, out, retained, n_retained, evicted, s);
     default: return TREEKV_EUNSUPPORTED;
   }
 }
 
 // LDS bytes the streaming kernel of the current shape (fused when nsplit == 1) asks for; 0 if no kernel exists.
+template <typename T, int D, int G, bool ROPE>
+size_t stream_lds_g(const Params& p) {
+  using Sf = typename PickStream<T, D, G, FUSED_THREADS, ROPE>::type;
+  using Ss = typename PickStream<T, D, G, SPLIT_THREADS, ROPE>::type;
+  return (p.nsplit == 1 ? Sf::LDS_FLOATS_FIXED + (size_t)Sf::LDS_WORDS_PER_ROW * p.cap
+                        : Ss::LDS_FLOATS_FIXED + (size_t)Ss::LDS_WORDS_PER_ROW * p.rows_per_split) * sizeof(float);
+}
 template <typename T, int D>
 size_t stream_lds_d(const Params& p) {
-  auto bytes = [&](size_t fixed_fused, size_t fixed_split) {
-    return (p.nsplit == 1 ? fixed_fused + (size_t)p.G * p.cap : fixed_split + (size_t)p.G * p.rows_per_split) * sizeof(float);
-  };
+  const bool rope = (p.flags & TREEKV_POSITION_RERANK) != 0;
   switch (p.G) {
-    case 1: return bytes(PickStream<T, D, 1, FUSED_THREADS>::type::LDS_FLOATS_FIXED, PickStream<T, D, 1, SPLIT_THREADS>::type::LDS_FLOATS_FIXED);
-    case 2: return bytes(PickStream<T, D, 2, FUSED_THREADS>::type::LDS_FLOATS_FIXED, PickStream<T, D, 2, SPLIT_THREADS>::type::LDS_FLOATS_FIXED);
-    case 4: return bytes(PickStream<T, D, 4, FUSED_THREADS>::type::LDS_FLOATS_FIXED, PickStream<T, D, 4, SPLIT_THREADS>::type::LDS_FLOATS_FIXED);
-    case 8: return bytes(PickStream<T, D, 8, FUSED_THREADS>::type::LDS_FLOATS_FIXED, PickStream<T, D, 8, SPLIT_THREADS>::type::LDS_FLOATS_FIXED);
+    case 1: return rope ? stream_lds_g<T, D, 1, true>(p) : stream_lds_g<T, D, 1, false>(p);
+    case 2: return rope ? stream_lds_g<T, D, 2, true>(p) : stream_lds_g<T, D, 2, false>(p);
+    case 4: return rope ? stream_lds_g<T, D, 4, true>(p) : stream_lds_g<T, D, 4, false>(p);
+    case 8: return rope ? stream_lds_g<T, D, 8, true>(p) : stream_lds_g<T, D, 8, false>(p);
     default: return 0;
   }
 }

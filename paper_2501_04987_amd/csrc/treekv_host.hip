@@ -53,6 +53,7 @@ size_t carve(Params& p, char* base) {
     p.pp_stat = (float*)take(U * (size_t)PROMPT_MAX_SPLITS * 128 * 2 * 4);
     p.pp_kept = (int*)take(U * (size_t)p.budget * 4);
   }
+  if (p.flags & TREEKV_POSITION_RERANK) p.rope_tab = (float2*)take(cap * (size_t)(p.D / 2) * sizeof(float2));
   return off;
 }
 
@@ -76,6 +77,16 @@ __global__ void reset_kernel(Params p) {
   uint4* Vz = reinterpret_cast<uint4*>(p.V) + (size_t)unit * vecs;
   for (size_t i = threadIdx.x; i < vecs; i += blockDim.x) Kz[i] = Vz[i] = make_uint4(0, 0, 0, 0);
   if (threadIdx.x < META_STRIDE) meta[threadIdx.x] = 0;
+}
+
+// (cos, sin) of distance * base^(-2i/D) for every distance two cached tokens can have, in double precision.
+__global__ void rope_table_kernel(Params p) {
+  const int n = p.cap * (p.D / 2);
+  for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < n; x += gridDim.x * blockDim.x) {
+    const int dist = x / (p.D / 2), i = x % (p.D / 2);
+    const double angle = (double)dist * pow((double)p.rope_base, -2.0 * (double)i / (double)p.D);
+    p.rope_tab[x] = make_float2((float)cos(angle), (float)sin(angle));
+  }
 }
 
 __global__ void scores_kernel(Params p, float* __restrict__ scores) {
@@ -119,6 +130,8 @@ int check_launch() { return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV
 
 int launch_reset(const Params& p, hipStream_t s) {
   hipLaunchKernelGGL(reset_kernel, dim3(p.U), dim3(256), 0, s, p);
+  if (p.flags & TREEKV_POSITION_RERANK)
+    hipLaunchKernelGGL(rope_table_kernel, dim3((p.cap * (p.D / 2) + 255) / 256), dim3(256), 0, s, p);
   return check_launch();
 }
 
@@ -177,7 +190,9 @@ int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg_in) {
   if (c.q_heads % c.kv_heads != 0) return TREEKV_EINVAL;
   if (c.n_sink < 0 || c.n_recent < 0 || c.budget - c.n_sink - c.n_recent < 1) return TREEKV_EINVAL;
   if (c.dtype != TREEKV_BF16 && c.dtype != TREEKV_F32) return TREEKV_EINVAL;
-  if (c.flags & ~(TREEKV_KEEP_LEFT | TREEKV_SCORE_ACCUMULATED)) return TREEKV_EINVAL;
+  if (c.flags & ~(TREEKV_KEEP_LEFT | TREEKV_SCORE_ACCUMULATED | TREEKV_POSITION_RERANK)) return TREEKV_EINVAL;
+  if (!(c.rope_base >= 0.0f) || isinf(c.rope_base)) return TREEKV_EINVAL;
+  if (c.rope_base == 0.0f) c.rope_base = 10000.0f;
   if (c.max_chunk < 0 || c.kv_splits < 0 || c.kv_splits > 64) return TREEKV_EINVAL;
   if (!(c.softmax_scale >= 0.0f) || isinf(c.softmax_scale)) return TREEKV_EINVAL;
   if (c.head_dim != 64 && c.head_dim != 128) return TREEKV_EUNSUPPORTED;
@@ -201,6 +216,7 @@ int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg_in) {
   p.B = c.batch; p.H = c.q_heads; p.Hkv = c.kv_heads; p.G = G; p.D = c.head_dim; p.U = c.batch * c.kv_heads;
   p.dtype = c.dtype; p.flags = c.flags; p.nsplit = c.kv_splits; p.max_chunk = c.max_chunk;
   p.max_prompt = c.max_prompt;
+  p.rope_base = c.rope_base;
   p.scale_log2e = c.softmax_scale * 1.4426950408889634f;
   // a unit whose logits do not fit one workgroup's LDS is split further
   for (;;) {
@@ -265,6 +281,7 @@ int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const vo
   if (!ctx || !Q || !K || !V || !out || !retained) return TREEKV_EINVAL;
   if (len < 1 || len > ctx->cfg.max_chunk) return TREEKV_EINVAL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out)) return TREEKV_EINVAL;
+  if (ctx->cfg.flags & TREEKV_POSITION_RERANK) return TREEKV_EUNSUPPORTED;
   if (!ctx->bound) return TREEKV_ENOWS;
   return record_hip(ctx, tkv::launch_prefill(ctx->p, Q, K, V, len, (float*)out, retained, n_retained, evicted,
                                              (hipStream_t)stream));
@@ -279,6 +296,7 @@ int treekv_prefill_prompt(treekv_ctx* ctx, const void* Qw, const void* K, const 
   const int cb = c.budget / block, sink_b = (c.n_sink + block - 1) / block, recent_b = (c.n_recent + block - 1) / block;
   if (cb - sink_b - recent_b < 1) return TREEKV_EINVAL;
   if (!aligned16(Qw) || !aligned16(K) || !aligned16(V)) return TREEKV_EINVAL;
+  if (c.flags & TREEKV_POSITION_RERANK) return TREEKV_EUNSUPPORTED;
   if (!ctx->bound) return TREEKV_ENOWS;
   // the window's queries of one KV head's group are the rows of one matrix operand set
   if (block * (c.q_heads / c.kv_heads) > 128) return TREEKV_EUNSUPPORTED;

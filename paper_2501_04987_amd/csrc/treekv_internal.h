@@ -58,6 +58,9 @@ struct Params {
   float* pp_beta;           // [U][T / block] block scores of the prompt in flight
   float* pp_stat;           // [U][PROMPT_MAX_SPLITS][128][2] per slice and window query row: max, sum
   int* pp_kept;             // [U][budget] kept blocks, ascending
+  // position re-assignment (only with TREEKV_POSITION_RERANK)
+  float rope_base;
+  float2* rope_tab;         // [cap][D/2] (cos, sin) of distance * rope_base^(-2i/D)
 };
 constexpr int PROMPT_MAX_SPLITS = 64;
 

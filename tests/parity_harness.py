@@ -51,7 +51,7 @@ def gpu_decode_run(kv, Qd, Kd, Vd, sample_steps=()):
 def oracle_cfg(kv, **over):
     c = kv.cfg
     d = dict(budget=c.budget, G=c.q_heads // c.kv_heads, d=c.head_dim, n_sink=c.n_sink, n_recent=c.n_recent,
-             scale=float(c.softmax_scale), flags=int(c.flags))
+             scale=float(c.softmax_scale), flags=int(c.flags), rope_base=float(c.rope_base))
     d.update(over)
     return d
 
@@ -148,7 +148,8 @@ def run_schedule(oracle, kv, Q, K, V, schedule, dtype="bf16", units=None, check_
     ocfg = oracle_cfg(kv)
     if streams is None:
         streams = {u: oracle.OracleStream(ocfg["budget"], G, c.head_dim, n_sink=ocfg["n_sink"],
-                                          n_recent=ocfg["n_recent"], scale=ocfg["scale"], flags=ocfg["flags"])
+                                          n_recent=ocfg["n_recent"], scale=ocfg["scale"], flags=ocfg["flags"],
+                                          rope_base=ocfg["rope_base"])
                    for u in units}
     tol = TOL[dtype]
     Qd, Kd, Vd = to_device(Q, dtype), to_device(K, dtype), to_device(V, dtype)

@@ -48,7 +48,7 @@ def _init(binding, **kw):
 def test_config_validation(binding):
     lib = binding.load()
     bad = [dict(budget=0), dict(q_heads=6, kv_heads=4), dict(n_sink=40, n_recent=24), dict(dtype=7),
-           dict(flags=8), dict(n_sink=-1), dict(softmax_scale=float("nan")), dict(kv_splits=100)]
+           dict(flags=16), dict(n_sink=-1), dict(softmax_scale=float("nan")), dict(kv_splits=100)]
     for kw in bad:
         rc, h = _init(binding, **kw)
         assert rc == binding.TREEKV_EINVAL and not h.value, kw
@@ -125,9 +125,30 @@ def test_prompt_compression_host_checks(binding):
     assert lib.treekv_prefill_prompt(h1, None, one, one, 1024, 32, one, None, None, None, None) == binding.TREEKV_EINVAL
     assert lib.treekv_prefill_prompt(h1, C.c_void_p(0x1008), one, one, 1024, 32, one, None, None, None, None) == binding.TREEKV_EINVAL
     assert call(h1, 1024, 32) == binding.TREEKV_ENOWS             # valid arguments, but no workspace bound
-    for bad_flags in (2, 8, 16):
+    for bad_flags in (2, 16, 32):
         assert _init(binding, flags=bad_flags)[0] == binding.TREEKV_EINVAL
     rc, h2 = _init(binding, flags=binding.TREEKV_KEEP_LEFT | binding.TREEKV_SCORE_ACCUMULATED)
     assert rc == 0
     for h in (h0, h1, h2):
+        lib.treekv_destroy(h)
+
+
+def test_position_rerank_host_checks(binding):
+    """TREEKV_POSITION_RERANK: the rotary table is part of the workspace, the base defaults to 10000, and the two
+    prefill calls refuse such a context before anything is enqueued."""
+    lib = binding.load()
+    rc0, h0 = _init(binding, budget=256, n_sink=4, n_recent=60, max_prompt=1024)
+    rc1, h1 = _init(binding, budget=256, n_sink=4, n_recent=60, max_prompt=1024, flags=binding.TREEKV_POSITION_RERANK)
+    assert rc0 == 0 and rc1 == 0
+    extra = lib.treekv_workspace_bytes(h1) - lib.treekv_workspace_bytes(h0)
+    assert extra >= 257 * 64 * 8                       # (cos, sin) per distance 0..budget and plane, head_dim 128
+    cfg = binding.treekv_config()
+    lib.treekv_get_config(h1, C.byref(cfg))
+    assert cfg.rope_base == 10000.0 and cfg.flags == binding.TREEKV_POSITION_RERANK
+    one = C.c_void_p(0x1000)
+    assert lib.treekv_prefill_prompt(h1, one, one, one, 1024, 32, one, None, None, None, None) == binding.TREEKV_EUNSUPPORTED
+    assert lib.treekv_prefill_chunk(h1, one, one, one, 16, one, one, None, None, None) == binding.TREEKV_EUNSUPPORTED
+    assert _init(binding, flags=binding.TREEKV_POSITION_RERANK, rope_base=-1.0)[0] == binding.TREEKV_EINVAL
+    assert _init(binding, flags=binding.TREEKV_POSITION_RERANK, rope_base=float("nan"))[0] == binding.TREEKV_EINVAL
+    for h in (h0, h1):
         lib.treekv_destroy(h)

@@ -1,0 +1,110 @@
+"""GPU parity: decode steps with positions re-assigned to cache ranks (Section 4.1, "Position Encoding") through
+the C ABI against the CPU oracle: q and k arrive without positional encoding, the rotary encoding of the in-cache
+ranks is applied inside the step."""
+import numpy as np
+import pytest
+
+from paper_2501_04987_amd import inputs
+from tests import parity_harness as ph
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2501_04987_amd import binding as b
+
+    b.load()
+    return b
+
+
+def _run(binding, oracle, *, T, B, H, Hkv, d, dtype, budget, n_sink, n_recent, seed, kv_splits=0, rope_base=0.0,
+         flags=0, kind=None, every_step=True, units=None, sample=None):
+    G = H // Hkv
+    kind = kind or ("lowrank" if dtype == "bf16" else "iid")
+    Q, K, V = inputs.batch_streams(kind, seed, T, B, Hkv, G, d, dtype=dtype)
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype=dtype, n_sink=n_sink, n_recent=n_recent,
+                        flags=flags | binding.TREEKV_POSITION_RERANK, kv_splits=kv_splits, rope_base=rope_base)
+    steps = range(T) if every_step else (sample or [T - 1])
+    gpu = ph.gpu_decode_run(kv, ph.to_device(Q, dtype), ph.to_device(K, dtype), ph.to_device(V, dtype), steps)
+    rep = ph.compare_decode(oracle, kv, Q, K, V, gpu, units=units, dtype=dtype)
+    rep["score_err"] = ph.compare_scores(kv, rep["results"], dtype)
+    assert rep["flagged"] <= max(2, rep["decisions"] // 500), rep["flagged"]
+    print(f"  flagged={rep['flagged']}/{rep['decisions']} max_err={rep['max_err']:.2e} score_err={rep['score_err']:.2e}")
+    return kv, gpu, rep
+
+
+@pytest.mark.parametrize("splits", [1, 3])
+def test_rerank_bf16_ragged_budget(binding, oracle, splits):
+    """Budget 203 with sinks and a recent ring that wraps several times; one workgroup per unit and three."""
+    _run(binding, oracle, T=650, B=1, H=3, Hkv=3, d=128, dtype="bf16", budget=203, n_sink=4, n_recent=98,
+         kv_splits=splits, seed=31)
+
+
+def test_rerank_pure_algorithm1(binding, oracle):
+    """No sinks, no recent window: the new token itself enters the tree region; a short rotary period (base 50)."""
+    _run(binding, oracle, T=700, B=2, H=2, Hkv=2, d=128, dtype="bf16", budget=160, n_sink=0, n_recent=0, kv_splits=4,
+         seed=32, rope_base=50.0)
+
+
+@pytest.mark.parametrize("G,d,dtype,splits", [(4, 64, "bf16", 2), (2, 128, "f32", 1), (8, 64, "f32", 2),
+                                              (8, 128, "bf16", 1), (1, 64, "f32", 1)])
+def test_rerank_grouped_queries_and_types(binding, oracle, G, d, dtype, splits):
+    _run(binding, oracle, T=400, B=2, H=2 * G, Hkv=2, d=d, dtype=dtype, budget=96, n_sink=2, n_recent=30,
+         kv_splits=splits, seed=33)
+
+
+def test_rerank_differs_from_plain_and_from_original_positions(binding, oracle):
+    """The same stream with and without the flag: identical while nothing could differ (one token), different after;
+    and once tokens have been evicted the outputs differ from rotary attention at the ORIGINAL positions (computed
+    here from the retained positions the step returns)."""
+    import torch
+
+    T, H, d, budget = 80, 2, 64, 24
+    Q, K, V = inputs.batch_streams("iid", 34, T, 1, H, 1, d, dtype="f32")
+    Qd, Kd, Vd = (ph.to_device(x, "f32") for x in (Q, K, V))
+    a = binding.TreeKV(budget, H, d, kv_heads=H, dtype="f32", n_sink=2, n_recent=6)
+    b = binding.TreeKV(budget, H, d, kv_heads=H, dtype="f32", n_sink=2, n_recent=6, flags=binding.TREEKV_POSITION_RERANK)
+    ga, gb = ph.gpu_decode_run(a, Qd, Kd, Vd, range(T)), ph.gpu_decode_run(b, Qd, Kd, Vd, range(T))
+    assert np.array_equal(ga["out"][0], gb["out"][0])
+    assert np.abs(ga["out"][5] - gb["out"][5]).max() > 1e-3
+    t = T - 1
+    kept = list(gb["retained"][t - 1][0, 0]) + [t]            # what step t attends: the cache after step t-1, and t
+    theta = 10000.0 ** (-2.0 * np.arange(d // 2) / d)
+
+    def rot(x, pos):
+        z = (x[..., 0::2] + 1j * x[..., 1::2]) * np.exp(1j * np.multiply.outer(pos, theta))
+        return z
+
+    def attend(pos_k, pos_q):
+        kz, qz = rot(K[kept, 0, 0], np.array(pos_k, dtype=np.float64)), rot(Q[t, 0, 0], float(pos_q))
+        lg = np.real(kz.conj() @ qz) / np.sqrt(d)
+        w = np.exp(lg - lg.max())
+        return (w / w.sum()) @ V[kept, 0, 0]
+
+    got = gb["out"][t][0, 0]
+    assert np.abs(got - attend(np.arange(len(kept)), len(kept) - 1)).max() < 1e-5
+    assert np.abs(got - attend(kept, t)).max() > 1e-3
+
+
+def test_rerank_prefill_calls_refuse(binding):
+    import torch
+
+    kv = binding.TreeKV(64, 2, 64, kv_heads=2, n_sink=2, n_recent=6, flags=binding.TREEKV_POSITION_RERANK, max_prompt=256)
+    z = torch.zeros(1, 256, 2, 64, dtype=torch.bfloat16, device="cuda")
+    out, ret, nret, ev = kv.new_outputs(16)
+    with pytest.raises(binding.TreeKVError) as e:
+        kv.prefill_chunk(z[:, :16], z[:, :16], z[:, :16], 16, out, ret, nret, ev)
+    assert e.value.status == binding.TREEKV_EUNSUPPORTED
+    with pytest.raises(binding.TreeKVError) as e:
+        kv.prefill_prompt(z[:, :16], z, z, 256, 16, ret)
+    assert e.value.status == binding.TREEKV_EUNSUPPORTED
+
+
+def test_rerank_llama7b_shaped_layer_sampled(binding, oracle):
+    """32 heads x 128, budget 1024 (4 + 512 + 508), 3000 steps; four heads checked at every step against the oracle."""
+    _run(binding, oracle, T=3000, B=1, H=32, Hkv=32, d=128, dtype="bf16", budget=1024, n_sink=4, n_recent=508,
+         seed=35, units=[(0, 0), (0, 9), (0, 21), (0, 31)], every_step=False, sample=[1500, 2999])
