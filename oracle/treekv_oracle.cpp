@@ -63,6 +63,17 @@
 //    paper does not say which flavour its models use; a model that pairs (i, i + d/2) instead
 //    permutes the head dimension of q and k accordingly.  Decode steps only.
 //
+//  * Wavelet analysis of Sections 3.2-3.3 (tko_wavelet_components, stateless): the signal is
+//    s[n] = a[n] * v[n] (one row per position, d columns); every column is decomposed along the
+//    sequence by L levels of the Haar filter pair (filtering, then down-sampling by two), and
+//    Rec(D_l) is rebuilt from the level-l detail coefficients alone by l single-level
+//    reconstructions, the first with a zero approximation, the others with zero details.
+//    Positions and coefficients are counted from 1 as in the printed reconstruction formula, so
+//    coefficient n belongs to the signal pair (2n-1, 2n).  "Magnitude" is |Rec(D_l)[n]| averaged
+//    over the d columns (the paper averages "across all layers, heads, and samples"; the columns
+//    are averaged too, the figure showing one curve per level).  The sequence length must be a
+//    multiple of 2^L (the paper's 512 with L = 5 is; it says nothing about other lengths).
+//
 // Near-tie handling for parity runs: every decision reports its relative
 // margin |Sbar_l - Sbar_r| / max(Sbar_l, Sbar_r).  A caller may pass the
 // position another implementation evicted; the oracle adopts it only when
@@ -120,6 +131,30 @@ std::vector<double> rotary(const double* x, int d, long long p, double base) {
     y[2 * i + 1] = x[2 * i] * si + x[2 * i + 1] * co;
   }
   return y;
+}
+
+// Single-level decomposition (Section 3.2): A[n] = sum_k s[k] g[2n-k], D[n] = sum_k s[k] h[2n-k], indices from 1,
+// with the Haar pair g = (r, r), h = (-r, r) on taps 0 and 1, r = sqrt(2)/2.
+void haar_decompose(const std::vector<double>& s, std::vector<double>& A, std::vector<double>& D) {
+  const double r = std::sqrt(2.0) / 2.0;
+  const double g[2] = {r, r}, h[2] = {-r, r};
+  const size_t half = s.size() / 2;
+  A.assign(half, 0.0);
+  D.assign(half, 0.0);
+  for (size_t n = 1; n <= half; ++n)
+    for (size_t k = 1; k <= s.size(); ++k) {
+      const long long tap = 2 * (long long)n - (long long)k;
+      if (tap == 0 || tap == 1) { A[n - 1] += s[k - 1] * g[tap]; D[n - 1] += s[k - 1] * h[tap]; }
+    }
+}
+
+// Single-level reconstruction R(A, D)[n], n from 1: odd n takes (A + D) of coefficient (n+1)/2, even n (A - D) of n/2.
+std::vector<double> haar_reconstruct(const std::vector<double>& A, const std::vector<double>& D) {
+  const double r = std::sqrt(2.0) / 2.0;
+  std::vector<double> out(2 * A.size());
+  for (size_t n = 1; n <= out.size(); ++n)
+    out[n - 1] = (n % 2 == 1) ? r * (A[(n + 1) / 2 - 1] + D[(n + 1) / 2 - 1]) : r * (A[n / 2 - 1] - D[n / 2 - 1]);
+  return out;
 }
 
 // Lines 9-17 of Algorithm 1 on a list of token handles `order` whose scores are sbar[handle].
@@ -424,6 +459,45 @@ int tko_prefill_prompt(void* h, const double* Qw, const double* K, const double*
   }
   s.t = T;
   s.idx = 1;
+  return 0;
+}
+
+// Wavelet analysis of Sections 3.2-3.3 for one head at one generation step.
+//   a [t]: attention weights; V [t][d]; levels L >= 1 with 2^L dividing t.
+//   magnitude [L][t]: row l-1 holds |Rec(D_l)[n]| averaged over the d columns.
+//   coeffs (may be null) [d][t]: per column the list [A_L, D_L, D_{L-1}, .., D_1] (lengths t/2^L, t/2^L, .., t/2).
+//   rec_sum (may be null) [d][t]: per column Rec(A_L) + sum_l Rec(D_l), which must give the signal back.
+// Returns 0, or -1 if the sizes do not fit.
+int tko_wavelet_components(const double* a, const double* V, int t, int d, int levels, double* magnitude,
+                           double* coeffs, double* rec_sum) {
+  if (t < 1 || d < 1 || levels < 1 || levels > 30 || t % (1 << levels) != 0) return -1;
+  for (size_t i = 0; i < (size_t)levels * t; ++i) magnitude[i] = 0.0;
+  for (int e = 0; e < d; ++e) {
+    std::vector<double> sig((size_t)t);
+    for (int n = 0; n < t; ++n) sig[n] = a[n] * V[(size_t)n * d + e];       // s = a^T o V, column e
+    std::vector<std::vector<double>> D((size_t)levels + 1);
+    std::vector<double> A = sig, A_next;
+    for (int l = 1; l <= levels; ++l) { haar_decompose(A, A_next, D[l]); A.swap(A_next); }
+    if (coeffs) {
+      double* c = coeffs + (size_t)e * t;
+      size_t o = 0;
+      for (double x : A) c[o++] = x;
+      for (int l = levels; l >= 1; --l) for (double x : D[l]) c[o++] = x;
+    }
+    std::vector<double> total((size_t)t, 0.0);
+    for (int l = 0; l <= levels; ++l) {       // l = 0 stands for Rec(A_L)
+      const int depth = l == 0 ? levels : l;
+      std::vector<double> rec;
+      if (l == 0) rec = haar_reconstruct(A, std::vector<double>(A.size(), 0.0));
+      else rec = haar_reconstruct(std::vector<double>(D[l].size(), 0.0), D[l]);
+      for (int up = depth - 1; up >= 1; --up) rec = haar_reconstruct(rec, std::vector<double>(rec.size(), 0.0));
+      for (int n = 0; n < t; ++n) {
+        total[n] += rec[n];
+        if (l >= 1) magnitude[(size_t)(l - 1) * t + n] += std::fabs(rec[n]) / (double)d;
+      }
+    }
+    if (rec_sum) for (int n = 0; n < t; ++n) rec_sum[(size_t)e * t + n] = total[n];
+  }
   return 0;
 }
 

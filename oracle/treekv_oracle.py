@@ -62,6 +62,8 @@ def _load():
         lib.tko_prefill_chunk.argtypes = [C.c_void_p, dp, dp, dp, C.c_int, dp, lp, C.c_double, lp, dp, ip, ip]
         lib.tko_prefill_prompt.restype = C.c_int
         lib.tko_prefill_prompt.argtypes = [C.c_void_p, dp, dp, dp, C.c_int, C.c_int, lp, C.c_double, lp, dp, lp, dp, dp]
+        lib.tko_wavelet_components.restype = C.c_int
+        lib.tko_wavelet_components.argtypes = [dp, dp, C.c_int, C.c_int, C.c_int, dp, dp, dp]
         _lib = lib
     return _lib
 
@@ -215,6 +217,22 @@ def run_decode_stream(cfg: dict, q, k, v, *, forced=None, follow_thresh: float =
                              _lptr(fp) if fp is not None else None, float(follow_thresh), _lptr(ev),
                              _dptr(mg), _lptr(counts))
     return dict(out=out, evicted=ev, margins=mg, adopted=int(counts[0]), disagreed=int(counts[1]), stream=s)
+
+
+def wavelet_components(a, V, levels: int, *, want_coeffs: bool = False):
+    """Sections 3.2-3.3 for one head at one step: a [t], V [t, d] -> magnitude [levels, t] of Rec(D_l), averaged
+    over the d columns; with want_coeffs also (coeffs [d, t] = [A_L, D_L, .., D_1] per column, rec_sum [d, t])."""
+    a = np.ascontiguousarray(a, np.float64)
+    V = np.ascontiguousarray(V, np.float64)
+    t, d = V.shape
+    mag = np.empty((levels, t), np.float64)
+    co = np.empty((d, t), np.float64) if want_coeffs else None
+    rs = np.empty((d, t), np.float64) if want_coeffs else None
+    rc = _load().tko_wavelet_components(_dptr(a.reshape(t)), _dptr(V), t, d, int(levels), _dptr(mag),
+                                        _dptr(co) if want_coeffs else None, _dptr(rs) if want_coeffs else None)
+    if rc != 0:
+        raise ValueError("wavelet_components: the length must be a multiple of 2**levels")
+    return (mag, co, rs) if want_coeffs else mag
 
 
 def run_many(fn, jobs, workers: int | None = None):

@@ -86,3 +86,21 @@ def test_random_prompt_then_chunks_and_steps(binding, oracle, seed):
     st = ph.run_prompt(oracle, kv, Q, K, V, T, block, 0)
     st2 = ph.run_schedule(oracle, kv, Q, K, V, sched, dtype="bf16", streams=st["streams"], t_start=T)
     ph.compare_scores(kv, st2["results"], "bf16")
+
+
+@pytest.mark.parametrize("seed", range(80, 104))
+def test_random_decode_streams_with_reassigned_positions(binding, oracle, seed):
+    """Decode streams with positions re-assigned to cache ranks: both storage types, every group size, random
+    layouts, split counts and rotary bases; every step compared."""
+    rng, c = _draw(seed)
+    dtype = "bf16" if seed % 2 == 0 else "f32"
+    base = float(rng.choice([0.0, 30.0, 500000.0]))
+    flags = binding.TREEKV_POSITION_RERANK | (binding.TREEKV_SCORE_ACCUMULATED if seed % 5 == 0 else 0)
+    T = 2 * c["budget"] + 50
+    Q, K, V = inputs.batch_streams("lowrank" if dtype == "bf16" else "iid", seed, T, c["B"], c["Hkv"], c["G"], c["d"],
+                                   dtype=dtype)
+    kv = binding.TreeKV(c["budget"], c["Hkv"] * c["G"], c["d"], kv_heads=c["Hkv"], batch=c["B"], dtype=dtype,
+                        n_sink=c["n_sink"], n_recent=c["n_recent"], kv_splits=c["splits"], flags=flags, rope_base=base)
+    st = ph.run_schedule(oracle, kv, Q, K, V, [0] * T, dtype=dtype)
+    ph.compare_scores(kv, st["results"], dtype)
+    assert st["flagged"] <= max(2, st["decisions"] // 200), (c, st["flagged"])

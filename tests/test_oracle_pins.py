@@ -841,3 +841,61 @@ def test_rerank_brute_force(oracle):
         _, S, C = s.state()
         np.testing.assert_allclose(S, S_b, rtol=1e-10)
         assert list(C) == C_b
+
+
+# --------------------------------------------------------------------------- #
+# Wavelet analysis (Sections 3.2-3.3)
+# --------------------------------------------------------------------------- #
+def _haar_matrix(t, levels):
+    """Orthonormal analysis matrix of the multi-level Haar transform, rows ordered [A_L, D_L, .., D_1], built
+    from Kronecker products (textbook construction), independent of the filter-bank code."""
+    r = math.sqrt(0.5)
+    rows_d = []
+    avg = np.eye(t)
+    for l in range(1, levels + 1):
+        n = avg.shape[0] // 2
+        lo = np.kron(np.eye(n), np.array([[r, r]])) @ avg
+        hi = np.kron(np.eye(n), np.array([[r, -r]])) @ avg
+        rows_d.append(hi)
+        avg = lo
+    return np.vstack([avg] + rows_d[::-1])
+
+
+@pytest.mark.parametrize("t,d,levels", [(32, 3, 5), (64, 2, 3), (96, 4, 5), (8, 1, 1)])
+def test_wavelet_decomposition_is_the_haar_transform(oracle, t, d, levels):
+    rng = np.random.default_rng(t + d)
+    a = rng.random(t)
+    a /= a.sum()
+    V = rng.standard_normal((t, d))
+    mag, co, rs = oracle.wavelet_components(a, V, levels, want_coeffs=True)
+    sig = a[:, None] * V
+    # the coefficient list equals the orthonormal Haar matrix applied to the signal (pair (2n-1, 2n), first minus
+    # second in the details), energy is preserved, and the components add up to the signal again
+    np.testing.assert_allclose(co.T, _haar_matrix(t, levels) @ sig, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose((co ** 2).sum(), (sig ** 2).sum(), rtol=1e-12)
+    np.testing.assert_allclose(rs.T, sig, rtol=1e-12, atol=1e-15)
+    # closed form: Rec(D_l) is constant in magnitude over a block of 2^l positions, 2^-l |first half - second half|
+    for l in range(1, levels + 1):
+        blk = sig.reshape(t >> l, 1 << l, d)
+        diff = np.abs(blk[:, : 1 << (l - 1)].sum(1) - blk[:, 1 << (l - 1):].sum(1)) / (1 << l)
+        np.testing.assert_allclose(mag[l - 1], np.repeat(diff.mean(-1), 1 << l), rtol=1e-11, atol=1e-16)
+
+
+def test_wavelet_special_signals(oracle):
+    t, levels = 64, 5
+    # a constant signal has no detail at any level
+    mag = oracle.wavelet_components(np.full(t, 1.0 / t), np.ones((t, 2)), levels)
+    assert np.abs(mag).max() < 1e-17
+    # an impulse at (1-based) position 1 shows in every level's first block with magnitude 2^-l
+    a = np.zeros(t)
+    a[0] = 1.0
+    mag = oracle.wavelet_components(a, np.ones((t, 1)), levels)
+    for l in range(1, levels + 1):
+        np.testing.assert_allclose(mag[l - 1, : 1 << l], 2.0 ** -l, rtol=1e-12)
+        assert np.all(mag[l - 1, 1 << l:] == 0.0)
+    # an alternating signal lives in level 1 only
+    mag = oracle.wavelet_components(np.ones(t), np.tile([[1.0], [-1.0]], (t // 2, 1)), levels)
+    np.testing.assert_allclose(mag[0], 1.0, rtol=1e-12)
+    assert np.abs(mag[1:]).max() < 1e-15
+    with pytest.raises(ValueError):
+        oracle.wavelet_components(np.ones(48), np.ones((48, 1)), 5)
