@@ -208,6 +208,36 @@ def bench_prompt(torch, binding, inputs, dev, calls=20, warm=3, layers=3):
                                  "kernels"}}
 
 
+def bench_wavelet(torch, binding, dev, calls=20, warm=3, samples=8, t=512, levels=5):
+    """The Haar analysis of Sections 3.2-3.3 in the figure's setting (5 levels at generation step 512) for
+    32 layers x 32 heads x `samples` sequences per call; a = softmax of random logits, V ~ N(0, 1) in bf16."""
+    heads = 32 * HEADS * samples
+    g = torch.Generator(device=dev).manual_seed(5)
+    a = torch.softmax(3.0 * torch.randn(heads, t, device=dev, generator=g), dim=-1).contiguous()
+    sets = [torch.randn(heads, t, HEAD_DIM, device=dev, generator=g).to(torch.bfloat16) for _ in range(2)]
+    per_head = torch.empty(heads, levels, t, dtype=torch.float32, device=dev)
+    mean = torch.empty(levels, t, dtype=torch.float32, device=dev)
+    for i in range(warm):
+        binding.wavelet_components(a, sets[i % 2], levels, per_head, mean)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(calls):
+        binding.wavelet_components(a, sets[i % 2], levels, per_head, mean)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / calls
+    # V and a read once, the per-head magnitudes written once and read once for the mean, the mean written
+    nbytes = heads * t * (HEAD_DIM * 2 + 4) + 2 * heads * levels * t * 4 + levels * t * 4
+    gbs = nbytes / (us * 1e-6) / 1e9
+    return {"workload": f"Haar analysis, {levels} levels, step {t}, {heads} heads (32 layers x {HEADS} heads x "
+                        f"{samples} samples) x {HEAD_DIM} dim, bf16 values",
+            "calls": calls, "us_per_call": us, "heads_per_s": heads / (us * 1e-6),
+            "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_call": nbytes,
+                         "note": "components kernel and mean kernel together"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -373,6 +403,8 @@ def main():
         res["prefill"] = bench_prefill(torch, binding, inputs, dev)
         torch.cuda.empty_cache()
         res["prompt"] = bench_prompt(torch, binding, inputs, dev)
+        torch.cuda.empty_cache()
+        res["wavelet"] = bench_wavelet(torch, binding, dev)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline()
     print(json.dumps(res))

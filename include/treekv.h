@@ -191,6 +191,24 @@ int treekv_scores(treekv_ctx* ctx, float* scores, void* stream);
  */
 int treekv_gather_kv(treekv_ctx* ctx, void* K_out, void* V_out, void* stream);
 
+/*
+ * treekv_wavelet_components - the analysis the method is motivated by (Sections 3.2-3.3), stateless.  For each
+ * of `heads` heads at one generation step the signal is s[n] = a[n] * v[n] (the information position n
+ * contributes to the attention output, Section 3.3); every column of s is decomposed along the sequence by
+ * `levels` levels of the Haar filter pair (Section 3.2) and Rec(D_l), the part of the signal carried by the
+ * level-l detail coefficients alone, is rebuilt; the result is its magnitude per position.
+ *   a [heads, t] float32: attention weights;  V [heads, t, d] of storage type `dtype`;  read only
+ *   per_head [heads, levels, t] float32: |Rec(D_l)[n]| averaged over the d columns (l = 1 first, the highest
+ *              frequency)
+ *   mean     [levels, t] float32 (may be NULL): per_head averaged over the heads (added in an order that
+ *              depends on the number of heads only: results repeat bit for bit)
+ * Positions pair up as (1,2), (3,4), .. counted from 1, as in the printed reconstruction formula.
+ * Errors: TREEKV_EINVAL for null pointers, sizes below 1 or a length 2^levels does not divide;
+ * TREEKV_EUNSUPPORTED for levels > 5, d other than 64 or 128, heads > 65535.
+ */
+int treekv_wavelet_components(const float* a, const void* V, int dtype, int heads, int t, int d, int levels,
+                              float* per_head, float* mean, void* stream);
+
 /* Static description of a status code. */
 const char* treekv_strerror(int status);
 

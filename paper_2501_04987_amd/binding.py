@@ -27,7 +27,7 @@ EXPORTS = [
     "treekv_init", "treekv_init_ex", "treekv_destroy", "treekv_get_config", "treekv_workspace_bytes",
     "treekv_bind_workspace", "treekv_reset", "treekv_decode_step", "treekv_prefill_chunk", "treekv_prefill_prompt",
     "treekv_scores",
-    "treekv_gather_kv", "treekv_strerror", "treekv_last_hip_error",
+    "treekv_gather_kv", "treekv_wavelet_components", "treekv_strerror", "treekv_last_hip_error",
 ]
 
 
@@ -69,6 +69,7 @@ def load() -> C.CDLL:
     lib.treekv_prefill_prompt.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, i32p, i32p, i32p, vp, vp]
     lib.treekv_scores.argtypes = [vp, vp, vp]
     lib.treekv_gather_kv.argtypes = [vp, vp, vp, vp]
+    lib.treekv_wavelet_components.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp]
     lib.treekv_strerror.argtypes = [C.c_int]
     lib.treekv_strerror.restype = C.c_char_p
     lib.treekv_last_hip_error.argtypes = [vp]
@@ -86,6 +87,26 @@ class TreeKVError(RuntimeError):
 
 def _ptr(t):
     return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def wavelet_components(a, V, levels: int, per_head=None, mean=None):
+    """treekv_wavelet_components on torch tensors: a [heads, t] float32, V [heads, t, d] bf16 or float32 ->
+    (per_head [heads, levels, t], mean [levels, t]), float32, on V's device and the current stream."""
+    import torch
+
+    lib = load()
+    heads, t, d = V.shape
+    dtype = {torch.bfloat16: TREEKV_BF16, torch.float32: TREEKV_F32}[V.dtype]
+    if per_head is None:
+        per_head = torch.empty(heads, levels, t, dtype=torch.float32, device=V.device)
+    if mean is None:
+        mean = torch.empty(levels, t, dtype=torch.float32, device=V.device)
+    assert a.dtype == torch.float32 and a.shape == (heads, t) and a.is_contiguous() and V.is_contiguous()
+    rc = lib.treekv_wavelet_components(_ptr(a), _ptr(V), dtype, heads, t, d, int(levels), _ptr(per_head), _ptr(mean),
+                                       C.c_void_p(torch.cuda.current_stream(V.device).cuda_stream))
+    if rc != TREEKV_OK:
+        raise TreeKVError(rc, "treekv_wavelet_components")
+    return per_head, mean
 
 
 class TreeKV:

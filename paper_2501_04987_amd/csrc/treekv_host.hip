@@ -318,6 +318,16 @@ int treekv_gather_kv(treekv_ctx* ctx, void* K_out, void* V_out, void* stream) {
   return record_hip(ctx, tkv::launch_gather_kv(ctx->p, K_out, V_out, (hipStream_t)stream));
 }
 
+int treekv_wavelet_components(const float* a, const void* V, int dtype, int heads, int t, int d, int levels,
+                              float* per_head, float* mean, void* stream) {
+  if (!a || !V || !per_head) return TREEKV_EINVAL;
+  if (dtype != TREEKV_BF16 && dtype != TREEKV_F32) return TREEKV_EINVAL;
+  if (heads < 1 || t < 1 || levels < 1 || levels > 30 || t % (1 << levels) != 0) return TREEKV_EINVAL;
+  if (!aligned16(V)) return TREEKV_EINVAL;
+  if (levels > 5 || (d != 64 && d != 128) || heads > 65535 || (long long)levels * t > (1ll << 30)) return TREEKV_EUNSUPPORTED;
+  return tkv::launch_wavelet(a, V, dtype, heads, t, d, levels, per_head, mean, (hipStream_t)stream);
+}
+
 const char* treekv_strerror(int status) {
   switch (status) {
     case TREEKV_OK: return "ok";

@@ -74,6 +74,8 @@ int launch_prefill(const Params& p, const void* Q, const void* K, const void* V,
 int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V, int T, int b, int32_t* retained,
                   int32_t* n_retained, int32_t* evicted_blocks, float* token_scores, hipStream_t s);
 size_t prompt_blocks_lds(int T, int b, int cb, int sink_b, int recent_b);
+int launch_wavelet(const float* a, const void* V, int dtype, int heads, int t, int d, int levels, float* per_head,
+                   float* mean, hipStream_t s);
 int launch_scores(const Params& p, float* scores, hipStream_t s);
 int launch_gather_kv(const Params& p, void* K_out, void* V_out, hipStream_t s);
 

@@ -152,3 +152,20 @@ def test_position_rerank_host_checks(binding):
     assert _init(binding, flags=binding.TREEKV_POSITION_RERANK, rope_base=float("nan"))[0] == binding.TREEKV_EINVAL
     for h in (h0, h1):
         lib.treekv_destroy(h)
+
+
+def test_wavelet_host_checks(binding):
+    lib = binding.load()
+    one = C.c_void_p(0x1000)
+    call = lambda a, V, dtype, heads, t, d, levels, out: lib.treekv_wavelet_components(a, V, dtype, heads, t, d, levels,
+                                                                                      out, None, None)
+    assert call(None, one, 0, 1, 64, 128, 5, one) == binding.TREEKV_EINVAL
+    assert call(one, one, 0, 1, 64, 128, 5, None) == binding.TREEKV_EINVAL
+    assert call(one, one, 5, 1, 64, 128, 5, one) == binding.TREEKV_EINVAL       # unknown storage type
+    assert call(one, one, 0, 0, 64, 128, 5, one) == binding.TREEKV_EINVAL
+    assert call(one, one, 0, 1, 48, 128, 5, one) == binding.TREEKV_EINVAL       # 32 does not divide 48
+    assert call(one, one, 0, 1, 64, 128, 0, one) == binding.TREEKV_EINVAL
+    assert call(one, C.c_void_p(0x1004), 0, 1, 64, 128, 5, one) == binding.TREEKV_EINVAL
+    assert call(one, one, 0, 1, 64, 128, 6, one) == binding.TREEKV_EUNSUPPORTED
+    assert call(one, one, 0, 1, 64, 96, 5, one) == binding.TREEKV_EUNSUPPORTED
+    assert call(one, one, 0, 70000, 64, 128, 5, one) == binding.TREEKV_EUNSUPPORTED
