@@ -294,3 +294,35 @@ def smoke_prompt(oracle, binding):
     st = run_prompt(oracle, kv, Q, K, V, T, block, steps)
     print(f"smoke: prompt ok, {st['decisions']} block evictions, {st['flagged']} near-ties, "
           f"max token score rel err {st['tok_err']:.2e}, then {st['decode']['decisions']} decode evictions")
+
+
+def smoke_rerank(oracle, binding):
+    """A short decode stream with positions re-assigned to cache ranks, against the oracle."""
+    from paper_2501_04987_amd import inputs
+
+    T, B, H, Hkv, d, budget = 120, 1, 4, 2, 128, 40
+    Q, K, V = inputs.batch_streams("lowrank", 3, T, B, Hkv, H // Hkv, d, dtype="bf16")
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=2, n_recent=10,
+                        flags=binding.TREEKV_POSITION_RERANK)
+    st = run_schedule(oracle, kv, Q, K, V, [0] * T, dtype="bf16")
+    print(f"smoke: re-assigned positions ok, {st['decisions']} evictions, {st['flagged']} near-ties, "
+          f"max |out err| {st['max_err']:.2e}")
+
+
+def smoke_wavelet(oracle, binding):
+    """The Haar analysis of a small random signal, against the oracle."""
+    import torch
+
+    rng = np.random.default_rng(4)
+    heads, t, d, levels = 3, 96, 128, 5
+    a = rng.random((heads, t)).astype(np.float32)
+    a /= a.sum(-1, keepdims=True)
+    V = torch.from_numpy(rng.standard_normal((heads, t, d)).astype(np.float32)).to(torch.bfloat16)
+    per_head, mean = binding.wavelet_components(torch.from_numpy(a).cuda(), V.cuda(), levels)
+    torch.cuda.synchronize()
+    Vf = V.float().numpy().astype(np.float64)
+    want = np.stack([oracle.wavelet_components(a[h].astype(np.float64), Vf[h], levels) for h in range(heads)])
+    bound = 2e-6 * float(np.abs(a[:, :, None] * Vf).max())
+    np.testing.assert_allclose(per_head.cpu().numpy(), want, rtol=1e-5, atol=bound)
+    np.testing.assert_allclose(mean.cpu().numpy(), want.mean(0), rtol=1e-5, atol=bound)
+    print(f"smoke: wavelet analysis ok, max magnitude {want.max():.3e}")
