@@ -157,6 +157,9 @@ PROMPT_BLOCK = 64
 # HBM bytes per prompt-compression call, measured like MEASURED_TRAFFIC_BYTES (same file under profiles/): the four
 # kernels' FETCH_SIZE x 2.0 (140438 + 140852 + 48 + 16679 KiB) plus WRITE_SIZE (128 + 4163 + 4 + 34165 KiB).
 PROMPT_MEASURED_TRAFFIC_BYTES = ((140438 + 140852 + 48 + 16679) * 2 + (128 + 4163 + 4 + 34165)) * 1024
+# HBM bytes of one wavelet-analysis call, measured the same way: the two kernels' FETCH_SIZE x 2.0
+# (532611.5 + 40974.5 KiB) plus WRITE_SIZE (81920 + 10 KiB).
+WAVELET_MEASURED_TRAFFIC_BYTES = int(((532611.5 + 40974.5) * 2 + (81920 + 10)) * 1024)
 
 
 def prompt_bytes_per_call(T=PROMPT_LEN, c=BUDGET, d=HEAD_DIM, heads=HEADS, block=PROMPT_BLOCK):
@@ -234,7 +237,7 @@ def bench_wavelet(torch, binding, dev, calls=20, warm=3, samples=8, t=512, level
                         f"{samples} samples) x {HEAD_DIM} dim, bf16 values",
             "calls": calls, "us_per_call": us, "heads_per_s": heads / (us * 1e-6),
             "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_call": nbytes,
+                         "frac": gbs / HBM_PEAK_GBS, "traffic": WAVELET_MEASURED_TRAFFIC_BYTES, "bytes_per_call": nbytes,
                          "note": "components kernel and mean kernel together"}}
 
 

@@ -10,7 +10,7 @@
 // through a small LDS tile as whole rows of the output.
 //
 //   wavelet_components_kernel   grid (ceil(t / 512), heads) x 256 threads -> per_head [heads][levels][t]
-//   wavelet_mean_kernel         grid ceil(levels * t / 16) x 1024 threads -> mean [levels][t], heads added in a fixed order
+//   wavelet_mean_kernel         grid ceil(levels * t / 32) x 1024 threads -> mean [levels][t], heads added in a fixed order
 
 #include "treekv_internal.h"
 
@@ -156,9 +156,9 @@ __global__ __launch_bounds__(WV_THREADS) void wavelet_components_kernel(const fl
   }
 }
 
-// Mean over the heads: a workgroup owns 16 adjacent outputs; 64 head lanes each add every 64th head, then a fixed
+// Mean over the heads: a workgroup owns 32 adjacent outputs (whole 128-byte lines); 32 head lanes each add every 32nd head, then a fixed
 // tree over the lanes: the order of the additions depends on nothing but `heads`.
-constexpr int MEAN_COLS = 16, MEAN_LANES = 64;
+constexpr int MEAN_COLS = 32, MEAN_LANES = 32;
 __global__ __launch_bounds__(MEAN_COLS * MEAN_LANES) void wavelet_mean_kernel(const float* __restrict__ per_head,
                                                                               int heads, int n, float* __restrict__ mean) {
   __shared__ float red[MEAN_LANES][MEAN_COLS];
