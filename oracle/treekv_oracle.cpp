@@ -61,7 +61,10 @@
 //    The rotary encoding is the one of its defining paper (RoFormer, eq. 15/34): dimensions
 //    (2i, 2i+1) form a plane rotated by position * base^(-2i/d), base 10000 unless set.  The
 //    paper does not say which flavour its models use; a model that pairs (i, i + d/2) instead
-//    permutes the head dimension of q and k accordingly.  Decode steps only.
+//    permutes the head dimension of q and k accordingly.  In the one-shot prompt compression
+//    nothing has been evicted yet when the window scores the prompt, so the positions are the
+//    original ones (key j at j, window query i at T - W + i); the cache it leaves holds the keys
+//    unencoded, as decoding expects.  The chunked prefill is not defined for such a stream.
 //
 //  * Wavelet analysis of Sections 3.2-3.3 (tko_wavelet_components, stateless): the signal is
 //    s[n] = a[n] * v[n] (one row per position, d columns); every column is decomposed along the
@@ -389,13 +392,12 @@ int tko_prefill_chunk(void* h, const double* Q, const double* K, const double* V
 //   evicted_block, margins [T/b]; counts[0] += adopted, counts[1] += disagreed;
 //   token_sbar [T], block_score [T/b] (any may be null).
 // Returns 0, or -1 if the arguments do not fit (non-empty stream, T or c not a multiple of b,
-// no tree block left, a stream with position re-assignment).
+// no tree block left).
 int tko_prefill_prompt(void* h, const double* Qw, const double* K, const double* V, int T, int b,
                        const long long* forced_block, double follow_thresh, long long* evicted_block,
                        double* margins, long long* counts, double* token_sbar, double* block_score) {
   Stream& s = *static_cast<Stream*>(h);
   if (!s.pos.empty() || s.t != 0 || b < 1 || T < b || T % b != 0 || s.c % b != 0) return -1;
-  if (s.flags & TKO_POSITION_RERANK) return -1;
   const int N = T / b, W = b;
   Stream blk;                                     // Algorithm 1's scalars, counted in blocks
   blk.c = s.c / b;
@@ -407,13 +409,26 @@ int tko_prefill_prompt(void* h, const double* Qw, const double* K, const double*
   // the observation window queries the entire sequence (causally); lines 6-8 for those queries only
   std::vector<double> Ssum((size_t)T, 0.0), logits((size_t)T), a((size_t)T);
   std::vector<long long> Cnt((size_t)T, 0);
+  // with position re-assignment the keys carry no positional encoding: key j is at position j here
+  const bool rerank = (s.flags & TKO_POSITION_RERANK) != 0;
+  std::vector<double> Kpos;
+  if (rerank) {
+    Kpos.resize((size_t)T * s.d);
+    for (int j = 0; j < T; ++j) {
+      const std::vector<double> kr = rotary(K + (size_t)j * s.d, s.d, j, s.rope_base);
+      for (int e = 0; e < s.d; ++e) Kpos[(size_t)j * s.d + e] = kr[e];
+    }
+  }
+  const double* Katt = rerank ? Kpos.data() : K;
   for (int i = 0; i < W; ++i) {
     const size_t vis = (size_t)(T - W + i) + 1;
     for (int g = 0; g < s.G; ++g) {
-      const double* q = Qw + ((size_t)i * s.G + g) * s.d;
+      std::vector<double> qv(Qw + ((size_t)i * s.G + g) * s.d, Qw + ((size_t)i * s.G + g + 1) * s.d);
+      if (rerank) qv = rotary(qv.data(), s.d, (long long)(T - W + i), s.rope_base);
+      const double* q = qv.data();
       for (size_t j = 0; j < vis; ++j) {
         double acc = 0.0;
-        for (int e = 0; e < s.d; ++e) acc += q[e] * K[j * s.d + e];
+        for (int e = 0; e < s.d; ++e) acc += q[e] * Katt[j * s.d + e];
         logits[j] = acc * s.scale;
       }
       softmax_row(logits, vis, a);

@@ -814,8 +814,6 @@ def test_rerank_off_is_untouched_and_prefill_refuses(oracle):
     s = oracle.OracleStream(8, 1, 4, flags=oracle.POSITION_RERANK)
     with pytest.raises(ValueError):
         s.prefill_chunk(q[:4], k[:4], v[:4])
-    with pytest.raises(ValueError):
-        s.prefill_prompt(q[:2], k[:8], v[:8], 2)
 
 
 def test_rerank_brute_force(oracle):
@@ -899,3 +897,57 @@ def test_wavelet_special_signals(oracle):
     assert np.abs(mag[1:]).max() < 1e-15
     with pytest.raises(ValueError):
         oracle.wavelet_components(np.ones(48), np.ones((48, 1)), 5)
+
+
+def test_rerank_prompt_scores_and_hand_over(oracle):
+    """One-shot compression of a prompt whose keys carry no positional encoding: the token scores are the column
+    averages of textbook rotary attention at the ORIGINAL positions (nothing has been evicted yet), the cache
+    keeps the keys unencoded, and the decode steps that follow see the kept tokens at their ranks."""
+    rng = np.random.default_rng(77)
+    G, d, b, T, c = 2, 8, 4, 40, 16
+    Qw, K, V = rng.standard_normal((b, G, d)), rng.standard_normal((T, d)), rng.standard_normal((T, d))
+    s = oracle.OracleStream(c, G, d, n_sink=2, n_recent=5, flags=oracle.POSITION_RERANK, rope_base=100.0)
+    r = s.prefill_prompt(Qw, K, V, b)
+    theta = 100.0 ** (-2.0 * np.arange(d // 2) / d)
+    kc = (K[:, 0::2] + 1j * K[:, 1::2]) * np.exp(1j * np.outer(np.arange(T), theta))
+    tot, cnt = np.zeros(T), np.zeros(T)
+    for i in range(b):
+        p = T - b + i
+        for g in range(G):
+            qc = (Qw[i, g, 0::2] + 1j * Qw[i, g, 1::2]) * np.exp(1j * p * theta)
+            lg = np.real(kc[: p + 1].conj() @ qc) / np.sqrt(d)
+            w = np.exp(lg - lg.max())
+            tot[: p + 1] += w / w.sum()
+        cnt[: p + 1] += 1
+    np.testing.assert_allclose(r["token_scores"], tot / cnt, rtol=1e-10)
+    kept = s.retained()
+    Kc, Vc = s.kv()
+    np.testing.assert_array_equal(Kc, K[kept])
+    q1, k1, v1 = rng.standard_normal((G, d)), rng.standard_normal(d), rng.standard_normal(d)
+    out = s.decode_step(q1, k1, v1, commit=False)[0]
+    want = _rotary_attention(q1, np.vstack([K[kept], k1]), np.vstack([V[kept], v1]), len(kept), np.arange(len(kept) + 1),
+                             s.scale, base=100.0)
+    np.testing.assert_allclose(out, want, rtol=1e-9, atol=1e-12)
+
+
+def test_rerank_prompt_brute_force(oracle):
+    for seed in range(20):
+        rng = np.random.default_rng(1700 + seed)
+        b = int(rng.integers(1, 4))
+        cb = int(rng.integers(3, 7))
+        c = cb * b
+        G, d = int(rng.integers(1, 3)), 2 * int(rng.integers(1, 4))
+        T = b * int(rng.integers(1, 14))
+        Qw, K, V = _prompt(4000 + seed, T, G, d, b)
+        s = oracle.OracleStream(c, G, d, flags=oracle.POSITION_RERANK, rope_base=30.0)
+        r = s.prefill_prompt(Qw, K, V, b)
+        bf = BruteTreeKV(c, G, d, rerank_base=30.0)
+        gone, sbar, beta = bf.prefill_prompt(Qw.tolist(), K.tolist(), V.tolist(), b)
+        assert list(r["evicted_blocks"]) == gone, seed
+        np.testing.assert_allclose(r["token_scores"], sbar, rtol=1e-10)
+        q, k, v = _rand_stream(5000 + seed, 6, G, d)
+        for t in range(6):
+            out, ev, *_ = s.decode_step(q[t], k[t], v[t])
+            o_b, ev_b = bf.decode_step(q[t].tolist(), k[t].tolist(), v[t].tolist())
+            assert ev == ev_b, (seed, t)
+            np.testing.assert_allclose(out, np.array(o_b), rtol=1e-9, atol=1e-12)
