@@ -102,9 +102,10 @@ __device__ inline float max3(float a, float b, float c) { return fmaxf(fmaxf(a, 
 
 template <bool B> struct BoolTag { static constexpr bool value = B; };
 
-// s_waitcnt vmcnt(N) alone (the other counters at their maxima, i.e. not waited for), N < 16
+// s_waitcnt vmcnt(N) alone (the other counters not waited for), N < 16.  A statement the compiler moves no memory
+// access across: LDS reads that follow it read what the awaited copies wrote.
 template <int N>
-__device__ inline void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | N); }
+__device__ inline void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
 // Asynchronous copy of 16 bytes per lane from global memory into LDS: lane i's bytes land at
 // lds_base + 16 * i (lds_base: wave-uniform LDS byte address, taken from M0).  Written as assembly on
@@ -346,7 +347,9 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       }
     };
     // Iteration t: request tile t+3, form the logits of tile t+1 while the statistics of tile t are updated.
-    // Stage (t+3)&3 held tile t-1, last read in iteration t-2.  One barrier per tile.
+    // Stage (t+3)&3 held tile t-1, last read in iteration t-2.  In this sweep a wave reads exactly the 16 rows
+    // of every tile that it requested itself, so the waves need no barrier between tiles: each runs on its own
+    // count of outstanding requests.
     f32x4_t sa[4], sb[4];
 #pragma unroll
     for (int t = 0; t < 3; ++t)
@@ -361,12 +364,12 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       stats(cur, t);
       // tile t+2 must have landed before the next iteration reads it; only this iteration's requests may stay out
       if (more) wait_vmcnt<CPW>(); else wait_vmcnt<0>();
-      __syncthreads();
     };
     for (int t = 0; t < ntiles; t += 2) {
       step(sa, sb, t);
       if (t + 1 < ntiles) step(sb, sa, t + 1);
     }
+    __syncthreads();                   // the statistics below reuse the staging memory other waves may still read
     // merge the four lanes that share a row, then the eight waves through LDS
     float* st = reinterpret_cast<float*>(pf_smem);       // [8 waves][64 rows][2]
 #pragma unroll
