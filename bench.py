@@ -169,12 +169,12 @@ def prompt_bytes_per_call(T=PROMPT_LEN, c=BUDGET, d=HEAD_DIM, heads=HEADS, block
     return per_head * heads
 
 
-def bench_prompt(torch, binding, inputs, dev, calls=20, warm=3, layers=3):
+def bench_prompt(torch, binding, inputs, dev, calls=20, warm=3, layers=3, flags=0):
     """One-shot block-level compression (Section 4.2) of a 32768-token prompt into 2048 slots, 32 heads x 128,
     blocks of 64, batch 1, cycling over a few prompts (each larger than the memory-side cache)."""
     T, b = PROMPT_LEN, PROMPT_BLOCK
     kv = binding.TreeKV(BUDGET, HEADS, HEAD_DIM, kv_heads=KV_HEADS, batch=1, dtype="bf16", n_sink=4,
-                        n_recent=BUDGET - BUDGET // 2 - 4, max_prompt=T)
+                        n_recent=BUDGET - BUDGET // 2 - 4, max_prompt=T, flags=flags)
     prompts = []
     for l in range(layers):
         q, k, v = inputs.device_lowrank(21 + l, T, 1, KV_HEADS, HEADS // KV_HEADS, HEAD_DIM, device=dev)
@@ -408,6 +408,10 @@ def main():
         res["prompt"] = bench_prompt(torch, binding, inputs, dev)
         torch.cuda.empty_cache()
         res["wavelet"] = bench_wavelet(torch, binding, dev)
+    if args.rerank:
+        del q, k, v, layers
+        torch.cuda.empty_cache()
+        res["prompt"] = bench_prompt(torch, binding, inputs, dev, flags=binding.TREEKV_POSITION_RERANK)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline()
     print(json.dumps(res))

@@ -62,8 +62,11 @@ enum {
                                     keys and the query inside the step.  Rotary encoding as defined by its
                                     authors: dimensions (2i, 2i+1) form a plane turned by
                                     position * rope_base^(-2i/d); a model that pairs (i, i + d/2) permutes the
-                                    head dimension of q and k accordingly.  Decode steps only: the two prefill
-                                    calls return TREEKV_EUNSUPPORTED for such a context.                  */
+                                    head dimension of q and k accordingly.  treekv_prefill_prompt takes its
+                                    queries and keys unencoded too: nothing has been evicted when the window
+                                    scores the prompt, so key j is at position j and window query i at
+                                    len - block + i; the cache it leaves holds the keys unencoded.
+                                    treekv_prefill_chunk returns TREEKV_EUNSUPPORTED for such a context.      */
 };
 
 typedef struct treekv_ctx treekv_ctx;          /* opaque, host memory, owns no device memory */

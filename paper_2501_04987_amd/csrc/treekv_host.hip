@@ -23,6 +23,8 @@ namespace {
 constexpr size_t ALIGN = 256;
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
+size_t rope_rows(const Params& p) { return (size_t)(p.cap > p.max_prompt ? p.cap : p.max_prompt); }
+
 // Walks the workspace layout; with base == nullptr it only measures.
 size_t carve(Params& p, char* base) {
   size_t off = 0;
@@ -53,7 +55,10 @@ size_t carve(Params& p, char* base) {
     p.pp_stat = (float*)take(U * (size_t)PROMPT_MAX_SPLITS * 128 * 2 * 4);
     p.pp_kept = (int*)take(U * (size_t)p.budget * 4);
   }
-  if (p.flags & TREEKV_POSITION_RERANK) p.rope_tab = (float2*)take(cap * (size_t)(p.D / 2) * sizeof(float2));
+  if (p.flags & TREEKV_POSITION_RERANK) {
+    p.rope_tab = (float2*)take(rope_rows(p) * (size_t)(p.D / 2) * sizeof(float2));
+    if (p.max_prompt > 0) p.pp_qrot = (uint16_t*)take(U * 2 * 128 * (size_t)p.D * 2);
+  }
   return off;
 }
 
@@ -81,9 +86,9 @@ __global__ void reset_kernel(Params p) {
 
 // (cos, sin) of distance * base^(-2i/D) for every distance two cached tokens can have, in double precision.
 __global__ void rope_table_kernel(Params p) {
-  const int n = p.cap * (p.D / 2);
-  for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < n; x += gridDim.x * blockDim.x) {
-    const int dist = x / (p.D / 2), i = x % (p.D / 2);
+  const size_t n = (size_t)(p.cap > p.max_prompt ? p.cap : p.max_prompt) * (p.D / 2);
+  for (size_t x = blockIdx.x * (size_t)blockDim.x + threadIdx.x; x < n; x += (size_t)gridDim.x * blockDim.x) {
+    const int dist = (int)(x / (p.D / 2)), i = (int)(x % (p.D / 2));
     const double angle = (double)dist * pow((double)p.rope_base, -2.0 * (double)i / (double)p.D);
     p.rope_tab[x] = make_float2((float)cos(angle), (float)sin(angle));
   }
@@ -131,7 +136,7 @@ int check_launch() { return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV
 int launch_reset(const Params& p, hipStream_t s) {
   hipLaunchKernelGGL(reset_kernel, dim3(p.U), dim3(256), 0, s, p);
   if (p.flags & TREEKV_POSITION_RERANK)
-    hipLaunchKernelGGL(rope_table_kernel, dim3((p.cap * (p.D / 2) + 255) / 256), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((rope_rows(p) * (p.D / 2) + 255) / 256)), dim3(256), 0, s, p);
   return check_launch();
 }
 
@@ -296,7 +301,6 @@ int treekv_prefill_prompt(treekv_ctx* ctx, const void* Qw, const void* K, const 
   const int cb = c.budget / block, sink_b = (c.n_sink + block - 1) / block, recent_b = (c.n_recent + block - 1) / block;
   if (cb - sink_b - recent_b < 1) return TREEKV_EINVAL;
   if (!aligned16(Qw) || !aligned16(K) || !aligned16(V)) return TREEKV_EINVAL;
-  if (c.flags & TREEKV_POSITION_RERANK) return TREEKV_EUNSUPPORTED;
   if (!ctx->bound) return TREEKV_ENOWS;
   // the window's queries of one KV head's group are the rows of one matrix operand set
   if (block * (c.q_heads / c.kv_heads) > 128) return TREEKV_EUNSUPPORTED;

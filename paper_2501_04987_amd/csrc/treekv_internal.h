@@ -60,7 +60,9 @@ struct Params {
   int* pp_kept;             // [U][budget] kept blocks, ascending
   // position re-assignment (only with TREEKV_POSITION_RERANK)
   float rope_base;
-  float2* rope_tab;         // [cap][D/2] (cos, sin) of distance * rope_base^(-2i/D)
+  float2* rope_tab;         // [max(cap, max_prompt)][D/2] (cos, sin) of n * rope_base^(-2i/D): n a distance between two
+                            // cached tokens (decode) or a prompt position (prompt compression)
+  uint16_t* pp_qrot;        // [U][hi, lo][128][D] bf16: the window's queries turned to their positions (max_prompt > 0)
 };
 constexpr int PROMPT_MAX_SPLITS = 64;
 

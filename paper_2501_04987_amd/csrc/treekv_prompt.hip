@@ -23,6 +23,12 @@
 // the keys read straight from global memory in operand order (S^T = K Q^T, 16 keys x 32 dims per
 // instruction; the window queries sit in registers as the other operand), so the vector ALU is left with
 // one exponential per logit.
+//
+// With positions re-assigned (TREEKV_POSITION_RERANK) the keys and queries come without positional encoding and
+// nothing has been evicted yet, so key j is at position j and window query i at T - W + i.  The keys are turned
+// in registers (fp32, angles from the table) right after they arrive and split into two bf16 parts, hi + lo; the
+// window's queries are turned and split once per call by a small kernel and sit in LDS; a logit is then
+// k_hi.q_hi + k_lo.q_hi + k_hi.q_lo (the missing lo.lo term is 2^-18 of the product).  Same four launches after that.
 
 #include "treekv_internal.h"
 
@@ -45,6 +51,22 @@ __device__ inline f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ inline unsigned pack_bf16(float a, float b) {       // (a in the low half), round to nearest even
+  f32x2_t v = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
+// One plane (two adjacent dims, packed as bf16 in `w`) turned by the angle whose (cos, sin) are given:
+// the bf16 pair nearest to the result, and the bf16 pair nearest to what that rounding lost.
+__device__ inline void turn_pair(unsigned w, float c, float s, unsigned& hi, unsigned& lo) {
+  const float x0 = __uint_as_float(w << 16), x1 = __uint_as_float(w & 0xffff0000u);
+  const float r0 = fmaf(x0, c, -(x1 * s)), r1 = fmaf(x0, s, x1 * c);
+  hi = pack_bf16(r0, r1);
+  lo = pack_bf16(r0 - __uint_as_float(hi << 16), r1 - __uint_as_float(hi & 0xffff0000u));
+}
+__device__ inline int q_swz(int D, int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+
 template <int CTRL>
 __device__ inline float dpp_add(float v) {
   const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
@@ -63,10 +85,16 @@ __device__ inline float row16_sum(float v) {
 // workgroup owns, and the loop that turns 32 keys into NB x 2 accumulators of scaled logits.
 //   query row qr = i * G + g (window query i, head g of the group), padded with rows that see nothing to NB * 16;
 //   row qr sees the keys below T - W + i + 1.
-template <int D, int NB>
+template <int D, int NB, bool ROPE>
 struct PromptStream {
   static constexpr int KS = D / 32;
-  uint4 qa[NB][KS];
+  static constexpr int Q_LDS_BYTES = ROPE ? 2 * NB * 16 * D * 2 : 0;
+  // one operand block of keys in flight: 16 keys x this lane's 8 dims of every k-step, and (ROPE) the (cos, sin)
+  // pairs of those dims at the keys' positions
+  struct KB { uint4 k[KS]; uint4 t[ROPE ? 2 * KS : 1]; };
+  uint4 qa[ROPE ? 1 : NB][KS];
+  const uint16_t* sq;          // ROPE: LDS [hi, lo][NB * 16 rows][D], 16-byte pieces swizzled by row
+  const float2* tab;           // ROPE: (cos, sin) of position * theta_i
   int lim[NB];                 // first key this lane's query of block nb does not see, capped at the slice's end
   const uint16_t* Ku;          // key 0 of the unit
   size_t row_stride;           // elements between consecutive keys of the unit
@@ -74,8 +102,10 @@ struct PromptStream {
   int lane, wave, lr, q4;
 
   __device__ inline void init(const Params& p, const uint16_t* Qw, const uint16_t* K, int T_, int W, int unit,
-                              int split, int rows_per_split) {
+                              int split, int rows_per_split, uint16_t* sm_q) {
     const int tid = threadIdx.x;
+    sq = sm_q;
+    tab = p.rope_tab;
     lane = tid & 63; wave = tid >> 6; lr = lane & 15; q4 = lane >> 4;
     T = T_;
     const int kvh = unit % p.Hkv, b = unit / p.Hkv;
@@ -92,42 +122,111 @@ struct PromptStream {
       // (a padding row repeats the window's last query: it sees no key, lim = 0, so what it holds does not matter,
       // and a load on every path lets the key requests go out without waiting for these)
       const int iq = live ? i : W - 1, gq = live ? g : 0;
+      if constexpr (!ROPE) {
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        qa[nb][ks] = *reinterpret_cast<const uint4*>(Qw + (((size_t)b * W + iq) * p.H + (size_t)kvh * p.G + gq) * D + ks * 32 + q4 * 8);
+        for (int ks = 0; ks < KS; ++ks)
+          qa[nb][ks] = *reinterpret_cast<const uint4*>(Qw + (((size_t)b * W + iq) * p.H + (size_t)kvh * p.G + gq) * D + ks * 32 + q4 * 8);
+      }
+    }
+    if constexpr (ROPE) {
+      // the turned queries of this unit (hi rows, then lo rows) -> LDS; the caller's barrier publishes them
+      constexpr int PIECES = D / 8;
+      const uint4* src = reinterpret_cast<const uint4*>(p.pp_qrot + (size_t)unit * 2 * 128 * D);
+      for (int x = tid; x < 2 * NB * 16 * PIECES; x += PP_THREADS) {
+        const int piece = x % PIECES, row = (x / PIECES) % (NB * 16), half = x / (PIECES * NB * 16);
+        *reinterpret_cast<uint4*>(sm_q + ((size_t)(half * NB * 16 + row) * D + ((piece ^ q_swz(D, row)) * 8))) =
+            src[((size_t)half * 128 + row) * PIECES + piece];
+      }
     }
   }
   // One operand block: keys base + lr (clamped into the prompt), this lane's 8 dims of every k-step.
   // The callers request blocks past their slice rather than branch around the request: with every load on
   // every path the compiler's count of outstanding loads is exact and a wait covers the block it needs only.
-  __device__ inline void load_block(uint4 (&k)[KS], int base) const {
-    const uint16_t* r = Ku + (size_t)max(0, min(base + lr, T - 1)) * row_stride + q4 * 8;
+  __device__ inline void load_block(KB& kb, int base) const {
+    const int row = max(0, min(base + lr, T - 1));
+    const uint16_t* r = Ku + (size_t)row * row_stride + q4 * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) k[ks] = *reinterpret_cast<const uint4*>(r + ks * 32);
+    for (int ks = 0; ks < KS; ++ks) kb.k[ks] = *reinterpret_cast<const uint4*>(r + ks * 32);
+    if constexpr (ROPE) {
+      const uint4* tr = reinterpret_cast<const uint4*>(tab + (size_t)row * (D / 2) + q4 * 4);   // key `row` is at position `row`
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) { kb.t[2 * ks] = tr[ks * 8]; kb.t[2 * ks + 1] = tr[ks * 8 + 1]; }
+    }
   }
   // scaled-logit accumulators of one operand block: acc[nb][i] = <key base + q4*4 + i, query nb*16 + lr>
-  __device__ inline void logits(const uint4 (&k)[KS], f32x4_t (&acc)[NB]) const {
+  // (STEPWISE, ROPE only: the scheduler may not fetch a later k-step's query operands before the current one
+  // is done - for the kernel that would otherwise run out of registers)
+  template <bool STEPWISE = false>
+  __device__ inline void logits(const KB& kb, f32x4_t (&acc)[NB]) const {
+    if constexpr (!ROPE) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      for (int nb = 0; nb < NB; ++nb) {
+        acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) acc[nb] = mfma16(k[ks], qa[nb][ks], acc[nb]);
+        for (int ks = 0; ks < KS; ++ks) acc[nb] = mfma16(kb.k[ks], qa[nb][ks], acc[nb]);
+      }
+    } else {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      // one k-step at a time: its 8 dims are turned and split, used against every query block, and forgotten
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const uint4 t0 = kb.t[2 * ks], t1 = kb.t[2 * ks + 1];
+        uint4 kh, kl;
+        turn_pair(kb.k[ks].x, __uint_as_float(t0.x), __uint_as_float(t0.y), kh.x, kl.x);
+        turn_pair(kb.k[ks].y, __uint_as_float(t0.z), __uint_as_float(t0.w), kh.y, kl.y);
+        turn_pair(kb.k[ks].z, __uint_as_float(t1.x), __uint_as_float(t1.y), kh.z, kl.z);
+        turn_pair(kb.k[ks].w, __uint_as_float(t1.z), __uint_as_float(t1.w), kh.w, kl.w);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const int row = nb * 16 + lr;
+          const int off = ((ks * 4 + q4) ^ q_swz(D, row)) * 8;
+          const uint4 bh = *reinterpret_cast<const uint4*>(sq + (size_t)row * D + off);
+          const uint4 bl = *reinterpret_cast<const uint4*>(sq + (size_t)(NB * 16 + row) * D + off);
+          acc[nb] = mfma16(kh, bh, acc[nb]);
+          acc[nb] = mfma16(kl, bh, acc[nb]);
+          acc[nb] = mfma16(kh, bl, acc[nb]);
+        }
+        if constexpr (STEPWISE) __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
 };
 
+// The window's queries turned to their positions (query i of the window at T - W + i) and split into bf16 hi and
+// lo parts: pp_qrot [unit][hi, lo][128 rows][D], row i * G + g, rows past W * G zero.
+template <int D>
+__global__ void prompt_turn_queries_kernel(Params p, const uint16_t* __restrict__ Qw, int T, int W) {
+  const int unit = blockIdx.y, kvh = unit % p.Hkv, b = unit / p.Hkv;
+  unsigned* dst = reinterpret_cast<unsigned*>(p.pp_qrot + (size_t)unit * 2 * 128 * D);
+  for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < 128 * (D / 2); x += gridDim.x * blockDim.x) {
+    const int pair = x % (D / 2), row = x / (D / 2);
+    unsigned hi = 0, lo = 0;
+    if (row < W * p.G) {
+      const int i = row / p.G, g = row % p.G;
+      const unsigned w = reinterpret_cast<const unsigned*>(Qw + (((size_t)b * W + i) * p.H + (size_t)kvh * p.G + g) * D)[pair];
+      const float2 cs = p.rope_tab[(size_t)(T - W + i) * (D / 2) + pair];
+      turn_pair(w, cs.x, cs.y, hi, lo);
+    }
+    dst[(size_t)row * (D / 2) + pair] = hi;
+    dst[(size_t)(128 + row) * (D / 2) + pair] = lo;
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // stats: per (unit, slice, query row) the maximum and the sum of exp2(logit - maximum) over the slice
 // ---------------------------------------------------------------------------------------------
-template <int D, int NB>
+template <int D, int NB, bool ROPE>
 __global__ __launch_bounds__(PP_THREADS) void prompt_stats_kernel(Params p, const uint16_t* __restrict__ Qw,
                                                                   const uint16_t* __restrict__ K, int T, int W,
                                                                   int rows_per_split, int nsplit) {
-  constexpr int KS = D / 32;
+  using PS = PromptStream<D, NB, ROPE>;
+  using KB = typename PS::KB;
   __shared__ float sm_m[PP_WAVES][NB * 16], sm_l[PP_WAVES][NB * 16];
-  PromptStream<D, NB> st;
+  extern __shared__ __attribute__((aligned(16))) uint16_t stats_q[];   // ROPE: the turned queries
+  PS st;
   const int split = blockIdx.x, unit = blockIdx.y;
-  st.init(p, Qw, K, T, W, unit, split, rows_per_split);
+  st.init(p, Qw, K, T, W, unit, split, rows_per_split, stats_q);
   const float sc = p.scale_log2e;
   const int lim_all = min(st.end, T - W + 1);      // every query sees the keys below this
 
@@ -138,18 +237,20 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_stats_kernel(Params p, cons
   // two tiles of 32 keys in flight per wave: (k0, k1) and (k2, k3); a block is requested again, two tiles on,
   // as soon as its logits are out
   // (one tile with all eight operand blocks of queries: the registers do not hold more)
-  constexpr int AHEAD = NB < 8 ? 2 : 1;
-  uint4 k0[KS], k1[KS], k2[KS], k3[KS];
+  // (and with the rotary angles travelling with the keys)
+  constexpr int AHEAD = (NB < 8 && !ROPE) ? 2 : 1;
+  KB k0, k1, k2, k3;
   int base = st.begin + st.wave * PP_TILE;
   st.load_block(k0, base); st.load_block(k1, base + 16);
   if (AHEAD == 2) { st.load_block(k2, base + PP_STEP); st.load_block(k3, base + PP_STEP + 16); }
+  if constexpr (ROPE) __syncthreads();               // the queries are in LDS
   // One operand block of 16 keys at a time: its accumulators are consumed before the next block's exist.
   // `ragged` (a type, so that the common case carries no masking code): some query does not see some key.
-  auto block = [&](auto ragged, uint4 (&k)[KS], int tile, int h) {
+  auto block = [&](auto ragged, KB& k, int tile, int h) {
     constexpr bool RAGGED = decltype(ragged)::value;
     f32x4_t a[NB];
-    st.logits(k, a);
-    st.load_block(k, tile + AHEAD * PP_STEP + h * 16);
+    st.template logits<true>(k, a);
+    if constexpr (!ROPE) st.load_block(k, tile + AHEAD * PP_STEP + h * 16);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       float r[4];                                    // raw logits; the scale is positive, so max commutes with it
@@ -169,8 +270,10 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_stats_kernel(Params p, cons
       l_run[nb] = fmaf(l_run[nb], fast_exp2(m_run[nb] - mx), add);
       m_run[nb] = mx;
     }
+    // (with the angles in tow a block takes too many registers to be requested while its predecessor is in use)
+    if constexpr (ROPE) st.load_block(k, tile + AHEAD * PP_STEP + h * 16);
   };
-  auto tile = [&](uint4 (&ka)[KS], uint4 (&kb)[KS], int t) {
+  auto tile = [&](KB& ka, KB& kb, int t) {
     if (t + PP_TILE > lim_all) { block(BoolTag<true>{}, ka, t, 0); block(BoolTag<true>{}, kb, t, 1); }
     else { block(BoolTag<false>{}, ka, t, 0); block(BoolTag<false>{}, kb, t, 1); }
   };
@@ -206,23 +309,25 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_stats_kernel(Params p, cons
 // ---------------------------------------------------------------------------------------------
 // scores: token score = (sum over the window queries that see the key of its probability) / (their number)
 // ---------------------------------------------------------------------------------------------
-template <int D, int NB>
+template <int D, int NB, bool ROPE>
 __global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, const uint16_t* __restrict__ Qw,
                                                                    const uint16_t* __restrict__ K, int T, int W,
                                                                    int rows_per_split, int nsplit, int block_means) {
-  constexpr int KS = D / 32;
+  using PS = PromptStream<D, NB, ROPE>;
+  using KB = typename PS::KB;
   __shared__ float sm_ML[NB * 16];
-  extern __shared__ __attribute__((aligned(16))) float sm_tok[];     // [rows_per_split] when block_means
-  PromptStream<D, NB> st;
+  extern __shared__ __attribute__((aligned(16))) uint16_t scores_q[];   // ROPE: the turned queries; then sm_tok
+  float* sm_tok = reinterpret_cast<float*>(scores_q + PS::Q_LDS_BYTES / 2);   // [rows_per_split] when block_means
+  PS st;
   const int split = blockIdx.x, unit = blockIdx.y, tid = threadIdx.x;
-  st.init(p, Qw, K, T, W, unit, split, rows_per_split);
+  st.init(p, Qw, K, T, W, unit, split, rows_per_split, scores_q);
   const float sc = p.scale_log2e;
   const int lim_all = min(st.end, T - W + 1);
 
   // This pass walks its slice from the end to the start: what the first pass read last is what the
   // memory-side cache still holds, so most of a prompt that is not much larger than that cache is not
   // fetched from HBM a second time.
-  uint4 k0[KS], k1[KS];
+  KB k0, k1;
   const int first = st.begin + st.wave * PP_TILE;
   int base = first < st.end ? first + (st.end - 1 - first) / PP_STEP * PP_STEP : first - PP_STEP;
   st.load_block(k0, base); st.load_block(k1, base + 16);
@@ -243,7 +348,7 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, con
   const bool averaged = !(p.flags & TREEKV_SCORE_ACCUMULATED);
 
   float* tok = p.pp_tok + (size_t)unit * T;
-  auto block = [&](auto ragged, uint4 (&k)[KS], int tile, int h) {
+  auto block = [&](auto ragged, KB& k, int tile, int h) {
     constexpr bool RAGGED = decltype(ragged)::value;
     f32x4_t a[NB];
     st.logits(k, a);
@@ -411,23 +516,39 @@ __global__ __launch_bounds__(256) void prompt_handoff_kernel(Params p, const uin
   }
 }
 
-template <int D, int NB>
-void launch_streams(const Params& p, const uint16_t* Qw, const uint16_t* K, int T, int W, int rows_per_split,
-                    int nsplit, int block_means, hipStream_t s) {
-  hipLaunchKernelGGL((prompt_stats_kernel<D, NB>), dim3(nsplit, p.U), dim3(PP_THREADS), 0, s, p, Qw, K, T, W,
+template <int D, int NB, bool ROPE>
+int launch_streams(const Params& p, const uint16_t* Qw, const uint16_t* K, int T, int W, int rows_per_split,
+                   int nsplit, int block_means, hipStream_t s) {
+  constexpr size_t q_lds = PromptStream<D, NB, ROPE>::Q_LDS_BYTES;
+  const size_t lds = q_lds + (block_means ? (size_t)rows_per_split * 4 : 0);
+  if (q_lds > 48 * 1024 && hipFuncSetAttribute((const void*)prompt_stats_kernel<D, NB, ROPE>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)q_lds) != hipSuccess)
+    return TREEKV_EHIP;
+  if (lds > 48 * 1024 && hipFuncSetAttribute((const void*)prompt_scores_kernel<D, NB, ROPE>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    return TREEKV_EHIP;
+  if constexpr (ROPE) hipLaunchKernelGGL((prompt_turn_queries_kernel<D>), dim3(128 * (D / 2) / 256, p.U), dim3(256), 0, s, p, Qw, T, W);
+  hipLaunchKernelGGL((prompt_stats_kernel<D, NB, ROPE>), dim3(nsplit, p.U), dim3(PP_THREADS), q_lds, s, p, Qw, K, T, W,
                      rows_per_split, nsplit);
-  const size_t lds = block_means ? (size_t)rows_per_split * 4 : 0;
-  hipLaunchKernelGGL((prompt_scores_kernel<D, NB>), dim3(nsplit, p.U), dim3(PP_THREADS), lds, s, p, Qw, K, T, W,
+  hipLaunchKernelGGL((prompt_scores_kernel<D, NB, ROPE>), dim3(nsplit, p.U), dim3(PP_THREADS), lds, s, p, Qw, K, T, W,
                      rows_per_split, nsplit, block_means);
+  return TREEKV_OK;
+}
+
+template <int D, bool ROPE>
+int launch_streams_r(const Params& p, const uint16_t* Qw, const uint16_t* K, int T, int W, int rows_per_split,
+                     int nsplit, int block_means, hipStream_t s) {
+  const int nb = (W * p.G + 15) / 16;
+  if (nb <= 2) return launch_streams<D, 2, ROPE>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
+  if (nb <= 4) return launch_streams<D, 4, ROPE>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
+  return launch_streams<D, 8, ROPE>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
 }
 
 template <int D>
-void launch_streams_d(const Params& p, const uint16_t* Qw, const uint16_t* K, int T, int W, int rows_per_split,
-                      int nsplit, int block_means, hipStream_t s) {
-  const int nb = (W * p.G + 15) / 16;
-  if (nb <= 2) launch_streams<D, 2>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
-  else if (nb <= 4) launch_streams<D, 4>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
-  else launch_streams<D, 8>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
+int launch_streams_d(const Params& p, const uint16_t* Qw, const uint16_t* K, int T, int W, int rows_per_split,
+                     int nsplit, int block_means, hipStream_t s) {
+  if (p.flags & TREEKV_POSITION_RERANK) return launch_streams_r<D, true>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
+  return launch_streams_r<D, false>(p, Qw, K, T, W, rows_per_split, nsplit, block_means, s);
 }
 
 }  // namespace
@@ -463,8 +584,9 @@ int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V,
   // the scores kernel also takes the block means when no block straddles two slices and a slice's scores fit
   // in 40 KB of LDS (slices start at multiples of what a workgroup takes per iteration)
   const int block_means = (PP_STEP % b == 0 && (size_t)rows_per_split * 4 <= 40 * 1024) ? 1 : 0;
-  if (p.D == 128) launch_streams_d<128>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, block_means, s);
-  else launch_streams_d<64>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, block_means, s);
+  const int rc = p.D == 128 ? launch_streams_d<128>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, block_means, s)
+                            : launch_streams_d<64>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, block_means, s);
+  if (rc != TREEKV_OK) return rc;
   const size_t lds = prompt_blocks_lds(T, b, cb, sink_b, recent_b);
   if (lds > 48 * 1024 &&
       hipFuncSetAttribute((const void*)prompt_blocks_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)

@@ -222,7 +222,8 @@ def run_prompt(oracle, kv, Q, K, V, T, block, decode_steps, units=None, dtype="b
         units = [(b, h) for b in range(c.batch) for h in range(c.kv_heads)]
     ocfg = oracle_cfg(kv)
     streams = {u: oracle.OracleStream(ocfg["budget"], G, c.head_dim, n_sink=ocfg["n_sink"], n_recent=ocfg["n_recent"],
-                                      scale=ocfg["scale"], flags=ocfg["flags"]) for u in units}
+                                      scale=ocfg["scale"], flags=ocfg["flags"], rope_base=ocfg["rope_base"])
+               for u in units}
     N = T // block
     Qd, Kd, Vd = to_device(Q[:T], dtype), to_device(K[:T], dtype), to_device(V[:T], dtype)
     qw = Qd[T - block:T].permute(1, 0, 2, 3).contiguous()          # [B, block, H, d]

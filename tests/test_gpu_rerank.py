@@ -90,7 +90,7 @@ def test_rerank_differs_from_plain_and_from_original_positions(binding, oracle):
     assert np.abs(got - attend(kept, t)).max() > 1e-3
 
 
-def test_rerank_prefill_calls_refuse(binding):
+def test_rerank_chunked_prefill_refuses(binding):
     import torch
 
     kv = binding.TreeKV(64, 2, 64, kv_heads=2, n_sink=2, n_recent=6, flags=binding.TREEKV_POSITION_RERANK, max_prompt=256)
@@ -99,9 +99,33 @@ def test_rerank_prefill_calls_refuse(binding):
     with pytest.raises(binding.TreeKVError) as e:
         kv.prefill_chunk(z[:, :16], z[:, :16], z[:, :16], 16, out, ret, nret, ev)
     assert e.value.status == binding.TREEKV_EUNSUPPORTED
-    with pytest.raises(binding.TreeKVError) as e:
-        kv.prefill_prompt(z[:, :16], z, z, 256, 16, ret)
-    assert e.value.status == binding.TREEKV_EUNSUPPORTED
+
+
+def _prompt(binding, oracle, *, T, block, steps, B, H, Hkv, d, budget, n_sink, n_recent, seed, rope_base=0.0, flags=0):
+    Q, K, V = inputs.batch_streams("lowrank", seed, T + steps, B, Hkv, H // Hkv, d, dtype="bf16")
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=n_sink, n_recent=n_recent,
+                        flags=flags | binding.TREEKV_POSITION_RERANK, max_prompt=T, rope_base=rope_base)
+    st = ph.run_prompt(oracle, kv, Q, K, V, T, block, steps)
+    assert st["flagged"] <= max(1, st["decisions"] // 200), st["flagged"]
+    print(f"  blocks evicted={st['decisions']} flagged={st['flagged']} token score rel err={st['tok_err']:.2e}")
+    return st
+
+
+def test_rerank_prompt_ragged_slices_then_decode(binding, oracle):
+    """One-shot compression of a prompt without positional encoding (rotary encoding of the original positions
+    applied while the window scores it), 37 blocks of 16 into 8 block slots, then 40 decode steps at cache ranks."""
+    _prompt(binding, oracle, T=592, block=16, steps=40, B=1, H=2, Hkv=2, d=128, budget=128, n_sink=4, n_recent=20, seed=51)
+
+
+@pytest.mark.parametrize("G,d,block", [(4, 64, 8), (2, 128, 16), (8, 64, 16), (1, 128, 128), (1, 64, 64)])
+def test_rerank_prompt_shapes(binding, oracle, G, d, block):
+    _prompt(binding, oracle, T=block * 41, block=block, steps=8, B=2, H=2 * G, Hkv=2, d=d, budget=block * 12, n_sink=3,
+            n_recent=block + 5, seed=52, rope_base=500.0)
+
+
+def test_rerank_prompt_long(binding, oracle):
+    """8192 tokens in blocks of 64 into 1024 slots: several slices per head, angles far around the circle."""
+    _prompt(binding, oracle, T=8192, block=64, steps=4, B=1, H=4, Hkv=4, d=128, budget=1024, n_sink=4, n_recent=508, seed=53)
 
 
 def test_rerank_llama7b_shaped_layer_sampled(binding, oracle):
