@@ -104,3 +104,27 @@ def test_random_decode_streams_with_reassigned_positions(binding, oracle, seed):
     st = ph.run_schedule(oracle, kv, Q, K, V, [0] * T, dtype=dtype)
     ph.compare_scores(kv, st["results"], dtype)
     assert st["flagged"] <= max(2, st["decisions"] // 200), (c, st["flagged"])
+
+
+@pytest.mark.parametrize("seed", range(104, 120))
+def test_random_prompt_then_steps_with_reassigned_positions(binding, oracle, seed):
+    """bf16, positions re-assigned: a prompt compressed in one shot (random block size, length, layout, rotary
+    base), then decode steps at cache ranks."""
+    rng, c = _draw(seed)
+    block = int(rng.choice([1, 2, 4, 8, 16, 32]))
+    block = min(block, 128 // c["G"])
+    cb = int(rng.integers(3, 14))
+    budget = cb * block
+    n_sink = int(rng.integers(0, block + 2))
+    n_recent = int(rng.integers(0, block + 2))
+    if cb - (-(-n_sink // block)) - (-(-n_recent // block)) < 1 or budget - n_sink - n_recent < 1:
+        n_sink = n_recent = 0
+    T = block * int(rng.integers(1, 4 * cb))
+    steps = int(rng.integers(3, 20))
+    base = float(rng.choice([0.0, 100.0]))
+    Q, K, V = inputs.batch_streams("lowrank", seed, T + steps, c["B"], c["Hkv"], c["G"], c["d"], dtype="bf16")
+    kv = binding.TreeKV(budget, c["Hkv"] * c["G"], c["d"], kv_heads=c["Hkv"], batch=c["B"], dtype="bf16",
+                        n_sink=n_sink, n_recent=n_recent, max_prompt=T, kv_splits=c["splits"],
+                        flags=binding.TREEKV_POSITION_RERANK, rope_base=base)
+    st = ph.run_prompt(oracle, kv, Q, K, V, T, block, steps)
+    assert st["flagged"] <= max(2, st["decisions"] // 100), (c, st["flagged"])
