@@ -132,3 +132,30 @@ def test_rerank_llama7b_shaped_layer_sampled(binding, oracle):
     """32 heads x 128, budget 1024 (4 + 512 + 508), 3000 steps; four heads checked at every step against the oracle."""
     _run(binding, oracle, T=3000, B=1, H=32, Hkv=32, d=128, dtype="bf16", budget=1024, n_sink=4, n_recent=508,
          seed=35, units=[(0, 0), (0, 9), (0, 21), (0, 31)], every_step=False, sample=[1500, 2999])
+
+
+def test_rerank_benchmark_launch_configuration_sampled(binding, oracle):
+    """The shape `bench.py --rerank` times: batch 8 x 32 heads x 128, bf16, budget 2048 (4 + 1024 + 1020), one
+    workgroup per unit.  A 4096-token prompt is compressed in one shot (blocks of 64), then 120 decode steps run
+    with evictions, all with re-assigned positions; the oracle audits 5 of the 256 streams, every stream is checked
+    for the properties that hold at any size."""
+    import torch
+
+    B, H, d, budget, T, block, steps = 8, 32, 128, 2048, 4096, 64, 120
+    Q, K, V = inputs.batch_streams("lowrank", 61, T + steps, B, H, 1, d, dtype="bf16", seed_per_batch=True)
+    kv = binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=4, n_recent=1020,
+                        flags=binding.TREEKV_POSITION_RERANK, max_prompt=T)
+    assert kv.cfg.kv_splits == 1
+    units = [(0, 0), (2, 13), (4, 31), (5, 8), (7, 21)]
+    st = ph.run_prompt(oracle, kv, Q, K, V, T, block, steps, units=units)
+    print(f"  prompt: flagged={st['flagged']}/{st['decisions']} tok_err={st['tok_err']:.2e}; decode: "
+          f"flagged={st['decode']['flagged']}/{st['decode']['decisions']} max_err={st['decode']['max_err']:.2e}")
+    assert st["decode"]["decisions"] == len(units) * steps and st["decode"]["flagged"] <= 2
+    out, ret, nret, ev = kv.new_outputs()
+    t = T + steps - 1
+    kv.decode_step(ph.to_device(Q[t], "bf16"), ph.to_device(K[t], "bf16"), ph.to_device(V[t], "bf16"), out, ret, nret, ev)
+    torch.cuda.synchronize()
+    ret, nret, ev = ret.cpu().numpy(), nret.cpu().numpy(), ev.cpu().numpy()
+    assert np.all(nret == budget) and np.all(np.diff(ret, axis=-1) > 0)
+    assert np.all(ret[..., :4] == np.arange(4)) and np.all(ret[..., -1020:] == np.arange(t + 2 - 1020, t + 2))
+    assert np.all((ev >= 4) & (ev < t + 2 - 1020)) and np.all(np.isfinite(out.cpu().numpy()))

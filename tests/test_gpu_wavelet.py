@@ -73,3 +73,26 @@ def test_wavelet_refuses_what_does_not_fit(binding):
     with pytest.raises(binding.TreeKVError) as e:
         binding.wavelet_components(a, V96, 4)
     assert e.value.status == binding.TREEKV_EUNSUPPORTED
+
+
+def test_wavelet_benchmark_size_sampled(binding, oracle):
+    """The size `bench.py` times: 8192 heads x 512 positions x 128, 5 levels.  Eight heads are checked against the
+    oracle; the mean over all heads against the per-head output itself (summed in fp64), and it must repeat bit for
+    bit."""
+    import torch
+
+    heads, t, d, levels = 8192, 512, 128, 5
+    g = torch.Generator(device="cuda").manual_seed(9)
+    a = torch.softmax(3.0 * torch.randn(heads, t, device="cuda", generator=g), dim=-1).contiguous()
+    V = torch.randn(heads, t, d, device="cuda", generator=g).to(torch.bfloat16)
+    per_head, mean = binding.wavelet_components(a, V, levels)
+    per_head2, mean2 = binding.wavelet_components(a, V, levels)
+    torch.cuda.synchronize()
+    assert torch.equal(mean, mean2) and torch.equal(per_head, per_head2)
+    want_mean = per_head.double().mean(0)
+    assert torch.allclose(mean.double(), want_mean, rtol=1e-5, atol=0.0)
+    for h in [0, 1, 777, 4095, 4096, 6001, 8190, 8191]:
+        ah, Vh = a[h].cpu().numpy(), V[h].float().cpu().numpy().astype(np.float64)
+        want = oracle.wavelet_components(ah.astype(np.float64), Vh, levels)
+        bound = 2e-6 * float(np.abs(ah[:, None] * Vh).max())
+        np.testing.assert_allclose(per_head[h].cpu().numpy(), want, rtol=1e-5, atol=bound)
