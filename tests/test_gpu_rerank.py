@@ -159,3 +159,33 @@ def test_rerank_benchmark_launch_configuration_sampled(binding, oracle):
     assert np.all(nret == budget) and np.all(np.diff(ret, axis=-1) > 0)
     assert np.all(ret[..., :4] == np.arange(4)) and np.all(ret[..., -1020:] == np.arange(t + 2 - 1020, t + 2))
     assert np.all((ev >= 4) & (ev < t + 2 - 1020)) and np.all(np.isfinite(out.cpu().numpy()))
+
+
+@pytest.mark.parametrize("splits", [1, 2])
+def test_rerank_decode_steps_replay_from_a_hip_graph(binding, splits):
+    """The ranks are rebuilt from the order arrays inside every step (no host-side state), so a captured step with
+    re-assigned positions replays like a plain one: exactly what eager launches give, with eager work in between."""
+    import torch
+
+    T, B, H, d, budget = 70, 2, 4, 128, 24
+    Q, K, V = inputs.batch_streams("lowrank", 71, T, B, H, 1, d, dtype="bf16")
+    Qd, Kd, Vd = (ph.to_device(x, "bf16") for x in (Q, K, V))
+    mk = lambda: binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=2, n_recent=6, kv_splits=splits,
+                                flags=binding.TREEKV_POSITION_RERANK)
+    eager, graph = mk(), mk()
+    want = ph.gpu_decode_run(eager, Qd, Kd, Vd, range(T))
+    q_s, k_s, v_s = Qd[0].clone(), Kd[0].clone(), Vd[0].clone()
+    out, ret, nret, ev = graph.new_outputs()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graph.decode_step(q_s, k_s, v_s, out, ret, nret, ev)
+    graph.reset()
+    torch.cuda.synchronize()
+    for t in range(T):
+        q_s.copy_(Qd[t]); k_s.copy_(Kd[t]); v_s.copy_(Vd[t])
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want["out"][t]), t
+        assert np.array_equal(ev.cpu().numpy(), want["evicted"][t]), t
+        assert np.array_equal(ret.cpu().numpy(), want["retained"][t]), t
+        _ = (Qd[t].float() * 2).sum().item()
