@@ -13,7 +13,8 @@
  *   - Every data pointer is a DEVICE pointer owned by the caller; the library
  *     never allocates or frees device memory.  Its own state lives in a
  *     workspace the caller allocates and binds (treekv_workspace_bytes,
- *     treekv_bind_workspace).  A snapshot of a context is a copy of that buffer.
+ *     treekv_bind_workspace).  treekv_export_state / treekv_import_state take and
+ *     restore snapshots of it in a layout-independent form.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; outputs are valid once the stream has been
  *     synchronised.  Calls on one context must be ordered (one stream, or
@@ -48,6 +49,9 @@ typedef enum treekv_status {
 } treekv_status;
 
 enum { TREEKV_BF16 = 0, TREEKV_F32 = 1 };      /* storage type of q, k, v and of the cache */
+/* The index update Algorithm 1 prints in its line 17, idx = (idx+1) mod c + 1, visits every other scope only
+ * and contradicts Section 4.1 (idx "cycles through 1, 2, 3, and 4"); this library advances idx by one,
+ * idx = (idx mod m) + 1, and has no flag for the printed form. */
 enum {
   TREEKV_KEEP_LEFT = 1,          /* flags: ablation of Section 5.4 (always keep the left slot of the scope,
                                     ignore the scores)                                                   */
@@ -69,6 +73,8 @@ enum {
                                     treekv_prefill_chunk returns TREEKV_EUNSUPPORTED for such a context.      */
 };
 
+enum { TREEKV_DEFAULT_LAYOUT = -1 };           /* n_sink = n_recent = this: 4 sinks, budget/2 tree slots, the rest recent */
+
 typedef struct treekv_ctx treekv_ctx;          /* opaque, host memory, owns no device memory */
 
 typedef struct treekv_config {
@@ -80,7 +86,8 @@ typedef struct treekv_config {
   int32_t batch;         /* B independent sequences, all advancing together                   */
   int32_t dtype;         /* TREEKV_BF16 or TREEKV_F32                                          */
   int32_t n_sink;        /* leading tokens never evicted  (Section 5.2: 4)                     */
-  int32_t n_recent;      /* trailing tokens never evicted (Section 5.2: 508 of 1024)           */
+  int32_t n_recent;      /* trailing tokens never evicted (Section 5.2: 508 of 1024); both
+                            TREEKV_DEFAULT_LAYOUT: the layout treekv_init chooses             */
   float softmax_scale;   /* multiplies q.k; 0 selects 1/sqrt(head_dim) (Section 3.1)           */
   int32_t flags;         /* 0, or an OR of TREEKV_KEEP_LEFT, TREEKV_SCORE_ACCUMULATED,
                             TREEKV_POSITION_RERANK                                             */
@@ -100,7 +107,8 @@ typedef struct treekv_config {
  */
 int treekv_init(treekv_ctx** out, int budget, int heads, int head_dim);
 
-/* treekv_init_ex - full configuration.  Requires budget - n_sink - n_recent >= 1. */
+/* treekv_init_ex - full configuration.  Requires budget - n_sink - n_recent >= 1 (or both TREEKV_DEFAULT_LAYOUT
+ * and budget >= 16). */
 int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg);
 
 /* Frees the host-side context (not the workspace, which is the caller's). */
@@ -212,10 +220,50 @@ int treekv_gather_kv(treekv_ctx* ctx, void* K_out, void* V_out, void* stream);
 int treekv_wavelet_components(const float* a, const void* V, int dtype, int heads, int t, int d, int levels,
                               float* per_head, float* mean, void* stream);
 
+/*
+ * Snapshots: Algorithm 1's state (line 1: S, C, K, V, idx; C is t - position) of every (batch, KV head) unit,
+ * in position order, independent of how the workspace lays the cache out.  A snapshot is one device buffer of
+ * treekv_state_bytes(ctx) bytes, 256-byte aligned, holding six arrays at the byte offsets treekv_get_state_layout
+ * reports (U = B * Hkv units, c = budget):
+ *   header    [U][4] int32   n (tokens kept), t (tokens processed so far), idx (the paper's, 1 .. m), 0
+ *   positions [U][c] int32   stream positions of the kept tokens, ascending; -1 past n
+ *   slots     [U][c] int32   the cache row each token sits in (0 .. c); -1 past n.  Restoring rows to the same
+ *                            slots makes the steps after an import repeat bit for bit what followed the export.
+ *                            A snapshot built by hand may set slots[u][0] = -1: token i then takes row i.
+ *   S         [U][c] float32 accumulated attention weight of each kept token (Algorithm 1, line 8); 0 past n
+ *   K, V      [U][c][d]      storage dtype; the kept tokens' rows, zero past n
+ */
+typedef struct treekv_state_layout {
+  size_t header, positions, slots, S, K, V;   /* byte offsets into the snapshot */
+  size_t bytes;                               /* its total size                  */
+} treekv_state_layout;
+
+size_t treekv_state_bytes(const treekv_ctx* ctx);                      /* 0 for a null context */
+int treekv_get_state_layout(const treekv_ctx* ctx, treekv_state_layout* out);
+
+/* treekv_export_state - writes a snapshot of the context, as it is once the calls enqueued before on `stream`
+ * have run, to dst (device memory, caller-owned).  TREEKV_EINVAL if dst is null, misaligned or `bytes` too small. */
+int treekv_export_state(treekv_ctx* ctx, void* dst, size_t bytes, void* stream);
+
+/*
+ * treekv_import_state - replaces the context's state by a snapshot (of a context with the same configuration;
+ * it may come from treekv_export_state or be built by the caller, e.g. from another implementation's state).
+ * The context must have been reset once since its workspace was bound.  Every unit's snapshot is checked on the
+ * device: 0 <= n <= c, 1 <= idx <= m; while the cache fills (n < c) nothing has been evicted: t = n, idx = 1,
+ * positions 0 .. n-1; once it is full: t >= n, positions ascending and below t, the first n_sink of them
+ * 0 .. n_sink-1, the last n_recent of them t-n_recent .. t-1, and slots either unset or all different.
+ *   status [U] int32 (device, may be NULL): TREEKV_OK or TREEKV_EINVAL per unit.  A unit that fails the check
+ *   is left EMPTY (as after treekv_reset); the others are imported.
+ * TREEKV_EINVAL (nothing enqueued) if src is null, misaligned or `bytes` too small.
+ */
+int treekv_import_state(treekv_ctx* ctx, const void* src, size_t bytes, int32_t* status, void* stream);
+
 /* Static description of a status code. */
 const char* treekv_strerror(int status);
 
-/* Text of the last HIP error seen by this context ("" if none). */
+/* Text of the HIP error behind the last TREEKV_EHIP this context returned ("" if none).  An error that an
+ * unrelated, earlier HIP call of the calling thread left pending is dropped when an entry point starts, not
+ * reported as this library's. */
 const char* treekv_last_hip_error(const treekv_ctx* ctx);
 
 #ifdef __cplusplus

@@ -22,11 +22,12 @@ TREEKV_F32 = 1
 TREEKV_KEEP_LEFT = 1
 TREEKV_SCORE_ACCUMULATED = 4
 TREEKV_POSITION_RERANK = 8
+TREEKV_DEFAULT_LAYOUT = -1
 
 EXPORTS = [
     "treekv_init", "treekv_init_ex", "treekv_destroy", "treekv_get_config", "treekv_workspace_bytes",
     "treekv_bind_workspace", "treekv_reset", "treekv_decode_step", "treekv_prefill_chunk", "treekv_prefill_prompt",
-    "treekv_scores",
+    "treekv_scores", "treekv_state_bytes", "treekv_get_state_layout", "treekv_export_state", "treekv_import_state",
     "treekv_gather_kv", "treekv_wavelet_components", "treekv_strerror", "treekv_last_hip_error",
 ]
 
@@ -38,6 +39,10 @@ class treekv_config(C.Structure):
         ("softmax_scale", C.c_float), ("flags", C.c_int32), ("max_chunk", C.c_int32), ("kv_splits", C.c_int32),
         ("max_prompt", C.c_int32), ("rope_base", C.c_float),
     ]
+
+
+class treekv_state_layout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("header", "positions", "slots", "S", "K", "V", "bytes")]
 
 
 _lib = None
@@ -69,6 +74,11 @@ def load() -> C.CDLL:
     lib.treekv_prefill_prompt.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, i32p, i32p, i32p, vp, vp]
     lib.treekv_scores.argtypes = [vp, vp, vp]
     lib.treekv_gather_kv.argtypes = [vp, vp, vp, vp]
+    lib.treekv_state_bytes.argtypes = [vp]
+    lib.treekv_state_bytes.restype = C.c_size_t
+    lib.treekv_get_state_layout.argtypes = [vp, C.POINTER(treekv_state_layout)]
+    lib.treekv_export_state.argtypes = [vp, vp, C.c_size_t, vp]
+    lib.treekv_import_state.argtypes = [vp, vp, C.c_size_t, i32p, vp]
     lib.treekv_wavelet_components.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp]
     lib.treekv_strerror.argtypes = [C.c_int]
     lib.treekv_strerror.restype = C.c_char_p
@@ -127,8 +137,8 @@ class TreeKV:
                 and rope_base == 0.0:
             rc = self._lib.treekv_init(C.byref(self._h), budget, heads, head_dim)
         else:
-            if n_sink is None and n_recent is None:      # same default layout as treekv_init
-                n_sink, n_recent = 4, budget - budget // 2 - 4
+            if n_sink is None and n_recent is None:      # the library's default layout, as treekv_init takes it
+                n_sink = n_recent = TREEKV_DEFAULT_LAYOUT
             cfg = treekv_config(budget, heads, kv_heads or heads, head_dim, batch,
                                 {"bf16": TREEKV_BF16, "f32": TREEKV_F32}[dtype], n_sink or 0, n_recent or 0,
                                 softmax_scale, flags, max_chunk, kv_splits, max_prompt, rope_base)
@@ -209,6 +219,22 @@ class TreeKV:
             scores = self._torch.empty(c.batch, c.kv_heads, c.budget, dtype=self._torch.float32, device=self.device)
         self._check(self._lib.treekv_scores(self._h, _ptr(scores), self._stream()), "treekv_scores")
         return scores
+
+    def state_layout(self) -> treekv_state_layout:
+        lay = treekv_state_layout()
+        self._check(self._lib.treekv_get_state_layout(self._h, C.byref(lay)), "treekv_get_state_layout")
+        return lay
+
+    def export_state(self, dst=None):
+        """Snapshot of the context into `dst` (uint8 device tensor of treekv_state_bytes; allocated if None)."""
+        if dst is None:
+            dst = self._torch.zeros(self._lib.treekv_state_bytes(self._h), dtype=self._torch.uint8, device=self.device)
+        self._check(self._lib.treekv_export_state(self._h, _ptr(dst), dst.numel(), self._stream()), "treekv_export_state")
+        return dst
+
+    def import_state(self, src, status=None):
+        self._check(self._lib.treekv_import_state(self._h, _ptr(src), src.numel(), _ptr(status), self._stream()),
+                    "treekv_import_state")
 
     def gather_kv(self, K_out=None, V_out=None):
         c = self.cfg

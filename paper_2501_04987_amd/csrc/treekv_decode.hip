@@ -26,48 +26,21 @@ namespace tkv {
 
 namespace {
 
-// Tuning constants (overridable at compile time for sweeps).
-#ifndef TKV_FUSED_THREADS
-#define TKV_FUSED_THREADS 512
-#endif
-#ifndef TKV_SPLIT_THREADS
-#define TKV_SPLIT_THREADS 512
-#endif
-#ifndef TKV_KU
-#define TKV_KU 2
-#endif
-#ifndef TKV_MID_NUM
-#define TKV_MID_NUM 3
-#endif
-#ifndef TKV_NT_S
-#define TKV_NT_S 1
-#endif
-#ifndef TKV_NT_LOAD
-#define TKV_NT_LOAD 1
-#endif
-// 16-byte row piece; optionally with the non-temporal hint (rows are read once per step)
+// 16-byte row piece with the non-temporal hint: a cache row is read once per step.
 __device__ inline uint4 ld_row16(const void* ptr) {
-#if TKV_NT_LOAD
   typedef unsigned v4u __attribute__((ext_vector_type(4)));
   const v4u r = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(ptr));
   return make_uint4(r.x, r.y, r.z, r.w);
-#else
-  return *reinterpret_cast<const uint4*>(ptr);
-#endif
 }
-template <bool NT, typename V>
-__device__ inline void store_maybe_nt(V v, V* ptr) {
-  if constexpr (NT) __builtin_nontemporal_store(v, ptr);
-  else *ptr = v;
-}
-constexpr int FUSED_THREADS = TKV_FUSED_THREADS;
-constexpr int SPLIT_THREADS = TKV_SPLIT_THREADS;
+// Measured best of 256 .. 1024 threads per workgroup, for both shapes.
+constexpr int FUSED_THREADS = 512;
+constexpr int SPLIT_THREADS = 512;
 constexpr int MERGE_THREADS = 1024;
-constexpr int KU = TKV_KU;             // wave loads of K (and of V) per tile
+constexpr int KU = 2;                  // wave loads of K (and of V) per tile (4: measured slower)
 constexpr float NEG_BIG = -1.0e30f;
 // Iteration (of n) of the streaming loop at which a workgroup issues its mid-stream stores.  Measured: the
 // later they go the better, as long as they are out before the epilogue; early ones interrupt the reads.
-__device__ inline int mid_point(int n) { return n * TKV_MID_NUM / 4; }
+__device__ inline int mid_point(int n) { return n * 3 / 4; }
 constexpr size_t LDS_LIMIT = 150 * 1024;   // of the 160 KB a workgroup can have
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
@@ -695,7 +668,7 @@ __device__ inline void epilogue(const Params& p, int unit, const Step& st, const
     return a;
   };
   auto put_score = [&](int slot, float sn) {
-    store_maybe_nt<TKV_NT_S>(sn, Su + slot);
+    __builtin_nontemporal_store(sn, Su + slot);    // read again only a whole step later
     if constexpr (EP > 0) park[slot] = sn;
     else {
       if (slot == st.scope_l) sm_sc[0] = sn;
@@ -1001,7 +974,7 @@ int launch_decode_g(const Params& p, const void* q, const void* k, const void* v
     if (lds > LDS_LIMIT) return TREEKV_EUNSUPPORTED;
     auto kern = decode_fused_kernel<T, D, G, ROPE>;
     if (lds > 48 * 1024 &&
-        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        hip_failed(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))
       return TREEKV_EHIP;
     hipLaunchKernelGGL(kern, dim3(p.U), dim3(FUSED_THREADS), lds, s, p, qt, kt, vt, out, retained, n_retained, evicted);
   } else {
@@ -1010,14 +983,14 @@ int launch_decode_g(const Params& p, const void* q, const void* k, const void* v
     if (lds > LDS_LIMIT) return TREEKV_EUNSUPPORTED;
     auto kern = decode_split_kernel<T, D, G, ROPE>;
     if (lds > 48 * 1024 &&
-        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        hip_failed(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))
       return TREEKV_EHIP;
     hipLaunchKernelGGL(kern, dim3(p.nsplit, p.U), dim3(SPLIT_THREADS), lds, s, p, qt, kt, vt);
     const size_t mlds = (size_t)G * p.cap * sizeof(float);
     if (mlds <= LDS_LIMIT) {
       auto merge = decode_merge_kernel<T, D, G, true>;
       if (mlds > 48 * 1024 &&
-          hipFuncSetAttribute((const void*)merge, hipFuncAttributeMaxDynamicSharedMemorySize, (int)mlds) != hipSuccess)
+          hip_failed(hipFuncSetAttribute((const void*)merge, hipFuncAttributeMaxDynamicSharedMemorySize, (int)mlds)))
         return TREEKV_EHIP;
       hipLaunchKernelGGL(merge, dim3(p.U), dim3(MERGE_THREADS), mlds, s, p, kt, vt, out, retained, n_retained, evicted);
     } else {
@@ -1025,7 +998,7 @@ int launch_decode_g(const Params& p, const void* q, const void* k, const void* v
                          retained, n_retained, evicted);
     }
   }
-  return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
+  return finish_launch();
 }
 
 template <typename T, int D>

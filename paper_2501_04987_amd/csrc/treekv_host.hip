@@ -129,9 +129,183 @@ __global__ void gather_kv_kernel(Params p, uint4* __restrict__ Kout, uint4* __re
   }
 }
 
-int check_launch() { return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP; }
+// ---- snapshots of a context's state (treekv_export_state / treekv_import_state) -------------------
+// Byte offsets of the snapshot's arrays; every array starts on a 256-byte boundary.
+treekv_state_layout state_layout(const Params& p) {
+  treekv_state_layout l;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off += align_up(bytes); return at; };
+  const size_t esz = p.dtype == TREEKV_BF16 ? 2 : 4, U = p.U, c = p.budget;
+  l.header = take(U * 4 * 4);
+  l.positions = take(U * c * 4);
+  l.slots = take(U * c * 4);
+  l.S = take(U * c * 4);
+  l.K = take(U * c * p.D * esz);
+  l.V = take(U * c * p.D * esz);
+  l.bytes = off;
+  return l;
+}
+
+// Header, positions, slots and S of every unit, in position order (the K and V rows go through gather_kv_kernel).
+__global__ void export_state_kernel(Params p, int* __restrict__ hdr, int* __restrict__ pos, int* __restrict__ slots,
+                                    float* __restrict__ S) {
+  const int unit = blockIdx.x;
+  const int* meta = p.meta + (size_t)unit * META_STRIDE;
+  const int n = meta[META_N], j = meta[META_J], rhead = meta[META_RHEAD], t = meta[META_T];
+  const int* Eu = p.E + (size_t)unit * 2 * p.m;
+  const int* PEu = p.PE + (size_t)unit * 2 * p.m;
+  const int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
+  if (threadIdx.x < 4) {
+    const int h[4] = {n, t, j + 1, 0};
+    hdr[(size_t)unit * 4 + threadIdx.x] = h[threadIdx.x];
+  }
+  for (int i = threadIdx.x; i < p.budget; i += blockDim.x) {
+    int po = -1, sl = -1;
+    float sc = 0.f;
+    if (i < n) {
+      po = sl = i;                        // while the cache fills, token i sits in slot i
+      if (n == p.budget) {
+        sl = logical_to_slot(p, Eu, Ru, rhead, j, i);
+        const int k = i - p.n_sink;
+        if (k >= p.m) po = t - p.n_recent + (k - p.m);
+        else if (k >= 0) po = PEu[tree_index(k, j)];
+      }
+      sc = p.S[(size_t)unit * p.cap + sl];
+    }
+    const size_t o = (size_t)unit * p.budget + i;
+    pos[o] = po; slots[o] = sl; S[o] = sc;
+  }
+}
+
+// Checks one unit's snapshot and, if it describes a state Algorithm 1 can be in, rebuilds the unit's bookkeeping
+// from it; a unit whose snapshot does not pass is left empty (as after a reset).  The slot every token's rows go to
+// is left in pf_list[unit][0 .. budget) for import_rows_kernel (-1: no row to copy).
+__global__ __launch_bounds__(256) void import_state_kernel(Params p, const int* __restrict__ hdr,
+                                                           const int* __restrict__ pos, const int* __restrict__ slots,
+                                                           const float* __restrict__ S, int32_t* __restrict__ status) {
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  const int n = hdr[(size_t)unit * 4], t = hdr[(size_t)unit * 4 + 1], j = hdr[(size_t)unit * 4 + 2] - 1;
+  const int c = p.budget, m = p.m, r = p.n_recent, sink = p.n_sink, cap = p.cap;
+  const int* po = pos + (size_t)unit * c;
+  const int* sl = slots + (size_t)unit * c;
+  int* meta = p.meta + (size_t)unit * META_STRIDE;
+  int* Eu = p.E + (size_t)unit * 2 * m;
+  int* PEu = p.PE + (size_t)unit * 2 * m;
+  int* Ru = p.R + (size_t)unit * max(r, 1);
+  float* Su = p.S + (size_t)unit * cap;
+  int* mark = p.pf_flag + (size_t)unit * (cap + p.max_chunk);       // [cap] scratch: which token claims a slot
+  int* dest = p.pf_list + (size_t)unit * (cap + p.max_chunk);       // [budget] slot of token i
+  __shared__ int sm_free;
+
+  // the scalars, then the arrays
+  int bad = (n < 0 || n > c || t < n || j < 0 || j >= m) ? 1 : 0;
+  const bool full = n == c;
+  if (!bad && !full && (t != n || j != 0)) bad = 1;                  // nothing has been evicted while the cache fills
+  const bool own_slots = !bad && full && sl[0] >= 0;                 // else: token i goes to slot i
+  if (!bad) {
+    for (int i = tid; i < n; i += 256) {
+      const int x = po[i];
+      if (!full) { if (x != i) bad = 1; continue; }
+      const int k = i - sink;
+      if (x < 0 || x >= t || (i > 0 && po[i - 1] >= x)) bad = 1;     // ascending positions below t
+      if (k < 0 && x != i) bad = 1;                                  // the sinks are the first tokens
+      if (k >= m && x != t - r + (k - m)) bad = 1;                   // the recent window is the last r tokens
+      if (own_slots && (sl[i] < 0 || sl[i] >= cap)) bad = 1;
+    }
+  }
+  bad = __syncthreads_or(bad);
+  if (!bad && own_slots) {                                           // every slot claimed once
+    for (int s = tid; s < cap; s += 256) mark[s] = -1;
+    __syncthreads();
+    for (int i = tid; i < n; i += 256) mark[sl[i]] = i;
+    __syncthreads();
+    for (int i = tid; i < n; i += 256) if (mark[sl[i]] != i) bad = 1;
+    bad = __syncthreads_or(bad);
+  }
+  if (status && tid == 0) status[unit] = bad ? TREEKV_EINVAL : TREEKV_OK;
+  const int n_eff = bad ? 0 : n;
+
+  int free_slot = n_eff;                                             // filling, or token i in slot i: the next slot
+  if (!bad && own_slots) {
+    for (int s = tid; s < cap; s += 256) if (mark[s] < 0) sm_free = s;   // cap = n + 1 slots: exactly one is unclaimed
+    __syncthreads();
+    free_slot = sm_free;
+  }
+  const bool use_slots = own_slots && !bad, use_pos = full && !bad;
+  auto slot_of = [&](int i) { return use_slots ? sl[i] : i; };
+  auto pos_of = [&](int i) { return use_pos ? po[i] : i; };
+  const int jd = bad ? 0 : j;
+  for (int i = tid; i < 2 * m; i += 256) Eu[i] = PEu[i] = 0;
+  for (int s = tid; s < cap; s += 256) Su[s] = 0.f;
+  __syncthreads();
+  for (int k = tid; k < m; k += 256) {
+    const int x = tree_index(k, jd);
+    Eu[x] = slot_of(sink + k);
+    PEu[x] = pos_of(sink + k);
+  }
+  for (int k = tid; k < r; k += 256) Ru[k] = slot_of(sink + m + k);
+  for (int i = tid; i < c; i += 256) {
+    dest[i] = i < n_eff ? slot_of(i) : -1;
+    if (i < n_eff) Su[slot_of(i)] = S[(size_t)unit * c + i];
+  }
+  if (tid < META_STRIDE) {
+    int w = 0;
+    if (tid == META_N) w = n_eff;
+    else if (tid == META_FREE) w = free_slot;
+    else if (tid == META_J) w = jd;
+    else if (tid == META_T) w = bad ? 0 : t;
+    meta[tid] = w;
+  }
+}
+
+__global__ void import_rows_kernel(Params p, const uint4* __restrict__ Kin, const uint4* __restrict__ Vin, int row_vec) {
+  const int unit = blockIdx.y, i = blockIdx.x;   // one block per snapshot row
+  const int slot = p.pf_list[(size_t)unit * (p.cap + p.max_chunk) + i];
+  if (slot < 0) return;
+  const size_t src = ((size_t)unit * p.budget + i) * row_vec;
+  const size_t dst = ((size_t)unit * p.cap + slot) * row_vec;
+  for (int e = threadIdx.x; e < row_vec; e += blockDim.x) {
+    reinterpret_cast<uint4*>(p.K)[dst + e] = Kin[src + e];
+    reinterpret_cast<uint4*>(p.V)[dst + e] = Vin[src + e];
+  }
+}
+
+thread_local hipError_t tl_hip_error = hipSuccess;
+
+int check_launch() { return finish_launch(); }
 
 }  // namespace
+
+bool hip_failed(hipError_t e) {
+  if (e == hipSuccess) return false;
+  tl_hip_error = e;
+  return true;
+}
+int finish_launch() { return hip_failed(hipGetLastError()) ? TREEKV_EHIP : TREEKV_OK; }
+hipError_t take_hip_error() {
+  const hipError_t e = tl_hip_error;
+  tl_hip_error = hipSuccess;
+  return e;
+}
+
+int launch_export_state(const Params& p, char* dst, hipStream_t s) {
+  const treekv_state_layout l = state_layout(p);
+  const int row_vec = p.D * (p.dtype == TREEKV_BF16 ? 2 : 4) / 16;
+  hipLaunchKernelGGL(export_state_kernel, dim3(p.U), dim3(256), 0, s, p, (int*)(dst + l.header), (int*)(dst + l.positions),
+                     (int*)(dst + l.slots), (float*)(dst + l.S));
+  hipLaunchKernelGGL(gather_kv_kernel, dim3(p.budget, p.U), dim3(64), 0, s, p, (uint4*)(dst + l.K), (uint4*)(dst + l.V), row_vec);
+  return finish_launch();
+}
+
+int launch_import_state(const Params& p, const char* src, int32_t* status, hipStream_t s) {
+  const treekv_state_layout l = state_layout(p);
+  const int row_vec = p.D * (p.dtype == TREEKV_BF16 ? 2 : 4) / 16;
+  hipLaunchKernelGGL(import_state_kernel, dim3(p.U), dim3(256), 0, s, p, (const int*)(src + l.header),
+                     (const int*)(src + l.positions), (const int*)(src + l.slots), (const float*)(src + l.S), status);
+  hipLaunchKernelGGL(import_rows_kernel, dim3(p.budget, p.U), dim3(64), 0, s, p, (const uint4*)(src + l.K),
+                     (const uint4*)(src + l.V), row_vec);
+  return finish_launch();
+}
 
 int launch_reset(const Params& p, hipStream_t s) {
   hipLaunchKernelGGL(reset_kernel, dim3(p.U), dim3(256), 0, s, p);
@@ -160,12 +334,16 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Every entry point that launches calls fresh() first: an error an earlier, unrelated HIP call of this thread
+// left behind is dropped there, so it is not taken for a failure of this library's launches.
+void fresh() {
+  (void)hipGetLastError();
+  (void)tkv::take_hip_error();
+}
+
 int record_hip(treekv_ctx* ctx, int rc) {
-  if (rc == TREEKV_EHIP) {
-    hipError_t e = hipPeekAtLastError();
-    snprintf(ctx->hip_err, sizeof(ctx->hip_err), "%s", hipGetErrorString(e));
-    (void)hipGetLastError();
-  }
+  const hipError_t e = tkv::take_hip_error();
+  if (rc == TREEKV_EHIP) snprintf(ctx->hip_err, sizeof(ctx->hip_err), "%s", hipGetErrorString(e));
   return rc;
 }
 
@@ -193,6 +371,12 @@ int treekv_init_ex(treekv_ctx** out, const treekv_config* cfg_in) {
   treekv_config c = *cfg_in;
   if (c.budget < 1 || c.q_heads < 1 || c.kv_heads < 1 || c.batch < 1) return TREEKV_EINVAL;
   if (c.q_heads % c.kv_heads != 0) return TREEKV_EINVAL;
+  if (c.n_sink == TREEKV_DEFAULT_LAYOUT && c.n_recent == TREEKV_DEFAULT_LAYOUT) {
+    // Section 5.2's 4 initial + 512 selected + 508 recent tokens of 1024, scaled to the budget
+    if (c.budget < 16) return TREEKV_EINVAL;
+    c.n_sink = 4;
+    c.n_recent = c.budget - c.budget / 2 - 4;
+  }
   if (c.n_sink < 0 || c.n_recent < 0 || c.budget - c.n_sink - c.n_recent < 1) return TREEKV_EINVAL;
   if (c.dtype != TREEKV_BF16 && c.dtype != TREEKV_F32) return TREEKV_EINVAL;
   if (c.flags & ~(TREEKV_KEEP_LEFT | TREEKV_SCORE_ACCUMULATED | TREEKV_POSITION_RERANK)) return TREEKV_EINVAL;
@@ -243,8 +427,7 @@ int treekv_init(treekv_ctx** out, int budget, int heads, int head_dim) {
   memset(&c, 0, sizeof(c));
   c.budget = budget; c.q_heads = heads; c.kv_heads = heads; c.head_dim = head_dim; c.batch = 1;
   c.dtype = TREEKV_BF16;
-  c.n_sink = 4;
-  c.n_recent = budget - budget / 2 - 4;   // tree region = budget / 2 slots
+  c.n_sink = c.n_recent = TREEKV_DEFAULT_LAYOUT;
   return treekv_init_ex(out, &c);
 }
 
@@ -269,6 +452,7 @@ int treekv_bind_workspace(treekv_ctx* ctx, void* dev_ptr, size_t bytes) {
 int treekv_reset(treekv_ctx* ctx, void* stream) {
   if (!ctx) return TREEKV_EINVAL;
   if (!ctx->bound) return TREEKV_ENOWS;
+  fresh();
   return record_hip(ctx, tkv::launch_reset(ctx->p, (hipStream_t)stream));
 }
 
@@ -277,6 +461,7 @@ int treekv_decode_step(treekv_ctx* ctx, const void* q, const void* k, const void
   if (!ctx || !q || !k || !v || !out || !retained) return TREEKV_EINVAL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return TREEKV_EINVAL;
   if (!ctx->bound) return TREEKV_ENOWS;
+  fresh();
   return record_hip(ctx, tkv::launch_decode(ctx->p, q, k, v, (float*)out, retained, n_retained, evicted,
                                             (hipStream_t)stream));
 }
@@ -288,6 +473,7 @@ int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const vo
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out)) return TREEKV_EINVAL;
   if (ctx->cfg.flags & TREEKV_POSITION_RERANK) return TREEKV_EUNSUPPORTED;
   if (!ctx->bound) return TREEKV_ENOWS;
+  fresh();
   return record_hip(ctx, tkv::launch_prefill(ctx->p, Q, K, V, len, (float*)out, retained, n_retained, evicted,
                                              (hipStream_t)stream));
 }
@@ -305,13 +491,39 @@ int treekv_prefill_prompt(treekv_ctx* ctx, const void* Qw, const void* K, const 
   // the window's queries of one KV head's group are the rows of one matrix operand set
   if (block * (c.q_heads / c.kv_heads) > 128) return TREEKV_EUNSUPPORTED;
   if (tkv::prompt_blocks_lds(len, block, cb, sink_b, recent_b) > 150 * 1024) return TREEKV_EUNSUPPORTED;
+  fresh();
   return record_hip(ctx, tkv::launch_prompt(ctx->p, Qw, K, V, len, block, retained, n_retained, evicted_blocks,
                                             token_scores, (hipStream_t)stream));
+}
+
+size_t treekv_state_bytes(const treekv_ctx* ctx) { return ctx ? tkv::state_layout(ctx->p).bytes : 0; }
+
+int treekv_get_state_layout(const treekv_ctx* ctx, treekv_state_layout* out) {
+  if (!ctx || !out) return TREEKV_EINVAL;
+  *out = tkv::state_layout(ctx->p);
+  return TREEKV_OK;
+}
+
+int treekv_export_state(treekv_ctx* ctx, void* dst, size_t bytes, void* stream) {
+  if (!ctx || !dst) return TREEKV_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(dst) & (tkv::ALIGN - 1)) != 0 || bytes < tkv::state_layout(ctx->p).bytes) return TREEKV_EINVAL;
+  if (!ctx->bound) return TREEKV_ENOWS;
+  fresh();
+  return record_hip(ctx, tkv::launch_export_state(ctx->p, static_cast<char*>(dst), (hipStream_t)stream));
+}
+
+int treekv_import_state(treekv_ctx* ctx, const void* src, size_t bytes, int32_t* status, void* stream) {
+  if (!ctx || !src) return TREEKV_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(src) & (tkv::ALIGN - 1)) != 0 || bytes < tkv::state_layout(ctx->p).bytes) return TREEKV_EINVAL;
+  if (!ctx->bound) return TREEKV_ENOWS;
+  fresh();
+  return record_hip(ctx, tkv::launch_import_state(ctx->p, static_cast<const char*>(src), status, (hipStream_t)stream));
 }
 
 int treekv_scores(treekv_ctx* ctx, float* scores, void* stream) {
   if (!ctx || !scores) return TREEKV_EINVAL;
   if (!ctx->bound) return TREEKV_ENOWS;
+  fresh();
   return record_hip(ctx, tkv::launch_scores(ctx->p, scores, (hipStream_t)stream));
 }
 
@@ -319,6 +531,7 @@ int treekv_gather_kv(treekv_ctx* ctx, void* K_out, void* V_out, void* stream) {
   if (!ctx || !K_out || !V_out) return TREEKV_EINVAL;
   if (!aligned16(K_out) || !aligned16(V_out)) return TREEKV_EINVAL;
   if (!ctx->bound) return TREEKV_ENOWS;
+  fresh();
   return record_hip(ctx, tkv::launch_gather_kv(ctx->p, K_out, V_out, (hipStream_t)stream));
 }
 
@@ -329,7 +542,10 @@ int treekv_wavelet_components(const float* a, const void* V, int dtype, int head
   if (heads < 1 || t < 1 || levels < 1 || levels > 30 || t % (1 << levels) != 0) return TREEKV_EINVAL;
   if (!aligned16(V)) return TREEKV_EINVAL;
   if (levels > 5 || (d != 64 && d != 128) || heads > 65535 || (long long)levels * t > (1ll << 30)) return TREEKV_EUNSUPPORTED;
-  return tkv::launch_wavelet(a, V, dtype, heads, t, d, levels, per_head, mean, (hipStream_t)stream);
+  fresh();
+  const int rc = tkv::launch_wavelet(a, V, dtype, heads, t, d, levels, per_head, mean, (hipStream_t)stream);
+  (void)tkv::take_hip_error();
+  return rc;
 }
 
 const char* treekv_strerror(int status) {

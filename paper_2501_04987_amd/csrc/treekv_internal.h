@@ -66,6 +66,13 @@ struct Params {
 };
 constexpr int PROMPT_MAX_SPLITS = 64;
 
+// HIP errors.  A launch_* function ends with finish_launch(), which takes HIP's last error (and so clears
+// it); hip_failed(e) is true for e != hipSuccess.  Either way the error is remembered, per host thread,
+// until the C entry point that ran the launch copies its text into the context (take_hip_error).
+int finish_launch();
+bool hip_failed(hipError_t e);
+hipError_t take_hip_error();
+
 // true if the decode kernels of the current shape (p.nsplit, p.rows_per_split) fit in LDS
 bool decode_shape_fits(const Params& p);
 int launch_reset(const Params& p, hipStream_t s);
@@ -80,6 +87,8 @@ int launch_wavelet(const float* a, const void* V, int dtype, int heads, int t, i
                    float* mean, hipStream_t s);
 int launch_scores(const Params& p, float* scores, hipStream_t s);
 int launch_gather_kv(const Params& p, void* K_out, void* V_out, hipStream_t s);
+int launch_export_state(const Params& p, char* dst, hipStream_t s);
+int launch_import_state(const Params& p, const char* src, int32_t* status, hipStream_t s);
 
 // ---- device helpers shared by the kernels ---------------------------------
 #if defined(__HIPCC__)

@@ -930,7 +930,7 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
   auto attend = prefill_attend_kernel<D>;
   const size_t lds = AttendLds<D>::BYTES;
   if (lds > 48 * 1024 &&
-      hipFuncSetAttribute((const void*)attend, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      hip_failed(hipFuncSetAttribute((const void*)attend, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))
     return TREEKV_EHIP;
   const int n_items = row_tiles * p.G * p.U;
   hipLaunchKernelGGL(attend, dim3((n_items + 7) / 8 * 8), dim3(AT_THREADS), lds, s, p, q, k, v, L, row_tiles, out);
@@ -938,7 +938,7 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
   if (rp_lds <= 140 * 1024) {
     auto replay = prefill_replay_kernel<true>;
     if (rp_lds > 48 * 1024 &&
-        hipFuncSetAttribute((const void*)replay, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rp_lds) != hipSuccess)
+        hip_failed(hipFuncSetAttribute((const void*)replay, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rp_lds)))
       return TREEKV_EHIP;
     hipLaunchKernelGGL(replay, dim3(p.U), dim3(RP_THREADS), rp_lds, s, p, L, retained, n_retained, evicted);
   } else {
@@ -947,7 +947,7 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
   }
   hipLaunchKernelGGL(prefill_scatter_kernel, dim3((L + 256 / (D / 8) - 1) / (256 / (D / 8)), p.U), dim3(256), 0, s, p, (const uint4*)K, (const uint4*)V, L,
                      D * 2 / 16);
-  return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
+  return finish_launch();
 }
 
 }  // namespace

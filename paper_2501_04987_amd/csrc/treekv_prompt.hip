@@ -521,11 +521,11 @@ int launch_streams(const Params& p, const uint16_t* Qw, const uint16_t* K, int T
                    int nsplit, int block_means, hipStream_t s) {
   constexpr size_t q_lds = PromptStream<D, NB, ROPE>::Q_LDS_BYTES;
   const size_t lds = q_lds + (block_means ? (size_t)rows_per_split * 4 : 0);
-  if (q_lds > 48 * 1024 && hipFuncSetAttribute((const void*)prompt_stats_kernel<D, NB, ROPE>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)q_lds) != hipSuccess)
+  if (q_lds > 48 * 1024 && hip_failed(hipFuncSetAttribute((const void*)prompt_stats_kernel<D, NB, ROPE>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)q_lds)))
     return TREEKV_EHIP;
-  if (lds > 48 * 1024 && hipFuncSetAttribute((const void*)prompt_scores_kernel<D, NB, ROPE>,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+  if (lds > 48 * 1024 && hip_failed(hipFuncSetAttribute((const void*)prompt_scores_kernel<D, NB, ROPE>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))
     return TREEKV_EHIP;
   if constexpr (ROPE) hipLaunchKernelGGL((prompt_turn_queries_kernel<D>), dim3(128 * (D / 2) / 256, p.U), dim3(256), 0, s, p, Qw, T, W);
   hipLaunchKernelGGL((prompt_stats_kernel<D, NB, ROPE>), dim3(nsplit, p.U), dim3(PP_THREADS), q_lds, s, p, Qw, K, T, W,
@@ -557,10 +557,7 @@ int launch_streams_d(const Params& p, const uint16_t* Qw, const uint16_t* K, int
 // statistics pass over a 32k prompt of 32 heads), a slice a multiple of what a workgroup
 // takes per iteration, at most PROMPT_MAX_SPLITS of them.
 int prompt_splits(const Params& p, int T, int* rows_per_split) {
-#ifndef TKV_PP_WGS
-#define TKV_PP_WGS 256
-#endif
-  int ns = (TKV_PP_WGS + p.U - 1) / p.U;
+  int ns = (256 + p.U - 1) / p.U;
   const int by_len = (T + PP_STEP - 1) / PP_STEP;
   if (ns > by_len) ns = by_len;
   if (ns > PROMPT_MAX_SPLITS) ns = PROMPT_MAX_SPLITS;
@@ -589,7 +586,7 @@ int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V,
   if (rc != TREEKV_OK) return rc;
   const size_t lds = prompt_blocks_lds(T, b, cb, sink_b, recent_b);
   if (lds > 48 * 1024 &&
-      hipFuncSetAttribute((const void*)prompt_blocks_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      hip_failed(hipFuncSetAttribute((const void*)prompt_blocks_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))
     return TREEKV_EHIP;
   const int blocks_threads = 256;
   hipLaunchKernelGGL(prompt_blocks_kernel, dim3(p.U), dim3(blocks_threads), lds, s, p, T, b, cb, sink_b, recent_b,
@@ -599,9 +596,9 @@ int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V,
   hipLaunchKernelGGL(prompt_handoff_kernel, dim3((p.budget + per_wg - 1) / per_wg, p.U), dim3(256), 0, s, p,
                      (const uint4*)K, (const uint4*)V, T, b, n, row_vec, retained, n_retained);
   if (token_scores &&
-      hipMemcpyAsync(token_scores, p.pp_tok, (size_t)p.U * T * sizeof(float), hipMemcpyDeviceToDevice, s) != hipSuccess)
+      hip_failed(hipMemcpyAsync(token_scores, p.pp_tok, (size_t)p.U * T * sizeof(float), hipMemcpyDeviceToDevice, s)))
     return TREEKV_EHIP;
-  return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
+  return finish_launch();
 }
 
 }  // namespace tkv

@@ -198,7 +198,7 @@ int launch_wavelet(const float* a, const void* V, int dtype, int heads, int t, i
     const int n = levels * t;
     hipLaunchKernelGGL(wavelet_mean_kernel, dim3((n + MEAN_COLS - 1) / MEAN_COLS), dim3(MEAN_COLS * MEAN_LANES), 0, s, per_head, heads, n, mean);
   }
-  return hipGetLastError() == hipSuccess ? TREEKV_OK : TREEKV_EHIP;
+  return finish_launch();
 }
 
 }  // namespace tkv

@@ -170,3 +170,44 @@ def test_wavelet_host_checks(binding):
     assert call(one, one, 0, 1, 64, 128, 6, one) == binding.TREEKV_EUNSUPPORTED
     assert call(one, one, 0, 1, 64, 96, 5, one) == binding.TREEKV_EUNSUPPORTED
     assert call(one, one, 0, 70000, 64, 128, 5, one) == binding.TREEKV_EUNSUPPORTED
+
+
+def test_default_layout_through_the_config(binding):
+    """n_sink = n_recent = TREEKV_DEFAULT_LAYOUT selects the layout treekv_init chooses; one of them alone is an error."""
+    lib = binding.load()
+    d = binding.TREEKV_DEFAULT_LAYOUT
+    rc, h = _init(binding, budget=1024, n_sink=d, n_recent=d, batch=3)
+    assert rc == 0
+    cfg = binding.treekv_config()
+    lib.treekv_get_config(h, C.byref(cfg))
+    assert (cfg.n_sink, cfg.budget - cfg.n_sink - cfg.n_recent, cfg.n_recent, cfg.batch) == (4, 512, 508, 3)
+    lib.treekv_destroy(h)
+    assert _init(binding, budget=8, n_sink=d, n_recent=d)[0] == binding.TREEKV_EINVAL
+    assert _init(binding, budget=64, n_sink=d, n_recent=3)[0] == binding.TREEKV_EINVAL
+
+
+def test_snapshot_sizes_and_argument_checks(binding):
+    """The snapshot's arrays are laid out back to back on 256-byte boundaries; bad arguments are refused before
+    anything is enqueued (so these calls need no GPU)."""
+    lib = binding.load()
+    rc, h = _init(binding, budget=100, q_heads=8, kv_heads=2, batch=3, n_sink=1, n_recent=9)
+    assert rc == 0
+    lay = binding.treekv_state_layout()
+    assert lib.treekv_get_state_layout(h, C.byref(lay)) == 0
+    U, c, d = 6, 100, 128
+    up = lambda x: (x + 255) // 256 * 256
+    want = [0]
+    for b in (U * 16, U * c * 4, U * c * 4, U * c * 4, U * c * d * 2, U * c * d * 2):
+        want.append(want[-1] + up(b))
+    assert [lay.header, lay.positions, lay.slots, lay.S, lay.K, lay.V, lay.bytes] == want
+    assert lib.treekv_state_bytes(h) == lay.bytes and lib.treekv_state_bytes(None) == 0
+    buf = C.c_void_p(0x10000)
+    assert lib.treekv_export_state(h, None, lay.bytes, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_export_state(h, buf, lay.bytes - 1, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_export_state(h, C.c_void_p(0x10010), lay.bytes, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_import_state(h, None, lay.bytes, None, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_import_state(h, buf, 5, None, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_export_state(h, buf, lay.bytes, None) == binding.TREEKV_ENOWS        # no workspace bound
+    assert lib.treekv_import_state(h, buf, lay.bytes, None, None) == binding.TREEKV_ENOWS
+    assert lib.treekv_get_state_layout(None, C.byref(lay)) == binding.TREEKV_EINVAL
+    lib.treekv_destroy(h)

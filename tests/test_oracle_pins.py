@@ -951,3 +951,126 @@ def test_rerank_prompt_brute_force(oracle):
             o_b, ev_b = bf.decode_step(q[t].tolist(), k[t].tolist(), v[t].tolist())
             assert ev == ev_b, (seed, t)
             np.testing.assert_allclose(out, np.array(o_b), rtol=1e-9, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- #
+# The decision margin |Sbar_l - Sbar_r| / max(Sbar_l, Sbar_r): it gates the near-tie handling of the parity runs
+# --------------------------------------------------------------------------- #
+class _UniformAttentionExact:
+    """Algorithm 1 under uniform attention (q = 0) in exact rational arithmetic: every step adds G / len to every
+    cached token, so S_p = G * (P[t] - P[p-1]) with P the running sum of 1 / len.  step() appends the next token and
+    returns None, or the scope (left position, right position, Sbar_l, Sbar_r) as Fractions; evict() removes one."""
+
+    def __init__(self, c, n_sink=0, n_recent=0, G=1):
+        from fractions import Fraction
+
+        self.F, self.c, self.n_sink, self.m, self.G = Fraction, c, n_sink, c - n_sink - n_recent, G
+        self.P, self.cache, self.idx0, self.t = [Fraction(0)], [], 0, -1
+
+    def step(self):
+        self.t += 1
+        t = self.t
+        self.cache.append(t)
+        self.P.append(self.P[-1] + self.F(1, len(self.cache)))
+        if len(self.cache) <= self.c:
+            return None
+        sbar = lambda p: self.G * (self.P[t + 1] - self.P[p]) / (t - p + 1)
+        l, r = self.cache[self.n_sink + self.idx0], self.cache[self.n_sink + self.idx0 + 1]
+        return l, r, sbar(l), sbar(r)
+
+    def evict(self, pos):
+        self.cache.remove(pos)
+        self.idx0 = (self.idx0 + 1) % self.m
+
+
+@pytest.mark.parametrize("c,n_sink,n_recent,G,T", [(4, 0, 0, 1, 40), (12, 2, 3, 2, 90), (64, 4, 28, 1, 400),
+                                                   (1023, 0, 0, 1, 1100)])
+def test_margin_is_the_relative_score_difference(oracle, c, n_sink, n_recent, G, T):
+    """With q = 0 the two scores of every scope are known rationals (tokens of unequal age have seen different cache
+    lengths), so the evicted position is known and the reported margin must equal |l - r| / max(l, r) to rounding.
+    (Where the rationals tie, the fp64 sums may differ in the last bit unless 1 / (c+1) is a binary fraction: the
+    reference then takes the oracle's pick of the two.)"""
+    d = 2
+    rng = np.random.default_rng(1)
+    k, v = rng.standard_normal((T, d)), rng.standard_normal((T, d))
+    s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent)
+    ref = _UniformAttentionExact(c, n_sink, n_recent, G)
+    apart = decided = 0
+    for t in range(T):
+        _, ev, margin, _, _ = s.decode_step(np.zeros((G, d)), k[t], v[t])
+        scope = ref.step()
+        if scope is None:
+            assert ev == -1 and margin == -1.0
+            continue
+        l, r, sl, sr = scope
+        mg = abs(sl - sr) / max(sl, sr)
+        assert abs(margin - float(mg)) <= 1e-12, (t, margin, float(mg))
+        if mg == 0:
+            assert ev in (l, r)
+            if (c + 1) & c == 0:
+                assert margin == 0.0 and ev == l         # an exact tie: the strict ">" evicts the left slot
+        else:
+            assert ev == (r if sl > sr else l), t
+            decided += 1
+            # what the margin is NOT: the absolute difference, or the difference over the smaller score
+            absolute, over_min = float(abs(sl - sr)), float(abs(sl - sr) / min(sl, sr))
+            if abs(absolute - float(mg)) > 1e-6 and abs(over_min - float(mg)) > 1e-6:
+                apart += 1
+        ref.evict(ev)
+        assert list(s.retained()) == ref.cache
+    assert apart > 0 and decided > 0
+
+
+def test_margin_relative_and_absolute_differ_by_orders_of_magnitude(oracle):
+    """Budget 1023, uniform attention: scores are about 1e-3, so a relative margin of a few per cent is an absolute
+    difference of order 1e-5 -- below a 1e-4 threshold taken absolutely, far above it taken relatively."""
+    c = 1023
+    ref = _UniformAttentionExact(c)
+    for _ in range(c):
+        assert ref.step() is None
+    l, r, sl, sr = ref.step()                   # first eviction: tokens 0 and 1, the older one scores higher
+    mg = abs(sl - sr) / max(sl, sr)
+    assert (l, r) == (0, 1) and sl > sr
+    assert float(mg) > 0.05 and float(abs(sl - sr)) < 1e-3 and float(abs(sl - sr)) * 50 < float(mg)
+    d = 2
+    s = oracle.OracleStream(c, 1, d)
+    rng = np.random.default_rng(2)
+    for t in range(c + 1):
+        _, ev, margin, _, _ = s.decode_step(np.zeros((1, d)), rng.standard_normal(d), rng.standard_normal(d),
+                                            forced_pos=0 if t == c else -1, follow_thresh=1e-4)
+    # the other implementation's choice (token 0) is NOT adopted: the margin is far above the threshold
+    assert ev == 1 and abs(margin - float(mg)) <= 1e-12
+    assert s.retained()[0] == 0
+
+
+def test_margin_in_prefill_chunk_and_prompt_blocks(oracle):
+    """The same definition in the chunk replay (frozen scores) and at block level: recomputed from the scores the
+    oracle reports."""
+    c, G, d = 8, 1, 4
+    q, k, v = _rand_stream(77, 60, G, d)
+    s = oracle.OracleStream(c, G, d, n_sink=1, n_recent=2)
+    s.prefill_chunk(q[:8], k[:8], v[:8])
+    pos0, S0, C0 = s.state()
+    t = oracle.OracleStream(c, G, d, n_sink=1, n_recent=2)
+    t.prefill_chunk(q[:8], k[:8], v[:8])
+    res = s.prefill_chunk(q[8:9], k[8:9], v[8:9])         # one token: scope = logical slots (1, 2) = positions 1, 2
+    o, ev, mg, _, _ = t.decode_step(q[8], k[8], v[8], commit=False)
+    assert res["margins"][0] == mg and res["evicted"][0] == ev
+    # rebuild both scores from the state before the step and this step's attention row
+    K = np.stack([k[p] for p in pos0] + [k[8]])
+    logit = K @ q[8, 0] / math.sqrt(d)
+    a = np.exp(logit - logit.max()); a /= a.sum()
+    sb = [(S0[i] + a[i]) / (C0[i] + 1) for i in (1, 2)]
+    assert abs(mg - abs(sb[0] - sb[1]) / max(sb)) < 1e-12
+    assert ev == (pos0[2] if sb[0] > sb[1] else pos0[1])
+    # block level
+    T, b = 48, 4
+    qw, kp, vp = q[T - b:T], k[:T], v[:T]
+    u = oracle.OracleStream(16, G, d, n_sink=0, n_recent=4)
+    r = u.prefill_prompt(qw, kp, vp, b)
+    beta = r["block_scores"]
+    first = int(np.flatnonzero(r["evicted_blocks"] >= 0)[0])     # block capacity 4: first eviction when block 4 arrives
+    assert first == 4
+    want = abs(beta[0] - beta[1]) / max(beta[0], beta[1])        # tree region = 3 blocks, scope (0, 1)
+    assert abs(r["margins"][first] - want) < 1e-12
+    assert r["evicted_blocks"][first] == (1 if beta[0] > beta[1] else 0)
