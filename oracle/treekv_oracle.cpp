@@ -204,6 +204,9 @@ void* tko_new(int budget, int n_sink, int n_recent, int G, int d, double scale, 
 
 void tko_free(void* h) { delete static_cast<Stream*>(h); }
 
+// An independent copy of a stream's whole state (for callers that may want to take a call back).
+void* tko_clone(void* h) { return new Stream(*static_cast<Stream*>(h)); }
+
 void tko_set_rope_base(void* h, double base) { static_cast<Stream*>(h)->rope_base = base; }
 
 int tko_len(void* h) { return (int)static_cast<Stream*>(h)->pos.size(); }

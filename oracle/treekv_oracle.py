@@ -47,6 +47,8 @@ def _load():
         lib.tko_new.restype = C.c_void_p
         lib.tko_new.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_int]
         lib.tko_free.argtypes = [C.c_void_p]
+        lib.tko_clone.restype = C.c_void_p
+        lib.tko_clone.argtypes = [C.c_void_p]
         lib.tko_len.argtypes = [C.c_void_p]
         lib.tko_len.restype = C.c_int
         lib.tko_t.argtypes = [C.c_void_p]
@@ -103,6 +105,13 @@ class OracleStream:
     def __len__(self):
         return self._lib.tko_len(self._h)
 
+    def clone(self) -> "OracleStream":
+        """An independent copy of the whole state."""
+        other = object.__new__(OracleStream)
+        other.__dict__.update({k: v for k, v in self.__dict__.items() if k != "_h"})
+        other._h = self._lib.tko_clone(self._h)
+        return other
+
     @property
     def t(self) -> int:
         return self._lib.tko_t(self._h)
@@ -143,6 +152,24 @@ class OracleStream:
         self._lib.tko_decode_step(self._h, _dptr(q), _dptr(k), _dptr(v), _dptr(out), int(forced_pos),
                                   float(follow_thresh), int(commit), _lptr(res), C.byref(margin))
         return out, int(res[0]), float(margin.value), int(res[1]), int(res[2])
+
+    def decode_stream(self, q, k, v, *, forced=None, follow_thresh: float = 0.0, keep_outputs: bool = True):
+        """T decode steps in a row from the current state: q [T, G, d], k/v [T, d]; forced: optional [T] evicted
+        positions of another implementation.  Returns dict(out [T, G, d] or None, evicted [T], margins [T],
+        adopted, disagreed)."""
+        T = q.shape[0]
+        q = np.ascontiguousarray(q, np.float64).reshape(T, self.G, self.d)
+        k = np.ascontiguousarray(k, np.float64).reshape(T, self.d)
+        v = np.ascontiguousarray(v, np.float64).reshape(T, self.d)
+        out = np.empty((T, self.G, self.d), np.float64) if keep_outputs else None
+        ev = np.empty(T, np.int64)
+        mg = np.empty(T, np.float64)
+        counts = np.zeros(2, np.int64)
+        fp = None if forced is None else np.ascontiguousarray(forced, np.int64).reshape(T)
+        self._lib.tko_decode_stream(self._h, _dptr(q), _dptr(k), _dptr(v), T, _dptr(out) if keep_outputs else None,
+                                    _lptr(fp) if fp is not None else None, float(follow_thresh), _lptr(ev),
+                                    _dptr(mg), _lptr(counts))
+        return dict(out=out, evicted=ev, margins=mg, adopted=int(counts[0]), disagreed=int(counts[1]))
 
     def prefill_chunk(self, Q, K, V, *, forced_pos=None, follow_thresh: float = 0.0):
         """Q [L, G, d], K [L, d], V [L, d] -> dict(out, evicted, margins, adopted, disagreed)."""
@@ -201,22 +228,12 @@ def run_decode_stream(cfg: dict, q, k, v, *, forced=None, follow_thresh: float =
     forced: optional [T] evicted positions of another implementation.
     Returns dict(out [T, G, d] or None, evicted [T], margins [T], adopted, disagreed, stream).
     """
-    T = q.shape[0]
     s = OracleStream(cfg["budget"], cfg["G"], cfg["d"], n_sink=cfg.get("n_sink", 0),
                      n_recent=cfg.get("n_recent", 0), scale=cfg.get("scale"), flags=cfg.get("flags", 0),
                      rope_base=cfg.get("rope_base", 10000.0))
-    q = np.ascontiguousarray(q, np.float64).reshape(T, s.G, s.d)
-    k = np.ascontiguousarray(k, np.float64).reshape(T, s.d)
-    v = np.ascontiguousarray(v, np.float64).reshape(T, s.d)
-    out = np.empty((T, s.G, s.d), np.float64) if keep_outputs else None
-    ev = np.empty(T, np.int64)
-    mg = np.empty(T, np.float64)
-    counts = np.zeros(2, np.int64)
-    fp = None if forced is None else np.ascontiguousarray(forced, np.int64).reshape(T)
-    s._lib.tko_decode_stream(s._h, _dptr(q), _dptr(k), _dptr(v), T, _dptr(out) if keep_outputs else None,
-                             _lptr(fp) if fp is not None else None, float(follow_thresh), _lptr(ev),
-                             _dptr(mg), _lptr(counts))
-    return dict(out=out, evicted=ev, margins=mg, adopted=int(counts[0]), disagreed=int(counts[1]), stream=s)
+    res = s.decode_stream(q, k, v, forced=forced, follow_thresh=follow_thresh, keep_outputs=keep_outputs)
+    res["stream"] = s
+    return res
 
 
 def wavelet_components(a, V, levels: int, *, want_coeffs: bool = False):

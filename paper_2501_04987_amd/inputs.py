@@ -18,7 +18,7 @@ import numpy as np
 
 __all__ = [
     "bf16_bits", "bf16_to_f32", "round_to_storage", "unit_rng",
-    "stream_iid", "stream_lowrank", "batch_streams", "device_lowrank",
+    "stream_iid", "stream_lowrank", "batch_streams", "device_lowrank", "redrawn_queries",
 ]
 
 
@@ -73,6 +73,35 @@ def stream_iid(seed: int, T: int, G: int, d: int, *, layer: int = 0, batch: int 
     return round_to_storage(q, dtype), round_to_storage(k, dtype), round_to_storage(v, dtype)
 
 
+def _lowrank_basis(layer: int, kv_head: int, d: int, rank: int):
+    basis = unit_rng(0x5EED, layer, 0, kv_head, sub=1)  # the basis depends on (layer, kv_head) only
+    U = basis.standard_normal((d, rank), dtype=np.float32) / np.float32(np.sqrt(d))
+    Uv = basis.standard_normal((d, rank), dtype=np.float32) / np.float32(np.sqrt(d))
+    return U, Uv
+
+
+def redrawn_queries(kind: str, seed: int, t: int, n: int, attempt: int, G: int, d: int, *, layer: int = 0,
+                    batch: int = 0, kv_head: int = 0, rank: int = 8, beta: float = 4.0, dtype: str = "bf16"):
+    """Fresh queries for tokens t .. t+n-1 of one stream: the same distribution as `stream_iid` / `stream_lowrank`
+    draw q from, from a generator keyed by (stream, t, attempt) with attempt >= 1.  Returns [n, G, d] float32.
+
+    A parity run may not want decisions whose score margin is below what two precisions can resolve; whoever
+    builds its inputs (with whatever reference it has) replaces the queries of such a step or chunk by these.
+    """
+    assert attempt >= 1
+    key = np.array([(np.uint64(seed) ^ np.uint64(0x7E57ED0000000000)) + np.uint64(attempt),
+                    (np.uint64(layer) << np.uint64(48)) | (np.uint64(batch) << np.uint64(32))
+                    | (np.uint64(kv_head) << np.uint64(16)) | np.uint64(2)], dtype=np.uint64)
+    rng = np.random.Generator(np.random.Philox(key=key, counter=np.array([0, 0, 0, t], dtype=np.uint64)))
+    q = rng.standard_normal((n, G, d), dtype=np.float32)
+    if kind == "lowrank":
+        U, _ = _lowrank_basis(layer, kv_head, d, rank)
+        q = q + np.float32(beta) * (rng.standard_normal((n, G, rank), dtype=np.float32) @ U.T)
+    elif kind != "iid":
+        raise ValueError(kind)
+    return round_to_storage(q, dtype)
+
+
 def stream_lowrank(seed: int, T: int, G: int, d: int, *, layer: int = 0, batch: int = 0,
                    kv_head: int = 0, rank: int = 8, beta: float = 4.0, dtype: str = "bf16"):
     """N(0,1) plus a per-head rank-`rank` component of strength `beta`.
@@ -83,9 +112,7 @@ def stream_lowrank(seed: int, T: int, G: int, d: int, *, layer: int = 0, batch: 
     elements.  The shared basis makes q.k have a heavy-tailed component, so a
     handful of slots carry most of the softmax mass.
     """
-    basis = unit_rng(0x5EED, layer, 0, kv_head, sub=1)  # the basis depends on (layer, kv_head) only
-    U = basis.standard_normal((d, rank), dtype=np.float32) / np.float32(np.sqrt(d))
-    Uv = basis.standard_normal((d, rank), dtype=np.float32) / np.float32(np.sqrt(d))
+    U, Uv = _lowrank_basis(layer, kv_head, d, rank)
     rng = unit_rng(seed, layer, batch, kv_head)
     q = rng.standard_normal((T, G, d), dtype=np.float32)
     k = rng.standard_normal((T, d), dtype=np.float32)
@@ -126,13 +153,16 @@ def batch_streams(kind: str, seed: int, T: int, B: int, Hkv: int, G: int, d: int
 # device generator for workloads too large to pre-generate on the host
 # --------------------------------------------------------------------------- #
 def device_lowrank(seed: int, T: int, B: int, Hkv: int, G: int, d: int, *, device="cuda",
-                   rank: int = 8, beta: float = 4.0, dtype: str = "bf16"):
+                   rank: int = 8, beta: float = 4.0, dtype: str = "bf16", slab: int | None = None):
     """Same recipe as `stream_lowrank`, drawn on the device with torch's generator.
 
     Returns torch tensors Q [T, B, Hkv*G, d], K [T, B, Hkv, d], V [T, B, Hkv, d]
     in the storage dtype.  The random stream differs from the numpy one; tests
     that audit such a run copy the audited streams' inputs back from the device,
-    so the device buffers are the single source of truth.
+    so the device buffers are the single source of truth.  With `slab` the tokens
+    are drawn `slab` at a time into preallocated tensors (the float32 intermediates
+    of a long stream would otherwise be several times the result's size); the
+    values then depend on `slab` too.
     """
     import torch
 
@@ -145,8 +175,20 @@ def device_lowrank(seed: int, T: int, B: int, Hkv: int, G: int, d: int, *, devic
 
     U = randn(Hkv, d, rank) / (d ** 0.5)
     Uv = randn(Hkv, d, rank) / (d ** 0.5)
-    q = randn(T, B, Hkv, G, d) + beta * torch.einsum("tbhgr,hdr->tbhgd", randn(T, B, Hkv, G, rank), U)
-    k = randn(T, B, Hkv, d) + beta * torch.einsum("tbhr,hdr->tbhd", randn(T, B, Hkv, rank), U)
-    v = randn(T, B, Hkv, d) + beta * torch.einsum("tbhr,hdr->tbhd", randn(T, B, Hkv, rank), Uv)
-    return (q.reshape(T, B, Hkv * G, d).to(tdt).contiguous(), k.to(tdt).contiguous(),
-            v.to(tdt).contiguous())
+
+    def draw(n):
+        q = randn(n, B, Hkv, G, d) + beta * torch.einsum("tbhgr,hdr->tbhgd", randn(n, B, Hkv, G, rank), U)
+        k = randn(n, B, Hkv, d) + beta * torch.einsum("tbhr,hdr->tbhd", randn(n, B, Hkv, rank), U)
+        v = randn(n, B, Hkv, d) + beta * torch.einsum("tbhr,hdr->tbhd", randn(n, B, Hkv, rank), Uv)
+        return q.reshape(n, B, Hkv * G, d).to(tdt), k.to(tdt), v.to(tdt)
+
+    if slab is None:
+        q, k, v = draw(T)
+        return q.contiguous(), k.contiguous(), v.contiguous()
+    Q = torch.empty(T, B, Hkv * G, d, dtype=tdt, device=device)
+    K = torch.empty(T, B, Hkv, d, dtype=tdt, device=device)
+    V = torch.empty(T, B, Hkv, d, dtype=tdt, device=device)
+    for lo in range(0, T, slab):
+        n = min(slab, T - lo)
+        Q[lo:lo + n], K[lo:lo + n], V[lo:lo + n] = draw(n)
+    return Q, K, V

@@ -327,3 +327,90 @@ def smoke_wavelet(oracle, binding):
     np.testing.assert_allclose(per_head.cpu().numpy(), want, rtol=1e-5, atol=bound)
     np.testing.assert_allclose(mean.cpu().numpy(), want.mean(0), rtol=1e-5, atol=bound)
     print(f"smoke: wavelet analysis ok, max magnitude {want.max():.3e}")
+
+
+# --------------------------------------------------------------------------- #
+# inputs without near-ties: the oracle runs first and queries behind a near-tie are drawn again
+# --------------------------------------------------------------------------- #
+def near_ties(margins, thresh=FOLLOW_THRESH) -> int:
+    """Decisions whose relative margin is below `thresh` (-1 marks a call without an eviction)."""
+    m = np.asarray(margins)
+    return int(np.count_nonzero((m >= 0) & (m < thresh)))
+
+
+def settle_schedule(oracle, ocfg, q, k, v, schedule, redraw, t_start=0, stream=None, progress=None,
+                    thresh=FOLLOW_THRESH):
+    """Run the oracle alone through `schedule` (chunk lengths, 0 = one decode step) on one stream and make every
+    decision's margin at least `thresh`: when a call meets a smaller one, the call is taken back, the queries of
+    its tokens are drawn again (`redraw(t, n, attempt) -> [n, G, d]`; written into `q` in place) and the call repeated.
+    Runs of decode steps go through the oracle's stream call, 512 steps at a time.
+
+    q [T, G, d], k/v [T, d] float arrays.  Returns dict(out [tokens, G, d], evicted [tokens], margins [tokens],
+    redraws, stream).
+    """
+    s = stream or oracle.OracleStream(ocfg["budget"], ocfg["G"], ocfg["d"], n_sink=ocfg["n_sink"], n_recent=ocfg["n_recent"],
+                                      scale=ocfg["scale"], flags=ocfg["flags"], rope_base=ocfg.get("rope_base", 10000.0))
+    n_tok = sum(max(L, 1) for L in schedule)
+    out = np.empty((n_tok, s.G, s.d), np.float64)
+    ev = np.empty(n_tok, np.int64)
+    mg = np.empty(n_tok, np.float64)
+    redraws = 0
+    t, i = t_start, 0
+    calls = list(schedule)
+    c = 0
+    while c < len(calls):
+        if calls[c] == 0:                                   # a run of decode steps
+            run = 1
+            while c + run < len(calls) and calls[c + run] == 0 and run < 512:
+                run += 1
+            keep = s.clone()
+            res = s.decode_stream(q[t:t + run], k[t:t + run], v[t:t + run])
+            low = np.flatnonzero((res["margins"] >= 0) & (res["margins"] < thresh))
+            if len(low):                                    # take the run back, redo it up to the near-tie, settle that step
+                s = keep
+                ok = int(low[0])
+                if ok:
+                    res = s.decode_stream(q[t:t + ok], k[t:t + ok], v[t:t + ok])
+                    out[i:i + ok], ev[i:i + ok], mg[i:i + ok] = res["out"], res["evicted"], res["margins"]
+                    t, i = t + ok, i + ok
+                attempt = 0
+                while True:
+                    o1, e1, m1, _, _ = s.decode_step(q[t], k[t], v[t], commit=False)
+                    if e1 < 0 or m1 >= thresh:
+                        break
+                    attempt += 1
+                    redraws += 1
+                    q[t] = redraw(t, 1, attempt)[0]
+                o1, e1, m1, _, _ = s.decode_step(q[t], k[t], v[t])
+                out[i], ev[i], mg[i] = o1, e1, m1
+                t, i, c = t + 1, i + 1, c + ok + 1
+            else:
+                out[i:i + run], ev[i:i + run], mg[i:i + run] = res["out"], res["evicted"], res["margins"]
+                t, i, c = t + run, i + run, c + run
+        else:
+            L = calls[c]
+            attempt = 0
+            while True:
+                keep = s.clone()
+                res = s.prefill_chunk(q[t:t + L], k[t:t + L], v[t:t + L])
+                if near_ties(res["margins"], thresh) == 0:
+                    break
+                s = keep
+                attempt += 1
+                redraws += 1
+                q[t:t + L] = redraw(t, L, attempt)
+            out[i:i + L], ev[i:i + L], mg[i:i + L] = res["out"], res["evicted"], res["margins"]
+            t, i, c = t + L, i + L, c + 1
+        if progress:
+            progress(t)
+    return dict(out=out, evicted=ev, margins=mg, redraws=redraws, stream=s)
+
+
+def check_against(ref, out_g, ev_g, tol, where):
+    """One stream's GPU outputs [tokens, G, d] and evicted positions [tokens] against an oracle run that met no
+    near-tie: the positions must be identical, the outputs within `tol`.  Returns the largest output error."""
+    assert near_ties(ref["margins"]) == 0
+    np.testing.assert_array_equal(ev_g, ref["evicted"], err_msg=f"{where}: evicted positions")
+    err = float(np.abs(ref["out"] - out_g).max())
+    assert err <= tol, f"{where}: attention output differs by {err} > {tol}"
+    return err

@@ -109,15 +109,6 @@ def test_prefill_argument_errors(binding):
     assert e.value.status == binding.TREEKV_EUNSUPPORTED
 
 
-def test_prefill_llama_shaped_prompt_sampled(binding, oracle):
-    """32 heads x 128, bf16, budget 2048 (4 + 1024 + 1020), prompt of 8192 tokens in chunks of 512, then
-    32 decode steps; the GPU runs all heads, the oracle audits 4 of them call by call."""
-    sched = [512] * 16 + [0] * 32
-    kv, st = _run(binding, oracle, sched, B=1, H=32, Hkv=32, d=128, budget=2048, n_sink=4, n_recent=1020,
-                  units=[(0, 0), (0, 11), (0, 22), (0, 31)], seed=0)
-    assert st["decisions"] == 4 * (8192 + 32 - 2048)
-
-
 def test_prefill_gather_kv_matches_retained(binding, oracle):
     """After chunks and decode steps the compacted cache (treekv_gather_kv) holds exactly the rows of the retained
     positions: surviving chunk rows were scattered into the right freed slots."""
