@@ -30,6 +30,7 @@ EXPORTS = [
     "treekv_scores", "treekv_state_bytes", "treekv_get_state_layout", "treekv_export_state", "treekv_import_state",
     "treekv_gather_kv", "treekv_wavelet_components", "treekv_strerror", "treekv_last_hip_error",
 ]
+PROBE_EXPORTS = ["treekv_probe_read", "treekv_probe_copy", "treekv_probe_mfma"]       # include/treekv_probe.h
 
 
 class treekv_config(C.Structure):
@@ -80,6 +81,9 @@ def load() -> C.CDLL:
     lib.treekv_export_state.argtypes = [vp, vp, C.c_size_t, vp]
     lib.treekv_import_state.argtypes = [vp, vp, C.c_size_t, i32p, vp]
     lib.treekv_wavelet_components.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp]
+    lib.treekv_probe_read.argtypes = [vp, C.c_size_t, vp, vp]
+    lib.treekv_probe_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    lib.treekv_probe_mfma.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), vp]
     lib.treekv_strerror.argtypes = [C.c_int]
     lib.treekv_strerror.restype = C.c_char_p
     lib.treekv_last_hip_error.argtypes = [vp]

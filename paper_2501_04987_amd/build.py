@@ -11,7 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtreekv.so")
-SOURCES = ["treekv_host.hip", "treekv_decode.hip", "treekv_prefill.hip", "treekv_prompt.hip", "treekv_wavelet.hip"]
+SOURCES = ["treekv_host.hip", "treekv_decode.hip", "treekv_prefill.hip", "treekv_prompt.hip", "treekv_wavelet.hip",
+           "treekv_probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -20,8 +20,8 @@ def binding():
     return b
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "treekv.h")).read()
+def _declared(header="treekv.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(treekv_[a-z_]+)\s*\(", text)))
 
@@ -33,6 +33,9 @@ def test_exports_every_declared_symbol(binding):
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in include/treekv.h but not exported"
     assert sorted(binding.EXPORTS) == names
+    probes = _declared("treekv_probe.h")
+    assert sorted(binding.PROBE_EXPORTS) == probes and all(hasattr(lib, n) for n in probes)
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["treekv.h", "treekv_probe.h"]
 
 
 def _init(binding, **kw):
@@ -211,3 +214,13 @@ def test_snapshot_sizes_and_argument_checks(binding):
     assert lib.treekv_import_state(h, buf, lay.bytes, None, None) == binding.TREEKV_ENOWS
     assert lib.treekv_get_state_layout(None, C.byref(lay)) == binding.TREEKV_EINVAL
     lib.treekv_destroy(h)
+
+
+def test_probe_argument_checks(binding):
+    lib = binding.load()
+    buf = C.c_void_p(0x100000)
+    assert lib.treekv_probe_read(buf, (1 << 20) + 16, buf, None) == binding.TREEKV_EINVAL      # not whole MiB
+    assert lib.treekv_probe_read(None, 1 << 20, buf, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_probe_copy(buf, C.c_void_p(0x100008), 1 << 20, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_probe_mfma(buf, 256, 3, 10, None, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_probe_mfma(None, 256, 1, 10, None, None) == binding.TREEKV_EINVAL
