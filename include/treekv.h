@@ -45,7 +45,9 @@ typedef enum treekv_status {
   TREEKV_EINVAL = -1,       /* null pointer, bad size, inconsistent configuration */
   TREEKV_ENOWS = -2,        /* workspace not bound, misaligned or too small        */
   TREEKV_EHIP = -3,         /* a HIP call or kernel launch failed                  */
-  TREEKV_EUNSUPPORTED = -4  /* valid request this build has no kernel for          */
+  TREEKV_EUNSUPPORTED = -4, /* valid request this build has no kernel for          */
+  TREEKV_ESCRATCH = -5      /* treekv_decode_step_static: the context needs more scratch than
+                               TREEKV_STATIC_SCRATCH_BYTES                            */
 } treekv_status;
 
 enum { TREEKV_BF16 = 0, TREEKV_F32 = 1 };      /* storage type of q, k, v and of the cache */
@@ -141,6 +143,25 @@ int treekv_reset(treekv_ctx* ctx, void* stream);
  */
 int treekv_decode_step(treekv_ctx* ctx, const void* q, const void* k, const void* v, void* out,
                        int32_t* retained, int32_t* n_retained, int32_t* evicted, void* stream);
+
+/*
+ * treekv_decode_step_static - treekv_decode_step with the same arguments, results and kernels, for callers that can
+ * neither allocate device memory nor hand the library scratch of their own for this: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The only scratch a decode step uses -- the scaled logits
+ * [U][G][c+1] float32 and the per-slice partial results [U][kv_splits][G][d+2] float32 that the two-kernel shape
+ * (kv_splits > 1) passes from its first kernel to its second -- lives in a fixed array of
+ * TREEKV_STATIC_SCRATCH_BYTES inside the library's device image instead of the bound workspace (the one-kernel
+ * shape, kv_splits = 1, uses none).  Each GPU holds one such array until the process ends; every call on a GPU,
+ * from any context, shares it: calls that may overlap on one GPU (different streams without ordering) race and
+ * must not both use this entry point.  Nothing in the array has to survive from one call to the next and nothing
+ * has to start at zero (the first kernel writes every word the second reads).  No hipMalloc, hipFree or other
+ * allocating call is made; the array's address is looked up once per device, on the first call there.
+ * Errors: as treekv_decode_step, and TREEKV_ESCRATCH (nothing enqueued) if the context's logits and partials
+ * exceed TREEKV_STATIC_SCRATCH_BYTES.
+ */
+enum { TREEKV_STATIC_SCRATCH_BYTES = 16 << 20 };
+int treekv_decode_step_static(treekv_ctx* ctx, const void* q, const void* k, const void* v, void* out,
+                              int32_t* retained, int32_t* n_retained, int32_t* evicted, void* stream);
 
 /*
  * treekv_prefill_chunk - `len` consecutive tokens at once (1 <= len <= max_chunk).

@@ -17,6 +17,7 @@ TREEKV_EINVAL = -1
 TREEKV_ENOWS = -2
 TREEKV_EHIP = -3
 TREEKV_EUNSUPPORTED = -4
+TREEKV_ESCRATCH = -5
 TREEKV_BF16 = 0
 TREEKV_F32 = 1
 TREEKV_KEEP_LEFT = 1
@@ -26,7 +27,7 @@ TREEKV_DEFAULT_LAYOUT = -1
 
 EXPORTS = [
     "treekv_init", "treekv_init_ex", "treekv_destroy", "treekv_get_config", "treekv_workspace_bytes",
-    "treekv_bind_workspace", "treekv_reset", "treekv_decode_step", "treekv_prefill_chunk", "treekv_prefill_prompt",
+    "treekv_bind_workspace", "treekv_reset", "treekv_decode_step", "treekv_decode_step_static", "treekv_prefill_chunk", "treekv_prefill_prompt",
     "treekv_scores", "treekv_state_bytes", "treekv_get_state_layout", "treekv_export_state", "treekv_import_state",
     "treekv_gather_kv", "treekv_wavelet_components", "treekv_strerror", "treekv_last_hip_error",
 ]
@@ -71,6 +72,7 @@ def load() -> C.CDLL:
     lib.treekv_bind_workspace.argtypes = [vp, vp, C.c_size_t]
     lib.treekv_reset.argtypes = [vp, vp]
     lib.treekv_decode_step.argtypes = [vp, vp, vp, vp, vp, i32p, i32p, i32p, vp]
+    lib.treekv_decode_step_static.argtypes = [vp, vp, vp, vp, vp, i32p, i32p, i32p, vp]
     lib.treekv_prefill_chunk.argtypes = [vp, vp, vp, vp, C.c_int, vp, i32p, i32p, i32p, vp]
     lib.treekv_prefill_prompt.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, i32p, i32p, i32p, vp, vp]
     lib.treekv_scores.argtypes = [vp, vp, vp]
@@ -204,6 +206,11 @@ class TreeKV:
         self._check(self._lib.treekv_decode_step(self._h, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(retained),
                                                  _ptr(n_retained), _ptr(evicted), self._stream()),
                     "treekv_decode_step")
+
+    def decode_step_static(self, q, k, v, out, retained, n_retained=None, evicted=None):
+        self._check(self._lib.treekv_decode_step_static(self._h, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(retained),
+                                                        _ptr(n_retained), _ptr(evicted), self._stream()),
+                    "treekv_decode_step_static")
 
     def prefill_chunk(self, Q, K, V, length, out, retained, n_retained=None, evicted=None):
         self._check(self._lib.treekv_prefill_chunk(self._h, _ptr(Q), _ptr(K), _ptr(V), int(length), _ptr(out),

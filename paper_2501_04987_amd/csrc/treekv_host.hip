@@ -5,9 +5,15 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "treekv_internal.h"
+
+// Scratch of treekv_decode_step_static: the split shape's logits and partial results, in the library's own image
+// instead of the caller's workspace.  Every GPU the library runs on holds its own copy, at its own address, until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[TREEKV_STATIC_SCRATCH_BYTES];
 
 struct treekv_ctx {
   treekv_config cfg;
@@ -347,6 +353,25 @@ int record_hip(treekv_ctx* ctx, int rc) {
   return rc;
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int MAX_DEVICES = 64;
+void* scratch_ptr[MAX_DEVICES];
+std::mutex scratch_mutex;
+
+int static_scratch(void** out) {
+  int dev = -1;
+  if (tkv::hip_failed(hipGetDevice(&dev))) return TREEKV_EHIP;
+  if (dev < 0 || dev >= MAX_DEVICES) return TREEKV_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (tkv::hip_failed(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) || !ptr) return TREEKV_EHIP;
+    scratch_ptr[dev] = ptr;
+  }
+  *out = scratch_ptr[dev];
+  return TREEKV_OK;
+}
+
 int pick_splits(const treekv_config& c) {
   // With about 200 units or more, one 512-thread workgroup per unit fills the 256 compute units and
   // keeps the whole step in one kernel.  Below that, split every unit's slots over a few 512-thread
@@ -466,6 +491,29 @@ int treekv_decode_step(treekv_ctx* ctx, const void* q, const void* k, const void
                                             (hipStream_t)stream));
 }
 
+int treekv_decode_step_static(treekv_ctx* ctx, const void* q, const void* k, const void* v, void* out,
+                              int32_t* retained, int32_t* n_retained, int32_t* evicted, void* stream) {
+  if (!ctx || !q || !k || !v || !out || !retained) return TREEKV_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return TREEKV_EINVAL;
+  if (!ctx->bound) return TREEKV_ENOWS;
+  tkv::Params p = ctx->p;
+  size_t lg = 0;
+  if (p.nsplit > 1) {                       // the one-kernel shape keeps its logits in LDS and needs no scratch
+    lg = tkv::align_up((size_t)p.U * p.G * p.cap * sizeof(float));
+    const size_t pt = tkv::align_up((size_t)p.U * p.nsplit * p.G * (size_t)(p.D + 2) * sizeof(float));
+    if (lg + pt > (size_t)TREEKV_STATIC_SCRATCH_BYTES) return TREEKV_ESCRATCH;
+  }
+  fresh();
+  if (p.nsplit > 1) {
+    void* base = nullptr;
+    const int rc = static_scratch(&base);
+    if (rc != TREEKV_OK) return record_hip(ctx, rc);
+    p.logits = static_cast<float*>(base);
+    p.partial = reinterpret_cast<float*>(static_cast<char*>(base) + lg);
+  }
+  return record_hip(ctx, tkv::launch_decode(p, q, k, v, (float*)out, retained, n_retained, evicted, (hipStream_t)stream));
+}
+
 int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const void* V, int len, void* out,
                          int32_t* retained, int32_t* n_retained, int32_t* evicted, void* stream) {
   if (!ctx || !Q || !K || !V || !out || !retained) return TREEKV_EINVAL;
@@ -555,6 +603,7 @@ const char* treekv_strerror(int status) {
     case TREEKV_ENOWS: return "workspace not bound, misaligned or too small";
     case TREEKV_EHIP: return "HIP call failed";
     case TREEKV_EUNSUPPORTED: return "configuration not supported by this build";
+    case TREEKV_ESCRATCH: return "needs more scratch than the library's fixed array holds";
     default: return "unknown status";
   }
 }
