@@ -422,6 +422,8 @@ def main():
     ap.add_argument("--rerank", action="store_true",
                     help="decode (and compress the prompt) with positions re-assigned to cache ranks; a side measurement")
     ap.add_argument("--peaks", action="store_true", help="run only the probe kernels and print their rates")
+    ap.add_argument("--only", choices=["prefill", "prompt", "wavelet"],
+                    help="run only that object of the default line (for profiling one call's kernels)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (every TreeKV stream is independent; there is no "
@@ -437,6 +439,14 @@ def main():
     binding.load()
     if args.peaks:
         print(json.dumps({"measured_peaks": measure_peaks(torch, binding, dev)}))
+        return
+
+    if args.only:
+        flags = binding.TREEKV_POSITION_RERANK if args.rerank else 0
+        obj = (bench_prefill(torch, binding, inputs, dev, None) if args.only == "prefill" else
+               bench_prompt(torch, binding, inputs, dev, None, flags=flags) if args.only == "prompt" else
+               bench_wavelet(torch, binding, dev, None))
+        print(json.dumps({args.only: obj}))
         return
 
     wl = WORKLOADS[args.workload]

@@ -5,7 +5,7 @@
 // scores are then frozen and Algorithm 1's append / compare / evict / advance (lines 4-5, 9-17)
 // is replayed for the L tokens.  L = 1 gives the decode step.
 //
-// Three launches per chunk:
+// Two launches per chunk:
 //   attend   grid row tiles x G x U (ids remapped so that a unit's row tiles share an XCD's L2).  Two passes
 //            over all visible columns with MFMA (16x16x32 bf16): the first finds the row statistics, the
 //            second forms the final probabilities, O^T += V^T P^T with P split into two bf16 halves
@@ -17,9 +17,8 @@
 //            accumulators, then Algorithm 1's eviction for the chunk's tokens with frozen scores.  Inside one
 //            sweep of idx over the tree region the scopes are disjoint pairs, so a sweep is one
 //            parallel pass; sweeps run one after the other.  Then surviving chunk tokens are
-//            matched with freed slots (prefix sums), the order arrays are rewritten and the
-//            retained positions emitted.
-//   scatter  grid (L/16, U), 16 lanes per token.  Copies the surviving chunk rows into their slots.
+//            matched with freed slots (ballot ranks), the order arrays are rewritten, the retained
+//            positions emitted and the surviving chunk rows copied into their slots.
 //
 // Token ids during the replay: a slot number (< cap) for a cached token, cap + i for chunk
 // token i that has no slot yet.
@@ -625,40 +624,50 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
 }
 
 // ---------------------------------------------------------------------------------------------
-// replay
+// replay (and the copy of the surviving chunk rows into their slots)
 // ---------------------------------------------------------------------------------------------
-constexpr int RP_THREADS = 512;
+constexpr int RP_THREADS = 1024;
+constexpr int RP_WAVES = RP_THREADS / 64;
 
-// Inclusive prefix sum of one int per thread over the workgroup (RP_THREADS threads).
-__device__ inline int block_scan_inclusive(int v, int* sm_wave) {
+// Rank of this thread's flag among the set flags of the threads before it, and the number of set flags in the
+// workgroup: one ballot per wave, the waves' counts through LDS.
+__device__ inline int block_rank(bool flag, int* sm_wave, int& total) {
+  const unsigned long long b = __ballot(flag);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int within = __popcll(b & ((1ull << lane) - 1ull));
+  if (lane == 0) sm_wave[wave] = __popcll(b);
+  __syncthreads();
+  int before = 0, tot = 0;
 #pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int o = __shfl_up(v, off, 64);
-    if (lane >= off) v += o;
+  for (int w = 0; w < RP_WAVES; ++w) {
+    const int c = sm_wave[w];
+    before += w < wave ? c : 0;
+    tot += c;
   }
-  __syncthreads();
-  if (lane == 63) sm_wave[wave] = v;
-  __syncthreads();
-  int add = 0;
-  for (int w = 0; w < wave; ++w) add += sm_wave[w];
-  return v + add;
+  __syncthreads();                 // sm_wave is free again
+  total = tot;
+  return before + within;
 }
 
-// Words of LDS the replay needs to keep a unit's order arrays, scores and flags on chip.
+// Words of LDS the replay needs to keep a unit's order arrays, scores, the chunk's scores, flags and lists on chip.
 __host__ __device__ inline size_t replay_lds_words(int m, int cap, int r, int L) {
-  return (size_t)4 * m + cap + L + (cap + L) + (L + 2) + (r > 0 ? r : 1);
+  return (size_t)4 * m + cap + 4 * (size_t)L + 4 + (r > 0 ? r : 1);
 }
 
-// IN_LDS: the unit's E, PE, R, S, the chunk's S, the flags and the free list are copied into LDS up
-// front, the replay runs on those copies (generic pointers, so the code below is the same either way) and
-// the live parts are written back at the end.  Without it (budgets too large for LDS) it runs in place.
+// One workgroup per unit.  IN_LDS: the unit's E, PE, R, S and the chunk's scores, flags and lists live in LDS (generic
+// pointers, so the code below is the same either way) and the live parts are written back at the end.  Without it
+// (budgets too large for LDS) the replay runs in place, with its lists in the workspace's prefill scratch.
+//
+// Tokens that lose a scope: a cached token frees its slot, a chunk token that has no slot yet just disappears.  The
+// k-th slot freed (in the order of the eviction steps, the slot that was free before the chunk first) goes to the
+// k-th surviving chunk token without a slot (in chunk order); the one slot left over is the next call's free slot.
 template <bool IN_LDS>
-__global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, int L, int32_t* __restrict__ retained,
+__global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, int L, const uint4* __restrict__ Kc,
+                                                                    const uint4* __restrict__ Vc, int row_vec,
+                                                                    int32_t* __restrict__ retained,
                                                                     int32_t* __restrict__ n_retained,
                                                                     int32_t* __restrict__ evicted) {
-  __shared__ int sm_wave[RP_THREADS / 64];
-  __shared__ int sm_carry;
+  __shared__ int sm_wave[RP_WAVES];
   extern __shared__ __attribute__((aligned(16))) int rp_smem[];
   const int unit = blockIdx.x, tid = threadIdx.x;
   int* meta = p.meta + (size_t)unit * META_STRIDE;
@@ -666,93 +675,96 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
   int* Eg = p.E + (size_t)unit * 2 * p.m;
   int* PEg = p.PE + (size_t)unit * 2 * p.m;
   int* Rg = p.R + (size_t)unit * max(p.n_recent, 1);
-  float* snew_w = p.pf_snew + (size_t)unit * p.max_chunk;    // the chunk tokens' scores (moved into LDS below)
-  int* flag_g = p.pf_flag + (size_t)unit * (p.cap + p.max_chunk);
   int32_t* evu = evicted ? evicted + (size_t)unit * L : nullptr;
+  const int cap = p.cap, c = p.budget, m = p.m, r = p.n_recent;
 
   float* Su = Sg;
   int *Eu = Eg, *PEu = PEg, *Ru = Rg;
-  int* flag = flag_g;              // [0,cap): slot freed; [cap, cap+L): chunk token dead -> later its destination slot
-  int* free_list = p.pf_list + (size_t)unit * (p.cap + p.max_chunk);
+  float* snew = p.pf_snew + (size_t)unit * p.max_chunk;                  // [L] the chunk tokens' scores
+  int* dest = p.pf_flag + (size_t)unit * (cap + p.max_chunk) + cap;     // [L] 1: the token lost a scope; later: its slot or -1
+  int* loser = p.pf_list + (size_t)unit * (cap + p.max_chunk);          // [L] slot freed at eviction step e, or -1
+  int* free_list = loser + L;                                           // [L + 1] freed slots in the order they are handed out
   if constexpr (IN_LDS) {
     int* w = rp_smem;
-    Eu = w; w += 2 * p.m;
-    PEu = w; w += 2 * p.m;
-    Su = reinterpret_cast<float*>(w); w += p.cap;
-    float* sn = reinterpret_cast<float*>(w); w += L;
-    flag = w; w += p.cap + L;
-    free_list = w; w += L + 2;
+    Eu = w; w += 2 * m;
+    PEu = w; w += 2 * m;
+    Su = reinterpret_cast<float*>(w); w += cap;
+    snew = reinterpret_cast<float*>(w); w += L;
+    dest = w; w += L;
+    loser = w; w += L;
+    free_list = w; w += L + 1;
     Ru = w;
-    snew_w = sn;
   }
 
   // Everything the kernel reads from global memory is requested here in one go (what a unit's replay costs is
   // memory round trips: its data was last touched a whole chunk ago): the bookkeeping words, the old scores and
-  // the chunk's column sums of the first PRE * 512 columns, and, for the LDS variant, the order arrays.
-  const int cap_cols = (p.cap + AT_COLS - 1) / AT_COLS * AT_COLS;
+  // the chunk's column sums of the first PRE * 1024 columns, and, for the LDS variant, the order arrays.
+  const int cap_cols = (cap + AT_COLS - 1) / AT_COLS * AT_COLS;
   const int cs_stride = cap_cols + (p.max_chunk + AT_COLS - 1) / AT_COLS * AT_COLS;
   unsigned long long* acc = p.pf_colacc + (size_t)unit * cs_stride;
-  constexpr int PRE = 8;
+  constexpr int PRE = 3;
   const int n0 = meta[META_N], f0 = meta[META_FREE], j0 = meta[META_J], rhead0 = meta[META_RHEAD], t0 = meta[META_T];
   float s_pre[PRE];
   unsigned long long a_pre[PRE], n_pre[PRE];
 #pragma unroll
   for (int u = 0; u < PRE; ++u) {
-    const int c = u * RP_THREADS + tid;
-    s_pre[u] = Sg[min(c, p.cap - 1)];
-    a_pre[u] = acc[min(c, p.cap - 1)];
-    n_pre[u] = acc[cap_cols + min(c, L - 1)];
+    const int x = u * RP_THREADS + tid;
+    s_pre[u] = Sg[min(x, cap - 1)];
+    a_pre[u] = acc[min(x, cap - 1)];
+    n_pre[u] = acc[cap_cols + min(x, L - 1)];
   }
   if constexpr (IN_LDS) {
-    for (int i0 = 0; i0 < 2 * p.m; i0 += 4 * RP_THREADS) {
+    // only the live entries: after j0 evictions of the sweep in progress the region reads E[0, j0) and E[2 j0, m + j0)
+    for (int i0 = 0; i0 < m; i0 += 4 * RP_THREADS) {
       int e[4], pe[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { const int i = min(i0 + u * RP_THREADS + tid, 2 * p.m - 1); e[u] = Eg[i]; pe[u] = PEg[i]; }
+      for (int u = 0; u < 4; ++u) { const int x = tree_index(min(i0 + u * RP_THREADS + tid, m - 1), j0); e[u] = Eg[x]; pe[u] = PEg[x]; }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { const int i = i0 + u * RP_THREADS + tid; if (i < 2 * p.m) { Eu[i] = e[u]; PEu[i] = pe[u]; } }
+      for (int u = 0; u < 4; ++u) {
+        const int k = i0 + u * RP_THREADS + tid;
+        if (k < m) { Eu[tree_index(k, j0)] = e[u]; PEu[tree_index(k, j0)] = pe[u]; }
+      }
     }
-    for (int i = tid; i < p.n_recent; i += RP_THREADS) Ru[i] = Rg[i];
+    for (int i = tid; i < r; i += RP_THREADS) Ru[i] = Rg[i];
   }
 
   // ---- Algorithm 1, line 8 for the whole chunk: add the column sums the attend kernel left in the accumulators ----
   {
     // every accumulator that is read is also cleared for the next chunk (the others only ever received zeros)
-    auto cache_col = [&](int c, float v, unsigned long long a) {
-      if (c <= n0 && c != f0) {                                      // the columns every row tile visited
+    auto cache_col = [&](int x, float v, unsigned long long a) {
+      if (x <= n0 && x != f0) {                                      // the columns every row tile visited
         v += (float)(long long)a * (1.0f / COLSUM_FIX);
-        Sg[c] = v;
-        acc[c] = 0;
+        Sg[x] = v;
+        acc[x] = 0;
       }
-      if constexpr (IN_LDS) Su[c] = v;
+      if constexpr (IN_LDS) Su[x] = v;
     };
-    auto chunk_col = [&](int c, unsigned long long a) {
-      snew_w[c] = (float)(long long)a * (1.0f / COLSUM_FIX);
-      acc[cap_cols + c] = 0;
+    auto chunk_col = [&](int x, unsigned long long a) {
+      snew[x] = (float)(long long)a * (1.0f / COLSUM_FIX);
+      acc[cap_cols + x] = 0;
     };
 #pragma unroll
     for (int u = 0; u < PRE; ++u) {
-      const int c = u * RP_THREADS + tid;
-      if (c < p.cap) cache_col(c, s_pre[u], a_pre[u]);
-      if (c < L) chunk_col(c, n_pre[u]);
+      const int x = u * RP_THREADS + tid;
+      if (x < cap) cache_col(x, s_pre[u], a_pre[u]);
+      if (x < L) chunk_col(x, n_pre[u]);
     }
-    for (int c = PRE * RP_THREADS + tid; c < p.cap; c += RP_THREADS) cache_col(c, Sg[c], acc[c]);
-    for (int c = PRE * RP_THREADS + tid; c < L; c += RP_THREADS) chunk_col(c, acc[cap_cols + c]);
-    __syncthreads();
+    for (int x = PRE * RP_THREADS + tid; x < cap; x += RP_THREADS) cache_col(x, Sg[x], acc[x]);
+    for (int x = PRE * RP_THREADS + tid; x < L; x += RP_THREADS) chunk_col(x, acc[cap_cols + x]);
   }
-  const float* snew = snew_w;
-  const int cap = p.cap, c = p.budget, m = p.m, r = p.n_recent;
   const int F = min(L, c - n0);            // tokens that still fit without eviction (they take slots n0 ..)
   const int Lev = L - F;                   // tokens that each trigger one eviction
   const int t_end = t0 + L - 1;            // every count C is t_end - position + 1 once the chunk is in
   const int tev = t0 + F;                  // position of the first evicting token
+  for (int i = tid; i < L; i += RP_THREADS) { dest[i] = 0; loser[i] = -1; }
+  __syncthreads();
 
-  // ---- phase 0: flags, scores of the tokens that got slots while filling ----
-  for (int i = tid; i < cap + L; i += RP_THREADS) flag[i] = 0;
+  // ---- tokens that got slots while filling ----
   for (int i = tid; i < F; i += RP_THREADS) {
     Su[n0 + i] = snew[i];
     if constexpr (IN_LDS) Sg[n0 + i] = snew[i];
+    if (evu) evu[i] = -1;
   }
-  for (int i = tid; i < F; i += RP_THREADS) if (evu) evu[i] = -1;
   __syncthreads();
 
   int j_final = j0, rhead_final = rhead0, f_final = n0 + F, n_final = n0 + F;
@@ -798,7 +810,11 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
         if (x < cnt) {
           const int j = j_a + x;
           Eu[j] = surv_id; PEu[j] = surv_pos;
-          flag[lose_id] = 1;               // a slot that is free now, or a chunk token that is gone
+          if (lose_id >= cap) dest[lose_id - cap] = 1;                       // a chunk token without a slot is gone
+          else {
+            loser[e_a + x] = lose_id;                                        // a slot that is free now
+            if (lose_id >= n0 && lose_id < n0 + F) dest[lose_id - n0] = 1;   // ... which a token of this chunk had taken
+          }
           if (evu) evu[F + e_a + x] = lose_pos;
         }
         __syncthreads();
@@ -818,62 +834,53 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
       }
       rhead_final = (rhead0 + Lev) % r;
     }
-    __syncthreads();
 
-    // ---- match surviving slot-less chunk tokens with free slots ----
-    if (tid == 0) flag[fstart] = 1;
-    __syncthreads();
-    // rank of every free slot among the free slots (ascending slot number)
-    int carry = 0;
-    for (int s0 = 0; s0 < cap; s0 += RP_THREADS) {
-      const int s = s0 + tid;
-      const int isf = s < cap ? flag[s] : 0;
-      const int inc = block_scan_inclusive(isf, sm_wave) + carry;
-      if (isf) free_list[inc - 1] = s;       // the free slots in ascending order
-      if (tid == RP_THREADS - 1) sm_carry = inc;
-      __syncthreads();
-      carry = sm_carry;
-      __syncthreads();
+    // ---- freed slots in the order they are handed out: the slot free before the chunk, then by eviction step ----
+    if (tid == 0) free_list[0] = fstart;
+    int n_free = 1;
+    for (int e0 = 0; e0 < Lev; e0 += RP_THREADS) {
+      const int e = e0 + tid;
+      const int slot = e < Lev ? loser[e] : -1;
+      int total;
+      const int rank = block_rank(slot >= 0, sm_wave, total);
+      if (slot >= 0) free_list[n_free + rank] = slot;
+      n_free += total;
     }
-    const int n_free = carry;
-    // rank of every surviving slot-less chunk token (ascending chunk index)
-    carry = 0;
+    __syncthreads();
+    // ---- surviving chunk tokens without a slot take them in chunk order ----
+    int n_alive = 0;
     for (int i0 = F; i0 < L; i0 += RP_THREADS) {
       const int i = i0 + tid;
-      const int alive = (i < L) ? (flag[cap + i] == 0) : 0;
-      const int inc = block_scan_inclusive(alive, sm_wave) + carry;
-      if (i < L) flag[cap + i] = alive ? free_list[inc - 1] : -1;   // now: its slot, or -1
-      if (tid == RP_THREADS - 1) sm_carry = inc;
-      __syncthreads();
-      carry = sm_carry;
-      __syncthreads();
+      const bool alive = i < L && dest[i] == 0;
+      int total;
+      const int rank = block_rank(alive, sm_wave, total);
+      if (i < L) dest[i] = alive ? free_list[n_alive + rank] : -1;
+      n_alive += total;
     }
-    const int n_alive = carry;                       // n_free == n_alive + 1: one slot stays free
-    f_final = free_list[n_alive < n_free ? n_alive : n_free - 1];
+    f_final = free_list[n_alive < n_free ? n_alive : n_free - 1];      // n_free == n_alive + 1: one slot stays free
+    __syncthreads();
 
     // ---- rewrite ids that still name chunk tokens, hand their scores to their slots ----
     for (int k = tid; k < m; k += RP_THREADS) {
       const int x = tree_index(k, j_final);
       const int id = Eu[x];
-      if (id >= cap) Eu[x] = flag[id];
+      if (id >= cap) Eu[x] = dest[id - cap];
     }
     for (int x = tid; x < r; x += RP_THREADS) {
       const int id = Ru[x];
-      if (id >= cap) Ru[x] = flag[id];
+      if (id >= cap) Ru[x] = dest[id - cap];
     }
     for (int i = F + tid; i < L; i += RP_THREADS) {
-      const int slot = flag[cap + i];
+      const int slot = dest[i];
       if (slot >= 0) Sg[slot] = snew[i];
     }
   }
-  // tokens that arrived while filling sit in slots n0 + i unless the chunk also evicted them;
-  // flag[cap + i] is now every chunk token's destination slot (or -1) for the scatter
-  for (int i = tid; i < F; i += RP_THREADS) flag[cap + i] = flag[n0 + i] ? -1 : n0 + i;
+  // tokens that arrived while filling sit in slots n0 + i unless the chunk also evicted them
+  for (int i = tid; i < F; i += RP_THREADS) dest[i] = dest[i] ? -1 : n0 + i;
   __syncthreads();
-  if constexpr (IN_LDS) {          // write back what later kernels and later calls read
-    for (int i = tid; i < L; i += RP_THREADS) flag_g[cap + i] = flag[cap + i];
+  if constexpr (IN_LDS) {          // write back what later calls read: the live entries
     if (Lev > 0) {
-      for (int i = tid; i < 2 * m; i += RP_THREADS) { Eg[i] = Eu[i]; PEg[i] = PEu[i]; }
+      for (int k = tid; k < m; k += RP_THREADS) { const int x = tree_index(k, j_final); Eg[x] = Eu[x]; PEg[x] = PEu[x]; }
       for (int i = tid; i < r; i += RP_THREADS) Rg[i] = Ru[i];
     }
   }
@@ -899,6 +906,11 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
     meta[META_RHEAD] = rhead_final;
     meta[META_T] = t0 + L;
     if (n_retained) n_retained[unit] = n_final;
+  }
+
+  if constexpr (IN_LDS) {
+    int* dest_g = p.pf_flag + (size_t)unit * (cap + p.max_chunk) + cap;
+    for (int i = tid; i < L; i += RP_THREADS) dest_g[i] = dest[i];
   }
 }
 
@@ -935,18 +947,20 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
   const int n_items = row_tiles * p.G * p.U;
   hipLaunchKernelGGL(attend, dim3((n_items + 7) / 8 * 8), dim3(AT_THREADS), lds, s, p, q, k, v, L, row_tiles, out);
   const size_t rp_lds = replay_lds_words(p.m, p.cap, p.n_recent, L) * sizeof(int);
+  const int row_vec = D * 2 / 16;
   if (rp_lds <= 140 * 1024) {
     auto replay = prefill_replay_kernel<true>;
     if (rp_lds > 48 * 1024 &&
         hip_failed(hipFuncSetAttribute((const void*)replay, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rp_lds)))
       return TREEKV_EHIP;
-    hipLaunchKernelGGL(replay, dim3(p.U), dim3(RP_THREADS), rp_lds, s, p, L, retained, n_retained, evicted);
+    hipLaunchKernelGGL(replay, dim3(p.U), dim3(RP_THREADS), rp_lds, s, p, L, (const uint4*)K, (const uint4*)V, row_vec,
+                       retained, n_retained, evicted);
   } else {
-    hipLaunchKernelGGL(prefill_replay_kernel<false>, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, retained, n_retained,
-                       evicted);
+    if (2 * (size_t)L + 1 > (size_t)p.cap + p.max_chunk) return TREEKV_EUNSUPPORTED;   // its lists live in pf_list
+    hipLaunchKernelGGL(prefill_replay_kernel<false>, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, (const uint4*)K,
+                       (const uint4*)V, row_vec, retained, n_retained, evicted);
   }
-  hipLaunchKernelGGL(prefill_scatter_kernel, dim3((L + 256 / (D / 8) - 1) / (256 / (D / 8)), p.U), dim3(256), 0, s, p, (const uint4*)K, (const uint4*)V, L,
-                     D * 2 / 16);
+  hipLaunchKernelGGL(prefill_scatter_kernel, dim3((L + 256 / row_vec - 1) / (256 / row_vec), p.U), dim3(256), 0, s, p, (const uint4*)K, (const uint4*)V, L, row_vec);
   return finish_launch();
 }
 
