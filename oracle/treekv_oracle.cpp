@@ -64,7 +64,9 @@
 //    permutes the head dimension of q and k accordingly.  In the one-shot prompt compression
 //    nothing has been evicted yet when the window scores the prompt, so the positions are the
 //    original ones (key j at j, window query i at T - W + i); the cache it leaves holds the keys
-//    unencoded, as decoding expects.  The chunked prefill is not defined for such a stream.
+//    unencoded, as decoding expects.  A prefill chunk (this build's own call, see above) is scored
+//    before any of its tokens is evicted: the n0 cached tokens are at positions 0 .. n0-1 and chunk
+//    token i at n0 + i, which for a chunk of one token is the decode step's rule.
 //
 //  * Wavelet analysis of Sections 3.2-3.3 (tko_wavelet_components, stateless): the signal is
 //    s[n] = a[n] * v[n] (one row per position, d columns); every column is decomposed along the
@@ -320,12 +322,13 @@ void tko_decode_stream(void* h, const double* q, const double* k, const double* 
 //   chunk's tokens (-1 where it evicted nothing).
 //   evicted [L], margins [L], adopted [L], disagreed [L]: per-token decision records
 //   (any may be null).
-// Returns 0, or -1 (nothing done) for a stream with position re-assignment.
+// With position re-assignment the chunk is scored before anything of it is evicted, so the positions are the
+// ranks at that moment: the n0 cached tokens are at 0 .. n0-1, chunk token i (and its query) at n0 + i.
+// Returns 0.
 int tko_prefill_chunk(void* h, const double* Q, const double* K, const double* V, int L, double* out,
                        const long long* forced_pos, double follow_thresh,
                        long long* evicted, double* margins, int* adopted, int* disagreed) {
   Stream& s = *static_cast<Stream*>(h);
-  if (s.flags & TKO_POSITION_RERANK) return -1;
   const size_t n0 = s.K.size();
   for (int i = 0; i < L; ++i) {
     s.K.emplace_back(K + (size_t)i * s.d, K + (size_t)(i + 1) * s.d);
@@ -335,15 +338,22 @@ int tko_prefill_chunk(void* h, const double* Q, const double* K, const double* V
     s.pos.push_back(s.t + i);
   }
   const size_t n = s.K.size();
+  const bool rerank = (s.flags & TKO_POSITION_RERANK) != 0;
+  std::vector<std::vector<double>> Kpos;
+  if (rerank)
+    for (size_t j = 0; j < n; ++j) Kpos.push_back(rotary(s.K[j].data(), s.d, (long long)j, s.rope_base));
+  const std::vector<std::vector<double>>& Katt = rerank ? Kpos : s.K;
   std::vector<double> logits(n), a(n), asum(n);
   for (int i = 0; i < L; ++i) {
     const size_t vis = n0 + (size_t)i + 1;  // the cache before the chunk, plus chunk tokens <= i
     for (size_t j = 0; j < vis; ++j) asum[j] = 0.0;
     for (int g = 0; g < s.G; ++g) {
-      const double* q = Q + ((size_t)i * s.G + g) * s.d;
+      std::vector<double> qv(Q + ((size_t)i * s.G + g) * s.d, Q + ((size_t)i * s.G + g + 1) * s.d);
+      if (rerank) qv = rotary(qv.data(), s.d, (long long)(n0 + (size_t)i), s.rope_base);
+      const double* q = qv.data();
       for (size_t j = 0; j < vis; ++j) {
         double acc = 0.0;
-        for (int e = 0; e < s.d; ++e) acc += q[e] * s.K[j][e];
+        for (int e = 0; e < s.d; ++e) acc += q[e] * Katt[j][e];
         logits[j] = acc * s.scale;
       }
       softmax_row(logits, vis, a);

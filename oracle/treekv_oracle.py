@@ -190,7 +190,7 @@ class OracleStream:
                                          _lptr(fp) if fp is not None else None, float(follow_thresh),
                                          _lptr(ev), _dptr(mg), _iptr(ad), _iptr(dis))
         if rc != 0:
-            raise ValueError("prefill_chunk: not defined for a stream with position re-assignment")
+            raise ValueError("prefill_chunk failed")
         return dict(out=out, evicted=ev, margins=mg, adopted=ad, disagreed=dis)
 
     def prefill_prompt(self, Qw, K, V, block: int, *, forced_blocks=None, follow_thresh: float = 0.0):

@@ -804,16 +804,13 @@ def test_rerank_closed_form_single_plane(oracle):
         s.decode_step(x[None], x, np.array([float(t), 1.0]))
 
 
-def test_rerank_off_is_untouched_and_prefill_refuses(oracle):
+def test_rerank_off_is_untouched(oracle):
     q, k, v = _rand_stream(5, 30, 1, 4)
     a = oracle.run_decode_stream(_cfg(8), q, k, v)
     b = oracle.run_decode_stream(dict(_cfg(8), rope_base=3.0), q, k, v)       # base without the flag: no effect
     np.testing.assert_array_equal(a["out"], b["out"])
     r = oracle.run_decode_stream(_cfg(8, flags=oracle.POSITION_RERANK), q, k, v)
     assert np.abs(r["out"] - a["out"]).max() > 1e-3
-    s = oracle.OracleStream(8, 1, 4, flags=oracle.POSITION_RERANK)
-    with pytest.raises(ValueError):
-        s.prefill_chunk(q[:4], k[:4], v[:4])
 
 
 def test_rerank_brute_force(oracle):
@@ -1074,3 +1071,90 @@ def test_margin_in_prefill_chunk_and_prompt_blocks(oracle):
     want = abs(beta[0] - beta[1]) / max(beta[0], beta[1])        # tree region = 3 blocks, scope (0, 1)
     assert abs(r["margins"][first] - want) < 1e-12
     assert r["evicted_blocks"][first] == (1 if beta[0] > beta[1] else 0)
+
+
+# --------------------------------------------------------------------------- #
+# Position re-assignment in the prefill chunk: ranks at the moment the chunk is scored
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("c,n_sink,n_recent,G,d", [(12, 0, 0, 1, 4), (16, 2, 5, 2, 6), (10, 1, 3, 3, 8)])
+def test_rerank_chunk_equals_rotary_attention_over_ranks(oracle, c, n_sink, n_recent, G, d):
+    """Row i of a chunk sees the n0 cached tokens at positions 0..n0-1 and chunk tokens 0..i at n0..n0+i: its output is
+    textbook rotary attention (complex arithmetic) over exactly those tokens, its probabilities are what the scores
+    grow by, and nothing depends on the tokens' original positions."""
+    sched = [5, 9, 1, 2 * c + 3, 4, 1, c]
+    T = sum(sched)
+    q, k, v = _rand_stream(c * 11 + d, T, G, d)
+    s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent, flags=oracle.POSITION_RERANK, rope_base=40.0)
+    t = 0
+    for L in sched:
+        kept = list(s.retained())
+        pos0, S0, C0 = s.state()
+        n0 = len(kept)
+        res = s.prefill_chunk(q[t:t + L], k[t:t + L], v[t:t + L])
+        add = np.zeros(n0 + L)
+        for i in range(L):
+            toks = kept + list(range(t, t + i + 1))
+            want = _rotary_attention(q[t + i], k[toks], v[toks], n0 + i, np.arange(n0 + i + 1), s.scale, base=40.0)
+            np.testing.assert_allclose(res["out"][i], want, rtol=1e-9, atol=1e-12)
+            # the probabilities behind the scores, from the same textbook formula
+            theta = 40.0 ** (-2.0 * np.arange(d // 2) / d)
+            kc = (k[toks][:, 0::2] + 1j * k[toks][:, 1::2]) * np.exp(1j * np.outer(np.arange(n0 + i + 1), theta))
+            for g in range(G):
+                qc = (q[t + i, g, 0::2] + 1j * q[t + i, g, 1::2]) * np.exp(1j * (n0 + i) * theta)
+                lg = np.real(kc.conj() @ qc) * s.scale
+                a = np.exp(lg - lg.max())
+                add[:n0 + i + 1] += a / a.sum()
+        pos1, S1, C1 = s.state()
+        before = dict(zip(list(pos0) + list(range(t, t + L)), list(S0) + [0.0] * L))
+        idx = {p: j for j, p in enumerate(kept + list(range(t, t + L)))}
+        for p, sc in zip(pos1, S1):
+            assert abs(sc - (before[p] + add[idx[p]])) < 1e-10
+        t += L
+
+
+def test_rerank_chunk_of_one_token_is_the_decode_step(oracle):
+    c, G, d, T = 9, 2, 6, 40
+    q, k, v = _rand_stream(77, T, G, d)
+    a = oracle.OracleStream(c, G, d, n_sink=1, n_recent=2, flags=oracle.POSITION_RERANK)
+    b = oracle.OracleStream(c, G, d, n_sink=1, n_recent=2, flags=oracle.POSITION_RERANK)
+    for t in range(T):
+        o, ev, mg, _, _ = a.decode_step(q[t], k[t], v[t])
+        r = b.prefill_chunk(q[t:t + 1], k[t:t + 1], v[t:t + 1])
+        assert np.array_equal(o, r["out"][0]) and ev == r["evicted"][0] and mg == r["margins"][0]
+    for x, y in zip(a.state(), b.state()):
+        assert np.array_equal(x, y)
+
+
+def test_rerank_chunk_brute_force(oracle):
+    """Chunks and decode steps mixed, against the independent re-simulation (relative form of the encoding)."""
+    for seed in range(20):
+        rng = np.random.default_rng(4100 + seed)
+        c = int(rng.integers(3, 9))
+        n_sink, n_recent = int(rng.integers(0, 2)), int(rng.integers(0, 3))
+        if c - n_sink - n_recent < 1:
+            n_recent = 0
+        G, d = int(rng.integers(1, 3)), 2 * int(rng.integers(1, 4))
+        base = float(rng.choice([10000.0, 5.0]))
+        sched = [int(x) for x in rng.integers(0, 2 * c, size=6)]
+        T = sum(max(L, 1) for L in sched)
+        q, k, v = _rand_stream(5200 + seed, T, G, d)
+        s = oracle.OracleStream(c, G, d, n_sink=n_sink, n_recent=n_recent, flags=oracle.POSITION_RERANK, rope_base=base)
+        bf = BruteTreeKV(c, G, d, n_sink=n_sink, n_recent=n_recent, rerank_base=base)
+        t = 0
+        for L in sched:
+            if L == 0:
+                out, ev, *_ = s.decode_step(q[t], k[t], v[t])
+                o_b, ev_b = bf.decode_step(q[t].tolist(), k[t].tolist(), v[t].tolist())
+                outs, evs, outs_b, evs_b = out[None], [ev], [o_b], [ev_b]
+                t += 1
+            else:
+                r = s.prefill_chunk(q[t:t + L], k[t:t + L], v[t:t + L])
+                outs_b, evs_b = bf.prefill_chunk(q[t:t + L].tolist(), k[t:t + L].tolist(), v[t:t + L].tolist())
+                outs, evs = r["out"], list(r["evicted"])
+                t += L
+            assert list(evs) == list(evs_b), (seed, t)
+            np.testing.assert_allclose(outs, np.array(outs_b), rtol=1e-9, atol=1e-12)
+        S_b, C_b = bf.scores()
+        _, S, C = s.state()
+        np.testing.assert_allclose(S, S_b, rtol=1e-10)
+        assert list(C) == C_b
