@@ -152,8 +152,8 @@ def bench_decode(torch, binding, inputs, dev, wl, steps, warmup, rerank=False):
     L, B, H, Hkv, c = wl["layers"], wl["batch"], wl["heads"], wl["kv_heads"], wl["budget"]
     G = H // Hkv
     flags = binding.TREEKV_POSITION_RERANK if rerank else 0
-    layers = [binding.TreeKV(c, H, HEAD_DIM, kv_heads=Hkv, batch=B, dtype="bf16", flags=flags,
-                             max_prompt=c if rerank else 0, max_chunk=PREFILL_CHUNK) for _ in range(L)]
+    layers = [binding.TreeKV(c, H, HEAD_DIM, kv_heads=Hkv, batch=B, dtype="bf16", flags=flags, max_chunk=PREFILL_CHUNK)
+              for _ in range(L)]
     cfg = layers[0].cfg
     assert (cfg.n_sink, cfg.n_recent) == (4, c - c // 2 - 4)
 
@@ -172,22 +172,14 @@ def bench_decode(torch, binding, inputs, dev, wl, steps, warmup, rerank=False):
         for l, kv in enumerate(layers):
             kv.decode_step(q[l], k[l], v[l], out[l], ret[l], nret[l], ev[l])
 
-    # fill the caches to the budget (untimed): prefill chunks, or (the chunked prefill has no re-assigned positions)
-    # one prompt of exactly `budget` tokens, which the one-shot compression keeps whole
-    if rerank:
-        q, k, v = gen(100, c)
+    # fill the caches to the budget (untimed) with prefill chunks
+    for i in range(c // PREFILL_CHUNK):
+        q, k, v = gen(100 + i, PREFILL_CHUNK)
+        o = torch.empty(B, PREFILL_CHUNK, H, HEAD_DIM, dtype=torch.float32, device=dev)
         for l, kv in enumerate(layers):
-            cut = lambda x: x[:, l].permute(1, 0, 2, 3).contiguous()          # [B, T, H, d]
-            kv.prefill_prompt(cut(q[c - PROMPT_BLOCK:]), cut(k), cut(v), c, PROMPT_BLOCK, ret[l], nret[l])
-        del q, k, v
-    else:
-        for i in range(c // PREFILL_CHUNK):
-            q, k, v = gen(100 + i, PREFILL_CHUNK)
-            o = torch.empty(B, PREFILL_CHUNK, H, HEAD_DIM, dtype=torch.float32, device=dev)
-            for l, kv in enumerate(layers):
-                cut = lambda x: x[:, l].permute(1, 0, 2, 3).contiguous()
-                kv.prefill_chunk(cut(q), cut(k), cut(v), PREFILL_CHUNK, o, ret[l], nret[l], None)
-            del q, k, v, o
+            cut = lambda x: x[:, l].permute(1, 0, 2, 3).contiguous()
+            kv.prefill_chunk(cut(q), cut(k), cut(v), PREFILL_CHUNK, o, ret[l], nret[l], None)
+        del q, k, v, o
     torch.cuda.synchronize()
     assert int(nret.min()) == c, "caches are not full"
 
@@ -291,9 +283,9 @@ def prefill_flops_per_chunk(c, L=PREFILL_CHUNK, d=HEAD_DIM, heads=32):
     return 2 * 2 * L * (c + (L + 1) / 2) * d * heads
 
 
-def bench_prefill(torch, binding, inputs, dev, peaks, chunks=24, warm=6, layers=4, c=2048, H=32):
+def bench_prefill(torch, binding, inputs, dev, peaks, chunks=24, warm=6, layers=4, c=2048, H=32, flags=0):
     """Chunks of 512 tokens into full 2048-slot caches, 32 heads x 128, batch 1, cycling over a few layers."""
-    kvs = [binding.TreeKV(c, H, HEAD_DIM, max_chunk=PREFILL_CHUNK) for _ in range(layers)]
+    kvs = [binding.TreeKV(c, H, HEAD_DIM, max_chunk=PREFILL_CHUNK, flags=flags) for _ in range(layers)]
     n_in = 8
     q, k, v = inputs.device_lowrank(11, n_in * PREFILL_CHUNK, 1, H, 1, HEAD_DIM, device=dev)
     mk = lambda x: x.view(n_in, PREFILL_CHUNK, 1, H, HEAD_DIM).permute(0, 2, 1, 3, 4).contiguous()   # [n,B,L,H,d]
@@ -321,7 +313,8 @@ def bench_prefill(torch, binding, inputs, dev, peaks, chunks=24, warm=6, layers=
     assert int(ev.min()) >= 0, "every token of a chunk into a full cache evicts one"
     flops = prefill_flops_per_chunk(c, heads=H)
     tf = flops / (us * 1e-6) / 1e12
-    return {"workload": "configs[3] shape: 512-token chunk into a full 2048-slot cache, 32 heads x 128 dim, bf16, batch 1",
+    return {"workload": "configs[3] shape: 512-token chunk into a full 2048-slot cache, 32 heads x 128 dim, bf16, batch 1"
+                        + (", positions re-assigned" if flags else ""),
             "chunks": chunks, "us_per_chunk": us, "prompt_tokens_per_s": PREFILL_CHUNK / (us * 1e-6),
             "roofline": roofline("mfma", tf, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", peaks and peaks["mfma_bf16_TFLOPs"],
                                  flops_per_chunk=flops,
@@ -443,7 +436,7 @@ def main():
 
     if args.only:
         flags = binding.TREEKV_POSITION_RERANK if args.rerank else 0
-        obj = (bench_prefill(torch, binding, inputs, dev, None) if args.only == "prefill" else
+        obj = (bench_prefill(torch, binding, inputs, dev, None, flags=flags) if args.only == "prefill" else
                bench_prompt(torch, binding, inputs, dev, None, flags=flags) if args.only == "prompt" else
                bench_wavelet(torch, binding, dev, None))
         print(json.dumps({args.only: obj}))
@@ -474,7 +467,7 @@ def main():
         "config": {"workload": wl["name"] + (", positions re-assigned to cache ranks" if args.rerank else ""),
                    "layers": wl["layers"], "batch": wl["batch"], "heads": wl["heads"], "kv_heads": wl["kv_heads"],
                    "head_dim": HEAD_DIM, "budget": wl["budget"], "kv_splits": r["kv_splits"], "launch": "stream",
-                   "filled_by": "one prompt of `budget` tokens" if args.rerank else "prefill chunks of 512"},
+                   "filled_by": "prefill chunks of 512"},
         "tokens_per_s": r["steps_per_s"] * wl["batch"],
         "layer_steps_per_s": r["steps_per_s"] * wl["layers"],
         "roofline": roof,
@@ -493,6 +486,8 @@ def main():
             "graded_shape_rerank": side_shape(torch, binding, inputs, dev, "graded", peaks, rerank=True),
         }
     if args.rerank and not args.no_extras:
+        res["prefill"] = bench_prefill(torch, binding, inputs, dev, peaks, flags=binding.TREEKV_POSITION_RERANK)
+        torch.cuda.empty_cache()
         res["prompt"] = bench_prompt(torch, binding, inputs, dev, peaks, flags=binding.TREEKV_POSITION_RERANK)
     if headline and not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)

@@ -68,11 +68,13 @@ enum {
                                     keys and the query inside the step.  Rotary encoding as defined by its
                                     authors: dimensions (2i, 2i+1) form a plane turned by
                                     position * rope_base^(-2i/d); a model that pairs (i, i + d/2) permutes the
-                                    head dimension of q and k accordingly.  treekv_prefill_prompt takes its
-                                    queries and keys unencoded too: nothing has been evicted when the window
-                                    scores the prompt, so key j is at position j and window query i at
-                                    len - block + i; the cache it leaves holds the keys unencoded.
-                                    treekv_prefill_chunk returns TREEKV_EUNSUPPORTED for such a context.      */
+                                    head dimension of q and k accordingly.  treekv_prefill_chunk scores a chunk
+                                    before anything of it is evicted: the n cached tokens are at positions
+                                    0 .. n-1 and chunk token i (and its query) at n + i -- for a one-token chunk
+                                    the decode step's rule.  treekv_prefill_prompt takes its queries and keys
+                                    unencoded too: nothing has been evicted when the window scores the prompt,
+                                    so key j is at position j and window query i at len - block + i.  The cache
+                                    always holds the keys unencoded.                                          */
 };
 
 enum { TREEKV_DEFAULT_LAYOUT = -1 };           /* n_sink = n_recent = this: 4 sinks, budget/2 tree slots, the rest recent */

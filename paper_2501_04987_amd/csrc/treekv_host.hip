@@ -29,7 +29,10 @@ namespace {
 constexpr size_t ALIGN = 256;
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
-size_t rope_rows(const Params& p) { return (size_t)(p.cap > p.max_prompt ? p.cap : p.max_prompt); }
+size_t rope_rows(const Params& p) {
+  const size_t chunk = (size_t)p.cap + p.max_chunk;
+  return chunk > (size_t)p.max_prompt ? chunk : (size_t)p.max_prompt;
+}
 
 // Walks the workspace layout; with base == nullptr it only measures.
 size_t carve(Params& p, char* base) {
@@ -64,6 +67,8 @@ size_t carve(Params& p, char* base) {
   if (p.flags & TREEKV_POSITION_RERANK) {
     p.rope_tab = (float2*)take(rope_rows(p) * (size_t)(p.D / 2) * sizeof(float2));
     if (p.max_prompt > 0) p.pp_qrot = (uint16_t*)take(U * 2 * 128 * (size_t)p.D * 2);
+    p.pf_krot = (uint16_t*)take(U * 2 * ext * p.D * 2);
+    p.pf_qrot = (uint16_t*)take(2 * (size_t)p.B * p.max_chunk * p.H * p.D * 2);
   }
   return off;
 }
@@ -92,7 +97,8 @@ __global__ void reset_kernel(Params p) {
 
 // (cos, sin) of distance * base^(-2i/D) for every distance two cached tokens can have, in double precision.
 __global__ void rope_table_kernel(Params p) {
-  const size_t n = (size_t)(p.cap > p.max_prompt ? p.cap : p.max_prompt) * (p.D / 2);
+  const size_t rows = (size_t)p.cap + p.max_chunk > (size_t)p.max_prompt ? (size_t)p.cap + p.max_chunk : (size_t)p.max_prompt;
+  const size_t n = rows * (p.D / 2);
   for (size_t x = blockIdx.x * (size_t)blockDim.x + threadIdx.x; x < n; x += (size_t)gridDim.x * blockDim.x) {
     const int dist = (int)(x / (p.D / 2)), i = (int)(x % (p.D / 2));
     const double angle = (double)dist * pow((double)p.rope_base, -2.0 * (double)i / (double)p.D);
@@ -519,7 +525,6 @@ int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const vo
   if (!ctx || !Q || !K || !V || !out || !retained) return TREEKV_EINVAL;
   if (len < 1 || len > ctx->cfg.max_chunk) return TREEKV_EINVAL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(out)) return TREEKV_EINVAL;
-  if (ctx->cfg.flags & TREEKV_POSITION_RERANK) return TREEKV_EUNSUPPORTED;
   if (!ctx->bound) return TREEKV_ENOWS;
   fresh();
   return record_hip(ctx, tkv::launch_prefill(ctx->p, Q, K, V, len, (float*)out, retained, n_retained, evicted,

@@ -60,9 +60,12 @@ struct Params {
   int* pp_kept;             // [U][budget] kept blocks, ascending
   // position re-assignment (only with TREEKV_POSITION_RERANK)
   float rope_base;
-  float2* rope_tab;         // [max(cap, max_prompt)][D/2] (cos, sin) of n * rope_base^(-2i/D): n a distance between two
-                            // cached tokens (decode) or a prompt position (prompt compression)
+  float2* rope_tab;         // [max(cap + max_chunk, max_prompt)][D/2] (cos, sin) of n * rope_base^(-2i/D): n a distance between
+                            // two cached tokens (decode), a rank (prefill chunk) or a prompt position (prompt compression)
   uint16_t* pp_qrot;        // [U][hi, lo][128][D] bf16: the window's queries turned to their positions (max_prompt > 0)
+  uint16_t* pf_krot;        // [U][hi, lo][cap + max_chunk][D] bf16: a prefill chunk's keys (cache rows by slot, then the
+                            // chunk's own) turned to their ranks, split into two bf16 parts
+  uint16_t* pf_qrot;        // [hi, lo][B][max_chunk][H][D] bf16: the chunk's queries, likewise
 };
 constexpr int PROMPT_MAX_SPLITS = 64;
 

@@ -174,7 +174,14 @@ __device__ inline unsigned lds_address(const void* shared_ptr) {
 // and add the tile's 128 sums to the unit's accumulators (the atomics then have a whole iteration to
 // complete before anything waits on the memory counter).  A workgroup touches every column of every tile
 // it visits (masked entries add zero) and nothing else.
-template <int D>
+//
+// ROPE (positions re-assigned to cache ranks): queries and keys come, already turned to their ranks and split into
+// two bf16 parts each, from the scratch prefill_turn_kernel fills (pf_qrot, pf_krot; the chunk's own keys lie behind
+// the cache rows there), and a logit is k_hi.q_hi + k_lo.q_hi + k_hi.q_lo (what is left out, lo.lo, is 2^-18 of the
+// product).  The staging memory then holds one tile pair (hi, lo) where the plain kernel holds two tiles: sweep 1
+// requests one tile ahead instead of three, and sweep 2 has a second barrier per tile (the K pair is requested once
+// every wave has formed its logits from it).  Everything after the logits is unchanged.
+template <int D, bool ROPE>
 __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, const uint16_t* __restrict__ Q,
                                                                     const uint16_t* __restrict__ Kc,
                                                                     const uint16_t* __restrict__ Vc, int L,
@@ -214,19 +221,30 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const int rbase = row_tile * ROW_TILE;                   // first chunk row of the workgroup
 
   // B operands: the Q rows of the four 16-row blocks (rows past the chunk repeat its last row)
-  uint4 qa[4][KS];
+  constexpr int QL = ROPE ? KS : 1;          // the second bf16 part of the queries exists only with ROPE
+  uint4 qa[4][KS], qlo[4][QL];
+  const uint16_t* Qsrc = ROPE ? p.pf_qrot : Q;
+  const size_t q_part = (size_t)p.B * p.max_chunk * p.H * D;      // pf_qrot: [hi, lo][B][max_chunk][H][D]
+  const int q_rows = ROPE ? p.max_chunk : L;
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb) {
-    const uint16_t* qp = Q + (((size_t)b * L + min(rbase + rb * 16 + lr, L - 1)) * p.H + h) * D + q4 * 8;
+    const uint16_t* qp = Qsrc + (((size_t)b * q_rows + min(rbase + rb * 16 + lr, L - 1)) * p.H + h) * D + q4 * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qa[rb][ks] = *reinterpret_cast<const uint4*>(qp + ks * 32);
+    if constexpr (ROPE) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) qlo[rb][ks] = *reinterpret_cast<const uint4*>(qp + q_part + ks * 32);
+    }
   }
 
-  const uint16_t* Ku = (const uint16_t*)p.K + (size_t)unit * p.cap * D;
+  const size_t krot_rows = (size_t)p.cap + p.max_chunk;            // pf_krot: [U][hi, lo][cap + max_chunk][D]
+  const uint16_t* Ku = ROPE ? p.pf_krot + (size_t)unit * 2 * krot_rows * D : (const uint16_t*)p.K + (size_t)unit * p.cap * D;
   const uint16_t* Vu = (const uint16_t*)p.V + (size_t)unit * p.cap * D;
   const int chunk_row_stride = p.Hkv * D;
-  const uint16_t* Kcu = Kc + ((size_t)b * L * p.Hkv + kvh) * D;
+  const int kchunk_row_stride = ROPE ? D : chunk_row_stride;
+  const uint16_t* Kcu = ROPE ? Ku + (size_t)p.cap * D : Kc + ((size_t)b * L * p.Hkv + kvh) * D;
   const uint16_t* Vcu = Vc + ((size_t)b * L * p.Hkv + kvh) * D;
+  const size_t klo_off = krot_rows * D;                            // from a key's hi part to its lo part (ROPE)
 
   const int cache_tiles = (ci.n + 1 + AT_COLS - 1) / AT_COLS;          // slots [0, n], the free one masked
   const int last_row = min(rbase + ROW_TILE, L) - 1;                   // last chunk row of the workgroup
@@ -241,11 +259,12 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   // multiple of 16 rows, so the swizzle of a lane's row depends on x and a_lrow only.
   static_assert(CPW * RPC == 16, "a wave covers 16 rows of every tile");
   const int a_lrow = lane / PARTS, a_slot = lane % PARTS;
-  auto issue_tile = [&](const uint16_t* cache_src, const uint16_t* chunk_src, int tile, uint16_t* stage, auto swz) {
+  auto issue_tile = [&](const uint16_t* cache_src, const uint16_t* chunk_src, int chunk_stride, int tile, uint16_t* stage,
+                        auto swz) {
     const bool is_cache = tile < cache_tiles;
     const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
     const uint16_t* base = is_cache ? cache_src : chunk_src;
-    const int rstride = is_cache ? D : chunk_row_stride;
+    const int rstride = is_cache ? D : chunk_stride;
     const int lim = is_cache ? cache_lim : chunk_lim;
     const int row_w = col0 + wave * 16;                   // first source row of this wave's 16 (wave uniform)
     if (row_w + 15 <= lim && is_cache) {
@@ -300,6 +319,18 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) s[rb] = mfma16(k[ks], qa[rb][ks], s[rb]);
+      if constexpr (ROPE) {          // stage holds the keys' hi parts, stage + 1 their lo parts
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb) s[rb] = mfma16(k[ks], qlo[rb][ks], s[rb]);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) k[ks] = *reinterpret_cast<const uint4*>(kp + Lds::TILE_ELEMS + ((ks * 4 + q4) ^ k1_swz) * 8);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb) s[rb] = mfma16(k[ks], qa[rb][ks], s[rb]);
+      }
     };
     // Masked logits become -inf: their exp2 is 0 against any finite running max, and a lane that has seen
     // nothing yet keeps its (finite) initial max, so no probability needs a guard.
@@ -350,19 +381,38 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     // of every tile that it requested itself, so the waves need no barrier between tiles: each runs on its own
     // count of outstanding requests.
     f32x4_t sa[4], sb[4];
+    // ROPE: tile t sits in the stage pair (t & 1) * 2 (hi), + 1 (lo) and is requested two tiles ahead
+    auto issue_k1 = [&](int t) {
+      if constexpr (ROPE) {
+        issue_tile(Ku, Kcu, kchunk_row_stride, t, sK + ((t & 1) * 2) * Lds::TILE_ELEMS, kswz);
+        issue_tile(Ku + klo_off, Kcu + klo_off, kchunk_row_stride, t, sK + ((t & 1) * 2 + 1) * Lds::TILE_ELEMS, kswz);
+      } else {
+        issue_tile(Ku, Kcu, kchunk_row_stride, t, sK + (t & 3) * Lds::TILE_ELEMS, kswz);
+      }
+    };
+    constexpr int AHEAD = ROPE ? 2 : 3;     // how many tiles ahead of the one being finished the requests run
 #pragma unroll
-    for (int t = 0; t < 3; ++t)
-      if (t < ntiles) issue_tile(Ku, Kcu, t, sK + t * Lds::TILE_ELEMS, kswz);
+    for (int t = 0; t < AHEAD; ++t)
+      if (t < ntiles) issue_k1(t);
     wait_vmcnt<0>();
     __syncthreads();
     qk(sa, 0);
     auto step = [&](f32x4_t (&cur)[4], f32x4_t (&nxt)[4], int t) {
-      const bool more = t + 3 < ntiles;
-      if (more) issue_tile(Ku, Kcu, t + 3, sK + ((t + 3) & 3) * Lds::TILE_ELEMS, kswz);
-      if (t + 1 < ntiles) qk(nxt, (t + 1) & 3);
-      stats(cur, t);
-      // tile t+2 must have landed before the next iteration reads it; only this iteration's requests may stay out
-      if (more) wait_vmcnt<CPW>(); else wait_vmcnt<0>();
+      const bool more = t + AHEAD < ntiles;
+      if constexpr (ROPE) {
+        // the pair of tile t+2 goes where tile t was (its logits were formed in iteration t-1) and is read in the
+        // next iteration: everything must have landed by then
+        if (more) issue_k1(t + 2);
+        if (t + 1 < ntiles) qk(nxt, ((t + 1) & 1) * 2);
+        stats(cur, t);
+        wait_vmcnt<0>();
+      } else {
+        if (more) issue_k1(t + 3);
+        if (t + 1 < ntiles) qk(nxt, (t + 1) & 3);
+        stats(cur, t);
+        // tile t+2 must have landed before the next iteration reads it; only this iteration's requests may stay out
+        if (more) wait_vmcnt<CPW>(); else wait_vmcnt<0>();
+      }
     };
     for (int t = 0; t < ntiles; t += 2) {
       step(sa, sb, t);
@@ -406,12 +456,20 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   // ------------------------------------------------------------------------------------------
   const int row0 = rbase + rg * 32;                        // first chunk row of this wave
   const int my_row0 = row0 + lr, my_row1 = row0 + 16 + lr; // the query rows this lane's results belong to
-  uint4 qa0[KS], qa1[KS];
+  uint4 qa0[KS], qa1[KS], ql0[QL], ql1[QL];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     const uint4 a0 = qa[0][ks], a1 = qa[1][ks], a2 = qa[2][ks], a3 = qa[3][ks];   // values, not addresses, into the select
     qa0[ks] = rg ? a2 : a0;
     qa1[ks] = rg ? a3 : a1;
+  }
+  if constexpr (ROPE) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const uint4 a0 = qlo[0][ks], a1 = qlo[1][ks], a2 = qlo[2][ks], a3 = qlo[3][ks];
+      ql0[ks] = rg ? a2 : a0;
+      ql1[ks] = rg ? a3 : a1;
+    }
   }
 
   // operand read offsets inside one stage (bf16 elements), tile independent
@@ -463,6 +521,24 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
         s0[bk] = mfma16(ka[bk][ks], qa0[ks], s0[bk]);
         s1[bk] = mfma16(ka[bk][ks], qa1[ks], s1[bk]);
       }
+    if constexpr (ROPE) {            // `stage` holds the keys' hi parts, the stage after it their lo parts
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int bk = 0; bk < 2; ++bk) {
+          s0[bk] = mfma16(ka[bk][ks], ql0[ks], s0[bk]);
+          s1[bk] = mfma16(ka[bk][ks], ql1[ks], s1[bk]);
+        }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int bk = 0; bk < 2; ++bk) {
+          const uint4 kl = *reinterpret_cast<const uint4*>(kp + Lds::TILE_ELEMS + bk * 16 * D +
+                                                           ((ks * 4 + q4) ^ (bk ? k2_swz1 : k2_swz0)) * 8);
+          s0[bk] = mfma16(kl, qa0[ks], s0[bk]);
+          s1[bk] = mfma16(kl, qa1[ks], s1[bk]);
+        }
+    }
   };
   // bf16 pairs (-1, 0) and (0, -1).  Kept opaque in scalar registers: as immediates, the second has the bit
   // pattern of the fp32 inline constant -1.0, which a packed 16-bit operand does not read as these two halves.
@@ -537,14 +613,15 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     }
   };
 
+  f32x4_t sa0[2], sa1[2], sb0[2], sb1[2];
+  if constexpr (!ROPE) {
   // Iteration t: request K of tile t+2 and V of tile t+1, form the logits of tile t+1, finish tile t.
   // K stage t&1 held tile t, whose logits were formed in iteration t-1; V stage (t+1)&1 held tile t-1.
-  issue_tile(Ku, Kcu, 0, sK, kswz);
-  issue_tile(Vu, Vcu, 0, sV, vswz);
-  if (ntiles > 1) issue_tile(Ku, Kcu, 1, sK + Lds::TILE_ELEMS, kswz);
+  issue_tile(Ku, Kcu, kchunk_row_stride, 0, sK, kswz);
+  issue_tile(Vu, Vcu, chunk_row_stride, 0, sV, vswz);
+  if (ntiles > 1) issue_tile(Ku, Kcu, kchunk_row_stride, 1, sK + Lds::TILE_ELEMS, kswz);
   wait_vmcnt<0>();
   __syncthreads();
-  f32x4_t sa0[2], sa1[2], sb0[2], sb1[2];
   qk2(sa0, sa1, 0);
   __syncthreads();                     // K stage 0 is requested again right below
   auto step2 = [&](f32x4_t (&c0)[2], f32x4_t (&c1)[2], f32x4_t (&n0)[2], f32x4_t (&n1)[2], int t, auto matrix_first) {
@@ -553,8 +630,8 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     const bool more_k = t + 2 < ntiles, more_v = t + 1 < ntiles;
     uint16_t* k_stage = sK + (t & 1) * Lds::TILE_ELEMS;
     uint16_t* v_stage = sV + ((t + 1) & 1) * Lds::TILE_ELEMS;
-    if (more_k) issue_tile(Ku, Kcu, t + 2, k_stage, kswz);
-    if (more_v) issue_tile(Vu, Vcu, t + 1, v_stage, vswz);
+    if (more_k) issue_tile(Ku, Kcu, kchunk_row_stride, t + 2, k_stage, kswz);
+    if (more_v) issue_tile(Vu, Vcu, chunk_row_stride, t + 1, v_stage, vswz);
     // The two waves that share a SIMD take the four pieces in different orders, so that one is on the matrix pipe
     // while the other is on the vector ALU instead of both wanting the same unit at the same time:
     //   waves 0-3: logits(t+1)  probabilities(t)  PV(t)  column sums(t)
@@ -589,6 +666,42 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       if (t + 1 < ntiles) step2(sb0, sb1, sa0, sa1, t + 1, BoolTag<false>{});
     }
   }
+  } else {
+  // ROPE: one K pair (hi in K stage 0, lo in K stage 1) and two V stages.  Iteration t: with the pair of tile t+1
+  // landed, form its logits; once every wave has done so, request the pair of tile t+2 into the same two stages and
+  // finish tile t while it is on its way.  V of tile t+1 goes into V stage (t+1)&1, which held tile t-1.
+  auto issue_k2 = [&](int t) {
+    issue_tile(Ku, Kcu, kchunk_row_stride, t, sK, kswz);
+    issue_tile(Ku + klo_off, Kcu + klo_off, kchunk_row_stride, t, sK + Lds::TILE_ELEMS, kswz);
+  };
+  issue_k2(0);
+  issue_tile(Vu, Vcu, chunk_row_stride, 0, sV, vswz);
+  wait_vmcnt<0>();
+  __syncthreads();
+  qk2(sa0, sa1, 0);
+  __syncthreads();                     // the pair is requested again right below
+  if (ntiles > 1) issue_k2(1);
+  auto step2 = [&](f32x4_t (&c0)[2], f32x4_t (&c1)[2], f32x4_t (&n0)[2], f32x4_t (&n1)[2], int t) {
+    wait_vmcnt<0>();                   // the pair of tile t+1 and V of tile t
+    __syncthreads();                   // ... for every wave; and every wave is done with V of tile t-1 and tile t-1's sums
+    if (t + 1 < ntiles) issue_tile(Vu, Vcu, chunk_row_stride, t + 1, sV + ((t + 1) & 1) * Lds::TILE_ELEMS, vswz);
+    if (t > 0 && cq == ((t - 1) & 3)) drain(t - 1);
+    if (t + 1 < ntiles) qk2(n0, n1, 0);
+    __syncthreads();                   // every wave has read the pair
+    if (t + 2 < ntiles) issue_k2(t + 2);
+    uint4 phi0, plo0, phi1, plo1;
+    mask_tile(c0, c1, t);
+    soft(c0, neg_ml0, phi0, plo0);
+    soft(c1, neg_ml1, phi1, plo1);
+    pv(t, phi0, plo0, phi1, plo1);
+    colsums(c0, c1, t);
+  };
+  for (int t = 0; t < ntiles; t += 2) {
+    step2(sa0, sa1, sb0, sb1, t);
+    if (t + 1 < ntiles) step2(sb0, sb1, sa0, sa1, t + 1);
+  }
+  __syncthreads();                     // the last tile's sums are in LDS
+  }
   if (cq == ((ntiles - 1) & 3)) drain(ntiles - 1);     // the last tile's sums (its barrier has passed)
 
   // ---- add the four column quarters of every row group through LDS ----
@@ -621,6 +734,71 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   };
   finish(my_row0, o0);
   finish(my_row1, o1);
+}
+
+// ---------------------------------------------------------------------------------------------
+// positions re-assigned to cache ranks: the chunk's queries and every key it attends, turned and split
+// ---------------------------------------------------------------------------------------------
+// A chunk is scored before anything of it is evicted, so the n0 cached tokens are at the positions 0 .. n0-1 of
+// their logical order and chunk token i (and its query) at n0 + i.  The rotary encoding turns plane (2i, 2i+1) of
+// a row by position * base^(-2i/d); here that is done once per call, in fp32 with the (cos, sin) table, and the
+// result is left as two bf16 parts (hi = the rounded value, lo = the rounded remainder) for the matrix pipe.
+// One thread turns 8 dimensions (4 planes, one 16-byte piece) of one row.  Rows of a unit: n0 cached keys (by
+// logical index, written at their slot), L chunk keys (written behind the cache rows), L * G queries.
+template <int D>
+__global__ __launch_bounds__(256) void prefill_turn_kernel(Params p, const uint16_t* __restrict__ Q,
+                                                           const uint16_t* __restrict__ Kc, int L) {
+  constexpr int PARTS = D / 8;
+  const int unit = blockIdx.y, kvh = unit % p.Hkv, b = unit / p.Hkv;
+  const int* meta = p.meta + (size_t)unit * META_STRIDE;
+  const int n0 = meta[META_N], j = meta[META_J], rhead = meta[META_RHEAD];
+  const int rows = n0 + L + L * p.G;
+  const int x = blockIdx.x * 256 + threadIdx.x;
+  const int row = x / PARTS, part = x % PARTS;
+  if (row >= rows) return;
+  const size_t krot_rows = (size_t)p.cap + p.max_chunk;
+  uint16_t* khi = p.pf_krot + (size_t)unit * 2 * krot_rows * D;
+  const uint16_t* src;
+  uint16_t* dst;
+  size_t lo_off;
+  int pos;
+  if (row < n0) {                                   // cached key at logical index `row`
+    const int* Eu = p.E + (size_t)unit * 2 * p.m;
+    const int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
+    const int slot = n0 < p.budget ? row : logical_to_slot(p, Eu, Ru, rhead, j, row);
+    src = (const uint16_t*)p.K + ((size_t)unit * p.cap + slot) * D;
+    dst = khi + (size_t)slot * D;
+    lo_off = krot_rows * D;
+    pos = row;
+  } else if (row < n0 + L) {                        // the chunk's own key i
+    const int i = row - n0;
+    src = Kc + (((size_t)b * L + i) * p.Hkv + kvh) * D;
+    dst = khi + ((size_t)p.cap + i) * D;
+    lo_off = krot_rows * D;
+    pos = row;
+  } else {                                          // query i of head g of the group
+    const int i = (row - n0 - L) / p.G, g = (row - n0 - L) % p.G;
+    const int h = kvh * p.G + g;
+    src = Q + (((size_t)b * L + i) * p.H + h) * D;
+    dst = p.pf_qrot + (((size_t)b * p.max_chunk + i) * p.H + h) * D;
+    lo_off = (size_t)p.B * p.max_chunk * p.H * D;
+    pos = n0 + i;
+  }
+  const uint4 raw = *reinterpret_cast<const uint4*>(src + part * 8);
+  const float4* cs = reinterpret_cast<const float4*>(p.rope_tab + (size_t)pos * (D / 2) + part * 4);
+  const float4 c01 = cs[0], c23 = cs[1];            // (cos, sin) of planes 4 part .. 4 part + 3
+  const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+  const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
+  unsigned hi[4], lo[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float x0 = __uint_as_float(w[e] << 16), x1 = __uint_as_float(w[e] & 0xffff0000u);
+    const float y0 = x0 * co[e] - x1 * si[e], y1 = x0 * si[e] + x1 * co[e];
+    hi[e] = pack_bf16(y0, y1);
+    lo[e] = pack_bf16(y0 - __uint_as_float(hi[e] << 16), y1 - __uint_as_float(hi[e] & 0xffff0000u));
+  }
+  *reinterpret_cast<uint4*>(dst + part * 8) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+  *reinterpret_cast<uint4*>(dst + lo_off + part * 8) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -939,7 +1117,12 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
   const uint16_t* k = (const uint16_t*)K;
   const uint16_t* v = (const uint16_t*)V;
   const int row_tiles = (L + ROW_TILE - 1) / ROW_TILE;
-  auto attend = prefill_attend_kernel<D>;
+  const bool rope = (p.flags & TREEKV_POSITION_RERANK) != 0;
+  if (rope) {
+    const int rows = p.budget + L + L * p.G;           // at most: every cached key, the chunk's keys and queries
+    hipLaunchKernelGGL(prefill_turn_kernel<D>, dim3((rows * (D / 8) + 255) / 256, p.U), dim3(256), 0, s, p, q, k, L);
+  }
+  auto attend = rope ? prefill_attend_kernel<D, true> : prefill_attend_kernel<D, false>;
   const size_t lds = AttendLds<D>::BYTES;
   if (lds > 48 * 1024 &&
       hip_failed(hipFuncSetAttribute((const void*)attend, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))

@@ -298,14 +298,14 @@ def smoke_prompt(oracle, binding):
 
 
 def smoke_rerank(oracle, binding):
-    """A short decode stream with positions re-assigned to cache ranks, against the oracle."""
+    """A prefill chunk and decode steps with positions re-assigned to cache ranks, against the oracle."""
     from paper_2501_04987_amd import inputs
 
     T, B, H, Hkv, d, budget = 120, 1, 4, 2, 128, 40
     Q, K, V = inputs.batch_streams("lowrank", 3, T, B, Hkv, H // Hkv, d, dtype="bf16")
-    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=2, n_recent=10,
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=2, n_recent=10, max_chunk=64,
                         flags=binding.TREEKV_POSITION_RERANK)
-    st = run_schedule(oracle, kv, Q, K, V, [0] * T, dtype="bf16")
+    st = run_schedule(oracle, kv, Q, K, V, [50] + [0] * 30 + [40], dtype="bf16")
     print(f"smoke: re-assigned positions ok, {st['decisions']} evictions, {st['flagged']} near-ties, "
           f"max |out err| {st['max_err']:.2e}")
 

@@ -1,6 +1,6 @@
-"""GPU parity: decode steps with positions re-assigned to cache ranks (Section 4.1, "Position Encoding") through
-the C ABI against the CPU oracle: q and k arrive without positional encoding, the rotary encoding of the in-cache
-ranks is applied inside the step."""
+"""GPU parity: decode steps, prefill chunks and the one-shot prompt compression with positions re-assigned to cache
+ranks (Section 4.1, "Position Encoding") through the C ABI against the CPU oracle: q and k arrive without positional
+encoding, the rotary encoding of the in-cache ranks is applied inside the call."""
 import numpy as np
 import pytest
 
@@ -90,15 +90,75 @@ def test_rerank_differs_from_plain_and_from_original_positions(binding, oracle):
     assert np.abs(got - attend(kept, t)).max() > 1e-3
 
 
-def test_rerank_chunked_prefill_refuses(binding):
+def _chunks(binding, oracle, schedule, *, B, H, Hkv, d, budget, n_sink, n_recent, seed, max_chunk=0, flags=0,
+            rope_base=0.0, units=None):
+    """Prefill chunks (and decode steps, 0) with re-assigned positions: the n0 cached tokens sit at ranks 0..n0-1, chunk
+    token i at n0 + i; compared call by call."""
+    T = sum(max(L, 1) for L in schedule)
+    Q, K, V = inputs.batch_streams("lowrank", seed, T, B, Hkv, H // Hkv, d, dtype="bf16")
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=n_sink, n_recent=n_recent,
+                        max_chunk=max_chunk, flags=flags | binding.TREEKV_POSITION_RERANK, rope_base=rope_base)
+    st = ph.run_schedule(oracle, kv, Q, K, V, schedule, dtype="bf16", units=units)
+    st["score_err"] = ph.compare_scores(kv, st["results"], "bf16")
+    assert st["flagged"] <= max(2, st["decisions"] // 500), st["flagged"]
+    print(f"  flagged={st['flagged']}/{st['decisions']} max_err={st['max_err']:.2e} score_err={st['score_err']:.2e}")
+    return kv, st
+
+
+def test_rerank_chunks_fill_then_evict(binding, oracle):
+    """Chunks that fill the cache, cross the budget and span several sweeps of the scope index; ragged lengths."""
+    _chunks(binding, oracle, [40, 17, 64, 1, 100, 33, 128, 7], B=1, H=2, Hkv=2, d=128, budget=96, n_sink=2, n_recent=30,
+            max_chunk=128, seed=61)
+
+
+def test_rerank_chunks_interleaved_with_decode(binding, oracle):
+    _chunks(binding, oracle, [0, 0, 20, 0, 64, 0, 0, 0, 70, 0, 5, 0], B=2, H=2, Hkv=2, d=128, budget=48, n_sink=1,
+            n_recent=15, max_chunk=128, seed=62, rope_base=50.0)
+
+
+@pytest.mark.parametrize("G,d", [(4, 128), (2, 64), (8, 64)])
+def test_rerank_chunks_grouped_queries(binding, oracle, G, d):
+    _chunks(binding, oracle, [50, 90, 0, 128, 13], B=2, H=2 * G, Hkv=2, d=d, budget=72, n_sink=3, n_recent=20,
+            max_chunk=128, seed=63)
+
+
+def test_rerank_chunks_pure_algorithm1_many_tiles(binding, oracle):
+    """No protected tokens; 300-token chunks over a 400-slot cache: several column tiles of cache and of chunk, the
+    causal diagonal crossing tiles, up to 2 sweeps per chunk."""
+    _chunks(binding, oracle, [300, 300, 7, 256, 300], B=1, H=2, Hkv=2, d=128, budget=400, n_sink=0, n_recent=0,
+            max_chunk=300, seed=64)
+
+
+def test_rerank_chunk_of_one_token_equals_decode(binding, oracle):
+    """A one-token chunk is a decode step with re-assigned positions: same evictions and retained list, outputs and
+    scores equal to rounding."""
     import torch
 
-    kv = binding.TreeKV(64, 2, 64, kv_heads=2, n_sink=2, n_recent=6, flags=binding.TREEKV_POSITION_RERANK, max_prompt=256)
-    z = torch.zeros(1, 256, 2, 64, dtype=torch.bfloat16, device="cuda")
-    out, ret, nret, ev = kv.new_outputs(16)
-    with pytest.raises(binding.TreeKVError) as e:
-        kv.prefill_chunk(z[:, :16], z[:, :16], z[:, :16], 16, out, ret, nret, ev)
-    assert e.value.status == binding.TREEKV_EUNSUPPORTED
+    T, B, H, d, budget = 150, 1, 4, 128, 32
+    Q, K, V = inputs.batch_streams("lowrank", 65, T, B, H, 1, d, dtype="bf16")
+    mk = lambda: binding.TreeKV(budget, H, d, kv_heads=H, batch=B, dtype="bf16", n_sink=2, n_recent=6, max_chunk=16,
+                                flags=binding.TREEKV_POSITION_RERANK)
+    a, b = mk(), mk()
+    Qd, Kd, Vd = (ph.to_device(x, "bf16") for x in (Q, K, V))
+    oa, ra, na, ea = a.new_outputs()
+    ob, rb, nb, eb = b.new_outputs(1)
+    for t in range(T):
+        a.decode_step(Qd[t], Kd[t], Vd[t], oa, ra, na, ea)
+        cut = lambda X: X[t:t + 1].permute(1, 0, 2, 3).contiguous()
+        b.prefill_chunk(cut(Qd), cut(Kd), cut(Vd), 1, ob, rb, nb, eb)
+        torch.cuda.synchronize()
+        assert torch.equal(ea.flatten(), eb.flatten()) and torch.equal(ra, rb) and torch.equal(na, nb), t
+        assert (oa - ob[:, 0]).abs().max().item() < 2e-4
+    assert (a.scores() - b.scores()).abs().max().item() < 1e-3
+
+
+def test_rerank_chunks_llama_shaped_sampled(binding, oracle):
+    """32 heads x 128, budget 2048 (4 + 1024 + 1020): 2560 tokens in chunks of 512, then decode steps; the oracle
+    audits 4 heads call by call."""
+    sched = [512] * 5 + [0] * 8
+    kv, st = _chunks(binding, oracle, sched, B=1, H=32, Hkv=32, d=128, budget=2048, n_sink=4, n_recent=1020,
+                     units=[(0, 0), (0, 11), (0, 22), (0, 31)], seed=66)
+    assert st["decisions"] == 4 * (2560 + 8 - 2048)
 
 
 def _prompt(binding, oracle, *, T, block, steps, B, H, Hkv, d, budget, n_sink, n_recent, seed, rope_base=0.0, flags=0):
