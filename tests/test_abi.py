@@ -138,20 +138,21 @@ def test_prompt_compression_host_checks(binding):
 
 def test_position_rerank_host_checks(binding):
     """TREEKV_POSITION_RERANK: the rotary table (one row per distance in the cache or prompt position) and the turned
-    window queries are part of the workspace, the base defaults to 10000, and the chunked prefill refuses such a
-    context before anything is enqueued."""
+    window queries are part of the workspace, as are the turned keys and queries of a prefill chunk (two bf16 parts of
+    every cache row and chunk token), and the base defaults to 10000."""
     lib = binding.load()
     rc0, h0 = _init(binding, budget=256, n_sink=4, n_recent=60, max_prompt=1024)
     rc1, h1 = _init(binding, budget=256, n_sink=4, n_recent=60, max_prompt=1024, flags=binding.TREEKV_POSITION_RERANK)
     assert rc0 == 0 and rc1 == 0
     extra = lib.treekv_workspace_bytes(h1) - lib.treekv_workspace_bytes(h0)
     assert extra >= 1024 * 64 * 8 + 4 * 2 * 128 * 128 * 2   # (cos, sin) per prompt position and plane; queries hi + lo
+    assert extra >= 4 * 2 * (257 + 512) * 128 * 2 + 2 * 512 * 4 * 128 * 2      # a chunk's turned keys and queries
     cfg = binding.treekv_config()
     lib.treekv_get_config(h1, C.byref(cfg))
     assert cfg.rope_base == 10000.0 and cfg.flags == binding.TREEKV_POSITION_RERANK
     one = C.c_void_p(0x1000)
     assert lib.treekv_prefill_prompt(h1, one, one, one, 1024, 32, one, None, None, None, None) == binding.TREEKV_ENOWS
-    assert lib.treekv_prefill_chunk(h1, one, one, one, 16, one, one, None, None, None) == binding.TREEKV_EUNSUPPORTED
+    assert lib.treekv_prefill_chunk(h1, one, one, one, 16, one, one, None, None, None) == binding.TREEKV_ENOWS
     assert _init(binding, flags=binding.TREEKV_POSITION_RERANK, rope_base=-1.0)[0] == binding.TREEKV_EINVAL
     assert _init(binding, flags=binding.TREEKV_POSITION_RERANK, rope_base=float("nan"))[0] == binding.TREEKV_EINVAL
     for h in (h0, h1):
