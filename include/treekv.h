@@ -177,6 +177,10 @@ int treekv_decode_step_static(treekv_ctx* ctx, const void* q, const void* k, con
  *   retained   [B, Hkv, c] int32, n_retained [B, Hkv] (may be NULL): as above
  *   evicted    [B, Hkv, len] int32 (may be NULL): position evicted when the
  *              chunk's i-th token was appended, or -1
+ * With bf16 storage the two contractions run on the matrix pipe; with fp32 storage
+ * they run, row by row, on the vector ALUs (held to 1e-5, not a fast path), and
+ * TREEKV_POSITION_RERANK is then not available (TREEKV_EUNSUPPORTED), nor are more than
+ * 10240 visible columns (budget + 1 + len).
  */
 int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const void* V, int len,
                          void* out, int32_t* retained, int32_t* n_retained, int32_t* evicted,

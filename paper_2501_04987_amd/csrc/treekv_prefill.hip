@@ -737,6 +737,137 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
 }
 
 // ---------------------------------------------------------------------------------------------
+// attend for fp32 storage: plain vector arithmetic, one query row at a time
+// ---------------------------------------------------------------------------------------------
+// The matrix pipe takes bf16; with fp32 storage the results are held to 1e-5, so this instance does the same
+// four steps (logits, row softmax, output, column sums) with fp32 multiply-adds.  A workgroup takes F32_ROWS
+// consecutive rows of one head: per row, LPR lanes share a key (16 bytes each, summed by shuffles), the scaled
+// logits and then the probabilities sit in LDS, the output is added up by (piece of the head dimension, stripe
+// of keys) and the stripes are merged through LDS; every thread keeps the column sums of the columns it owns and
+// adds them, as 2^-40 fixed point, to the unit's accumulators at the end (integer adds: order does not matter).
+// Not a fast path: the one configuration with fp32 storage decodes.
+constexpr int F32_THREADS = 256;
+constexpr int F32_ROWS = 16;
+
+template <int D>
+__global__ __launch_bounds__(F32_THREADS) void prefill_attend_f32_kernel(Params p, const float* __restrict__ Q,
+                                                                         const float* __restrict__ Kc,
+                                                                         const float* __restrict__ Vc, int L,
+                                                                         float* __restrict__ out) {
+  constexpr int LPR = D / 4;                       // lanes per row (16 bytes each)
+  constexpr int KPP = F32_THREADS / LPR;           // keys per pass
+  extern __shared__ float f32_smem[];
+  const int unit = blockIdx.z, g = blockIdx.y, tid = threadIdx.x;
+  const int kvh = unit % p.Hkv, b = unit / p.Hkv, h = kvh * p.G + g;
+  const ChunkInfo ci = load_chunk_info(p.meta + (size_t)unit * META_STRIDE);
+  const int ncache = ci.n + 1;                     // slots [0, n], the free one masked
+  const int r0 = blockIdx.x * F32_ROWS, r1 = min(L, r0 + F32_ROWS);
+  const int ncols = ncache + r1;                   // columns any of this workgroup's rows can see
+  float* sp = f32_smem;                            // [ncols] scaled logits, then probabilities
+  float* sred = sp + ncols;                        // [F32_THREADS] reductions, then [KPP][D] output stripes
+  float* sq = sred + (KPP * D > F32_THREADS ? KPP * D : F32_THREADS);    // [D] the query row
+  const float* Ku = (const float*)p.K + (size_t)unit * p.cap * D;
+  const float* Vu = (const float*)p.V + (size_t)unit * p.cap * D;
+  const float* Kcu = Kc + ((size_t)b * L * p.Hkv + kvh) * D;
+  const float* Vcu = Vc + ((size_t)b * L * p.Hkv + kvh) * D;
+  const size_t cstride = (size_t)p.Hkv * D;
+  const int grp = tid / LPR, piece = tid % LPR;
+  constexpr int OWN = 40;                          // columns a thread owns: ncols <= OWN * F32_THREADS (checked by the host)
+  float csum[OWN];
+#pragma unroll
+  for (int x = 0; x < OWN; ++x) csum[x] = 0.f;
+  auto block_reduce = [&](float v, bool take_max) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float o = __shfl_xor(v, off, 64);
+      v = take_max ? fmaxf(v, o) : v + o;
+    }
+    __syncthreads();
+    if ((tid & 63) == 0) sred[tid >> 6] = v;
+    __syncthreads();
+    float r = sred[0];
+#pragma unroll
+    for (int w = 1; w < F32_THREADS / 64; ++w) r = take_max ? fmaxf(r, sred[w]) : r + sred[w];
+    __syncthreads();
+    return r;
+  };
+  for (int i = r0; i < r1; ++i) {
+    const int nvis = ncache + i + 1;
+    if (tid < D) sq[tid] = Q[(((size_t)b * L + i) * p.H + h) * D + tid];
+    __syncthreads();
+    const float4 qv = *reinterpret_cast<const float4*>(sq + piece * 4);
+    // logits
+    for (int j0 = 0; j0 < nvis; j0 += KPP) {
+      const int j = j0 + grp;
+      float acc = 0.f;
+      if (j < nvis) {
+        const float* row = j < ncache ? Ku + (size_t)j * D : Kcu + (size_t)(j - ncache) * cstride;
+        const float4 kv = *reinterpret_cast<const float4*>(row + piece * 4);
+        acc = kv.x * qv.x;
+        acc = fmaf(kv.y, qv.y, acc);
+        acc = fmaf(kv.z, qv.z, acc);
+        acc = fmaf(kv.w, qv.w, acc);
+      }
+#pragma unroll
+      for (int off = LPR / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+      if (j < nvis && piece == 0) sp[j] = (j == ci.fslot && j < ncache) ? -INFINITY : acc * p.scale_log2e;
+    }
+    __syncthreads();
+    // row softmax
+    float mx = NEG_BIG;
+    for (int j = tid; j < nvis; j += F32_THREADS) mx = fmaxf(mx, sp[j]);
+    mx = block_reduce(mx, true);
+    float sum = 0.f;
+    for (int j = tid; j < nvis; j += F32_THREADS) {
+      const float e = fast_exp2(sp[j] - mx);
+      sp[j] = e;
+      sum += e;
+    }
+    sum = block_reduce(sum, false);
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int x = 0; x < OWN; ++x) {
+      const int j = tid + x * F32_THREADS;
+      if (j < nvis) {
+        const float pj = sp[j] * inv;
+        sp[j] = pj;
+        csum[x] += pj;
+      }
+    }
+    __syncthreads();
+    // output: this thread's 4 dimensions over its stripe of keys
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = grp; j < nvis; j += KPP) {
+      const float* row = j < ncache ? Vu + (size_t)j * D : Vcu + (size_t)(j - ncache) * cstride;
+      const float4 vv = *reinterpret_cast<const float4*>(row + piece * 4);
+      const float pj = sp[j];
+      o.x = fmaf(pj, vv.x, o.x); o.y = fmaf(pj, vv.y, o.y); o.z = fmaf(pj, vv.z, o.z); o.w = fmaf(pj, vv.w, o.w);
+    }
+    *reinterpret_cast<float4*>(sred + grp * D + piece * 4) = o;
+    __syncthreads();
+    if (tid < D) {
+      float a = 0.f;
+#pragma unroll
+      for (int w = 0; w < KPP; ++w) a += sred[w * D + tid];
+      out[(((size_t)b * L + i) * p.H + h) * D + tid] = a;
+    }
+    __syncthreads();
+  }
+  // the column sums of this workgroup's rows
+  const int cap_cols = (p.cap + AT_COLS - 1) / AT_COLS * AT_COLS;
+  const int cs_stride = cap_cols + (p.max_chunk + AT_COLS - 1) / AT_COLS * AT_COLS;
+  unsigned long long* cs_acc = p.pf_colacc + (size_t)unit * cs_stride;
+#pragma unroll
+  for (int x = 0; x < OWN; ++x) {
+    const int j = tid + x * F32_THREADS;
+    if (j < ncols && csum[x] != 0.f) {
+      const long long fix = (long long)(csum[x] * COLSUM_FIX + 0.5f);
+      atomicAdd(cs_acc + (j < ncache ? j : cap_cols + (j - ncache)), (unsigned long long)fix);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // positions re-assigned to cache ranks: the chunk's queries and every key it attends, turned and split
 // ---------------------------------------------------------------------------------------------
 // A chunk is scored before anything of it is evicted, so the n0 cached tokens are at the positions 0 .. n0-1 of
@@ -1110,6 +1241,27 @@ __global__ __launch_bounds__(256) void prefill_scatter_kernel(Params p, const ui
   reinterpret_cast<uint4*>(p.V)[dst] = Vc[src];
 }
 
+// What follows the attend kernel, whatever the storage type: replay, then the surviving rows' copy.
+int launch_replay(const Params& p, const void* K, const void* V, int L, int32_t* retained, int32_t* n_retained,
+                  int32_t* evicted, hipStream_t s) {
+  const size_t rp_lds = replay_lds_words(p.m, p.cap, p.n_recent, L) * sizeof(int);
+  const int row_vec = p.D * (p.dtype == TREEKV_BF16 ? 2 : 4) / 16;
+  if (rp_lds <= 140 * 1024) {
+    auto replay = prefill_replay_kernel<true>;
+    if (rp_lds > 48 * 1024 &&
+        hip_failed(hipFuncSetAttribute((const void*)replay, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rp_lds)))
+      return TREEKV_EHIP;
+    hipLaunchKernelGGL(replay, dim3(p.U), dim3(RP_THREADS), rp_lds, s, p, L, (const uint4*)K, (const uint4*)V, row_vec,
+                       retained, n_retained, evicted);
+  } else {
+    if (2 * (size_t)L + 1 > (size_t)p.cap + p.max_chunk) return TREEKV_EUNSUPPORTED;   // its lists live in pf_list
+    hipLaunchKernelGGL(prefill_replay_kernel<false>, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, (const uint4*)K,
+                       (const uint4*)V, row_vec, retained, n_retained, evicted);
+  }
+  hipLaunchKernelGGL(prefill_scatter_kernel, dim3((L + 256 / row_vec - 1) / (256 / row_vec), p.U), dim3(256), 0, s, p, (const uint4*)K, (const uint4*)V, L, row_vec);
+  return finish_launch();
+}
+
 template <int D>
 int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* V, int L, float* out,
                      int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s) {
@@ -1129,29 +1281,36 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
     return TREEKV_EHIP;
   const int n_items = row_tiles * p.G * p.U;
   hipLaunchKernelGGL(attend, dim3((n_items + 7) / 8 * 8), dim3(AT_THREADS), lds, s, p, q, k, v, L, row_tiles, out);
-  const size_t rp_lds = replay_lds_words(p.m, p.cap, p.n_recent, L) * sizeof(int);
-  const int row_vec = D * 2 / 16;
-  if (rp_lds <= 140 * 1024) {
-    auto replay = prefill_replay_kernel<true>;
-    if (rp_lds > 48 * 1024 &&
-        hip_failed(hipFuncSetAttribute((const void*)replay, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rp_lds)))
-      return TREEKV_EHIP;
-    hipLaunchKernelGGL(replay, dim3(p.U), dim3(RP_THREADS), rp_lds, s, p, L, (const uint4*)K, (const uint4*)V, row_vec,
-                       retained, n_retained, evicted);
-  } else {
-    if (2 * (size_t)L + 1 > (size_t)p.cap + p.max_chunk) return TREEKV_EUNSUPPORTED;   // its lists live in pf_list
-    hipLaunchKernelGGL(prefill_replay_kernel<false>, dim3(p.U), dim3(RP_THREADS), 0, s, p, L, (const uint4*)K,
-                       (const uint4*)V, row_vec, retained, n_retained, evicted);
-  }
-  hipLaunchKernelGGL(prefill_scatter_kernel, dim3((L + 256 / row_vec - 1) / (256 / row_vec), p.U), dim3(256), 0, s, p, (const uint4*)K, (const uint4*)V, L, row_vec);
-  return finish_launch();
+  return launch_replay(p, K, V, L, retained, n_retained, evicted, s);
+}
+
+// fp32 storage: the vector-arithmetic attend (no position re-assignment there), then the same replay.
+template <int D>
+int launch_prefill_f32(const Params& p, const void* Q, const void* K, const void* V, int L, float* out,
+                       int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s) {
+  if (p.flags & TREEKV_POSITION_RERANK) return TREEKV_EUNSUPPORTED;
+  const size_t ncols = (size_t)p.cap + L;
+  if (ncols > 40 * (size_t)F32_THREADS) return TREEKV_EUNSUPPORTED;      // a thread owns at most 40 columns' sums
+  constexpr int KPP = F32_THREADS / (D / 4);
+  const size_t lds = (ncols + (KPP * D > F32_THREADS ? KPP * D : F32_THREADS) + D) * sizeof(float);
+  auto attend = prefill_attend_f32_kernel<D>;
+  if (lds > 48 * 1024 &&
+      hip_failed(hipFuncSetAttribute((const void*)attend, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))
+    return TREEKV_EHIP;
+  hipLaunchKernelGGL(attend, dim3((L + F32_ROWS - 1) / F32_ROWS, p.G, p.U), dim3(F32_THREADS), lds, s, p, (const float*)Q,
+                     (const float*)K, (const float*)V, L, out);
+  return launch_replay(p, K, V, L, retained, n_retained, evicted, s);
 }
 
 }  // namespace
 
 int launch_prefill(const Params& p, const void* Q, const void* K, const void* V, int len, float* out,
                    int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s) {
-  if (p.dtype != TREEKV_BF16) return TREEKV_EUNSUPPORTED;      // the MFMA path is bf16
+  if (p.dtype == TREEKV_F32) {
+    if (p.D == 128) return launch_prefill_f32<128>(p, Q, K, V, len, out, retained, n_retained, evicted, s);
+    if (p.D == 64) return launch_prefill_f32<64>(p, Q, K, V, len, out, retained, n_retained, evicted, s);
+    return TREEKV_EUNSUPPORTED;
+  }
   if (p.D == 128) return launch_prefill_d<128>(p, Q, K, V, len, out, retained, n_retained, evicted, s);
   if (p.D == 64) return launch_prefill_d<64>(p, Q, K, V, len, out, retained, n_retained, evicted, s);
   return TREEKV_EUNSUPPORTED;

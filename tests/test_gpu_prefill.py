@@ -20,13 +20,13 @@ def binding():
 
 
 def _run(binding, oracle, schedule, *, B, H, Hkv, d, budget, n_sink, n_recent, seed=0, max_chunk=0, flags=0,
-         units=None, kind="lowrank"):
+         units=None, kind="lowrank", dtype="bf16", scale=0.0, **gen_kw):
     T = sum(max(L, 1) for L in schedule)
-    Q, K, V = inputs.batch_streams(kind, seed, T, B, Hkv, H // Hkv, d, dtype="bf16")
-    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=n_sink, n_recent=n_recent,
-                        max_chunk=max_chunk, flags=flags)
-    st = ph.run_schedule(oracle, kv, Q, K, V, schedule, dtype="bf16", units=units)
-    st["score_err"] = ph.compare_scores(kv, st["results"], "bf16")
+    Q, K, V = inputs.batch_streams(kind, seed, T, B, Hkv, H // Hkv, d, dtype=dtype, **gen_kw)
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype=dtype, n_sink=n_sink, n_recent=n_recent,
+                        max_chunk=max_chunk, flags=flags, softmax_scale=scale)
+    st = ph.run_schedule(oracle, kv, Q, K, V, schedule, dtype=dtype, units=units)
+    st["score_err"] = ph.compare_scores(kv, st["results"], dtype)
     assert st["flagged"] <= max(2, st["decisions"] // 500), st["flagged"]
     print(f"  flagged={st['flagged']}/{st['decisions']} max_err={st['max_err']:.2e} score_err={st['score_err']:.2e}")
     return kv, st
@@ -103,9 +103,9 @@ def test_prefill_argument_errors(binding):
         kv.prefill_chunk(x, x, x, 65, out, ret, nret, ev)          # longer than max_chunk
     with pytest.raises(binding.TreeKVError):
         kv.prefill_chunk(x, x, x, 0, out, ret, nret, ev)
-    kv32 = binding.TreeKV(32, 2, 64, kv_heads=2, dtype="f32", n_sink=0, n_recent=0)
+    kv32 = binding.TreeKV(32, 2, 64, kv_heads=2, dtype="f32", n_sink=0, n_recent=0, flags=binding.TREEKV_POSITION_RERANK)
     with pytest.raises(binding.TreeKVError) as e:
-        kv32.prefill_chunk(x, x, x, 8, out, ret, nret, ev)         # the MFMA prefill is bf16 only
+        kv32.prefill_chunk(x, x, x, 8, out, ret, nret, ev)         # fp32 storage has no re-assigned positions in a chunk
     assert e.value.status == binding.TREEKV_EUNSUPPORTED
 
 
@@ -131,3 +131,24 @@ def test_prefill_gather_kv_matches_retained(binding, oracle):
 def test_prefill_accumulated_weight_criterion(binding, oracle):
     _run(binding, oracle, [40, 64, 0, 128, 0, 0, 77, 5], B=1, H=4, Hkv=2, d=128, budget=72, n_sink=2, n_recent=20,
          max_chunk=128, flags=binding.TREEKV_SCORE_ACCUMULATED, seed=23)
+
+
+@pytest.mark.parametrize("G,d", [(1, 64), (2, 128), (4, 64)])
+def test_prefill_fp32_storage(binding, oracle, G, d):
+    """fp32 storage: the chunk's attention runs on the vector ALUs (the matrix pipe takes bf16) and is held to 1e-5;
+    chunks that fill, cross the budget and span sweeps, decode steps in between, ragged lengths."""
+    _run(binding, oracle, [40, 17, 64, 1, 0, 100, 33, 0, 0, 128, 7], B=2, H=2 * G, Hkv=2, d=d, budget=96, n_sink=2,
+         n_recent=30, max_chunk=128, seed=14, kind="iid", dtype="f32")
+
+
+def test_prefill_fp32_tiny_configuration_in_chunks(binding, oracle):
+    """The tiny fp32 configuration (2 heads x 64, budget 64, 512 tokens, K carrying the 1/sqrt(64)) fed as chunks."""
+    _run(binding, oracle, [64] * 7 + [63, 1], B=1, H=2, Hkv=2, d=64, budget=64, n_sink=4, n_recent=28, max_chunk=64,
+         seed=0, kind="iid", dtype="f32", scale=1.0, k_scale=0.125)
+
+
+def test_prefill_fp32_degenerate_and_keep_left(binding, oracle):
+    _run(binding, oracle, [5, 1, 16, 0, 33], B=1, H=1, Hkv=1, d=64, budget=3, n_sink=1, n_recent=1, max_chunk=64,
+         seed=15, kind="iid", dtype="f32")
+    _run(binding, oracle, [30, 30, 10, 30], B=1, H=2, Hkv=2, d=128, budget=40, n_sink=0, n_recent=8, max_chunk=32,
+         flags=binding.TREEKV_KEEP_LEFT | binding.TREEKV_SCORE_ACCUMULATED, seed=16, kind="iid", dtype="f32")

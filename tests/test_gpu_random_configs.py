@@ -128,3 +128,41 @@ def test_random_prompt_then_steps_with_reassigned_positions(binding, oracle, see
                         flags=binding.TREEKV_POSITION_RERANK, rope_base=base)
     st = ph.run_prompt(oracle, kv, Q, K, V, T, block, steps)
     assert st["flagged"] <= max(2, st["decisions"] // 100), (c, st["flagged"])
+
+
+def _random_schedule(rng, budget, max_chunk):
+    sched, total = [], 0
+    while total < 2 * budget + 60:
+        L = 0 if rng.random() < 0.45 else int(rng.integers(1, max_chunk + 1))
+        sched.append(L)
+        total += max(L, 1)
+    return sched, total
+
+
+@pytest.mark.parametrize("seed", range(80, 96))
+def test_random_fp32_schedule_of_chunks_and_steps(binding, oracle, seed):
+    """fp32 storage: chunks (vector-ALU attention) and decode steps mixed, held to 1e-5."""
+    rng, c = _draw(seed)
+    max_chunk = int(rng.choice([16, 64, 200]))
+    sched, total = _random_schedule(rng, c["budget"], max_chunk)
+    Q, K, V = inputs.batch_streams("iid", seed, total, c["B"], c["Hkv"], c["G"], c["d"], dtype="f32")
+    kv = binding.TreeKV(c["budget"], c["Hkv"] * c["G"], c["d"], kv_heads=c["Hkv"], batch=c["B"], dtype="f32",
+                        n_sink=c["n_sink"], n_recent=c["n_recent"], max_chunk=max_chunk, kv_splits=c["splits"])
+    st = ph.run_schedule(oracle, kv, Q, K, V, sched, dtype="f32")
+    ph.compare_scores(kv, st["results"], "f32")
+    assert st["flagged"] <= max(2, st["decisions"] // 200), (c, st["flagged"])
+
+
+@pytest.mark.parametrize("seed", range(96, 116))
+def test_random_rerank_schedule_of_chunks_and_steps(binding, oracle, seed):
+    """bf16 with positions re-assigned to cache ranks: chunks and decode steps mixed, random rotary base."""
+    rng, c = _draw(seed)
+    max_chunk = int(rng.choice([16, 64, 200]))
+    sched, total = _random_schedule(rng, c["budget"], max_chunk)
+    Q, K, V = inputs.batch_streams("lowrank", seed, total, c["B"], c["Hkv"], c["G"], c["d"], dtype="bf16")
+    kv = binding.TreeKV(c["budget"], c["Hkv"] * c["G"], c["d"], kv_heads=c["Hkv"], batch=c["B"], dtype="bf16",
+                        n_sink=c["n_sink"], n_recent=c["n_recent"], max_chunk=max_chunk, kv_splits=c["splits"],
+                        flags=binding.TREEKV_POSITION_RERANK, rope_base=float(rng.choice([0.0, 50.0, 500000.0])))
+    st = ph.run_schedule(oracle, kv, Q, K, V, sched, dtype="bf16")
+    ph.compare_scores(kv, st["results"], "bf16")
+    assert st["flagged"] <= max(2, st["decisions"] // 200), (c, st["flagged"])
