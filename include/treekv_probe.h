@@ -16,10 +16,12 @@
 extern "C" {
 #endif
 
-/* Reads `bytes` (a multiple of 1 MiB, 16-byte aligned) once with 16-byte non-temporal lane loads, 1 MiB per
- * 512-thread workgroup -- the decode kernel's launch shape and load type.  `sink` [1] float32 receives a value only
- * if the data hashes to a fixed pattern (so the loads cannot be dropped). */
-int treekv_probe_read(const void* src, size_t bytes, float* sink, void* stream);
+/* Reads `bytes` (a multiple of 1 MiB, 16-byte aligned) once with 16-byte non-temporal lane loads -- the decode
+ * kernel's load type -- from 512-thread workgroups that take `kib_per_workgroup` KiB each (a power of two, 32 .. 1024;
+ * 1024 with 256 MiB is the decode kernel's launch shape) with `loads_in_flight` (2, 4 or 8) loads per thread
+ * outstanding.  `sink` [1] float32 receives a value only if the data hashes to a fixed pattern (so the loads cannot
+ * be dropped). */
+int treekv_probe_read(const void* src, size_t bytes, int kib_per_workgroup, int loads_in_flight, float* sink, void* stream);
 
 /* Copies `bytes` (a multiple of 1 MiB, both 16-byte aligned) with ordinary 16-byte loads and stores: exactly
  * `bytes` read and `bytes` written. */

@@ -83,7 +83,7 @@ def load() -> C.CDLL:
     lib.treekv_export_state.argtypes = [vp, vp, C.c_size_t, vp]
     lib.treekv_import_state.argtypes = [vp, vp, C.c_size_t, i32p, vp]
     lib.treekv_wavelet_components.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp]
-    lib.treekv_probe_read.argtypes = [vp, C.c_size_t, vp, vp]
+    lib.treekv_probe_read.argtypes = [vp, C.c_size_t, C.c_int, C.c_int, vp, vp]
     lib.treekv_probe_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.treekv_probe_mfma.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), vp]
     lib.treekv_strerror.argtypes = [C.c_int]

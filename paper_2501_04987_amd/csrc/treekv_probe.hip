@@ -10,11 +10,12 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 constexpr int RD_THREADS = 512;
 constexpr size_t WG_BYTES = (size_t)1 << 20;
 
-__global__ __launch_bounds__(RD_THREADS) void probe_read_kernel(const v4u* __restrict__ src, float* __restrict__ sink) {
-  const v4u* p = src + (size_t)blockIdx.x * (WG_BYTES / 16);
+template <int UN>
+__global__ __launch_bounds__(RD_THREADS) void probe_read_kernel(const v4u* __restrict__ src, size_t wg_vecs,
+                                                                float* __restrict__ sink) {
+  const v4u* p = src + (size_t)blockIdx.x * wg_vecs;
   unsigned acc = 0;
-  constexpr int UN = 4;
-  for (size_t i = threadIdx.x; i < WG_BYTES / 16; i += RD_THREADS * UN) {
+  for (size_t i = threadIdx.x; i < wg_vecs; i += RD_THREADS * UN) {
     v4u r[UN];
 #pragma unroll
     for (int u = 0; u < UN; ++u) r[u] = __builtin_nontemporal_load(p + i + (size_t)u * RD_THREADS);
@@ -60,10 +61,17 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 extern "C" {
 
-int treekv_probe_read(const void* src, size_t bytes, float* sink, void* stream) {
+int treekv_probe_read(const void* src, size_t bytes, int kib_per_workgroup, int loads_in_flight, float* sink, void* stream) {
   if (!src || !sink || !aligned16(src) || !mib_multiple(bytes)) return TREEKV_EINVAL;
-  hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)(bytes / WG_BYTES)), dim3(RD_THREADS), 0, (hipStream_t)stream,
-                     (const v4u*)src, sink);
+  if (kib_per_workgroup < 32 || kib_per_workgroup > 1024 || (kib_per_workgroup & (kib_per_workgroup - 1))) return TREEKV_EINVAL;
+  const size_t wg_bytes = (size_t)kib_per_workgroup << 10, wg_vecs = wg_bytes / 16;
+  const dim3 grid((unsigned)(bytes / wg_bytes)), block(RD_THREADS);
+  hipStream_t st = (hipStream_t)stream;
+  // a workgroup's share is a multiple of 512 threads x 16 bytes x the loads in flight (32 KiB at 4)
+  if (loads_in_flight == 2) hipLaunchKernelGGL(probe_read_kernel<2>, grid, block, 0, st, (const v4u*)src, wg_vecs, sink);
+  else if (loads_in_flight == 4) hipLaunchKernelGGL(probe_read_kernel<4>, grid, block, 0, st, (const v4u*)src, wg_vecs, sink);
+  else if (loads_in_flight == 8 && kib_per_workgroup >= 64) hipLaunchKernelGGL(probe_read_kernel<8>, grid, block, 0, st, (const v4u*)src, wg_vecs, sink);
+  else return TREEKV_EINVAL;
   const int rc = tkv::finish_launch();
   (void)tkv::take_hip_error();
   return rc;

@@ -220,8 +220,10 @@ def test_snapshot_sizes_and_argument_checks(binding):
 def test_probe_argument_checks(binding):
     lib = binding.load()
     buf = C.c_void_p(0x100000)
-    assert lib.treekv_probe_read(buf, (1 << 20) + 16, buf, None) == binding.TREEKV_EINVAL      # not whole MiB
-    assert lib.treekv_probe_read(None, 1 << 20, buf, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_probe_read(buf, (1 << 20) + 16, 1024, 4, buf, None) == binding.TREEKV_EINVAL      # not whole MiB
+    assert lib.treekv_probe_read(None, 1 << 20, 1024, 4, buf, None) == binding.TREEKV_EINVAL
+    assert lib.treekv_probe_read(buf, 1 << 20, 48, 4, buf, None) == binding.TREEKV_EINVAL               # not a power of two
+    assert lib.treekv_probe_read(buf, 1 << 20, 1024, 3, buf, None) == binding.TREEKV_EINVAL
     assert lib.treekv_probe_copy(buf, C.c_void_p(0x100008), 1 << 20, None) == binding.TREEKV_EINVAL
     assert lib.treekv_probe_mfma(buf, 256, 3, 10, None, None) == binding.TREEKV_EINVAL
     assert lib.treekv_probe_mfma(None, 256, 1, 10, None, None) == binding.TREEKV_EINVAL
