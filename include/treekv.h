@@ -200,15 +200,17 @@ int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const vo
  * averaged score stays its window average (its count becomes len - position, its accumulated weight
  * that count times the average) and token-level eviction starts at the first scope.
  *   Qw [B, block, H, d]: queries of the prompt's last `block` tokens; K, V [B, len, Hkv, d]: the whole
- *   prompt; storage dtype (bf16 only), read only
+ *   prompt; storage dtype, read only
  *   retained   [B, Hkv, c] int32: positions kept, ascending, padded with -1 (len < c keeps everything)
  *   n_retained [B, Hkv] int32 (may be NULL)
  *   evicted_blocks [B, Hkv, len / block] int32 (may be NULL): the block evicted when block i was
  *              appended, or -1
  *   token_scores [B, Hkv, len] float32 (may be NULL): the tokens' averaged window attention
+ * With fp32 storage the window's scores are computed on the vector ALUs, one window query at a time (not a
+ * fast path), without TREEKV_POSITION_RERANK and for len <= 32768.
  * Errors: TREEKV_EINVAL unless 1 <= block <= len <= max_prompt, block divides len and budget, and
  * budget / block - ceil(n_sink / block) - ceil(n_recent / block) >= 1; TREEKV_EUNSUPPORTED if
- * block * G > 128 or the dtype is not bf16.
+ * block * G > 128, or with fp32 storage as said above.
  */
 int treekv_prefill_prompt(treekv_ctx* ctx, const void* Qw, const void* K, const void* V, int len, int block,
                           int32_t* retained, int32_t* n_retained, int32_t* evicted_blocks,

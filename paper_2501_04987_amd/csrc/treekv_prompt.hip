@@ -396,6 +396,86 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, con
 }
 
 // ---------------------------------------------------------------------------------------------
+// token scores for fp32 storage: plain vector arithmetic, one window query at a time
+// ---------------------------------------------------------------------------------------------
+// The matrix pipe takes bf16; with fp32 storage the scores are held to the precision of fp32 sums, so this instance
+// works through the window's queries one after the other: LPR lanes share a key (16 bytes each, summed by shuffles),
+// the scaled logits of the query sit in LDS, then become probabilities, and every thread adds those of the keys it
+// owns to the unit's token scores.  One workgroup per unit; not a fast path (the one configuration with fp32
+// storage has no prompt to compress).
+constexpr int PF_THREADS = 256;
+
+template <int D>
+__global__ __launch_bounds__(PF_THREADS) void prompt_scores_f32_kernel(Params p, const float* __restrict__ Qw,
+                                                                       const float* __restrict__ K, int T, int W) {
+  constexpr int LPR = D / 4, KPP = PF_THREADS / LPR;
+  extern __shared__ float pf_smem[];
+  float* sp = pf_smem;                  // [T] scaled logits, then exponentials
+  float* sred = sp + T;                 // [PF_THREADS / 64]
+  float* sq = sred + PF_THREADS / 64;   // [D]
+  const int unit = blockIdx.x, tid = threadIdx.x, kvh = unit % p.Hkv, b = unit / p.Hkv;
+  const int grp = tid / LPR, piece = tid % LPR;
+  float* tok = p.pp_tok + (size_t)unit * T;
+  const float* Ku = K + ((size_t)b * T * p.Hkv + kvh) * D;
+  const size_t kstride = (size_t)p.Hkv * D;
+  for (int j = tid; j < T; j += PF_THREADS) tok[j] = 0.f;      // a thread only ever touches the keys j = tid mod PF_THREADS
+  auto block_reduce = [&](float v, bool take_max) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float o = __shfl_xor(v, off, 64);
+      v = take_max ? fmaxf(v, o) : v + o;
+    }
+    __syncthreads();
+    if ((tid & 63) == 0) sred[tid >> 6] = v;
+    __syncthreads();
+    float r = sred[0];
+#pragma unroll
+    for (int w = 1; w < PF_THREADS / 64; ++w) r = take_max ? fmaxf(r, sred[w]) : r + sred[w];
+    __syncthreads();
+    return r;
+  };
+  for (int i = 0; i < W; ++i) {
+    const int nvis = T - W + i + 1;                             // window query i sees the keys up to its own
+    for (int g = 0; g < p.G; ++g) {
+      if (tid < D) sq[tid] = Qw[(((size_t)b * W + i) * p.H + kvh * p.G + g) * D + tid];
+      __syncthreads();
+      const float4 qv = *reinterpret_cast<const float4*>(sq + piece * 4);
+      for (int j0 = 0; j0 < nvis; j0 += KPP) {
+        const int j = j0 + grp;
+        float acc = 0.f;
+        if (j < nvis) {
+          const float4 kv = *reinterpret_cast<const float4*>(Ku + (size_t)j * kstride + piece * 4);
+          acc = kv.x * qv.x;
+          acc = fmaf(kv.y, qv.y, acc);
+          acc = fmaf(kv.z, qv.z, acc);
+          acc = fmaf(kv.w, qv.w, acc);
+        }
+#pragma unroll
+        for (int off = LPR / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+        if (j < nvis && piece == 0) sp[j] = acc * p.scale_log2e;
+      }
+      __syncthreads();
+      float mx = NEG_BIG;
+      for (int j = tid; j < nvis; j += PF_THREADS) mx = fmaxf(mx, sp[j]);
+      mx = block_reduce(mx, true);
+      float sum = 0.f;
+      for (int j = tid; j < nvis; j += PF_THREADS) {
+        const float e = fast_exp2(sp[j] - mx);
+        sp[j] = e;
+        sum += e;
+      }
+      sum = block_reduce(sum, false);
+      const float inv = 1.0f / sum;
+      for (int j = tid; j < nvis; j += PF_THREADS) tok[j] += sp[j] * inv;
+      __syncthreads();
+    }
+  }
+  // the key T - x is seen by x of the window's queries, every key before the window by all W of them
+  if (!(p.flags & TREEKV_SCORE_ACCUMULATED))
+    for (int j = tid; j < T; j += PF_THREADS) tok[j] /= (float)min(W, T - j);
+}
+
+// ---------------------------------------------------------------------------------------------
 // blocks: block means, Algorithm 1 over blocks with frozen scores, the kept blocks in ascending order
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prompt_blocks_kernel(Params p, int T, int b, int cb, int sink_b, int recent_b,
@@ -574,16 +654,26 @@ size_t prompt_blocks_lds(int T, int b, int cb, int sink_b, int recent_b) {
 
 int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V, int T, int b, int32_t* retained,
                   int32_t* n_retained, int32_t* evicted_blocks, float* token_scores, hipStream_t s) {
-  if (p.dtype != TREEKV_BF16) return TREEKV_EUNSUPPORTED;      // the MFMA path is bf16
   const int cb = p.budget / b, sink_b = (p.n_sink + b - 1) / b, recent_b = (p.n_recent + b - 1) / b;
-  int rows_per_split = 0;
-  const int nsplit = prompt_splits(p, T, &rows_per_split);
-  // the scores kernel also takes the block means when no block straddles two slices and a slice's scores fit
-  // in 40 KB of LDS (slices start at multiples of what a workgroup takes per iteration)
-  const int block_means = (PP_STEP % b == 0 && (size_t)rows_per_split * 4 <= 40 * 1024) ? 1 : 0;
-  const int rc = p.D == 128 ? launch_streams_d<128>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, block_means, s)
-                            : launch_streams_d<64>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, block_means, s);
-  if (rc != TREEKV_OK) return rc;
+  int block_means = 0;
+  if (p.dtype == TREEKV_F32) {
+    // fp32 storage: the vector-ALU instance (no position re-assignment there; a query's logits must fit in LDS)
+    if ((p.flags & TREEKV_POSITION_RERANK) || T > 32768) return TREEKV_EUNSUPPORTED;
+    const size_t lds = ((size_t)T + PF_THREADS / 64 + p.D) * sizeof(float);
+    auto kern = p.D == 128 ? prompt_scores_f32_kernel<128> : prompt_scores_f32_kernel<64>;
+    if (lds > 48 * 1024 && hip_failed(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))
+      return TREEKV_EHIP;
+    hipLaunchKernelGGL(kern, dim3(p.U), dim3(PF_THREADS), lds, s, p, (const float*)Qw, (const float*)K, T, b);
+  } else {
+    int rows_per_split = 0;
+    const int nsplit = prompt_splits(p, T, &rows_per_split);
+    // the scores kernel also takes the block means when no block straddles two slices and a slice's scores fit
+    // in 40 KB of LDS (slices start at multiples of what a workgroup takes per iteration)
+    block_means = (PP_STEP % b == 0 && (size_t)rows_per_split * 4 <= 40 * 1024) ? 1 : 0;
+    const int rc = p.D == 128 ? launch_streams_d<128>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, block_means, s)
+                              : launch_streams_d<64>(p, (const uint16_t*)Qw, (const uint16_t*)K, T, b, rows_per_split, nsplit, block_means, s);
+    if (rc != TREEKV_OK) return rc;
+  }
   const size_t lds = prompt_blocks_lds(T, b, cb, sink_b, recent_b);
   if (lds > 48 * 1024 &&
       hip_failed(hipFuncSetAttribute((const void*)prompt_blocks_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))
@@ -591,7 +681,7 @@ int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V,
   const int blocks_threads = 256;
   hipLaunchKernelGGL(prompt_blocks_kernel, dim3(p.U), dim3(blocks_threads), lds, s, p, T, b, cb, sink_b, recent_b,
                      block_means, evicted_blocks);
-  const int row_vec = p.D * 2 / 16, per_wg = 256 / row_vec;
+  const int row_vec = p.D * (p.dtype == TREEKV_BF16 ? 2 : 4) / 16, per_wg = 256 / row_vec;
   const int n = T < p.budget ? T : p.budget;
   hipLaunchKernelGGL(prompt_handoff_kernel, dim3((p.budget + per_wg - 1) / per_wg, p.U), dim3(256), 0, s, p,
                      (const uint4*)K, (const uint4*)V, T, b, n, row_vec, retained, n_retained);

@@ -21,11 +21,11 @@ def binding():
 
 
 def _run(binding, oracle, *, T, block, steps, B, H, Hkv, d, budget, n_sink, n_recent, seed=0, flags=0, units=None,
-         kind="lowrank"):
-    Q, K, V = inputs.batch_streams(kind, seed, T + steps, B, Hkv, H // Hkv, d, dtype="bf16")
-    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=n_sink, n_recent=n_recent,
+         kind="lowrank", dtype="bf16"):
+    Q, K, V = inputs.batch_streams(kind, seed, T + steps, B, Hkv, H // Hkv, d, dtype=dtype)
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype=dtype, n_sink=n_sink, n_recent=n_recent,
                         flags=flags, max_prompt=T)
-    st = ph.run_prompt(oracle, kv, Q, K, V, T, block, steps, units=units)
+    st = ph.run_prompt(oracle, kv, Q, K, V, T, block, steps, units=units, dtype=dtype)
     assert st["flagged"] <= max(1, st["decisions"] // 200), st["flagged"]
     print(f"  blocks evicted={st['decisions']} flagged={st['flagged']} token score rel err={st['tok_err']:.2e} "
           f"score_err={st['score_err']:.2e}")
@@ -219,3 +219,18 @@ def test_prompt_and_chunked_prefill_share_the_span_structure(binding):
     # different criteria: the two must not simply coincide on the tree region
     assert same < H * budget, same
     print(f"  same token kept in {same - H * (n_sink + n_recent)} of {H * (budget - n_sink - n_recent)} spans")
+
+
+@pytest.mark.parametrize("G,d,block", [(1, 64, 16), (2, 128, 8), (4, 64, 4)])
+def test_prompt_fp32_storage(binding, oracle, G, d, block):
+    """fp32 storage: the window's scores come from the vector-ALU instance; blocks, hand-over and the decode steps
+    that follow are the same kernels."""
+    _run(binding, oracle, T=block * 41, block=block, steps=40, B=2, H=2 * G, Hkv=2, d=d, budget=block * 9, n_sink=2,
+         n_recent=block + 3, seed=17, kind="iid", dtype="f32")
+
+
+def test_prompt_fp32_that_fits_and_accumulated(binding, oracle):
+    _run(binding, oracle, T=48, block=8, steps=30, B=1, H=2, Hkv=2, d=64, budget=64, n_sink=1, n_recent=10, seed=18,
+         kind="iid", dtype="f32")
+    _run(binding, oracle, T=320, block=16, steps=20, B=1, H=2, Hkv=1, d=128, budget=96, n_sink=0, n_recent=16, seed=19,
+         kind="iid", dtype="f32", flags=binding.TREEKV_SCORE_ACCUMULATED)
