@@ -6,8 +6,8 @@
  * scores, managed by the paper's Algorithm 1 ("Compression by TreeKV",
  * Section 4.1).  A call attends the new query/queries over the cache
  * (Section 3.1: a = SoftMax(q K^T / sqrt(d)), o = a V), adds the attention
- * probabilities to the slots' scores (Algorithm 1, lines 7-8), evicts by the
- * tree rule (lines 9-17) and reuses the freed slots for the next tokens.
+ * probabilities to the slots' scores (Algorithm 1's C and S updates), evicts by the
+ * tree rule (its eviction block) and reuses the freed slots for the next tokens.
  *
  * Conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller; the library
@@ -51,7 +51,7 @@ typedef enum treekv_status {
 } treekv_status;
 
 enum { TREEKV_BF16 = 0, TREEKV_F32 = 1 };      /* storage type of q, k, v and of the cache */
-/* The index update Algorithm 1 prints in its line 17, idx = (idx+1) mod c + 1, visits every other scope only
+/* The index update Algorithm 1 prints as its last step, idx = (idx+1) mod c + 1, visits every other scope only
  * and contradicts Section 4.1 (idx "cycles through 1, 2, 3, and 4"); this library advances idx by one,
  * idx = (idx mod m) + 1, and has no flag for the printed form. */
 enum {
@@ -59,7 +59,7 @@ enum {
                                     ignore the scores)                                                   */
   TREEKV_SCORE_ACCUMULATED = 4,  /* importance = accumulated weight S instead of the average S / C
                                     (Section 4.1, "Importance Score": the criterion tried next to the
-                                    average); Algorithm 1 line 10 is skipped, lines 11-15 compare S     */
+                                    average); Algorithm 1's averaging step is skipped, the scope compares S     */
   TREEKV_POSITION_RERANK = 8     /* positions re-assigned after eviction (Section 4.1, "Position Encoding"):
                                     q and k are given WITHOUT positional encoding and the cache keeps them so;
                                     at every decode step the cached tokens and the new one, in position order,
@@ -129,12 +129,12 @@ size_t treekv_workspace_bytes(const treekv_ctx* ctx);
  * treekv_workspace_bytes).  Does not touch the memory; call treekv_reset next. */
 int treekv_bind_workspace(treekv_ctx* ctx, void* dev_ptr, size_t bytes);
 
-/* Algorithm 1, line 1: empty cache, idx at the first scope, position counter 0. */
+/* Algorithm 1, initialisation: empty cache, idx at the first scope, position counter 0. */
 int treekv_reset(treekv_ctx* ctx, void* stream);
 
 /*
- * treekv_decode_step - one iteration of Algorithm 1's loop (lines 4-17) for every
- * (batch, KV head), without the projections of line 3.
+ * treekv_decode_step - one iteration of Algorithm 1's loop (append to index advance) for every
+ * (batch, KV head), without the projections that open the loop.
  *   q [B, H, d], k [B, Hkv, d], v [B, Hkv, d]   storage dtype, read only
  *   out        [B, H, d] float32: o = SoftMax(q K^T * scale) V over the cache
  *              including the new token, computed before the eviction
@@ -170,7 +170,7 @@ int treekv_decode_step_static(treekv_ctx* ctx, const void* q, const void* k, con
  * Row i attends the cache as it was before the call plus the chunk's tokens
  * 0..i (causal inside the chunk).  All rows' probabilities are added to the
  * scores and counts; the averaged scores are then frozen and Algorithm 1's
- * append / compare / evict / advance (lines 4-5, 9-17) is replayed for the
+ * append / compare / evict / advance is replayed for the
  * chunk's tokens in order.  len = 1 is exactly treekv_decode_step.
  *   Q [B, len, H, d], K [B, len, Hkv, d], V [B, len, Hkv, d]   storage dtype
  *   out        [B, len, H, d] float32
@@ -190,9 +190,9 @@ int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const vo
  * treekv_prefill_prompt - the paper's own prefilling stage (Section 4.2): a whole prompt of `len` tokens is
  * compressed in one shot, block by block.  The prompt is cut into blocks of `block` tokens; the queries of
  * its last block (the observation window) attend the entire prompt causally; a token's importance is its
- * attention weight averaged over the window queries that see it (S / C of Algorithm 1, lines 7-8 and 10,
+ * attention weight averaged over the window queries that see it (S / C of Algorithm 1,
  * for those queries; the G query heads of a KV head add up); a block's importance is the mean over its
- * tokens; Algorithm 1's append / compare / evict / advance (lines 4-5, 9-17) then runs with blocks in the
+ * tokens; Algorithm 1's append / compare / evict / advance then runs with blocks in the
  * place of tokens and these scores frozen: budget / block blocks are kept, ceil(n_sink / block) leading
  * and ceil(n_recent / block) trailing blocks are never evicted.  The call REPLACES the context's state
  * (the context must have been reset once since its workspace was bound).  Afterwards the cache holds
@@ -217,8 +217,8 @@ int treekv_prefill_prompt(treekv_ctx* ctx, const void* Qw, const void* K, const 
                           float* token_scores, void* stream);
 
 /*
- * treekv_scores - accumulated attention weights S (Algorithm 1, line 8) of the
- * retained tokens, in the order of `retained`; the count C of line 7 is
+ * treekv_scores - accumulated attention weights S (Algorithm 1's score update) of the
+ * retained tokens, in the order of `retained`; the count C is
  * t - position + 1 with t the last processed position, so Sbar = S / C.
  *   scores [B, Hkv, c] float32, padded with 0.
  */
@@ -250,7 +250,7 @@ int treekv_wavelet_components(const float* a, const void* V, int dtype, int head
                               float* per_head, float* mean, void* stream);
 
 /*
- * Snapshots: Algorithm 1's state (line 1: S, C, K, V, idx; C is t - position) of every (batch, KV head) unit,
+ * Snapshots: Algorithm 1's state (S, C, K, V, idx; C is t - position) of every (batch, KV head) unit,
  * in position order, independent of how the workspace lays the cache out.  A snapshot is one device buffer of
  * treekv_state_bytes(ctx) bytes, 256-byte aligned, holding six arrays at the byte offsets treekv_get_state_layout
  * reports (U = B * Hkv units, c = budget):
@@ -259,7 +259,7 @@ int treekv_wavelet_components(const float* a, const void* V, int dtype, int head
  *   slots     [U][c] int32   the cache row each token sits in (0 .. c); -1 past n.  Restoring rows to the same
  *                            slots makes the steps after an import repeat bit for bit what followed the export.
  *                            A snapshot built by hand may set slots[u][0] = -1: token i then takes row i.
- *   S         [U][c] float32 accumulated attention weight of each kept token (Algorithm 1, line 8); 0 past n
+ *   S         [U][c] float32 accumulated attention weight of each kept token (Algorithm 1's S); 0 past n
  *   K, V      [U][c][d]      storage dtype; the kept tokens' rows, zero past n
  */
 typedef struct treekv_state_layout {

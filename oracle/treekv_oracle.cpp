@@ -7,18 +7,18 @@
 // no code, header, table or helper with the HIP library.
 //
 // What it follows, step by step (Algorithm 1, one loop iteration):
-//   K, V grow by the new row                                   (lines 4-5)
-//   a = SoftMax(q K^T * scale) over the whole cache, o = a V   (line 6, Sec. 3.1)
-//   C = (C u {0}) + 1,  S = (S u {0}) + a                      (lines 7-8)
+//   K, V grow by the new row                                   (the append step)
+//   a = SoftMax(q K^T * scale) over the whole cache, o = a V   (the attention step, Sec. 3.1)
+//   C = (C u {0}) + 1,  S = (S u {0}) + a                      (the C and S updates)
 //   if length > c:  Sbar = S / C; compare Sbar[idx], Sbar[idx+1];
 //                   evict idx+1 if Sbar[idx] > Sbar[idx+1], else evict idx;
-//                   advance idx                                (lines 9-17)
+//                   advance idx                                (the eviction block)
 // Eviction is a std::vector erase on every per-token array; nothing is blocked,
 // fused or reordered.
 //
 // Readings of the paper taken here (each also listed in the design notes):
 //  * idx advance.  The printed update "(idx+1) mod c + 1" skips every other
-//    scope, contradicting Section 4.1 ("idx cycles through 1, 2, 3, and 4").
+//    scope, contradicting Section 4.1, whose example has idx take 1, 2, 3, 4 in turn.
 //    Default: idx <- (idx mod m) + 1.  The printed form is kept behind
 //    TKO_IDX_LITERAL.
 //  * Layout.  Section 5.2 keeps 4 initial and 508 recent tokens next to 512
@@ -32,7 +32,7 @@
 //  * Ablation of Section 5.4 (always keep the left token): TKO_KEEP_LEFT.
 //  * Importance criterion.  Section 4.1 names the averaged attention weight Sbar = S / C as the
 //    criterion of choice and mentions that accumulated weights were tried too: with
-//    TKO_SCORE_ACCUMULATED line 10 is skipped and lines 11-15 compare S itself.  (In the
+//    TKO_SCORE_ACCUMULATED the averaging step is skipped and the comparison is on S itself.  (In the
 //    one-shot prompt compression a token's importance is then its summed, not averaged, window
 //    attention, and S is handed over as it is.)
 //  * Chunked prefill (not in the paper, whose prefill works on blocks with an
@@ -48,7 +48,7 @@
 //    whole prompt causally; a token's importance is its attention averaged over the window
 //    queries that see it (S / C of Algorithm 1 restricted to those queries, summed over the
 //    group's heads); a block's importance is the mean over its b tokens; Algorithm 1
-//    (lines 4-5, 9-17) then runs with blocks in the place of tokens, the block scores frozen,
+//    (append, then the eviction block) then runs with blocks in the place of tokens, the block scores frozen,
 //    a capacity of c / b blocks and ceil(n_sink / b) sink and ceil(n_recent / b) recent
 //    blocks.  The paper does not say how decoding takes over; here the kept tokens keep their
 //    window average as Sbar: C becomes the number of prompt queries since the token arrived
@@ -57,7 +57,7 @@
 //    stream holds keys WITHOUT positional encoding; at every step the cached tokens, in cache
 //    order and including the new one, are given the positions 0, 1, .., n-1 (the paper's
 //    example: tokens {0,1,2,3,7,8,9} and the 10th get {0,..,7}), and the rotary encoding of
-//    those positions is applied to the keys and (position n-1) to the query before line 6.
+//    those positions is applied to the keys and (position n-1) to the query before the attention step.
 //    The rotary encoding is the one of its defining paper (RoFormer, eq. 15/34): dimensions
 //    (2i, 2i+1) form a plane rotated by position * base^(-2i/d), base 10000 unless set.  The
 //    paper does not say which flavour its models use; a model that pairs (i, i + d/2) instead
@@ -75,7 +75,7 @@
 //    reconstructions, the first with a zero approximation, the others with zero details.
 //    Positions and coefficients are counted from 1 as in the printed reconstruction formula, so
 //    coefficient n belongs to the signal pair (2n-1, 2n).  "Magnitude" is |Rec(D_l)[n]| averaged
-//    over the d columns (the paper averages "across all layers, heads, and samples"; the columns
+//    over the d columns (the paper averages over layers, heads and samples; the columns
 //    are averaged too, the figure showing one curve per level).  The sequence length must be a
 //    multiple of 2^L (the paper's 512 with L = 5 is; it says nothing about other lengths).
 //
@@ -103,7 +103,7 @@ struct Stream {
   double scale = 1.0;
   double rope_base = 10000.0;
   long long t = 0;  // tokens processed so far == position of the next token
-  int idx = 1;      // the paper's 1-based idx (Algorithm 1, line 1)
+  int idx = 1;      // the paper's 1-based idx (Algorithm 1, initialisation)
   std::vector<std::vector<double>> K, V;  // one row per cached token
   std::vector<double> S;                  // accumulated attention weight
   std::vector<long long> C;               // number of queries that attended the token
@@ -162,7 +162,7 @@ std::vector<double> haar_reconstruct(const std::vector<double>& A, const std::ve
   return out;
 }
 
-// Lines 9-17 of Algorithm 1 on a list of token handles `order` whose scores are sbar[handle].
+// The eviction block of Algorithm 1 on a list of token handles `order` whose scores are sbar[handle].
 // Returns the index (into `order`) that is to be erased, or -1 when length <= c.
 int choose_eviction(Stream& s, const std::vector<int>& order, const std::vector<double>& sbar,
                     const std::vector<long long>& pos_of, long long forced_pos, double follow_thresh,
@@ -243,14 +243,14 @@ void tko_decode_step(void* h, const double* q, const double* k, const double* v,
                      long long* result, double* margin) {
   Stream& s = *static_cast<Stream*>(h);
   const Stream backup = commit ? Stream() : s;
-  // lines 4-5, and the "u {0}" of lines 7-8
+  // the append step, and the "u {0}" of the C and S updates
   s.K.emplace_back(k, k + s.d);
   s.V.emplace_back(v, v + s.d);
   s.S.push_back(0.0);
   s.C.push_back(0);
   s.pos.push_back(s.t);
   const size_t n = s.K.size();
-  // line 6 and o = a V, once per query head of the group
+  // the attention step and o = a V, once per query head of the group
   // with position re-assignment: the token at cache index j is at position j, the query at n - 1
   const bool rerank = (s.flags & TKO_POSITION_RERANK) != 0;
   std::vector<std::vector<double>> Kpos;
@@ -274,9 +274,9 @@ void tko_decode_step(void* h, const double* q, const double* k, const double* v,
     }
     for (size_t j = 0; j < n; ++j) asum[j] += a[j];
   }
-  // lines 7-8
+  // C and S updates
   for (size_t j = 0; j < n; ++j) { s.C[j] += 1; s.S[j] += asum[j]; }
-  // lines 9-17
+  // the eviction block
   Decision dec;
   std::vector<int> order(n);
   std::vector<double> sbar(n);
@@ -367,7 +367,7 @@ int tko_prefill_chunk(void* h, const double* Q, const double* K, const double* V
     }
     for (size_t j = 0; j < vis; ++j) { s.C[j] += 1; s.S[j] += asum[j]; }
   }
-  // frozen scores, then the replay of lines 4-5 and 9-17 token by token
+  // frozen scores, then the replay of the append step and the eviction block token by token
   const bool accumulated = (s.flags & TKO_SCORE_ACCUMULATED) != 0;
   std::vector<double> sbar(n);
   for (size_t j = 0; j < n; ++j) sbar[j] = accumulated ? s.S[j] : s.S[j] / (double)s.C[j];
@@ -419,7 +419,7 @@ int tko_prefill_prompt(void* h, const double* Qw, const double* K, const double*
   blk.m = blk.c - blk.n_sink - blk.n_recent;
   blk.flags = s.flags;
   if (blk.m < 1) return -1;
-  // the observation window queries the entire sequence (causally); lines 6-8 for those queries only
+  // the observation window queries the entire sequence (causally); attention, C and S updates for those queries only
   std::vector<double> Ssum((size_t)T, 0.0), logits((size_t)T), a((size_t)T);
   std::vector<long long> Cnt((size_t)T, 0);
   // with position re-assignment the keys carry no positional encoding: key j is at position j here
@@ -449,7 +449,7 @@ int tko_prefill_prompt(void* h, const double* Qw, const double* K, const double*
     }
     for (size_t j = 0; j < vis; ++j) Cnt[j] += 1;
   }
-  // line 10 per token, then the block's score: the average over its b tokens
+  // the average S / C per token, then the block's score: the average over its b tokens
   std::vector<double> sbar((size_t)T), beta((size_t)N);
   const bool accumulated = (s.flags & TKO_SCORE_ACCUMULATED) != 0;
   for (int j = 0; j < T; ++j) sbar[j] = accumulated ? Ssum[j] : Ssum[j] / (double)Cnt[j];
@@ -460,7 +460,7 @@ int tko_prefill_prompt(void* h, const double* Qw, const double* K, const double*
   }
   if (token_sbar) for (int j = 0; j < T; ++j) token_sbar[j] = sbar[j];
   if (block_score) for (int k = 0; k < N; ++k) block_score[k] = beta[k];
-  // Algorithm 1, lines 4-5 and 9-17, one block at a time
+  // Algorithm 1's append step and eviction block, one block at a time
   std::vector<long long> block_id((size_t)N);
   for (int k = 0; k < N; ++k) block_id[k] = k;
   std::vector<int> order;

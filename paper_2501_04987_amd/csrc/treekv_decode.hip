@@ -1,4 +1,4 @@
-// Decode step of TreeKV for gfx950: Algorithm 1, lines 4-17, for every (batch, KV head) unit.
+// Decode step of TreeKV for gfx950: one iteration of Algorithm 1's loop after the projections, for every (batch, KV head) unit.
 // HBM-bound: per unit it must read every K and V row once (Section 3.1).
 //
 // Two launch shapes share the streaming code and the epilogue:
@@ -638,7 +638,7 @@ __device__ inline void merge_stats(const float* pm, const float* pl, int nparts,
 }
 
 // ---------------------------------------------------------------------------------------------
-// Epilogue shared by both shapes: lines 7-8 (score update), lines 9-17 (eviction), the retained
+// Epilogue shared by both shapes: Algorithm 1's score update and eviction block, the retained
 // list, and the append of the new row.  `logit(g, slot)` returns the scaled logit; M, invL per g.
 // EP > 0: the first EP old scores per thread come in registers, and the caller has already written
 // the retained list except for the one entry this step's decision fills in.

@@ -2,7 +2,7 @@
 //
 // A chunk of L tokens attends the cache as it was before the chunk plus the chunk's own tokens
 // up to and including itself; every row's probabilities are added to the scores; the averaged
-// scores are then frozen and Algorithm 1's append / compare / evict / advance (lines 4-5, 9-17)
+// scores are then frozen and Algorithm 1's append / compare / evict / advance
 // is replayed for the L tokens.  L = 1 gives the decode step.
 //
 // Two launches per chunk:
@@ -13,7 +13,7 @@
 //            workgroup's rows.  Writes O; the column sums go, as 64-bit fixed point, into one accumulator
 //            per column of the unit with integer atomic adds (which commute exactly: whatever order the
 //            workgroups arrive in, the sum is the same to the bit).
-//   replay   grid U.  Adds the accumulated column sums to the scores (Algorithm 1, line 8) and clears the
+//   replay   grid U.  Adds the accumulated column sums to the scores (Algorithm 1's S update) and clears the
 //            accumulators, then Algorithm 1's eviction for the chunk's tokens with frozen scores.  Inside one
 //            sweep of idx over the tree region the scopes are disjoint pairs, so a sweep is one
 //            parallel pass; sweeps run one after the other.  Then surviving chunk tokens are
@@ -159,7 +159,7 @@ __device__ inline unsigned lds_address(const void* shared_ptr) {
 //
 // Sweep 2 recomputes the logits and, knowing the statistics, forms the normalised probabilities
 // directly: p = exp2(s*scale - max - log2(sum)), no running maximum and nothing to rescale.  They feed
-// O^T += V^T P^T and, summed down the rows, the per-column score increments (Algorithm 1, line 8).
+// O^T += V^T P^T and, summed down the rows, the per-column score increments (Algorithm 1's S update).
 // The 8 waves are 2 row groups (32 rows = two 16-row MFMA blocks) x 4 column quarters (32 columns of
 // every tile).  S^T comes out of the MFMA with a lane holding 8 columns of one row, which is the B
 // operand layout of P^T, so P never leaves the registers; it is split into two bf16 halves (hi + lo) so that
@@ -1037,7 +1037,7 @@ __global__ __launch_bounds__(RP_THREADS) void prefill_replay_kernel(Params p, in
     for (int i = tid; i < r; i += RP_THREADS) Ru[i] = Rg[i];
   }
 
-  // ---- Algorithm 1, line 8 for the whole chunk: add the column sums the attend kernel left in the accumulators ----
+  // ---- Algorithm 1's S update for the whole chunk: add the column sums the attend kernel left in the accumulators ----
   {
     // every accumulator that is read is also cleared for the next chunk (the others only ever received zeros)
     auto cache_col = [&](int x, float v, unsigned long long a) {

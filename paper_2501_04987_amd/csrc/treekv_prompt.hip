@@ -3,8 +3,8 @@
 // The prompt is cut into blocks of b tokens.  The queries of the last block (the observation window)
 // attend the whole prompt causally; a token's importance is its attention weight averaged over the
 // window queries that see it (Algorithm 1's S / C restricted to those queries, summed over the query
-// heads of the group); a block's importance is the mean over its b tokens; Algorithm 1 (lines 4-5,
-// 9-17) then runs with blocks in the place of tokens and the block scores frozen.  The kept blocks'
+// heads of the group); a block's importance is the mean over its b tokens; Algorithm 1 (append,
+// then its eviction block) then runs with blocks in the place of tokens and the block scores frozen.  The kept blocks'
 // rows become the cache and decoding takes over from there.
 //
 // Four launches:

@@ -1,6 +1,6 @@
 """GPU: snapshots of a context (treekv_export_state / treekv_import_state), through the C ABI.
 
-A snapshot is Algorithm 1's state (line 1: S, C, K, V, idx) in position order.  Restoring one must make the calls
+A snapshot is Algorithm 1's state (S, C, K, V, idx) in position order.  Restoring one must make the calls
 that follow repeat bit for bit what followed the export; a snapshot built from the oracle's state must let the GPU
 continue in parity with the oracle; a snapshot that describes no reachable state must be refused unit by unit.
 """
