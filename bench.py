@@ -54,11 +54,13 @@ PROMPT_BLOCK = 64
 # WRITE_SIZE 1.0).  These are CONSTANTS taken from the files named beside them, not measurements of this run; they
 # are reported only for the shape and kernels they were taken on.
 PROFILED_TRAFFIC = {
-    "decode": dict(bytes=(132954 * 2 + 4432) * 1024, source="profiles/decode_fused_kernel_hbm_traffic.txt"),
-    "prompt": dict(bytes=((140438 + 140852 + 48 + 16679) * 2 + (128 + 4163 + 4 + 34165)) * 1024,
-                   source="profiles/decode_fused_kernel_hbm_traffic.txt"),
-    "wavelet": dict(bytes=int(((532611.5 + 40974.5) * 2 + (81920 + 10)) * 1024),
-                    source="profiles/wavelet_components_kernel_8192_heads.txt"),
+    "decode": dict(bytes=(132960 * 2 + 4424) * 1024, source="profiles/hbm_traffic_counters_bench_kernels.txt"),
+    "prompt": dict(bytes=((140461 + 140860 + 48 + 16680) * 2 + (128 + 4162 + 4 + 34166)) * 1024,
+                   source="profiles/hbm_traffic_counters_bench_kernels.txt"),
+    "prefill": dict(bytes=int(((26547 + 719 + 4204) * 2 + (13184 + 1669 + 8192)) * 1024),
+                    source="profiles/hbm_traffic_counters_bench_kernels.txt"),
+    "wavelet": dict(bytes=int(((532612 + 40974.5) * 2 + (81920 + 10)) * 1024),
+                    source="profiles/hbm_traffic_counters_bench_kernels.txt"),
 }
 
 
@@ -292,8 +294,10 @@ def prefill_flops_per_chunk(c, L=PREFILL_CHUNK, d=HEAD_DIM, heads=32):
     return 2 * 2 * L * (c + (L + 1) / 2) * d * heads
 
 
-def bench_prefill(torch, binding, inputs, dev, peaks, chunks=24, warm=6, layers=4, c=2048, H=32, flags=0):
-    """Chunks of 512 tokens into full 2048-slot caches, 32 heads x 128, batch 1, cycling over a few layers."""
+def bench_prefill(torch, binding, inputs, dev, peaks, chunks=64, warm=64, layers=4, c=2048, H=32, flags=0):
+    """Chunks of 512 tokens into full 2048-slot caches, 32 heads x 128, batch 1, cycling over a few layers: one
+    32768-token prompt's worth of chunks to warm up (a few milliseconds of work, so that the clocks have settled when
+    this runs on its own), then another one timed."""
     kvs = [binding.TreeKV(c, H, HEAD_DIM, max_chunk=PREFILL_CHUNK, flags=flags) for _ in range(layers)]
     n_in = 8
     q, k, v = inputs.device_lowrank(11, n_in * PREFILL_CHUNK, 1, H, 1, HEAD_DIM, device=dev)
@@ -322,13 +326,17 @@ def bench_prefill(torch, binding, inputs, dev, peaks, chunks=24, warm=6, layers=
     assert int(ev.min()) >= 0, "every token of a chunk into a full cache evicts one"
     flops = prefill_flops_per_chunk(c, heads=H)
     tf = flops / (us * 1e-6) / 1e12
+    extra = {}
+    if not flags:
+        extra = dict(traffic=PROFILED_TRAFFIC["prefill"]["bytes"],
+                     traffic_source=PROFILED_TRAFFIC["prefill"]["source"] + " (a constant from that file, not measured in this run)")
     return {"workload": "configs[3] shape: 512-token chunk into a full 2048-slot cache, 32 heads x 128 dim, bf16, batch 1"
                         + (", positions re-assigned" if flags else ""),
             "chunks": chunks, "us_per_chunk": us, "prompt_tokens_per_s": PREFILL_CHUNK / (us * 1e-6),
             "roofline": roofline("mfma", tf, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", peaks and peaks["mfma_bf16_TFLOPs"],
                                  flops_per_chunk=flops,
                                  note="algorithmic flops (Q.K^T and P.V once each) over the whole chunk call: every "
-                                      "kernel of treekv_prefill_chunk, launch gaps included")}
+                                      "kernel of treekv_prefill_chunk, launch gaps included", **extra)}
 
 
 def prompt_bytes_per_call(T, c, d=HEAD_DIM, heads=32, block=PROMPT_BLOCK):
