@@ -212,9 +212,20 @@ def bench_decode(torch, binding, inputs, dev, wl, steps, warmup, rerank=False):
     assert int(nret.min()) == c and int(ev.min()) >= 0, "every unit must evict once per step"
     launch_us = dev_ms * 1e3 / (steps * L)
     bytes_per_launch = algorithmic_bytes_per_unit(c, G) * B * Hkv
+    # the same call one at a time: events around a single ABI call, the stream idle before and after it
+    singles = []
+    for i in range(min(64, steps * L)):
+        t, l = warmup + i // L, i % L
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        layers[l].decode_step(q[t, l], k[t, l], v[t, l], out[l], ret[l], nret[l], ev[l])
+        b_.record(stream)
+        torch.cuda.synchronize()
+        singles.append(a.elapsed_time(b_) * 1e3)
+    singles.sort()
     return dict(total_s=total_s, ms_per_step=total_s * 1e3 / steps, steps_per_s=steps / total_s, launch_us=launch_us,
                 bytes_per_launch=bytes_per_launch, achieved_GBs=bytes_per_launch / (launch_us * 1e-6) / 1e9,
-                kv_splits=int(cfg.kv_splits))
+                kv_splits=int(cfg.kv_splits), single_call_us=singles[len(singles) // 2])
 
 
 def side_shape(torch, binding, inputs, dev, name, peaks, rerank=False, steps=40, warmup=5):
@@ -294,19 +305,19 @@ def prefill_flops_per_chunk(c, L=PREFILL_CHUNK, d=HEAD_DIM, heads=32):
     return 2 * 2 * L * (c + (L + 1) / 2) * d * heads
 
 
-def bench_prefill(torch, binding, inputs, dev, peaks, chunks=64, warm=64, layers=4, c=2048, H=32, flags=0):
+def bench_prefill(torch, binding, inputs, dev, peaks, chunks=64, warm=64, layers=4, c=2048, H=32, flags=0, B=1):
     """Chunks of 512 tokens into full 2048-slot caches, 32 heads x 128, batch 1, cycling over a few layers: one
     32768-token prompt's worth of chunks to warm up (a few milliseconds of work, so that the clocks have settled when
     this runs on its own), then another one timed."""
-    kvs = [binding.TreeKV(c, H, HEAD_DIM, max_chunk=PREFILL_CHUNK, flags=flags) for _ in range(layers)]
+    kvs = [binding.TreeKV(c, H, HEAD_DIM, batch=B, max_chunk=PREFILL_CHUNK, flags=flags) for _ in range(layers)]
     n_in = 8
-    q, k, v = inputs.device_lowrank(11, n_in * PREFILL_CHUNK, 1, H, 1, HEAD_DIM, device=dev)
-    mk = lambda x: x.view(n_in, PREFILL_CHUNK, 1, H, HEAD_DIM).permute(0, 2, 1, 3, 4).contiguous()   # [n,B,L,H,d]
+    q, k, v = inputs.device_lowrank(11, n_in * PREFILL_CHUNK, B, H, 1, HEAD_DIM, device=dev)
+    mk = lambda x: x.view(n_in, PREFILL_CHUNK, B, H, HEAD_DIM).permute(0, 2, 1, 3, 4).contiguous()   # [n,B,L,H,d]
     q, k, v = mk(q), mk(k), mk(v)
-    out = torch.empty(1, PREFILL_CHUNK, H, HEAD_DIM, dtype=torch.float32, device=dev)
-    ret = torch.empty(layers, 1, H, c, dtype=torch.int32, device=dev)
-    nret = torch.empty(layers, 1, H, dtype=torch.int32, device=dev)
-    ev = torch.empty(1, H, PREFILL_CHUNK, dtype=torch.int32, device=dev)
+    out = torch.empty(B, PREFILL_CHUNK, H, HEAD_DIM, dtype=torch.float32, device=dev)
+    ret = torch.empty(layers, B, H, c, dtype=torch.int32, device=dev)
+    nret = torch.empty(layers, B, H, dtype=torch.int32, device=dev)
+    ev = torch.empty(B, H, PREFILL_CHUNK, dtype=torch.int32, device=dev)
 
     def run(i):
         l = i % layers
@@ -324,15 +335,15 @@ def bench_prefill(torch, binding, inputs, dev, peaks, chunks=64, warm=64, layers
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / chunks
     assert int(ev.min()) >= 0, "every token of a chunk into a full cache evicts one"
-    flops = prefill_flops_per_chunk(c, heads=H)
+    flops = prefill_flops_per_chunk(c, heads=H) * B
     tf = flops / (us * 1e-6) / 1e12
     extra = {}
-    if not flags:
+    if not flags and B == 1:
         extra = dict(traffic=PROFILED_TRAFFIC["prefill"]["bytes"],
                      traffic_source=PROFILED_TRAFFIC["prefill"]["source"] + " (a constant from that file, not measured in this run)")
-    return {"workload": "configs[3] shape: 512-token chunk into a full 2048-slot cache, 32 heads x 128 dim, bf16, batch 1"
+    return {"workload": f"configs[3] shape: 512-token chunk into a full 2048-slot cache, 32 heads x 128 dim, bf16, batch {B}"
                         + (", positions re-assigned" if flags else ""),
-            "chunks": chunks, "us_per_chunk": us, "prompt_tokens_per_s": PREFILL_CHUNK / (us * 1e-6),
+            "chunks": chunks, "us_per_chunk": us, "prompt_tokens_per_s": B * PREFILL_CHUNK / (us * 1e-6),
             "roofline": roofline("mfma", tf, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", peaks and peaks["mfma_bf16_TFLOPs"],
                                  flops_per_chunk=flops,
                                  note="algorithmic flops (Q.K^T and P.V once each) over the whole chunk call: every "
@@ -432,7 +443,7 @@ def main():
     ap.add_argument("--rerank", action="store_true",
                     help="decode (and compress the prompt) with positions re-assigned to cache ranks; a side measurement")
     ap.add_argument("--peaks", action="store_true", help="run only the probe kernels and print their rates")
-    ap.add_argument("--only", choices=["prefill", "prompt", "wavelet"],
+    ap.add_argument("--only", choices=["prefill", "prefill_batch8", "prompt", "wavelet"],
                     help="run only that object of the default line (for profiling one call's kernels)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -454,6 +465,8 @@ def main():
     if args.only:
         flags = binding.TREEKV_POSITION_RERANK if args.rerank else 0
         obj = (bench_prefill(torch, binding, inputs, dev, None, flags=flags) if args.only == "prefill" else
+               bench_prefill(torch, binding, inputs, dev, None, chunks=16, warm=8, layers=2, B=8, flags=flags)
+               if args.only == "prefill_batch8" else
                bench_prompt(torch, binding, inputs, dev, None, flags=flags) if args.only == "prompt" else
                bench_wavelet(torch, binding, dev, None))
         print(json.dumps({args.only: obj}))
@@ -467,9 +480,11 @@ def main():
     peaks = measure_peaks(torch, binding, dev)
     roof = roofline("hbm", r["achieved_GBs"], HBM_PEAK_GBS, "GB/s", peaks["hbm_read_GBs"],
                     kernel="decode_fused_kernel<bf16,128,1>" if r["kv_splits"] == 1 else "decode_split_kernel + decode_merge_kernel",
-                    bytes_per_launch=r["bytes_per_launch"], launch_us=r["launch_us"],
-                    note="launch_us = HIP-event time of the timed region / number of layer launches (gaps between "
-                         "launches included); frac is against the published 8 TB/s, frac_of_measured against "
+                    bytes_per_launch=r["bytes_per_launch"], launch_us=r["launch_us"], single_call_us=r["single_call_us"],
+                    note="launch_us = HIP-event time of the timed region / number of layer launches, calls enqueued back "
+                         "to back (gaps between launches included): achieved and frac refer to it; single_call_us = "
+                         "median HIP-event time around one call with the stream idle before and after (not what frac "
+                         "uses); frac is against the published 8 TB/s, frac_of_measured against "
                          "measured_peaks.hbm_read_GBs of this run")
     if headline:
         roof["traffic"] = PROFILED_TRAFFIC["decode"]["bytes"]
@@ -494,6 +509,8 @@ def main():
         res["prefill"] = bench_prefill(torch, binding, inputs, dev, peaks)
         torch.cuda.empty_cache()
         res["prompt"] = bench_prompt(torch, binding, inputs, dev, peaks)
+        torch.cuda.empty_cache()
+        res["prefill_batch8"] = bench_prefill(torch, binding, inputs, dev, peaks, chunks=16, warm=8, layers=2, B=8)
         torch.cuda.empty_cache()
         res["wavelet"] = bench_wavelet(torch, binding, dev, peaks)
         torch.cuda.empty_cache()
