@@ -52,7 +52,7 @@ typedef enum treekv_status {
 
 enum { TREEKV_BF16 = 0, TREEKV_F32 = 1 };      /* storage type of q, k, v and of the cache */
 /* The index update Algorithm 1 prints as its last step, idx = (idx+1) mod c + 1, visits every other scope only
- * and contradicts Section 4.1 (idx "cycles through 1, 2, 3, and 4"); this library advances idx by one,
+ * and contradicts Section 4.1 (whose example has idx take 1, 2, 3, 4 in turn); this library advances idx by one,
  * idx = (idx mod m) + 1, and has no flag for the printed form. */
 enum {
   TREEKV_KEEP_LEFT = 1,          /* flags: ablation of Section 5.4 (always keep the left slot of the scope,
