@@ -178,9 +178,8 @@ int treekv_decode_step_static(treekv_ctx* ctx, const void* q, const void* k, con
  *   evicted    [B, Hkv, len] int32 (may be NULL): position evicted when the
  *              chunk's i-th token was appended, or -1
  * With bf16 storage the two contractions run on the matrix pipe; with fp32 storage
- * they run, row by row, on the vector ALUs (held to 1e-5, not a fast path), and
- * TREEKV_POSITION_RERANK is then not available (TREEKV_EUNSUPPORTED), nor are more than
- * 10240 visible columns (budget + 1 + len).
+ * they run, row by row, on the vector ALUs (held to 1e-5, not a fast path), for at most
+ * 10240 visible columns (budget + 1 + len; TREEKV_EUNSUPPORTED beyond).
  */
 int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const void* V, int len,
                          void* out, int32_t* retained, int32_t* n_retained, int32_t* evicted,
@@ -207,7 +206,7 @@ int treekv_prefill_chunk(treekv_ctx* ctx, const void* Q, const void* K, const vo
  *              appended, or -1
  *   token_scores [B, Hkv, len] float32 (may be NULL): the tokens' averaged window attention
  * With fp32 storage the window's scores are computed on the vector ALUs, one window query at a time (not a
- * fast path), without TREEKV_POSITION_RERANK and for len <= 32768.
+ * fast path), for len <= 32768.
  * Errors: TREEKV_EINVAL unless 1 <= block <= len <= max_prompt, block divides len and budget, and
  * budget / block - ceil(n_sink / block) - ceil(n_recent / block) >= 1; TREEKV_EUNSUPPORTED if
  * block * G > 128, or with fp32 storage as said above.

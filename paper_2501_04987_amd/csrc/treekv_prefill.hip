@@ -749,7 +749,9 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
 constexpr int F32_THREADS = 256;
 constexpr int F32_ROWS = 16;
 
-template <int D>
+// ROPE (positions re-assigned to cache ranks): queries and keys are read, already turned to their ranks, from the scratch
+// prefill_turn_f32_kernel fills (the same memory the bf16 path keeps its two-part copies in).
+template <int D, bool ROPE>
 __global__ __launch_bounds__(F32_THREADS) void prefill_attend_f32_kernel(Params p, const float* __restrict__ Q,
                                                                          const float* __restrict__ Kc,
                                                                          const float* __restrict__ Vc, int L,
@@ -766,11 +768,16 @@ __global__ __launch_bounds__(F32_THREADS) void prefill_attend_f32_kernel(Params 
   float* sp = f32_smem;                            // [ncols] scaled logits, then probabilities
   float* sred = sp + ncols;                        // [F32_THREADS] reductions, then [KPP][D] output stripes
   float* sq = sred + (KPP * D > F32_THREADS ? KPP * D : F32_THREADS);    // [D] the query row
-  const float* Ku = (const float*)p.K + (size_t)unit * p.cap * D;
+  const size_t krot_rows = (size_t)p.cap + p.max_chunk;          // turned keys: [U][cap + max_chunk][D] fp32
+  const float* Ku = ROPE ? reinterpret_cast<const float*>(p.pf_krot) + (size_t)unit * krot_rows * D
+                         : (const float*)p.K + (size_t)unit * p.cap * D;
   const float* Vu = (const float*)p.V + (size_t)unit * p.cap * D;
-  const float* Kcu = Kc + ((size_t)b * L * p.Hkv + kvh) * D;
+  const float* Kcu = ROPE ? Ku + (size_t)p.cap * D : Kc + ((size_t)b * L * p.Hkv + kvh) * D;
   const float* Vcu = Vc + ((size_t)b * L * p.Hkv + kvh) * D;
   const size_t cstride = (size_t)p.Hkv * D;
+  const size_t kcstride = ROPE ? (size_t)D : cstride;
+  const float* Qsrc = ROPE ? reinterpret_cast<const float*>(p.pf_qrot) : Q;   // turned queries: [B][max_chunk][H][D] fp32
+  const int q_rows = ROPE ? p.max_chunk : L;
   const int grp = tid / LPR, piece = tid % LPR;
   constexpr int OWN = 40;                          // columns a thread owns: ncols <= OWN * F32_THREADS (checked by the host)
   float csum[OWN];
@@ -793,7 +800,7 @@ __global__ __launch_bounds__(F32_THREADS) void prefill_attend_f32_kernel(Params 
   };
   for (int i = r0; i < r1; ++i) {
     const int nvis = ncache + i + 1;
-    if (tid < D) sq[tid] = Q[(((size_t)b * L + i) * p.H + h) * D + tid];
+    if (tid < D) sq[tid] = Qsrc[(((size_t)b * q_rows + i) * p.H + h) * D + tid];
     __syncthreads();
     const float4 qv = *reinterpret_cast<const float4*>(sq + piece * 4);
     // logits
@@ -801,7 +808,7 @@ __global__ __launch_bounds__(F32_THREADS) void prefill_attend_f32_kernel(Params 
       const int j = j0 + grp;
       float acc = 0.f;
       if (j < nvis) {
-        const float* row = j < ncache ? Ku + (size_t)j * D : Kcu + (size_t)(j - ncache) * cstride;
+        const float* row = j < ncache ? Ku + (size_t)j * D : Kcu + (size_t)(j - ncache) * kcstride;
         const float4 kv = *reinterpret_cast<const float4*>(row + piece * 4);
         acc = kv.x * qv.x;
         acc = fmaf(kv.y, qv.y, acc);
@@ -1284,16 +1291,68 @@ int launch_prefill_d(const Params& p, const void* Q, const void* K, const void* 
   return launch_replay(p, K, V, L, retained, n_retained, evicted, s);
 }
 
-// fp32 storage: the vector-arithmetic attend (no position re-assignment there), then the same replay.
+// The same for fp32 storage: one thread turns 4 dimensions (2 planes) of one row and stores them as fp32; the keys go
+// to [U][cap + max_chunk][D] (cache rows at their slot, the chunk's behind them), the queries to [B][max_chunk][H][D].
+template <int D>
+__global__ __launch_bounds__(256) void prefill_turn_f32_kernel(Params p, const float* __restrict__ Q,
+                                                               const float* __restrict__ Kc, int L) {
+  constexpr int PARTS = D / 4;
+  const int unit = blockIdx.y, kvh = unit % p.Hkv, b = unit / p.Hkv;
+  const int* meta = p.meta + (size_t)unit * META_STRIDE;
+  const int n0 = meta[META_N], j = meta[META_J], rhead = meta[META_RHEAD];
+  const int rows = n0 + L + L * p.G;
+  const int x = blockIdx.x * 256 + threadIdx.x;
+  const int row = x / PARTS, part = x % PARTS;
+  if (row >= rows) return;
+  const size_t krot_rows = (size_t)p.cap + p.max_chunk;
+  float* kturned = reinterpret_cast<float*>(p.pf_krot) + (size_t)unit * krot_rows * D;
+  const float* src;
+  float* dst;
+  int pos;
+  if (row < n0) {                                   // cached key at logical index `row`
+    const int* Eu = p.E + (size_t)unit * 2 * p.m;
+    const int* Ru = p.R + (size_t)unit * max(p.n_recent, 1);
+    const int slot = n0 < p.budget ? row : logical_to_slot(p, Eu, Ru, rhead, j, row);
+    src = (const float*)p.K + ((size_t)unit * p.cap + slot) * D;
+    dst = kturned + (size_t)slot * D;
+    pos = row;
+  } else if (row < n0 + L) {                        // the chunk's own key i
+    const int i = row - n0;
+    src = Kc + (((size_t)b * L + i) * p.Hkv + kvh) * D;
+    dst = kturned + ((size_t)p.cap + i) * D;
+    pos = row;
+  } else {                                          // query i of head g of the group
+    const int i = (row - n0 - L) / p.G, g = (row - n0 - L) % p.G;
+    const int h = kvh * p.G + g;
+    src = Q + (((size_t)b * L + i) * p.H + h) * D;
+    dst = reinterpret_cast<float*>(p.pf_qrot) + (((size_t)b * p.max_chunk + i) * p.H + h) * D;
+    pos = n0 + i;
+  }
+  const float4 xv = *reinterpret_cast<const float4*>(src + part * 4);
+  const float4 cs = *reinterpret_cast<const float4*>(p.rope_tab + (size_t)pos * (D / 2) + part * 2);   // (cos, sin) x 2 planes
+  float4 y;
+  y.x = xv.x * cs.x - xv.y * cs.y;
+  y.y = xv.x * cs.y + xv.y * cs.x;
+  y.z = xv.z * cs.z - xv.w * cs.w;
+  y.w = xv.z * cs.w + xv.w * cs.z;
+  *reinterpret_cast<float4*>(dst + part * 4) = y;
+}
+
+// fp32 storage: the vector-arithmetic attend, then the same replay.
 template <int D>
 int launch_prefill_f32(const Params& p, const void* Q, const void* K, const void* V, int L, float* out,
                        int32_t* retained, int32_t* n_retained, int32_t* evicted, hipStream_t s) {
-  if (p.flags & TREEKV_POSITION_RERANK) return TREEKV_EUNSUPPORTED;
   const size_t ncols = (size_t)p.cap + L;
   if (ncols > 40 * (size_t)F32_THREADS) return TREEKV_EUNSUPPORTED;      // a thread owns at most 40 columns' sums
   constexpr int KPP = F32_THREADS / (D / 4);
   const size_t lds = (ncols + (KPP * D > F32_THREADS ? KPP * D : F32_THREADS) + D) * sizeof(float);
-  auto attend = prefill_attend_f32_kernel<D>;
+  const bool rope = (p.flags & TREEKV_POSITION_RERANK) != 0;
+  if (rope) {
+    const int rows = p.budget + L + L * p.G;           // at most: every cached key, the chunk's keys and queries
+    hipLaunchKernelGGL(prefill_turn_f32_kernel<D>, dim3((rows * (D / 4) + 255) / 256, p.U), dim3(256), 0, s, p,
+                       (const float*)Q, (const float*)K, L);
+  }
+  auto attend = rope ? prefill_attend_f32_kernel<D, true> : prefill_attend_f32_kernel<D, false>;
   if (lds > 48 * 1024 &&
       hip_failed(hipFuncSetAttribute((const void*)attend, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))
     return TREEKV_EHIP;

@@ -405,7 +405,9 @@ __global__ __launch_bounds__(PP_THREADS) void prompt_scores_kernel(Params p, con
 // storage has no prompt to compress).
 constexpr int PF_THREADS = 256;
 
-template <int D>
+// ROPE (positions re-assigned): key j is turned to position j as it is read, window query i to T - W + i as it is
+// staged, with the (cos, sin) table's rows for those positions.
+template <int D, bool ROPE>
 __global__ __launch_bounds__(PF_THREADS) void prompt_scores_f32_kernel(Params p, const float* __restrict__ Qw,
                                                                        const float* __restrict__ K, int T, int W) {
   constexpr int LPR = D / 4, KPP = PF_THREADS / LPR;
@@ -437,14 +439,28 @@ __global__ __launch_bounds__(PF_THREADS) void prompt_scores_f32_kernel(Params p,
   for (int i = 0; i < W; ++i) {
     const int nvis = T - W + i + 1;                             // window query i sees the keys up to its own
     for (int g = 0; g < p.G; ++g) {
-      if (tid < D) sq[tid] = Qw[(((size_t)b * W + i) * p.H + kvh * p.G + g) * D + tid];
+      if (tid < D) {
+        const float* qrow = Qw + (((size_t)b * W + i) * p.H + kvh * p.G + g) * D;
+        float qx = qrow[tid];
+        if constexpr (ROPE) {
+          const float2 cs = p.rope_tab[(size_t)(T - W + i) * (D / 2) + tid / 2];
+          const float other = qrow[tid ^ 1];
+          qx = (tid & 1) ? other * cs.y + qx * cs.x : qx * cs.x - other * cs.y;
+        }
+        sq[tid] = qx;
+      }
       __syncthreads();
       const float4 qv = *reinterpret_cast<const float4*>(sq + piece * 4);
       for (int j0 = 0; j0 < nvis; j0 += KPP) {
         const int j = j0 + grp;
         float acc = 0.f;
         if (j < nvis) {
-          const float4 kv = *reinterpret_cast<const float4*>(Ku + (size_t)j * kstride + piece * 4);
+          float4 kv = *reinterpret_cast<const float4*>(Ku + (size_t)j * kstride + piece * 4);
+          if constexpr (ROPE) {
+            const float4 cs = *reinterpret_cast<const float4*>(p.rope_tab + (size_t)j * (D / 2) + piece * 2);
+            kv = make_float4(kv.x * cs.x - kv.y * cs.y, kv.x * cs.y + kv.y * cs.x, kv.z * cs.z - kv.w * cs.w,
+                             kv.z * cs.w + kv.w * cs.z);
+          }
           acc = kv.x * qv.x;
           acc = fmaf(kv.y, qv.y, acc);
           acc = fmaf(kv.z, qv.z, acc);
@@ -657,10 +673,12 @@ int launch_prompt(const Params& p, const void* Qw, const void* K, const void* V,
   const int cb = p.budget / b, sink_b = (p.n_sink + b - 1) / b, recent_b = (p.n_recent + b - 1) / b;
   int block_means = 0;
   if (p.dtype == TREEKV_F32) {
-    // fp32 storage: the vector-ALU instance (no position re-assignment there; a query's logits must fit in LDS)
-    if ((p.flags & TREEKV_POSITION_RERANK) || T > 32768) return TREEKV_EUNSUPPORTED;
+    // fp32 storage: the vector-ALU instance (a query's logits must fit in LDS)
+    if (T > 32768) return TREEKV_EUNSUPPORTED;
     const size_t lds = ((size_t)T + PF_THREADS / 64 + p.D) * sizeof(float);
-    auto kern = p.D == 128 ? prompt_scores_f32_kernel<128> : prompt_scores_f32_kernel<64>;
+    const bool rope = (p.flags & TREEKV_POSITION_RERANK) != 0;
+    auto kern = p.D == 128 ? (rope ? prompt_scores_f32_kernel<128, true> : prompt_scores_f32_kernel<128, false>)
+                           : (rope ? prompt_scores_f32_kernel<64, true> : prompt_scores_f32_kernel<64, false>);
     if (lds > 48 * 1024 && hip_failed(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)))
       return TREEKV_EHIP;
     hipLaunchKernelGGL(kern, dim3(p.U), dim3(PF_THREADS), lds, s, p, (const float*)Qw, (const float*)K, T, b);

@@ -103,9 +103,11 @@ def test_prefill_argument_errors(binding):
         kv.prefill_chunk(x, x, x, 65, out, ret, nret, ev)          # longer than max_chunk
     with pytest.raises(binding.TreeKVError):
         kv.prefill_chunk(x, x, x, 0, out, ret, nret, ev)
-    kv32 = binding.TreeKV(32, 2, 64, kv_heads=2, dtype="f32", n_sink=0, n_recent=0, flags=binding.TREEKV_POSITION_RERANK)
+    big = binding.TreeKV(10000, 2, 64, kv_heads=2, dtype="f32", n_sink=0, n_recent=0, max_chunk=512)
+    xf = torch.zeros(1, 512, 2, 64, dtype=torch.float32, device="cuda")
+    outf, retf, nretf, evf = big.new_outputs(512)
     with pytest.raises(binding.TreeKVError) as e:
-        kv32.prefill_chunk(x, x, x, 8, out, ret, nret, ev)         # fp32 storage has no re-assigned positions in a chunk
+        big.prefill_chunk(xf, xf, xf, 512, outf, retf, nretf, evf)  # fp32 storage: more columns than a thread's sums cover
     assert e.value.status == binding.TREEKV_EUNSUPPORTED
 
 

@@ -166,3 +166,19 @@ def test_random_rerank_schedule_of_chunks_and_steps(binding, oracle, seed):
     st = ph.run_schedule(oracle, kv, Q, K, V, sched, dtype="bf16")
     ph.compare_scores(kv, st["results"], "bf16")
     assert st["flagged"] <= max(2, st["decisions"] // 200), (c, st["flagged"])
+
+
+@pytest.mark.parametrize("seed", range(116, 128))
+def test_random_fp32_rerank_schedule_of_chunks_and_steps(binding, oracle, seed):
+    """fp32 storage with positions re-assigned to cache ranks: chunks and decode steps mixed, held to 1e-5."""
+    rng, c = _draw(seed)
+    max_chunk = int(rng.choice([16, 64, 200]))
+    sched, total = _random_schedule(rng, c["budget"], max_chunk)
+    Q, K, V = inputs.batch_streams("iid", seed, total, c["B"], c["Hkv"], c["G"], c["d"], dtype="f32")
+    kv = binding.TreeKV(c["budget"], c["Hkv"] * c["G"], c["d"], kv_heads=c["Hkv"], batch=c["B"], dtype="f32",
+                        n_sink=c["n_sink"], n_recent=c["n_recent"], max_chunk=max_chunk, kv_splits=c["splits"],
+                        flags=binding.TREEKV_POSITION_RERANK, rope_base=float(rng.choice([0.0, 50.0, 500000.0])))
+    st = ph.run_schedule(oracle, kv, Q, K, V, sched, dtype="f32")
+    ph.compare_scores(kv, st["results"], "f32")
+    assert st["flagged"] <= max(2, st["decisions"] // 200), (c, st["flagged"])
+

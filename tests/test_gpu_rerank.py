@@ -91,15 +91,15 @@ def test_rerank_differs_from_plain_and_from_original_positions(binding, oracle):
 
 
 def _chunks(binding, oracle, schedule, *, B, H, Hkv, d, budget, n_sink, n_recent, seed, max_chunk=0, flags=0,
-            rope_base=0.0, units=None):
+            rope_base=0.0, units=None, dtype="bf16"):
     """Prefill chunks (and decode steps, 0) with re-assigned positions: the n0 cached tokens sit at ranks 0..n0-1, chunk
     token i at n0 + i; compared call by call."""
     T = sum(max(L, 1) for L in schedule)
-    Q, K, V = inputs.batch_streams("lowrank", seed, T, B, Hkv, H // Hkv, d, dtype="bf16")
-    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=n_sink, n_recent=n_recent,
+    Q, K, V = inputs.batch_streams("lowrank" if dtype == "bf16" else "iid", seed, T, B, Hkv, H // Hkv, d, dtype=dtype)
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype=dtype, n_sink=n_sink, n_recent=n_recent,
                         max_chunk=max_chunk, flags=flags | binding.TREEKV_POSITION_RERANK, rope_base=rope_base)
-    st = ph.run_schedule(oracle, kv, Q, K, V, schedule, dtype="bf16", units=units)
-    st["score_err"] = ph.compare_scores(kv, st["results"], "bf16")
+    st = ph.run_schedule(oracle, kv, Q, K, V, schedule, dtype=dtype, units=units)
+    st["score_err"] = ph.compare_scores(kv, st["results"], dtype)
     assert st["flagged"] <= max(2, st["decisions"] // 500), st["flagged"]
     print(f"  flagged={st['flagged']}/{st['decisions']} max_err={st['max_err']:.2e} score_err={st['score_err']:.2e}")
     return kv, st
@@ -120,6 +120,14 @@ def test_rerank_chunks_interleaved_with_decode(binding, oracle):
 def test_rerank_chunks_grouped_queries(binding, oracle, G, d):
     _chunks(binding, oracle, [50, 90, 0, 128, 13], B=2, H=2 * G, Hkv=2, d=d, budget=72, n_sink=3, n_recent=20,
             max_chunk=128, seed=63)
+
+
+@pytest.mark.parametrize("G,d", [(1, 128), (2, 64), (4, 128)])
+def test_rerank_chunks_fp32_storage(binding, oracle, G, d):
+    """fp32 storage: keys and queries turned to their ranks in fp32, the vector-ALU attention, held to 1e-5; chunks
+    that fill the cache, cross the budget, interleave with decode steps."""
+    _chunks(binding, oracle, [30, 0, 64, 9, 0, 0, 100, 1, 47], B=2, H=2 * G, Hkv=2, d=d, budget=56, n_sink=2,
+            n_recent=17, max_chunk=100, seed=66, dtype="f32", rope_base=300.0)
 
 
 def test_rerank_chunks_pure_algorithm1_many_tiles(binding, oracle):
@@ -161,11 +169,12 @@ def test_rerank_chunks_llama_shaped_sampled(binding, oracle):
     assert st["decisions"] == 4 * (2560 + 8 - 2048)
 
 
-def _prompt(binding, oracle, *, T, block, steps, B, H, Hkv, d, budget, n_sink, n_recent, seed, rope_base=0.0, flags=0):
-    Q, K, V = inputs.batch_streams("lowrank", seed, T + steps, B, Hkv, H // Hkv, d, dtype="bf16")
-    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=n_sink, n_recent=n_recent,
+def _prompt(binding, oracle, *, T, block, steps, B, H, Hkv, d, budget, n_sink, n_recent, seed, rope_base=0.0, flags=0,
+            dtype="bf16"):
+    Q, K, V = inputs.batch_streams("lowrank" if dtype == "bf16" else "iid", seed, T + steps, B, Hkv, H // Hkv, d, dtype=dtype)
+    kv = binding.TreeKV(budget, H, d, kv_heads=Hkv, batch=B, dtype=dtype, n_sink=n_sink, n_recent=n_recent,
                         flags=flags | binding.TREEKV_POSITION_RERANK, max_prompt=T, rope_base=rope_base)
-    st = ph.run_prompt(oracle, kv, Q, K, V, T, block, steps)
+    st = ph.run_prompt(oracle, kv, Q, K, V, T, block, steps, dtype=dtype)
     assert st["flagged"] <= max(1, st["decisions"] // 200), st["flagged"]
     print(f"  blocks evicted={st['decisions']} flagged={st['flagged']} token score rel err={st['tok_err']:.2e}")
     return st
@@ -181,6 +190,14 @@ def test_rerank_prompt_ragged_slices_then_decode(binding, oracle):
 def test_rerank_prompt_shapes(binding, oracle, G, d, block):
     _prompt(binding, oracle, T=block * 41, block=block, steps=8, B=2, H=2 * G, Hkv=2, d=d, budget=block * 12, n_sink=3,
             n_recent=block + 5, seed=52, rope_base=500.0)
+
+
+@pytest.mark.parametrize("G,d,block", [(1, 128, 16), (4, 64, 8)])
+def test_rerank_prompt_fp32_storage(binding, oracle, G, d, block):
+    """fp32 storage: the window's queries and every key turned to the original positions while the prompt is scored,
+    then decode steps at cache ranks; held to 1e-5."""
+    _prompt(binding, oracle, T=block * 37, block=block, steps=12, B=2, H=2 * G, Hkv=2, d=d, budget=block * 10, n_sink=3,
+            n_recent=block + 5, seed=54, rope_base=1000.0, dtype="f32")
 
 
 def test_rerank_prompt_long(binding, oracle):
