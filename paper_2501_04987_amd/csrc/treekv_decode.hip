@@ -158,7 +158,8 @@ __device__ inline int position_of(const Params& p, const Step& s, const int* PEu
 // the rotary encoding enters the logit in its relative form: with (c, s) = (cos, sin) of distance * theta_i from a
 // table, plane i of the key is turned back by that angle and then multiplied with the query's plane.  The ranks of
 // the slots a workgroup streams are laid out in LDS (behind the logits) from the order arrays before the first
-// tile is consumed; table rows are requested together with the K/V rows they belong to.
+// tile is consumed; the (cos, sin) pairs come from two small tables in LDS (see TAB_STEP below), looked up one
+// tile ahead of their use.
 template <typename T, int D, int G, int THREADS, bool ROPE = false>
 struct Stream {
   static constexpr int WAVES = THREADS / 64;
@@ -170,6 +171,19 @@ struct Stream {
   static constexpr int LDS_FLOATS_FIXED = WAVES * G * (D + 2);
   static constexpr int LDS_WORDS_PER_ROW = G + (ROPE ? 1 : 0);     // logits, and the slot's rank
   static constexpr int TV = EPL / 4;            // 16-byte pieces of a lane's (cos, sin) pairs
+  // ROPE: the angles' (cos, sin) come from two small tables in LDS, rows 0, 64, 128, .. and rows 0 .. 63 of the
+  // context's table, multiplied as complex numbers: (cos, sin)(n theta) = (cos, sin)(64 a theta) x (cos, sin)(b theta)
+  // for n = 64 a + b.  Read from the full table in memory, the pairs are as many bytes per row as K and V together and
+  // cost the launch 6 us at 256 units x 2048 slots.
+  static constexpr int TAB_STEP = 64;
+  __host__ __device__ static inline int tab_rows(int cap) { return (cap - 1) / TAB_STEP + 1 + TAB_STEP; }
+  __host__ __device__ static inline size_t tab_offset(int rows) {     // in floats from the start of the dynamic LDS
+    return ((size_t)LDS_FLOATS_FIXED + (size_t)LDS_WORDS_PER_ROW * rows + 3) & ~(size_t)3;
+  }
+  // floats of dynamic LDS for `rows` streamed rows of a cache of `cap` slots
+  __host__ __device__ static inline size_t lds_floats(int cap, int rows) {
+    return ROPE ? tab_offset(rows) + (size_t)tab_rows(cap) * D : (size_t)LDS_FLOATS_FIXED + (size_t)LDS_WORDS_PER_ROW * rows;
+  }
 
   // sm_acc [WAVES][G][D], sm_wm [WAVES][G], sm_wl [WAVES][G].  `after_meta(st)` runs once the
   // bookkeeping words are known, after the first tile has been requested.
@@ -207,6 +221,19 @@ struct Stream {
     for (int g = 0; g < G; ++g)
       qr[g] = *reinterpret_cast<const uint4*>(q_in + ((size_t)b * p.H + (size_t)kvh * G + g) * D + li * EPL);
 
+    // ROPE: the two small tables, copied while the first rows are on their way.  A table row is laid out so that
+    // the LPR lanes of a row read consecutive 16-byte pieces: piece x of lane l at [x][l].
+    uint4* sm_tab = reinterpret_cast<uint4*>(sm_s - LDS_FLOATS_FIXED + tab_offset(lds_rows));
+    const int tab_a = (p.cap - 1) / TAB_STEP + 1;         // rows 0, 64, .. come first, rows 0 .. 63 after them
+    if constexpr (ROPE) {
+      constexpr int RV = D / 4;                           // 16-byte pieces of a table row
+      for (int e = tid; e < tab_rows(p.cap) * RV; e += THREADS) {
+        const int r = e / RV, c = e % RV;
+        const int pos = min(r < tab_a ? r * TAB_STEP : r - tab_a, p.cap - 1);   // rows past cap - 1 are never looked up
+        sm_tab[r * RV + (c % TV) * LPR + c / TV] = reinterpret_cast<const uint4*>(p.rope_tab + (size_t)pos * (D / 2))[c];
+      }
+    }
+
     st = load_meta(p, meta);
     begin = begin_spec;
     end = fused ? st.n1 : min(st.n1, begin + p.rows_per_split);
@@ -222,9 +249,16 @@ struct Stream {
         for (int u = 0; u < KU; ++u) {
           const int row = max(min(tb + u * RPL + ri, end - 1), begin);
           const int dist = min(max(st.n1 - 1 - sm_rank[row - begin], 0), p.cap - 1);
-          const uint4* src = reinterpret_cast<const uint4*>(p.rope_tab + (size_t)dist * (D / 2) + li * (EPL / 2));
+          const uint4* ra = sm_tab + (dist / TAB_STEP) * (D / 4) + li;
+          const uint4* rb = sm_tab + (tab_a + dist % TAB_STEP) * (D / 4) + li;
 #pragma unroll
-          for (int x = 0; x < TV; ++x) td[u][x] = src[x];
+          for (int x = 0; x < TV; ++x) {
+            const uint4 a = ra[x * LPR], c = rb[x * LPR];
+            const float ac0 = __uint_as_float(a.x), as0 = __uint_as_float(a.y), ac1 = __uint_as_float(a.z), as1 = __uint_as_float(a.w);
+            const float bc0 = __uint_as_float(c.x), bs0 = __uint_as_float(c.y), bc1 = __uint_as_float(c.z), bs1 = __uint_as_float(c.w);
+            td[u][x] = make_uint4(__float_as_uint(fmaf(ac0, bc0, -(as0 * bs0))), __float_as_uint(fmaf(as0, bc0, ac0 * bs0)),
+                                  __float_as_uint(fmaf(ac1, bc1, -(as1 * bs1))), __float_as_uint(fmaf(as1, bc1, ac1 * bs1)));
+          }
         }
       }
     };
@@ -436,6 +470,9 @@ struct StreamMfma {
   static constexpr int VT_FLOATS = D * VSTRIDE / 2;
   static constexpr int LDS_FLOATS_FIXED = WAVES * G * (D + 2) + WAVES * VT_FLOATS;
   static constexpr int LDS_WORDS_PER_ROW = G;
+  __host__ __device__ static inline size_t lds_floats(int, int rows) {
+    return (size_t)LDS_FLOATS_FIXED + (size_t)LDS_WORDS_PER_ROW * rows;
+  }
   static constexpr int VLOADS = TILE * PARTS / 64;        // 16-byte V pieces per lane and tile (8 at d=128, 4 at d=64)
   static_assert(G >= 2 && G <= 16 && (VLOADS == 8 || VLOADS == 4), "written for head_dim 64 / 128");
 
@@ -755,7 +792,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
   using St = typename PickStream<T, D, G, THREADS, ROPE>::type;
   constexpr int WAVES = St::WAVES;
   constexpr int EP = 5 * 1024 / THREADS;       // covers budgets up to 5119 from registers
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   float* sm_acc = smem;
   float* sm_wm = sm_acc + WAVES * G * D;
   float* sm_wl = sm_wm + WAVES * G;
@@ -848,7 +885,7 @@ __global__ __launch_bounds__(SPLIT_THREADS) void decode_split_kernel(Params p, c
   constexpr int THREADS = SPLIT_THREADS;
   using St = typename PickStream<T, D, G, THREADS, ROPE>::type;
   constexpr int WAVES = St::WAVES;
-  extern __shared__ float smem[];
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   float* sm_acc = smem;
   float* sm_wm = sm_acc + WAVES * G * D;
   float* sm_wl = sm_wm + WAVES * G;
@@ -891,7 +928,7 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, c
   // slots / list entries per thread served from registers (none when the logits do not fit in LDS: huge budgets)
   constexpr int EP = LOGITS_IN_LDS ? 5 * 1024 / THREADS : 0;
   constexpr int LPR = D / Storage<T>::EPL;
-  extern __shared__ float smem[];              // [G][cap] logits
+  extern __shared__ __attribute__((aligned(16))) float smem[];              // [G][cap] logits
   __shared__ float sm_sc[2];
   const int unit = blockIdx.x, tid = threadIdx.x;
   int* meta = p.meta + (size_t)unit * META_STRIDE;
@@ -970,7 +1007,7 @@ int launch_decode_g(const Params& p, const void* q, const void* k, const void* v
   const T* vt = (const T*)v;
   if (p.nsplit == 1) {
     using St = typename PickStream<T, D, G, FUSED_THREADS, ROPE>::type;
-    const size_t lds = (St::LDS_FLOATS_FIXED + (size_t)St::LDS_WORDS_PER_ROW * p.cap) * sizeof(float);
+    const size_t lds = St::lds_floats(p.cap, p.cap) * sizeof(float);
     if (lds > LDS_LIMIT) return TREEKV_EUNSUPPORTED;
     auto kern = decode_fused_kernel<T, D, G, ROPE>;
     if (lds > 48 * 1024 &&
@@ -979,7 +1016,7 @@ int launch_decode_g(const Params& p, const void* q, const void* k, const void* v
     hipLaunchKernelGGL(kern, dim3(p.U), dim3(FUSED_THREADS), lds, s, p, qt, kt, vt, out, retained, n_retained, evicted);
   } else {
     using St = typename PickStream<T, D, G, SPLIT_THREADS, ROPE>::type;
-    const size_t lds = (St::LDS_FLOATS_FIXED + (size_t)St::LDS_WORDS_PER_ROW * p.rows_per_split) * sizeof(float);
+    const size_t lds = St::lds_floats(p.cap, p.rows_per_split) * sizeof(float);
     if (lds > LDS_LIMIT) return TREEKV_EUNSUPPORTED;
     auto kern = decode_split_kernel<T, D, G, ROPE>;
     if (lds > 48 * 1024 &&
@@ -1027,8 +1064,7 @@ template <typename T, int D, int G, bool ROPE>
 size_t stream_lds_g(const Params& p) {
   using Sf = typename PickStream<T, D, G, FUSED_THREADS, ROPE>::type;
   using Ss = typename PickStream<T, D, G, SPLIT_THREADS, ROPE>::type;
-  return (p.nsplit == 1 ? Sf::LDS_FLOATS_FIXED + (size_t)Sf::LDS_WORDS_PER_ROW * p.cap
-                        : Ss::LDS_FLOATS_FIXED + (size_t)Ss::LDS_WORDS_PER_ROW * p.rows_per_split) * sizeof(float);
+  return (p.nsplit == 1 ? Sf::lds_floats(p.cap, p.cap) : Ss::lds_floats(p.cap, p.rows_per_split)) * sizeof(float);
 }
 template <typename T, int D>
 size_t stream_lds_d(const Params& p) {
