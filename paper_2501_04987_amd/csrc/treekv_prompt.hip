@@ -522,12 +522,38 @@ __global__ __launch_bounds__(256) void prompt_blocks_kernel(Params p, int T, int
     return;
   }
   __syncthreads();
-  for (int k = tid; k < m_b; k += nt) cur[k] = make_int2(sink_b + k, __float_as_int(beta[sink_b + k]));
-  __syncthreads();
   // One pass of idx over the tree region: the sequence is the region at the pass's start followed by the blocks
   // that enter during the pass; the block entering at eviction step e is block sink_b + m_b + e (the one that
   // just left the recent window, or the arriving block itself without one), the block arriving then is cb + e.
   const int n_ev = N - cb;
+  if (m_b <= 64) {
+    // A region that fits one wave stays in that wave's registers, one entry per lane, and a pass is a handful of
+    // lane exchanges: no barrier between the passes (there are (N - cb) / m_b of them, 32 at 32768 tokens in blocks
+    // of 64 into 2048 slots, and a workgroup barrier each was most of this kernel's time).
+    if (tid < 64) {
+      const int k = tid;
+      int2 c = k < m_b ? make_int2(sink_b + k, __float_as_int(beta[sink_b + k])) : make_int2(0, 0);
+      for (int e0 = 0; e0 < n_ev; e0 += m_b) {
+        const int cnt = min(m_b, n_ev - e0);
+        // entry `i` of the pass's sequence; every lane takes part in the exchanges, whatever its own i
+        auto seq = [&](int i) {
+          const int from = min(i, 63);
+          int2 v = make_int2(__shfl(c.x, from, 64), __shfl(c.y, from, 64));
+          if (i >= m_b && k < m_b) v = make_int2(sink_b + e0 + i, __float_as_int(beta[sink_b + e0 + i]));
+          return v;
+        };
+        const bool scope = k < cnt;
+        const int2 l = seq(scope ? 2 * k : k + cnt), r = seq(scope ? 2 * k + 1 : k + cnt);
+        const bool drop_right = (p.flags & TREEKV_KEEP_LEFT) || (__int_as_float(l.y) > __int_as_float(r.y));   // a tie evicts the left block
+        if (scope && evu) evu[cb + e0 + k] = drop_right ? r.x : l.x;
+        c = (!scope || drop_right) ? l : r;
+      }
+      if (k < m_b) cur[k] = c;
+    }
+    __syncthreads();
+  } else {
+  for (int k = tid; k < m_b; k += nt) cur[k] = make_int2(sink_b + k, __float_as_int(beta[sink_b + k]));
+  __syncthreads();
   for (int e0 = 0; e0 < n_ev; e0 += m_b) {
     const int cnt = min(m_b, n_ev - e0);
     auto seq = [&](int k) { return k < m_b ? cur[k] : make_int2(sink_b + e0 + k, __float_as_int(beta[sink_b + e0 + k])); };
@@ -545,6 +571,7 @@ __global__ __launch_bounds__(256) void prompt_blocks_kernel(Params p, int T, int
     }
     __syncthreads();
     int2* t = cur; cur = nxt; nxt = t;
+  }
   }
   for (int i = tid; i < cb; i += nt) {
     int v;

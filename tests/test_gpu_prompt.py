@@ -60,6 +60,16 @@ def test_prompt_pure_algorithm1_single_token_blocks(binding, oracle):
     _run(binding, oracle, T=301, block=1, steps=25, B=1, H=2, Hkv=2, d=64, budget=20, n_sink=0, n_recent=0, seed=7)
 
 
+def test_prompt_tree_region_wider_than_a_wave(binding, oracle):
+    """150 tree slots (blocks of 1): the passes over the region take the workgroup-wide path, several passes and a
+    partial last one."""
+    _run(binding, oracle, T=777, block=1, steps=10, B=1, H=2, Hkv=2, d=64, budget=200, n_sink=10, n_recent=40, seed=8)
+
+
+def test_prompt_tree_region_of_exactly_a_wave(binding, oracle):
+    _run(binding, oracle, T=64 * 9 + 30, block=1, steps=5, B=2, H=2, Hkv=2, d=64, budget=70, n_sink=2, n_recent=4, seed=9)
+
+
 def test_prompt_that_fits_keeps_everything(binding, oracle):
     kv, st = _run(binding, oracle, T=160, block=32, steps=120, B=1, H=2, Hkv=2, d=128, budget=256, n_sink=4,
                   n_recent=60, seed=8)
