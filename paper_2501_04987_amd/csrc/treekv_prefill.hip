@@ -172,8 +172,8 @@ __device__ inline unsigned lds_address(const void* shared_ptr) {
 // Column sums: a wave adds its two row blocks, reduces over the 16 lanes that hold the 16 rows and
 // leaves the 32 sums of its columns in LDS.  During the next tile two of the waves add the two row groups
 // and add the tile's 128 sums to the unit's accumulators (the atomics then have a whole iteration to
-// complete before anything waits on the memory counter).  A workgroup touches every column of every tile
-// it visits (masked entries add zero) and nothing else.
+// complete before anything waits on the memory counter).  A workgroup touches the accumulators of the columns
+// of the tiles it visits (masked entries add zero; cache columns past the last cached token are left alone).
 //
 // ROPE (positions re-assigned to cache ranks): queries and keys come, already turned to their ranks and split into
 // two bf16 parts each, from the scratch prefill_turn_kernel fills (pf_qrot, pf_krot; the chunk's own keys lie behind
@@ -246,12 +246,15 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   const uint16_t* Vcu = Vc + ((size_t)b * L * p.Hkv + kvh) * D;
   const size_t klo_off = krot_rows * D;                            // from a key's hi part to its lo part (ROPE)
 
-  const int cache_tiles = (ci.n + 1 + AT_COLS - 1) / AT_COLS;          // slots [0, n], the free one masked
+  // Cache columns are the n cached tokens' slots in slot order with the free slot left out: column j is slot
+  // j + (j >= fslot).  (Walking slots [0, n] and masking the free one would cost a full cache of 2048 a 17th tile
+  // for its one last slot.)
+  const int cache_tiles = (ci.n + AT_COLS - 1) / AT_COLS;
   const int last_row = min(rbase + ROW_TILE, L) - 1;                   // last chunk row of the workgroup
   const int chunk_tiles = last_row / AT_COLS + 1;                      // causal: columns <= last_row
   const int ntiles = cache_tiles + chunk_tiles;
   const float sc = p.scale_log2e;
-  const int n_cached = ci.n, fslot = ci.fslot;
+  const int last_cached = ci.n - 1, fslot = ci.fslot;                   // last visible cache column
   const int cache_lim = p.cap - 1, chunk_lim = L - 1;                   // last row that exists
 
   // ---- asynchronous tile loads: this wave's CPW instructions of 1 KB each ----
@@ -266,8 +269,12 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     const uint16_t* base = is_cache ? cache_src : chunk_src;
     const int rstride = is_cache ? D : chunk_stride;
     const int lim = is_cache ? cache_lim : chunk_lim;
-    const int row_w = col0 + wave * 16;                   // first source row of this wave's 16 (wave uniform)
-    if (row_w + 15 <= lim && is_cache) {
+    const int col_w = col0 + wave * 16;                   // first column of this wave's 16 (wave uniform)
+    // cache columns at and after the free slot sit one row further on
+    const int shift = (is_cache && col_w >= fslot) ? 1 : 0;
+    const bool straddles = is_cache && col_w < fslot && fslot <= col_w + 15;
+    const int row_w = col_w + shift;                      // first source row, unless the wave straddles the free slot
+    if (row_w + 15 <= lim && is_cache && !straddles) {
       // Cache rows are contiguous, like their LDS image: one scalar base and one M0 for the run of requests;
       // the per-lane offsets differ only in the swizzled piece.
       const unsigned lane_row = (unsigned)(a_lrow * D) * 2;
@@ -276,7 +283,7 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       auto voff = [&](int x) { return lane_row + ((a_slot ^ swz(x * RPC + a_lrow)) * 16); };
       if constexpr (CPW == 4) async_copy16_run(sbase, m0, voff(0), voff(1), voff(2), voff(3));
       else async_copy16_run(sbase, m0, voff(0), voff(1));
-    } else if (row_w + 15 <= lim) {
+    } else if (row_w + 15 <= lim && !straddles) {
       // every row exists: a scalar base per instruction plus a per-lane byte offset
       const unsigned lane_row = (unsigned)(a_lrow * rstride) * 2;
 #pragma unroll
@@ -290,7 +297,9 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
 #pragma unroll
       for (int x = 0; x < CPW; ++x) {
         const int r = x * RPC + a_lrow;
-        const uint16_t* src = base + (size_t)min(row_w + r, lim) * rstride + (a_slot ^ swz(r)) * 8;
+        const int col = col_w + r;
+        const int row = col + ((is_cache && col >= fslot) ? 1 : 0);
+        const uint16_t* src = base + (size_t)min(row, lim) * rstride + (a_slot ^ swz(r)) * 8;
         async_copy16(src, __builtin_amdgcn_readfirstlane(lds_address(stage + (wave * CPW + x) * 512)));
       }
     }
@@ -338,16 +347,15 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
       const bool is_cache = tile < cache_tiles;
       const int c0 = (is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS) + wave * 16;   // this wave's 16 columns
       // only tiles that touch the end of the cache, the free slot or the causal diagonal need a mask (wave uniform)
-      const bool need_mask = is_cache ? (c0 + 15 > n_cached || (fslot >= c0 && fslot < c0 + 16)) : (c0 + 15 > rbase);
+      const bool need_mask = is_cache ? (c0 + 15 > last_cached) : (c0 + 15 > rbase);
       if (need_mask) {
-        const int excl = is_cache ? fslot : -1;
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) {
-          const int lim = is_cache ? n_cached : rbase + rb * 16 + lr;      // last visible column of this lane's row
+          const int lim = is_cache ? last_cached : rbase + rb * 16 + lr;   // last visible column of this lane's row
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int col = c0 + q4 * 4 + i;
-            s[rb][i] = (col <= lim && col != excl) ? s[rb][i] : -INFINITY;
+            s[rb][i] = col <= lim ? s[rb][i] : -INFINITY;
           }
         }
       }
@@ -500,7 +508,12 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
     // column in any order and the result is still the same to the bit.  A tile's sum is below 64; 2^-40 resolves it
     // far finer than fp32 does.
     const long long fix = (long long)((src[0] + src[AT_COLS]) * COLSUM_FIX + 0.5f);
-    atomicAdd(cs_acc + (is_cache ? col0 : cap_cols + col0) + (tid & 127), (unsigned long long)fix);
+    const int col = col0 + (tid & 127);
+    if (is_cache) {             // the accumulators are indexed by slot
+      if (col <= last_cached) atomicAdd(cs_acc + col + (col >= fslot ? 1 : 0), (unsigned long long)fix);
+    } else {
+      atomicAdd(cs_acc + cap_cols + col, (unsigned long long)fix);
+    }
   };
 
   // S^T blocks of a staged K tile: rows = columns cq*32 + bk*16 + q4*4 + i, column = the lane's query row of block 0 / 1
@@ -567,20 +580,18 @@ __global__ __launch_bounds__(AT_THREADS) void prefill_attend_kernel(Params p, co
   auto mask_tile = [&](f32x4_t (&s0)[2], f32x4_t (&s1)[2], int tile) {
     const bool is_cache = tile < cache_tiles;
     const int col0 = is_cache ? tile * AT_COLS : (tile - cache_tiles) * AT_COLS;
-    // only tiles that touch the end of the cache, the free slot or the causal diagonal need a mask (wave uniform)
-    const bool need_mask = is_cache ? (col0 + AT_COLS - 1 > n_cached || (fslot >= col0 && fslot < col0 + AT_COLS))
-                                    : (col0 + AT_COLS - 1 > row0);
+    // only tiles that touch the end of the cache or the causal diagonal need a mask (wave uniform)
+    const bool need_mask = is_cache ? (col0 + AT_COLS - 1 > last_cached) : (col0 + AT_COLS - 1 > row0);
     if (need_mask) {
       const int cbase = col0 + cq * 32 + q4 * 4;
-      const int excl = is_cache ? fslot : -1;
-      const int lim0 = is_cache ? n_cached : my_row0, lim1 = is_cache ? n_cached : my_row1;   // last visible column
+      const int lim0 = is_cache ? last_cached : my_row0, lim1 = is_cache ? last_cached : my_row1;   // last visible column
 #pragma unroll
       for (int bk = 0; bk < 2; ++bk)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int col = cbase + bk * 16 + i;
-          s0[bk][i] = (col <= lim0 && col != excl) ? s0[bk][i] : -INFINITY;   // exp2 gives exactly 0
-          s1[bk][i] = (col <= lim1 && col != excl) ? s1[bk][i] : -INFINITY;
+          s0[bk][i] = col <= lim0 ? s0[bk][i] : -INFINITY;   // exp2 gives exactly 0
+          s1[bk][i] = col <= lim1 ? s1[bk][i] : -INFINITY;
         }
     }
   };
