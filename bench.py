@@ -57,7 +57,7 @@ PROFILED_TRAFFIC = {
     "decode": dict(bytes=(132960 * 2 + 4424) * 1024, source="profiles/hbm_traffic_counters_bench_kernels.txt"),
     "prompt": dict(bytes=((140461 + 140860 + 48 + 16680) * 2 + (128 + 4162 + 4 + 34166)) * 1024,
                    source="profiles/hbm_traffic_counters_bench_kernels.txt"),
-    "prefill": dict(bytes=int(((26547 + 719 + 4204) * 2 + (13184 + 1669 + 8192)) * 1024),
+    "prefill": dict(bytes=int(((26377 + 716 + 4200) * 2 + (13068 + 1669 + 8192)) * 1024),
                     source="profiles/hbm_traffic_counters_bench_kernels.txt"),
     "wavelet": dict(bytes=int(((532612 + 40974.5) * 2 + (81920 + 10)) * 1024),
                     source="profiles/hbm_traffic_counters_bench_kernels.txt"),
