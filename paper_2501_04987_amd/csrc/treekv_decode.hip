@@ -34,6 +34,9 @@ __device__ inline uint4 ld_row16(const void* ptr) {
 }
 // Measured best of 256 .. 1024 threads per workgroup, for both shapes.
 constexpr int FUSED_THREADS = 512;
+// position re-assignment in the streaming kernels: off; the angles' (cos, sin) from two small tables in LDS; from the
+// context's full table in memory (budgets whose small tables would not fit)
+enum : int { ROPE_OFF = 0, ROPE_LDS = 1, ROPE_MEM = 2 };
 constexpr int SPLIT_THREADS = 512;
 constexpr int MERGE_THREADS = 1024;
 constexpr int KU = 2;                  // wave loads of K (and of V) per tile (4: measured slower)
@@ -160,7 +163,7 @@ __device__ inline int position_of(const Params& p, const Step& s, const int* PEu
 // the slots a workgroup streams are laid out in LDS (behind the logits) from the order arrays before the first
 // tile is consumed; the (cos, sin) pairs come from two small tables in LDS (see TAB_STEP below), looked up one
 // tile ahead of their use.
-template <typename T, int D, int G, int THREADS, bool ROPE = false>
+template <typename T, int D, int G, int THREADS, int ROPE = ROPE_OFF>
 struct Stream {
   static constexpr int WAVES = THREADS / 64;
   static constexpr int EPL = Storage<T>::EPL;   // elements per 16-byte lane load
@@ -177,12 +180,16 @@ struct Stream {
   // cost the launch 6 us at 256 units x 2048 slots.
   static constexpr int TAB_STEP = 64;
   __host__ __device__ static inline int tab_rows(int cap) { return (cap - 1) / TAB_STEP + 1 + TAB_STEP; }
+  // budgets whose two tables would take more than 80 KB of LDS (more than 6144 slots at head_dim 128, twice that
+  // at 64) read the pairs from the full table in memory instead
+  __host__ __device__ static inline bool tab_in_lds(int cap) { return (size_t)tab_rows(cap) * D * sizeof(float) <= 80 * 1024; }
   __host__ __device__ static inline size_t tab_offset(int rows) {     // in floats from the start of the dynamic LDS
     return ((size_t)LDS_FLOATS_FIXED + (size_t)LDS_WORDS_PER_ROW * rows + 3) & ~(size_t)3;
   }
   // floats of dynamic LDS for `rows` streamed rows of a cache of `cap` slots
   __host__ __device__ static inline size_t lds_floats(int cap, int rows) {
-    return ROPE ? tab_offset(rows) + (size_t)tab_rows(cap) * D : (size_t)LDS_FLOATS_FIXED + (size_t)LDS_WORDS_PER_ROW * rows;
+    return ROPE == ROPE_LDS ? tab_offset(rows) + (size_t)tab_rows(cap) * D
+                            : (size_t)LDS_FLOATS_FIXED + (size_t)LDS_WORDS_PER_ROW * rows;
   }
 
   // sm_acc [WAVES][G][D], sm_wm [WAVES][G], sm_wl [WAVES][G].  `after_meta(st)` runs once the
@@ -225,7 +232,8 @@ struct Stream {
     // the LPR lanes of a row read consecutive 16-byte pieces: piece x of lane l at [x][l].
     uint4* sm_tab = reinterpret_cast<uint4*>(sm_s - LDS_FLOATS_FIXED + tab_offset(lds_rows));
     const int tab_a = (p.cap - 1) / TAB_STEP + 1;         // rows 0, 64, .. come first, rows 0 .. 63 after them
-    if constexpr (ROPE) {
+    constexpr bool lds_tab = ROPE == ROPE_LDS;
+    if constexpr (lds_tab) {
       constexpr int RV = D / 4;                           // 16-byte pieces of a table row
       for (int e = tid; e < tab_rows(p.cap) * RV; e += THREADS) {
         const int r = e / RV, c = e % RV;
@@ -249,6 +257,11 @@ struct Stream {
         for (int u = 0; u < KU; ++u) {
           const int row = max(min(tb + u * RPL + ri, end - 1), begin);
           const int dist = min(max(st.n1 - 1 - sm_rank[row - begin], 0), p.cap - 1);
+          if constexpr (!lds_tab) {
+            const uint4* src = reinterpret_cast<const uint4*>(p.rope_tab + (size_t)dist * (D / 2) + li * (EPL / 2));
+#pragma unroll
+            for (int x = 0; x < TV; ++x) td[u][x] = src[x];
+          } else {
           const uint4* ra = sm_tab + (dist / TAB_STEP) * (D / 4) + li;
           const uint4* rb = sm_tab + (tab_a + dist % TAB_STEP) * (D / 4) + li;
 #pragma unroll
@@ -258,6 +271,7 @@ struct Stream {
             const float bc0 = __uint_as_float(c.x), bs0 = __uint_as_float(c.y), bc1 = __uint_as_float(c.z), bs1 = __uint_as_float(c.w);
             td[u][x] = make_uint4(__float_as_uint(fmaf(ac0, bc0, -(as0 * bs0))), __float_as_uint(fmaf(as0, bc0, ac0 * bs0)),
                                   __float_as_uint(fmaf(ac1, bc1, -(as1 * bs1))), __float_as_uint(fmaf(as1, bc1, ac1 * bs1)));
+          }
           }
         }
       }
@@ -660,10 +674,16 @@ struct StreamMfma {
 };
 
 // The stream to use for a storage type and group size.
-template <typename T, int D, int G, int THREADS, bool ROPE> struct PickStream { using type = Stream<T, D, G, THREADS, ROPE>; };
-template <int D, int THREADS> struct PickStream<uint16_t, D, 2, THREADS, false> { using type = StreamMfma<D, 2, THREADS>; };
-template <int D, int THREADS> struct PickStream<uint16_t, D, 4, THREADS, false> { using type = StreamMfma<D, 4, THREADS>; };
-template <int D, int THREADS> struct PickStream<uint16_t, D, 8, THREADS, false> { using type = StreamMfma<D, 8, THREADS>; };
+template <typename T, int D, int G, int THREADS, int ROPE> struct PickStream { using type = Stream<T, D, G, THREADS, ROPE>; };
+// which instance a context's decode steps take
+template <typename T, int D>
+inline int rope_mode(const Params& p) {
+  if (!(p.flags & TREEKV_POSITION_RERANK)) return ROPE_OFF;
+  return Stream<T, D, 1, FUSED_THREADS, ROPE_LDS>::tab_in_lds(p.cap) ? ROPE_LDS : ROPE_MEM;
+}
+template <int D, int THREADS> struct PickStream<uint16_t, D, 2, THREADS, ROPE_OFF> { using type = StreamMfma<D, 2, THREADS>; };
+template <int D, int THREADS> struct PickStream<uint16_t, D, 4, THREADS, ROPE_OFF> { using type = StreamMfma<D, 4, THREADS>; };
+template <int D, int THREADS> struct PickStream<uint16_t, D, 8, THREADS, ROPE_OFF> { using type = StreamMfma<D, 8, THREADS>; };
 
 // Global (max, sum) over the parts' (max, sum) pairs, identical in every thread that calls it.
 __device__ inline void merge_stats(const float* pm, const float* pl, int nparts, int stride, float& M, float& L) {
@@ -780,7 +800,7 @@ __device__ inline void epilogue(const Params& p, int unit, const Step& st, const
 }
 
 // ---------------------------------------------------------------------------------------------
-template <typename T, int D, int G, bool ROPE>
+template <typename T, int D, int G, int ROPE>
 __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, const T* __restrict__ q_in,
                                                                      const T* __restrict__ k_in,
                                                                      const T* __restrict__ v_in,
@@ -878,7 +898,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void decode_fused_kernel(Params p, c
   }
 }
 
-template <typename T, int D, int G, bool ROPE>
+template <typename T, int D, int G, int ROPE>
 __global__ __launch_bounds__(SPLIT_THREADS) void decode_split_kernel(Params p, const T* __restrict__ q_in,
                                                                      const T* __restrict__ k_in,
                                                                      const T* __restrict__ v_in) {
@@ -999,7 +1019,7 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(Params p, c
   }
 }
 
-template <typename T, int D, int G, bool ROPE>
+template <typename T, int D, int G, int ROPE>
 int launch_decode_g(const Params& p, const void* q, const void* k, const void* v, float* out, int32_t* retained,
                     int32_t* n_retained, int32_t* evicted, hipStream_t s) {
   const T* qt = (const T*)q;
@@ -1041,26 +1061,24 @@ int launch_decode_g(const Params& p, const void* q, const void* k, const void* v
 template <typename T, int D>
 int launch_decode_d(const Params& p, const void* q, const void* k, const void* v, float* out, int32_t* retained,
                     int32_t* n_retained, int32_t* evicted, hipStream_t s) {
-  if (p.flags & TREEKV_POSITION_RERANK) {
-    switch (p.G) {
-      case 1: return launch_decode_g<T, D, 1, true>(p, q, k, v, out, retained, n_retained, evicted, s);
-      case 2: return launch_decode_g<T, D, 2, true>(p, q, k, v, out, retained, n_retained, evicted, s);
-      case 4: return launch_decode_g<T, D, 4, true>(p, q, k, v, out, retained, n_retained, evicted, s);
-      case 8: return launch_decode_g<T, D, 8, true>(p, q, k, v, out, retained, n_retained, evicted, s);
-      default: return TREEKV_EUNSUPPORTED;
-    }
-  }
+  const int mode = rope_mode<T, D>(p);
+#define TKV_LAUNCH_G(G_)                                                                                              \
+  case G_:                                                                                                            \
+    return mode == ROPE_LDS   ? launch_decode_g<T, D, G_, ROPE_LDS>(p, q, k, v, out, retained, n_retained, evicted, s) \
+           : mode == ROPE_MEM ? launch_decode_g<T, D, G_, ROPE_MEM>(p, q, k, v, out, retained, n_retained, evicted, s) \
+                              : launch_decode_g<T, D, G_, ROPE_OFF>(p, q, k, v, out, retained, n_retained, evicted, s);
   switch (p.G) {
-    case 1: return launch_decode_g<T, D, 1, false>(p, q, k, v, out, retained, n_retained, evicted, s);
-    case 2: return launch_decode_g<T, D, 2, false>(p, q, k, v, out, retained, n_retained, evicted, s);
-    case 4: return launch_decode_g<T, D, 4, false>(p, q, k, v, out, retained, n_retained, evicted, s);
-    case 8: return launch_decode_g<T, D, 8, false>(p, q, k, v, out, retained, n_retained, evicted, s);
+    TKV_LAUNCH_G(1)
+    TKV_LAUNCH_G(2)
+    TKV_LAUNCH_G(4)
+    TKV_LAUNCH_G(8)
     default: return TREEKV_EUNSUPPORTED;
   }
+#undef TKV_LAUNCH_G
 }
 
 // LDS bytes the streaming kernel of the current shape (fused when nsplit == 1) asks for; 0 if no kernel exists.
-template <typename T, int D, int G, bool ROPE>
+template <typename T, int D, int G, int ROPE>
 size_t stream_lds_g(const Params& p) {
   using Sf = typename PickStream<T, D, G, FUSED_THREADS, ROPE>::type;
   using Ss = typename PickStream<T, D, G, SPLIT_THREADS, ROPE>::type;
@@ -1068,14 +1086,20 @@ size_t stream_lds_g(const Params& p) {
 }
 template <typename T, int D>
 size_t stream_lds_d(const Params& p) {
-  const bool rope = (p.flags & TREEKV_POSITION_RERANK) != 0;
+  const int mode = rope_mode<T, D>(p);
+#define TKV_LDS_G(G_)                                                   \
+  case G_:                                                              \
+    return mode == ROPE_LDS   ? stream_lds_g<T, D, G_, ROPE_LDS>(p)     \
+           : mode == ROPE_MEM ? stream_lds_g<T, D, G_, ROPE_MEM>(p)     \
+                              : stream_lds_g<T, D, G_, ROPE_OFF>(p);
   switch (p.G) {
-    case 1: return rope ? stream_lds_g<T, D, 1, true>(p) : stream_lds_g<T, D, 1, false>(p);
-    case 2: return rope ? stream_lds_g<T, D, 2, true>(p) : stream_lds_g<T, D, 2, false>(p);
-    case 4: return rope ? stream_lds_g<T, D, 4, true>(p) : stream_lds_g<T, D, 4, false>(p);
-    case 8: return rope ? stream_lds_g<T, D, 8, true>(p) : stream_lds_g<T, D, 8, false>(p);
+    TKV_LDS_G(1)
+    TKV_LDS_G(2)
+    TKV_LDS_G(4)
+    TKV_LDS_G(8)
     default: return 0;
   }
+#undef TKV_LDS_G
 }
 
 }  // namespace

@@ -130,6 +130,13 @@ def test_rerank_chunks_fp32_storage(binding, oracle, G, d):
             n_recent=17, max_chunk=100, seed=66, dtype="f32", rope_base=300.0)
 
 
+def test_rerank_budget_beyond_the_lds_angle_tables(binding, oracle):
+    """6500 slots: the decode step's two small angle tables no longer fit beside the logits and the pairs come from
+    the context's full table; filled by chunks, then decode steps that evict."""
+    _chunks(binding, oracle, [512] * 13 + [0] * 120, B=1, H=1, Hkv=1, d=64, budget=6500, n_sink=4, n_recent=1000,
+            max_chunk=512, seed=67)
+
+
 def test_rerank_chunks_pure_algorithm1_many_tiles(binding, oracle):
     """No protected tokens; 300-token chunks over a 400-slot cache: several column tiles of cache and of chunk, the
     causal diagonal crossing tiles, up to 2 sweeps per chunk."""
