@@ -68,6 +68,31 @@ def test_restore_repeats_bit_for_bit(binding, dtype, splits, G, layout):
     assert torch.equal(b.export_state(), snap)
 
 
+@pytest.mark.parametrize("splits,G", [(1, 1), (3, 2)])
+def test_restore_with_reassigned_positions(binding, splits, G):
+    """With positions re-assigned to cache ranks the steps after a restore depend on the order arrays the import
+    rebuilds (a slot's rank is read off them): they must repeat bit for bit too, in the context the snapshot came
+    from and in a fresh one."""
+    import torch
+
+    budget, B, Hkv, d, T0, N = 45, 2, 2, 128, 130, 60
+    T = T0 + N
+    Q, K, V = inputs.batch_streams("lowrank", 41, T, B, Hkv, G, d, dtype="bf16")
+    Qd, Kd, Vd = (ph.to_device(x, "bf16") for x in (Q, K, V))
+    mk = lambda: binding.TreeKV(budget, Hkv * G, d, kv_heads=Hkv, batch=B, dtype="bf16", n_sink=2, n_recent=13,
+                                kv_splits=splits, flags=binding.TREEKV_POSITION_RERANK, rope_base=200.0)
+    a, b = mk(), mk()
+    _steps(a, Qd, Kd, Vd, 0, T0)
+    snap = a.export_state()
+    want = _steps(a, Qd, Kd, Vd, T0, T)
+    assert (want[1] >= 0).all()
+    for kv in (a, b):
+        kv.import_state(snap)
+        got = _steps(kv, Qd, Kd, Vd, T0, T)
+        for w, g, name in zip(want, got, ("out", "evicted", "retained")):
+            assert np.array_equal(w, g), name
+
+
 def test_snapshot_while_filling_and_after_chunks(binding):
     """A snapshot taken before the cache is full, and one taken after prefill chunks, restore exactly."""
     import torch
